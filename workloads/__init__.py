@@ -1,0 +1,329 @@
+"""Workload tables and seeded synthetic inputs shared by the tests, the bench and the checker.
+
+This module holds shapes and random draws only: no convolution, GEMM, loss or
+optimiser arithmetic lives here.  Both the HIP path's Python binding and the CPU
+checker are driven from the same tables and the same seeded tensors, so that the
+two are compared on identical inputs while sharing no code of the method itself.
+
+Layouts (all C-contiguous numpy arrays):
+  activations  NHWC float32                 [N][H][W][C]
+  conv weights [Kout][R][S][Cin] float32
+  FC weights   [out][in] float32
+  features     [n][A], A is the NHWC flattening (h*W + w)*C + c of the last map
+  labels       int32
+
+The networks are the CNN shapes the paper trains (Evaluation, Setup: table of
+models and per-worker batch sizes) at ImageNet / CIFAR input shapes; the images
+are N(0,1) noise standing in for those datasets.
+
+A conv stack is an op list over named buffers; every op is a dict:
+  {"op": "conv", "name", "src", "dst", "K","R","S","stride","pad","relu"}
+  {"op": "pool", "src", "dst", "win","stride","pad","relu"}
+  {"op": "add_relu", "a", "b", "dst"}          dst = max(0, a + b)
+  {"op": "gap", "src", "dst"}                  global average pool
+The first buffer is "x0" (the images) and the last op writes "feat".
+"""
+from __future__ import annotations
+
+import math
+from dataclasses import dataclass, field
+from typing import Dict, List, Tuple
+
+import numpy as np
+
+__all__ = [
+    "Workload", "get_workload", "WORKLOAD_NAMES", "shape_pass", "conv_param_shapes",
+    "fc_param_shapes", "gen_images", "gen_labels", "gen_conv_params", "gen_fc_params",
+    "gen_ps_case", "rng_for", "conv_flops", "fc_flops", "count_params",
+]
+
+
+@dataclass
+class Workload:
+    name: str
+    K: int                      # number of conv workers feeding the FC worker
+    B: int                      # per-worker batch
+    image: Tuple[int, int, int]  # H, W, C
+    ops: List[dict]
+    fc_dims: List[int]          # A, hidden..., classes
+    lr: float = 0.01
+    momentum: float = 0.9
+    weight_decay: float = 0.0
+    notes: str = ""
+
+    @property
+    def n(self) -> int:
+        return self.K * self.B
+
+    @property
+    def classes(self) -> int:
+        return self.fc_dims[-1]
+
+
+def _conv(name, src, dst, K, R, stride=1, pad=0, relu=True, S=None):
+    return dict(op="conv", name=name, src=src, dst=dst, K=K, R=R, S=R if S is None else S,
+                stride=stride, pad=pad, relu=relu)
+
+
+def _pool(src, dst, win, stride, pad=0, relu=True):
+    return dict(op="pool", src=src, dst=dst, win=win, stride=stride, pad=pad, relu=relu)
+
+
+def _chain(spec):
+    """spec: list of ("c", K, R, stride, pad) / ("p", win, stride, pad) -> linear op list."""
+    ops, cur, ci, pi = [], "x0", 0, 0
+    for s in spec:
+        if s[0] == "c":
+            ci += 1
+            dst = f"c{ci}"
+            ops.append(_conv(f"conv{ci}", cur, dst, s[1], s[2], s[3], s[4], relu=True))
+        else:
+            pi += 1
+            dst = f"p{pi}"
+            ops.append(_pool(cur, dst, s[1], s[2], s[3], relu=True))
+        cur = dst
+    ops[-1]["dst"] = "feat"
+    return ops
+
+
+def _tiny_ops():
+    return _chain([("c", 16, 3, 1, 1), ("p", 2, 2, 0), ("c", 32, 3, 1, 1), ("p", 2, 2, 0)])
+
+
+def _alexnet_ops():
+    return _chain([("c", 96, 11, 4, 2), ("p", 3, 2, 0), ("c", 256, 5, 1, 2), ("p", 3, 2, 0),
+                   ("c", 384, 3, 1, 1), ("c", 384, 3, 1, 1), ("c", 256, 3, 1, 1), ("p", 3, 2, 0)])
+
+
+def _vgg16_ops():
+    spec = []
+    for width, reps in ((64, 2), (128, 2), (256, 3), (512, 3), (512, 3)):
+        spec += [("c", width, 3, 1, 1)] * reps + [("p", 2, 2, 0)]
+    return _chain(spec)
+
+
+def _resnet50_ops():
+    """Bottleneck residual stack without normalisation layers: stem 7x7/2, 3x3/2 max-pool
+    (pad 1), stages [3,4,6,3] of 1x1 -> 3x3 (carries the stride) -> 1x1 with a projection
+    shortcut in the first block of each stage, global average pool."""
+    ops = [_conv("stem", "x0", "stem", 64, 7, 2, 3, relu=True),
+           _pool("stem", "s0", 3, 2, 1, relu=True)]
+    cur = "s0"
+    for si, (width, blocks) in enumerate(((64, 3), (128, 4), (256, 6), (512, 3)), start=1):
+        for bi in range(blocks):
+            stride = 2 if (bi == 0 and si > 1) else 1
+            tag = f"s{si}b{bi}"
+            ops.append(_conv(tag + "a", cur, tag + "a", width, 1, 1, 0, relu=True))
+            ops.append(_conv(tag + "b", tag + "a", tag + "b", width, 3, stride, 1, relu=True))
+            ops.append(_conv(tag + "c", tag + "b", tag + "c", 4 * width, 1, 1, 0, relu=False))
+            if bi == 0:
+                ops.append(_conv(tag + "sc", cur, tag + "sc", 4 * width, 1, stride, 0, relu=False))
+                short = tag + "sc"
+            else:
+                short = cur
+            ops.append(dict(op="add_relu", a=tag + "c", b=short, dst=tag + "o"))
+            cur = tag + "o"
+    ops.append(dict(op="gap", src=cur, dst="feat"))
+    return ops
+
+
+def _mini_res_ops():
+    """A two-block residual stack small enough for exhaustive checks: exercises 7x7/2,
+    padded 3x3/2 pooling, 1x1, strided 3x3, projection and identity shortcuts, GAP."""
+    ops = [_conv("stem", "x0", "stem", 8, 7, 2, 3, relu=True),
+           _pool("stem", "s0", 3, 2, 1, relu=True)]
+    cur = "s0"
+    for bi, (width, stride, proj) in enumerate(((4, 1, True), (4, 1, False), (8, 2, True))):
+        tag = f"b{bi}"
+        ops.append(_conv(tag + "a", cur, tag + "a", width, 1, 1, 0, relu=True))
+        ops.append(_conv(tag + "b", tag + "a", tag + "b", width, 3, stride, 1, relu=True))
+        ops.append(_conv(tag + "c", tag + "b", tag + "c", 4 * width, 1, 1, 0, relu=False))
+        if proj:
+            ops.append(_conv(tag + "sc", cur, tag + "sc", 4 * width, 1, stride, 0, relu=False))
+            short = tag + "sc"
+        else:
+            short = cur
+        ops.append(dict(op="add_relu", a=tag + "c", b=short, dst=tag + "o"))
+        cur = tag + "o"
+    ops.append(dict(op="gap", src=cur, dst="feat"))
+    return ops
+
+
+def get_workload(name: str) -> Workload:
+    if name == "tiny":
+        return Workload("tiny", K=2, B=4, image=(32, 32, 3), ops=_tiny_ops(), fc_dims=[2048, 256, 10])
+    if name == "alexnet":
+        return Workload("alexnet", K=4, B=128, image=(224, 224, 3), ops=_alexnet_ops(),
+                        fc_dims=[9216, 4096, 4096, 1000])
+    if name == "vgg16":
+        return Workload("vgg16", K=8, B=64, image=(224, 224, 3), ops=_vgg16_ops(),
+                        fc_dims=[25088, 4096, 4096, 1000])
+    if name == "resnet50":
+        return Workload("resnet50", K=16, B=64, image=(224, 224, 3), ops=_resnet50_ops(),
+                        fc_dims=[2048, 1000])
+    if name == "minires":
+        return Workload("minires", K=2, B=3, image=(33, 35, 3), ops=_mini_res_ops(),
+                        fc_dims=[32, 7], notes="small residual stack for exhaustive parity")
+    raise KeyError(name)
+
+
+WORKLOAD_NAMES = ("tiny", "alexnet", "vgg16", "resnet50", "minires")
+
+
+def _out_dim(h, win, stride, pad):
+    return (h + 2 * pad - win) // stride + 1
+
+
+def shape_pass(wl: Workload, batch: int | None = None) -> Dict[str, Tuple[int, int, int, int]]:
+    """NHWC shape of every named buffer for a batch of `batch` images (default wl.B)."""
+    n = wl.B if batch is None else batch
+    shapes = {"x0": (n,) + tuple(wl.image)}
+    for op in wl.ops:
+        if op["op"] == "conv":
+            _, h, w, _ = shapes[op["src"]]
+            shapes[op["dst"]] = (n, _out_dim(h, op["R"], op["stride"], op["pad"]),
+                                 _out_dim(w, op["S"], op["stride"], op["pad"]), op["K"])
+        elif op["op"] == "pool":
+            _, h, w, c = shapes[op["src"]]
+            shapes[op["dst"]] = (n, _out_dim(h, op["win"], op["stride"], op["pad"]),
+                                 _out_dim(w, op["win"], op["stride"], op["pad"]), c)
+        elif op["op"] == "add_relu":
+            assert shapes[op["a"]] == shapes[op["b"]], (op, shapes[op["a"]], shapes[op["b"]])
+            shapes[op["dst"]] = shapes[op["a"]]
+        elif op["op"] == "gap":
+            _, h, w, c = shapes[op["src"]]
+            shapes[op["dst"]] = (n, 1, 1, c)
+        else:
+            raise ValueError(op)
+    return shapes
+
+
+def conv_param_shapes(wl: Workload) -> List[Tuple[str, Tuple[int, int, int, int]]]:
+    """[(conv name, (Kout, R, S, Cin))] in op order."""
+    shapes = shape_pass(wl, 1)
+    return [(op["name"], (op["K"], op["R"], op["S"], shapes[op["src"]][3]))
+            for op in wl.ops if op["op"] == "conv"]
+
+
+def fc_param_shapes(wl: Workload) -> List[Tuple[int, int]]:
+    """[(out, in)] per FC layer."""
+    d = wl.fc_dims
+    return [(d[i + 1], d[i]) for i in range(len(d) - 1)]
+
+
+def count_params(wl: Workload) -> Tuple[int, int]:
+    conv = sum(k * r * s * c + k for _, (k, r, s, c) in conv_param_shapes(wl))
+    fc = sum(o * i + o for o, i in fc_param_shapes(wl))
+    return conv, fc
+
+
+def conv_flops(wl: Workload, batch: int | None = None) -> Tuple[float, float]:
+    """(forward, backward) multiply-add flops of the conv stack, 2*M*N*Kd per GEMM pass;
+    the first conv has no backward-data pass."""
+    shapes = shape_pass(wl, batch)
+    fwd = bwd = 0.0
+    for op in wl.ops:
+        if op["op"] != "conv":
+            continue
+        n, ho, wo, k = shapes[op["dst"]]
+        c = shapes[op["src"]][3]
+        f = 2.0 * n * ho * wo * k * c * op["R"] * op["S"]
+        fwd += f
+        bwd += f if op["src"] == "x0" else 2 * f
+    return fwd, bwd
+
+
+def fc_flops(wl: Workload) -> float:
+    """Forward + both backward GEMMs of the FC stack (dA of the first layer included)."""
+    return sum(3 * 2.0 * wl.n * o * i for o, i in fc_param_shapes(wl))
+
+
+# ----------------------------------------------------------------------------
+# seeded draws
+# ----------------------------------------------------------------------------
+
+def rng_for(seed: int, *stream) -> np.random.Generator:
+    """Independent generator per (seed, stream key); the key is hashed position by position
+    so that tensors can be drawn in any order and at any subset."""
+    key = [int(seed)]
+    for s in stream:
+        if isinstance(s, str):
+            key += [len(s)] + [ord(ch) for ch in s]
+        else:
+            key.append(int(s))
+    return np.random.Generator(np.random.Philox(np.random.SeedSequence(key)))
+
+
+def gen_images(wl: Workload, seed: int, worker: int, batch: int | None = None) -> np.ndarray:
+    n = wl.B if batch is None else batch
+    h, w, c = wl.image
+    return rng_for(seed, "img", worker).standard_normal((n, h, w, c), dtype=np.float32)
+
+
+def gen_labels(wl: Workload, seed: int, n: int | None = None) -> np.ndarray:
+    n = wl.n if n is None else n
+    return rng_for(seed, "lab").integers(0, wl.classes, size=n, dtype=np.int32)
+
+
+def _kaiming(rng, shape, fan_in):
+    w = rng.standard_normal(shape, dtype=np.float32)
+    w *= np.float32(math.sqrt(2.0 / fan_in))
+    return w
+
+
+def _bias(rng, n, fan_in):
+    b = rng.random(n, dtype=np.float32)
+    bound = np.float32(1.0 / math.sqrt(fan_in))
+    return (b * 2 - 1) * bound
+
+
+def gen_conv_params(wl: Workload, seed: int):
+    """{name: (W [K,R,S,C], b [K])}: normal weights with variance 2/fan_in, uniform biases."""
+    out = {}
+    for name, (k, r, s, c) in conv_param_shapes(wl):
+        fan = r * s * c
+        out[name] = (_kaiming(rng_for(seed, "cw", name), (k, r, s, c), fan),
+                     _bias(rng_for(seed, "cb", name), k, fan))
+    return out
+
+
+def gen_fc_params(wl: Workload, seed: int):
+    """[(W [out,in], b [out])] per FC layer."""
+    out = []
+    for li, (o, i) in enumerate(fc_param_shapes(wl)):
+        out.append((_kaiming(rng_for(seed, "fw", li), (o, i), i),
+                    _bias(rng_for(seed, "fb", li), o, i)))
+    return out
+
+
+def gen_ps_case(numels: List[int], K: int, seed: int, fan_ins: List[int] | None = None):
+    """Parameter-server aggregation inputs: per tensor w (normal, variance 2/fan_in),
+    momentum v ~ N(0, 1e-3^2), and K gradient shards ~ N(0, 1e-3^2)."""
+    ws, vs, gs = [], [], []
+    for ti, ne in enumerate(numels):
+        fan = fan_ins[ti] if fan_ins is not None else 64
+        ws.append(_kaiming(rng_for(seed, "psw", ti), (ne,), fan))
+        v = rng_for(seed, "psv", ti).standard_normal(ne, dtype=np.float32)
+        v *= np.float32(1e-3)
+        vs.append(v)
+        shard = []
+        for k in range(K):
+            g = rng_for(seed, "psg", ti, k).standard_normal(ne, dtype=np.float32)
+            g *= np.float32(1e-3)
+            shard.append(g)
+        gs.append(shard)
+    return ws, vs, gs
+
+
+def param_tensor_numels(wl: Workload, which: str) -> Tuple[List[int], List[int]]:
+    """(numels, fan_ins) of the per-layer parameter tensors (W then b per layer)."""
+    numels, fans = [], []
+    if which == "conv":
+        for _, (k, r, s, c) in conv_param_shapes(wl):
+            numels += [k * r * s * c, k]
+            fans += [r * s * c, r * s * c]
+    else:
+        for o, i in fc_param_shapes(wl):
+            numels += [o * i, o]
+            fans += [i, i]
+    return numels, fans
