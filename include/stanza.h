@@ -1,0 +1,194 @@
+/*
+ * stanza.h — C ABI of the MI355X (gfx950) library for one GPU's share of a training
+ * iteration with the CONV and FC layers trained on separate workers.
+ *
+ * The calls follow the paper's training process with layer separation (Sec. 3.2 and
+ * Fig. 5): a CONV worker runs its conv stack forward (stanza_conv_fwd, stanza_pool_relu_fwd)
+ * and hands the activations after the last pooling layer to the FC worker
+ * ("push_activation" in the API table of Sec. 5); the FC worker runs stanza_fc_step over
+ * the row-concatenated activations of all K workers, returns the gradient of those
+ * activations ("pull_fc") and updates the FC parameters; every CONV worker continues
+ * backpropagation (stanza_pool_relu_bwd, stanza_conv_bwd_weight, stanza_conv_bwd_data);
+ * the K workers' conv gradients are summed and applied by stanza_ps_aggregate
+ * ("pull_grad" plus the optimiser step; over the whole model it is the server-side
+ * aggregation of the parameter-server iteration of Sec. 2.2).
+ *
+ * Conventions, valid for every entry point unless it says otherwise
+ *   - Pointers are DEVICE pointers unless the name starts with host_; descriptor structs
+ *     are read on the host during the call and may be freed after it returns.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls only
+ *     enqueue work and return; nothing synchronises.  Scalar results stay in device memory.
+ *   - The caller owns every buffer, workspace included.  The library allocates no device
+ *     memory and keeps no state between calls.
+ *   - Layouts: activations NHWC ([N][H][W][C], C fastest); conv weights [K][R][S][C];
+ *     FC weights [out][in]; features [n][A] with A the NHWC flattening (h*W + w)*C + c of
+ *     the last pooled map, worker k owning rows k*B .. (k+1)*B-1.
+ *   - Convolution is cross-correlation with zero padding and floor output size
+ *     Ho = (H + 2*pad_h - R)/stride_h + 1.  Pool windows are clipped to the image.
+ *   - Element type: float32 everywhere for STANZA_F32.  For STANZA_BF16 the tensors x, w, y,
+ *     dy, dx of the conv calls are bfloat16 (products accumulate in float32); bias, dw, dbias
+ *     and everything in fc_step / ps_aggregate stay float32.
+ *   - Every tensor must have fewer than 2^31 elements and a 16-byte aligned base pointer.
+ *   - Return value: STANZA_OK (0) or a negative stanza_status.  Errors are decided before
+ *     any launch (nothing has been written) except STANZA_EHIP, which reports a launch
+ *     failure.  No C++ exception crosses this boundary.
+ *   - Not checkable on the host and therefore preconditions: labels in [0, classes), finite
+ *     inputs, no aliasing between inputs and outputs other than the documented in-place
+ *     parameters.
+ */
+#ifndef STANZA_H
+#define STANZA_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    STANZA_OK = 0,
+    STANZA_EINVAL = -1,       /* a size, stride, pad or count is out of range */
+    STANZA_ENULL = -2,        /* a required pointer is NULL */
+    STANZA_EALIGN = -3,       /* a pointer is not 16-byte aligned */
+    STANZA_EUNSUPPORTED = -4, /* dtype / shape combination this build has no kernel for */
+    STANZA_EWORKSPACE = -5,   /* ws_bytes is smaller than the matching *_workspace_bytes() */
+    STANZA_EHIP = -6          /* the HIP runtime reported an error at launch */
+} stanza_status;
+
+typedef enum { STANZA_F32 = 0, STANZA_BF16 = 1 } stanza_dtype;
+
+enum {
+    STANZA_CONV_BIAS = 1u,   /* fwd: add bias[k];  bwd_weight: also produce dbias */
+    STANZA_CONV_RELU = 2u,   /* fwd: y = max(y, 0);  bwd_*: dy is gated by [y > 0] when y is given */
+    STANZA_CONV_ACCUM = 4u   /* bwd_data: dx += result instead of dx = result (residual joins) */
+};
+enum { STANZA_POOL_RELU = 1u };
+
+/* One CONV layer (Sec. 3.1).  x: [N][H][W][C], w: [K][R][S][C], y: [N][Ho][Wo][K]. */
+typedef struct {
+    int32_t N, H, W, C;
+    int32_t K, R, S;
+    int32_t stride_h, stride_w, pad_h, pad_w;
+    int32_t dtype;           /* stanza_dtype */
+    uint32_t flags;          /* STANZA_CONV_* */
+} stanza_conv_desc;
+
+/* Max-pool window over x: [N][H][W][C] -> y: [N][Ho][Wo][C]; requires pad < win, win_h*win_w <= 255. */
+typedef struct {
+    int32_t N, H, W, C;
+    int32_t win_h, win_w, stride_h, stride_w, pad_h, pad_w;
+    uint32_t flags;          /* STANZA_POOL_RELU: y = max(pool, 0), backward gated by [y > 0] */
+} stanza_pool_desc;
+
+/* The FC worker's stack: host_dims = {A, hidden_1, ..., classes} (n_layers + 1 entries), ReLU
+ * between layers and none after the last; n_samples = K*B rows of features. */
+typedef struct {
+    int32_t n_layers;
+    const int32_t *host_dims;
+    int32_t n_samples;
+    float lr, momentum, weight_decay;
+} stanza_fc_desc;
+
+const char *stanza_strerror(int status);
+int stanza_version(void);
+
+/* ---- CONV worker: forward (Sec. 3.2: "each CONV worker processes [its batch] up to the last CONV layer")
+ *   y[n,p,q,k] = bias[k] + sum_{r,s,c} x[n, p*stride_h - pad_h + r, q*stride_w - pad_w + s, c] * w[k,r,s,c]
+ * followed by max(.,0) with STANZA_CONV_RELU.  bias (float32 [K]) is required iff STANZA_CONV_BIAS.
+ * which: 0 forward, 1 backward-data, 2 backward-weight.  Forward and backward-data need no
+ * workspace (0 is returned; ws may be NULL). */
+size_t stanza_conv_workspace_bytes(const stanza_conv_desc *desc, int which);
+int stanza_conv_fwd(const stanza_conv_desc *desc, const void *x, const void *w, const float *bias,
+                    void *y, void *ws, size_t ws_bytes, void *stream);
+
+/* ---- CONV worker: backpropagation to the layer input (Sec. 3.2: "CONV workers then continue the
+ * backpropagation"):
+ *   dx[n,h,w,c] = sum_{k,r,s} g[n,(h+pad_h-r)/stride_h,(w+pad_w-s)/stride_w,k] * w[k,r,s,c]
+ * over the taps where both divisions are exact and in range, with g = dy, or dy*[y>0] when
+ * STANZA_CONV_RELU is set and y (the forward output) is not NULL.
+ * x_mask (optional, same shape as dx): the result is multiplied by [x_mask > 0] on store, which is the
+ * backward of the ReLU that produced this layer's input.  STANZA_CONV_ACCUM adds the result to the
+ * existing dx before masking. */
+int stanza_conv_bwd_data(const stanza_conv_desc *desc, const void *dy, const void *y, const void *w,
+                         const void *x_mask, void *dx, void *ws, size_t ws_bytes, void *stream);
+
+/* ---- CONV worker: filter and bias gradients ("time to compute CONV layer gradients", T_c of Sec. 4.2.1)
+ *   dw[k,r,s,c] = sum_{n,p,q} g[n,p,q,k] * x[n, p*stride_h - pad_h + r, q*stride_w - pad_w + s, c]
+ *   dbias[k]    = sum_{n,p,q} g[n,p,q,k]           (written iff STANZA_CONV_BIAS; then dbias != NULL)
+ * g as above.  dw, dbias are float32 and overwritten.  The long reduction is split over workgroups
+ * and the partial sums are added in a fixed order (results are run-to-run identical); ws must hold
+ * stanza_conv_workspace_bytes(desc, 2) bytes. */
+int stanza_conv_bwd_weight(const stanza_conv_desc *desc, const void *x, const void *dy, const void *y,
+                           float *dw, float *dbias, void *ws, size_t ws_bytes, void *stream);
+
+/* ---- Max-pool (+ReLU), kept on the CONV worker so that fewer activations cross to the FC worker
+ * (Sec. 3.2, note on the split point).
+ *   y[n,p,q,c] = max over the clipped window of x, then max(.,0) with STANZA_POOL_RELU
+ *   argmax[n,p,q,c] = i*win_w + j of the first maximum in row-major window order (uint8)
+ * backward: dx[n,h,w,c] = sum of dy over the windows whose argmax is (h,w), gated by [y > 0] with
+ * STANZA_POOL_RELU.  dtype: STANZA_F32 or STANZA_BF16 for x, y, dy, dx. */
+int stanza_pool_relu_fwd(const stanza_pool_desc *desc, int32_t dtype, const void *x, void *y, uint8_t *argmax, void *stream);
+int stanza_pool_relu_bwd(const stanza_pool_desc *desc, int32_t dtype, const void *dy, const void *y,
+                         const uint8_t *argmax, void *dx, void *stream);
+
+/* ---- Residual join and global average pool of the residual-network-shaped workload (the paper trains
+ * such a network, Sec. 6.1 table of models, without describing these layers: plain definitions).
+ *   add_relu_fwd: o = max(a + b, 0);  add_relu_bwd: dz = dout * [o > 0] (the gradient of both a and b)
+ *   gap_fwd: f[n,c] = mean_{h,w} x[n,h,w,c];  gap_bwd: dx[n,h,w,c] = df[n,c] / (H*W) */
+int stanza_add_relu_fwd(int64_t numel, int32_t dtype, const void *a, const void *b, void *o, void *stream);
+int stanza_add_relu_bwd(int64_t numel, int32_t dtype, const void *dout, const void *o, void *dz, void *stream);
+int stanza_gap_fwd(int32_t N, int32_t HW, int32_t C, int32_t dtype, const void *x, float *f, void *stream);
+int stanza_gap_bwd(int32_t N, int32_t HW, int32_t C, int32_t dtype, const float *df, void *dx, void *stream);
+
+/* float32 -> bfloat16 (round to nearest even) and back, for feeding the STANZA_BF16 conv path from
+ * float32 master weights and images. */
+int stanza_cast_f32_to_bf16(int64_t numel, const float *src, void *dst, void *stream);
+int stanza_cast_bf16_to_f32(int64_t numel, const void *src, float *dst, void *stream);
+
+/* ---- FC worker step (Sec. 3.2: the FC worker collects the activations of all workers, continues the
+ * forward pass to the loss, backpropagates through the FC layers and "the last CONV layer"'s
+ * activations, sends those gradients back and updates the FC parameters).
+ *   forward   Z_l = A_{l-1} W_l^T + b_l, A_l = max(Z_l, 0) for l < n_layers, A_0 = feats
+ *   loss      (1/n) sum_i [logsumexp(Z_L[i,:]) - Z_L[i, labels[i]]]   (mean over the GLOBAL batch n, which
+ *             is what makes the sum of the workers' conv gradients the whole-batch gradient, Eq. 1)
+ *   pred[i]   lowest index of the maximum of Z_L[i,:]
+ *   backward  dZ_L = (softmax(Z_L) - onehot)/n; db_l = column sums of dZ_l; dW_l = dZ_l^T A_{l-1};
+ *             dA_{l-1} = (dZ_l W_l) * [A_{l-1} > 0], all with the weights as they were BEFORE this call;
+ *             dfeats = dZ_1 W_1 (no gate)
+ *   update    for every W_l, b_l:  g += weight_decay*p;  v = momentum*v + g;  p -= lr*v   (Sec. 6.1)
+ * host_W, host_b, host_vW, host_vb: host arrays of n_layers device pointers; parameters and momentum
+ * buffers are updated in place.  dfeats [n][A] and loss (1 float) are outputs; pred [n] may be NULL.
+ * ws must hold stanza_fc_workspace_bytes(desc) bytes. */
+size_t stanza_fc_workspace_bytes(const stanza_fc_desc *desc);
+int stanza_fc_step(const stanza_fc_desc *desc, const float *feats, const int32_t *labels,
+                   float *const *host_W, float *const *host_b, float *const *host_vW, float *const *host_vb,
+                   float *dfeats, float *loss, int32_t *pred, void *ws, size_t ws_bytes, void *stream);
+
+/* ---- Gradient aggregation and update (Sec. 3.2: the CONV workers "exchange [their gradients] to get
+ * global information sum_x grad l(x, w_conv)" and update; Sec. 2.2: servers aggregate the gradients
+ * from all workers and perform the global update).  Per tensor t and element i:
+ *   g = scale * (g_0[i] + g_1[i] + ... + g_{K-1}[i]) + weight_decay * w[i]   (shards added in index order)
+ *   v[i] = momentum * v[i] + g;   w[i] -= lr * v[i]
+ * host_numel [n_tensors]; host_w, host_v [n_tensors] device pointers (updated in place);
+ * host_grads [K * n_tensors] device pointers, shard-major: host_grads[k*n_tensors + t].
+ * One launch covers all tensors.  ws receives the pointer table
+ * (stanza_ps_workspace_bytes(n_tensors, K) bytes, uploaded on `stream` from the host arrays, which
+ * may be freed when the call returns).
+ * stanza_ps_plan uploads the table only; it is the one call that waits (for its own small copy on
+ * `stream`).  stanza_ps_aggregate_planned runs the launch on a table a previous stanza_ps_plan /
+ * stanza_ps_aggregate put into ws (same n_tensors, host_numel, K), for callers whose buffers stay put
+ * from one iteration to the next; it only enqueues. */
+size_t stanza_ps_workspace_bytes(int32_t n_tensors, int32_t K);
+int stanza_ps_plan(int32_t n_tensors, const int64_t *host_numel, float *const *host_w, float *const *host_v,
+                   const float *const *host_grads, int32_t K, void *ws, size_t ws_bytes, void *stream);
+int stanza_ps_aggregate_planned(int32_t n_tensors, const int64_t *host_numel, int32_t K, float scale, float lr,
+                                float momentum, float weight_decay, const void *ws, size_t ws_bytes, void *stream);
+int stanza_ps_aggregate(int32_t n_tensors, const int64_t *host_numel, float *const *host_w, float *const *host_v,
+                        const float *const *host_grads, int32_t K, float scale, float lr, float momentum,
+                        float weight_decay, void *ws, size_t ws_bytes, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* STANZA_H */

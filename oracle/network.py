@@ -60,7 +60,7 @@ def conv_stack_backward(o: Oracle, ops: List[dict], buf, params, dfeat):
             x = buf[op["src"]]
             n, h, w, c = x.shape
             g = ConvGeom(n, h, w, c, op["K"], op["R"], op["S"], op["stride"], op["pad"])
-            dy = grad.pop(op["dst"])
+            dy = grad[op["dst"]]
             if op["relu"]:
                 dy = o.relu_bwd(dy, buf[op["dst"]])
             wt, _ = params[op["name"]]
@@ -71,13 +71,13 @@ def conv_stack_backward(o: Oracle, ops: List[dict], buf, params, dfeat):
             x = buf[op["src"]]
             n, h, w, c = x.shape
             g = PoolGeom(n, h, w, c, op["win"], op["stride"], op["pad"], op["relu"])
-            give(op["src"], o.pool_relu_bwd(g, grad.pop(op["dst"]), buf[op["dst"]], buf[op["dst"] + "#argmax"]))
+            give(op["src"], o.pool_relu_bwd(g, grad[op["dst"]], buf[op["dst"]], buf[op["dst"] + "#argmax"]))
         elif kind == "add_relu":
-            dz = o.relu_bwd(grad.pop(op["dst"]), buf[op["dst"]])
+            dz = o.relu_bwd(grad[op["dst"]], buf[op["dst"]])
             give(op["a"], dz)
             give(op["b"], dz)
         elif kind == "gap":
-            give(op["src"], o.gap_bwd(grad.pop(op["dst"]), buf[op["src"]].shape))
+            give(op["src"], o.gap_bwd(grad[op["dst"]], buf[op["src"]].shape))
         else:
             raise ValueError(kind)
     return pgrads, grad

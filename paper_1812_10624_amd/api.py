@@ -1,0 +1,231 @@
+"""ctypes binding of libstanza.so: the same names as include/stanza.h, argument marshalling only.
+
+Tensors are torch CUDA(ROCm) tensors used purely as device buffers; every function passes
+`tensor.data_ptr()` and the current stream's handle through the C ABI.  There is no fallback: if
+the library is missing or a call returns an error, an exception is raised.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import List, Optional, Sequence
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libstanza.so")
+
+F32, BF16 = 0, 1
+CONV_BIAS, CONV_RELU, CONV_ACCUM = 1, 2, 4
+POOL_RELU = 1
+
+EXPORTS = (
+    "stanza_strerror", "stanza_version", "stanza_conv_workspace_bytes", "stanza_conv_fwd", "stanza_conv_bwd_data",
+    "stanza_conv_bwd_weight", "stanza_pool_relu_fwd", "stanza_pool_relu_bwd", "stanza_add_relu_fwd",
+    "stanza_add_relu_bwd", "stanza_gap_fwd", "stanza_gap_bwd", "stanza_cast_f32_to_bf16", "stanza_cast_bf16_to_f32",
+    "stanza_fc_workspace_bytes", "stanza_fc_step", "stanza_ps_workspace_bytes", "stanza_ps_plan",
+    "stanza_ps_aggregate_planned", "stanza_ps_aggregate",
+)
+
+
+class StanzaError(RuntimeError):
+    pass
+
+
+class ConvDesc(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("N", "H", "W", "C", "K", "R", "S", "stride_h", "stride_w", "pad_h", "pad_w", "dtype")] + \
+               [("flags", C.c_uint32)]
+
+
+class PoolDesc(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("N", "H", "W", "C", "win_h", "win_w", "stride_h", "stride_w", "pad_h", "pad_w")] + \
+               [("flags", C.c_uint32)]
+
+
+class FcDesc(C.Structure):
+    _fields_ = [("n_layers", C.c_int32), ("host_dims", C.POINTER(C.c_int32)), ("n_samples", C.c_int32),
+                ("lr", C.c_float), ("momentum", C.c_float), ("weight_decay", C.c_float)]
+
+
+_lib = None
+
+
+def load() -> C.CDLL:
+    """Load libstanza.so (built beforehand by `__graft_entry__.build()` / `python -m paper_1812_10624_amd.build`)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise StanzaError(f"{LIB_PATH} is missing: build it with `python -m paper_1812_10624_amd.build` (no CPU fallback exists)")
+    lib = C.CDLL(LIB_PATH)
+    vp, sz, i32, i64, f32 = C.c_void_p, C.c_size_t, C.c_int32, C.c_int64, C.c_float
+    lib.stanza_strerror.restype = C.c_char_p
+    lib.stanza_strerror.argtypes = [C.c_int]
+    lib.stanza_version.restype = C.c_int
+    lib.stanza_conv_workspace_bytes.restype = sz
+    lib.stanza_conv_workspace_bytes.argtypes = [C.POINTER(ConvDesc), C.c_int]
+    lib.stanza_conv_fwd.argtypes = [C.POINTER(ConvDesc), vp, vp, vp, vp, vp, sz, vp]
+    lib.stanza_conv_bwd_data.argtypes = [C.POINTER(ConvDesc), vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.stanza_conv_bwd_weight.argtypes = [C.POINTER(ConvDesc), vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.stanza_pool_relu_fwd.argtypes = [C.POINTER(PoolDesc), i32, vp, vp, vp, vp]
+    lib.stanza_pool_relu_bwd.argtypes = [C.POINTER(PoolDesc), i32, vp, vp, vp, vp, vp]
+    lib.stanza_add_relu_fwd.argtypes = [i64, i32, vp, vp, vp, vp]
+    lib.stanza_add_relu_bwd.argtypes = [i64, i32, vp, vp, vp, vp]
+    lib.stanza_gap_fwd.argtypes = [i32, i32, i32, i32, vp, vp, vp]
+    lib.stanza_gap_bwd.argtypes = [i32, i32, i32, i32, vp, vp, vp]
+    lib.stanza_cast_f32_to_bf16.argtypes = [i64, vp, vp, vp]
+    lib.stanza_cast_bf16_to_f32.argtypes = [i64, vp, vp, vp]
+    lib.stanza_fc_workspace_bytes.restype = sz
+    lib.stanza_fc_workspace_bytes.argtypes = [C.POINTER(FcDesc)]
+    lib.stanza_fc_step.argtypes = [C.POINTER(FcDesc), vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.stanza_ps_workspace_bytes.restype = sz
+    lib.stanza_ps_workspace_bytes.argtypes = [i32, i32]
+    lib.stanza_ps_plan.argtypes = [i32, vp, vp, vp, vp, i32, vp, sz, vp]
+    lib.stanza_ps_aggregate_planned.argtypes = [i32, vp, i32, f32, f32, f32, f32, vp, sz, vp]
+    lib.stanza_ps_aggregate.argtypes = [i32, vp, vp, vp, vp, i32, f32, f32, f32, f32, vp, sz, vp]
+    _lib = lib
+    return lib
+
+
+def _check(rc: int, what: str):
+    if rc != 0:
+        raise StanzaError(f"{what}: {load().stanza_strerror(rc).decode()} ({rc})")
+
+
+def _ptr(t: Optional[torch.Tensor]):
+    if t is None:
+        return None
+    assert t.is_cuda and t.is_contiguous(), "device-resident contiguous tensor expected"
+    return C.c_void_p(t.data_ptr())
+
+
+def _stream():
+    return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _ws(t: Optional[torch.Tensor]):
+    return (None, 0) if t is None else (_ptr(t), t.numel() * t.element_size())
+
+
+def conv_desc(N, H, W, Cin, K, R, S, stride, pad, dtype=F32, flags=0) -> ConvDesc:
+    return ConvDesc(N, H, W, Cin, K, R, S, stride, stride, pad, pad, dtype, flags)
+
+
+def pool_desc(N, H, W, Cc, win, stride, pad, relu=True) -> PoolDesc:
+    return PoolDesc(N, H, W, Cc, win, win, stride, stride, pad, pad, POOL_RELU if relu else 0)
+
+
+def conv_out_hw(d: ConvDesc):
+    return ((d.H + 2 * d.pad_h - d.R) // d.stride_h + 1, (d.W + 2 * d.pad_w - d.S) // d.stride_w + 1)
+
+
+def stanza_conv_workspace_bytes(d: ConvDesc, which: int) -> int:
+    return int(load().stanza_conv_workspace_bytes(C.byref(d), which))
+
+
+def stanza_conv_fwd(d: ConvDesc, x, w, bias, y, ws=None):
+    p, n = _ws(ws)
+    _check(load().stanza_conv_fwd(C.byref(d), _ptr(x), _ptr(w), _ptr(bias), _ptr(y), p, n, _stream()), "stanza_conv_fwd")
+
+
+def stanza_conv_bwd_data(d: ConvDesc, dy, y, w, x_mask, dx, ws=None):
+    p, n = _ws(ws)
+    _check(load().stanza_conv_bwd_data(C.byref(d), _ptr(dy), _ptr(y), _ptr(w), _ptr(x_mask), _ptr(dx), p, n, _stream()),
+           "stanza_conv_bwd_data")
+
+
+def stanza_conv_bwd_weight(d: ConvDesc, x, dy, y, dw, dbias, ws):
+    p, n = _ws(ws)
+    _check(load().stanza_conv_bwd_weight(C.byref(d), _ptr(x), _ptr(dy), _ptr(y), _ptr(dw), _ptr(dbias), p, n, _stream()),
+           "stanza_conv_bwd_weight")
+
+
+def stanza_pool_relu_fwd(d: PoolDesc, x, y, argmax, dtype=F32):
+    _check(load().stanza_pool_relu_fwd(C.byref(d), dtype, _ptr(x), _ptr(y), _ptr(argmax), _stream()), "stanza_pool_relu_fwd")
+
+
+def stanza_pool_relu_bwd(d: PoolDesc, dy, y, argmax, dx, dtype=F32):
+    _check(load().stanza_pool_relu_bwd(C.byref(d), dtype, _ptr(dy), _ptr(y), _ptr(argmax), _ptr(dx), _stream()), "stanza_pool_relu_bwd")
+
+
+def stanza_add_relu_fwd(a, b, o, dtype=F32):
+    _check(load().stanza_add_relu_fwd(a.numel(), dtype, _ptr(a), _ptr(b), _ptr(o), _stream()), "stanza_add_relu_fwd")
+
+
+def stanza_add_relu_bwd(dout, o, dz, dtype=F32):
+    _check(load().stanza_add_relu_bwd(dout.numel(), dtype, _ptr(dout), _ptr(o), _ptr(dz), _stream()), "stanza_add_relu_bwd")
+
+
+def stanza_gap_fwd(x, f, dtype=F32):
+    n, h, w, c = x.shape
+    _check(load().stanza_gap_fwd(n, h * w, c, dtype, _ptr(x), _ptr(f), _stream()), "stanza_gap_fwd")
+
+
+def stanza_gap_bwd(df, dx, dtype=F32):
+    n, h, w, c = dx.shape
+    _check(load().stanza_gap_bwd(n, h * w, c, dtype, _ptr(df), _ptr(dx), _stream()), "stanza_gap_bwd")
+
+
+def stanza_cast_f32_to_bf16(src, dst):
+    _check(load().stanza_cast_f32_to_bf16(src.numel(), _ptr(src), _ptr(dst), _stream()), "stanza_cast_f32_to_bf16")
+
+
+def stanza_cast_bf16_to_f32(src, dst):
+    _check(load().stanza_cast_bf16_to_f32(src.numel(), _ptr(src), _ptr(dst), _stream()), "stanza_cast_bf16_to_f32")
+
+
+class FcPlan:
+    """Host-side descriptor of an FC stack plus its keep-alive arrays."""
+
+    def __init__(self, dims: Sequence[int], n_samples: int, lr: float, momentum: float, weight_decay: float):
+        self.dims = (C.c_int32 * len(dims))(*dims)
+        self.desc = FcDesc(len(dims) - 1, self.dims, n_samples, lr, momentum, weight_decay)
+
+    def workspace_bytes(self) -> int:
+        return int(load().stanza_fc_workspace_bytes(C.byref(self.desc)))
+
+
+def _ptr_array(ts: Sequence[torch.Tensor]):
+    for t in ts:
+        assert t.is_cuda and t.is_contiguous()
+    return (C.c_void_p * len(ts))(*[t.data_ptr() for t in ts])
+
+
+def stanza_fc_step(plan: FcPlan, feats, labels, W: List[torch.Tensor], b, vW, vb, dfeats, loss, pred, ws):
+    p, n = _ws(ws)
+    _check(load().stanza_fc_step(C.byref(plan.desc), _ptr(feats), _ptr(labels), _ptr_array(W), _ptr_array(b), _ptr_array(vW),
+                                 _ptr_array(vb), _ptr(dfeats), _ptr(loss), _ptr(pred), p, n, _stream()), "stanza_fc_step")
+
+
+def stanza_ps_workspace_bytes(n_tensors: int, K: int) -> int:
+    return int(load().stanza_ps_workspace_bytes(n_tensors, K))
+
+
+def _ps_args(w, v, grads):
+    """w, v: lists of tensors; grads: list over shards of lists over tensors."""
+    nt, K = len(w), len(grads)
+    numel = (C.c_int64 * nt)(*[t.numel() for t in w])
+    flat = [g for shard in grads for g in shard]
+    assert len(flat) == nt * K
+    return nt, K, numel, _ptr_array(w), _ptr_array(v), _ptr_array(flat)
+
+
+def stanza_ps_plan(w, v, grads, ws):
+    nt, K, numel, pw, pv, pg = _ps_args(w, v, grads)
+    p, n = _ws(ws)
+    _check(load().stanza_ps_plan(nt, numel, pw, pv, pg, K, p, n, _stream()), "stanza_ps_plan")
+    return nt, K, numel
+
+
+def stanza_ps_aggregate_planned(plan, scale, lr, momentum, weight_decay, ws):
+    nt, K, numel = plan
+    p, n = _ws(ws)
+    _check(load().stanza_ps_aggregate_planned(nt, numel, K, scale, lr, momentum, weight_decay, p, n, _stream()),
+           "stanza_ps_aggregate_planned")
+
+
+def stanza_ps_aggregate(w, v, grads, scale, lr, momentum, weight_decay, ws):
+    nt, K, numel, pw, pv, pg = _ps_args(w, v, grads)
+    p, n = _ws(ws)
+    _check(load().stanza_ps_aggregate(nt, numel, pw, pv, pg, K, scale, lr, momentum, weight_decay, p, n, _stream()),
+           "stanza_ps_aggregate")

@@ -1,0 +1,253 @@
+// CONV-worker entry points: forward, backward-data, backward-weight (paper Sec. 3.2), all three as
+// launches of the implicit-GEMM engine in igemm.h, plus the two small fixed-order reductions the
+// filter gradient needs (split partial sums, bias-gradient column sums).
+#include "internal.h"
+
+namespace stanza {
+
+int conv_geometry(const stanza_conv_desc *d, ConvGeo *g)
+{
+    if (d->N <= 0 || d->H <= 0 || d->W <= 0 || d->C <= 0 || d->K <= 0 || d->R <= 0 || d->S <= 0) return STANZA_EINVAL;
+    if (d->stride_h <= 0 || d->stride_w <= 0 || d->pad_h < 0 || d->pad_w < 0) return STANZA_EINVAL;
+    if (d->pad_h >= d->R || d->pad_w >= d->S) return STANZA_EINVAL;
+    if (d->H + 2 * d->pad_h < d->R || d->W + 2 * d->pad_w < d->S) return STANZA_EINVAL;
+    const int Ho = (d->H + 2 * d->pad_h - d->R) / d->stride_h + 1;
+    const int Wo = (d->W + 2 * d->pad_w - d->S) / d->stride_w + 1;
+    const int64_t lim = (int64_t(1) << 31) - 1;
+    if ((int64_t)d->N * d->H * d->W * d->C > lim || (int64_t)d->N * Ho * Wo * d->K > lim ||
+        (int64_t)d->K * d->R * d->S * d->C > lim)
+        return STANZA_EINVAL;
+    *g = ConvGeo{d->N, d->H, d->W, d->C, d->K, d->R, d->S, d->stride_h, d->stride_w, d->pad_h, d->pad_w, Ho, Wo};
+    return STANZA_OK;
+}
+
+// ------------------------------------------------------------------ tile choice and launch
+template <int MODE, int BM, int BN, int WM, int WN>
+static int launch_tile(GemmParams &p, bool vec, int splits, hipStream_t st)
+{
+    p.tilesM = cdiv(p.M, BM);
+    p.tilesN = cdiv(p.Nn, BN);
+    p.tiles = p.tilesM * p.tilesN;
+    dim3 grid((unsigned)(cdiv(p.tiles, 8) * 8), (unsigned)splits);
+    if (vec)
+        hipLaunchKernelGGL((igemm_kernel<MODE, BM, BN, WM, WN, true>), grid, dim3(NTHREADS), 0, st, p);
+    else
+        hipLaunchKernelGGL((igemm_kernel<MODE, BM, BN, WM, WN, false>), grid, dim3(NTHREADS), 0, st, p);
+    return launch_status();
+}
+
+template <int MODE>
+static int launch_mode(GemmParams &p, bool vec, int splits, hipStream_t st)
+{
+    // Tall tiles while they still give every CU a couple of workgroups; 64-wide when the GEMM is narrow.
+    const int want = 512;
+    if (p.Nn <= 64) {
+        if (MODE != MODE_BWD_WEIGHT && (int64_t)cdiv(p.M, 256) * splits >= want) return launch_tile<MODE, 256, 64, 4, 1>(p, vec, splits, st);
+        if ((int64_t)cdiv(p.M, 128) * splits >= want) return launch_tile<MODE, 128, 64, 2, 2>(p, vec, splits, st);
+        return launch_tile<MODE, 64, 64, 2, 2>(p, vec, splits, st);
+    }
+    if (p.M <= 64 || (int64_t)cdiv(p.M, 128) * cdiv(p.Nn, 128) * splits < want) {
+        if (p.M <= 64 || (int64_t)cdiv(p.M, 64) * cdiv(p.Nn, 128) * splits < want * 2)
+            return launch_tile<MODE, 64, 128, 2, 2>(p, vec, splits, st);
+    }
+    return launch_tile<MODE, 128, 128, 2, 2>(p, vec, splits, st);
+}
+
+int launch_igemm(int mode, GemmParams &p, int splits, hipStream_t st)
+{
+    const ConvGeo &g = p.g;
+    if (p.M <= 0 || p.Nn <= 0 || p.Kd <= 0 || splits <= 0) return STANZA_EINVAL;
+    switch (mode) {
+    case MODE_FWD: return launch_mode<MODE_FWD>(p, g.C % 4 == 0, 1, st);
+    case MODE_BWD_DATA: return launch_mode<MODE_BWD_DATA>(p, g.C % 4 == 0 && g.K % 4 == 0, 1, st);
+    case MODE_BWD_WEIGHT: return launch_mode<MODE_BWD_WEIGHT>(p, g.C % 4 == 0 && g.K % 4 == 0, splits, st);
+    }
+    return STANZA_EINVAL;
+}
+
+// ------------------------------------------------------------------ fixed-order reductions
+__global__ void split_reduce_kernel(const float *__restrict__ partial, int splits, size_t numel, float *__restrict__ out)
+{
+    const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= numel) return;
+    float s = 0.f;
+    for (int k = 0; k < splits; ++k) s += partial[(size_t)k * numel + i];
+    out[i] = s;
+}
+
+int launch_split_reduce(const float *partial, int splits, size_t numel, float *out, hipStream_t st)
+{
+    hipLaunchKernelGGL(split_reduce_kernel, dim3((unsigned)cdiv64(numel, 256)), dim3(256), 0, st, partial, splits, numel, out);
+    return launch_status();
+}
+
+// pass 1: workgroup (bx, by) sums rows [bx*rows_per, (bx+1)*rows_per) of columns by*64 .. by*64+63;
+// wavefront w takes every 4th row, lanes take consecutive columns (256-byte row segments).
+__global__ __launch_bounds__(256) void colsum_pass1(const float *__restrict__ a, const float *__restrict__ mask, int rows, int cols,
+                                                    int rows_per, float *__restrict__ scratch)
+{
+    __shared__ float red[4][64];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int col = blockIdx.y * 64 + lane;
+    const int rbeg = blockIdx.x * rows_per, rend = min(rows, rbeg + rows_per);
+    float s = 0.f;
+    if (col < cols) {
+        for (int r = rbeg + wave; r < rend; r += 4) {
+            const size_t o = (size_t)r * cols + col;
+            float v = a[o];
+            if (mask) v = mask[o] > 0.f ? v : 0.f;
+            s += v;
+        }
+    }
+    red[wave][lane] = s;
+    __syncthreads();
+    if (wave == 0 && col < cols) scratch[(size_t)blockIdx.x * cols + col] = (red[0][lane] + red[1][lane]) + (red[2][lane] + red[3][lane]);
+}
+
+__global__ void colsum_pass2(const float *__restrict__ scratch, int blocks, int cols, float *__restrict__ out,
+                             float *__restrict__ sgd_p, float *__restrict__ sgd_v, float lr, float mom, float wd)
+{
+    const int col = blockIdx.x * blockDim.x + threadIdx.x;
+    if (col >= cols) return;
+    float s = 0.f;
+    for (int b = 0; b < blocks; ++b) s += scratch[(size_t)b * cols + col];
+    if (sgd_p) {
+        const float w = sgd_p[col];
+        const float vel = mom * sgd_v[col] + (s + wd * w);
+        sgd_v[col] = vel;
+        sgd_p[col] = w - lr * vel;
+    } else {
+        out[col] = s;
+    }
+}
+
+int colsum_blocks(int rows) { return max(1, min(512, cdiv(rows, 64))); }
+
+int launch_colsum(const float *a, const float *mask, int rows, int cols, float *scratch, int blocks, float *out,
+                  float *sgd_p, float *sgd_v, float lr, float mom, float wd, hipStream_t st)
+{
+    const int rows_per = cdiv(rows, blocks);
+    hipLaunchKernelGGL(colsum_pass1, dim3(blocks, cdiv(cols, 64)), dim3(256), 0, st, a, mask, rows, cols, rows_per, scratch);
+    int rc = launch_status();
+    if (rc) return rc;
+    hipLaunchKernelGGL(colsum_pass2, dim3(cdiv(cols, 256)), dim3(256), 0, st, scratch, blocks, cols, out, sgd_p, sgd_v, lr, mom, wd);
+    return launch_status();
+}
+
+WgradPlan plan_wgrad(const ConvGeo &g, bool want_bias)
+{
+    WgradPlan pl{};
+    const int M = g.K, Nn = g.R * g.S * g.C;
+    const int64_t red = (int64_t)g.N * g.Ho * g.Wo;
+    const int chunks = (int)cdiv64(red, BK);
+    const int bm = M <= 64 ? 64 : 128, bn = Nn <= 64 ? 64 : 128;
+    const int tiles = cdiv(M, bm) * cdiv(Nn, bn);
+    int splits = cdiv(1024, tiles);
+    splits = max(1, min(splits, chunks / 8));
+    pl.chunks_per_split = cdiv(chunks, splits);
+    pl.splits = cdiv(chunks, pl.chunks_per_split);
+    pl.partial_floats = pl.splits > 1 ? (size_t)pl.splits * M * Nn : 0;
+    pl.db_blocks = want_bias ? colsum_blocks((int)red) : 0;
+    pl.db_floats = (size_t)pl.db_blocks * g.K;
+    pl.bytes = round256(pl.partial_floats * 4) + round256(pl.db_floats * 4);
+    return pl;
+}
+
+}  // namespace stanza
+
+using namespace stanza;
+
+extern "C" size_t stanza_conv_workspace_bytes(const stanza_conv_desc *desc, int which)
+{
+    ConvGeo g;
+    if (!desc || which != 2 || conv_geometry(desc, &g) != STANZA_OK) return 0;
+    return plan_wgrad(g, (desc->flags & STANZA_CONV_BIAS) != 0).bytes;
+}
+
+static int check_dtype(const stanza_conv_desc *d)
+{
+    if (d->dtype == STANZA_F32) return STANZA_OK;
+    return STANZA_EUNSUPPORTED;
+}
+
+extern "C" int stanza_conv_fwd(const stanza_conv_desc *desc, const void *x, const void *w, const float *bias, void *y,
+                               void *ws, size_t ws_bytes, void *stream)
+{
+    (void)ws; (void)ws_bytes;
+    if (!desc) return STANZA_ENULL;
+    GemmParams p{};
+    int rc = conv_geometry(desc, &p.g);
+    if (rc) return rc;
+    if ((rc = check_dtype(desc))) return rc;
+    const bool has_bias = desc->flags & STANZA_CONV_BIAS;
+    if (!x || !w || !y || (has_bias && !bias)) return STANZA_ENULL;
+    if (!aligned16(x) || !aligned16(w) || !aligned16(y)) return STANZA_EALIGN;
+    p.a = (const float *)x;
+    p.b = (const float *)w;
+    p.out = (float *)y;
+    p.bias = bias;
+    p.M = p.g.N * p.g.Ho * p.g.Wo;
+    p.Nn = p.g.K;
+    p.Kd = p.g.R * p.g.S * p.g.C;
+    p.flags = (has_bias ? EPI_BIAS : 0u) | ((desc->flags & STANZA_CONV_RELU) ? EPI_RELU : 0u);
+    return launch_igemm(MODE_FWD, p, 1, (hipStream_t)stream);
+}
+
+extern "C" int stanza_conv_bwd_data(const stanza_conv_desc *desc, const void *dy, const void *y, const void *w,
+                                    const void *x_mask, void *dx, void *ws, size_t ws_bytes, void *stream)
+{
+    (void)ws; (void)ws_bytes;
+    if (!desc) return STANZA_ENULL;
+    GemmParams p{};
+    int rc = conv_geometry(desc, &p.g);
+    if (rc) return rc;
+    if ((rc = check_dtype(desc))) return rc;
+    if (!dy || !w || !dx) return STANZA_ENULL;
+    if (!aligned16(dy) || !aligned16(w) || !aligned16(dx) || !aligned16(y) || !aligned16(x_mask)) return STANZA_EALIGN;
+    p.a = (const float *)dy;
+    p.amask = (desc->flags & STANZA_CONV_RELU) ? (const float *)y : nullptr;
+    p.b = (const float *)w;
+    p.out = (float *)dx;
+    p.xmask = (const float *)x_mask;
+    p.M = p.g.N * p.g.H * p.g.W;
+    p.Nn = p.g.C;
+    p.Kd = p.g.R * p.g.S * p.g.K;
+    p.flags = ((desc->flags & STANZA_CONV_ACCUM) ? EPI_ACCUM : 0u) | (x_mask ? EPI_XMASK : 0u) | (p.amask ? LOAD_AMASK : 0u);
+    return launch_igemm(MODE_BWD_DATA, p, 1, (hipStream_t)stream);
+}
+
+extern "C" int stanza_conv_bwd_weight(const stanza_conv_desc *desc, const void *x, const void *dy, const void *y, float *dw,
+                                      float *dbias, void *ws, size_t ws_bytes, void *stream)
+{
+    if (!desc) return STANZA_ENULL;
+    GemmParams p{};
+    int rc = conv_geometry(desc, &p.g);
+    if (rc) return rc;
+    if ((rc = check_dtype(desc))) return rc;
+    const bool want_bias = desc->flags & STANZA_CONV_BIAS;
+    if (!x || !dy || !dw || (want_bias && !dbias)) return STANZA_ENULL;
+    if (!aligned16(x) || !aligned16(dy) || !aligned16(dw) || !aligned16(y) || !aligned16(ws)) return STANZA_EALIGN;
+    const WgradPlan pl = plan_wgrad(p.g, want_bias);
+    if (pl.bytes > 0 && (!ws || ws_bytes < pl.bytes)) return ws ? STANZA_EWORKSPACE : STANZA_ENULL;
+    hipStream_t st = (hipStream_t)stream;
+    float *partial = (float *)ws;
+    float *dbscratch = (float *)((char *)ws + round256(pl.partial_floats * 4));
+    p.a = (const float *)dy;
+    p.amask = (desc->flags & STANZA_CONV_RELU) ? (const float *)y : nullptr;
+    p.b = (const float *)x;
+    p.M = p.g.K;
+    p.Nn = p.g.R * p.g.S * p.g.C;
+    p.Kd = p.g.N * p.g.Ho * p.g.Wo;
+    p.chunks_per_split = pl.chunks_per_split;
+    p.flags = p.amask ? LOAD_AMASK : 0u;
+    p.out = pl.splits > 1 ? partial : dw;
+    rc = launch_igemm(MODE_BWD_WEIGHT, p, pl.splits, st);
+    if (rc) return rc;
+    if (pl.splits > 1) {
+        rc = launch_split_reduce(partial, pl.splits, (size_t)p.M * p.Nn, dw, st);
+        if (rc) return rc;
+    }
+    if (want_bias)
+        rc = launch_colsum((const float *)dy, p.amask, p.Kd, p.g.K, dbscratch, pl.db_blocks, dbias, nullptr, nullptr, 0.f, 0.f, 0.f, st);
+    return rc;
+}

@@ -1,0 +1,187 @@
+// FC-worker step (paper Sec. 3.2): forward over the concatenated activations of all CONV workers,
+// mean softmax cross-entropy over the global batch, backpropagation through the FC layers down to the
+// gradient of the received activations, and the momentum-SGD update (Sec. 6.1) of every FC parameter.
+//
+// The three GEMMs of a layer are launches of the implicit-GEMM engine with a 1x1 "image":
+//   forward    Z  = A W^T + b        FWD        (N=n, H=W=1, C=in,  K=out)
+//   to input   dA = dZ W             BWD_DATA   gated by [A > 0] on store
+//   to weights dW = dZ^T A           BWD_WEIGHT with the update fused into the tile store, so the
+//                                    gradient matrix never goes to memory
+// dA is always issued before the update of the same layer's W, so it sees the pre-update weights.
+#include "internal.h"
+
+namespace stanza {
+
+// One wavefront per row: max / argmax (lowest index wins ties), sum of exponentials, then the gradient
+// (softmax - onehot)/n and the row's loss term  log(sum) + max - z[label].
+__global__ __launch_bounds__(256) void softmax_ce_kernel(int n, int classes, const float *__restrict__ z, const int32_t *__restrict__ labels,
+                                                         float *__restrict__ dz, float *__restrict__ row_loss, int32_t *__restrict__ pred)
+{
+    const int lane = threadIdx.x & 63;
+    const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (row >= n) return;
+    const float *zr = z + (size_t)row * classes;
+    float best = -INFINITY;
+    int bidx = 0x7fffffff;
+    for (int j = lane; j < classes; j += 64) {
+        const float v = zr[j];
+        if (v > best) { best = v; bidx = j; }   // ascending j per lane: first maximum kept
+    }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) {
+        const float ob = __shfl_xor(best, off);
+        const int oi = __shfl_xor(bidx, off);
+        if (ob > best || (ob == best && oi < bidx)) { best = ob; bidx = oi; }
+    }
+    float sum = 0.f;
+    for (int j = lane; j < classes; j += 64) sum += expf(zr[j] - best);
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) sum += __shfl_xor(sum, off);
+    const int label = labels[row];
+    const float inv = 1.f / sum, invn = 1.f / (float)n;
+    float *dr = dz + (size_t)row * classes;
+    for (int j = lane; j < classes; j += 64) {
+        const float sm = expf(zr[j] - best) * inv;
+        dr[j] = (sm - (j == label ? 1.f : 0.f)) * invn;
+    }
+    if (lane == 0) {
+        const float zl = ((unsigned)label < (unsigned)classes) ? zr[label] : NAN;
+        row_loss[row] = logf(sum) + best - zl;
+        if (pred) pred[row] = bidx;
+    }
+}
+
+// Mean of the row losses, summed in a fixed order by one workgroup.
+__global__ __launch_bounds__(256) void mean_loss_kernel(int n, const float *__restrict__ row_loss, float *__restrict__ loss)
+{
+    __shared__ float red[256];
+    float s = 0.f;
+    for (int i = threadIdx.x; i < n; i += 256) s += row_loss[i];
+    red[threadIdx.x] = s;
+    __syncthreads();
+    for (int w = 128; w > 0; w >>= 1) {
+        if (threadIdx.x < w) red[threadIdx.x] += red[threadIdx.x + w];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) *loss = red[0] / (float)n;
+}
+
+struct FcLayout {
+    size_t act_off[32];   // float offset of A_l (l = 1..L) in the workspace
+    size_t dz_off[2];     // two gradient buffers of n * max_width floats
+    size_t row_loss_off;
+    size_t db_off;        // column-sum scratch: colsum_blocks(n) * max_width
+    size_t floats;
+};
+
+static int fc_layout(const stanza_fc_desc *d, FcLayout *lay)
+{
+    if (!d || !d->host_dims) return STANZA_ENULL;
+    if (d->n_layers <= 0 || d->n_layers > 30 || d->n_samples <= 0) return STANZA_EINVAL;
+    size_t off = 0;
+    int maxw = 0;
+    for (int l = 0; l <= d->n_layers; ++l) {
+        const int w = d->host_dims[l];
+        if (w <= 0 || (int64_t)w * d->n_samples >= (int64_t(1) << 31)) return STANZA_EINVAL;
+        if (l > 0) {
+            if ((int64_t)w * d->host_dims[l - 1] >= (int64_t(1) << 31)) return STANZA_EINVAL;
+            lay->act_off[l] = off;
+            off += (round256((size_t)d->n_samples * w * 4)) / 4;
+            maxw = max(maxw, w);
+        }
+    }
+    const size_t dzf = round256((size_t)d->n_samples * maxw * 4) / 4;
+    lay->dz_off[0] = off; off += dzf;
+    lay->dz_off[1] = off; off += dzf;
+    lay->row_loss_off = off; off += round256((size_t)d->n_samples * 4) / 4;
+    lay->db_off = off; off += round256((size_t)colsum_blocks(d->n_samples) * maxw * 4) / 4;
+    lay->floats = off;
+    return STANZA_OK;
+}
+
+static ConvGeo fc_geo(int n, int in, int out) { return ConvGeo{n, 1, 1, in, out, 1, 1, 1, 1, 0, 0, 1, 1}; }
+
+}  // namespace stanza
+
+using namespace stanza;
+
+extern "C" size_t stanza_fc_workspace_bytes(const stanza_fc_desc *desc)
+{
+    FcLayout lay;
+    if (fc_layout(desc, &lay) != STANZA_OK) return 0;
+    return lay.floats * 4;
+}
+
+extern "C" int stanza_fc_step(const stanza_fc_desc *desc, const float *feats, const int32_t *labels, float *const *host_W,
+                              float *const *host_b, float *const *host_vW, float *const *host_vb, float *dfeats, float *loss,
+                              int32_t *pred, void *ws, size_t ws_bytes, void *stream)
+{
+    FcLayout lay;
+    int rc = fc_layout(desc, &lay);
+    if (rc) return rc;
+    if (!feats || !labels || !host_W || !host_b || !host_vW || !host_vb || !dfeats || !loss || !ws) return STANZA_ENULL;
+    if (ws_bytes < lay.floats * 4) return STANZA_EWORKSPACE;
+    if (!aligned16(feats) || !aligned16(dfeats) || !aligned16(ws)) return STANZA_EALIGN;
+    const int L = desc->n_layers, n = desc->n_samples;
+    const int32_t *dims = desc->host_dims;
+    for (int l = 0; l < L; ++l) {
+        if (!host_W[l] || !host_b[l] || !host_vW[l] || !host_vb[l]) return STANZA_ENULL;
+        if (!aligned16(host_W[l]) || !aligned16(host_vW[l])) return STANZA_EALIGN;
+    }
+    hipStream_t st = (hipStream_t)stream;
+    float *base = (float *)ws;
+    auto act = [&](int l) -> const float * { return l == 0 ? feats : base + lay.act_off[l]; };
+
+    // forward
+    for (int l = 1; l <= L; ++l) {
+        GemmParams p{};
+        p.g = fc_geo(n, dims[l - 1], dims[l]);
+        p.a = act(l - 1);
+        p.b = host_W[l - 1];
+        p.bias = host_b[l - 1];
+        p.out = base + lay.act_off[l];
+        p.M = n; p.Nn = dims[l]; p.Kd = dims[l - 1];
+        p.flags = EPI_BIAS | (l < L ? EPI_RELU : 0u);
+        if ((rc = launch_igemm(MODE_FWD, p, 1, st))) return rc;
+    }
+    // loss and its gradient
+    float *dz = base + lay.dz_off[0], *dz_next = base + lay.dz_off[1];
+    float *row_loss = base + lay.row_loss_off;
+    hipLaunchKernelGGL(softmax_ce_kernel, dim3(cdiv(n, 4)), dim3(256), 0, st, n, dims[L], act(L), labels, dz, row_loss, pred);
+    if ((rc = launch_status())) return rc;
+    hipLaunchKernelGGL(mean_loss_kernel, dim3(1), dim3(256), 0, st, n, row_loss, loss);
+    if ((rc = launch_status())) return rc;
+    // backward + update, last layer first
+    const int dbb = colsum_blocks(n);
+    for (int l = L; l >= 1; --l) {
+        const int in = dims[l - 1], out = dims[l];
+        {   // gradient of the layer input, with the weights as they still are
+            GemmParams p{};
+            p.g = fc_geo(n, in, out);
+            p.a = dz;
+            p.b = host_W[l - 1];
+            p.out = (l == 1) ? dfeats : dz_next;
+            p.xmask = (l == 1) ? nullptr : act(l - 1);
+            p.M = n; p.Nn = in; p.Kd = out;
+            p.flags = p.xmask ? EPI_XMASK : 0u;
+            if ((rc = launch_igemm(MODE_BWD_DATA, p, 1, st))) return rc;
+        }
+        {   // weight gradient fused with the update
+            GemmParams p{};
+            p.g = fc_geo(n, in, out);
+            p.a = dz;
+            p.b = act(l - 1);
+            p.M = out; p.Nn = in; p.Kd = n;
+            p.chunks_per_split = cdiv(n, BK);
+            p.flags = EPI_SGD;
+            p.sgd_w = host_W[l - 1]; p.sgd_v = host_vW[l - 1];
+            p.lr = desc->lr; p.mom = desc->momentum; p.wd = desc->weight_decay;
+            if ((rc = launch_igemm(MODE_BWD_WEIGHT, p, 1, st))) return rc;
+        }
+        if ((rc = launch_colsum(dz, nullptr, n, out, base + lay.db_off, dbb, nullptr, host_b[l - 1], host_vb[l - 1], desc->lr,
+                                desc->momentum, desc->weight_decay, st)))
+            return rc;
+        float *tmp = dz; dz = dz_next; dz_next = tmp;
+    }
+    return STANZA_OK;
+}

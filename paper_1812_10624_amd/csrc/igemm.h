@@ -1,0 +1,459 @@
+// Implicit-GEMM engine for gfx950: one LDS-tiled, MFMA (v_mfma_f32_32x32x2_f32) main loop with
+// three operand-gather modes that cover the convolution forward pass and its two adjoints
+// (paper Sec. 3.2: CONV worker forward and backpropagation) and, with H = W = R = S = 1, the FC
+// worker's three GEMMs.
+//
+//   FWD         C[m=(n,p,q)][j=k]       = sum_{(r,s,c)} x[n,p*sh-ph+r,q*sw-pw+s,c] * w[k,r,s,c]
+//   BWD_DATA    C[m=(n,h,w)][j=c]       = sum_{(r,s,k)} dy[n,(h+ph-r)/sh,(w+pw-s)/sw,k] * w[k,r,s,c]
+//   BWD_WEIGHT  C[m=k][j=(r,s,c)]       = sum_{(n,p,q)} dy[n,p,q,k] * x[n,p*sh-ph+r,q*sw-pw+s,c]
+//
+// Both LDS tiles are stored reduction-major ([BK][BM+4], [BK][BN+4]) so that the MFMA operand
+// reads (lane -> row = lane%32, k = lane/32) are conflict-free 128-byte rows.  Operands whose
+// reduction index is contiguous in memory (x and w in FWD, dy in BWD_DATA) are fetched as 16-byte
+// vectors along the reduction and transposed on the way into LDS; operands whose GEMM row/column
+// index is contiguous (w in BWD_DATA, dy and x in BWD_WEIGHT) are fetched and stored as 16-byte
+// vectors directly.  Out-of-image taps, ragged tile edges and the reduction tail are predicated
+// loads that yield zero; nothing is padded in memory.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace stanza {
+
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+constexpr int BK = 16;         // reduction depth of one LDS stage
+constexpr int NTHREADS = 256;  // 4 wavefronts
+constexpr int LDS_PAD = 4;     // row stride = tile + 4 floats: transposed stores hit 2 lanes per bank at most
+
+enum { MODE_FWD = 0, MODE_BWD_DATA = 1, MODE_BWD_WEIGHT = 2 };
+
+enum : uint32_t {
+    EPI_BIAS = 1u,     // FWD: + bias[j]
+    EPI_RELU = 2u,     // FWD: max(.,0)
+    EPI_ACCUM = 4u,    // BWD_DATA: += previous contents
+    EPI_XMASK = 8u,    // BWD_DATA: * [xmask > 0]
+    EPI_SGD = 16u,     // BWD_WEIGHT: fused momentum-SGD update of sgd_w / sgd_v with the tile as gradient
+    LOAD_AMASK = 32u   // BWD_*: dy is gated by [amask > 0] as it is read
+};
+
+struct ConvGeo {
+    int N, H, W, C, K, R, S, sh, sw, ph, pw, Ho, Wo;
+};
+
+struct GemmParams {
+    ConvGeo g;
+    const float *a;       // FWD: x      BWD_DATA: dy   BWD_WEIGHT: dy
+    const float *amask;   // BWD_*: forward output y gating dy, or nullptr
+    const float *b;       // FWD: w      BWD_DATA: w    BWD_WEIGHT: x
+    float *out;           // FWD: y      BWD_DATA: dx   BWD_WEIGHT: dw or split partials [split][M*Nn]
+    const float *bias;    // FWD
+    const float *xmask;   // BWD_DATA
+    float *sgd_w, *sgd_v; // EPI_SGD
+    float lr, mom, wd;
+    int M, Nn, Kd;        // GEMM extents (Kd = full reduction length)
+    int tilesM, tilesN, tiles;
+    int chunks_per_split; // BWD_WEIGHT: reduction chunks (of BK) per blockIdx.y
+    uint32_t flags;
+};
+
+__device__ __forceinline__ float4 ldg4(const float *p) { return *reinterpret_cast<const float4 *>(p); }
+__device__ __forceinline__ float4 zero4() { return make_float4(0.f, 0.f, 0.f, 0.f); }
+__device__ __forceinline__ float &f4at(float4 &v, int e) { return reinterpret_cast<float *>(&v)[e]; }
+__device__ __forceinline__ float4 gate4(float4 v, float4 m)
+{
+    return make_float4(m.x > 0.f ? v.x : 0.f, m.y > 0.f ? v.y : 0.f, m.z > 0.f ? v.z : 0.f, m.w > 0.f ? v.w : 0.f);
+}
+
+// Exact quotient test for the strided adjoint: hp = p*stride with 0 <= p < limit.
+__device__ __forceinline__ bool strided_src(int hp, int stride, int limit, int &p)
+{
+    if (stride == 1) { p = hp; return (unsigned)hp < (unsigned)limit; }
+    if (hp < 0) { p = 0; return false; }
+    if (stride == 2) { p = hp >> 1; return !(hp & 1) && p < limit; }
+    p = hp / stride;
+    return (hp - p * stride == 0) && p < limit;
+}
+
+template <int MODE, int BM, int BN, int WM, int WN, bool VEC>
+__global__ __launch_bounds__(NTHREADS) void igemm_kernel(const GemmParams p)
+{
+    static_assert(WM * WN == 4, "four wavefronts per workgroup");
+    static_assert(BM % 64 == 0 && BN % 64 == 0, "loader granularity");
+    constexpr int WTM = BM / WM, WTN = BN / WN;          // wavefront tile
+    static_assert(WTM % 32 == 0 && WTN % 32 == 0, "MFMA granularity");
+    constexpr int TM = WTM / 32, TN = WTN / 32;
+    constexpr int AV = BM / 64, BV = BN / 64;            // 16-byte vectors per thread per stage
+    constexpr int LDA = BM + LDS_PAD, LDB = BN + LDS_PAD;
+
+    __shared__ __attribute__((aligned(16))) float As[2][BK][LDA];
+    __shared__ __attribute__((aligned(16))) float Bs[2][BK][LDB];
+
+    // Workgroup -> tile.  Consecutive workgroup ids land on different XCDs (round robin over 8), so give
+    // each XCD one contiguous run of tiles: neighbours in M share their input halo and the whole weight
+    // panel in that XCD's L2.
+    const int per_xcd = gridDim.x >> 3;
+    const int L = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+    if (L >= p.tiles) return;
+    const int tile_n = L % p.tilesN, tile_m = L / p.tilesN;
+    const int m0 = tile_m * BM, n0 = tile_n * BN;
+
+    const ConvGeo &g = p.g;
+    const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+    const int wave_m = wave / WN, wave_n = wave % WN;
+
+    int kbeg = 0, kend = p.Kd;
+    if (MODE == MODE_BWD_WEIGHT) {
+        kbeg = blockIdx.y * p.chunks_per_split * BK;
+        kend = min(p.Kd, kbeg + p.chunks_per_split * BK);
+    }
+    const int nchunks = (kend - kbeg + BK - 1) / BK;
+    const bool amask = (p.flags & LOAD_AMASK) != 0;
+
+    // ------------------------------------------------------------------ loader state
+    // "KC" loaders (reduction contiguous in memory): thread -> vector kq of 4 along the reduction, rows row0 + 64*i.
+    const int kq = t & 3, row0 = t >> 2;
+    // "MC" loaders (row/column index contiguous): thread -> vector c4 along the tile edge, reduction rows kr0 + RP*i.
+    constexpr int A_F4 = BM / 4, A_RP = NTHREADS / A_F4;
+    constexpr int B_F4 = BN / 4, B_RP = NTHREADS / B_F4;
+
+    // A operand state
+    int a_hb[AV], a_wb[AV];          // FWD: p*sh-ph, q*sw-pw      BWD_DATA: h+ph, w+pw
+    int a_base[AV];                  // element offset of the image (FWD: n*H*W*C, BWD_DATA: n*Ho*Wo*K)
+    int a_r = 0, a_s = 0, a_c = 0, a_kk = 0;   // KC reduction cursor (kk = linear index of this thread's vector)
+    // B operand state
+    int b_r[BV], b_s[BV], b_c[BV];   // BWD_DATA: (r,s,k) cursor per reduction row;  BWD_WEIGHT: pixel cursor (n,p,q)
+    int bw_r[4], bw_s[4], bw_c[4];   // BWD_WEIGHT: fixed (r,s,c) of this thread's 4 columns
+
+    if (MODE == MODE_FWD) {
+        const int HoWo = g.Ho * g.Wo;
+#pragma unroll
+        for (int i = 0; i < AV; ++i) {
+            const int m = m0 + row0 + 64 * i;
+            if (m < p.M) {
+                const int n = m / HoWo, pq = m - n * HoWo, pp = pq / g.Wo, q = pq - pp * g.Wo;
+                a_hb[i] = pp * g.sh - g.ph;
+                a_wb[i] = q * g.sw - g.pw;
+                a_base[i] = n * g.H * g.W * g.C;
+            } else {
+                a_hb[i] = -(1 << 28); a_wb[i] = 0; a_base[i] = 0;
+            }
+        }
+        a_kk = kq * 4;
+        a_c = a_kk % g.C;
+        const int rs = a_kk / g.C;
+        a_s = rs % g.S;
+        a_r = rs / g.S;
+    } else if (MODE == MODE_BWD_DATA) {
+        const int HW = g.H * g.W;
+#pragma unroll
+        for (int i = 0; i < AV; ++i) {
+            const int m = m0 + row0 + 64 * i;
+            if (m < p.M) {
+                const int n = m / HW, hw = m - n * HW, h = hw / g.W, w = hw - h * g.W;
+                a_hb[i] = h + g.ph;
+                a_wb[i] = w + g.pw;
+                a_base[i] = n * g.Ho * g.Wo * g.K;
+            } else {
+                a_hb[i] = -(1 << 28); a_wb[i] = 0; a_base[i] = 0;
+            }
+        }
+        a_kk = kq * 4;
+        a_c = a_kk % g.K;              // here "c" runs over the output channels k of dy
+        const int rs = a_kk / g.K;
+        a_s = rs % g.S;
+        a_r = rs / g.S;
+#pragma unroll
+        for (int i = 0; i < BV; ++i) {
+            const int kk = t / B_F4 + B_RP * i;
+            b_c[i] = kk % g.K;
+            const int rs2 = kk / g.K;
+            b_s[i] = rs2 % g.S;
+            b_r[i] = rs2 / g.S;
+        }
+    } else {
+        const int HoWo = g.Ho * g.Wo;
+#pragma unroll
+        for (int i = 0; i < BV; ++i) {
+            const int pix = kbeg + t / B_F4 + B_RP * i;
+            const int n = pix / HoWo, pq = pix - n * HoWo;
+            b_r[i] = n;                 // image
+            b_s[i] = pq / g.Wo;         // p
+            b_c[i] = pq - b_s[i] * g.Wo; // q
+        }
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const int j = n0 + (t % B_F4) * 4 + e;
+            bw_c[e] = j % g.C;
+            const int rs = j / g.C;
+            bw_s[e] = rs % g.S;
+            bw_r[e] = rs / g.S;         // >= R when j >= Nn: the column predicate below covers it
+        }
+    }
+
+    float4 ra[AV], rb[BV];
+
+    // Fetch stage `ch` (reduction offset kbeg + ch*BK) into registers.
+    auto fetch = [&](int ch) {
+        const int kchunk = kbeg + ch * BK;
+        // ---------------- A
+        if (MODE == MODE_FWD || MODE == MODE_BWD_DATA) {
+            const int CC = (MODE == MODE_FWD) ? g.C : g.K;
+            if (VEC) {
+                const bool kok = a_kk < p.Kd;
+#pragma unroll
+                for (int i = 0; i < AV; ++i) {
+                    int off;
+                    bool ok;
+                    if (MODE == MODE_FWD) {
+                        const int h = a_hb[i] + a_r, w = a_wb[i] + a_s;
+                        ok = kok && (unsigned)h < (unsigned)g.H && (unsigned)w < (unsigned)g.W;
+                        off = a_base[i] + (h * g.W + w) * g.C + a_c;
+                    } else {
+                        int pp, q;
+                        ok = strided_src(a_hb[i] - a_r, g.sh, g.Ho, pp);
+                        ok = strided_src(a_wb[i] - a_s, g.sw, g.Wo, q) && ok && kok;
+                        off = a_base[i] + (pp * g.Wo + q) * g.K + a_c;
+                    }
+                    float4 v = zero4();
+                    if (ok) {
+                        v = ldg4(p.a + off);
+                        if (MODE == MODE_BWD_DATA && amask) v = gate4(v, ldg4(p.amask + off));
+                    }
+                    ra[i] = v;
+                }
+                a_kk += BK;
+                a_c += BK;
+                while (a_c >= CC) {
+                    a_c -= CC;
+                    if (++a_s == g.S) { a_s = 0; ++a_r; }
+                }
+            } else {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const int kk = kchunk + kq * 4 + e;
+                    const int c = kk % CC, rs = kk / CC, s = rs % g.S, r = rs / g.S;
+                    const bool kok = kk < p.Kd;
+#pragma unroll
+                    for (int i = 0; i < AV; ++i) {
+                        int off;
+                        bool ok;
+                        if (MODE == MODE_FWD) {
+                            const int h = a_hb[i] + r, w = a_wb[i] + s;
+                            ok = kok && (unsigned)h < (unsigned)g.H && (unsigned)w < (unsigned)g.W;
+                            off = a_base[i] + (h * g.W + w) * g.C + c;
+                        } else {
+                            int pp, q;
+                            ok = strided_src(a_hb[i] - r, g.sh, g.Ho, pp);
+                            ok = strided_src(a_wb[i] - s, g.sw, g.Wo, q) && ok && kok;
+                            off = a_base[i] + (pp * g.Wo + q) * g.K + c;
+                        }
+                        float v = 0.f;
+                        if (ok) {
+                            v = p.a[off];
+                            if (MODE == MODE_BWD_DATA && amask) v = p.amask[off] > 0.f ? v : 0.f;
+                        }
+                        f4at(ra[i], e) = v;
+                    }
+                }
+            }
+        } else {  // BWD_WEIGHT A: dy viewed as [pixel][K], row m = output channel
+            const int col = m0 + (t % A_F4) * 4;
+#pragma unroll
+            for (int i = 0; i < AV; ++i) {
+                const int pix = kchunk + t / A_F4 + A_RP * i;
+                float4 v = zero4();
+                if (pix < kend) {
+                    const int off = pix * g.K + col;
+                    if (VEC) {
+                        if (col < p.M) {
+                            v = ldg4(p.a + off);
+                            if (amask) v = gate4(v, ldg4(p.amask + off));
+                        }
+                    } else {
+#pragma unroll
+                        for (int e = 0; e < 4; ++e)
+                            if (col + e < p.M) {
+                                float x = p.a[off + e];
+                                if (amask) x = p.amask[off + e] > 0.f ? x : 0.f;
+                                f4at(v, e) = x;
+                            }
+                    }
+                }
+                ra[i] = v;
+            }
+        }
+        // ---------------- B
+        if (MODE == MODE_FWD) {  // w as [Nn][Kd], reduction contiguous
+#pragma unroll
+            for (int i = 0; i < BV; ++i) {
+                const int j = n0 + row0 + 64 * i;
+                const int kk = kchunk + kq * 4;
+                float4 v = zero4();
+                if (j < p.Nn) {
+                    const int off = j * p.Kd + kk;
+                    if (VEC) {
+                        if (kk < p.Kd) v = ldg4(p.b + off);
+                    } else {
+#pragma unroll
+                        for (int e = 0; e < 4; ++e)
+                            if (kk + e < p.Kd) f4at(v, e) = p.b[off + e];
+                    }
+                }
+                rb[i] = v;
+            }
+        } else if (MODE == MODE_BWD_DATA) {  // w[k][r][s][c]: column j = c contiguous, row (r,s,k)
+            const int col = n0 + (t % B_F4) * 4;
+#pragma unroll
+            for (int i = 0; i < BV; ++i) {
+                float4 v = zero4();
+                if (b_r[i] < g.R) {
+                    const int off = ((b_c[i] * g.R + b_r[i]) * g.S + b_s[i]) * g.C + col;
+                    if (VEC) {
+                        if (col < p.Nn) v = ldg4(p.b + off);
+                    } else {
+#pragma unroll
+                        for (int e = 0; e < 4; ++e)
+                            if (col + e < p.Nn) f4at(v, e) = p.b[off + e];
+                    }
+                }
+                rb[i] = v;
+                b_c[i] += BK;
+                while (b_c[i] >= g.K) {
+                    b_c[i] -= g.K;
+                    if (++b_s[i] == g.S) { b_s[i] = 0; ++b_r[i]; }
+                }
+            }
+        } else {  // BWD_WEIGHT B: x gathered at (pixel row, column (r,s,c))
+            const int col = n0 + (t % B_F4) * 4;
+#pragma unroll
+            for (int i = 0; i < BV; ++i) {
+                const int pix = kchunk + t / B_F4 + B_RP * i;
+                float4 v = zero4();
+                if (pix < kend) {
+                    const int hb = b_s[i] * g.sh - g.ph, wb = b_c[i] * g.sw - g.pw;
+                    const int ib = b_r[i] * g.H;
+                    if (VEC) {
+                        const int h = hb + bw_r[0], w = wb + bw_s[0];
+                        if (col < p.Nn && (unsigned)h < (unsigned)g.H && (unsigned)w < (unsigned)g.W)
+                            v = ldg4(p.b + ((ib + h) * g.W + w) * g.C + bw_c[0]);
+                    } else {
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) {
+                            const int h = hb + bw_r[e], w = wb + bw_s[e];
+                            if (col + e < p.Nn && (unsigned)h < (unsigned)g.H && (unsigned)w < (unsigned)g.W)
+                                f4at(v, e) = p.b[((ib + h) * g.W + w) * g.C + bw_c[e]];
+                        }
+                    }
+                }
+                rb[i] = v;
+                b_c[i] += BK;                       // advance the pixel cursor by one stage
+                while (b_c[i] >= g.Wo) {
+                    b_c[i] -= g.Wo;
+                    if (++b_s[i] == g.Ho) { b_s[i] = 0; ++b_r[i]; }
+                }
+            }
+        }
+    };
+
+    auto stash = [&](int buf) {
+        if (MODE == MODE_BWD_WEIGHT) {
+#pragma unroll
+            for (int i = 0; i < AV; ++i)
+                *reinterpret_cast<float4 *>(&As[buf][t / A_F4 + A_RP * i][(t % A_F4) * 4]) = ra[i];
+        } else {
+#pragma unroll
+            for (int i = 0; i < AV; ++i)
+#pragma unroll
+                for (int e = 0; e < 4; ++e) As[buf][kq * 4 + e][row0 + 64 * i] = f4at(ra[i], e);
+        }
+        if (MODE == MODE_FWD) {
+#pragma unroll
+            for (int i = 0; i < BV; ++i)
+#pragma unroll
+                for (int e = 0; e < 4; ++e) Bs[buf][kq * 4 + e][row0 + 64 * i] = f4at(rb[i], e);
+        } else {
+#pragma unroll
+            for (int i = 0; i < BV; ++i)
+                *reinterpret_cast<float4 *>(&Bs[buf][t / B_F4 + B_RP * i][(t % B_F4) * 4]) = rb[i];
+        }
+    };
+
+    f32x16 acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+    if (nchunks > 0) {
+        fetch(0);
+        stash(0);
+    }
+    __syncthreads();
+
+    const int lrow = lane & 31, lk = lane >> 5;
+    for (int ch = 0; ch < nchunks; ++ch) {
+        const int buf = ch & 1;
+        const bool more = ch + 1 < nchunks;
+        if (more) fetch(ch + 1);
+#pragma unroll
+        for (int ks = 0; ks < BK / 2; ++ks) {
+            float av[TM], bv[TN];
+#pragma unroll
+            for (int i = 0; i < TM; ++i) av[i] = As[buf][ks * 2 + lk][wave_m * WTM + i * 32 + lrow];
+#pragma unroll
+            for (int j = 0; j < TN; ++j) bv[j] = Bs[buf][ks * 2 + lk][wave_n * WTN + j * 32 + lrow];
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[i], bv[j], acc[i][j], 0, 0, 0);
+        }
+        if (more) stash(buf ^ 1);
+        __syncthreads();
+    }
+
+    // ------------------------------------------------------------------ epilogue
+    // Accumulator register r of lane l holds row 8*(r/4) + 4*(l/32) + r%4, column l%32 of its 32x32 tile.
+    const size_t split_off = (MODE == MODE_BWD_WEIGHT && !(p.flags & EPI_SGD)) ? (size_t)blockIdx.y * p.M * p.Nn : 0;
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+        const int col = n0 + wave_n * WTN + j * 32 + lrow;
+        if (col >= p.Nn) continue;
+        float bias = 0.f;
+        if (MODE == MODE_FWD && (p.flags & EPI_BIAS)) bias = p.bias[col];
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int row = m0 + wave_m * WTM + i * 32 + 8 * (r >> 2) + 4 * lk + (r & 3);
+                if (row >= p.M) continue;
+                const size_t o = (size_t)row * p.Nn + col;
+                float v = acc[i][j][r];
+                if (MODE == MODE_FWD) {
+                    v += bias;
+                    if (p.flags & EPI_RELU) v = fmaxf(v, 0.f);
+                    p.out[o] = v;
+                } else if (MODE == MODE_BWD_DATA) {
+                    if (p.flags & EPI_ACCUM) v += p.out[o];
+                    if (p.flags & EPI_XMASK) v = p.xmask[o] > 0.f ? v : 0.f;
+                    p.out[o] = v;
+                } else {
+                    if (p.flags & EPI_SGD) {
+                        const float w = p.sgd_w[o];
+                        const float gg = v + p.wd * w;
+                        const float vel = p.mom * p.sgd_v[o] + gg;
+                        p.sgd_v[o] = vel;
+                        p.sgd_w[o] = w - p.lr * vel;
+                    } else {
+                        p.out[split_off + o] = v;
+                    }
+                }
+            }
+        }
+    }
+}
+
+}  // namespace stanza

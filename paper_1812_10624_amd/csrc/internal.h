@@ -1,0 +1,49 @@
+// Host-side helpers shared by the translation units of libstanza (not part of the ABI).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "../../include/stanza.h"
+#include "igemm.h"
+
+namespace stanza {
+
+inline int cdiv(int a, int b) { return (a + b - 1) / b; }
+inline int64_t cdiv64(int64_t a, int64_t b) { return (a + b - 1) / b; }
+inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+inline size_t round256(size_t b) { return (b + 255) & ~size_t(255); }
+
+inline int hip_status(hipError_t e) { return e == hipSuccess ? STANZA_OK : STANZA_EHIP; }
+inline int launch_status() { return hip_status(hipGetLastError()); }
+
+// Validates a conv descriptor and fills the kernel-side geometry.
+int conv_geometry(const stanza_conv_desc *d, ConvGeo *g);
+
+// How the filter-gradient reduction is cut into workgroups; the same plan sizes the workspace and drives
+// the launch, so the two can never disagree.
+struct WgradPlan {
+    int splits;            // reduction slices (blockIdx.y)
+    int chunks_per_split;  // BK-deep stages per slice
+    int db_blocks;         // row slabs of the bias-gradient column sum
+    size_t partial_floats; // splits * K * R*S*C when splits > 1, else 0
+    size_t db_floats;      // db_blocks * K
+    size_t bytes;
+};
+WgradPlan plan_wgrad(const ConvGeo &g, bool want_bias);
+
+// Launch the implicit GEMM in `mode` over p (M, Nn, Kd, pointers and flags already set); picks the tile
+// shape, fills the tile counts.  `splits` > 1 only for MODE_BWD_WEIGHT.
+int launch_igemm(int mode, GemmParams &p, int splits, hipStream_t st);
+
+// out[i] = sum_s partial[s*numel + i], s ascending.
+int launch_split_reduce(const float *partial, int splits, size_t numel, float *out, hipStream_t st);
+
+// Column sums of a [rows][cols] matrix (optionally gated by mask > 0) in two fixed-order passes.
+// scratch: blocks*cols floats.  With sgd_p != nullptr the sums are used as the gradient of a fused
+// momentum-SGD update of sgd_p / sgd_v instead of being written to out.
+int colsum_blocks(int rows);
+int launch_colsum(const float *a, const float *mask, int rows, int cols, float *scratch, int blocks, float *out,
+                  float *sgd_p, float *sgd_v, float lr, float mom, float wd, hipStream_t st);
+
+}  // namespace stanza

@@ -1,0 +1,496 @@
+// HBM-bound entry points: max-pool(+ReLU) forward/backward kept on the CONV worker (paper Sec. 3.2,
+// note on the split point), the residual join and global average pool of the residual-network-shaped
+// workload, bf16 casts, and the gradient aggregation + momentum-SGD update (Sec. 3.2 "exchange
+// [gradients] among all CONV workers ... and perform CONV layer parameter update"; Sec. 2.2 server-side
+// aggregation).  Every kernel moves each byte once with 16-byte accesses along the contiguous axis.
+#include "internal.h"
+
+namespace stanza {
+
+// ------------------------------------------------------------------ max-pool (+ReLU)
+struct PoolGeo {
+    int N, H, W, C, wh, ww, sh, sw, ph, pw, Ho, Wo, relu;
+};
+
+// One thread per output pixel and group of VW channels.
+template <int VW>
+__global__ __launch_bounds__(256) void pool_fwd_kernel(const PoolGeo g, const float *__restrict__ x, float *__restrict__ y,
+                                                       uint8_t *__restrict__ argmax, size_t total)
+{
+    const size_t id = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (id >= total) return;
+    const int CV = g.C / VW;
+    const int cv = (int)(id % CV);
+    size_t pix = id / CV;
+    const int q = (int)(pix % g.Wo);
+    pix /= g.Wo;
+    const int pp = (int)(pix % g.Ho);
+    const int n = (int)(pix / g.Ho);
+    float best[VW];
+    int bidx[VW];
+    bool found = false;
+    for (int i = 0; i < g.wh; ++i) {
+        const int h = pp * g.sh - g.ph + i;
+        if ((unsigned)h >= (unsigned)g.H) continue;
+        for (int j = 0; j < g.ww; ++j) {
+            const int w = q * g.sw - g.pw + j;
+            if ((unsigned)w >= (unsigned)g.W) continue;
+            const float *src = x + (((size_t)n * g.H + h) * g.W + w) * g.C + cv * VW;
+            float v[VW];
+            if constexpr (VW == 4) {
+                const float4 t = *reinterpret_cast<const float4 *>(src);
+                v[0] = t.x; v[1] = t.y; v[2] = t.z; v[3] = t.w;
+            } else {
+                v[0] = src[0];
+            }
+#pragma unroll
+            for (int e = 0; e < VW; ++e)
+                if (!found || v[e] > best[e]) { best[e] = v[e]; bidx[e] = i * g.ww + j; }
+            found = true;
+        }
+    }
+    const size_t o = id * VW;
+#pragma unroll
+    for (int e = 0; e < VW; ++e)
+        if (g.relu && best[e] < 0.f) best[e] = 0.f;
+    if constexpr (VW == 4) {
+        *reinterpret_cast<float4 *>(y + o) = make_float4(best[0], best[1], best[2], best[3]);
+        if (argmax)
+            *reinterpret_cast<uint32_t *>(argmax + o) =
+                (uint32_t)bidx[0] | ((uint32_t)bidx[1] << 8) | ((uint32_t)bidx[2] << 16) | ((uint32_t)bidx[3] << 24);
+    } else {
+        y[o] = best[0];
+        if (argmax) argmax[o] = (uint8_t)bidx[0];
+    }
+}
+
+// One thread per input pixel and group of VW channels: gather over the windows that cover it.
+template <int VW>
+__global__ __launch_bounds__(256) void pool_bwd_kernel(const PoolGeo g, const float *__restrict__ dy, const float *__restrict__ y,
+                                                       const uint8_t *__restrict__ argmax, float *__restrict__ dx, size_t total)
+{
+    const size_t id = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (id >= total) return;
+    const int CV = g.C / VW;
+    const int cv = (int)(id % CV);
+    size_t pix = id / CV;
+    const int w = (int)(pix % g.W);
+    pix /= g.W;
+    const int h = (int)(pix % g.H);
+    const int n = (int)(pix / g.H);
+    float acc[VW];
+#pragma unroll
+    for (int e = 0; e < VW; ++e) acc[e] = 0.f;
+    for (int i = 0; i < g.wh; ++i) {
+        const int hp = h + g.ph - i;
+        if (hp < 0) break;
+        const int pp = hp / g.sh;
+        if (pp * g.sh != hp || pp >= g.Ho) continue;
+        for (int j = 0; j < g.ww; ++j) {
+            const int wq = w + g.pw - j;
+            if (wq < 0) break;
+            const int q = wq / g.sw;
+            if (q * g.sw != wq || q >= g.Wo) continue;
+            const size_t o = (((size_t)n * g.Ho + pp) * g.Wo + q) * g.C + cv * VW;
+            const uint32_t code = (uint32_t)(i * g.ww + j);
+            if constexpr (VW == 4) {
+                const uint32_t am = *reinterpret_cast<const uint32_t *>(argmax + o);
+                const float4 d = *reinterpret_cast<const float4 *>(dy + o);
+                float4 yy = make_float4(1.f, 1.f, 1.f, 1.f);
+                if (g.relu) yy = *reinterpret_cast<const float4 *>(y + o);
+                if ((am & 255u) == code && yy.x > 0.f) acc[0] += d.x;
+                if (((am >> 8) & 255u) == code && yy.y > 0.f) acc[1] += d.y;
+                if (((am >> 16) & 255u) == code && yy.z > 0.f) acc[2] += d.z;
+                if ((am >> 24) == code && yy.w > 0.f) acc[3] += d.w;
+            } else {
+                if (argmax[o] == code && (!g.relu || y[o] > 0.f)) acc[0] += dy[o];
+            }
+        }
+    }
+    const size_t o = id * VW;
+    if constexpr (VW == 4)
+        *reinterpret_cast<float4 *>(dx + o) = make_float4(acc[0], acc[1], acc[2], acc[3]);
+    else
+        dx[o] = acc[0];
+}
+
+static int pool_geometry(const stanza_pool_desc *d, PoolGeo *g)
+{
+    if (d->N <= 0 || d->H <= 0 || d->W <= 0 || d->C <= 0 || d->win_h <= 0 || d->win_w <= 0) return STANZA_EINVAL;
+    if (d->stride_h <= 0 || d->stride_w <= 0 || d->pad_h < 0 || d->pad_w < 0) return STANZA_EINVAL;
+    if (d->pad_h >= d->win_h || d->pad_w >= d->win_w || d->win_h * d->win_w > 255) return STANZA_EINVAL;
+    if (d->H + 2 * d->pad_h < d->win_h || d->W + 2 * d->pad_w < d->win_w) return STANZA_EINVAL;
+    const int Ho = (d->H + 2 * d->pad_h - d->win_h) / d->stride_h + 1;
+    const int Wo = (d->W + 2 * d->pad_w - d->win_w) / d->stride_w + 1;
+    // every window must reach at least one pixel of the image (clipped windows are never empty)
+    if ((Ho - 1) * d->stride_h - d->pad_h >= d->H || (Wo - 1) * d->stride_w - d->pad_w >= d->W) return STANZA_EINVAL;
+    if ((int64_t)d->N * d->H * d->W * d->C >= (int64_t(1) << 31)) return STANZA_EINVAL;
+    *g = PoolGeo{d->N, d->H, d->W, d->C, d->win_h, d->win_w, d->stride_h, d->stride_w, d->pad_h, d->pad_w, Ho, Wo,
+                 (d->flags & STANZA_POOL_RELU) ? 1 : 0};
+    return STANZA_OK;
+}
+
+// ------------------------------------------------------------------ residual join, global average pool
+__global__ __launch_bounds__(256) void add_relu_fwd_kernel(size_t n4, size_t numel, const float *__restrict__ a, const float *__restrict__ b,
+                                                           float *__restrict__ o)
+{
+    const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n4) {
+        const float4 x = reinterpret_cast<const float4 *>(a)[i], y = reinterpret_cast<const float4 *>(b)[i];
+        reinterpret_cast<float4 *>(o)[i] =
+            make_float4(fmaxf(x.x + y.x, 0.f), fmaxf(x.y + y.y, 0.f), fmaxf(x.z + y.z, 0.f), fmaxf(x.w + y.w, 0.f));
+    } else if (i == n4) {
+        for (size_t j = n4 * 4; j < numel; ++j) o[j] = fmaxf(a[j] + b[j], 0.f);
+    }
+}
+
+__global__ __launch_bounds__(256) void add_relu_bwd_kernel(size_t n4, size_t numel, const float *__restrict__ dout,
+                                                           const float *__restrict__ o, float *__restrict__ dz)
+{
+    const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n4) {
+        const float4 d = reinterpret_cast<const float4 *>(dout)[i], y = reinterpret_cast<const float4 *>(o)[i];
+        reinterpret_cast<float4 *>(dz)[i] = gate4(d, y);
+    } else if (i == n4) {
+        for (size_t j = n4 * 4; j < numel; ++j) dz[j] = o[j] > 0.f ? dout[j] : 0.f;
+    }
+}
+
+__global__ void gap_fwd_kernel(int N, int HW, int C, const float *__restrict__ x, float *__restrict__ f)
+{
+    const int c = blockIdx.x * blockDim.x + threadIdx.x, n = blockIdx.y;
+    if (c >= C) return;
+    float s = 0.f;
+    for (int i = 0; i < HW; ++i) s += x[((size_t)n * HW + i) * C + c];
+    f[(size_t)n * C + c] = s / (float)HW;
+}
+
+__global__ void gap_bwd_kernel(size_t total, int HW, int C, const float *__restrict__ df, float *__restrict__ dx)
+{
+    const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= total) return;
+    const int c = (int)(i % C);
+    const size_t n = i / ((size_t)HW * C);
+    dx[i] = df[n * C + c] / (float)HW;
+}
+
+// ------------------------------------------------------------------ bf16 casts
+__device__ __forceinline__ uint16_t f32_to_bf16_rne(float f)
+{
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40u);  // NaN stays NaN
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+
+__global__ void cast_f32_bf16_kernel(size_t numel, const float *__restrict__ src, uint16_t *__restrict__ dst)
+{
+    const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < numel) dst[i] = f32_to_bf16_rne(src[i]);
+}
+
+__global__ void cast_bf16_f32_kernel(size_t numel, const uint16_t *__restrict__ src, float *__restrict__ dst)
+{
+    const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < numel) dst[i] = __uint_as_float((uint32_t)src[i] << 16);
+}
+
+// ------------------------------------------------------------------ aggregation + momentum SGD
+// Table in device memory (built by stanza_ps_plan):
+//   int64 chunk_prefix[n_tensors + 1]   exclusive prefix of per-tensor chunk counts (PS_CHUNK elements each)
+//   int64 numel[n_tensors]
+//   float* w[n_tensors], v[n_tensors]
+//   const float* grads[K * n_tensors]   shard-major
+typedef float v4f __attribute__((ext_vector_type(4)));
+constexpr int PS_CHUNK = 2048;  // elements per workgroup: 256 threads x 2 vectors of 4
+
+struct PsTable {
+    const int64_t *prefix;
+    const int64_t *numel;
+    float *const *w;
+    float *const *v;
+    const float *const *grads;
+};
+
+__host__ __device__ inline PsTable ps_table_at(const void *ws, int n_tensors)
+{
+    const char *b = (const char *)ws;
+    PsTable t;
+    t.prefix = (const int64_t *)b;
+    t.numel = t.prefix + (n_tensors + 1);
+    t.w = (float *const *)(t.numel + n_tensors);
+    t.v = t.w + n_tensors;
+    t.grads = (const float *const *)(t.v + n_tensors);
+    return t;
+}
+
+template <int KFIX>
+__global__ __launch_bounds__(256) void ps_aggregate_kernel(const void *ws, int n_tensors, int K, float scale, float lr, float mom, float wd)
+{
+    const PsTable tb = ps_table_at(ws, n_tensors);
+    const int64_t chunk = blockIdx.x;
+    // binary search: largest t with prefix[t] <= chunk
+    int lo = 0, hi = n_tensors;
+    while (hi - lo > 1) {
+        const int mid = (lo + hi) >> 1;
+        if (tb.prefix[mid] <= chunk) lo = mid; else hi = mid;
+    }
+    const int t = lo;
+    const int64_t numel = tb.numel[t];
+    const int64_t base = (chunk - tb.prefix[t]) * PS_CHUNK;
+    float *__restrict__ w = tb.w[t];
+    float *__restrict__ v = tb.v[t];
+    const float *const *gp = tb.grads + t;   // shard k at gp[k * n_tensors]
+    const int kk = KFIX > 0 ? KFIX : K;
+#pragma unroll
+    for (int it = 0; it < PS_CHUNK / 1024; ++it) {
+        const int64_t i = base + (int64_t)it * 1024 + threadIdx.x * 4;
+        if (i + 3 < numel) {
+            float4 s = zero4();
+#pragma unroll
+            for (int k = 0; k < kk; ++k) {
+                const v4f gk = __builtin_nontemporal_load(reinterpret_cast<const v4f *>(gp[(size_t)k * n_tensors] + i));
+                s.x += gk[0]; s.y += gk[1]; s.z += gk[2]; s.w += gk[3];
+            }
+            float4 wv = *reinterpret_cast<const float4 *>(w + i);
+            float4 vv = *reinterpret_cast<const float4 *>(v + i);
+            vv.x = mom * vv.x + (scale * s.x + wd * wv.x);
+            vv.y = mom * vv.y + (scale * s.y + wd * wv.y);
+            vv.z = mom * vv.z + (scale * s.z + wd * wv.z);
+            vv.w = mom * vv.w + (scale * s.w + wd * wv.w);
+            wv.x -= lr * vv.x; wv.y -= lr * vv.y; wv.z -= lr * vv.z; wv.w -= lr * vv.w;
+            *reinterpret_cast<float4 *>(v + i) = vv;
+            *reinterpret_cast<float4 *>(w + i) = wv;
+        } else {
+            for (int64_t j = i; j < numel && j < i + 4; ++j) {
+                float s = 0.f;
+                for (int k = 0; k < kk; ++k) s += gp[(size_t)k * n_tensors][j];
+                const float wj = w[j];
+                const float vel = mom * v[j] + (scale * s + wd * wj);
+                v[j] = vel;
+                w[j] = wj - lr * vel;
+            }
+        }
+    }
+}
+
+}  // namespace stanza
+
+using namespace stanza;
+
+extern "C" const char *stanza_strerror(int status)
+{
+    switch (status) {
+    case STANZA_OK: return "ok";
+    case STANZA_EINVAL: return "invalid size, stride, pad or count";
+    case STANZA_ENULL: return "required pointer is NULL";
+    case STANZA_EALIGN: return "pointer is not 16-byte aligned";
+    case STANZA_EUNSUPPORTED: return "unsupported dtype or shape";
+    case STANZA_EWORKSPACE: return "workspace too small";
+    case STANZA_EHIP: return "HIP runtime error at launch";
+    }
+    return "unknown status";
+}
+
+extern "C" int stanza_version(void) { return 100; }
+
+extern "C" int stanza_pool_relu_fwd(const stanza_pool_desc *desc, int32_t dtype, const void *x, void *y, uint8_t *argmax, void *stream)
+{
+    if (!desc) return STANZA_ENULL;
+    PoolGeo g;
+    int rc = pool_geometry(desc, &g);
+    if (rc) return rc;
+    if (dtype != STANZA_F32) return STANZA_EUNSUPPORTED;
+    if (!x || !y) return STANZA_ENULL;
+    if (!aligned16(x) || !aligned16(y) || (reinterpret_cast<uintptr_t>(argmax) & 3u)) return STANZA_EALIGN;
+    hipStream_t st = (hipStream_t)stream;
+    const size_t outs = (size_t)g.N * g.Ho * g.Wo * g.C;
+    if (g.C % 4 == 0) {
+        const size_t total = outs / 4;
+        hipLaunchKernelGGL(pool_fwd_kernel<4>, dim3((unsigned)cdiv64(total, 256)), dim3(256), 0, st, g, (const float *)x, (float *)y, argmax, total);
+    } else {
+        hipLaunchKernelGGL(pool_fwd_kernel<1>, dim3((unsigned)cdiv64(outs, 256)), dim3(256), 0, st, g, (const float *)x, (float *)y, argmax, outs);
+    }
+    return launch_status();
+}
+
+extern "C" int stanza_pool_relu_bwd(const stanza_pool_desc *desc, int32_t dtype, const void *dy, const void *y, const uint8_t *argmax,
+                                    void *dx, void *stream)
+{
+    if (!desc) return STANZA_ENULL;
+    PoolGeo g;
+    int rc = pool_geometry(desc, &g);
+    if (rc) return rc;
+    if (dtype != STANZA_F32) return STANZA_EUNSUPPORTED;
+    if (!dy || !argmax || !dx || (g.relu && !y)) return STANZA_ENULL;
+    if (!aligned16(dy) || !aligned16(dx) || !aligned16(y) || (reinterpret_cast<uintptr_t>(argmax) & 3u)) return STANZA_EALIGN;
+    hipStream_t st = (hipStream_t)stream;
+    const size_t ins = (size_t)g.N * g.H * g.W * g.C;
+    if (g.C % 4 == 0) {
+        const size_t total = ins / 4;
+        hipLaunchKernelGGL(pool_bwd_kernel<4>, dim3((unsigned)cdiv64(total, 256)), dim3(256), 0, st, g, (const float *)dy, (const float *)y, argmax,
+                           (float *)dx, total);
+    } else {
+        hipLaunchKernelGGL(pool_bwd_kernel<1>, dim3((unsigned)cdiv64(ins, 256)), dim3(256), 0, st, g, (const float *)dy, (const float *)y, argmax,
+                           (float *)dx, ins);
+    }
+    return launch_status();
+}
+
+static int ew_check(int64_t numel, int32_t dtype, const void *a, const void *b, const void *c)
+{
+    if (numel <= 0 || numel >= (int64_t(1) << 31)) return STANZA_EINVAL;
+    if (dtype != STANZA_F32) return STANZA_EUNSUPPORTED;
+    if (!a || !b || !c) return STANZA_ENULL;
+    if (!aligned16(a) || !aligned16(b) || !aligned16(c)) return STANZA_EALIGN;
+    return STANZA_OK;
+}
+
+extern "C" int stanza_add_relu_fwd(int64_t numel, int32_t dtype, const void *a, const void *b, void *o, void *stream)
+{
+    int rc = ew_check(numel, dtype, a, b, o);
+    if (rc) return rc;
+    const size_t n4 = (size_t)numel / 4;
+    hipLaunchKernelGGL(add_relu_fwd_kernel, dim3((unsigned)cdiv64(n4 + 1, 256)), dim3(256), 0, (hipStream_t)stream, n4, (size_t)numel,
+                       (const float *)a, (const float *)b, (float *)o);
+    return launch_status();
+}
+
+extern "C" int stanza_add_relu_bwd(int64_t numel, int32_t dtype, const void *dout, const void *o, void *dz, void *stream)
+{
+    int rc = ew_check(numel, dtype, dout, o, dz);
+    if (rc) return rc;
+    const size_t n4 = (size_t)numel / 4;
+    hipLaunchKernelGGL(add_relu_bwd_kernel, dim3((unsigned)cdiv64(n4 + 1, 256)), dim3(256), 0, (hipStream_t)stream, n4, (size_t)numel,
+                       (const float *)dout, (const float *)o, (float *)dz);
+    return launch_status();
+}
+
+extern "C" int stanza_gap_fwd(int32_t N, int32_t HW, int32_t C, int32_t dtype, const void *x, float *f, void *stream)
+{
+    if (N <= 0 || HW <= 0 || C <= 0 || (int64_t)N * HW * C >= (int64_t(1) << 31)) return STANZA_EINVAL;
+    if (dtype != STANZA_F32) return STANZA_EUNSUPPORTED;
+    if (!x || !f) return STANZA_ENULL;
+    hipLaunchKernelGGL(gap_fwd_kernel, dim3(cdiv(C, 256), N), dim3(256), 0, (hipStream_t)stream, N, HW, C, (const float *)x, f);
+    return launch_status();
+}
+
+extern "C" int stanza_gap_bwd(int32_t N, int32_t HW, int32_t C, int32_t dtype, const float *df, void *dx, void *stream)
+{
+    if (N <= 0 || HW <= 0 || C <= 0 || (int64_t)N * HW * C >= (int64_t(1) << 31)) return STANZA_EINVAL;
+    if (dtype != STANZA_F32) return STANZA_EUNSUPPORTED;
+    if (!df || !dx) return STANZA_ENULL;
+    const size_t total = (size_t)N * HW * C;
+    hipLaunchKernelGGL(gap_bwd_kernel, dim3((unsigned)cdiv64(total, 256)), dim3(256), 0, (hipStream_t)stream, total, HW, C, df, (float *)dx);
+    return launch_status();
+}
+
+extern "C" int stanza_cast_f32_to_bf16(int64_t numel, const float *src, void *dst, void *stream)
+{
+    if (numel <= 0) return STANZA_EINVAL;
+    if (!src || !dst) return STANZA_ENULL;
+    hipLaunchKernelGGL(cast_f32_bf16_kernel, dim3((unsigned)cdiv64(numel, 256)), dim3(256), 0, (hipStream_t)stream, (size_t)numel, src, (uint16_t *)dst);
+    return launch_status();
+}
+
+extern "C" int stanza_cast_bf16_to_f32(int64_t numel, const void *src, float *dst, void *stream)
+{
+    if (numel <= 0) return STANZA_EINVAL;
+    if (!src || !dst) return STANZA_ENULL;
+    hipLaunchKernelGGL(cast_bf16_f32_kernel, dim3((unsigned)cdiv64(numel, 256)), dim3(256), 0, (hipStream_t)stream, (size_t)numel, (const uint16_t *)src, dst);
+    return launch_status();
+}
+
+// ------------------------------------------------------------------ ps_aggregate host side
+extern "C" size_t stanza_ps_workspace_bytes(int32_t n_tensors, int32_t K)
+{
+    if (n_tensors <= 0 || K <= 0) return 0;
+    return round256(sizeof(int64_t) * (2 * (size_t)n_tensors + 1) + sizeof(void *) * ((size_t)n_tensors * (2 + (size_t)K)));
+}
+
+static int ps_total_chunks(int32_t n_tensors, const int64_t *host_numel, int64_t *total)
+{
+    int64_t acc = 0;
+    for (int t = 0; t < n_tensors; ++t) {
+        if (host_numel[t] <= 0) return STANZA_EINVAL;
+        acc += cdiv64(host_numel[t], PS_CHUNK);
+    }
+    if (acc >= (int64_t(1) << 31)) return STANZA_EINVAL;
+    *total = acc;
+    return STANZA_OK;
+}
+
+extern "C" int stanza_ps_plan(int32_t n_tensors, const int64_t *host_numel, float *const *host_w, float *const *host_v,
+                              const float *const *host_grads, int32_t K, void *ws, size_t ws_bytes, void *stream)
+{
+    if (n_tensors <= 0 || K <= 0 || n_tensors > (1 << 20) || K > 4096) return STANZA_EINVAL;
+    if (!host_numel || !host_w || !host_v || !host_grads || !ws) return STANZA_ENULL;
+    const size_t need = stanza_ps_workspace_bytes(n_tensors, K);
+    if (ws_bytes < need) return STANZA_EWORKSPACE;
+    if (!aligned16(ws)) return STANZA_EALIGN;
+    int64_t total;
+    int rc = ps_total_chunks(n_tensors, host_numel, &total);
+    if (rc) return rc;
+    for (int t = 0; t < n_tensors; ++t) {
+        if (!host_w[t] || !host_v[t]) return STANZA_ENULL;
+        if (!aligned16(host_w[t]) || !aligned16(host_v[t])) return STANZA_EALIGN;
+        for (int k = 0; k < K; ++k) {
+            const float *gp = host_grads[(size_t)k * n_tensors + t];
+            if (!gp) return STANZA_ENULL;
+            if (!aligned16(gp)) return STANZA_EALIGN;
+        }
+    }
+    // Assemble the table on the host in the device layout, then one copy.
+    char *stage = (char *)malloc(need);
+    if (!stage) return STANZA_EINVAL;
+    int64_t *prefix = (int64_t *)stage;
+    int64_t *numel = prefix + (n_tensors + 1);
+    void **w = (void **)(numel + n_tensors);
+    void **v = w + n_tensors;
+    const void **grads = (const void **)(v + n_tensors);
+    int64_t acc = 0;
+    for (int t = 0; t < n_tensors; ++t) {
+        prefix[t] = acc;
+        acc += cdiv64(host_numel[t], PS_CHUNK);
+        numel[t] = host_numel[t];
+        w[t] = host_w[t];
+        v[t] = host_v[t];
+    }
+    prefix[n_tensors] = acc;
+    for (size_t i = 0; i < (size_t)K * n_tensors; ++i) grads[i] = host_grads[i];
+    // Pageable source: the runtime has consumed `stage` when this returns, so it can be freed at once.
+    hipError_t e = hipMemcpyAsync(ws, stage, need, hipMemcpyHostToDevice, (hipStream_t)stream);
+    if (e == hipSuccess) e = hipStreamSynchronize((hipStream_t)stream);
+    free(stage);
+    return hip_status(e);
+}
+
+extern "C" int stanza_ps_aggregate_planned(int32_t n_tensors, const int64_t *host_numel, int32_t K, float scale, float lr, float momentum,
+                                           float weight_decay, const void *ws, size_t ws_bytes, void *stream)
+{
+    if (n_tensors <= 0 || K <= 0) return STANZA_EINVAL;
+    if (!host_numel || !ws) return STANZA_ENULL;
+    if (ws_bytes < stanza_ps_workspace_bytes(n_tensors, K)) return STANZA_EWORKSPACE;
+    int64_t total;
+    int rc = ps_total_chunks(n_tensors, host_numel, &total);
+    if (rc) return rc;
+    hipStream_t st = (hipStream_t)stream;
+    const dim3 grid((unsigned)total), block(256);
+    switch (K) {
+    case 2: hipLaunchKernelGGL(ps_aggregate_kernel<2>, grid, block, 0, st, ws, n_tensors, K, scale, lr, momentum, weight_decay); break;
+    case 4: hipLaunchKernelGGL(ps_aggregate_kernel<4>, grid, block, 0, st, ws, n_tensors, K, scale, lr, momentum, weight_decay); break;
+    case 8: hipLaunchKernelGGL(ps_aggregate_kernel<8>, grid, block, 0, st, ws, n_tensors, K, scale, lr, momentum, weight_decay); break;
+    case 16: hipLaunchKernelGGL(ps_aggregate_kernel<16>, grid, block, 0, st, ws, n_tensors, K, scale, lr, momentum, weight_decay); break;
+    default: hipLaunchKernelGGL(ps_aggregate_kernel<0>, grid, block, 0, st, ws, n_tensors, K, scale, lr, momentum, weight_decay); break;
+    }
+    return launch_status();
+}
+
+extern "C" int stanza_ps_aggregate(int32_t n_tensors, const int64_t *host_numel, float *const *host_w, float *const *host_v,
+                                   const float *const *host_grads, int32_t K, float scale, float lr, float momentum, float weight_decay,
+                                   void *ws, size_t ws_bytes, void *stream)
+{
+    int rc = stanza_ps_plan(n_tensors, host_numel, host_w, host_v, host_grads, K, ws, ws_bytes, stream);
+    if (rc) return rc;
+    return stanza_ps_aggregate_planned(n_tensors, host_numel, K, scale, lr, momentum, weight_decay, ws, ws_bytes, stream);
+}

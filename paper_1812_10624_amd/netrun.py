@@ -1,0 +1,160 @@
+"""Sequencing of libstanza calls for one CONV worker, the FC worker and the gradient aggregation.
+
+This is the role the training loop plays in the paper (Sec. 3.2, Fig. 5): it owns device buffers
+(torch tensors) and issues the C-ABI calls in order.  It performs no arithmetic of its own.
+"""
+from __future__ import annotations
+
+from typing import Dict, List, Optional
+
+import torch
+
+from . import api
+
+
+class ConvWorker:
+    """One CONV worker: its conv stack forward up to the activations handed to the FC worker, and the
+    backward pass from the gradient of those activations to per-layer filter/bias gradients."""
+
+    def __init__(self, ops: List[dict], image_shape, batch: int, params: Dict[str, tuple], device="cuda:0"):
+        self.ops = ops
+        self.dev = torch.device(device)
+        self.params = params                      # name -> (W [K,R,S,C], b [K]) device tensors (shared between workers)
+        self.shapes = {"x0": (batch,) + tuple(image_shape)}
+        self.producer = {}
+        self.descs = {}
+        for i, op in enumerate(ops):
+            kind = op["op"]
+            if kind == "conv":
+                n, h, w, c = self.shapes[op["src"]]
+                flags = api.CONV_BIAS | (api.CONV_RELU if op["relu"] else 0)
+                d = api.conv_desc(n, h, w, c, op["K"], op["R"], op["S"], op["stride"], op["pad"], api.F32, flags)
+                ho, wo = api.conv_out_hw(d)
+                self.shapes[op["dst"]] = (n, ho, wo, op["K"])
+                self.descs[i] = d
+            elif kind == "pool":
+                n, h, w, c = self.shapes[op["src"]]
+                d = api.pool_desc(n, h, w, c, op["win"], op["stride"], op["pad"], op["relu"])
+                ho = (h + 2 * op["pad"] - op["win"]) // op["stride"] + 1
+                wo = (w + 2 * op["pad"] - op["win"]) // op["stride"] + 1
+                self.shapes[op["dst"]] = (n, ho, wo, c)
+                self.descs[i] = d
+            elif kind == "add_relu":
+                self.shapes[op["dst"]] = self.shapes[op["a"]]
+            elif kind == "gap":
+                n, h, w, c = self.shapes[op["src"]]
+                self.shapes[op["dst"]] = (n, 1, 1, c)
+            self.producer[op["dst"]] = op
+        f32 = dict(device=self.dev, dtype=torch.float32)
+        self.buf = {name: torch.empty(shape, **f32) for name, shape in self.shapes.items()}
+        self.argmax = {op["dst"]: torch.empty(self.shapes[op["dst"]], device=self.dev, dtype=torch.uint8)
+                       for op in ops if op["op"] == "pool"}
+        self.gbuf: Dict[str, torch.Tensor] = {}
+        self.grads = {name: (torch.empty_like(w), torch.empty_like(b)) for name, (w, b) in params.items()}
+        ws_bytes = max([api.stanza_conv_workspace_bytes(d, 2) for i, d in self.descs.items() if ops[i]["op"] == "conv"] + [16])
+        self.ws = torch.empty(ws_bytes, device=self.dev, dtype=torch.uint8)
+
+    # ------------------------------------------------------------------ forward
+    def forward(self, images: Optional[torch.Tensor] = None) -> torch.Tensor:
+        if images is not None:
+            self.buf["x0"].copy_(images)
+        for i, op in enumerate(self.ops):
+            kind = op["op"]
+            if kind == "conv":
+                w, b = self.params[op["name"]]
+                api.stanza_conv_fwd(self.descs[i], self.buf[op["src"]], w, b, self.buf[op["dst"]])
+            elif kind == "pool":
+                api.stanza_pool_relu_fwd(self.descs[i], self.buf[op["src"]], self.buf[op["dst"]], self.argmax[op["dst"]])
+            elif kind == "add_relu":
+                api.stanza_add_relu_fwd(self.buf[op["a"]], self.buf[op["b"]], self.buf[op["dst"]])
+            elif kind == "gap":
+                api.stanza_gap_fwd(self.buf[op["src"]], self.buf[op["dst"]])
+        return self.buf["feat"]
+
+    # ------------------------------------------------------------------ backward
+    def _grad_buffer(self, name, like=None):
+        if name not in self.gbuf:
+            self.gbuf[name] = torch.empty(self.shapes[like or name], device=self.dev, dtype=torch.float32)
+        return self.gbuf[name]
+
+    def backward(self, dfeat: torch.Tensor):
+        """dfeat: gradient of the activations handed to the FC worker, [B, A] or the buffer's own shape."""
+        have: Dict[str, torch.Tensor] = {"feat": dfeat.view(self.shapes["feat"])}
+        gated = {"feat": False}   # True when the stored gradient is already multiplied by [buffer > 0]
+        for i in reversed(range(len(self.ops))):
+            op = self.ops[i]
+            kind = op["op"]
+            if kind == "conv":
+                d = self.descs[i]
+                dy = have.pop(op["dst"])
+                # ReLU backward: already applied by whoever produced dy, or gate while loading
+                y = None if (gated.get(op["dst"], False) or not op["relu"]) else self.buf[op["dst"]]
+                w, _ = self.params[op["name"]]
+                dw, db = self.grads[op["name"]]
+                api.stanza_conv_bwd_weight(d, self.buf[op["src"]], dy, y, dw, db, self.ws)
+                src = op["src"]
+                if src != "x0":
+                    prod = self.producer[src]
+                    x_mask = self.buf[src] if (prod["op"] == "conv" and prod["relu"]) else None
+                    dd = api.ConvDesc.from_buffer_copy(d)
+                    if src in have:
+                        dd.flags |= api.CONV_ACCUM
+                        dx = have[src]
+                    else:
+                        dx = self._grad_buffer(src)
+                        have[src] = dx
+                    api.stanza_conv_bwd_data(dd, dy, y, w, x_mask, dx)
+                    gated[src] = x_mask is not None
+            elif kind == "pool":
+                dx = self._grad_buffer(op["src"])
+                assert op["src"] not in have
+                api.stanza_pool_relu_bwd(self.descs[i], have.pop(op["dst"]), self.buf[op["dst"]], self.argmax[op["dst"]], dx)
+                have[op["src"]] = dx
+                gated[op["src"]] = bool(op["relu"])   # [P>0] at the argmax equals [Y>0] there
+            elif kind == "add_relu":
+                dz = self._grad_buffer(op["dst"] + "#dz", like=op["dst"])
+                api.stanza_add_relu_bwd(have.pop(op["dst"]), self.buf[op["dst"]], dz)
+                # Both addends receive dz.  They share one tensor: in the reversed op order every reader of
+                # the main-branch gradient runs before the first accumulation into the shortcut's gradient.
+                for name in (op["a"], op["b"]):
+                    assert name not in have
+                    have[name] = dz
+                    gated[name] = False
+            elif kind == "gap":
+                dx = self._grad_buffer(op["src"])
+                api.stanza_gap_bwd(have.pop(op["dst"]).view(self.shapes[op["dst"]][0], -1), dx)
+                have[op["src"]] = dx
+                gated[op["src"]] = False
+        return self.grads
+
+
+class FcWorker:
+    """The FC worker: owns the FC parameters and momentum buffers and runs stanza_fc_step."""
+
+    def __init__(self, dims, n_samples, fc_params, fc_mom, lr, momentum, weight_decay, device="cuda:0"):
+        self.dev = torch.device(device)
+        self.plan = api.FcPlan(dims, n_samples, lr, momentum, weight_decay)
+        self.W = [w for w, _ in fc_params]
+        self.b = [b for _, b in fc_params]
+        self.vW = [w for w, _ in fc_mom]
+        self.vb = [b for _, b in fc_mom]
+        self.ws = torch.empty(self.plan.workspace_bytes(), device=self.dev, dtype=torch.uint8)
+        self.dfeats = torch.empty((n_samples, dims[0]), device=self.dev, dtype=torch.float32)
+        self.loss = torch.zeros(1, device=self.dev, dtype=torch.float32)
+        self.pred = torch.empty(n_samples, device=self.dev, dtype=torch.int32)
+
+    def step(self, feats: torch.Tensor, labels: torch.Tensor):
+        api.stanza_fc_step(self.plan, feats, labels, self.W, self.b, self.vW, self.vb, self.dfeats, self.loss, self.pred, self.ws)
+        return self.dfeats
+
+
+class Aggregator:
+    """Sum of K workers' gradient shards + momentum-SGD update over a list of parameter tensors."""
+
+    def __init__(self, w: List[torch.Tensor], v: List[torch.Tensor], grads: List[List[torch.Tensor]], device="cuda:0"):
+        self.w, self.v, self.grads = w, v, grads
+        self.ws = torch.empty(api.stanza_ps_workspace_bytes(len(w), len(grads)), device=device, dtype=torch.uint8)
+        self.plan = api.stanza_ps_plan(w, v, grads, self.ws)
+
+    def step(self, scale, lr, momentum, weight_decay):
+        api.stanza_ps_aggregate_planned(self.plan, scale, lr, momentum, weight_decay, self.ws)

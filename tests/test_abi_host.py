@@ -1,0 +1,105 @@
+"""Host-only checks of the C ABI: the library loads without a GPU, exports every symbol that
+include/stanza.h declares, and rejects bad arguments before touching the device."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def api():
+    from paper_1812_10624_amd import api as a
+    if not os.path.exists(a.LIB_PATH):
+        from paper_1812_10624_amd.build import build_library
+        build_library()
+    a.load()
+    return a
+
+
+def test_every_declared_symbol_is_exported(api):
+    header = open(os.path.join(ROOT, "include", "stanza.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b(stanza_[a-z0-9_]+)\s*\(", header))
+    assert declared, "no declarations found"
+    lib = api.load()
+    for name in sorted(declared):
+        assert hasattr(lib, name), f"{name} declared in stanza.h but not exported"
+    assert declared == set(api.EXPORTS)
+
+
+def test_status_strings_and_version(api):
+    lib = api.load()
+    assert lib.stanza_version() >= 100
+    assert lib.stanza_strerror(0) == b"ok"
+    for code in range(-6, 0):
+        assert lib.stanza_strerror(code) not in (b"ok", b"unknown status")
+    assert lib.stanza_strerror(-99) == b"unknown status"
+
+
+def test_conv_errors_before_launch(api):
+    lib = api.load()
+    good = api.conv_desc(2, 8, 8, 4, 8, 3, 3, 1, 1, api.F32, api.CONV_BIAS)
+    p16, p4 = C.c_void_p(0x1000), C.c_void_p(0x1004)
+    assert lib.stanza_conv_fwd(None, p16, p16, p16, p16, None, 0, None) == -2
+    assert lib.stanza_conv_fwd(C.byref(good), None, p16, p16, p16, None, 0, None) == -2
+    assert lib.stanza_conv_fwd(C.byref(good), p16, p16, None, p16, None, 0, None) == -2       # bias flagged, missing
+    assert lib.stanza_conv_fwd(C.byref(good), p4, p16, p16, p16, None, 0, None) == -3
+    for field, val in (("N", 0), ("C", -1), ("stride_h", 0), ("pad_h", 3), ("pad_w", -1), ("R", 11)):
+        d = api.conv_desc(2, 8, 8, 4, 8, 3, 3, 1, 1, api.F32, 0)
+        setattr(d, field, val)
+        assert lib.stanza_conv_fwd(C.byref(d), p16, p16, None, p16, None, 0, None) == -1, field
+    big = api.conv_desc(4096, 1024, 1024, 64, 8, 3, 3, 1, 1, api.F32, 0)                       # >= 2^31 elements
+    assert lib.stanza_conv_fwd(C.byref(big), p16, p16, None, p16, None, 0, None) == -1
+    bad_dtype = api.conv_desc(2, 8, 8, 4, 8, 3, 3, 1, 1, 7, 0)
+    assert lib.stanza_conv_fwd(C.byref(bad_dtype), p16, p16, None, p16, None, 0, None) == -4
+    assert lib.stanza_conv_bwd_data(C.byref(good), p16, None, p16, None, None, None, 0, None) == -2
+    assert lib.stanza_conv_bwd_data(C.byref(good), p16, None, p16, p4, p16, None, 0, None) == -3
+    # filter gradient: workspace is mandatory and sized by the query
+    need = lib.stanza_conv_workspace_bytes(C.byref(good), 2)
+    assert need > 0 and lib.stanza_conv_workspace_bytes(C.byref(good), 0) == 0
+    assert lib.stanza_conv_bwd_weight(C.byref(good), p16, p16, None, p16, p16, p16, need - 1, None) == -5
+    assert lib.stanza_conv_bwd_weight(C.byref(good), p16, p16, None, p16, None, p16, need, None) == -2   # dbias missing
+
+
+def test_pool_and_elementwise_errors(api):
+    lib = api.load()
+    p16 = C.c_void_p(0x1000)
+    d = api.pool_desc(1, 8, 8, 4, 2, 2, 0)
+    assert lib.stanza_pool_relu_fwd(C.byref(d), api.F32, None, p16, p16, None) == -2
+    assert lib.stanza_pool_relu_fwd(C.byref(d), 5, p16, p16, p16, None) == -4
+    d.pad_h = 2
+    assert lib.stanza_pool_relu_fwd(C.byref(d), api.F32, p16, p16, p16, None) == -1          # pad >= window
+    d = api.pool_desc(1, 8, 8, 4, 16, 16, 0)
+    assert lib.stanza_pool_relu_fwd(C.byref(d), api.F32, p16, p16, p16, None) == -1          # window code > 255 / larger than image
+    assert lib.stanza_add_relu_fwd(0, api.F32, p16, p16, p16, None) == -1
+    assert lib.stanza_add_relu_fwd(16, api.F32, p16, None, p16, None) == -2
+    assert lib.stanza_gap_fwd(1, 0, 4, api.F32, p16, p16, None) == -1
+
+
+def test_fc_and_ps_errors(api):
+    lib = api.load()
+    p16 = C.c_void_p(0x1000)
+    plan = api.FcPlan([64, 32, 10], 8, 0.01, 0.9, 0.0)
+    need = plan.workspace_bytes()
+    assert need > 0
+    arr = (C.c_void_p * 2)(0x1000, 0x2000)
+    assert lib.stanza_fc_step(C.byref(plan.desc), p16, p16, arr, arr, arr, arr, p16, p16, None, p16, need - 1, None) == -5
+    assert lib.stanza_fc_step(C.byref(plan.desc), None, p16, arr, arr, arr, arr, p16, p16, None, p16, need, None) == -2
+    nullarr = (C.c_void_p * 2)(0x1000, None)
+    assert lib.stanza_fc_step(C.byref(plan.desc), p16, p16, nullarr, arr, arr, arr, p16, p16, None, p16, need, None) == -2
+    bad = api.FcPlan([64, 0, 10], 8, 0.01, 0.9, 0.0)
+    assert bad.workspace_bytes() == 0
+    assert lib.stanza_ps_workspace_bytes(0, 4) == 0
+    need = lib.stanza_ps_workspace_bytes(2, 3)
+    numel = (C.c_int64 * 2)(100, 0)
+    w = (C.c_void_p * 2)(0x1000, 0x2000)
+    g = (C.c_void_p * 6)(*([0x3000] * 6))
+    assert lib.stanza_ps_plan(2, numel, w, w, g, 3, p16, need, None) == -1                     # empty tensor
+    numel = (C.c_int64 * 2)(100, 50)
+    assert lib.stanza_ps_plan(2, numel, w, w, g, 3, p16, need - 1, None) == -5
+    g_bad = (C.c_void_p * 6)(0x3000, 0x3000, 0x3004, 0x3000, 0x3000, 0x3000)
+    assert lib.stanza_ps_plan(2, numel, w, w, g_bad, 3, p16, need, None) == -3
+    assert lib.stanza_ps_aggregate_planned(2, numel, 3, 1.0, 0.1, 0.9, 0.0, None, need, None) == -2

@@ -1,0 +1,347 @@
+"""GPU parity: every entry point of libstanza against the CPU checker, element by element, on seeded
+inputs at sizes the checker finishes in seconds and that span several tiles plus ragged tails."""
+import copy
+
+import numpy as np
+import pytest
+import torch
+
+import workloads as wl_mod
+from gpu_util import TOL_F32, dev, host, rel_err
+from oracle import ConvGeom, PoolGeom
+from oracle import network as onet
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def api():
+    from paper_1812_10624_amd import api as a
+    a.load()
+    assert torch.cuda.is_available()
+    return a
+
+
+def rng(seed):
+    return np.random.default_rng(seed)
+
+
+# (N,H,W,C,K,R,S,stride,pad): vector and scalar loader paths, every tile shape, ragged M/N/K tails,
+# strides 2 and 4, filters 1/3/5/7/11, enough pixels for several reduction slices in the filter gradient
+CONV_CASES = [
+    (2, 19, 17, 8, 24, 3, 3, 1, 1),
+    (2, 16, 16, 3, 16, 3, 3, 1, 1),        # C = 3: scalar gather
+    (3, 13, 13, 16, 72, 3, 3, 1, 1),       # K not a multiple of the tile
+    (2, 14, 14, 64, 160, 3, 3, 1, 1),      # two 128-wide column tiles, ragged
+    (1, 56, 56, 64, 64, 3, 3, 1, 1),       # 64-wide output, many row tiles
+    (2, 28, 28, 20, 12, 1, 1, 1, 0),       # pointwise
+    (2, 15, 15, 24, 40, 1, 1, 2, 0),       # strided pointwise (projection shortcut)
+    (2, 29, 29, 16, 32, 3, 3, 2, 1),       # strided 3x3
+    (2, 35, 33, 3, 16, 7, 7, 2, 3),        # stem
+    (2, 27, 27, 12, 20, 5, 5, 1, 2),
+    (1, 67, 67, 3, 24, 11, 11, 4, 2),
+    (2, 9, 9, 6, 10, 3, 3, 1, 0),          # C, K not multiples of 4
+    (4, 1, 1, 300, 70, 1, 1, 1, 0),        # an FC layer as a convolution
+]
+
+
+def _ids(c):
+    return "n{}h{}w{}c{}k{}r{}s{}st{}p{}".format(*c)
+
+
+@pytest.mark.parametrize("case", CONV_CASES, ids=_ids)
+def test_conv_forward(api, o32, case):
+    N, H, W, C, K, R, S, st, pad = case
+    g = ConvGeom(N, H, W, C, K, R, S, st, pad)
+    r = rng(1)
+    x = r.standard_normal((N, H, W, C), dtype=np.float32)
+    w = (r.standard_normal((K, R, S, C), dtype=np.float32) / np.sqrt(R * S * C)).astype(np.float32)
+    b = r.standard_normal(K, dtype=np.float32)
+    for relu in (False, True):
+        ref = o32.conv_fwd(g, x, w, b, relu=relu)
+        d = api.conv_desc(N, H, W, C, K, R, S, st, pad, api.F32, api.CONV_BIAS | (api.CONV_RELU if relu else 0))
+        y = torch.full(ref.shape, float("nan"), device="cuda:0")
+        api.stanza_conv_fwd(d, dev(x), dev(w), dev(b), y)
+        e = rel_err(host(y), ref)
+        assert e < TOL_F32, (case, relu, e)
+    # no bias
+    d = api.conv_desc(N, H, W, C, K, R, S, st, pad, api.F32, 0)
+    y = torch.full(ref.shape, float("nan"), device="cuda:0")
+    api.stanza_conv_fwd(d, dev(x), dev(w), None, y)
+    assert rel_err(host(y), o32.conv_fwd(g, x, w, None)) < TOL_F32
+
+
+@pytest.mark.parametrize("case", CONV_CASES, ids=_ids)
+def test_conv_backward_data(api, o32, case):
+    N, H, W, C, K, R, S, st, pad = case
+    g = ConvGeom(N, H, W, C, K, R, S, st, pad)
+    r = rng(2)
+    w = (r.standard_normal((K, R, S, C), dtype=np.float32) / np.sqrt(R * S * K)).astype(np.float32)
+    dy = r.standard_normal((N, g.Ho, g.Wo, K), dtype=np.float32)
+    yfwd = r.standard_normal(dy.shape, dtype=np.float32)        # stands for the forward output (sign pattern)
+    xin = r.standard_normal((N, H, W, C), dtype=np.float32)     # stands for the layer input (sign pattern)
+    prev = r.standard_normal((N, H, W, C), dtype=np.float32)
+    ref_plain = o32.conv_bwd_data(g, dy, w)
+    d = api.conv_desc(N, H, W, C, K, R, S, st, pad, api.F32, api.CONV_BIAS)
+    dx = torch.full(ref_plain.shape, float("nan"), device="cuda:0")
+    api.stanza_conv_bwd_data(d, dev(dy), None, dev(w), None, dx)
+    assert rel_err(host(dx), ref_plain) < TOL_F32
+    # gated dy, accumulate onto prev, gate the result by the layer input's sign
+    ref = o32.conv_bwd_data(g, o32.relu_bwd(dy, yfwd), w)
+    ref = o32.relu_bwd((ref.astype(np.float64) + prev).astype(np.float32), xin)
+    d2 = api.conv_desc(N, H, W, C, K, R, S, st, pad, api.F32, api.CONV_RELU | api.CONV_ACCUM)
+    dx2 = dev(prev)
+    api.stanza_conv_bwd_data(d2, dev(dy), dev(yfwd), dev(w), dev(xin), dx2)
+    assert rel_err(host(dx2), ref) < TOL_F32
+    np.testing.assert_array_equal(host(dx2) == 0, ref == 0)
+
+
+@pytest.mark.parametrize("case", CONV_CASES, ids=_ids)
+def test_conv_backward_weight(api, o32, case):
+    N, H, W, C, K, R, S, st, pad = case
+    g = ConvGeom(N, H, W, C, K, R, S, st, pad)
+    r = rng(3)
+    x = r.standard_normal((N, H, W, C), dtype=np.float32)
+    dy = r.standard_normal((N, g.Ho, g.Wo, K), dtype=np.float32)
+    yfwd = r.standard_normal(dy.shape, dtype=np.float32)
+    for gate in (False, True):
+        dye = o32.relu_bwd(dy, yfwd) if gate else dy
+        ref_dw, ref_db = o32.conv_bwd_weight(g, x, dye)
+        d = api.conv_desc(N, H, W, C, K, R, S, st, pad, api.F32, api.CONV_BIAS | (api.CONV_RELU if gate else 0))
+        ws = torch.empty(max(16, api.stanza_conv_workspace_bytes(d, 2)), dtype=torch.uint8, device="cuda:0")
+        dw = torch.full(ref_dw.shape, float("nan"), device="cuda:0")
+        db = torch.full(ref_db.shape, float("nan"), device="cuda:0")
+        xd, dyd, yd = dev(x), dev(dy), dev(yfwd) if gate else None
+        api.stanza_conv_bwd_weight(d, xd, dyd, yd, dw, db, ws)
+        assert rel_err(host(dw), ref_dw) < TOL_F32, (case, gate)
+        assert rel_err(host(db), ref_db) < TOL_F32, (case, gate)
+        # run-to-run bit reproducibility (fixed-order reductions, no float atomics)
+        dw2, db2 = torch.empty_like(dw), torch.empty_like(db)
+        api.stanza_conv_bwd_weight(d, xd, dyd, yd, dw2, db2, ws)
+        assert torch.equal(dw, dw2) and torch.equal(db, db2)
+
+
+POOL_CASES = [(2, 16, 16, 8, 2, 2, 0, True), (2, 15, 13, 12, 3, 2, 0, True), (2, 14, 15, 16, 3, 2, 1, True),
+              (1, 9, 9, 3, 2, 2, 0, True), (1, 11, 11, 5, 3, 2, 1, False), (3, 8, 8, 4, 2, 2, 0, False),
+              (1, 12, 12, 4, 3, 1, 1, True)]
+
+
+@pytest.mark.parametrize("case", POOL_CASES, ids=lambda c: "n{}h{}w{}c{}win{}s{}p{}r{}".format(*c))
+def test_pool_relu(api, o32, case):
+    N, H, W, C, win, st, pad, relu = case
+    g = PoolGeom(N, H, W, C, win, st, pad, relu)
+    r = rng(4)
+    x = r.standard_normal((N, H, W, C), dtype=np.float32)
+    x[0, :4, :4, :] = 0.25                     # ties
+    x[0, 4:8, :, 0] = -np.abs(x[0, 4:8, :, 0]) - 1   # all-negative windows
+    y_ref, am_ref = o32.pool_relu_fwd(g, x)
+    d = api.pool_desc(N, H, W, C, win, st, pad, relu)
+    y = torch.full(y_ref.shape, float("nan"), device="cuda:0")
+    am = torch.full(y_ref.shape, 255, dtype=torch.uint8, device="cuda:0")
+    api.stanza_pool_relu_fwd(d, dev(x), y, am)
+    np.testing.assert_array_equal(host(y), y_ref)            # a max is exact
+    np.testing.assert_array_equal(host(am), am_ref)          # index work is bit-exact
+    dy = r.standard_normal(y_ref.shape, dtype=np.float32)
+    dx_ref = o32.pool_relu_bwd(g, dy, y_ref, am_ref)
+    dx = torch.full(x.shape, float("nan"), device="cuda:0")
+    api.stanza_pool_relu_bwd(d, dev(dy), dev(y_ref), dev(am_ref), dx)
+    assert rel_err(host(dx), dx_ref) < TOL_F32
+    np.testing.assert_array_equal(host(dx) == 0, dx_ref == 0)
+
+
+def test_add_relu_and_gap(api, o32):
+    r = rng(5)
+    for shape in ((2, 7, 7, 12), (1, 3, 3, 5), (3, 14, 14, 64)):
+        a, b = r.standard_normal(shape, dtype=np.float32), r.standard_normal(shape, dtype=np.float32)
+        o_ref = o32.add_relu_fwd(a, b)
+        o = torch.full(shape, float("nan"), device="cuda:0")
+        api.stanza_add_relu_fwd(dev(a), dev(b), o)
+        assert rel_err(host(o), o_ref) < 1e-6
+        dout = r.standard_normal(shape, dtype=np.float32)
+        dz = torch.full(shape, float("nan"), device="cuda:0")
+        api.stanza_add_relu_bwd(dev(dout), dev(o_ref), dz)
+        np.testing.assert_array_equal(host(dz), o32.relu_bwd(dout, o_ref))
+        f_ref = o32.gap_fwd(a)
+        f = torch.full((shape[0], shape[3]), float("nan"), device="cuda:0")
+        api.stanza_gap_fwd(dev(a), f)
+        assert rel_err(host(f), f_ref.reshape(shape[0], shape[3])) < 1e-5
+        df = r.standard_normal((shape[0], shape[3]), dtype=np.float32)
+        dx = torch.full(shape, float("nan"), device="cuda:0")
+        api.stanza_gap_bwd(dev(df), dx)
+        assert rel_err(host(dx), o32.gap_bwd(df, shape)) < 1e-6
+
+
+FC_CASES = [([2048, 256, 10], 8), ([520, 136, 50], 96), ([64, 1000], 130), ([300, 128, 64, 12], 33)]
+
+
+@pytest.mark.parametrize("dims,n", FC_CASES, ids=lambda v: str(v).replace(" ", ""))
+def test_fc_step(api, o32, dims, n):
+    from paper_1812_10624_amd.netrun import FcWorker
+    r = rng(6)
+    feats = np.maximum(r.standard_normal((n, dims[0]), dtype=np.float32), 0)
+    labels = r.integers(0, dims[-1], n).astype(np.int32)
+    params = [((r.standard_normal((dims[i + 1], dims[i]), dtype=np.float32) * np.sqrt(2.0 / dims[i])).astype(np.float32),
+               (r.standard_normal(dims[i + 1], dtype=np.float32) * 0.1).astype(np.float32)) for i in range(len(dims) - 1)]
+    mom = [((r.standard_normal(w.shape, dtype=np.float32) * 1e-2).astype(np.float32),
+            (r.standard_normal(b.shape, dtype=np.float32) * 1e-2).astype(np.float32)) for w, b in params]
+    lr, m, wd = 0.05, 0.9, 1e-3
+    p_ref, m_ref = copy.deepcopy(params), copy.deepcopy(mom)
+    ref = onet.fc_step(o32, feats, labels, p_ref, m_ref, lr, m, wd)
+    gp = [(dev(w), dev(b)) for w, b in params]
+    gm = [(dev(w), dev(b)) for w, b in mom]
+    fw = FcWorker(dims, n, gp, gm, lr, m, wd)
+    fw.step(dev(feats), dev(labels))
+    assert abs(float(host(fw.loss)[0]) - ref["loss"]) < 1e-5 * max(1.0, abs(ref["loss"]))
+    np.testing.assert_array_equal(host(fw.pred), ref["pred"])
+    assert rel_err(host(fw.dfeats), ref["dfeats"]) < TOL_F32
+    for li in range(len(params)):
+        for which in range(2):
+            got, want, before = host(gp[li][which]), p_ref[li][which], params[li][which]
+            # compare the update itself (new - old), which is what the step computes
+            assert rel_err(got - before, want - before) < 5e-4, (li, which)
+            assert rel_err(got, want) < 1e-5
+            assert rel_err(host(gm[li][which]), m_ref[li][which]) < TOL_F32, (li, which)
+
+
+@pytest.mark.parametrize("K", [1, 2, 3, 8, 16])
+def test_ps_aggregate(api, o32, K):
+    numels = [1000, 10, 4097, 2048 * 3 + 1, 2048, 64 * 3 * 3 * 64, 3]
+    ws_, vs_, gs_ = wl_mod.gen_ps_case(numels, K, seed=11)
+    w_ref, v_ref = copy.deepcopy(ws_), copy.deepcopy(vs_)
+    for t in range(len(numels)):
+        o32.ps_aggregate(w_ref[t], v_ref[t], gs_[t], 1.0, 0.01, 0.9, 5e-4)
+    gw, gv = [dev(a) for a in ws_], [dev(a) for a in vs_]
+    gg = [[dev(gs_[t][k]) for t in range(len(numels))] for k in range(K)]
+    ws = torch.empty(api.stanza_ps_workspace_bytes(len(numels), K), dtype=torch.uint8, device="cuda:0")
+    api.stanza_ps_aggregate(gw, gv, gg, 1.0, 0.01, 0.9, 5e-4, ws)
+    for t in range(len(numels)):
+        assert rel_err(host(gv[t]), v_ref[t]) < 1e-5, t
+        assert rel_err(host(gw[t]), w_ref[t]) < 1e-6, t
+    # second step through the planned entry point, other scale
+    plan = api.stanza_ps_plan(gw, gv, gg, ws)
+    api.stanza_ps_aggregate_planned(plan, 1.0 / K, 0.02, 0.5, 0.0, ws)
+    for t in range(len(numels)):
+        o32.ps_aggregate(w_ref[t], v_ref[t], gs_[t], 1.0 / K, 0.02, 0.5, 0.0)
+        assert rel_err(host(gv[t]), v_ref[t]) < 1e-5, t
+        assert rel_err(host(gw[t]), w_ref[t]) < 1e-6, t
+
+
+def _gpu_params(params):
+    return {n: (dev(w), dev(b)) for n, (w, b) in params.items()}
+
+
+@pytest.mark.parametrize("name", ["tiny", "minires"])
+def test_layerwise_and_split_step(api, o32, name):
+    """Gate 1: every op of the stack fed the checker's own inputs for that op, forward and backward.
+    Gate 2: the whole layer-separated step (K workers -> FC worker -> workers -> aggregation) and its
+    parameter updates."""
+    from paper_1812_10624_amd.netrun import Aggregator, ConvWorker, FcWorker
+    wl = wl_mod.get_workload(name)
+    K, B, seed = wl.K, wl.B, 0
+    imgs = [wl_mod.gen_images(wl, seed, k) for k in range(K)]
+    labels = wl_mod.gen_labels(wl, seed)
+    cp = wl_mod.gen_conv_params(wl, seed)
+    fp = wl_mod.gen_fc_params(wl, seed)
+    cm = {n: (np.zeros_like(w), np.zeros_like(b)) for n, (w, b) in cp.items()}
+    fm = [(np.zeros_like(w), np.zeros_like(b)) for w, b in fp]
+    cp_ref, cm_ref, fp_ref, fm_ref = (copy.deepcopy(a) for a in (cp, cm, fp, fm))
+    ref = onet.split_step(o32, wl.ops, imgs, labels, cp_ref, cm_ref, fp_ref, fm_ref, wl.lr, wl.momentum, wl.weight_decay, keep=True)
+
+    # ---- gate 1: layer-wise on worker 0, inputs taken from the checker
+    bufs, bgr = ref["bufs"][0], ref["buf_grads"][0]
+    gpar = _gpu_params(cp)
+    for op in wl.ops:
+        if op["op"] == "conv":
+            x = bufs[op["src"]]
+            n, h, w, c = x.shape
+            d = api.conv_desc(n, h, w, c, op["K"], op["R"], op["S"], op["stride"], op["pad"], api.F32,
+                              api.CONV_BIAS | (api.CONV_RELU if op["relu"] else 0))
+            y = torch.empty(bufs[op["dst"]].shape, device="cuda:0")
+            api.stanza_conv_fwd(d, dev(x), gpar[op["name"]][0], gpar[op["name"]][1], y)
+            assert rel_err(host(y), bufs[op["dst"]]) < TOL_F32, op
+        elif op["op"] == "pool":
+            x = bufs[op["src"]]
+            n, h, w, c = x.shape
+            d = api.pool_desc(n, h, w, c, op["win"], op["stride"], op["pad"], op["relu"])
+            y = torch.empty(bufs[op["dst"]].shape, device="cuda:0")
+            am = torch.empty(bufs[op["dst"]].shape, dtype=torch.uint8, device="cuda:0")
+            api.stanza_pool_relu_fwd(d, dev(x), y, am)
+            np.testing.assert_array_equal(host(y), bufs[op["dst"]])
+            np.testing.assert_array_equal(host(am), bufs[op["dst"] + "#argmax"])
+
+    # ---- gate 2: the whole step on the GPU
+    gfp = [(dev(w), dev(b)) for w, b in fp]
+    gfm = [(dev(w), dev(b)) for w, b in fm]
+    gcm = _gpu_params(cm)
+    workers = [ConvWorker(wl.ops, wl.image, B, gpar) for _ in range(K)]
+    fcw = FcWorker(wl.fc_dims, K * B, gfp, gfm, wl.lr, wl.momentum, wl.weight_decay)
+    feats = torch.empty((K * B, wl.fc_dims[0]), device="cuda:0")
+    for k, wk in enumerate(workers):
+        feats[k * B:(k + 1) * B].copy_(wk.forward(dev(imgs[k])).view(B, -1))
+    assert rel_err(host(feats), ref["feats"]) < TOL_F32
+    dfeats = fcw.step(feats, dev(labels))
+    assert abs(float(host(fcw.loss)[0]) - ref["loss"]) < 1e-5 * max(1.0, abs(ref["loss"]))
+    np.testing.assert_array_equal(host(fcw.pred), ref["pred"])
+    assert rel_err(host(dfeats), ref["dfeats"]) < TOL_F32
+    for k, wk in enumerate(workers):
+        wk.backward(dfeats[k * B:(k + 1) * B])
+        for nme in cp:
+            assert rel_err(host(wk.grads[nme][0]), ref["worker_grads"][k][nme][0]) < 5 * TOL_F32, (k, nme)
+            assert rel_err(host(wk.grads[nme][1]), ref["worker_grads"][k][nme][1]) < 5 * TOL_F32, (k, nme)
+    names = list(cp)
+    agg = Aggregator([gpar[n][i] for n in names for i in range(2)], [gcm[n][i] for n in names for i in range(2)],
+                     [[wk.grads[n][i] for n in names for i in range(2)] for wk in workers])
+    agg.step(1.0, wl.lr, wl.momentum, wl.weight_decay)
+    # the momentum buffer is the update divided by lr: compare it at gradient accuracy, the parameter itself tightly
+    for nme in names:
+        for i in range(2):
+            assert rel_err(host(gcm[nme][i]), cm_ref[nme][i]) < 5 * TOL_F32, (nme, i)
+            assert rel_err(host(gpar[nme][i]), cp_ref[nme][i]) < 1e-5, (nme, i)
+            assert not np.array_equal(host(gpar[nme][i]), cp[nme][i])
+    for li in range(len(fp)):
+        for i in range(2):
+            assert rel_err(host(gfm[li][i]), fm_ref[li][i]) < 5 * TOL_F32, (li, i)
+            assert rel_err(host(gfp[li][i]), fp_ref[li][i]) < 1e-5, (li, i)
+    # gate 1 for the backward ops: feed the checker's gradients of each buffer
+    gpar0 = _gpu_params(cp)
+    for op in wl.ops:
+        dyv = np.ascontiguousarray(bgr[op["dst"]]) if op["op"] in ("pool", "conv") else None
+        if op["op"] == "pool":
+            n, h, w, c = bufs[op["src"]].shape
+            d = api.pool_desc(n, h, w, c, op["win"], op["stride"], op["pad"], op["relu"])
+            dx = torch.empty((n, h, w, c), device="cuda:0")
+            api.stanza_pool_relu_bwd(d, dev(dyv), dev(bufs[op["dst"]]), dev(bufs[op["dst"] + "#argmax"]), dx)
+            assert rel_err(host(dx), o32.pool_relu_bwd(PoolGeom(n, h, w, c, op["win"], op["stride"], op["pad"], op["relu"]),
+                                                       dyv, bufs[op["dst"]], bufs[op["dst"] + "#argmax"])) < TOL_F32
+        elif op["op"] == "conv":
+            x = bufs[op["src"]]
+            n, h, w, c = x.shape
+            g = ConvGeom(n, h, w, c, op["K"], op["R"], op["S"], op["stride"], op["pad"])
+            d = api.conv_desc(n, h, w, c, op["K"], op["R"], op["S"], op["stride"], op["pad"], api.F32,
+                              api.CONV_BIAS | (api.CONV_RELU if op["relu"] else 0))
+            yd = dev(bufs[op["dst"]]) if op["relu"] else None
+            ws = torch.empty(max(16, api.stanza_conv_workspace_bytes(d, 2)), dtype=torch.uint8, device="cuda:0")
+            dw = torch.empty(cp[op["name"]][0].shape, device="cuda:0")
+            db = torch.empty(op["K"], device="cuda:0")
+            api.stanza_conv_bwd_weight(d, dev(x), dev(dyv), yd, dw, db, ws)
+            assert rel_err(host(dw), ref["worker_grads"][0][op["name"]][0]) < TOL_F32, op
+            assert rel_err(host(db), ref["worker_grads"][0][op["name"]][1]) < TOL_F32, op
+            if op["src"] != "x0":
+                dz = o32.relu_bwd(dyv, bufs[op["dst"]]) if op["relu"] else dyv
+                dx = torch.empty(x.shape, device="cuda:0")
+                api.stanza_conv_bwd_data(d, dev(dyv), yd, gpar0[op["name"]][0], None, dx)
+                assert rel_err(host(dx), o32.conv_bwd_data(g, dz, cp[op["name"]][0])) < TOL_F32, op
+
+
+def test_error_paths_on_device(api):
+    d = api.conv_desc(1, 8, 8, 4, 4, 3, 3, 1, 1, api.F32, api.CONV_BIAS)
+    x = torch.zeros(1, 8, 8, 4, device="cuda:0")
+    w = torch.zeros(4, 3, 3, 4, device="cuda:0")
+    y = torch.zeros(1, 8, 8, 4, device="cuda:0")
+    with pytest.raises(api.StanzaError):
+        api.stanza_conv_fwd(d, x, w, None, y)                       # bias flagged but missing
+    with pytest.raises(api.StanzaError):
+        api.stanza_conv_bwd_weight(d, x, y, None, w, torch.zeros(4, device="cuda:0"), torch.zeros(8, dtype=torch.uint8, device="cuda:0"))
+    d16 = api.conv_desc(1, 8, 8, 4, 4, 3, 3, 1, 1, api.BF16, 0)
+    with pytest.raises(api.StanzaError):
+        api.stanza_conv_fwd(d16, x, w, None, y)
