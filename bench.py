@@ -1,0 +1,217 @@
+#!/usr/bin/env python3
+"""Throughput of one GPU's share of a layer-separated training iteration (paper Sec. 3.2) on MI355X.
+
+A step is one pass of the whole hot path over one batch of synthetic input:
+  CONV worker forward (all conv + pool layers)  ->  FC worker step over the n = K*B rows of features
+  (this worker's B rows plus filler rows standing for the other K-1 workers)  ->  CONV worker backward
+  ->  aggregation of K gradient shards + momentum-SGD update of the conv parameters.
+Inputs are resident in HBM before the timed region.  Prints ONE JSON line.
+
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload vgg16|alexnet|resnet50|tiny]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0        # MI355X HBM3E
+MFMA_F32_PEAK_TFLOPS = 157.3  # MI355X dense fp32 matrix peak
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--workload", default="vgg16")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--detail", action="store_true", help="per-call timing table on stderr")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build measures one GPU's share of the iteration; run with --gpus 1 "
+              "(no collectives or multi-GPU paths exist here)", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    import workloads as W
+    from paper_1812_10624_amd import api
+    from paper_1812_10624_amd.netrun import Aggregator, ConvWorker, FcWorker
+
+    api.load()
+    assert torch.cuda.is_available(), "bench.py needs the GPU (there is no CPU path)"
+    dev = torch.device("cuda:0")
+    wl = W.get_workload(args.workload)
+    K, B, n = wl.K, wl.B, wl.n
+    seed = 0
+    to_dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(dev)
+
+    # ---- inputs, resident before timing
+    images = to_dev(W.gen_images(wl, seed, 0))
+    labels = to_dev(W.gen_labels(wl, seed))
+    cp = {nm: (to_dev(w), to_dev(b)) for nm, (w, b) in W.gen_conv_params(wl, seed).items()}
+    cm = {nm: (torch.zeros_like(w), torch.zeros_like(b)) for nm, (w, b) in cp.items()}
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(seed)
+    fp, fm = [], []
+    for o, i in W.fc_param_shapes(wl):   # drawn on the device: the FC set is up to 495 MB
+        fp.append((torch.randn((o, i), device=dev, generator=gen) * (2.0 / i) ** 0.5,
+                   (torch.rand(o, device=dev, generator=gen) * 2 - 1) / i ** 0.5))
+        fm.append((torch.zeros((o, i), device=dev), torch.zeros(o, device=dev)))
+    worker = ConvWorker(wl.ops, wl.image, B, cp)
+    fcw = FcWorker(wl.fc_dims, n, fp, fm, wl.lr, wl.momentum, wl.weight_decay)
+    feats = torch.randn((n, wl.fc_dims[0]), device=dev, generator=gen).clamp_(min=0)   # filler rows of the other workers
+    names = list(cp)
+    shard0 = [worker.grads[nm][i] for nm in names for i in range(2)]
+    shards = [shard0] + [[torch.randn(t.shape, device=dev, generator=gen) * 1e-3 for t in shard0] for _ in range(K - 1)]
+    agg = Aggregator([cp[nm][i] for nm in names for i in range(2)], [cm[nm][i] for nm in names for i in range(2)], shards)
+    worker.buf["x0"].copy_(images)
+
+    # ---- per-call instrumentation (HIP events on the stream the kernels are launched on)
+    records = []     # (tag, start_event, end_event)
+
+    def timed(tag, fn, *a):
+        s, e = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        s.record()
+        fn(*a)
+        e.record()
+        records.append((tag, s, e))
+
+    real = {k: getattr(api, k) for k in ("stanza_conv_fwd", "stanza_conv_bwd_data", "stanza_conv_bwd_weight",
+                                         "stanza_pool_relu_fwd", "stanza_pool_relu_bwd", "stanza_add_relu_fwd",
+                                         "stanza_add_relu_bwd", "stanza_gap_fwd", "stanza_gap_bwd")}
+    import paper_1812_10624_amd.netrun as netrun
+
+    class _Tap:
+        """Same call surface as the api module, with an event pair around every call."""
+        def __getattr__(self, k):
+            if k in real:
+                return lambda *a, **kw: timed(k, real[k], *a, **kw)
+            return getattr(api, k)
+    netrun.api = _Tap()
+
+    def step():
+        worker.forward()
+        feats[:B].copy_(worker.buf["feat"].view(B, -1))        # hand-off: this worker's rows of the FC input
+        timed("stanza_fc_step", fcw.step, feats, labels)
+        worker.backward(fcw.dfeats[:B])                         # hand-back: this worker's slice of the gradient
+        timed("stanza_ps_aggregate", agg.step, 1.0, wl.lr, wl.momentum, wl.weight_decay)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    records.clear()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+
+    per = {}
+    for tag, s, e in records:
+        per.setdefault(tag, []).append(s.elapsed_time(e))
+    tot = {k: sum(v) / args.steps for k, v in per.items()}      # ms per step per entry point
+    conv_ms = sum(tot.get(k, 0.0) for k in ("stanza_conv_fwd", "stanza_conv_bwd_data", "stanza_conv_bwd_weight"))
+    conv_worker_ms = sum(v for k, v in tot.items() if k not in ("stanza_fc_step", "stanza_ps_aggregate"))
+    fwd_f, bwd_f = W.conv_flops(wl)
+    conv_tflops = (fwd_f + bwd_f) / (conv_ms * 1e-3) / 1e12
+    conv_params, fc_params = W.count_params(wl)
+    ps_bytes = (K + 4) * 4 * conv_params
+    ps_gbs = ps_bytes / (tot["stanza_ps_aggregate"] * 1e-3) / 1e9
+
+    if args.detail:
+        nconv = sum(1 for op in wl.ops if op["op"] == "conv")
+        print(f"per entry point, ms/step: " + ", ".join(f"{k}={v:.3f}" for k, v in sorted(tot.items())), file=sys.stderr)
+        conv_ops = [op for op in wl.ops if op["op"] == "conv"]
+        shapes = W.shape_pass(wl)
+        for kind in ("stanza_conv_fwd", "stanza_conv_bwd_weight", "stanza_conv_bwd_data"):
+            v = per.get(kind, [])
+            calls = len(v) // args.steps
+            ops_k = conv_ops if kind == "stanza_conv_fwd" else list(reversed(conv_ops))
+            if kind == "stanza_conv_bwd_data":
+                ops_k = [op for op in ops_k if op["src"] != "x0"]
+            for ci in range(calls):
+                ms = sum(v[ci::calls]) / args.steps
+                op = ops_k[ci]
+                nn, ho, wo, kk = shapes[op["dst"]]
+                c = shapes[op["src"]][3]
+                fl = 2.0 * nn * ho * wo * kk * c * op["R"] * op["S"]
+                print(f"  {kind[7:]:16s} {op['name']:8s} {shapes[op['src']][1]:3d}x{shapes[op['src']][2]:<3d} C{c:<4d} K{kk:<4d} "
+                      f"R{op['R']} s{op['stride']}  {ms:8.3f} ms  {fl / ms / 1e9:7.1f} TFLOP/s", file=sys.stderr)
+
+    out = {
+        "metric": "conv_worker_train_images_per_sec_per_gpu",
+        "value": B / (ms_per_step * 1e-3),
+        "unit": "images/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"{wl.name}_shaped_conv_worker_B{B}_fc_worker_n{n}_K{K}_fp32",
+                   "per_worker_batch": B, "conv_workers_K": K, "fc_rows": n},
+        "conv_worker_images_per_s": B / (conv_worker_ms * 1e-3),
+        "conv_worker_ms": conv_worker_ms,
+        "fc_worker_samples_per_s": n / (tot["stanza_fc_step"] * 1e-3),
+        "fc_step_ms": tot["stanza_fc_step"],
+        "fc_tflops": W.fc_flops(wl) / (tot["stanza_fc_step"] * 1e-3) / 1e12,
+        "ps_aggregate_ms": tot["stanza_ps_aggregate"], "ps_aggregate_GBps": ps_gbs, "ps_aggregate_frac_hbm": ps_gbs / HBM_PEAK_GBS,
+        "roofline": {"bound": "mfma", "kernel": "stanza::igemm_kernel (conv fwd + bwd_data + bwd_weight launches)",
+                     "achieved": conv_tflops, "peak": MFMA_F32_PEAK_TFLOPS, "unit": "TFLOP/s",
+                     "frac": conv_tflops / MFMA_F32_PEAK_TFLOPS, "traffic": None,
+                     "algorithmic_gflop_per_step": (fwd_f + bwd_f) / 1e9, "kernel_ms_per_step": conv_ms},
+    }
+
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(wl, seed)
+    print(json.dumps(out))
+
+
+def cpu_baseline(wl, seed):
+    """The CPU checker as it stands, timed on a bounded sample of the same workload: the same step with
+    one image per CONV worker (conv stack forward + backward for 1 image, FC step over K rows,
+    aggregation of K shards over the full conv parameter set)."""
+    import copy
+
+    import numpy as np
+
+    import oracle
+    import workloads as W
+    from oracle import network as onet
+
+    o = oracle.lib("f32")
+    K = wl.K
+    b1 = 1
+    img = W.gen_images(wl, seed, 0, b1)
+    cp = W.gen_conv_params(wl, seed)
+    rng = np.random.default_rng(seed)
+    fp = [((rng.standard_normal((oo, ii), dtype=np.float32) * np.float32((2.0 / ii) ** 0.5)), np.zeros(oo, np.float32))
+          for oo, ii in W.fc_param_shapes(wl)]
+    fm = [(np.zeros_like(w), np.zeros_like(b)) for w, b in fp]
+    labels = W.gen_labels(wl, seed, K * b1)
+    t0 = time.perf_counter()
+    bufs = onet.conv_stack_forward(o, wl.ops, img, cp)
+    feats = np.concatenate([bufs["feat"].reshape(b1, -1)] + [np.maximum(rng.standard_normal((b1, wl.fc_dims[0]), dtype=np.float32), 0)
+                                                              for _ in range(K - 1)], 0)
+    fc = onet.fc_step(o, feats, labels, fp, fm, wl.lr, wl.momentum, wl.weight_decay)
+    pg, _ = onet.conv_stack_backward(o, wl.ops, bufs, cp, fc["dfeats"][:b1])
+    for nm, (w, b) in cp.items():
+        shards_w = [np.ascontiguousarray(pg[nm][0]).reshape(-1)] * K
+        o.ps_aggregate(w.reshape(-1), np.zeros(w.size, np.float32), shards_w, 1.0, wl.lr, wl.momentum, wl.weight_decay)
+        o.ps_aggregate(b, np.zeros_like(b), [pg[nm][1]] * K, 1.0, wl.lr, wl.momentum, wl.weight_decay)
+    dt = time.perf_counter() - t0
+    return {"value": b1 / dt, "unit": "images/s", "cores": o.threads(),
+            "kind": "oracle", "seconds": dt,
+            "sample": f"same step at 1 image per CONV worker: conv stack fwd+bwd on 1 image, FC step over {K} rows, "
+                      f"aggregation of {K} shards over the full conv parameter set"}
+
+
+if __name__ == "__main__":
+    main()

@@ -102,6 +102,9 @@ class Oracle:
                      "oracle_colsum_at", "oracle_fc_fwd_at", "oracle_softmax_ce"):
             getattr(self._l, name).restype = C.c_double
 
+    def threads(self) -> int:
+        return int(self._l.oracle_threads())
+
     # -- helpers
     def arr(self, a):
         return np.ascontiguousarray(a, dtype=self.dtype)

@@ -47,6 +47,17 @@ static inline int out_dim(int h, int win, int stride, int pad) { return (h + 2 *
 
 int oracle_real_bytes(void) { return (int)sizeof(REAL); }
 
+/* number of OpenMP threads the loops below will use */
+int oracle_threads(void)
+{
+#ifdef _OPENMP
+    extern int omp_get_max_threads(void);
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
+
 /* ---------------------------------------------------------------- convolution
  * Forward pass of a CONV layer (Sec. 3.1: each filter is slid over the input):
  *   Y[n,p,q,k] = b[k] + sum_{r,s,c} X[n, p*sh - ph + r, q*sw - pw + s, c] * Wt[k,r,s,c]
