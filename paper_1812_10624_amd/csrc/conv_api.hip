@@ -23,34 +23,37 @@ int conv_geometry(const stanza_conv_desc *d, ConvGeo *g)
 
 // ------------------------------------------------------------------ tile choice and launch
 template <int MODE, int BM, int BN, int WM, int WN>
-static int launch_tile(GemmParams &p, bool vec, int splits, hipStream_t st)
+static int launch_tile(GemmParams &p, bool veca, bool vecb, int splits, hipStream_t st)
 {
     p.tilesM = cdiv(p.M, BM);
     p.tilesN = cdiv(p.Nn, BN);
     p.tiles = p.tilesM * p.tilesN;
-    dim3 grid((unsigned)(cdiv(p.tiles, 8) * 8), (unsigned)splits);
-    if (vec)
-        hipLaunchKernelGGL((igemm_kernel<MODE, BM, BN, WM, WN, true>), grid, dim3(NTHREADS), 0, st, p);
+    p.splits = splits;
+    dim3 grid((unsigned)(cdiv(p.tiles * splits, 8) * 8));
+    if (veca && vecb)
+        hipLaunchKernelGGL((igemm_kernel<MODE, BM, BN, WM, WN, true, true>), grid, dim3(NTHREADS), 0, st, p);
+    else if (MODE == MODE_BWD_WEIGHT && veca)   // first layer: dy is vectorisable, the 3-channel image is not
+        hipLaunchKernelGGL((igemm_kernel<MODE, BM, BN, WM, WN, true, false>), grid, dim3(NTHREADS), 0, st, p);
     else
-        hipLaunchKernelGGL((igemm_kernel<MODE, BM, BN, WM, WN, false>), grid, dim3(NTHREADS), 0, st, p);
+        hipLaunchKernelGGL((igemm_kernel<MODE, BM, BN, WM, WN, false, false>), grid, dim3(NTHREADS), 0, st, p);
     return launch_status();
 }
 
 template <int MODE>
-static int launch_mode(GemmParams &p, bool vec, int splits, hipStream_t st)
+static int launch_mode(GemmParams &p, bool veca, bool vecb, int splits, hipStream_t st)
 {
     // Tall tiles while they still give every CU a couple of workgroups; 64-wide when the GEMM is narrow.
     const int want = 512;
     if (p.Nn <= 64) {
-        if (MODE != MODE_BWD_WEIGHT && (int64_t)cdiv(p.M, 256) * splits >= want) return launch_tile<MODE, 256, 64, 4, 1>(p, vec, splits, st);
-        if ((int64_t)cdiv(p.M, 128) * splits >= want) return launch_tile<MODE, 128, 64, 2, 2>(p, vec, splits, st);
-        return launch_tile<MODE, 64, 64, 2, 2>(p, vec, splits, st);
+        if (MODE != MODE_BWD_WEIGHT && (int64_t)cdiv(p.M, 256) * splits >= want) return launch_tile<MODE, 256, 64, 4, 1>(p, veca, vecb, splits, st);
+        if ((int64_t)cdiv(p.M, 128) * splits >= want) return launch_tile<MODE, 128, 64, 2, 2>(p, veca, vecb, splits, st);
+        return launch_tile<MODE, 64, 64, 2, 2>(p, veca, vecb, splits, st);
     }
     if (p.M <= 64 || (int64_t)cdiv(p.M, 128) * cdiv(p.Nn, 128) * splits < want) {
         if (p.M <= 64 || (int64_t)cdiv(p.M, 64) * cdiv(p.Nn, 128) * splits < want * 2)
-            return launch_tile<MODE, 64, 128, 2, 2>(p, vec, splits, st);
+            return launch_tile<MODE, 64, 128, 2, 2>(p, veca, vecb, splits, st);
     }
-    return launch_tile<MODE, 128, 128, 2, 2>(p, vec, splits, st);
+    return launch_tile<MODE, 128, 128, 2, 2>(p, veca, vecb, splits, st);
 }
 
 int launch_igemm(int mode, GemmParams &p, int splits, hipStream_t st)
@@ -58,26 +61,35 @@ int launch_igemm(int mode, GemmParams &p, int splits, hipStream_t st)
     const ConvGeo &g = p.g;
     if (p.M <= 0 || p.Nn <= 0 || p.Kd <= 0 || splits <= 0) return STANZA_EINVAL;
     switch (mode) {
-    case MODE_FWD: return launch_mode<MODE_FWD>(p, g.C % 4 == 0, 1, st);
-    case MODE_BWD_DATA: return launch_mode<MODE_BWD_DATA>(p, g.C % 4 == 0 && g.K % 4 == 0, 1, st);
-    case MODE_BWD_WEIGHT: return launch_mode<MODE_BWD_WEIGHT>(p, g.C % 4 == 0 && g.K % 4 == 0, splits, st);
+    case MODE_FWD: return launch_mode<MODE_FWD>(p, g.C % 4 == 0, g.C % 4 == 0, 1, st);
+    case MODE_BWD_DATA: return launch_mode<MODE_BWD_DATA>(p, g.K % 4 == 0, g.C % 4 == 0, 1, st);
+    case MODE_BWD_WEIGHT: return launch_mode<MODE_BWD_WEIGHT>(p, g.K % 4 == 0, g.C % 4 == 0, splits, st);
     }
     return STANZA_EINVAL;
 }
 
 // ------------------------------------------------------------------ fixed-order reductions
-__global__ void split_reduce_kernel(const float *__restrict__ partial, int splits, size_t numel, float *__restrict__ out)
+// Threads [0, numel) reduce the first segment, threads [numel, numel + numel2) the second (bias gradient).
+__global__ void split_reduce_kernel(const float *__restrict__ partial, int splits, size_t numel, float *__restrict__ out,
+                                    const float *__restrict__ partial2, size_t numel2, float *__restrict__ out2)
 {
-    const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i >= numel) return;
-    float s = 0.f;
-    for (int k = 0; k < splits; ++k) s += partial[(size_t)k * numel + i];
-    out[i] = s;
+    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < numel) {
+        float s = 0.f;
+        for (int k = 0; k < splits; ++k) s += partial[(size_t)k * numel + i];
+        out[i] = s;
+    } else if ((i -= numel) < numel2) {
+        float s = 0.f;
+        for (int k = 0; k < splits; ++k) s += partial2[(size_t)k * numel2 + i];
+        out2[i] = s;
+    }
 }
 
-int launch_split_reduce(const float *partial, int splits, size_t numel, float *out, hipStream_t st)
+int launch_split_reduce(const float *partial, int splits, size_t numel, float *out, const float *partial2, size_t numel2, float *out2,
+                        hipStream_t st)
 {
-    hipLaunchKernelGGL(split_reduce_kernel, dim3((unsigned)cdiv64(numel, 256)), dim3(256), 0, st, partial, splits, numel, out);
+    hipLaunchKernelGGL(split_reduce_kernel, dim3((unsigned)cdiv64(numel + numel2, 256)), dim3(256), 0, st, partial, splits, numel, out,
+                       partial2, numel2, out2);
     return launch_status();
 }
 
@@ -121,7 +133,7 @@ __global__ void colsum_pass2(const float *__restrict__ scratch, int blocks, int 
     }
 }
 
-int colsum_blocks(int rows) { return max(1, min(512, cdiv(rows, 64))); }
+int colsum_blocks(int rows) { return max(1, min(64, cdiv(rows, 64))); }
 
 int launch_colsum(const float *a, const float *mask, int rows, int cols, float *scratch, int blocks, float *out,
                   float *sgd_p, float *sgd_v, float lr, float mom, float wd, hipStream_t st)
@@ -147,8 +159,7 @@ WgradPlan plan_wgrad(const ConvGeo &g, bool want_bias)
     pl.chunks_per_split = cdiv(chunks, splits);
     pl.splits = cdiv(chunks, pl.chunks_per_split);
     pl.partial_floats = pl.splits > 1 ? (size_t)pl.splits * M * Nn : 0;
-    pl.db_blocks = want_bias ? colsum_blocks((int)red) : 0;
-    pl.db_floats = (size_t)pl.db_blocks * g.K;
+    pl.db_floats = (want_bias && pl.splits > 1) ? (size_t)pl.splits * g.K : 0;
     pl.bytes = round256(pl.partial_floats * 4) + round256(pl.db_floats * 4);
     return pl;
 }
@@ -239,15 +250,13 @@ extern "C" int stanza_conv_bwd_weight(const stanza_conv_desc *desc, const void *
     p.Nn = p.g.R * p.g.S * p.g.C;
     p.Kd = p.g.N * p.g.Ho * p.g.Wo;
     p.chunks_per_split = pl.chunks_per_split;
-    p.flags = p.amask ? LOAD_AMASK : 0u;
+    p.flags = (p.amask ? LOAD_AMASK : 0u) | (want_bias ? EPI_DBIAS : 0u);
     p.out = pl.splits > 1 ? partial : dw;
+    p.dbias = pl.splits > 1 ? dbscratch : dbias;
+    p.dbias_stride = p.g.K;
     rc = launch_igemm(MODE_BWD_WEIGHT, p, pl.splits, st);
     if (rc) return rc;
-    if (pl.splits > 1) {
-        rc = launch_split_reduce(partial, pl.splits, (size_t)p.M * p.Nn, dw, st);
-        if (rc) return rc;
-    }
-    if (want_bias)
-        rc = launch_colsum((const float *)dy, p.amask, p.Kd, p.g.K, dbscratch, pl.db_blocks, dbias, nullptr, nullptr, 0.f, 0.f, 0.f, st);
+    if (pl.splits > 1)
+        rc = launch_split_reduce(partial, pl.splits, (size_t)p.M * p.Nn, dw, dbscratch, want_bias ? (size_t)p.g.K : 0, dbias, st);
     return rc;
 }

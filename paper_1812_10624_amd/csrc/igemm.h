@@ -7,7 +7,7 @@
 //   BWD_DATA    C[m=(n,h,w)][j=c]       = sum_{(r,s,k)} dy[n,(h+ph-r)/sh,(w+pw-s)/sw,k] * w[k,r,s,c]
 //   BWD_WEIGHT  C[m=k][j=(r,s,c)]       = sum_{(n,p,q)} dy[n,p,q,k] * x[n,p*sh-ph+r,q*sw-pw+s,c]
 //
-// Both LDS tiles are stored reduction-major ([BK][BM+4], [BK][BN+4]) so that the MFMA operand
+// Both LDS tiles are stored reduction-major ([BK][BM+pad], [BK][BN+pad]) so that the MFMA operand
 // reads (lane -> row = lane%32, k = lane/32) are conflict-free 128-byte rows.  Operands whose
 // reduction index is contiguous in memory (x and w in FWD, dy in BWD_DATA) are fetched as 16-byte
 // vectors along the reduction and transposed on the way into LDS; operands whose GEMM row/column
@@ -24,7 +24,9 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 
 constexpr int BK = 16;         // reduction depth of one LDS stage
 constexpr int NTHREADS = 256;  // 4 wavefronts
-constexpr int LDS_PAD = 4;     // row stride = tile + 4 floats: transposed stores hit 2 lanes per bank at most
+constexpr int PAD_T = 2;  // row pad of a tile written transposed (4 scalar stores per fetched vector): a half-wave's
+                          // 4 reduction rows x 8 tile rows land on 32 distinct banks
+constexpr int PAD_V = 4;  // row pad of a tile written as 16-byte vectors (keeps rows 16-byte aligned)
 
 enum { MODE_FWD = 0, MODE_BWD_DATA = 1, MODE_BWD_WEIGHT = 2 };
 
@@ -34,7 +36,8 @@ enum : uint32_t {
     EPI_ACCUM = 4u,    // BWD_DATA: += previous contents
     EPI_XMASK = 8u,    // BWD_DATA: * [xmask > 0]
     EPI_SGD = 16u,     // BWD_WEIGHT: fused momentum-SGD update of sgd_w / sgd_v with the tile as gradient
-    LOAD_AMASK = 32u   // BWD_*: dy is gated by [amask > 0] as it is read
+    LOAD_AMASK = 32u,  // BWD_*: dy is gated by [amask > 0] as it is read
+    EPI_DBIAS = 64u    // BWD_WEIGHT: column-tile-0 workgroups also sum dy over their reduction slice (bias gradient)
 };
 
 struct ConvGeo {
@@ -49,11 +52,14 @@ struct GemmParams {
     float *out;           // FWD: y      BWD_DATA: dx   BWD_WEIGHT: dw or split partials [split][M*Nn]
     const float *bias;    // FWD
     const float *xmask;   // BWD_DATA
+    float *dbias;         // EPI_DBIAS: [M] or split partials (stride dbias_stride floats per slice)
+    size_t dbias_stride;
     float *sgd_w, *sgd_v; // EPI_SGD
     float lr, mom, wd;
     int M, Nn, Kd;        // GEMM extents (Kd = full reduction length)
     int tilesM, tilesN, tiles;
-    int chunks_per_split; // BWD_WEIGHT: reduction chunks (of BK) per blockIdx.y
+    int splits;           // reduction slices (1 except for BWD_WEIGHT)
+    int chunks_per_split; // BWD_WEIGHT: reduction chunks (of BK) per slice
     uint32_t flags;
 };
 
@@ -75,7 +81,7 @@ __device__ __forceinline__ bool strided_src(int hp, int stride, int limit, int &
     return (hp - p * stride == 0) && p < limit;
 }
 
-template <int MODE, int BM, int BN, int WM, int WN, bool VEC>
+template <int MODE, int BM, int BN, int WM, int WN, bool VECA, bool VECB>
 __global__ __launch_bounds__(NTHREADS) void igemm_kernel(const GemmParams p)
 {
     static_assert(WM * WN == 4, "four wavefronts per workgroup");
@@ -84,18 +90,20 @@ __global__ __launch_bounds__(NTHREADS) void igemm_kernel(const GemmParams p)
     static_assert(WTM % 32 == 0 && WTN % 32 == 0, "MFMA granularity");
     constexpr int TM = WTM / 32, TN = WTN / 32;
     constexpr int AV = BM / 64, BV = BN / 64;            // 16-byte vectors per thread per stage
-    constexpr int LDA = BM + LDS_PAD, LDB = BN + LDS_PAD;
+    constexpr int LDA = BM + (MODE == MODE_BWD_WEIGHT ? PAD_V : PAD_T), LDB = BN + (MODE == MODE_FWD ? PAD_T : PAD_V);
 
     __shared__ __attribute__((aligned(16))) float As[2][BK][LDA];
     __shared__ __attribute__((aligned(16))) float Bs[2][BK][LDB];
 
-    // Workgroup -> tile.  Consecutive workgroup ids land on different XCDs (round robin over 8), so give
-    // each XCD one contiguous run of tiles: neighbours in M share their input halo and the whole weight
-    // panel in that XCD's L2.
+    // Workgroup -> (reduction slice, tile).  Consecutive workgroup ids land on different XCDs (round robin over
+    // 8), so give each XCD one contiguous run of work items: neighbours in M share their input halo and the
+    // whole weight panel in that XCD's L2, and for BWD_WEIGHT all column tiles of one reduction slice (which
+    // read the same dy rows and the same pixels of x, shifted by a tap) run side by side on one XCD.
     const int per_xcd = gridDim.x >> 3;
     const int L = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
-    if (L >= p.tiles) return;
-    const int tile_n = L % p.tilesN, tile_m = L / p.tilesN;
+    if (L >= p.tiles * p.splits) return;
+    const int split = L / p.tiles, tile = L - split * p.tiles;
+    const int tile_n = tile % p.tilesN, tile_m = tile / p.tilesN;
     const int m0 = tile_m * BM, n0 = tile_n * BN;
 
     const ConvGeo &g = p.g;
@@ -104,7 +112,7 @@ __global__ __launch_bounds__(NTHREADS) void igemm_kernel(const GemmParams p)
 
     int kbeg = 0, kend = p.Kd;
     if (MODE == MODE_BWD_WEIGHT) {
-        kbeg = blockIdx.y * p.chunks_per_split * BK;
+        kbeg = split * p.chunks_per_split * BK;
         kend = min(p.Kd, kbeg + p.chunks_per_split * BK);
     }
     const int nchunks = (kend - kbeg + BK - 1) / BK;
@@ -192,6 +200,9 @@ __global__ __launch_bounds__(NTHREADS) void igemm_kernel(const GemmParams p)
     }
 
     float4 ra[AV], rb[BV];
+    // bias gradient: running sum of this thread's dy vectors (4 output channels, its reduction rows)
+    const bool want_db = MODE == MODE_BWD_WEIGHT && (p.flags & EPI_DBIAS) && tile_n == 0;
+    float4 dbacc = zero4();
 
     // Fetch stage `ch` (reduction offset kbeg + ch*BK) into registers.
     auto fetch = [&](int ch) {
@@ -199,7 +210,7 @@ __global__ __launch_bounds__(NTHREADS) void igemm_kernel(const GemmParams p)
         // ---------------- A
         if (MODE == MODE_FWD || MODE == MODE_BWD_DATA) {
             const int CC = (MODE == MODE_FWD) ? g.C : g.K;
-            if (VEC) {
+            if (VECA) {
                 const bool kok = a_kk < p.Kd;
 #pragma unroll
                 for (int i = 0; i < AV; ++i) {
@@ -265,7 +276,7 @@ __global__ __launch_bounds__(NTHREADS) void igemm_kernel(const GemmParams p)
                 float4 v = zero4();
                 if (pix < kend) {
                     const int off = pix * g.K + col;
-                    if (VEC) {
+                    if (VECA) {
                         if (col < p.M) {
                             v = ldg4(p.a + off);
                             if (amask) v = gate4(v, ldg4(p.amask + off));
@@ -281,6 +292,7 @@ __global__ __launch_bounds__(NTHREADS) void igemm_kernel(const GemmParams p)
                     }
                 }
                 ra[i] = v;
+                if (want_db) { dbacc.x += v.x; dbacc.y += v.y; dbacc.z += v.z; dbacc.w += v.w; }
             }
         }
         // ---------------- B
@@ -292,7 +304,7 @@ __global__ __launch_bounds__(NTHREADS) void igemm_kernel(const GemmParams p)
                 float4 v = zero4();
                 if (j < p.Nn) {
                     const int off = j * p.Kd + kk;
-                    if (VEC) {
+                    if (VECB) {
                         if (kk < p.Kd) v = ldg4(p.b + off);
                     } else {
 #pragma unroll
@@ -309,7 +321,7 @@ __global__ __launch_bounds__(NTHREADS) void igemm_kernel(const GemmParams p)
                 float4 v = zero4();
                 if (b_r[i] < g.R) {
                     const int off = ((b_c[i] * g.R + b_r[i]) * g.S + b_s[i]) * g.C + col;
-                    if (VEC) {
+                    if (VECB) {
                         if (col < p.Nn) v = ldg4(p.b + off);
                     } else {
 #pragma unroll
@@ -333,7 +345,7 @@ __global__ __launch_bounds__(NTHREADS) void igemm_kernel(const GemmParams p)
                 if (pix < kend) {
                     const int hb = b_s[i] * g.sh - g.ph, wb = b_c[i] * g.sw - g.pw;
                     const int ib = b_r[i] * g.H;
-                    if (VEC) {
+                    if (VECB) {
                         const int h = hb + bw_r[0], w = wb + bw_s[0];
                         if (col < p.Nn && (unsigned)h < (unsigned)g.H && (unsigned)w < (unsigned)g.W)
                             v = ldg4(p.b + ((ib + h) * g.W + w) * g.C + bw_c[0]);
@@ -398,26 +410,49 @@ __global__ __launch_bounds__(NTHREADS) void igemm_kernel(const GemmParams p)
         const int buf = ch & 1;
         const bool more = ch + 1 < nchunks;
         if (more) fetch(ch + 1);
+        // Operand registers are double-buffered so that the LDS reads of k-step ks+1 are in flight while the
+        // MFMAs of k-step ks issue.
+        float av[2][TM], bv[2][TN];
+#pragma unroll
+        for (int i = 0; i < TM; ++i) av[0][i] = As[buf][lk][wave_m * WTM + i * 32 + lrow];
+#pragma unroll
+        for (int j = 0; j < TN; ++j) bv[0][j] = Bs[buf][lk][wave_n * WTN + j * 32 + lrow];
 #pragma unroll
         for (int ks = 0; ks < BK / 2; ++ks) {
-            float av[TM], bv[TN];
+            const int cur = ks & 1, nxt = cur ^ 1;
+            if (ks + 1 < BK / 2) {
 #pragma unroll
-            for (int i = 0; i < TM; ++i) av[i] = As[buf][ks * 2 + lk][wave_m * WTM + i * 32 + lrow];
+                for (int i = 0; i < TM; ++i) av[nxt][i] = As[buf][(ks + 1) * 2 + lk][wave_m * WTM + i * 32 + lrow];
 #pragma unroll
-            for (int j = 0; j < TN; ++j) bv[j] = Bs[buf][ks * 2 + lk][wave_n * WTN + j * 32 + lrow];
+                for (int j = 0; j < TN; ++j) bv[nxt][j] = Bs[buf][(ks + 1) * 2 + lk][wave_n * WTN + j * 32 + lrow];
+            }
 #pragma unroll
             for (int i = 0; i < TM; ++i)
 #pragma unroll
                 for (int j = 0; j < TN; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[i], bv[j], acc[i][j], 0, 0, 0);
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[cur][i], bv[cur][j], acc[i][j], 0, 0, 0);
         }
         if (more) stash(buf ^ 1);
         __syncthreads();
     }
 
+    if (MODE == MODE_BWD_WEIGHT && want_db) {
+        // The A_RP threads t, t + A_F4, ... hold partial sums of the same 4 channels: add them in thread order
+        // through LDS (the last stage barrier has passed, the tiles are free).
+        float *red = &As[0][0][0];
+        *reinterpret_cast<float4 *>(&red[(t / A_F4) * LDA + (t % A_F4) * 4]) = dbacc;
+        __syncthreads();
+        if (t < BM && m0 + t < p.M) {
+            float s = 0.f;
+#pragma unroll
+            for (int r = 0; r < A_RP; ++r) s += red[r * LDA + t];
+            p.dbias[(size_t)split * p.dbias_stride + m0 + t] = s;
+        }
+    }
+
     // ------------------------------------------------------------------ epilogue
     // Accumulator register r of lane l holds row 8*(r/4) + 4*(l/32) + r%4, column l%32 of its 32x32 tile.
-    const size_t split_off = (MODE == MODE_BWD_WEIGHT && !(p.flags & EPI_SGD)) ? (size_t)blockIdx.y * p.M * p.Nn : 0;
+    const size_t split_off = (MODE == MODE_BWD_WEIGHT && !(p.flags & EPI_SGD)) ? (size_t)split * p.M * p.Nn : 0;
 #pragma unroll
     for (int j = 0; j < TN; ++j) {
         const int col = n0 + wave_n * WTN + j * 32 + lrow;

@@ -25,9 +25,8 @@ int conv_geometry(const stanza_conv_desc *d, ConvGeo *g);
 struct WgradPlan {
     int splits;            // reduction slices (blockIdx.y)
     int chunks_per_split;  // BK-deep stages per slice
-    int db_blocks;         // row slabs of the bias-gradient column sum
     size_t partial_floats; // splits * K * R*S*C when splits > 1, else 0
-    size_t db_floats;      // db_blocks * K
+    size_t db_floats;      // splits * K bias-gradient partials when splits > 1 and a bias gradient is wanted
     size_t bytes;
 };
 WgradPlan plan_wgrad(const ConvGeo &g, bool want_bias);
@@ -36,8 +35,9 @@ WgradPlan plan_wgrad(const ConvGeo &g, bool want_bias);
 // shape, fills the tile counts.  `splits` > 1 only for MODE_BWD_WEIGHT.
 int launch_igemm(int mode, GemmParams &p, int splits, hipStream_t st);
 
-// out[i] = sum_s partial[s*numel + i], s ascending.
-int launch_split_reduce(const float *partial, int splits, size_t numel, float *out, hipStream_t st);
+// out[i] = sum_s partial[s*numel + i], s ascending; likewise out2 from partial2 (numel2 may be 0).
+int launch_split_reduce(const float *partial, int splits, size_t numel, float *out, const float *partial2, size_t numel2, float *out2,
+                        hipStream_t st);
 
 // Column sums of a [rows][cols] matrix (optionally gated by mask > 0) in two fixed-order passes.
 // scratch: blocks*cols floats.  With sgd_p != nullptr the sums are used as the gradient of a fused

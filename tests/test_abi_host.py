@@ -58,10 +58,12 @@ def test_conv_errors_before_launch(api):
     assert lib.stanza_conv_bwd_data(C.byref(good), p16, None, p16, None, None, None, 0, None) == -2
     assert lib.stanza_conv_bwd_data(C.byref(good), p16, None, p16, p4, p16, None, 0, None) == -3
     # filter gradient: workspace is mandatory and sized by the query
-    need = lib.stanza_conv_workspace_bytes(C.byref(good), 2)
-    assert need > 0 and lib.stanza_conv_workspace_bytes(C.byref(good), 0) == 0
-    assert lib.stanza_conv_bwd_weight(C.byref(good), p16, p16, None, p16, p16, p16, need - 1, None) == -5
-    assert lib.stanza_conv_bwd_weight(C.byref(good), p16, p16, None, p16, None, p16, need, None) == -2   # dbias missing
+    long_red = api.conv_desc(8, 32, 32, 4, 8, 3, 3, 1, 1, api.F32, api.CONV_BIAS)       # 8192 pixels: the reduction is split
+    need = lib.stanza_conv_workspace_bytes(C.byref(long_red), 2)
+    assert need > 0 and lib.stanza_conv_workspace_bytes(C.byref(long_red), 0) == 0
+    assert lib.stanza_conv_bwd_weight(C.byref(long_red), p16, p16, None, p16, p16, p16, need - 1, None) == -5
+    assert lib.stanza_conv_bwd_weight(C.byref(long_red), p16, p16, None, p16, p16, None, need, None) == -2
+    assert lib.stanza_conv_bwd_weight(C.byref(long_red), p16, p16, None, p16, None, p16, need, None) == -2   # dbias missing
 
 
 def test_pool_and_elementwise_errors(api):

@@ -340,8 +340,10 @@ def test_error_paths_on_device(api):
     y = torch.zeros(1, 8, 8, 4, device="cuda:0")
     with pytest.raises(api.StanzaError):
         api.stanza_conv_fwd(d, x, w, None, y)                       # bias flagged but missing
+    dl = api.conv_desc(8, 32, 32, 4, 4, 3, 3, 1, 1, api.F32, api.CONV_BIAS)       # long reduction: needs a workspace
+    xl = torch.zeros(8, 32, 32, 4, device="cuda:0")
     with pytest.raises(api.StanzaError):
-        api.stanza_conv_bwd_weight(d, x, y, None, w, torch.zeros(4, device="cuda:0"), torch.zeros(8, dtype=torch.uint8, device="cuda:0"))
+        api.stanza_conv_bwd_weight(dl, xl, xl, None, w, torch.zeros(4, device="cuda:0"), torch.zeros(8, dtype=torch.uint8, device="cuda:0"))
     d16 = api.conv_desc(1, 8, 8, 4, 4, 3, 3, 1, 1, api.BF16, 0)
     with pytest.raises(api.StanzaError):
         api.stanza_conv_fwd(d16, x, w, None, y)
