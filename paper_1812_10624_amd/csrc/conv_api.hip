@@ -60,6 +60,11 @@ int launch_igemm(int mode, GemmParams &p, int splits, hipStream_t st)
 {
     const ConvGeo &g = p.g;
     if (p.M <= 0 || p.Nn <= 0 || p.Kd <= 0 || splits <= 0) return STANZA_EINVAL;
+    p.fd_c = make_fastdiv(g.C);
+    p.fd_k = make_fastdiv(g.K);
+    p.fd_s = make_fastdiv(g.S);
+    p.fd_howo = make_fastdiv(g.Ho * g.Wo);
+    p.fd_wo = make_fastdiv(g.Wo);
     switch (mode) {
     case MODE_FWD: return launch_mode<MODE_FWD>(p, g.C % 4 == 0, g.C % 4 == 0, 1, st);
     case MODE_BWD_DATA: return launch_mode<MODE_BWD_DATA>(p, g.K % 4 == 0, g.C % 4 == 0, 1, st);

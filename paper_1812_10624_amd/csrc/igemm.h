@@ -24,8 +24,9 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 
 constexpr int BK = 16;         // reduction depth of one LDS stage
 constexpr int NTHREADS = 256;  // 4 wavefronts
-constexpr int PAD_T = 2;  // row pad of a tile written transposed (4 scalar stores per fetched vector): a half-wave's
-                          // 4 reduction rows x 8 tile rows land on 32 distinct banks
+constexpr int KQ = BK / 4;     // 16-byte vectors along the reduction per tile row
+constexpr int PAD_T = 8 / KQ;  // row pad of a tile written transposed (4 scalar stores per fetched vector): a half-wave's
+                               // KQ reduction vectors x 32/KQ tile rows land on 32 distinct banks (stride = 4*pad mod 32)
 constexpr int PAD_V = 4;  // row pad of a tile written as 16-byte vectors (keeps rows 16-byte aligned)
 
 enum { MODE_FWD = 0, MODE_BWD_DATA = 1, MODE_BWD_WEIGHT = 2 };
@@ -44,8 +45,24 @@ struct ConvGeo {
     int N, H, W, C, K, R, S, sh, sw, ph, pw, Ho, Wo;
 };
 
+// Division of a non-negative 31-bit value by a launch-time constant: q = (n * mul) >> sh  (exact for n < 2^31).
+struct FastDiv {
+    uint32_t mul, sh;
+};
+__host__ inline FastDiv make_fastdiv(uint32_t d)
+{
+    uint32_t l = 0;
+    while ((1ull << l) < d) ++l;
+    FastDiv f;
+    f.mul = (uint32_t)(((1ull << (31 + l)) / d) + 1);
+    f.sh = 31 + l;
+    return f;
+}
+__device__ __forceinline__ int fdiv(int n, FastDiv f) { return (int)(((uint64_t)(uint32_t)n * f.mul) >> f.sh); }
+
 struct GemmParams {
     ConvGeo g;
+    FastDiv fd_c, fd_k, fd_s, fd_howo, fd_wo;   // divisors C, K, S, Ho*Wo, Wo
     const float *a;       // FWD: x      BWD_DATA: dy   BWD_WEIGHT: dy
     const float *amask;   // BWD_*: forward output y gating dy, or nullptr
     const float *b;       // FWD: w      BWD_DATA: w    BWD_WEIGHT: x
@@ -65,6 +82,12 @@ struct GemmParams {
 
 __device__ __forceinline__ float4 ldg4(const float *p) { return *reinterpret_cast<const float4 *>(p); }
 __device__ __forceinline__ float4 zero4() { return make_float4(0.f, 0.f, 0.f, 0.f); }
+// Branch-free predicated vector load: masked lanes read the (always valid) base address and get zero.
+__device__ __forceinline__ float4 ldg4_if(const float *base, int off, bool ok)
+{
+    const float4 v = ldg4(base + (ok ? off : 0));
+    return make_float4(ok ? v.x : 0.f, ok ? v.y : 0.f, ok ? v.z : 0.f, ok ? v.w : 0.f);
+}
 __device__ __forceinline__ float &f4at(float4 &v, int e) { return reinterpret_cast<float *>(&v)[e]; }
 __device__ __forceinline__ float4 gate4(float4 v, float4 m)
 {
@@ -89,7 +112,8 @@ __global__ __launch_bounds__(NTHREADS) void igemm_kernel(const GemmParams p)
     constexpr int WTM = BM / WM, WTN = BN / WN;          // wavefront tile
     static_assert(WTM % 32 == 0 && WTN % 32 == 0, "MFMA granularity");
     constexpr int TM = WTM / 32, TN = WTN / 32;
-    constexpr int AV = BM / 64, BV = BN / 64;            // 16-byte vectors per thread per stage
+    constexpr int RPP = NTHREADS / KQ;                   // tile rows covered by one pass of a reduction-contiguous fetch
+    constexpr int AV = BM * BK / 1024, BV = BN * BK / 1024;  // 16-byte vectors per thread per stage
     constexpr int LDA = BM + (MODE == MODE_BWD_WEIGHT ? PAD_V : PAD_T), LDB = BN + (MODE == MODE_FWD ? PAD_T : PAD_V);
 
     __shared__ __attribute__((aligned(16))) float As[2][BK][LDA];
@@ -120,7 +144,7 @@ __global__ __launch_bounds__(NTHREADS) void igemm_kernel(const GemmParams p)
 
     // ------------------------------------------------------------------ loader state
     // "KC" loaders (reduction contiguous in memory): thread -> vector kq of 4 along the reduction, rows row0 + 64*i.
-    const int kq = t & 3, row0 = t >> 2;
+    const int kq = t % KQ, row0 = t / KQ;
     // "MC" loaders (row/column index contiguous): thread -> vector c4 along the tile edge, reduction rows kr0 + RP*i.
     constexpr int A_F4 = BM / 4, A_RP = NTHREADS / A_F4;
     constexpr int B_F4 = BN / 4, B_RP = NTHREADS / B_F4;
@@ -128,16 +152,14 @@ __global__ __launch_bounds__(NTHREADS) void igemm_kernel(const GemmParams p)
     // A operand state
     int a_hb[AV], a_wb[AV];          // FWD: p*sh-ph, q*sw-pw      BWD_DATA: h+ph, w+pw
     int a_base[AV];                  // element offset of the image (FWD: n*H*W*C, BWD_DATA: n*Ho*Wo*K)
-    int a_r = 0, a_s = 0, a_c = 0, a_kk = 0;   // KC reduction cursor (kk = linear index of this thread's vector)
     // B operand state
-    int b_r[BV], b_s[BV], b_c[BV];   // BWD_DATA: (r,s,k) cursor per reduction row;  BWD_WEIGHT: pixel cursor (n,p,q)
     int bw_r[4], bw_s[4], bw_c[4];   // BWD_WEIGHT: fixed (r,s,c) of this thread's 4 columns
 
     if (MODE == MODE_FWD) {
         const int HoWo = g.Ho * g.Wo;
 #pragma unroll
         for (int i = 0; i < AV; ++i) {
-            const int m = m0 + row0 + 64 * i;
+            const int m = m0 + row0 + RPP * i;
             if (m < p.M) {
                 const int n = m / HoWo, pq = m - n * HoWo, pp = pq / g.Wo, q = pq - pp * g.Wo;
                 a_hb[i] = pp * g.sh - g.ph;
@@ -147,16 +169,11 @@ __global__ __launch_bounds__(NTHREADS) void igemm_kernel(const GemmParams p)
                 a_hb[i] = -(1 << 28); a_wb[i] = 0; a_base[i] = 0;
             }
         }
-        a_kk = kq * 4;
-        a_c = a_kk % g.C;
-        const int rs = a_kk / g.C;
-        a_s = rs % g.S;
-        a_r = rs / g.S;
     } else if (MODE == MODE_BWD_DATA) {
         const int HW = g.H * g.W;
 #pragma unroll
         for (int i = 0; i < AV; ++i) {
-            const int m = m0 + row0 + 64 * i;
+            const int m = m0 + row0 + RPP * i;
             if (m < p.M) {
                 const int n = m / HW, hw = m - n * HW, h = hw / g.W, w = hw - h * g.W;
                 a_hb[i] = h + g.ph;
@@ -166,29 +183,7 @@ __global__ __launch_bounds__(NTHREADS) void igemm_kernel(const GemmParams p)
                 a_hb[i] = -(1 << 28); a_wb[i] = 0; a_base[i] = 0;
             }
         }
-        a_kk = kq * 4;
-        a_c = a_kk % g.K;              // here "c" runs over the output channels k of dy
-        const int rs = a_kk / g.K;
-        a_s = rs % g.S;
-        a_r = rs / g.S;
-#pragma unroll
-        for (int i = 0; i < BV; ++i) {
-            const int kk = t / B_F4 + B_RP * i;
-            b_c[i] = kk % g.K;
-            const int rs2 = kk / g.K;
-            b_s[i] = rs2 % g.S;
-            b_r[i] = rs2 / g.S;
-        }
     } else {
-        const int HoWo = g.Ho * g.Wo;
-#pragma unroll
-        for (int i = 0; i < BV; ++i) {
-            const int pix = kbeg + t / B_F4 + B_RP * i;
-            const int n = pix / HoWo, pq = pix - n * HoWo;
-            b_r[i] = n;                 // image
-            b_s[i] = pq / g.Wo;         // p
-            b_c[i] = pq - b_s[i] * g.Wo; // q
-        }
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
             const int j = n0 + (t % B_F4) * 4 + e;
@@ -199,196 +194,191 @@ __global__ __launch_bounds__(NTHREADS) void igemm_kernel(const GemmParams p)
         }
     }
 
-    float4 ra[AV], rb[BV];
-    // bias gradient: running sum of this thread's dy vectors (4 output channels, its reduction rows)
+    // Stage registers: raw loaded vectors, their validity bits (applied when the stage is written to LDS, so
+    // that nothing waits on a global load before the MFMAs of the current stage), optional ReLU-gate vectors.
+    float4 ra[AV], rb[BV], rg[AV];
+    unsigned oka = 0, okb = 0;
     const bool want_db = MODE == MODE_BWD_WEIGHT && (p.flags & EPI_DBIAS) && tile_n == 0;
-    float4 dbacc = zero4();
+    float4 dbacc = zero4();   // bias gradient: running sum of this thread's dy vectors (4 channels, its reduction rows)
 
-    // Fetch stage `ch` (reduction offset kbeg + ch*BK) into registers.
-    auto fetch = [&](int ch) {
+    // Issue the global loads of A vector i of stage `ch` (reduction offset kbeg + ch*BK).  Stages past the end
+    // are fetched too: every lane is masked and reads the (valid) base address.
+    auto fetch_a = [&](int ch, int i) {
         const int kchunk = kbeg + ch * BK;
-        // ---------------- A
         if (MODE == MODE_FWD || MODE == MODE_BWD_DATA) {
             const int CC = (MODE == MODE_FWD) ? g.C : g.K;
             if (VECA) {
-                const bool kok = a_kk < p.Kd;
-#pragma unroll
-                for (int i = 0; i < AV; ++i) {
-                    int off;
-                    bool ok;
-                    if (MODE == MODE_FWD) {
-                        const int h = a_hb[i] + a_r, w = a_wb[i] + a_s;
-                        ok = kok && (unsigned)h < (unsigned)g.H && (unsigned)w < (unsigned)g.W;
-                        off = a_base[i] + (h * g.W + w) * g.C + a_c;
-                    } else {
-                        int pp, q;
-                        ok = strided_src(a_hb[i] - a_r, g.sh, g.Ho, pp);
-                        ok = strided_src(a_wb[i] - a_s, g.sw, g.Wo, q) && ok && kok;
-                        off = a_base[i] + (pp * g.Wo + q) * g.K + a_c;
-                    }
-                    float4 v = zero4();
-                    if (ok) {
-                        v = ldg4(p.a + off);
-                        if (MODE == MODE_BWD_DATA && amask) v = gate4(v, ldg4(p.amask + off));
-                    }
-                    ra[i] = v;
+                const int kk = kchunk + kq * 4;
+                const int rs = fdiv(kk, MODE == MODE_FWD ? p.fd_c : p.fd_k), cc = kk - rs * CC;
+                const int ar = fdiv(rs, p.fd_s), as = rs - ar * g.S;
+                int off;
+                bool ok;
+                if (MODE == MODE_FWD) {
+                    const int h = a_hb[i] + ar, w = a_wb[i] + as;
+                    ok = kk < p.Kd && (unsigned)h < (unsigned)g.H && (unsigned)w < (unsigned)g.W;
+                    off = a_base[i] + (h * g.W + w) * g.C + cc;
+                } else {
+                    int pp, q;
+                    ok = strided_src(a_hb[i] - ar, g.sh, g.Ho, pp);
+                    ok = strided_src(a_wb[i] - as, g.sw, g.Wo, q) && ok && kk < p.Kd;
+                    off = a_base[i] + (pp * g.Wo + q) * g.K + cc;
                 }
-                a_kk += BK;
-                a_c += BK;
-                while (a_c >= CC) {
-                    a_c -= CC;
-                    if (++a_s == g.S) { a_s = 0; ++a_r; }
-                }
+                off = ok ? off : 0;
+                ra[i] = ldg4(p.a + off);
+                if (MODE == MODE_BWD_DATA && amask) rg[i] = ldg4(p.amask + off);
+                oka |= (unsigned)ok << i;
             } else {
+                float4 v = zero4();
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
                     const int kk = kchunk + kq * 4 + e;
                     const int c = kk % CC, rs = kk / CC, s = rs % g.S, r = rs / g.S;
-                    const bool kok = kk < p.Kd;
-#pragma unroll
-                    for (int i = 0; i < AV; ++i) {
-                        int off;
-                        bool ok;
-                        if (MODE == MODE_FWD) {
-                            const int h = a_hb[i] + r, w = a_wb[i] + s;
-                            ok = kok && (unsigned)h < (unsigned)g.H && (unsigned)w < (unsigned)g.W;
-                            off = a_base[i] + (h * g.W + w) * g.C + c;
-                        } else {
-                            int pp, q;
-                            ok = strided_src(a_hb[i] - r, g.sh, g.Ho, pp);
-                            ok = strided_src(a_wb[i] - s, g.sw, g.Wo, q) && ok && kok;
-                            off = a_base[i] + (pp * g.Wo + q) * g.K + c;
-                        }
-                        float v = 0.f;
-                        if (ok) {
-                            v = p.a[off];
-                            if (MODE == MODE_BWD_DATA && amask) v = p.amask[off] > 0.f ? v : 0.f;
-                        }
-                        f4at(ra[i], e) = v;
-                    }
-                }
-            }
-        } else {  // BWD_WEIGHT A: dy viewed as [pixel][K], row m = output channel
-            const int col = m0 + (t % A_F4) * 4;
-#pragma unroll
-            for (int i = 0; i < AV; ++i) {
-                const int pix = kchunk + t / A_F4 + A_RP * i;
-                float4 v = zero4();
-                if (pix < kend) {
-                    const int off = pix * g.K + col;
-                    if (VECA) {
-                        if (col < p.M) {
-                            v = ldg4(p.a + off);
-                            if (amask) v = gate4(v, ldg4(p.amask + off));
-                        }
+                    int off;
+                    bool ok;
+                    if (MODE == MODE_FWD) {
+                        const int h = a_hb[i] + r, w = a_wb[i] + s;
+                        ok = kk < p.Kd && (unsigned)h < (unsigned)g.H && (unsigned)w < (unsigned)g.W;
+                        off = a_base[i] + (h * g.W + w) * g.C + c;
                     } else {
-#pragma unroll
-                        for (int e = 0; e < 4; ++e)
-                            if (col + e < p.M) {
-                                float x = p.a[off + e];
-                                if (amask) x = p.amask[off + e] > 0.f ? x : 0.f;
-                                f4at(v, e) = x;
-                            }
+                        int pp, q;
+                        ok = strided_src(a_hb[i] - r, g.sh, g.Ho, pp);
+                        ok = strided_src(a_wb[i] - s, g.sw, g.Wo, q) && ok && kk < p.Kd;
+                        off = a_base[i] + (pp * g.Wo + q) * g.K + c;
+                    }
+                    if (ok) {
+                        float x = p.a[off];
+                        if (MODE == MODE_BWD_DATA && amask) x = p.amask[off] > 0.f ? x : 0.f;
+                        f4at(v, e) = x;
                     }
                 }
                 ra[i] = v;
-                if (want_db) { dbacc.x += v.x; dbacc.y += v.y; dbacc.z += v.z; dbacc.w += v.w; }
+                rg[i] = make_float4(1.f, 1.f, 1.f, 1.f);
+                oka |= 1u << i;
             }
-        }
-        // ---------------- B
-        if (MODE == MODE_FWD) {  // w as [Nn][Kd], reduction contiguous
-#pragma unroll
-            for (int i = 0; i < BV; ++i) {
-                const int j = n0 + row0 + 64 * i;
-                const int kk = kchunk + kq * 4;
-                float4 v = zero4();
-                if (j < p.Nn) {
-                    const int off = j * p.Kd + kk;
-                    if (VECB) {
-                        if (kk < p.Kd) v = ldg4(p.b + off);
-                    } else {
-#pragma unroll
-                        for (int e = 0; e < 4; ++e)
-                            if (kk + e < p.Kd) f4at(v, e) = p.b[off + e];
-                    }
-                }
-                rb[i] = v;
-            }
-        } else if (MODE == MODE_BWD_DATA) {  // w[k][r][s][c]: column j = c contiguous, row (r,s,k)
-            const int col = n0 + (t % B_F4) * 4;
-#pragma unroll
-            for (int i = 0; i < BV; ++i) {
-                float4 v = zero4();
-                if (b_r[i] < g.R) {
-                    const int off = ((b_c[i] * g.R + b_r[i]) * g.S + b_s[i]) * g.C + col;
-                    if (VECB) {
-                        if (col < p.Nn) v = ldg4(p.b + off);
-                    } else {
-#pragma unroll
-                        for (int e = 0; e < 4; ++e)
-                            if (col + e < p.Nn) f4at(v, e) = p.b[off + e];
-                    }
-                }
-                rb[i] = v;
-                b_c[i] += BK;
-                while (b_c[i] >= g.K) {
-                    b_c[i] -= g.K;
-                    if (++b_s[i] == g.S) { b_s[i] = 0; ++b_r[i]; }
-                }
-            }
-        } else {  // BWD_WEIGHT B: x gathered at (pixel row, column (r,s,c))
-            const int col = n0 + (t % B_F4) * 4;
-#pragma unroll
-            for (int i = 0; i < BV; ++i) {
-                const int pix = kchunk + t / B_F4 + B_RP * i;
+        } else {  // BWD_WEIGHT A: dy viewed as [pixel][K], row m = output channel
+            const int col = m0 + (t % A_F4) * 4;
+            const int pix = kchunk + t / A_F4 + A_RP * i;
+            if (VECA) {
+                const bool ok = pix < kend && col < p.M;
+                const int off = ok ? pix * g.K + col : 0;
+                ra[i] = ldg4(p.a + off);
+                if (amask) rg[i] = ldg4(p.amask + off);
+                oka |= (unsigned)ok << i;
+            } else {
                 float4 v = zero4();
                 if (pix < kend) {
-                    const int hb = b_s[i] * g.sh - g.ph, wb = b_c[i] * g.sw - g.pw;
-                    const int ib = b_r[i] * g.H;
-                    if (VECB) {
-                        const int h = hb + bw_r[0], w = wb + bw_s[0];
-                        if (col < p.Nn && (unsigned)h < (unsigned)g.H && (unsigned)w < (unsigned)g.W)
-                            v = ldg4(p.b + ((ib + h) * g.W + w) * g.C + bw_c[0]);
-                    } else {
+                    const int off = pix * g.K + col;
 #pragma unroll
-                        for (int e = 0; e < 4; ++e) {
-                            const int h = hb + bw_r[e], w = wb + bw_s[e];
-                            if (col + e < p.Nn && (unsigned)h < (unsigned)g.H && (unsigned)w < (unsigned)g.W)
-                                f4at(v, e) = p.b[((ib + h) * g.W + w) * g.C + bw_c[e]];
+                    for (int e = 0; e < 4; ++e)
+                        if (col + e < p.M) {
+                            float x = p.a[off + e];
+                            if (amask) x = p.amask[off + e] > 0.f ? x : 0.f;
+                            f4at(v, e) = x;
                         }
-                    }
                 }
-                rb[i] = v;
-                b_c[i] += BK;                       // advance the pixel cursor by one stage
-                while (b_c[i] >= g.Wo) {
-                    b_c[i] -= g.Wo;
-                    if (++b_s[i] == g.Ho) { b_s[i] = 0; ++b_r[i]; }
-                }
+                ra[i] = v;
+                rg[i] = make_float4(1.f, 1.f, 1.f, 1.f);
+                oka |= 1u << i;
             }
         }
     };
 
+    auto fetch_b = [&](int ch, int i) {
+        const int kchunk = kbeg + ch * BK;
+        if (MODE == MODE_FWD) {  // w as [Nn][Kd], reduction contiguous
+            const int j = n0 + row0 + RPP * i;
+            const int kk = kchunk + kq * 4;
+            if (VECB) {
+                const bool ok = j < p.Nn && kk < p.Kd;
+                rb[i] = ldg4(p.b + (ok ? j * p.Kd + kk : 0));
+                okb |= (unsigned)ok << i;
+            } else {
+                float4 v = zero4();
+                if (j < p.Nn) {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e)
+                        if (kk + e < p.Kd) f4at(v, e) = p.b[j * p.Kd + kk + e];
+                }
+                rb[i] = v;
+                okb |= 1u << i;
+            }
+        } else if (MODE == MODE_BWD_DATA) {  // w[k][r][s][c]: column j = c contiguous, row (r,s,k)
+            const int col = n0 + (t % B_F4) * 4;
+            const int kk = kchunk + t / B_F4 + B_RP * i;
+            const int rs = fdiv(kk, p.fd_k), bk = kk - rs * g.K;
+            const int br = fdiv(rs, p.fd_s), bs = rs - br * g.S;
+            const int off = ((bk * g.R + br) * g.S + bs) * g.C + col;
+            if (VECB) {
+                const bool ok = kk < p.Kd && col < p.Nn;
+                rb[i] = ldg4(p.b + (ok ? off : 0));
+                okb |= (unsigned)ok << i;
+            } else {
+                float4 v = zero4();
+                if (kk < p.Kd) {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e)
+                        if (col + e < p.Nn) f4at(v, e) = p.b[off + e];
+                }
+                rb[i] = v;
+                okb |= 1u << i;
+            }
+        } else {  // BWD_WEIGHT B: x gathered at (pixel row, column (r,s,c))
+            const int col = n0 + (t % B_F4) * 4;
+            const int pix = kchunk + t / B_F4 + B_RP * i;
+            const int img = fdiv(pix, p.fd_howo), pq = pix - img * (g.Ho * g.Wo);
+            const int pp = fdiv(pq, p.fd_wo), q = pq - pp * g.Wo;
+            const int hb = pp * g.sh - g.ph, wb = q * g.sw - g.pw;
+            const int ib = img * g.H;
+            if (VECB) {
+                const int h = hb + bw_r[0], w = wb + bw_s[0];
+                const bool ok = pix < kend && col < p.Nn && (unsigned)h < (unsigned)g.H && (unsigned)w < (unsigned)g.W;
+                rb[i] = ldg4(p.b + (ok ? ((ib + h) * g.W + w) * g.C + bw_c[0] : 0));
+                okb |= (unsigned)ok << i;
+            } else {
+                float4 v = zero4();
+                if (pix < kend) {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const int h = hb + bw_r[e], w = wb + bw_s[e];
+                        if (col + e < p.Nn && (unsigned)h < (unsigned)g.H && (unsigned)w < (unsigned)g.W)
+                            f4at(v, e) = p.b[((ib + h) * g.W + w) * g.C + bw_c[e]];
+                    }
+                }
+                rb[i] = v;
+                okb |= 1u << i;
+            }
+        }
+    };
+
+    // Mask, gate and write the fetched stage into LDS buffer `buf`.
     auto stash = [&](int buf) {
-        if (MODE == MODE_BWD_WEIGHT) {
 #pragma unroll
-            for (int i = 0; i < AV; ++i)
-                *reinterpret_cast<float4 *>(&As[buf][t / A_F4 + A_RP * i][(t % A_F4) * 4]) = ra[i];
-        } else {
+        for (int i = 0; i < AV; ++i) {
+            float4 v = ra[i];
+            if (MODE != MODE_FWD && amask) v = gate4(v, rg[i]);
+            const bool ok = (oka >> i) & 1u;
+            v = make_float4(ok ? v.x : 0.f, ok ? v.y : 0.f, ok ? v.z : 0.f, ok ? v.w : 0.f);
+            if (MODE == MODE_BWD_WEIGHT) {
+                *reinterpret_cast<float4 *>(&As[buf][t / A_F4 + A_RP * i][(t % A_F4) * 4]) = v;
+                if (want_db) { dbacc.x += v.x; dbacc.y += v.y; dbacc.z += v.z; dbacc.w += v.w; }
+            } else {
 #pragma unroll
-            for (int i = 0; i < AV; ++i)
-#pragma unroll
-                for (int e = 0; e < 4; ++e) As[buf][kq * 4 + e][row0 + 64 * i] = f4at(ra[i], e);
+                for (int e = 0; e < 4; ++e) As[buf][kq * 4 + e][row0 + RPP * i] = f4at(v, e);
+            }
         }
-        if (MODE == MODE_FWD) {
 #pragma unroll
-            for (int i = 0; i < BV; ++i)
+        for (int i = 0; i < BV; ++i) {
+            const bool ok = (okb >> i) & 1u;
+            const float4 v = make_float4(ok ? rb[i].x : 0.f, ok ? rb[i].y : 0.f, ok ? rb[i].z : 0.f, ok ? rb[i].w : 0.f);
+            if (MODE == MODE_FWD) {
 #pragma unroll
-                for (int e = 0; e < 4; ++e) Bs[buf][kq * 4 + e][row0 + 64 * i] = f4at(rb[i], e);
-        } else {
-#pragma unroll
-            for (int i = 0; i < BV; ++i)
-                *reinterpret_cast<float4 *>(&Bs[buf][t / B_F4 + B_RP * i][(t % B_F4) * 4]) = rb[i];
+                for (int e = 0; e < 4; ++e) Bs[buf][kq * 4 + e][row0 + RPP * i] = f4at(const_cast<float4 &>(v), e);
+            } else {
+                *reinterpret_cast<float4 *>(&Bs[buf][t / B_F4 + B_RP * i][(t % B_F4) * 4]) = v;
+            }
         }
+        oka = 0;
+        okb = 0;
     };
 
     f32x16 acc[TM][TN];
@@ -399,40 +389,46 @@ __global__ __launch_bounds__(NTHREADS) void igemm_kernel(const GemmParams p)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-    if (nchunks > 0) {
-        fetch(0);
-        stash(0);
-    }
+#pragma unroll
+    for (int i = 0; i < AV; ++i) fetch_a(0, i);
+#pragma unroll
+    for (int i = 0; i < BV; ++i) fetch_b(0, i);
+    stash(0);
     __syncthreads();
 
     const int lrow = lane & 31, lk = lane >> 5;
+    constexpr int KS = BK / 2;                      // MFMA k-steps per stage
+    static_assert(AV + BV <= KS, "one fetch slot per k-step");
     for (int ch = 0; ch < nchunks; ++ch) {
         const int buf = ch & 1;
-        const bool more = ch + 1 < nchunks;
-        if (more) fetch(ch + 1);
-        // Operand registers are double-buffered so that the LDS reads of k-step ks+1 are in flight while the
-        // MFMAs of k-step ks issue.
+        // Per k-step: (1) LDS reads of the NEXT k-step's operands, (2) this k-step's MFMAs, (3) one slice of the
+        // next stage's global fetch (address arithmetic + load issue), which executes in the shadow of the MFMAs.
+        // The scheduling barriers pin this order.
         float av[2][TM], bv[2][TN];
 #pragma unroll
         for (int i = 0; i < TM; ++i) av[0][i] = As[buf][lk][wave_m * WTM + i * 32 + lrow];
 #pragma unroll
         for (int j = 0; j < TN; ++j) bv[0][j] = Bs[buf][lk][wave_n * WTN + j * 32 + lrow];
 #pragma unroll
-        for (int ks = 0; ks < BK / 2; ++ks) {
+        for (int ks = 0; ks < KS; ++ks) {
             const int cur = ks & 1, nxt = cur ^ 1;
-            if (ks + 1 < BK / 2) {
+            if (ks + 1 < KS) {
 #pragma unroll
                 for (int i = 0; i < TM; ++i) av[nxt][i] = As[buf][(ks + 1) * 2 + lk][wave_m * WTM + i * 32 + lrow];
 #pragma unroll
                 for (int j = 0; j < TN; ++j) bv[nxt][j] = Bs[buf][(ks + 1) * 2 + lk][wave_n * WTN + j * 32 + lrow];
             }
+            __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int i = 0; i < TM; ++i)
 #pragma unroll
                 for (int j = 0; j < TN; ++j)
                     acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[cur][i], bv[cur][j], acc[i][j], 0, 0, 0);
+            if (ks < AV) fetch_a(ch + 1, ks);
+            else if (ks < AV + BV) fetch_b(ch + 1, ks - AV);
+            __builtin_amdgcn_sched_barrier(0);
         }
-        if (more) stash(buf ^ 1);
+        stash(buf ^ 1);
         __syncthreads();
     }
 
