@@ -169,9 +169,46 @@ def main():
                      "algorithmic_gflop_per_step": (fwd_f + bwd_f) / 1e9, "kernel_ms_per_step": conv_ms},
     }
 
+    del worker, fcw, agg, shards, feats
+    torch.cuda.empty_cache()
+    out["ps_aggregate_k16"] = ps_config5(torch, api, W, dev)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(wl, seed)
     print(json.dumps(out))
+
+
+def ps_config5(torch, api, W, dev):
+    """Benchmark config 5: K = 16 gradient shards over the VGG-16-shaped conv parameter set (26 tensors) and
+    over the FC set (6 tensors); one launch each, timed with HIP events, three buffer sets rotated for the conv
+    set so that w and v do not stay in the 256 MB Infinity Cache between repetitions."""
+    wl = W.get_workload("vgg16")
+    K, res = 16, {}
+    for which, nsets in (("conv", 3), ("fc", 1)):
+        numels, _ = W.param_tensor_numels(wl, which)
+        sets = []
+        for _ in range(nsets):
+            w = [torch.randn(n, device=dev) * 0.05 for n in numels]
+            v = [torch.zeros(n, device=dev) for n in numels]
+            g = [[torch.randn(n, device=dev) * 1e-3 for n in numels] for _ in range(K)]
+            ws = torch.empty(api.stanza_ps_workspace_bytes(len(numels), K), dtype=torch.uint8, device=dev)
+            sets.append((ws, api.stanza_ps_plan(w, v, g, ws), w, v, g))
+        for i in range(3):
+            api.stanza_ps_aggregate_planned(sets[i % nsets][1], 1.0, 0.01, 0.9, 5e-4, sets[i % nsets][0])
+        torch.cuda.synchronize()
+        iters = 20
+        s, e = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        s.record()
+        for i in range(iters):
+            api.stanza_ps_aggregate_planned(sets[i % nsets][1], 1.0, 0.01, 0.9, 5e-4, sets[i % nsets][0])
+        e.record()
+        torch.cuda.synchronize()
+        us = s.elapsed_time(e) * 1e3 / iters
+        by = (K + 4) * 4 * sum(numels)
+        res[which] = {"params": sum(numels), "tensors": len(numels), "us": us, "GBps": by / us / 1e3,
+                      "frac_hbm": by / us / 1e3 / HBM_PEAK_GBS, "algorithmic_bytes": by}
+        del sets
+        torch.cuda.empty_cache()
+    return res
 
 
 def cpu_baseline(wl, seed):

@@ -13,7 +13,7 @@ from typing import List, Optional, Sequence
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libstanza.so")
+LIB_PATH = os.environ.get("STANZA_LIB", os.path.join(_HERE, "libstanza.so"))   # override: an alternative build of the same library
 
 F32, BF16 = 0, 1
 CONV_BIAS, CONV_RELU, CONV_ACCUM = 1, 2, 4

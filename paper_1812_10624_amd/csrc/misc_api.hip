@@ -202,7 +202,13 @@ __global__ void cast_bf16_f32_kernel(size_t numel, const uint16_t *__restrict__ 
 //   float* w[n_tensors], v[n_tensors]
 //   const float* grads[K * n_tensors]   shard-major
 typedef float v4f __attribute__((ext_vector_type(4)));
-constexpr int PS_CHUNK = 2048;  // elements per workgroup: 256 threads x 2 vectors of 4
+#ifndef STANZA_PS_CHUNK
+#define STANZA_PS_CHUNK 4096
+#endif
+#ifndef STANZA_PS_NT
+#define STANZA_PS_NT 1
+#endif
+constexpr int PS_CHUNK = STANZA_PS_CHUNK;  // elements per workgroup: 256 threads x PS_CHUNK/1024 vectors of 4
 
 struct PsTable {
     const int64_t *prefix;
@@ -242,34 +248,49 @@ __global__ __launch_bounds__(256) void ps_aggregate_kernel(const void *ws, int n
     float *__restrict__ v = tb.v[t];
     const float *const *gp = tb.grads + t;   // shard k at gp[k * n_tensors]
     const int kk = KFIX > 0 ? KFIX : K;
+    constexpr int U = PS_CHUNK / 1024;   // vectors per thread; all of their loads are issued before any store
+    if (base + PS_CHUNK <= numel) {
+        float4 s[U], wv[U], vv[U];
 #pragma unroll
-    for (int it = 0; it < PS_CHUNK / 1024; ++it) {
-        const int64_t i = base + (int64_t)it * 1024 + threadIdx.x * 4;
-        if (i + 3 < numel) {
-            float4 s = zero4();
+        for (int u = 0; u < U; ++u) s[u] = zero4();
 #pragma unroll
-            for (int k = 0; k < kk; ++k) {
-                const v4f gk = __builtin_nontemporal_load(reinterpret_cast<const v4f *>(gp[(size_t)k * n_tensors] + i));
-                s.x += gk[0]; s.y += gk[1]; s.z += gk[2]; s.w += gk[3];
+        for (int k = 0; k < kk; ++k) {
+            const float *gk = gp[(size_t)k * n_tensors] + base + threadIdx.x * 4;
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+#if STANZA_PS_NT
+                const v4f x = __builtin_nontemporal_load(reinterpret_cast<const v4f *>(gk + u * 1024));
+#else
+                const v4f x = *reinterpret_cast<const v4f *>(gk + u * 1024);
+#endif
+                s[u].x += x[0]; s[u].y += x[1]; s[u].z += x[2]; s[u].w += x[3];
             }
-            float4 wv = *reinterpret_cast<const float4 *>(w + i);
-            float4 vv = *reinterpret_cast<const float4 *>(v + i);
-            vv.x = mom * vv.x + (scale * s.x + wd * wv.x);
-            vv.y = mom * vv.y + (scale * s.y + wd * wv.y);
-            vv.z = mom * vv.z + (scale * s.z + wd * wv.z);
-            vv.w = mom * vv.w + (scale * s.w + wd * wv.w);
-            wv.x -= lr * vv.x; wv.y -= lr * vv.y; wv.z -= lr * vv.z; wv.w -= lr * vv.w;
-            *reinterpret_cast<float4 *>(v + i) = vv;
-            *reinterpret_cast<float4 *>(w + i) = wv;
-        } else {
-            for (int64_t j = i; j < numel && j < i + 4; ++j) {
-                float s = 0.f;
-                for (int k = 0; k < kk; ++k) s += gp[(size_t)k * n_tensors][j];
-                const float wj = w[j];
-                const float vel = mom * v[j] + (scale * s + wd * wj);
-                v[j] = vel;
-                w[j] = wj - lr * vel;
-            }
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            wv[u] = *reinterpret_cast<const float4 *>(w + base + u * 1024 + threadIdx.x * 4);
+            vv[u] = *reinterpret_cast<const float4 *>(v + base + u * 1024 + threadIdx.x * 4);
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            float4 a = vv[u], b = wv[u];
+            a.x = mom * a.x + (scale * s[u].x + wd * b.x);
+            a.y = mom * a.y + (scale * s[u].y + wd * b.y);
+            a.z = mom * a.z + (scale * s[u].z + wd * b.z);
+            a.w = mom * a.w + (scale * s[u].w + wd * b.w);
+            b.x -= lr * a.x; b.y -= lr * a.y; b.z -= lr * a.z; b.w -= lr * a.w;
+            *reinterpret_cast<float4 *>(v + base + u * 1024 + threadIdx.x * 4) = a;
+            *reinterpret_cast<float4 *>(w + base + u * 1024 + threadIdx.x * 4) = b;
+        }
+    } else {
+        // ragged last chunk of a tensor: scalar, same summation order
+        for (int64_t j = base + threadIdx.x; j < numel; j += 256) {
+            float sum = 0.f;
+            for (int k = 0; k < kk; ++k) sum += gp[(size_t)k * n_tensors][j];
+            const float wj = w[j];
+            const float vel = mom * v[j] + (scale * sum + wd * wj);
+            v[j] = vel;
+            w[j] = wj - lr * vel;
         }
     }
 }
