@@ -65,6 +65,8 @@ int launch_igemm(int mode, GemmParams &p, int splits, hipStream_t st)
     p.fd_s = make_fastdiv(g.S);
     p.fd_howo = make_fastdiv(g.Ho * g.Wo);
     p.fd_wo = make_fastdiv(g.Wo);
+    p.fd_rs = make_fastdiv(g.R * g.S);
+    if (g.R * g.S > 1 && ((mode == MODE_FWD && g.C % BK == 0) || (mode == MODE_BWD_DATA && g.K % BK == 0))) p.flags |= ORDER_TAP_MINOR;
     switch (mode) {
     case MODE_FWD: return launch_mode<MODE_FWD>(p, g.C % 4 == 0, g.C % 4 == 0, 1, st);
     case MODE_BWD_DATA: return launch_mode<MODE_BWD_DATA>(p, g.K % 4 == 0, g.C % 4 == 0, 1, st);

@@ -38,7 +38,8 @@ enum : uint32_t {
     EPI_XMASK = 8u,    // BWD_DATA: * [xmask > 0]
     EPI_SGD = 16u,     // BWD_WEIGHT: fused momentum-SGD update of sgd_w / sgd_v with the tile as gradient
     LOAD_AMASK = 32u,  // BWD_*: dy is gated by [amask > 0] as it is read
-    EPI_DBIAS = 64u    // BWD_WEIGHT: column-tile-0 workgroups also sum dy over their reduction slice (bias gradient)
+    EPI_DBIAS = 64u,   // BWD_WEIGHT: column-tile-0 workgroups also sum dy over their reduction slice (bias gradient)
+    ORDER_TAP_MINOR = 128u  // FWD / BWD_DATA: visit the reduction channel-block-major, tap-minor (needs channels % BK == 0)
 };
 
 struct ConvGeo {
@@ -62,7 +63,7 @@ __device__ __forceinline__ int fdiv(int n, FastDiv f) { return (int)(((uint64_t)
 
 struct GemmParams {
     ConvGeo g;
-    FastDiv fd_c, fd_k, fd_s, fd_howo, fd_wo;   // divisors C, K, S, Ho*Wo, Wo
+    FastDiv fd_c, fd_k, fd_s, fd_howo, fd_wo, fd_rs;   // divisors C, K, S, Ho*Wo, Wo, R*S
     const float *a;       // FWD: x      BWD_DATA: dy   BWD_WEIGHT: dy
     const float *amask;   // BWD_*: forward output y gating dy, or nullptr
     const float *b;       // FWD: w      BWD_DATA: w    BWD_WEIGHT: x
@@ -201,10 +202,22 @@ __global__ __launch_bounds__(NTHREADS) void igemm_kernel(const GemmParams p)
     const bool want_db = MODE == MODE_BWD_WEIGHT && (p.flags & EPI_DBIAS) && tile_n == 0;
     float4 dbacc = zero4();   // bias gradient: running sum of this thread's dy vectors (4 channels, its reduction rows)
 
+    // Reduction offset of stage `ch`.  The reduction index of FWD / BWD_DATA is (tap, channel); when the channel
+    // count is a multiple of BK a stage stays inside one tap, and the stages are visited channel-block-major,
+    // tap-minor: the R*S taps of one 64-byte channel block re-read the same few image rows back to back, so they
+    // hit in L2 instead of going out to the fabric once per tap.  Any visiting order gives the same sum up to
+    // rounding; this one is fixed by the shape alone.
+    const bool tap_minor = MODE != MODE_BWD_WEIGHT && (p.flags & ORDER_TAP_MINOR);
+    auto stage_k = [&](int ch) -> int {
+        if (!tap_minor) return kbeg + ch * BK;
+        const int cblk = fdiv(ch, p.fd_rs), tap = ch - cblk * (g.R * g.S);
+        return tap * (MODE == MODE_FWD ? g.C : g.K) + cblk * BK;
+    };
+
     // Issue the global loads of A vector i of stage `ch` (reduction offset kbeg + ch*BK).  Stages past the end
     // are fetched too: every lane is masked and reads the (valid) base address.
     auto fetch_a = [&](int ch, int i) {
-        const int kchunk = kbeg + ch * BK;
+        const int kchunk = stage_k(ch);
         if (MODE == MODE_FWD || MODE == MODE_BWD_DATA) {
             const int CC = (MODE == MODE_FWD) ? g.C : g.K;
             if (VECA) {
@@ -284,7 +297,7 @@ __global__ __launch_bounds__(NTHREADS) void igemm_kernel(const GemmParams p)
     };
 
     auto fetch_b = [&](int ch, int i) {
-        const int kchunk = kbeg + ch * BK;
+        const int kchunk = stage_k(ch);
         if (MODE == MODE_FWD) {  // w as [Nn][Kd], reduction contiguous
             const int j = n0 + row0 + RPP * i;
             const int kk = kchunk + kq * 4;
