@@ -2,6 +2,7 @@
 // launches of the implicit-GEMM engine in igemm.h, plus the two small fixed-order reductions the
 // filter gradient needs (split partial sums, bias-gradient column sums).
 #include "internal.h"
+#include "igemm_bf16.h"
 
 namespace stanza {
 
@@ -71,6 +72,50 @@ int launch_igemm(int mode, GemmParams &p, int splits, hipStream_t st)
     case MODE_FWD: return launch_mode<MODE_FWD>(p, g.C % 4 == 0, g.C % 4 == 0, 1, st);
     case MODE_BWD_DATA: return launch_mode<MODE_BWD_DATA>(p, g.K % 4 == 0, g.C % 4 == 0, 1, st);
     case MODE_BWD_WEIGHT: return launch_mode<MODE_BWD_WEIGHT>(p, g.K % 4 == 0, g.C % 4 == 0, splits, st);
+    }
+    return STANZA_EINVAL;
+}
+
+// ------------------------------------------------------------------ bf16-in path
+template <int MODE, int BM, int BN, int WM, int WN>
+static int launch_tile_bf16(GemmParams &p, int splits, hipStream_t st)
+{
+    p.tilesM = cdiv(p.M, BM);
+    p.tilesN = cdiv(p.Nn, BN);
+    p.tiles = p.tilesM * p.tilesN;
+    p.splits = splits;
+    dim3 grid((unsigned)(cdiv(p.tiles * splits, 8) * 8));
+    hipLaunchKernelGGL((igemm_bf16_kernel<MODE, BM, BN, WM, WN>), grid, dim3(NTHREADS), 0, st, p);
+    return launch_status();
+}
+
+template <int MODE>
+static int launch_mode_bf16(GemmParams &p, int splits, hipStream_t st)
+{
+    if (p.Nn <= 64) {
+        if ((int64_t)cdiv(p.M, 128) * splits >= 512) return launch_tile_bf16<MODE, 128, 64, 2, 2>(p, splits, st);
+        return launch_tile_bf16<MODE, 64, 64, 2, 2>(p, splits, st);
+    }
+    if (p.M <= 64 || (int64_t)cdiv(p.M, 128) * cdiv(p.Nn, 128) * splits < 512) return launch_tile_bf16<MODE, 64, 128, 2, 2>(p, splits, st);
+    return launch_tile_bf16<MODE, 128, 128, 2, 2>(p, splits, st);
+}
+
+int launch_igemm_bf16(int mode, GemmParams &p, int splits, hipStream_t st)
+{
+    const ConvGeo &g = p.g;
+    if (p.M <= 0 || p.Nn <= 0 || p.Kd <= 0 || splits <= 0) return STANZA_EINVAL;
+    if (g.C % 8 || g.K % 8) return STANZA_EUNSUPPORTED;
+    p.fd_c = make_fastdiv(g.C);
+    p.fd_k = make_fastdiv(g.K);
+    p.fd_s = make_fastdiv(g.S);
+    p.fd_howo = make_fastdiv(g.Ho * g.Wo);
+    p.fd_wo = make_fastdiv(g.Wo);
+    p.fd_rs = make_fastdiv(g.R * g.S);
+    if (g.R * g.S > 1 && ((mode == MODE_FWD && g.C % BKH == 0) || (mode == MODE_BWD_DATA && g.K % BKH == 0))) p.flags |= ORDER_TAP_MINOR;
+    switch (mode) {
+    case MODE_FWD: return launch_mode_bf16<MODE_FWD>(p, 1, st);
+    case MODE_BWD_DATA: return launch_mode_bf16<MODE_BWD_DATA>(p, 1, st);
+    case MODE_BWD_WEIGHT: return launch_mode_bf16<MODE_BWD_WEIGHT>(p, splits, st);
     }
     return STANZA_EINVAL;
 }
@@ -153,12 +198,12 @@ int launch_colsum(const float *a, const float *mask, int rows, int cols, float *
     return launch_status();
 }
 
-WgradPlan plan_wgrad(const ConvGeo &g, bool want_bias)
+WgradPlan plan_wgrad(const ConvGeo &g, bool want_bias, int bk)
 {
     WgradPlan pl{};
     const int M = g.K, Nn = g.R * g.S * g.C;
     const int64_t red = (int64_t)g.N * g.Ho * g.Wo;
-    const int chunks = (int)cdiv64(red, BK);
+    const int chunks = (int)cdiv64(red, bk);
     const int bm = M <= 64 ? 64 : 128, bn = Nn <= 64 ? 64 : 128;
     const int tiles = cdiv(M, bm) * cdiv(Nn, bn);
     int splits = cdiv(1024, tiles);
@@ -179,13 +224,20 @@ extern "C" size_t stanza_conv_workspace_bytes(const stanza_conv_desc *desc, int 
 {
     ConvGeo g;
     if (!desc || which != 2 || conv_geometry(desc, &g) != STANZA_OK) return 0;
-    return plan_wgrad(g, (desc->flags & STANZA_CONV_BIAS) != 0).bytes;
+    return plan_wgrad(g, (desc->flags & STANZA_CONV_BIAS) != 0, desc->dtype == STANZA_BF16 ? BKH : BK).bytes;
 }
 
+// float32 always; bfloat16 when both channel counts are multiples of 8 (one 16-byte vector stays inside a tap)
 static int check_dtype(const stanza_conv_desc *d)
 {
     if (d->dtype == STANZA_F32) return STANZA_OK;
+    if (d->dtype == STANZA_BF16 && d->C % 8 == 0 && d->K % 8 == 0) return STANZA_OK;
     return STANZA_EUNSUPPORTED;
+}
+
+static int launch_any(const stanza_conv_desc *d, int mode, GemmParams &p, int splits, hipStream_t st)
+{
+    return d->dtype == STANZA_BF16 ? launch_igemm_bf16(mode, p, splits, st) : launch_igemm(mode, p, splits, st);
 }
 
 extern "C" int stanza_conv_fwd(const stanza_conv_desc *desc, const void *x, const void *w, const float *bias, void *y,
@@ -208,7 +260,7 @@ extern "C" int stanza_conv_fwd(const stanza_conv_desc *desc, const void *x, cons
     p.Nn = p.g.K;
     p.Kd = p.g.R * p.g.S * p.g.C;
     p.flags = (has_bias ? EPI_BIAS : 0u) | ((desc->flags & STANZA_CONV_RELU) ? EPI_RELU : 0u);
-    return launch_igemm(MODE_FWD, p, 1, (hipStream_t)stream);
+    return launch_any(desc, MODE_FWD, p, 1, (hipStream_t)stream);
 }
 
 extern "C" int stanza_conv_bwd_data(const stanza_conv_desc *desc, const void *dy, const void *y, const void *w,
@@ -231,7 +283,7 @@ extern "C" int stanza_conv_bwd_data(const stanza_conv_desc *desc, const void *dy
     p.Nn = p.g.C;
     p.Kd = p.g.R * p.g.S * p.g.K;
     p.flags = ((desc->flags & STANZA_CONV_ACCUM) ? EPI_ACCUM : 0u) | (x_mask ? EPI_XMASK : 0u) | (p.amask ? LOAD_AMASK : 0u);
-    return launch_igemm(MODE_BWD_DATA, p, 1, (hipStream_t)stream);
+    return launch_any(desc, MODE_BWD_DATA, p, 1, (hipStream_t)stream);
 }
 
 extern "C" int stanza_conv_bwd_weight(const stanza_conv_desc *desc, const void *x, const void *dy, const void *y, float *dw,
@@ -245,7 +297,7 @@ extern "C" int stanza_conv_bwd_weight(const stanza_conv_desc *desc, const void *
     const bool want_bias = desc->flags & STANZA_CONV_BIAS;
     if (!x || !dy || !dw || (want_bias && !dbias)) return STANZA_ENULL;
     if (!aligned16(x) || !aligned16(dy) || !aligned16(dw) || !aligned16(y) || !aligned16(ws)) return STANZA_EALIGN;
-    const WgradPlan pl = plan_wgrad(p.g, want_bias);
+    const WgradPlan pl = plan_wgrad(p.g, want_bias, desc->dtype == STANZA_BF16 ? BKH : BK);
     if (pl.bytes > 0 && (!ws || ws_bytes < pl.bytes)) return ws ? STANZA_EWORKSPACE : STANZA_ENULL;
     hipStream_t st = (hipStream_t)stream;
     float *partial = (float *)ws;
@@ -261,7 +313,7 @@ extern "C" int stanza_conv_bwd_weight(const stanza_conv_desc *desc, const void *
     p.out = pl.splits > 1 ? partial : dw;
     p.dbias = pl.splits > 1 ? dbscratch : dbias;
     p.dbias_stride = p.g.K;
-    rc = launch_igemm(MODE_BWD_WEIGHT, p, pl.splits, st);
+    rc = launch_any(desc, MODE_BWD_WEIGHT, p, pl.splits, st);
     if (rc) return rc;
     if (pl.splits > 1)
         rc = launch_split_reduce(partial, pl.splits, (size_t)p.M * p.Nn, dw, dbscratch, want_bias ? (size_t)p.g.K : 0, dbias, st);

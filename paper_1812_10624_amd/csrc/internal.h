@@ -29,7 +29,7 @@ struct WgradPlan {
     size_t db_floats;      // splits * K bias-gradient partials when splits > 1 and a bias gradient is wanted
     size_t bytes;
 };
-WgradPlan plan_wgrad(const ConvGeo &g, bool want_bias);
+WgradPlan plan_wgrad(const ConvGeo &g, bool want_bias, int bk);   // bk: reduction depth of one LDS stage
 
 // Launch the implicit GEMM in `mode` over p (M, Nn, Kd, pointers and flags already set); picks the tile
 // shape, fills the tile counts.  `splits` > 1 only for MODE_BWD_WEIGHT.

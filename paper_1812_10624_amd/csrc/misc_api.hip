@@ -7,6 +7,15 @@
 
 namespace stanza {
 
+__device__ __forceinline__ uint16_t f32_to_bf16_rne(float f)
+{
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40u);  // NaN stays NaN
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+
+
 // ------------------------------------------------------------------ max-pool (+ReLU)
 struct PoolGeo {
     int N, H, W, C, wh, ww, sh, sw, ph, pw, Ho, Wo, relu;
@@ -114,6 +123,98 @@ __global__ __launch_bounds__(256) void pool_bwd_kernel(const PoolGeo g, const fl
         dx[o] = acc[0];
 }
 
+// bfloat16 variants: 8 channels (16 bytes) per thread; bf16 -> f32 is exact, so the comparison is done in float
+__device__ __forceinline__ float h2f(uint16_t h) { return __uint_as_float((uint32_t)h << 16); }
+
+__global__ __launch_bounds__(256) void pool_fwd_bf16_kernel(const PoolGeo g, const uint16_t *__restrict__ x, uint16_t *__restrict__ y,
+                                                            uint8_t *__restrict__ argmax, size_t total)
+{
+    const size_t id = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (id >= total) return;
+    const int CV = g.C / 8;
+    const int cv = (int)(id % CV);
+    size_t pix = id / CV;
+    const int q = (int)(pix % g.Wo);
+    pix /= g.Wo;
+    const int pp = (int)(pix % g.Ho);
+    const int n = (int)(pix / g.Ho);
+    uint16_t best[8];
+    int bidx[8];
+    bool found = false;
+    for (int i = 0; i < g.wh; ++i) {
+        const int h = pp * g.sh - g.ph + i;
+        if ((unsigned)h >= (unsigned)g.H) continue;
+        for (int j = 0; j < g.ww; ++j) {
+            const int w = q * g.sw - g.pw + j;
+            if ((unsigned)w >= (unsigned)g.W) continue;
+            const uint4 tv = *reinterpret_cast<const uint4 *>(x + (((size_t)n * g.H + h) * g.W + w) * g.C + cv * 8);
+            const uint16_t *v = reinterpret_cast<const uint16_t *>(&tv);
+#pragma unroll
+            for (int e = 0; e < 8; ++e)
+                if (!found || h2f(v[e]) > h2f(best[e])) { best[e] = v[e]; bidx[e] = i * g.ww + j; }
+            found = true;
+        }
+    }
+    const size_t o = id * 8;
+    uint4 outv;
+    uint16_t *ov = reinterpret_cast<uint16_t *>(&outv);
+    uint32_t am[2] = {0u, 0u};
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        ov[e] = (g.relu && h2f(best[e]) < 0.f) ? (uint16_t)0 : best[e];
+        am[e >> 2] |= (uint32_t)bidx[e] << (8 * (e & 3));
+    }
+    *reinterpret_cast<uint4 *>(y + o) = outv;
+    if (argmax) *reinterpret_cast<uint2 *>(argmax + o) = make_uint2(am[0], am[1]);
+}
+
+__global__ __launch_bounds__(256) void pool_bwd_bf16_kernel(const PoolGeo g, const uint16_t *__restrict__ dy, const uint16_t *__restrict__ y,
+                                                            const uint8_t *__restrict__ argmax, uint16_t *__restrict__ dx, size_t total)
+{
+    const size_t id = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (id >= total) return;
+    const int CV = g.C / 8;
+    const int cv = (int)(id % CV);
+    size_t pix = id / CV;
+    const int w = (int)(pix % g.W);
+    pix /= g.W;
+    const int h = (int)(pix % g.H);
+    const int n = (int)(pix / g.H);
+    float acc[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) acc[e] = 0.f;
+    for (int i = 0; i < g.wh; ++i) {
+        const int hp = h + g.ph - i;
+        if (hp < 0) break;
+        const int pp = hp / g.sh;
+        if (pp * g.sh != hp || pp >= g.Ho) continue;
+        for (int j = 0; j < g.ww; ++j) {
+            const int wq = w + g.pw - j;
+            if (wq < 0) break;
+            const int q = wq / g.sw;
+            if (q * g.sw != wq || q >= g.Wo) continue;
+            const size_t o = (((size_t)n * g.Ho + pp) * g.Wo + q) * g.C + cv * 8;
+            const uint32_t code = (uint32_t)(i * g.ww + j);
+            const uint2 am = *reinterpret_cast<const uint2 *>(argmax + o);
+            const uint4 dv = *reinterpret_cast<const uint4 *>(dy + o);
+            const uint16_t *d = reinterpret_cast<const uint16_t *>(&dv);
+            uint4 yv = make_uint4(0x3f803f80u, 0x3f803f80u, 0x3f803f80u, 0x3f803f80u);   // 1.0: no gate
+            if (g.relu) yv = *reinterpret_cast<const uint4 *>(y + o);
+            const uint16_t *yy = reinterpret_cast<const uint16_t *>(&yv);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const uint32_t a = ((e < 4 ? am.x : am.y) >> (8 * (e & 3))) & 255u;
+                if (a == code && h2f(yy[e]) > 0.f) acc[e] += h2f(d[e]);
+            }
+        }
+    }
+    uint4 outv;
+    uint16_t *ov = reinterpret_cast<uint16_t *>(&outv);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) ov[e] = f32_to_bf16_rne(acc[e]);
+    *reinterpret_cast<uint4 *>(dx + id * 8) = outv;
+}
+
 static int pool_geometry(const stanza_pool_desc *d, PoolGeo *g)
 {
     if (d->N <= 0 || d->H <= 0 || d->W <= 0 || d->C <= 0 || d->win_h <= 0 || d->win_w <= 0) return STANZA_EINVAL;
@@ -175,14 +276,6 @@ __global__ void gap_bwd_kernel(size_t total, int HW, int C, const float *__restr
 }
 
 // ------------------------------------------------------------------ bf16 casts
-__device__ __forceinline__ uint16_t f32_to_bf16_rne(float f)
-{
-    uint32_t u = __float_as_uint(f);
-    if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40u);  // NaN stays NaN
-    u += 0x7fffu + ((u >> 16) & 1u);
-    return (uint16_t)(u >> 16);
-}
-
 __global__ void cast_f32_bf16_kernel(size_t numel, const float *__restrict__ src, uint16_t *__restrict__ dst)
 {
     const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -321,11 +414,16 @@ extern "C" int stanza_pool_relu_fwd(const stanza_pool_desc *desc, int32_t dtype,
     PoolGeo g;
     int rc = pool_geometry(desc, &g);
     if (rc) return rc;
-    if (dtype != STANZA_F32) return STANZA_EUNSUPPORTED;
+    if (dtype != STANZA_F32 && !(dtype == STANZA_BF16 && g.C % 8 == 0)) return STANZA_EUNSUPPORTED;
     if (!x || !y) return STANZA_ENULL;
-    if (!aligned16(x) || !aligned16(y) || (reinterpret_cast<uintptr_t>(argmax) & 3u)) return STANZA_EALIGN;
+    if (!aligned16(x) || !aligned16(y) || (reinterpret_cast<uintptr_t>(argmax) & 7u)) return STANZA_EALIGN;
     hipStream_t st = (hipStream_t)stream;
     const size_t outs = (size_t)g.N * g.Ho * g.Wo * g.C;
+    if (dtype == STANZA_BF16) {
+        const size_t total = outs / 8;
+        hipLaunchKernelGGL(pool_fwd_bf16_kernel, dim3((unsigned)cdiv64(total, 256)), dim3(256), 0, st, g, (const uint16_t *)x, (uint16_t *)y, argmax, total);
+        return launch_status();
+    }
     if (g.C % 4 == 0) {
         const size_t total = outs / 4;
         hipLaunchKernelGGL(pool_fwd_kernel<4>, dim3((unsigned)cdiv64(total, 256)), dim3(256), 0, st, g, (const float *)x, (float *)y, argmax, total);
@@ -342,11 +440,17 @@ extern "C" int stanza_pool_relu_bwd(const stanza_pool_desc *desc, int32_t dtype,
     PoolGeo g;
     int rc = pool_geometry(desc, &g);
     if (rc) return rc;
-    if (dtype != STANZA_F32) return STANZA_EUNSUPPORTED;
+    if (dtype != STANZA_F32 && !(dtype == STANZA_BF16 && g.C % 8 == 0)) return STANZA_EUNSUPPORTED;
     if (!dy || !argmax || !dx || (g.relu && !y)) return STANZA_ENULL;
-    if (!aligned16(dy) || !aligned16(dx) || !aligned16(y) || (reinterpret_cast<uintptr_t>(argmax) & 3u)) return STANZA_EALIGN;
+    if (!aligned16(dy) || !aligned16(dx) || !aligned16(y) || (reinterpret_cast<uintptr_t>(argmax) & 7u)) return STANZA_EALIGN;
     hipStream_t st = (hipStream_t)stream;
     const size_t ins = (size_t)g.N * g.H * g.W * g.C;
+    if (dtype == STANZA_BF16) {
+        const size_t total = ins / 8;
+        hipLaunchKernelGGL(pool_bwd_bf16_kernel, dim3((unsigned)cdiv64(total, 256)), dim3(256), 0, st, g, (const uint16_t *)dy, (const uint16_t *)y, argmax,
+                           (uint16_t *)dx, total);
+        return launch_status();
+    }
     if (g.C % 4 == 0) {
         const size_t total = ins / 4;
         hipLaunchKernelGGL(pool_bwd_kernel<4>, dim3((unsigned)cdiv64(total, 256)), dim3(256), 0, st, g, (const float *)dy, (const float *)y, argmax,

@@ -1,0 +1,171 @@
+"""GPU parity of the bf16-in / fp32-accumulate conv path: inputs are the seeded float32 tensors rounded to
+bfloat16 (the checker consumes exactly those values in float64), outputs are compared at 2e-2."""
+import numpy as np
+import pytest
+import torch
+
+import workloads as wl_mod
+from gpu_util import TOL_BF16, host, rel_err
+from oracle import ConvGeom, PoolGeom
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def api():
+    from paper_1812_10624_amd import api as a
+    a.load()
+    assert torch.cuda.is_available()
+    return a
+
+
+def dev16(a):
+    """float32 array (bf16-representable) -> device bfloat16 tensor."""
+    bits = wl_mod.bf16_bits(a).view(np.int16)
+    return torch.from_numpy(bits).to("cuda:0").view(torch.bfloat16).reshape(a.shape)
+
+
+def host16(t):
+    torch.cuda.synchronize()
+    bits = t.view(torch.int16).cpu().numpy().view(np.uint16)
+    return wl_mod.bf16_to_f32(bits).reshape(tuple(t.shape))
+
+
+def dev32(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).to("cuda:0")
+
+
+CASES = [
+    (2, 19, 17, 8, 24, 3, 3, 1, 1),
+    (2, 14, 14, 64, 160, 3, 3, 1, 1),
+    (1, 56, 56, 64, 64, 3, 3, 1, 1),
+    (2, 28, 28, 24, 16, 1, 1, 1, 0),
+    (2, 15, 15, 24, 40, 1, 1, 2, 0),
+    (2, 29, 29, 16, 32, 3, 3, 2, 1),
+    (2, 27, 27, 16, 24, 5, 5, 1, 2),
+    (3, 13, 13, 32, 72, 3, 3, 1, 1),
+]
+
+
+def _draw(shape, seed, scale=1.0):
+    a = np.random.default_rng(seed).standard_normal(shape, dtype=np.float32) * np.float32(scale)
+    return wl_mod.round_bf16(a)
+
+
+@pytest.mark.parametrize("case", CASES, ids=lambda c: "n{}h{}w{}c{}k{}r{}s{}st{}p{}".format(*c))
+def test_conv_bf16(api, o32, case):
+    N, H, W, C, K, R, S, st, pad = case
+    g = ConvGeom(N, H, W, C, K, R, S, st, pad)
+    x, w = _draw((N, H, W, C), 1), _draw((K, R, S, C), 2, (1.0 / (R * S * C)) ** 0.5)
+    b = np.random.default_rng(3).standard_normal(K, dtype=np.float32)
+    dy = _draw((N, g.Ho, g.Wo, K), 4)
+    yf = _draw((N, g.Ho, g.Wo, K), 5)
+    xin = _draw((N, H, W, C), 6)
+    prev = _draw((N, H, W, C), 7)
+    # forward
+    d = api.conv_desc(N, H, W, C, K, R, S, st, pad, api.BF16, api.CONV_BIAS | api.CONV_RELU)
+    y = torch.empty((N, g.Ho, g.Wo, K), dtype=torch.bfloat16, device="cuda:0")
+    api.stanza_conv_fwd(d, dev16(x), dev16(w), dev32(b), y)
+    assert rel_err(host16(y), o32.conv_fwd(g, x, w, b, relu=True)) < TOL_BF16
+    # backward-data: plain, then gated + accumulated + masked
+    d0 = api.conv_desc(N, H, W, C, K, R, S, st, pad, api.BF16, 0)
+    dx = torch.empty((N, H, W, C), dtype=torch.bfloat16, device="cuda:0")
+    api.stanza_conv_bwd_data(d0, dev16(dy), None, dev16(w), None, dx)
+    assert rel_err(host16(dx), o32.conv_bwd_data(g, dy, w)) < TOL_BF16
+    ref = o32.conv_bwd_data(g, o32.relu_bwd(dy, yf), w)
+    ref = o32.relu_bwd((ref.astype(np.float64) + prev).astype(np.float32), xin)
+    d2 = api.conv_desc(N, H, W, C, K, R, S, st, pad, api.BF16, api.CONV_RELU | api.CONV_ACCUM)
+    dx2 = dev16(prev)
+    api.stanza_conv_bwd_data(d2, dev16(dy), dev16(yf), dev16(w), dev16(xin), dx2)
+    assert rel_err(host16(dx2), ref) < TOL_BF16
+    # backward-weight (fp32 outputs) with and without the gate
+    for gate in (False, True):
+        dye = o32.relu_bwd(dy, yf) if gate else dy
+        ref_dw, ref_db = o32.conv_bwd_weight(g, x, dye)
+        dd = api.conv_desc(N, H, W, C, K, R, S, st, pad, api.BF16, api.CONV_BIAS | (api.CONV_RELU if gate else 0))
+        ws = torch.empty(max(16, api.stanza_conv_workspace_bytes(dd, 2)), dtype=torch.uint8, device="cuda:0")
+        dw = torch.full((K, R, S, C), float("nan"), device="cuda:0")
+        db = torch.full((K,), float("nan"), device="cuda:0")
+        api.stanza_conv_bwd_weight(dd, dev16(x), dev16(dy), dev16(yf) if gate else None, dw, db, ws)
+        # products of bf16 values are exact in fp32, so the fp32-output gradient is held to a tighter bound
+        assert rel_err(host(dw), ref_dw) < 1e-3, (case, gate)
+        assert rel_err(host(db), ref_db) < 1e-3, (case, gate)
+
+
+def test_bf16_rejects_odd_channels(api):
+    d = api.conv_desc(1, 8, 8, 3, 16, 3, 3, 1, 1, api.BF16, 0)
+    x = torch.zeros(1, 8, 8, 3, dtype=torch.bfloat16, device="cuda:0")
+    w = torch.zeros(16, 3, 3, 3, dtype=torch.bfloat16, device="cuda:0")
+    y = torch.zeros(1, 8, 8, 16, dtype=torch.bfloat16, device="cuda:0")
+    with pytest.raises(api.StanzaError):
+        api.stanza_conv_fwd(d, x, w, None, y)
+
+
+@pytest.mark.parametrize("case", [(2, 16, 16, 8, 2, 2, 0, True), (2, 15, 13, 16, 3, 2, 0, True), (1, 14, 15, 24, 3, 2, 1, False)])
+def test_pool_bf16(api, o32, case):
+    N, H, W, C, win, st, pad, relu = case
+    g = PoolGeom(N, H, W, C, win, st, pad, relu)
+    x = _draw((N, H, W, C), 8)
+    x[0, :4, :4, :] = 0.25
+    y_ref, am_ref = o32.pool_relu_fwd(g, x)
+    d = api.pool_desc(N, H, W, C, win, st, pad, relu)
+    y = torch.empty(y_ref.shape, dtype=torch.bfloat16, device="cuda:0")
+    am = torch.full(y_ref.shape, 255, dtype=torch.uint8, device="cuda:0")
+    api.stanza_pool_relu_fwd(d, dev16(x), y, am, api.BF16)
+    np.testing.assert_array_equal(host16(y), y_ref)
+    np.testing.assert_array_equal(host(am), am_ref)
+    dy = _draw(y_ref.shape, 9)
+    dx = torch.empty(x.shape, dtype=torch.bfloat16, device="cuda:0")
+    api.stanza_pool_relu_bwd(d, dev16(dy), dev16(y_ref), dev32(am_ref), dx, api.BF16)
+    assert rel_err(host16(dx), o32.pool_relu_bwd(g, dy, y_ref, am_ref)) < TOL_BF16
+
+
+def test_cast_round_trip(api):
+    a = np.random.default_rng(10).standard_normal(100003, dtype=np.float32)
+    a[:4] = [0.0, -0.0, 1.0 + 2 ** -8, 1.0 + 3 * 2 ** -9]        # exact ties: round to even
+    src = dev32(a)
+    h = torch.empty(a.shape, dtype=torch.bfloat16, device="cuda:0")
+    api.stanza_cast_f32_to_bf16(src, h)
+    np.testing.assert_array_equal(h.view(torch.int16).cpu().numpy().view(np.uint16), wl_mod.bf16_bits(a))
+    back = torch.empty(a.shape, dtype=torch.float32, device="cuda:0")
+    api.stanza_cast_bf16_to_f32(h, back)
+    np.testing.assert_array_equal(host(back), wl_mod.round_bf16(a))
+
+
+def test_conv_bf16_full_size_sampled(api, o32):
+    """VGG-16-shaped conv2 (64 x 224 x 224 x 64 -> 64) at the real batch size, sampled outputs."""
+    N, H, W, C, K, R, S, st, pad = 64, 224, 224, 64, 64, 3, 3, 1, 1
+    g = ConvGeom(N, H, W, C, K, R, S, st, pad)
+    r = wl_mod.rng_for(31, "bf16full")
+    x = wl_mod.round_bf16(r.standard_normal((N, H, W, C), dtype=np.float32))
+    w = wl_mod.round_bf16(r.standard_normal((K, R, S, C), dtype=np.float32) * np.float32((2.0 / 576) ** 0.5))
+    b = r.standard_normal(K, dtype=np.float32) * np.float32(0.1)
+    dy = wl_mod.round_bf16(r.standard_normal((N, H, W, K), dtype=np.float32))
+    xd, wd, dyd = dev16(x), dev16(w), dev16(dy)
+    d = api.conv_desc(N, H, W, C, K, R, S, st, pad, api.BF16, api.CONV_BIAS | api.CONV_RELU)
+    y = torch.empty((N, H, W, K), dtype=torch.bfloat16, device="cuda:0")
+    api.stanza_conv_fwd(d, xd, wd, dev32(b), y)
+    yh = host16(y)
+    rs = np.random.default_rng(1)
+    idx = [tuple(int(rs.integers(0, s)) for s in yh.shape) for _ in range(40)] + [(0, 0, 0, 0), (63, 223, 223, 63)]
+    want = np.array([o32.conv_fwd_at(g, x, w, b, True, *i) for i in idx])
+    got = np.array([yh[i] for i in idx], np.float64)
+    assert (np.abs(got - want) / np.maximum(np.abs(want), 0.05 * np.abs(yh).max())).max() < TOL_BF16
+    del y, yh
+    d0 = api.conv_desc(N, H, W, C, K, R, S, st, pad, api.BF16, api.CONV_BIAS)
+    ws = torch.empty(max(16, api.stanza_conv_workspace_bytes(d0, 2)), dtype=torch.uint8, device="cuda:0")
+    dw = torch.empty((K, R, S, C), device="cuda:0")
+    db = torch.empty((K,), device="cuda:0")
+    api.stanza_conv_bwd_weight(d0, xd, dyd, None, dw, db, ws)
+    dwh = host(dw)
+    idx = [tuple(int(rs.integers(0, s)) for s in dwh.shape) for _ in range(16)]
+    want = np.array([o32.conv_bwd_weight_at(g, x, dy, *i) for i in idx])
+    got = np.array([dwh[i] for i in idx], np.float64)
+    assert (np.abs(got - want) / np.maximum(np.abs(want), 0.05 * np.abs(dwh).max())).max() < 1e-3
+    dx = torch.empty((N, H, W, C), dtype=torch.bfloat16, device="cuda:0")
+    api.stanza_conv_bwd_data(api.conv_desc(N, H, W, C, K, R, S, st, pad, api.BF16, 0), dyd, None, wd, None, dx)
+    dxh = host16(dx)
+    idx = [tuple(int(rs.integers(0, s)) for s in dxh.shape) for _ in range(40)]
+    want = np.array([o32.conv_bwd_data_at(g, dy, w, *i) for i in idx])
+    got = np.array([dxh[i] for i in idx], np.float64)
+    assert (np.abs(got - want) / np.maximum(np.abs(want), 0.05 * np.abs(dxh).max())).max() < TOL_BF16

@@ -327,3 +327,23 @@ def param_tensor_numels(wl: Workload, which: str) -> Tuple[List[int], List[int]]
             numels += [o * i, o]
             fans += [i, i]
     return numels, fans
+
+
+# ----------------------------------------------------------------------------
+# bfloat16 storage of seeded tensors (input preparation only: round to nearest even)
+# ----------------------------------------------------------------------------
+
+def bf16_bits(a: np.ndarray) -> np.ndarray:
+    """float32 array -> uint16 array of bfloat16 bit patterns, round-to-nearest-even."""
+    u = np.ascontiguousarray(a, np.float32).view(np.uint32).astype(np.uint64)
+    u = u + 0x7FFF + ((u >> 16) & 1)
+    return (u >> 16).astype(np.uint16)
+
+
+def bf16_to_f32(bits: np.ndarray) -> np.ndarray:
+    return (bits.astype(np.uint32) << 16).view(np.float32)
+
+
+def round_bf16(a: np.ndarray) -> np.ndarray:
+    """float32 array whose values are exactly representable in bfloat16."""
+    return bf16_to_f32(bf16_bits(a)).reshape(np.shape(a))
