@@ -22,6 +22,7 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0        # MI355X HBM3E
 MFMA_F32_PEAK_TFLOPS = 157.3  # MI355X dense fp32 matrix peak
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 matrix peak
 
 
 def main():
@@ -30,6 +31,7 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="vgg16")
+    ap.add_argument("--dtype", default="f32", choices=["f32", "bf16"], help="conv-stack storage type (accumulation is always f32)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--detail", action="store_true", help="per-call timing table on stderr")
     ap.add_argument("--calibrate", action="store_true",
@@ -68,7 +70,7 @@ def main():
         fp.append((torch.randn((o, i), device=dev, generator=gen) * (2.0 / i) ** 0.5,
                    (torch.rand(o, device=dev, generator=gen) * 2 - 1) / i ** 0.5))
         fm.append((torch.zeros((o, i), device=dev), torch.zeros(o, device=dev)))
-    worker = ConvWorker(wl.ops, wl.image, B, cp)
+    worker = ConvWorker(wl.ops, wl.image, B, cp, dtype=api.BF16 if args.dtype == "bf16" else api.F32)
     fcw = FcWorker(wl.fc_dims, n, fp, fm, wl.lr, wl.momentum, wl.weight_decay)
     feats = torch.randn((n, wl.fc_dims[0]), device=dev, generator=gen).clamp_(min=0)   # filler rows of the other workers
     names = list(cp)
@@ -89,7 +91,8 @@ def main():
 
     real = {k: getattr(api, k) for k in ("stanza_conv_fwd", "stanza_conv_bwd_data", "stanza_conv_bwd_weight",
                                          "stanza_pool_relu_fwd", "stanza_pool_relu_bwd", "stanza_add_relu_fwd",
-                                         "stanza_add_relu_bwd", "stanza_gap_fwd", "stanza_gap_bwd")}
+                                         "stanza_add_relu_bwd", "stanza_gap_fwd", "stanza_gap_bwd", "stanza_cast_f32_to_bf16",
+                                         "stanza_cast_bf16_to_f32")}
     import paper_1812_10624_amd.netrun as netrun
 
     class _Tap:
@@ -101,8 +104,7 @@ def main():
     netrun.api = _Tap()
 
     def step():
-        worker.forward()
-        feats[:B].copy_(worker.buf["feat"].view(B, -1))        # hand-off: this worker's rows of the FC input
+        feats[:B].copy_(worker.forward().view(B, -1))          # hand-off: this worker's rows of the FC input
         timed("stanza_fc_step", fcw.step, feats, labels)
         worker.backward(fcw.dfeats[:B])                         # hand-back: this worker's slice of the gradient
         timed("stanza_ps_aggregate", agg.step, 1.0, wl.lr, wl.momentum, wl.weight_decay)
@@ -165,8 +167,8 @@ def main():
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f32", "data": "synthetic",
-        "config": {"workload": f"{wl.name}_shaped_conv_worker_B{B}_fc_worker_n{n}_K{K}_fp32",
+        "dtype": args.dtype, "data": "synthetic",
+        "config": {"workload": f"{wl.name}_shaped_conv_worker_B{B}_fc_worker_n{n}_K{K}_" + ("fp32" if args.dtype == "f32" else "bf16in_fp32acc"),
                    "per_worker_batch": B, "conv_workers_K": K, "fc_rows": n},
         "conv_worker_images_per_s": B / (conv_worker_ms * 1e-3),
         "conv_worker_ms": conv_worker_ms,
@@ -177,7 +179,7 @@ def main():
         "roofline": {"bound": "mfma", "kernel": "stanza::igemm_kernel (all launches of a step: conv fwd / bwd_data / bwd_weight "
                                                  "and the FC worker's GEMMs)",
                      "achieved": gemm_tflops, "peak": MFMA_F32_PEAK_TFLOPS, "unit": "TFLOP/s",
-                     "frac": gemm_tflops / MFMA_F32_PEAK_TFLOPS, "traffic": traffic_from_profile(wl.name),
+                     "frac": gemm_tflops / MFMA_F32_PEAK_TFLOPS, "traffic": traffic_from_profile(wl.name) if args.dtype == "f32" else None,
                      "algorithmic_gflop_per_step": gemm_flops / 1e9, "kernel_ms_per_step": gemm_ms,
                      "conv_only": {"achieved": conv_tflops, "frac": conv_tflops / MFMA_F32_PEAK_TFLOPS,
                                    "algorithmic_gflop_per_step": (fwd_f + bwd_f) / 1e9, "kernel_ms_per_step": conv_ms}},
@@ -186,6 +188,12 @@ def main():
     del worker, fcw, agg, shards, feats
     torch.cuda.empty_cache()
     out["ps_aggregate_k16"] = ps_config5(torch, api, W, dev)
+    if args.dtype == "bf16":
+        # the conv GEMMs run on the bf16 matrix pipe (the 3-channel first layer and the FC worker stay f32)
+        out["roofline"] = {"bound": "mfma", "kernel": "stanza::igemm_bf16_kernel (conv fwd / bwd_data / bwd_weight launches; first layer in f32)",
+                           "achieved": conv_tflops, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                           "frac": conv_tflops / MFMA_BF16_PEAK_TFLOPS, "traffic": None,
+                           "algorithmic_gflop_per_step": (fwd_f + bwd_f) / 1e9, "kernel_ms_per_step": conv_ms}
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(wl, seed)
     print(json.dumps(out))

@@ -14,21 +14,30 @@ from . import api
 
 class ConvWorker:
     """One CONV worker: its conv stack forward up to the activations handed to the FC worker, and the
-    backward pass from the gradient of those activations to per-layer filter/bias gradients."""
+    backward pass from the gradient of those activations to per-layer filter/bias gradients.
 
-    def __init__(self, ops: List[dict], image_shape, batch: int, params: Dict[str, tuple], device="cuda:0"):
+    dtype=api.BF16 keeps activations, activation gradients and a per-step copy of the filters in bfloat16
+    (master filters, filter/bias gradients, images, features and feature gradients stay float32); a conv
+    whose channel counts are not multiples of 8 (the first layer, C = 3) runs in float32 between casts."""
+
+    def __init__(self, ops: List[dict], image_shape, batch: int, params: Dict[str, tuple], device="cuda:0", dtype=api.F32):
         self.ops = ops
         self.dev = torch.device(device)
-        self.params = params                      # name -> (W [K,R,S,C], b [K]) device tensors (shared between workers)
+        self.dtype = dtype
+        self.tdt = torch.bfloat16 if dtype == api.BF16 else torch.float32
+        self.params = params                      # name -> (W [K,R,S,C], b [K]) float32 device tensors (shared between workers)
         self.shapes = {"x0": (batch,) + tuple(image_shape)}
         self.producer = {}
         self.descs = {}
+        self.f32_layer = {}                       # op index -> True when a conv runs in float32 inside a bf16 stack
         for i, op in enumerate(ops):
             kind = op["op"]
             if kind == "conv":
                 n, h, w, c = self.shapes[op["src"]]
                 flags = api.CONV_BIAS | (api.CONV_RELU if op["relu"] else 0)
-                d = api.conv_desc(n, h, w, c, op["K"], op["R"], op["S"], op["stride"], op["pad"], api.F32, flags)
+                low = dtype == api.BF16 and c % 8 == 0 and op["K"] % 8 == 0
+                self.f32_layer[i] = dtype == api.BF16 and not low
+                d = api.conv_desc(n, h, w, c, op["K"], op["R"], op["S"], op["stride"], op["pad"], api.BF16 if low else api.F32, flags)
                 ho, wo = api.conv_out_hw(d)
                 self.shapes[op["dst"]] = (n, ho, wo, op["K"])
                 self.descs[i] = d
@@ -45,41 +54,67 @@ class ConvWorker:
                 n, h, w, c = self.shapes[op["src"]]
                 self.shapes[op["dst"]] = (n, 1, 1, c)
             self.producer[op["dst"]] = op
-        f32 = dict(device=self.dev, dtype=torch.float32)
-        self.buf = {name: torch.empty(shape, **f32) for name, shape in self.shapes.items()}
+        if dtype == api.BF16:
+            assert all(op["op"] in ("conv", "pool") for op in ops), "bf16 stacks: conv and pool ops only"
+        self.buf = {name: torch.empty(shape, device=self.dev, dtype=torch.float32 if name == "x0" else self.tdt)
+                    for name, shape in self.shapes.items()}
         self.argmax = {op["dst"]: torch.empty(self.shapes[op["dst"]], device=self.dev, dtype=torch.uint8)
                        for op in ops if op["op"] == "pool"}
         self.gbuf: Dict[str, torch.Tensor] = {}
         self.grads = {name: (torch.empty_like(w), torch.empty_like(b)) for name, (w, b) in params.items()}
         ws_bytes = max([api.stanza_conv_workspace_bytes(d, 2) for i, d in self.descs.items() if ops[i]["op"] == "conv"] + [16])
         self.ws = torch.empty(ws_bytes, device=self.dev, dtype=torch.uint8)
+        if dtype == api.BF16:
+            self.w16 = {op["name"]: torch.empty_like(params[op["name"]][0], dtype=torch.bfloat16)
+                        for i, op in enumerate(ops) if op["op"] == "conv" and not self.f32_layer[i]}
+            big = max(int(torch.tensor(self.shapes[op["dst"]]).prod()) for i, op in enumerate(ops) if op["op"] == "conv" and self.f32_layer[i]) \
+                if any(self.f32_layer.values()) else 0
+            self.tmp32 = torch.empty(max(big, 1), device=self.dev, dtype=torch.float32)   # float32 staging of a mixed layer's y / dy
+            self.feat32 = torch.empty(self.shapes["feat"], device=self.dev, dtype=torch.float32)
+            self.dfeat16 = torch.empty(self.shapes["feat"], device=self.dev, dtype=torch.bfloat16)
 
     # ------------------------------------------------------------------ forward
     def forward(self, images: Optional[torch.Tensor] = None) -> torch.Tensor:
+        """Returns the float32 activations handed to the FC worker."""
         if images is not None:
             self.buf["x0"].copy_(images)
         for i, op in enumerate(self.ops):
             kind = op["op"]
             if kind == "conv":
                 w, b = self.params[op["name"]]
-                api.stanza_conv_fwd(self.descs[i], self.buf[op["src"]], w, b, self.buf[op["dst"]])
+                if self.dtype == api.BF16 and not self.f32_layer[i]:
+                    api.stanza_cast_f32_to_bf16(w, self.w16[op["name"]])      # this step's bf16 copy of the master filter
+                    api.stanza_conv_fwd(self.descs[i], self.buf[op["src"]], self.w16[op["name"]], b, self.buf[op["dst"]])
+                elif self.f32_layer[i]:
+                    y32 = self.tmp32[: self.buf[op["dst"]].numel()].view(self.shapes[op["dst"]])
+                    api.stanza_conv_fwd(self.descs[i], self.buf[op["src"]], w, b, y32)
+                    api.stanza_cast_f32_to_bf16(y32, self.buf[op["dst"]])
+                else:
+                    api.stanza_conv_fwd(self.descs[i], self.buf[op["src"]], w, b, self.buf[op["dst"]])
             elif kind == "pool":
-                api.stanza_pool_relu_fwd(self.descs[i], self.buf[op["src"]], self.buf[op["dst"]], self.argmax[op["dst"]])
+                api.stanza_pool_relu_fwd(self.descs[i], self.buf[op["src"]], self.buf[op["dst"]], self.argmax[op["dst"]], self.dtype)
             elif kind == "add_relu":
                 api.stanza_add_relu_fwd(self.buf[op["a"]], self.buf[op["b"]], self.buf[op["dst"]])
             elif kind == "gap":
                 api.stanza_gap_fwd(self.buf[op["src"]], self.buf[op["dst"]])
+        if self.dtype == api.BF16:
+            api.stanza_cast_bf16_to_f32(self.buf["feat"], self.feat32)
+            return self.feat32
         return self.buf["feat"]
 
     # ------------------------------------------------------------------ backward
     def _grad_buffer(self, name, like=None):
         if name not in self.gbuf:
-            self.gbuf[name] = torch.empty(self.shapes[like or name], device=self.dev, dtype=torch.float32)
+            self.gbuf[name] = torch.empty(self.shapes[like or name], device=self.dev, dtype=self.tdt)
         return self.gbuf[name]
 
     def backward(self, dfeat: torch.Tensor):
-        """dfeat: gradient of the activations handed to the FC worker, [B, A] or the buffer's own shape."""
-        have: Dict[str, torch.Tensor] = {"feat": dfeat.view(self.shapes["feat"])}
+        """dfeat: float32 gradient of the activations handed to the FC worker, [B, A] or the buffer's own shape."""
+        dfeat = dfeat.reshape(self.shapes["feat"])
+        if self.dtype == api.BF16:
+            api.stanza_cast_f32_to_bf16(dfeat.contiguous(), self.dfeat16)
+            dfeat = self.dfeat16
+        have: Dict[str, torch.Tensor] = {"feat": dfeat}
         gated = {"feat": False}   # True when the stored gradient is already multiplied by [buffer > 0]
         for i in reversed(range(len(self.ops))):
             op = self.ops[i]
@@ -91,6 +126,16 @@ class ConvWorker:
                 y = None if (gated.get(op["dst"], False) or not op["relu"]) else self.buf[op["dst"]]
                 w, _ = self.params[op["name"]]
                 dw, db = self.grads[op["name"]]
+                if self.f32_layer.get(i, False):
+                    # mixed layer (first conv of a bf16 stack): float32 filter gradient from a float32 copy of dy
+                    assert op["src"] == "x0", "a float32 conv inside a bf16 stack must be the first layer"
+                    if y is not None:
+                        raise NotImplementedError("ungated gradient into a mixed-precision first layer")
+                    dy32 = self.tmp32[: dy.numel()].view(dy.shape)
+                    api.stanza_cast_bf16_to_f32(dy, dy32)
+                    api.stanza_conv_bwd_weight(d, self.buf["x0"], dy32, None, dw, db, self.ws)
+                    continue
+                wk = self.w16[op["name"]] if self.dtype == api.BF16 else w
                 api.stanza_conv_bwd_weight(d, self.buf[op["src"]], dy, y, dw, db, self.ws)
                 src = op["src"]
                 if src != "x0":
@@ -103,12 +148,12 @@ class ConvWorker:
                     else:
                         dx = self._grad_buffer(src)
                         have[src] = dx
-                    api.stanza_conv_bwd_data(dd, dy, y, w, x_mask, dx)
+                    api.stanza_conv_bwd_data(dd, dy, y, wk, x_mask, dx)
                     gated[src] = x_mask is not None
             elif kind == "pool":
                 dx = self._grad_buffer(op["src"])
                 assert op["src"] not in have
-                api.stanza_pool_relu_bwd(self.descs[i], have.pop(op["dst"]), self.buf[op["dst"]], self.argmax[op["dst"]], dx)
+                api.stanza_pool_relu_bwd(self.descs[i], have.pop(op["dst"]), self.buf[op["dst"]], self.argmax[op["dst"]], dx, self.dtype)
                 have[op["src"]] = dx
                 gated[op["src"]] = bool(op["relu"])   # [P>0] at the argmax equals [Y>0] there
             elif kind == "add_relu":
