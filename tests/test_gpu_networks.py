@@ -1,0 +1,75 @@
+"""Whole conv stacks of the benchmark's configs 2-4 at their real layer shapes (224 x 224 images, every layer,
+the residual DAG) and a reduced per-worker batch, GPU sequencer against the CPU checker: features handed to the FC
+worker, per-layer filter and bias gradients, then the FC step on those features."""
+import numpy as np
+import pytest
+import torch
+
+import workloads as wl_mod
+from gpu_util import dev, host, rel_err
+from oracle import network as onet
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def api():
+    from paper_1812_10624_amd import api as a
+    a.load()
+    assert torch.cuda.is_available()
+    return a
+
+
+@pytest.mark.parametrize("name,B", [("alexnet", 2), ("vgg16", 1), ("resnet50", 2)])
+def test_conv_stack_real_shapes(api, o32, name, B):
+    from paper_1812_10624_amd.netrun import ConvWorker
+    wl = wl_mod.get_workload(name)
+    img = wl_mod.gen_images(wl, 0, 0, B)
+    cp = wl_mod.gen_conv_params(wl, 0)
+    bufs = onet.conv_stack_forward(o32, wl.ops, img, cp)
+    feat_ref = bufs["feat"].reshape(B, -1)
+    dfeat = (wl_mod.rng_for(5, "dfeat", name).standard_normal(feat_ref.shape, dtype=np.float32) / np.float32(feat_ref.shape[0]))
+    pg, bgr = onet.conv_stack_backward(o32, wl.ops, bufs, cp, dfeat)
+    gcp = {n: (dev(w), dev(b)) for n, (w, b) in cp.items()}
+    wk = ConvWorker(wl.ops, wl.image, B, gcp)
+    feat = wk.forward(dev(img)).view(B, -1)
+    e_feat = rel_err(host(feat), feat_ref)
+    assert e_feat < 1e-4, (name, e_feat)
+    wk.backward(dev(dfeat))
+    # Whole chain: far down a deep stack a last-bit difference flips a few ReLU masks / pool argmaxes and moves single
+    # entries, so the end-to-end gradients are held to direction and size ...
+    for n in cp:
+        for which in range(2):
+            a, b = host(wk.grads[n][which]).ravel().astype(np.float64), pg[n][which].ravel().astype(np.float64)
+            cos = float(a @ b / (np.linalg.norm(a) * np.linalg.norm(b) + 1e-300))
+            assert cos > 0.9999, (name, n, which, cos)
+            assert abs(np.linalg.norm(a) / np.linalg.norm(b) - 1) < 1e-2, (name, n, which)
+    # ... and every conv layer's backward is held to the 1e-4 bound on the checker's own inputs for that layer.
+    from oracle import ConvGeom
+    worst = 0.0
+    for op in wl.ops:
+        if op["op"] != "conv":
+            continue
+        x = bufs[op["src"]]
+        n_, h, w, c = x.shape
+        g = ConvGeom(n_, h, w, c, op["K"], op["R"], op["S"], op["stride"], op["pad"])
+        dy = np.ascontiguousarray(bgr[op["dst"]])
+        dz = o32.relu_bwd(dy, bufs[op["dst"]]) if op["relu"] else dy
+        d = api.conv_desc(n_, h, w, c, op["K"], op["R"], op["S"], op["stride"], op["pad"], api.F32,
+                          api.CONV_BIAS | (api.CONV_RELU if op["relu"] else 0))
+        yd = dev(bufs[op["dst"]]) if op["relu"] else None
+        ws = torch.empty(max(16, api.stanza_conv_workspace_bytes(d, 2)), dtype=torch.uint8, device="cuda:0")
+        dw, db = torch.empty(cp[op["name"]][0].shape, device="cuda:0"), torch.empty(op["K"], device="cuda:0")
+        xd, dyd = dev(x), dev(dy)
+        api.stanza_conv_bwd_weight(d, xd, dyd, yd, dw, db, ws)
+        ref_dw, ref_db = o32.conv_bwd_weight(g, x, dz)
+        e1, e2 = rel_err(host(dw), ref_dw), rel_err(host(db), ref_db)
+        assert e1 < 1e-4 and e2 < 1e-4, (name, op["name"], e1, e2)
+        worst = max(worst, e1, e2)
+        if op["src"] != "x0":
+            dx = torch.empty(x.shape, device="cuda:0")
+            api.stanza_conv_bwd_data(d, dyd, yd, gcp[op["name"]][0], None, dx)
+            e3 = rel_err(host(dx), o32.conv_bwd_data(g, dz, cp[op["name"]][0]))
+            assert e3 < 1e-4, (name, op["name"], e3)
+            worst = max(worst, e3)
+    print(f"{name}: features E={e_feat:.2e}, worst layer-wise backward E={worst:.2e}")
