@@ -188,6 +188,30 @@ int stanza_ps_aggregate(int32_t n_tensors, const int64_t *host_numel, float *con
                         const float *const *host_grads, int32_t K, float scale, float lr, float momentum,
                         float weight_decay, void *ws, size_t ws_bytes, void *stream);
 
+/* ---- Performance model and node assignment (host arithmetic only; Sec. 4.2 and Sec. 7.1).  Times in seconds,
+ * bandwidth in bit/s per node, every transferred value is 32 bits wide.
+ *   rounds(n_c)          = log2 n_c when n_c is a power of two, floor(log2 n_c) + 2 otherwise (recursive doubling with
+ *                          the extra send/return rounds for the surplus workers, Sec. 4.1.2); 0 for n_c = 1
+ *   t_s(n_c, n_f)        = T_c + (n_c/n_f) T_f + 2 n_c A K / (n_f B) + P_c rounds(n_c) / B            (Eqs. 2-3)
+ *   throughput_s         = n_c K / t_s                                                             (Eq. 4)
+ *   assignment           = argmax over n_c + n_f = N, n_c, n_f >= 1 of throughput_s, by exhaustive search   (Eq. 5)
+ *   t_ps(n_w, n_s)       = 2 n_w P / (n_s B) + T_ps ;  throughput_ps = n_w K / t_ps                  (Eqs. 6-7)
+ * T_c, T_f: single-worker CONV time and FC time for ONE conv worker's activations (measured, e.g. by bench.py);
+ * A: activations per sample handed to the FC worker; K: per-node batch; P_c, P: parameter counts.
+ * The time functions return a negative value on invalid arguments (counts < 1, non-positive bandwidth). */
+typedef struct {
+    double T_c, T_f;          /* seconds */
+    double A, K, P_c;         /* activations per sample, per-node batch, conv parameters */
+    double bandwidth_bits;    /* per-node bandwidth, bit/s */
+} stanza_model_params;
+
+int32_t stanza_model_allreduce_rounds(int32_t n_c);
+double stanza_model_stanza_time(const stanza_model_params *m, int32_t n_c, int32_t n_f);
+double stanza_model_stanza_throughput(const stanza_model_params *m, int32_t n_c, int32_t n_f);
+int stanza_model_assign(const stanza_model_params *m, int32_t N, int32_t *n_c, int32_t *n_f, double *throughput);
+double stanza_model_ps_time(double P, double T_ps, int32_t n_w, int32_t n_s, double bandwidth_bits);
+double stanza_model_ps_throughput(double P, double T_ps, double K, int32_t n_w, int32_t n_s, double bandwidth_bits);
+
 #ifdef __cplusplus
 }
 #endif

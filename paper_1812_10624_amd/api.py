@@ -25,6 +25,8 @@ EXPORTS = (
     "stanza_add_relu_bwd", "stanza_gap_fwd", "stanza_gap_bwd", "stanza_cast_f32_to_bf16", "stanza_cast_bf16_to_f32",
     "stanza_fc_workspace_bytes", "stanza_fc_step", "stanza_ps_workspace_bytes", "stanza_ps_plan",
     "stanza_ps_aggregate_planned", "stanza_ps_aggregate",
+    "stanza_model_allreduce_rounds", "stanza_model_stanza_time", "stanza_model_stanza_throughput", "stanza_model_assign",
+    "stanza_model_ps_time", "stanza_model_ps_throughput",
 )
 
 
@@ -40,6 +42,10 @@ class ConvDesc(C.Structure):
 class PoolDesc(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("N", "H", "W", "C", "win_h", "win_w", "stride_h", "stride_w", "pad_h", "pad_w")] + \
                [("flags", C.c_uint32)]
+
+
+class ModelParams(C.Structure):
+    _fields_ = [(n, C.c_double) for n in ("T_c", "T_f", "A", "K", "P_c", "bandwidth_bits")]
 
 
 class FcDesc(C.Structure):
@@ -83,6 +89,18 @@ def load() -> C.CDLL:
     lib.stanza_ps_plan.argtypes = [i32, vp, vp, vp, vp, i32, vp, sz, vp]
     lib.stanza_ps_aggregate_planned.argtypes = [i32, vp, i32, f32, f32, f32, f32, vp, sz, vp]
     lib.stanza_ps_aggregate.argtypes = [i32, vp, vp, vp, vp, i32, f32, f32, f32, f32, vp, sz, vp]
+    f64 = C.c_double
+    lib.stanza_model_allreduce_rounds.restype = i32
+    lib.stanza_model_allreduce_rounds.argtypes = [i32]
+    lib.stanza_model_stanza_time.restype = f64
+    lib.stanza_model_stanza_time.argtypes = [C.POINTER(ModelParams), i32, i32]
+    lib.stanza_model_stanza_throughput.restype = f64
+    lib.stanza_model_stanza_throughput.argtypes = [C.POINTER(ModelParams), i32, i32]
+    lib.stanza_model_assign.argtypes = [C.POINTER(ModelParams), i32, C.POINTER(i32), C.POINTER(i32), C.POINTER(f64)]
+    lib.stanza_model_ps_time.restype = f64
+    lib.stanza_model_ps_time.argtypes = [f64, f64, i32, i32, f64]
+    lib.stanza_model_ps_throughput.restype = f64
+    lib.stanza_model_ps_throughput.argtypes = [f64, f64, f64, i32, i32, f64]
     _lib = lib
     return lib
 
@@ -229,3 +247,30 @@ def stanza_ps_aggregate(w, v, grads, scale, lr, momentum, weight_decay, ws):
     p, n = _ws(ws)
     _check(load().stanza_ps_aggregate(nt, numel, pw, pv, pg, K, scale, lr, momentum, weight_decay, p, n, _stream()),
            "stanza_ps_aggregate")
+
+
+# ---- performance model (host arithmetic)
+def stanza_model_allreduce_rounds(n_c: int) -> int:
+    return int(load().stanza_model_allreduce_rounds(n_c))
+
+
+def stanza_model_stanza_time(m: ModelParams, n_c: int, n_f: int) -> float:
+    return float(load().stanza_model_stanza_time(C.byref(m), n_c, n_f))
+
+
+def stanza_model_stanza_throughput(m: ModelParams, n_c: int, n_f: int) -> float:
+    return float(load().stanza_model_stanza_throughput(C.byref(m), n_c, n_f))
+
+
+def stanza_model_assign(m: ModelParams, N: int):
+    nc, nf, th = C.c_int32(), C.c_int32(), C.c_double()
+    _check(load().stanza_model_assign(C.byref(m), N, C.byref(nc), C.byref(nf), C.byref(th)), "stanza_model_assign")
+    return nc.value, nf.value, th.value
+
+
+def stanza_model_ps_time(P, T_ps, n_w, n_s, bandwidth_bits) -> float:
+    return float(load().stanza_model_ps_time(P, T_ps, n_w, n_s, bandwidth_bits))
+
+
+def stanza_model_ps_throughput(P, T_ps, K, n_w, n_s, bandwidth_bits) -> float:
+    return float(load().stanza_model_ps_throughput(P, T_ps, K, n_w, n_s, bandwidth_bits))
