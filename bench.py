@@ -185,6 +185,16 @@ def main():
                                    "algorithmic_gflop_per_step": (fwd_f + bwd_f) / 1e9, "kernel_ms_per_step": conv_ms}},
     }
 
+    # the paper's performance model (Sec. 4.2) fed with the times measured above
+    mp = api.ModelParams(conv_worker_ms * 1e-3, tot["stanza_fc_step"] * 1e-3 / K, float(wl.fc_dims[0]), float(B), float(conv_params), 10e9)
+    model = {"T_c_s": mp.T_c, "T_f_s_per_conv_worker": mp.T_f, "A": mp.A, "K_per_node_batch": mp.K, "P_c": mp.P_c}
+    for tag, bw in (("ethernet_10Gb", 10e9), ("xgmi_link_153GBps", 153e9 * 8)):
+        mp.bandwidth_bits = bw
+        nc, nf, th = api.stanza_model_assign(mp, 9)
+        model[tag] = {"t_iteration_s_at_K_conv_1_fc": api.stanza_model_stanza_time(mp, K, 1),
+                      "throughput_samples_per_s_at_K_conv_1_fc": api.stanza_model_stanza_throughput(mp, K, 1),
+                      "best_split_of_9_nodes": [nc, nf], "best_throughput_samples_per_s": th}
+    out["stanza_model"] = model
     del worker, fcw, agg, shards, feats
     torch.cuda.empty_cache()
     out["ps_aggregate_k16"] = ps_config5(torch, api, W, dev)
