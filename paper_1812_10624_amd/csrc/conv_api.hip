@@ -31,7 +31,12 @@ static int launch_tile(GemmParams &p, bool veca, bool vecb, int splits, hipStrea
     p.tiles = p.tilesM * p.tilesN;
     p.splits = splits;
     dim3 grid((unsigned)(cdiv(p.tiles * splits, 8) * 8));
-    if (veca && vecb)
+    const ConvGeo &g = p.g;
+    const bool fast = veca && vecb &&
+                      ((MODE == MODE_FWD && g.C % BK == 0) || (MODE == MODE_BWD_DATA && g.K % BK == 0 && g.sh == 1 && g.sw == 1));
+    if (MODE != MODE_BWD_WEIGHT && fast)
+        hipLaunchKernelGGL((igemm_kernel<MODE, BM, BN, WM, WN, true, true, MODE != MODE_BWD_WEIGHT>), grid, dim3(NTHREADS), 0, st, p);
+    else if (veca && vecb)
         hipLaunchKernelGGL((igemm_kernel<MODE, BM, BN, WM, WN, true, true>), grid, dim3(NTHREADS), 0, st, p);
     else if (MODE == MODE_BWD_WEIGHT && veca)   // first layer: dy is vectorisable, the 3-channel image is not
         hipLaunchKernelGGL((igemm_kernel<MODE, BM, BN, WM, WN, true, false>), grid, dim3(NTHREADS), 0, st, p);
@@ -68,10 +73,17 @@ int launch_igemm(int mode, GemmParams &p, int splits, hipStream_t st)
     p.fd_wo = make_fastdiv(g.Wo);
     p.fd_rs = make_fastdiv(g.R * g.S);
     if (g.R * g.S > 1 && ((mode == MODE_FWD && g.C % BK == 0) || (mode == MODE_BWD_DATA && g.K % BK == 0))) p.flags |= ORDER_TAP_MINOR;
+    // extents of the two gathered tensors; the vector fetch paths address them with 32-bit byte offsets below 2 GiB
+    const int64_t xb = (int64_t)g.N * g.H * g.W * g.C * 4, yb = (int64_t)g.N * g.Ho * g.Wo * g.K * 4, wb = (int64_t)g.K * g.R * g.S * g.C * 4;
+    const int64_t ab = mode == MODE_FWD ? xb : yb, bb = mode == MODE_BWD_WEIGHT ? xb : wb;
+    const int64_t lim = int64_t(1) << 31;
+    p.a_bytes = (uint32_t)(ab < lim ? ab : 0);
+    p.b_bytes = (uint32_t)(bb < lim ? bb : 0);
+    const bool small_a = ab < lim, small_b = bb < lim;
     switch (mode) {
-    case MODE_FWD: return launch_mode<MODE_FWD>(p, g.C % 4 == 0, g.C % 4 == 0, 1, st);
-    case MODE_BWD_DATA: return launch_mode<MODE_BWD_DATA>(p, g.K % 4 == 0, g.C % 4 == 0, 1, st);
-    case MODE_BWD_WEIGHT: return launch_mode<MODE_BWD_WEIGHT>(p, g.K % 4 == 0, g.C % 4 == 0, splits, st);
+    case MODE_FWD: return launch_mode<MODE_FWD>(p, g.C % 4 == 0 && small_a && small_b, g.C % 4 == 0 && small_a && small_b, 1, st);
+    case MODE_BWD_DATA: return launch_mode<MODE_BWD_DATA>(p, g.K % 4 == 0 && small_a, g.C % 4 == 0 && small_b, 1, st);
+    case MODE_BWD_WEIGHT: return launch_mode<MODE_BWD_WEIGHT>(p, g.K % 4 == 0 && small_a, g.C % 4 == 0 && small_b, splits, st);
     }
     return STANZA_EINVAL;
 }

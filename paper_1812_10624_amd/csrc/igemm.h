@@ -79,6 +79,7 @@ struct GemmParams {
     int splits;           // reduction slices (1 except for BWD_WEIGHT)
     int chunks_per_split; // BWD_WEIGHT: reduction chunks (of BK) per slice
     uint32_t flags;
+    uint32_t a_bytes, b_bytes;   // extent of the a / b tensors (vector fetch paths address them as 32-bit buffer offsets)
 };
 
 __device__ __forceinline__ float4 ldg4(const float *p) { return *reinterpret_cast<const float4 *>(p); }
@@ -88,6 +89,19 @@ __device__ __forceinline__ float4 ldg4_if(const float *base, int off, bool ok)
 {
     const float4 v = ldg4(base + (ok ? off : 0));
     return make_float4(ok ? v.x : 0.f, ok ? v.y : 0.f, ok ? v.z : 0.f, ok ? v.w : 0.f);
+}
+// Vector fetches go through buffer loads: a lane whose element is padding, beyond a ragged edge or past the end of the
+// reduction is given the offset OOB_OFF, which lies outside the buffer, and the hardware returns zero for it.  That
+// replaces a pointer select, a 64-bit address computation and four data selects per vector.
+constexpr uint32_t OOB_OFF = 0x80000000u;   // tensors on this path are at most 2 GiB
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void *ptr, uint32_t bytes)
+{
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(ptr), 0, bytes, 0x00020000);
+}
+__device__ __forceinline__ float4 bload4(__amdgpu_buffer_rsrc_t r, uint32_t byte_off)
+{
+    return __builtin_bit_cast(float4, __builtin_amdgcn_raw_buffer_load_b128(r, byte_off, 0, 0));
 }
 __device__ __forceinline__ float &f4at(float4 &v, int e) { return reinterpret_cast<float *>(&v)[e]; }
 __device__ __forceinline__ float4 gate4(float4 v, float4 m)
@@ -105,7 +119,10 @@ __device__ __forceinline__ bool strided_src(int hp, int stride, int limit, int &
     return (hp - p * stride == 0) && p < limit;
 }
 
-template <int MODE, int BM, int BN, int WM, int WN, bool VECA, bool VECB>
+// FAST (FWD / BWD_DATA with both vector paths, channel count a multiple of BK, unit stride for BWD_DATA): a stage lies
+// inside one filter tap, so the tap is wavefront-uniform (scalar registers) and a row's address is a precomputed row
+// offset plus a scalar; no per-thread division or multiplication is left in the main loop.
+template <int MODE, int BM, int BN, int WM, int WN, bool VECA, bool VECB, bool FAST = false>
 __global__ __launch_bounds__(NTHREADS) void igemm_kernel(const GemmParams p)
 {
     static_assert(WM * WN == 4, "four wavefronts per workgroup");
@@ -153,6 +170,8 @@ __global__ __launch_bounds__(NTHREADS) void igemm_kernel(const GemmParams p)
     // A operand state
     int a_hb[AV], a_wb[AV];          // FWD: p*sh-ph, q*sw-pw      BWD_DATA: h+ph, w+pw
     int a_base[AV];                  // element offset of the image (FWD: n*H*W*C, BWD_DATA: n*Ho*Wo*K)
+    int a_row[AV];                   // FAST: element offset of the row's tap-(0,0) source pixel (may be out of the image)
+    int b_row[BV];                   // FAST: element offset of this thread's B vector at stage 0
     // B operand state
     int bw_r[4], bw_s[4], bw_c[4];   // BWD_WEIGHT: fixed (r,s,c) of this thread's 4 columns
 
@@ -169,7 +188,10 @@ __global__ __launch_bounds__(NTHREADS) void igemm_kernel(const GemmParams p)
             } else {
                 a_hb[i] = -(1 << 28); a_wb[i] = 0; a_base[i] = 0;
             }
+            a_row[i] = m < p.M ? a_base[i] + (a_hb[i] * g.W + a_wb[i]) * g.C + kq * 4 : 0;
         }
+#pragma unroll
+        for (int i = 0; i < BV; ++i) b_row[i] = (n0 + row0 + RPP * i) * p.Kd + kq * 4;
     } else if (MODE == MODE_BWD_DATA) {
         const int HW = g.H * g.W;
 #pragma unroll
@@ -183,7 +205,11 @@ __global__ __launch_bounds__(NTHREADS) void igemm_kernel(const GemmParams p)
             } else {
                 a_hb[i] = -(1 << 28); a_wb[i] = 0; a_base[i] = 0;
             }
+            a_row[i] = m < p.M ? a_base[i] + (a_hb[i] * g.Wo + a_wb[i]) * g.K + kq * 4 : 0;   // unit stride: p = h+ph-r, q = w+pw-s
         }
+#pragma unroll
+        for (int i = 0; i < BV; ++i)   // w[k][r][s][c] at k = reduction row of this thread, tap (0,0), its 4 columns
+            b_row[i] = (t / (BN / 4) + (NTHREADS / (BN / 4)) * i) * (g.R * g.S * g.C) + n0 + (t % (BN / 4)) * 4;
     } else {
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
@@ -195,10 +221,14 @@ __global__ __launch_bounds__(NTHREADS) void igemm_kernel(const GemmParams p)
         }
     }
 
-    // Stage registers: raw loaded vectors, their validity bits (applied when the stage is written to LDS, so
-    // that nothing waits on a global load before the MFMAs of the current stage), optional ReLU-gate vectors.
+    const __amdgpu_buffer_rsrc_t rsrc_a = make_rsrc(p.a, p.a_bytes);
+    const __amdgpu_buffer_rsrc_t rsrc_g = make_rsrc(p.amask ? p.amask : p.a, p.a_bytes);
+    const __amdgpu_buffer_rsrc_t rsrc_b = make_rsrc(p.b, p.b_bytes);
+
+    // Stage registers: loaded vectors (vector paths: already zero where masked, see OOB_OFF) and optional ReLU-gate
+    // vectors; the gate is applied when the stage is written to LDS, so that nothing waits on a global load before
+    // the MFMAs of the current stage.
     float4 ra[AV], rb[BV], rg[AV];
-    unsigned oka = 0, okb = 0;
     const bool want_db = MODE == MODE_BWD_WEIGHT && (p.flags & EPI_DBIAS) && tile_n == 0;
     float4 dbacc = zero4();   // bias gradient: running sum of this thread's dy vectors (4 channels, its reduction rows)
 
@@ -207,16 +237,34 @@ __global__ __launch_bounds__(NTHREADS) void igemm_kernel(const GemmParams p)
     // tap-minor: the R*S taps of one 64-byte channel block re-read the same few image rows back to back, so they
     // hit in L2 instead of going out to the fabric once per tap.  Any visiting order gives the same sum up to
     // rounding; this one is fixed by the shape alone.
-    const bool tap_minor = MODE != MODE_BWD_WEIGHT && (p.flags & ORDER_TAP_MINOR);
+    const bool tap_minor = MODE != MODE_BWD_WEIGHT && (FAST || (p.flags & ORDER_TAP_MINOR));
     auto stage_k = [&](int ch) -> int {
         if (!tap_minor) return kbeg + ch * BK;
         const int cblk = fdiv(ch, p.fd_rs), tap = ch - cblk * (g.R * g.S);
         return tap * (MODE == MODE_FWD ? g.C : g.K) + cblk * BK;
     };
 
-    // Issue the global loads of A vector i of stage `ch` (reduction offset kbeg + ch*BK).  Stages past the end
-    // are fetched too: every lane is masked and reads the (valid) base address.
+    // Issue the global loads of A vector i of stage `ch`.  Stages past the end are fetched too, fully masked.
     auto fetch_a = [&](int ch, int i) {
+        if (FAST) {
+            // wavefront-uniform: channel block and tap of the stage
+            const int cblk = fdiv(ch, p.fd_rs), tap = ch - cblk * (g.R * g.S);
+            const int ar = fdiv(tap, p.fd_s), as = tap - ar * g.S;
+            const bool kok = ch < nchunks;
+            int off;
+            bool ok;
+            if (MODE == MODE_FWD) {
+                ok = kok && (unsigned)(a_hb[i] + ar) < (unsigned)g.H && (unsigned)(a_wb[i] + as) < (unsigned)g.W;
+                off = a_row[i] + ((ar * g.W + as) * g.C + cblk * BK);
+            } else {
+                ok = kok && (unsigned)(a_hb[i] - ar) < (unsigned)g.Ho && (unsigned)(a_wb[i] - as) < (unsigned)g.Wo;
+                off = a_row[i] + (cblk * BK - (ar * g.Wo + as) * g.K);
+            }
+            const uint32_t bo = ok ? (uint32_t)off * 4u : OOB_OFF;
+            ra[i] = bload4(rsrc_a, bo);
+            if (MODE == MODE_BWD_DATA && amask) rg[i] = bload4(rsrc_g, bo);
+            return;
+        }
         const int kchunk = stage_k(ch);
         if (MODE == MODE_FWD || MODE == MODE_BWD_DATA) {
             const int CC = (MODE == MODE_FWD) ? g.C : g.K;
@@ -236,10 +284,9 @@ __global__ __launch_bounds__(NTHREADS) void igemm_kernel(const GemmParams p)
                     ok = strided_src(a_wb[i] - as, g.sw, g.Wo, q) && ok && kk < p.Kd;
                     off = a_base[i] + (pp * g.Wo + q) * g.K + cc;
                 }
-                off = ok ? off : 0;
-                ra[i] = ldg4(p.a + off);
-                if (MODE == MODE_BWD_DATA && amask) rg[i] = ldg4(p.amask + off);
-                oka |= (unsigned)ok << i;
+                const uint32_t bo = ok ? (uint32_t)off * 4u : OOB_OFF;
+                ra[i] = bload4(rsrc_a, bo);
+                if (MODE == MODE_BWD_DATA && amask) rg[i] = bload4(rsrc_g, bo);
             } else {
                 float4 v = zero4();
 #pragma unroll
@@ -266,17 +313,15 @@ __global__ __launch_bounds__(NTHREADS) void igemm_kernel(const GemmParams p)
                 }
                 ra[i] = v;
                 rg[i] = make_float4(1.f, 1.f, 1.f, 1.f);
-                oka |= 1u << i;
             }
         } else {  // BWD_WEIGHT A: dy viewed as [pixel][K], row m = output channel
             const int col = m0 + (t % A_F4) * 4;
             const int pix = kchunk + t / A_F4 + A_RP * i;
             if (VECA) {
                 const bool ok = pix < kend && col < p.M;
-                const int off = ok ? pix * g.K + col : 0;
-                ra[i] = ldg4(p.a + off);
-                if (amask) rg[i] = ldg4(p.amask + off);
-                oka |= (unsigned)ok << i;
+                const uint32_t bo = ok ? (uint32_t)(pix * g.K + col) * 4u : OOB_OFF;
+                ra[i] = bload4(rsrc_a, bo);
+                if (amask) rg[i] = bload4(rsrc_g, bo);
             } else {
                 float4 v = zero4();
                 if (pix < kend) {
@@ -291,20 +336,32 @@ __global__ __launch_bounds__(NTHREADS) void igemm_kernel(const GemmParams p)
                 }
                 ra[i] = v;
                 rg[i] = make_float4(1.f, 1.f, 1.f, 1.f);
-                oka |= 1u << i;
             }
         }
     };
 
     auto fetch_b = [&](int ch, int i) {
+        if (FAST) {
+            const int cblk = fdiv(ch, p.fd_rs), tap = ch - cblk * (g.R * g.S);
+            bool ok = ch < nchunks;
+            int off;
+            if (MODE == MODE_FWD) {
+                ok = ok && n0 + row0 + RPP * i < p.Nn;
+                off = b_row[i] + (tap * g.C + cblk * BK);
+            } else {
+                ok = ok && n0 + (t % B_F4) * 4 < p.Nn;
+                off = b_row[i] + (cblk * BK * (g.R * g.S) + tap) * g.C;
+            }
+            rb[i] = bload4(rsrc_b, ok ? (uint32_t)off * 4u : OOB_OFF);
+            return;
+        }
         const int kchunk = stage_k(ch);
         if (MODE == MODE_FWD) {  // w as [Nn][Kd], reduction contiguous
             const int j = n0 + row0 + RPP * i;
             const int kk = kchunk + kq * 4;
             if (VECB) {
                 const bool ok = j < p.Nn && kk < p.Kd;
-                rb[i] = ldg4(p.b + (ok ? j * p.Kd + kk : 0));
-                okb |= (unsigned)ok << i;
+                rb[i] = bload4(rsrc_b, ok ? (uint32_t)(j * p.Kd + kk) * 4u : OOB_OFF);
             } else {
                 float4 v = zero4();
                 if (j < p.Nn) {
@@ -313,7 +370,6 @@ __global__ __launch_bounds__(NTHREADS) void igemm_kernel(const GemmParams p)
                         if (kk + e < p.Kd) f4at(v, e) = p.b[j * p.Kd + kk + e];
                 }
                 rb[i] = v;
-                okb |= 1u << i;
             }
         } else if (MODE == MODE_BWD_DATA) {  // w[k][r][s][c]: column j = c contiguous, row (r,s,k)
             const int col = n0 + (t % B_F4) * 4;
@@ -323,8 +379,7 @@ __global__ __launch_bounds__(NTHREADS) void igemm_kernel(const GemmParams p)
             const int off = ((bk * g.R + br) * g.S + bs) * g.C + col;
             if (VECB) {
                 const bool ok = kk < p.Kd && col < p.Nn;
-                rb[i] = ldg4(p.b + (ok ? off : 0));
-                okb |= (unsigned)ok << i;
+                rb[i] = bload4(rsrc_b, ok ? (uint32_t)off * 4u : OOB_OFF);
             } else {
                 float4 v = zero4();
                 if (kk < p.Kd) {
@@ -333,7 +388,6 @@ __global__ __launch_bounds__(NTHREADS) void igemm_kernel(const GemmParams p)
                         if (col + e < p.Nn) f4at(v, e) = p.b[off + e];
                 }
                 rb[i] = v;
-                okb |= 1u << i;
             }
         } else {  // BWD_WEIGHT B: x gathered at (pixel row, column (r,s,c))
             const int col = n0 + (t % B_F4) * 4;
@@ -345,8 +399,7 @@ __global__ __launch_bounds__(NTHREADS) void igemm_kernel(const GemmParams p)
             if (VECB) {
                 const int h = hb + bw_r[0], w = wb + bw_s[0];
                 const bool ok = pix < kend && col < p.Nn && (unsigned)h < (unsigned)g.H && (unsigned)w < (unsigned)g.W;
-                rb[i] = ldg4(p.b + (ok ? ((ib + h) * g.W + w) * g.C + bw_c[0] : 0));
-                okb |= (unsigned)ok << i;
+                rb[i] = bload4(rsrc_b, ok ? (uint32_t)(((ib + h) * g.W + w) * g.C + bw_c[0]) * 4u : OOB_OFF);
             } else {
                 float4 v = zero4();
                 if (pix < kend) {
@@ -358,19 +411,16 @@ __global__ __launch_bounds__(NTHREADS) void igemm_kernel(const GemmParams p)
                     }
                 }
                 rb[i] = v;
-                okb |= 1u << i;
             }
         }
     };
 
-    // Mask, gate and write the fetched stage into LDS buffer `buf`.
+    // Gate and write the fetched stage into LDS buffer `buf`.
     auto stash = [&](int buf) {
 #pragma unroll
         for (int i = 0; i < AV; ++i) {
             float4 v = ra[i];
             if (MODE != MODE_FWD && amask) v = gate4(v, rg[i]);
-            const bool ok = (oka >> i) & 1u;
-            v = make_float4(ok ? v.x : 0.f, ok ? v.y : 0.f, ok ? v.z : 0.f, ok ? v.w : 0.f);
             if (MODE == MODE_BWD_WEIGHT) {
                 *reinterpret_cast<float4 *>(&As[buf][t / A_F4 + A_RP * i][(t % A_F4) * 4]) = v;
                 if (want_db) { dbacc.x += v.x; dbacc.y += v.y; dbacc.z += v.z; dbacc.w += v.w; }
@@ -381,17 +431,13 @@ __global__ __launch_bounds__(NTHREADS) void igemm_kernel(const GemmParams p)
         }
 #pragma unroll
         for (int i = 0; i < BV; ++i) {
-            const bool ok = (okb >> i) & 1u;
-            const float4 v = make_float4(ok ? rb[i].x : 0.f, ok ? rb[i].y : 0.f, ok ? rb[i].z : 0.f, ok ? rb[i].w : 0.f);
             if (MODE == MODE_FWD) {
 #pragma unroll
-                for (int e = 0; e < 4; ++e) Bs[buf][kq * 4 + e][row0 + RPP * i] = f4at(const_cast<float4 &>(v), e);
+                for (int e = 0; e < 4; ++e) Bs[buf][kq * 4 + e][row0 + RPP * i] = f4at(rb[i], e);
             } else {
-                *reinterpret_cast<float4 *>(&Bs[buf][t / B_F4 + B_RP * i][(t % B_F4) * 4]) = v;
+                *reinterpret_cast<float4 *>(&Bs[buf][t / B_F4 + B_RP * i][(t % B_F4) * 4]) = rb[i];
             }
         }
-        oka = 0;
-        okb = 0;
     };
 
     f32x16 acc[TM][TN];
