@@ -132,10 +132,19 @@ __global__ __launch_bounds__(NTHREADS) void igemm_kernel(const GemmParams p)
     constexpr int TM = WTM / 32, TN = WTN / 32;
     constexpr int RPP = NTHREADS / KQ;                   // tile rows covered by one pass of a reduction-contiguous fetch
     constexpr int AV = BM * BK / 1024, BV = BN * BK / 1024;  // 16-byte vectors per thread per stage
-    constexpr int LDA = BM + (MODE == MODE_BWD_WEIGHT ? PAD_V : PAD_T), LDB = BN + (MODE == MODE_FWD ? PAD_T : PAD_V);
-
-    __shared__ __attribute__((aligned(16))) float As[2][BK][LDA];
-    __shared__ __attribute__((aligned(16))) float Bs[2][BK][LDB];
+    // LDS layouts.  An operand whose reduction index is contiguous in memory (x and w in FWD, dy in BWD_DATA) is kept
+    // ROW-MAJOR, [rows][BK+4]: the fetched 16-byte vector is stored as it is, and a lane reads 4 consecutive reduction
+    // elements of its row with one 16-byte read (80-byte rows: 8 consecutive rows cover all 32 banks), which feed 4
+    // MFMAs.  Lanes 0-31 take elements 8g..8g+3 and lanes 32-63 elements 8g+4..8g+7 of reduction group g, so MFMA j of
+    // the group multiplies the element pair (8g+j, 8g+4+j): a permutation of the reduction that both operands follow.
+    // An operand whose row/column index is contiguous (w in BWD_DATA, dy and x in BWD_WEIGHT) is kept
+    // REDUCTION-MAJOR, [BK][rows+4], stored as 16-byte vectors and read as scalars (conflict-free 128-byte rows).
+    constexpr bool A_ROWK = MODE != MODE_BWD_WEIGHT, B_ROWK = MODE == MODE_FWD;
+    constexpr int LDK = BK + 4;
+    constexpr int LDA = BM + PAD_V, LDB = BN + PAD_V;
+    constexpr int A_FLOATS = A_ROWK ? BM * LDK : BK * LDA, B_FLOATS = B_ROWK ? BN * LDK : BK * LDB;
+    __shared__ __attribute__((aligned(16))) float As[2][A_FLOATS];
+    __shared__ __attribute__((aligned(16))) float Bs[2][B_FLOATS];
 
     // Workgroup -> (reduction slice, tile).  Consecutive workgroup ids land on different XCDs (round robin over
     // 8), so give each XCD one contiguous run of work items: neighbours in M share their input halo and the
@@ -422,20 +431,18 @@ __global__ __launch_bounds__(NTHREADS) void igemm_kernel(const GemmParams p)
             float4 v = ra[i];
             if (MODE != MODE_FWD && amask) v = gate4(v, rg[i]);
             if (MODE == MODE_BWD_WEIGHT) {
-                *reinterpret_cast<float4 *>(&As[buf][t / A_F4 + A_RP * i][(t % A_F4) * 4]) = v;
+                *reinterpret_cast<float4 *>(&As[buf][(t / A_F4 + A_RP * i) * LDA + (t % A_F4) * 4]) = v;
                 if (want_db) { dbacc.x += v.x; dbacc.y += v.y; dbacc.z += v.z; dbacc.w += v.w; }
             } else {
-#pragma unroll
-                for (int e = 0; e < 4; ++e) As[buf][kq * 4 + e][row0 + RPP * i] = f4at(v, e);
+                *reinterpret_cast<float4 *>(&As[buf][(row0 + RPP * i) * LDK + kq * 4]) = v;
             }
         }
 #pragma unroll
         for (int i = 0; i < BV; ++i) {
             if (MODE == MODE_FWD) {
-#pragma unroll
-                for (int e = 0; e < 4; ++e) Bs[buf][kq * 4 + e][row0 + RPP * i] = f4at(rb[i], e);
+                *reinterpret_cast<float4 *>(&Bs[buf][(row0 + RPP * i) * LDK + kq * 4]) = rb[i];
             } else {
-                *reinterpret_cast<float4 *>(&Bs[buf][t / B_F4 + B_RP * i][(t % B_F4) * 4]) = rb[i];
+                *reinterpret_cast<float4 *>(&Bs[buf][(t / B_F4 + B_RP * i) * LDB + (t % B_F4) * 4]) = rb[i];
             }
         }
     };
@@ -463,26 +470,52 @@ __global__ __launch_bounds__(NTHREADS) void igemm_kernel(const GemmParams p)
         // Per k-step: (1) LDS reads of the NEXT k-step's operands, (2) this k-step's MFMAs, (3) one slice of the
         // next stage's global fetch (address arithmetic + load issue), which executes in the shadow of the MFMAs.
         // The scheduling barriers pin this order.
-        float av[2][TM], bv[2][TN];
+        // Operand registers for one reduction group (8 elements = 4 k-steps): row-major operands arrive as one float4
+        // per 32-row tile and group, reduction-major operands as one scalar per tile and k-step (double-buffered so that
+        // the LDS read of k-step ks+1 is in flight during the MFMAs of k-step ks).
+        float4 a4[2][TM], b4[2][TN];
+        float a1[2][TM], b1[2][TN];
+        auto read_group = [&](int gi, int slot) {
+            if (A_ROWK) {
 #pragma unroll
-        for (int i = 0; i < TM; ++i) av[0][i] = As[buf][lk][wave_m * WTM + i * 32 + lrow];
+                for (int i = 0; i < TM; ++i)
+                    a4[slot][i] = *reinterpret_cast<const float4 *>(&As[buf][(wave_m * WTM + i * 32 + lrow) * LDK + gi * 8 + lk * 4]);
+            }
+            if (B_ROWK) {
 #pragma unroll
-        for (int j = 0; j < TN; ++j) bv[0][j] = Bs[buf][lk][wave_n * WTN + j * 32 + lrow];
+                for (int j = 0; j < TN; ++j)
+                    b4[slot][j] = *reinterpret_cast<const float4 *>(&Bs[buf][(wave_n * WTN + j * 32 + lrow) * LDK + gi * 8 + lk * 4]);
+            }
+        };
+        // reduction row that lane half lk multiplies in k-step ks: pairs (8g+j, 8g+4+j) when a row-major operand fixes
+        // the order, (2ks, 2ks+1) otherwise
+        auto krow = [&](int ks) -> int { return (A_ROWK || B_ROWK) ? (ks >> 2) * 8 + lk * 4 + (ks & 3) : ks * 2 + lk; };
+        auto read_scalar = [&](int ks, int slot) {
+            if (!A_ROWK) {
+#pragma unroll
+                for (int i = 0; i < TM; ++i) a1[slot][i] = As[buf][krow(ks) * LDA + wave_m * WTM + i * 32 + lrow];
+            }
+            if (!B_ROWK) {
+#pragma unroll
+                for (int j = 0; j < TN; ++j) b1[slot][j] = Bs[buf][krow(ks) * LDB + wave_n * WTN + j * 32 + lrow];
+            }
+        };
+        read_group(0, 0);
+        read_scalar(0, 0);
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) {
-            const int cur = ks & 1, nxt = cur ^ 1;
-            if (ks + 1 < KS) {
-#pragma unroll
-                for (int i = 0; i < TM; ++i) av[nxt][i] = As[buf][(ks + 1) * 2 + lk][wave_m * WTM + i * 32 + lrow];
-#pragma unroll
-                for (int j = 0; j < TN; ++j) bv[nxt][j] = Bs[buf][(ks + 1) * 2 + lk][wave_n * WTN + j * 32 + lrow];
-            }
+            const int cur = ks & 1, nxt = cur ^ 1, gi = ks >> 2, e = ks & 3, gs = gi & 1;
+            if (e == 0 && (gi + 1) * 4 < KS) read_group(gi + 1, gs ^ 1);
+            if (ks + 1 < KS) read_scalar(ks + 1, nxt);
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int i = 0; i < TM; ++i)
 #pragma unroll
-                for (int j = 0; j < TN; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[cur][i], bv[cur][j], acc[i][j], 0, 0, 0);
+                for (int j = 0; j < TN; ++j) {
+                    const float av = A_ROWK ? f4at(a4[gs][i], e) : a1[cur][i];
+                    const float bv = B_ROWK ? f4at(b4[gs][j], e) : b1[cur][j];
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(av, bv, acc[i][j], 0, 0, 0);
+                }
             if (ks < AV) fetch_a(ch + 1, ks);
             else if (ks < AV + BV) fetch_b(ch + 1, ks - AV);
             __builtin_amdgcn_sched_barrier(0);
@@ -494,7 +527,7 @@ __global__ __launch_bounds__(NTHREADS) void igemm_kernel(const GemmParams p)
     if (MODE == MODE_BWD_WEIGHT && want_db) {
         // The A_RP threads t, t + A_F4, ... hold partial sums of the same 4 channels: add them in thread order
         // through LDS (the last stage barrier has passed, the tiles are free).
-        float *red = &As[0][0][0];
+        float *red = &As[0][0];
         *reinterpret_cast<float4 *>(&red[(t / A_F4) * LDA + (t % A_F4) * 4]) = dbacc;
         __syncthreads();
         if (t < BM && m0 + t < p.M) {
