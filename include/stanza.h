@@ -188,6 +188,24 @@ int stanza_ps_aggregate(int32_t n_tensors, const int64_t *host_numel, float *con
                         const float *const *host_grads, int32_t K, float scale, float lr, float momentum,
                         float weight_decay, void *ws, size_t ws_bytes, void *stream);
 
+/* ---- The same aggregation with the shards added in the order of the paper's all-reduce (Sec. 4.1.2, recursive
+ * doubling): in round i = 1, 2, ... worker j adds to its own partial sum the partial sum of worker j xor 2^(i-1), so
+ * after log2 K rounds every worker holds the balanced pairwise tree ((g_0+g_1)+(g_2+g_3))+((g_4+g_5)+(g_6+g_7))...
+ * Addition being commutative, every worker holds the same bits (the property the paper chose the schedule for),
+ * and on one GPU one tree gives them all.  When K is not a power of two, P = 2^floor(log2 K) workers take part: the
+ * surplus worker P + i first sends its gradient to worker i (i < K - P), which adds it to its own before round 1; the
+ * paper picks the surplus workers and their partners at random, this library takes the last K - P workers and
+ * partners them with the first K - P.  The final round that returns the result to the surplus workers is a copy.
+ * order: STANZA_SUM_INDEX_ORDER gives exactly stanza_ps_aggregate / stanza_ps_aggregate_planned.
+ * Errors and ownership as above; an unknown order is STANZA_EINVAL. */
+typedef enum { STANZA_SUM_INDEX_ORDER = 0, STANZA_SUM_RECURSIVE_DOUBLING = 1 } stanza_sum_order;
+int stanza_ps_aggregate_ordered_planned(int32_t order, int32_t n_tensors, const int64_t *host_numel, int32_t K, float scale,
+                                        float lr, float momentum, float weight_decay, const void *ws, size_t ws_bytes,
+                                        void *stream);
+int stanza_ps_aggregate_ordered(int32_t order, int32_t n_tensors, const int64_t *host_numel, float *const *host_w,
+                                float *const *host_v, const float *const *host_grads, int32_t K, float scale, float lr,
+                                float momentum, float weight_decay, void *ws, size_t ws_bytes, void *stream);
+
 /* ---- Performance model and node assignment (host arithmetic only; Sec. 4.2 and Sec. 7.1).  Times in seconds,
  * bandwidth in bit/s per node, every transferred value is 32 bits wide.
  *   rounds(n_c)          = log2 n_c when n_c is a power of two, floor(log2 n_c) + 2 otherwise (recursive doubling with

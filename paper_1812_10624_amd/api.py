@@ -24,7 +24,7 @@ EXPORTS = (
     "stanza_conv_bwd_weight", "stanza_pool_relu_fwd", "stanza_pool_relu_bwd", "stanza_add_relu_fwd",
     "stanza_add_relu_bwd", "stanza_gap_fwd", "stanza_gap_bwd", "stanza_cast_f32_to_bf16", "stanza_cast_bf16_to_f32",
     "stanza_fc_workspace_bytes", "stanza_fc_step", "stanza_ps_workspace_bytes", "stanza_ps_plan",
-    "stanza_ps_aggregate_planned", "stanza_ps_aggregate",
+    "stanza_ps_aggregate_planned", "stanza_ps_aggregate", "stanza_ps_aggregate_ordered_planned", "stanza_ps_aggregate_ordered",
     "stanza_model_allreduce_rounds", "stanza_model_stanza_time", "stanza_model_stanza_throughput", "stanza_model_assign",
     "stanza_model_ps_time", "stanza_model_ps_throughput",
 )
@@ -89,6 +89,8 @@ def load() -> C.CDLL:
     lib.stanza_ps_plan.argtypes = [i32, vp, vp, vp, vp, i32, vp, sz, vp]
     lib.stanza_ps_aggregate_planned.argtypes = [i32, vp, i32, f32, f32, f32, f32, vp, sz, vp]
     lib.stanza_ps_aggregate.argtypes = [i32, vp, vp, vp, vp, i32, f32, f32, f32, f32, vp, sz, vp]
+    lib.stanza_ps_aggregate_ordered_planned.argtypes = [i32, i32, vp, i32, f32, f32, f32, f32, vp, sz, vp]
+    lib.stanza_ps_aggregate_ordered.argtypes = [i32, i32, vp, vp, vp, vp, i32, f32, f32, f32, f32, vp, sz, vp]
     f64 = C.c_double
     lib.stanza_model_allreduce_rounds.restype = i32
     lib.stanza_model_allreduce_rounds.argtypes = [i32]
@@ -247,6 +249,23 @@ def stanza_ps_aggregate(w, v, grads, scale, lr, momentum, weight_decay, ws):
     p, n = _ws(ws)
     _check(load().stanza_ps_aggregate(nt, numel, pw, pv, pg, K, scale, lr, momentum, weight_decay, p, n, _stream()),
            "stanza_ps_aggregate")
+
+
+SUM_INDEX_ORDER, SUM_RECURSIVE_DOUBLING = 0, 1
+
+
+def stanza_ps_aggregate_ordered_planned(order, plan, scale, lr, momentum, weight_decay, ws):
+    nt, K, numel = plan
+    p, n = _ws(ws)
+    _check(load().stanza_ps_aggregate_ordered_planned(order, nt, numel, K, scale, lr, momentum, weight_decay, p, n, _stream()),
+           "stanza_ps_aggregate_ordered_planned")
+
+
+def stanza_ps_aggregate_ordered(order, w, v, grads, scale, lr, momentum, weight_decay, ws):
+    nt, K, numel, pw, pv, pg = _ps_args(w, v, grads)
+    p, n = _ws(ws)
+    _check(load().stanza_ps_aggregate_ordered(order, nt, numel, pw, pv, pg, K, scale, lr, momentum, weight_decay, p, n, _stream()),
+           "stanza_ps_aggregate_ordered")
 
 
 # ---- performance model (host arithmetic)

@@ -105,3 +105,6 @@ def test_fc_and_ps_errors(api):
     g_bad = (C.c_void_p * 6)(0x3000, 0x3000, 0x3004, 0x3000, 0x3000, 0x3000)
     assert lib.stanza_ps_plan(2, numel, w, w, g_bad, 3, p16, need, None) == -3
     assert lib.stanza_ps_aggregate_planned(2, numel, 3, 1.0, 0.1, 0.9, 0.0, None, need, None) == -2
+    assert lib.stanza_ps_aggregate_ordered_planned(7, 2, numel, 3, 1.0, 0.1, 0.9, 0.0, p16, need, None) == -1   # unknown order
+    assert lib.stanza_ps_aggregate_ordered_planned(1, 2, numel, 3, 1.0, 0.1, 0.9, 0.0, None, need, None) == -2
+    assert lib.stanza_ps_aggregate_ordered(9, 2, numel, w, w, g, 3, 1.0, 0.1, 0.9, 0.0, p16, need, None) == -1

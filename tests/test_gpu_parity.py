@@ -226,6 +226,46 @@ def test_ps_aggregate(api, o32, K):
         assert rel_err(host(gw[t]), w_ref[t]) < 1e-6, t
 
 
+@pytest.mark.parametrize("K", [1, 2, 3, 4, 5, 6, 8, 11, 16, 19])
+def test_ps_aggregate_recursive_doubling(api, K):
+    """Shards added in the order of the all-reduce of Sec. 4.1.2.  The sum itself is compared BIT-EXACT: with
+    momentum 0, weight decay 0, scale 1 the velocity written is the sum (0*v + (1*s + 0*w) is exact), and both sides
+    add float32 values in the same tree.  Then a full update at tolerance."""
+    from oracle import allreduce as oar
+    numels = [1000, 10, 4097, 4096 * 2 + 5, 4096, 3]
+    ws_, vs_, gs_ = wl_mod.gen_ps_case(numels, K, seed=23)
+    # make the order visible: large cancelling terms in some shards
+    for t in range(len(numels)):
+        for k in range(K):
+            gs_[t][k][::7] *= np.float32(1e4 * (-1) ** k)
+    gw, gv = [dev(a) for a in ws_], [dev(a) for a in vs_]
+    gg = [[dev(gs_[t][k]) for t in range(len(numels))] for k in range(K)]
+    ws = torch.empty(api.stanza_ps_workspace_bytes(len(numels), K), dtype=torch.uint8, device="cuda:0")
+    api.stanza_ps_aggregate_ordered(api.SUM_RECURSIVE_DOUBLING, gw, gv, gg, 1.0, 1.0, 0.0, 0.0, ws)
+    for t in range(len(numels)):
+        want = oar.recursive_doubling_allreduce(gs_[t])[0][0]
+        got = host(gv[t])
+        np.testing.assert_array_equal(got, want, err_msg=f"tensor {t}")
+        np.testing.assert_array_equal(host(gw[t]), ws_[t] - want)
+    # full update through the planned entry point from fresh state
+    gw, gv = [dev(a) for a in ws_], [dev(a) for a in vs_]
+    plan = api.stanza_ps_plan(gw, gv, gg, ws)
+    api.stanza_ps_aggregate_ordered_planned(api.SUM_RECURSIVE_DOUBLING, plan, 1.0 / K, 0.02, 0.9, 5e-4, ws)
+    for t in range(len(numels)):
+        w_ref, v_ref = ws_[t].copy(), vs_[t].copy()
+        oar.ps_aggregate_rd(w_ref, v_ref, gs_[t], 1.0 / K, 0.02, 0.9, 5e-4)
+        assert rel_err(host(gv[t]), v_ref) < 1e-5, t
+        assert rel_err(host(gw[t]), w_ref) < 1e-6, t
+    # index order through the same entry point equals stanza_ps_aggregate bit for bit
+    a_w, a_v = [dev(a) for a in ws_], [dev(a) for a in vs_]
+    b_w, b_v = [dev(a) for a in ws_], [dev(a) for a in vs_]
+    api.stanza_ps_aggregate_ordered(api.SUM_INDEX_ORDER, a_w, a_v, gg, 1.0, 0.01, 0.9, 5e-4, ws)
+    api.stanza_ps_aggregate(b_w, b_v, gg, 1.0, 0.01, 0.9, 5e-4, ws)
+    for t in range(len(numels)):
+        np.testing.assert_array_equal(host(a_w[t]), host(b_w[t]))
+        np.testing.assert_array_equal(host(a_v[t]), host(b_v[t]))
+
+
 def _gpu_params(params):
     return {n: (dev(w), dev(b)) for n, (w, b) in params.items()}
 
