@@ -24,7 +24,8 @@ def _setup(o, wl, seed, K, B, small_fc=None):
     return imgs, labels, cp, cm, fp, fm
 
 
-@pytest.mark.parametrize("name,K,B", [("tiny", 1, 2), ("tiny", 2, 2), ("tiny", 3, 1), ("tiny", 4, 1), ("minires", 2, 2), ("minires", 3, 1)])
+@pytest.mark.parametrize("name,K,B", [("tiny", 1, 2), ("tiny", 2, 2), ("tiny", 3, 1), ("tiny", 4, 1), ("minires", 2, 2), ("minires", 3, 1),
+                                        ("minimlp", 3, 2), ("minimlp", 2, 5)])
 def test_split_equals_monolithic(o64, name, K, B):
     wl = wl_mod.get_workload(name)
     imgs, labels, cp, cm, fp, fm = _setup(o64, wl, 3, K, B)
@@ -58,7 +59,7 @@ def _loss_only(o, wl, imgs, labels, cp, fp):
     return o.softmax_ce(a, labels)[0]
 
 
-@pytest.mark.parametrize("name", ["tiny", "minires"])
+@pytest.mark.parametrize("name", ["tiny", "minires", "minimlp"])
 def test_chain_gradients_match_finite_differences(o64, name):
     """Central differences of the mean loss over the global batch with respect to single conv and FC
     parameters, against the gradients the split step sums over workers."""
@@ -141,7 +142,9 @@ def test_workload_tables_match_printed_counts():
         assert abs(got - val) <= tol * val + (0 if tol else 0), (name, part, got, val)
     # exact counts of the five configurations, derived from their layer lists
     exact = {"tiny": (5088, 527114), "alexnet": (3747200, 58631144), "vgg16": (14714688, 123642856),
-             "resnet50": (23481472, 2049000)}
+             "resnet50": (23481472, 2049000),
+             # MLP of the paper's last table, 3072 inputs: front 3072-1024-1024, back 1024-4096-10
+             "mlp": (3072 * 1024 + 1024 + 1024 * 1024 + 1024, 1024 * 4096 + 4096 + 4096 * 10 + 10)}
     for name, pair in exact.items():
         assert wl_mod.count_params(wl_mod.get_workload(name)) == pair
     for name in wl_mod.WORKLOAD_NAMES:

@@ -149,6 +149,18 @@ def _mini_res_ops():
     return ops
 
 
+def _mlp_front_ops(widths):
+    """The front part of a layer-separated multilayer perceptron (Discussion, "Beyond CNNs"): fully connected
+    layers with ReLU, written as 1x1 convolutions over a 1x1 "image" whose channels are the input vector, so that
+    the front workers run through the same entry points as CONV workers."""
+    ops, cur = [], "x0"
+    for i, wdt in enumerate(widths, start=1):
+        ops.append(_conv(f"fc_front{i}", cur, f"h{i}", wdt, 1, 1, 0, relu=True))
+        cur = f"h{i}"
+    ops[-1]["dst"] = "feat"
+    return ops
+
+
 def get_workload(name: str) -> Workload:
     if name == "tiny":
         return Workload("tiny", K=2, B=4, image=(32, 32, 3), ops=_tiny_ops(), fc_dims=[2048, 256, 10])
@@ -164,10 +176,19 @@ def get_workload(name: str) -> Workload:
     if name == "minires":
         return Workload("minires", K=2, B=3, image=(33, 35, 3), ops=_mini_res_ops(),
                         fc_dims=[32, 7], notes="small residual stack for exhaustive parity")
+    if name == "mlp":
+        # 3 hidden layers of 1024, 1024, 4096 units on 3x32x32 inputs, separated after the second hidden layer;
+        # the largest row of the paper's table: total batch 1024, base learning rate 0.08, vanilla SGD
+        return Workload("mlp", K=8, B=128, image=(1, 1, 3072), ops=_mlp_front_ops([1024, 1024]),
+                        fc_dims=[1024, 4096, 10], lr=0.08, momentum=0.0,
+                        notes="layer-separated MLP: front workers 3072-1024-1024, back worker 1024-4096-10")
+    if name == "minimlp":
+        return Workload("minimlp", K=3, B=5, image=(1, 1, 52), ops=_mlp_front_ops([40, 24]),
+                        fc_dims=[24, 56, 10], lr=0.08, momentum=0.0, notes="small MLP for exhaustive parity")
     raise KeyError(name)
 
 
-WORKLOAD_NAMES = ("tiny", "alexnet", "vgg16", "resnet50", "minires")
+WORKLOAD_NAMES = ("tiny", "alexnet", "vgg16", "resnet50", "minires", "mlp", "minimlp")
 
 
 def _out_dim(h, win, stride, pad):
