@@ -97,7 +97,13 @@ static int launch_tile_bf16(GemmParams &p, int splits, hipStream_t st)
     p.tiles = p.tilesM * p.tilesN;
     p.splits = splits;
     dim3 grid((unsigned)(cdiv(p.tiles * splits, 8) * 8));
-    hipLaunchKernelGGL((igemm_bf16_kernel<MODE, BM, BN, WM, WN>), grid, dim3(NTHREADS), 0, st, p);
+    const ConvGeo &g = p.g;
+    // a stage that stays inside one filter tap: wavefront-uniform tap decode, no per-thread division in the main loop
+    const bool fast = (MODE == MODE_FWD && g.C % BKH == 0) || (MODE == MODE_BWD_DATA && g.K % BKH == 0 && g.sh == 1 && g.sw == 1);
+    if (MODE != MODE_BWD_WEIGHT && fast)
+        hipLaunchKernelGGL((igemm_bf16_kernel<MODE, BM, BN, WM, WN, MODE != MODE_BWD_WEIGHT>), grid, dim3(NTHREADS), 0, st, p);
+    else
+        hipLaunchKernelGGL((igemm_bf16_kernel<MODE, BM, BN, WM, WN, false>), grid, dim3(NTHREADS), 0, st, p);
     return launch_status();
 }
 
@@ -123,7 +129,12 @@ int launch_igemm_bf16(int mode, GemmParams &p, int splits, hipStream_t st)
     p.fd_howo = make_fastdiv(g.Ho * g.Wo);
     p.fd_wo = make_fastdiv(g.Wo);
     p.fd_rs = make_fastdiv(g.R * g.S);
-    if (g.R * g.S > 1 && ((mode == MODE_FWD && g.C % BKH == 0) || (mode == MODE_BWD_DATA && g.K % BKH == 0))) p.flags |= ORDER_TAP_MINOR;
+    // the gathered tensors are addressed with 32-bit byte offsets below 2 GiB (an offset of 2 GiB marks a masked lane)
+    const int64_t xb = (int64_t)g.N * g.H * g.W * g.C * 2, yb = (int64_t)g.N * g.Ho * g.Wo * g.K * 2, wb = (int64_t)g.K * g.R * g.S * g.C * 2;
+    const int64_t ab = mode == MODE_FWD ? xb : yb, bb = mode == MODE_BWD_WEIGHT ? xb : wb;
+    if (ab >= (int64_t(1) << 31) || bb >= (int64_t(1) << 31)) return STANZA_EUNSUPPORTED;
+    p.a_bytes = (uint32_t)ab;
+    p.b_bytes = (uint32_t)bb;
     switch (mode) {
     case MODE_FWD: return launch_mode_bf16<MODE_FWD>(p, 1, st);
     case MODE_BWD_DATA: return launch_mode_bf16<MODE_BWD_DATA>(p, 1, st);
@@ -263,7 +274,7 @@ extern "C" int stanza_conv_fwd(const stanza_conv_desc *desc, const void *x, cons
     if ((rc = check_dtype(desc))) return rc;
     const bool has_bias = desc->flags & STANZA_CONV_BIAS;
     if (!x || !w || !y || (has_bias && !bias)) return STANZA_ENULL;
-    if (!aligned16(x) || !aligned16(w) || !aligned16(y)) return STANZA_EALIGN;
+    if (!aligned16(x) || !aligned16(w) || !aligned16(y) || !aligned16(bias)) return STANZA_EALIGN;
     p.a = (const float *)x;
     p.b = (const float *)w;
     p.out = (float *)y;

@@ -2,19 +2,32 @@
 // GemmParams as igemm.h; see there for the index conventions).  x, w, y, dy, dx are bfloat16; products are
 // accumulated in float32 by v_mfma_f32_32x32x16_bf16; bias, filter gradients and bias gradients are float32.
 //
-// One MFMA lane supplies 8 consecutive reduction elements of one tile row, so both LDS tiles are stored
-// row-major with the reduction contiguous ([BM][BK+8] bf16, 80-byte rows: 16-byte operand reads of 8
-// consecutive rows cover all 32 banks).  Operands whose reduction is contiguous in memory go global -> register
-// -> LDS as 16-byte vectors; operands whose row index is contiguous (w in BWD_DATA, dy and x in BWD_WEIGHT)
-// are transposed element by element on the LDS store.
+// One MFMA lane supplies 8 consecutive reduction elements of one tile row.  Every operand goes global -> register
+// -> LDS as 16-byte vectors in the order it has in memory, and nothing is transposed element by element:
+//   * an operand whose reduction index is contiguous in memory (x and w in FWD, dy in BWD_DATA) is kept ROW-MAJOR
+//     in LDS, [rows][BKH+8], and a lane reads its 8 elements with one 16-byte read;
+//   * an operand whose row/column index is contiguous (w in BWD_DATA, dy and x in BWD_WEIGHT) is kept
+//     REDUCTION-MAJOR, [BKH][rows+32], and is read with the gfx950 LDS transpose read (ds_read_b64_tr_b16): within
+//     each group of 16 lanes, lane s points at 4 consecutive row elements of reduction row s/4, chunk s%4, and the
+//     hardware hands lane i the 4 reduction elements of row i.  Two such reads give the lane its 8 elements.
+//     (Lane layout checked on the device against a tile holding its own indices.)
+// Fetches are buffer loads (a masked lane gets an out-of-range offset and the hardware returns zero), issued two
+// stages ahead of their use: the registers of stage s+2 are loaded while stage s is multiplied and stage s+1 is
+// written to LDS.  bf16 outputs leave through LDS so that every global store is a 16-byte vector of a full row
+// segment; for that the MFMA operands are swapped (the accumulators hold the transposed tile, 4 consecutive output
+// columns per lane).
 #pragma once
 #include "igemm.h"
+#include <type_traits>
 
 namespace stanza {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-constexpr int BKH = 32;        // reduction depth of one LDS stage (bf16 elements)
-constexpr int LDKH = BKH + 8;  // LDS row stride in elements
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef short s16x8 __attribute__((ext_vector_type(8)));
+constexpr int BKH = 32;        // reduction depth of one LDS stage (bf16 elements); also the filter-gradient slice unit
+constexpr int KPAD = 32;       // row pad of a reduction-major tile: row stride = 64 bytes mod 256, so the four reduction rows
+                               // a 16-lane group reads land on four different 64-byte bank groups
 
 __device__ __forceinline__ float bf16_to_f32(uint16_t h) { return __uint_as_float((uint32_t)h << 16); }
 __device__ __forceinline__ uint16_t f32_to_bf16(float f)
@@ -24,9 +37,9 @@ __device__ __forceinline__ uint16_t f32_to_bf16(float f)
     u += 0x7fffu + ((u >> 16) & 1u);
     return (uint16_t)(u >> 16);
 }
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) { return (uint32_t)f32_to_bf16(lo) | ((uint32_t)f32_to_bf16(hi) << 16); }
 __device__ __forceinline__ bool bf16_pos(uint16_t h) { return h != 0 && !(h & 0x8000u); }   // h > 0 (finite inputs)
 __device__ __forceinline__ uint16_t h8at(const uint4 &v, int e) { return reinterpret_cast<const uint16_t *>(&v)[e]; }
-__device__ __forceinline__ uint4 ldg16(const uint16_t *p) { return *reinterpret_cast<const uint4 *>(p); }
 // keep element e of v where the matching element of m is > 0
 __device__ __forceinline__ uint4 gate8(uint4 v, uint4 m)
 {
@@ -40,19 +53,44 @@ __device__ __forceinline__ uint4 gate8(uint4 v, uint4 m)
     }
     return v;
 }
+__device__ __forceinline__ uint4 bload16(__amdgpu_buffer_rsrc_t r, uint32_t byte_off)
+{
+    return __builtin_bit_cast(uint4, __builtin_amdgcn_raw_buffer_load_b128(r, byte_off, 0, 0));
+}
+// 4 consecutive reduction elements of this lane's row out of a reduction-major LDS tile (see the header comment)
+__device__ __forceinline__ s16x4 lds_tr4(const uint16_t *p)
+{
+    return __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3))) *)(p));
+}
 
-template <int MODE, int BM, int BN, int WM, int WN>
-__global__ __launch_bounds__(NTHREADS) void igemm_bf16_kernel(const GemmParams p)
+template <int MODE, int BM, int BN, int WM, int WN, bool FAST>
+__global__ __launch_bounds__(NTHREADS, 2) void igemm_bf16_kernel(const GemmParams p)
 {
     static_assert(WM * WN == 4, "four wavefronts per workgroup");
     static_assert(BM % 64 == 0 && BN % 64 == 0, "loader granularity");
     constexpr int WTM = BM / WM, WTN = BN / WN;
+    static_assert(WTM % 32 == 0 && WTN % 32 == 0 && WTM <= 128, "MFMA granularity");
     constexpr int TM = WTM / 32, TN = WTN / 32;
-    constexpr int AV = BM / 64, BV = BN / 64;            // 16-byte vectors (8 elements) per thread per stage
     constexpr int KS = BKH / 16;                         // MFMA k-steps per stage
+    constexpr bool A_KMAJ = MODE == MODE_BWD_WEIGHT, B_KMAJ = MODE != MODE_FWD;
+    constexpr bool SWAP = MODE != MODE_BWD_WEIGHT;       // bf16 output: accumulate the transposed tile
+    constexpr int LDR = BKH + 8;                         // row-major tile: elements per row (80 bytes)
+    constexpr int LDAK = BM + KPAD, LDBK = BN + KPAD;    // reduction-major tiles: elements per reduction row
+    constexpr int A_ELEMS = A_KMAJ ? BKH * LDAK : BM * LDR;
+    constexpr int B_ELEMS = B_KMAJ ? BKH * LDBK : BN * LDR;
+    constexpr int STAGE = A_ELEMS + B_ELEMS;
+    constexpr int CROWS = BM < 128 ? BM : 128;           // output rows staged per epilogue pass
+    constexpr int LDC = BN + 8;
+    constexpr int C_ELEMS = SWAP ? CROWS * LDC : 0;
+    constexpr int SMEM = 2 * STAGE > C_ELEMS ? 2 * STAGE : C_ELEMS;
+    __shared__ __attribute__((aligned(16))) uint16_t smem[SMEM];
 
-    __shared__ __attribute__((aligned(16))) uint16_t As[2][BM][LDKH];
-    __shared__ __attribute__((aligned(16))) uint16_t Bs[2][BN][LDKH];
+    // 16-byte vectors per thread per stage and their thread mapping
+    constexpr int KQ = BKH / 8, RPP = NTHREADS / KQ;     // row-major fetch: vector kq along the stage, rows row0 + RPP*i
+    constexpr int A_F8 = BM / 8, A_RP = NTHREADS / A_F8; // reduction-major fetch: vector c8 along the tile edge, rows kr0 + RP*i
+    constexpr int B_F8 = BN / 8, B_RP = NTHREADS / B_F8;
+    constexpr int AV = BM * BKH / 8 / NTHREADS, BV = BN * BKH / 8 / NTHREADS;
+    static_assert(AV >= 1 && BV >= 1, "tile too small for the loader");
 
     const int per_xcd = gridDim.x >> 3;
     const int L = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
@@ -62,9 +100,6 @@ __global__ __launch_bounds__(NTHREADS) void igemm_bf16_kernel(const GemmParams p
     const int m0 = tile_m * BM, n0 = tile_n * BN;
 
     const ConvGeo &g = p.g;
-    const uint16_t *pa = reinterpret_cast<const uint16_t *>(p.a);
-    const uint16_t *pb = reinterpret_cast<const uint16_t *>(p.b);
-    const uint16_t *pmask = reinterpret_cast<const uint16_t *>(p.amask);
     const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
     const int wave_m = wave / WN, wave_n = wave % WN;
 
@@ -76,19 +111,14 @@ __global__ __launch_bounds__(NTHREADS) void igemm_bf16_kernel(const GemmParams p
     const int nchunks = (kend - kbeg + BKH - 1) / BKH;
     const bool amask = (p.flags & LOAD_AMASK) != 0;
 
-    // reduction-contiguous fetch: thread -> vector kq (8 elements) of 4 along the stage, rows row0 + 64*i
-    const int kq = t & 3, row0 = t >> 2;
-    // row-contiguous fetch: thread -> vector c8 along the tile edge, reduction rows kr0 + RP*i
-    constexpr int A_F8 = BM / 8, A_RP = NTHREADS / A_F8;
-    constexpr int B_F8 = BN / 8, B_RP = NTHREADS / B_F8;
-
-    int a_hb[AV], a_wb[AV], a_base[AV];
+    const int kq = t % KQ, row0 = t / KQ;
+    int a_hb[AV], a_wb[AV], a_base[AV], a_row[AV], b_row[BV];
     int bw_r = 0, bw_s = 0, bw_c = 0;
     if (MODE == MODE_FWD) {
         const int HoWo = g.Ho * g.Wo;
 #pragma unroll
         for (int i = 0; i < AV; ++i) {
-            const int m = m0 + row0 + 64 * i;
+            const int m = m0 + row0 + RPP * i;
             if (m < p.M) {
                 const int n = m / HoWo, pq = m - n * HoWo, pp = pq / g.Wo, q = pq - pp * g.Wo;
                 a_hb[i] = pp * g.sh - g.ph;
@@ -97,12 +127,15 @@ __global__ __launch_bounds__(NTHREADS) void igemm_bf16_kernel(const GemmParams p
             } else {
                 a_hb[i] = -(1 << 28); a_wb[i] = 0; a_base[i] = 0;
             }
+            a_row[i] = m < p.M ? a_base[i] + (a_hb[i] * g.W + a_wb[i]) * g.C + kq * 8 : 0;
         }
+#pragma unroll
+        for (int i = 0; i < BV; ++i) b_row[i] = (n0 + row0 + RPP * i) * p.Kd + kq * 8;
     } else if (MODE == MODE_BWD_DATA) {
         const int HW = g.H * g.W;
 #pragma unroll
         for (int i = 0; i < AV; ++i) {
-            const int m = m0 + row0 + 64 * i;
+            const int m = m0 + row0 + RPP * i;
             if (m < p.M) {
                 const int n = m / HW, hw = m - n * HW, h = hw / g.W, w = hw - h * g.W;
                 a_hb[i] = h + g.ph;
@@ -111,120 +144,154 @@ __global__ __launch_bounds__(NTHREADS) void igemm_bf16_kernel(const GemmParams p
             } else {
                 a_hb[i] = -(1 << 28); a_wb[i] = 0; a_base[i] = 0;
             }
+            a_row[i] = m < p.M ? a_base[i] + (a_hb[i] * g.Wo + a_wb[i]) * g.K + kq * 8 : 0;   // unit stride only (FAST)
         }
+#pragma unroll
+        for (int i = 0; i < BV; ++i)   // w[k][r][s][c] at k = this thread's reduction row, tap (0,0), its 8 columns
+            b_row[i] = (t / B_F8 + B_RP * i) * (g.R * g.S * g.C) + n0 + (t % B_F8) * 8;
     } else {
         const int j = n0 + (t % B_F8) * 8;           // C % 8 == 0: the 8 columns share one tap
         bw_c = j % g.C;
         const int rs = j / g.C;
         bw_s = rs % g.S;
-        bw_r = rs / g.S;
+        bw_r = rs / g.S;                             // >= R when j >= Nn: the column predicate covers it
+#pragma unroll
+        for (int i = 0; i < AV; ++i) { a_hb[i] = a_wb[i] = a_base[i] = a_row[i] = 0; }
+#pragma unroll
+        for (int i = 0; i < BV; ++i) b_row[i] = 0;
     }
 
-    const bool tap_minor = MODE != MODE_BWD_WEIGHT && (p.flags & ORDER_TAP_MINOR);
-    auto stage_k = [&](int ch) -> int {
-        if (!tap_minor) return kbeg + ch * BKH;
-        const int cblk = fdiv(ch, p.fd_rs), tap = ch - cblk * (g.R * g.S);
-        return tap * (MODE == MODE_FWD ? g.C : g.K) + cblk * BKH;
-    };
+    const __amdgpu_buffer_rsrc_t rsrc_a = make_rsrc(p.a, p.a_bytes);
+    const __amdgpu_buffer_rsrc_t rsrc_g = make_rsrc(p.amask ? p.amask : p.a, p.a_bytes);
+    const __amdgpu_buffer_rsrc_t rsrc_b = make_rsrc(p.b, p.b_bytes);
 
-    uint4 ra[AV], rb[BV], rg[AV];
-    unsigned oka = 0, okb = 0;
+    // two register sets: set (s & 1) holds stage s from its fetch until it is written to LDS
+    uint4 ra[2][AV], rb[2][BV], rg[2][AV];
     const bool want_db = MODE == MODE_BWD_WEIGHT && (p.flags & EPI_DBIAS) && tile_n == 0;
     float dbacc[8];
 #pragma unroll
     for (int e = 0; e < 8; ++e) dbacc[e] = 0.f;
 
-    auto fetch_a = [&](int ch, int i) {
-        const int kchunk = stage_k(ch);
-        int off;
-        bool ok;
-        if (MODE == MODE_FWD || MODE == MODE_BWD_DATA) {
-            const int CC = (MODE == MODE_FWD) ? g.C : g.K;
-            const int kk = kchunk + kq * 8;
-            const int rs = fdiv(kk, MODE == MODE_FWD ? p.fd_c : p.fd_k), cc = kk - rs * CC;
-            const int ar = fdiv(rs, p.fd_s), as = rs - ar * g.S;
-            if (MODE == MODE_FWD) {
-                const int h = a_hb[i] + ar, w = a_wb[i] + as;
-                ok = kk < p.Kd && (unsigned)h < (unsigned)g.H && (unsigned)w < (unsigned)g.W;
-                off = a_base[i] + (h * g.W + w) * g.C + cc;
-            } else {
-                int pp, q;
-                ok = strided_src(a_hb[i] - ar, g.sh, g.Ho, pp);
-                ok = strided_src(a_wb[i] - as, g.sw, g.Wo, q) && ok && kk < p.Kd;
-                off = a_base[i] + (pp * g.Wo + q) * g.K + cc;
+    // Issue the global loads of stage `ch` into register set `set`.  Stages past the end are fetched fully masked.
+    auto fetch = [&](int ch, auto set_c) {
+        constexpr int set = decltype(set_c)::value;
+        const bool kok = ch < nchunks;
+        if (FAST) {
+            // channel-block-major, tap-minor visiting order: the taps of one channel block re-read the same image rows
+            const int cblk = fdiv(ch, p.fd_rs), tap = ch - cblk * (g.R * g.S);
+            const int ar = fdiv(tap, p.fd_s), as = tap - ar * g.S;
+#pragma unroll
+            for (int i = 0; i < AV; ++i) {
+                int off;
+                bool ok;
+                if (MODE == MODE_FWD) {
+                    ok = kok && (unsigned)(a_hb[i] + ar) < (unsigned)g.H && (unsigned)(a_wb[i] + as) < (unsigned)g.W;
+                    off = a_row[i] + ((ar * g.W + as) * g.C + cblk * BKH);
+                } else {
+                    ok = kok && (unsigned)(a_hb[i] - ar) < (unsigned)g.Ho && (unsigned)(a_wb[i] - as) < (unsigned)g.Wo;
+                    off = a_row[i] + (cblk * BKH - (ar * g.Wo + as) * g.K);
+                }
+                const uint32_t bo = ok ? (uint32_t)off * 2u : OOB_OFF;
+                ra[set][i] = bload16(rsrc_a, bo);
+                if (MODE == MODE_BWD_DATA && amask) rg[set][i] = bload16(rsrc_g, bo);
             }
-        } else {
-            const int col = m0 + (t % A_F8) * 8;
-            const int pix = kchunk + t / A_F8 + A_RP * i;
-            ok = pix < kend && col < p.M;
-            off = pix * g.K + col;
+#pragma unroll
+            for (int i = 0; i < BV; ++i) {
+                bool ok = kok;
+                int off;
+                if (MODE == MODE_FWD) {
+                    ok = ok && n0 + row0 + RPP * i < p.Nn;
+                    off = b_row[i] + (tap * g.C + cblk * BKH);
+                } else {
+                    ok = ok && n0 + (t % B_F8) * 8 < p.Nn;
+                    off = b_row[i] + (cblk * BKH * (g.R * g.S) + tap) * g.C;
+                }
+                rb[set][i] = bload16(rsrc_b, ok ? (uint32_t)off * 2u : OOB_OFF);
+            }
+            return;
         }
-        off = ok ? off : 0;
-        ra[i] = ldg16(pa + off);
-        if (MODE != MODE_FWD && amask) rg[i] = ldg16(pmask + off);
-        oka |= (unsigned)ok << i;
-    };
-
-    auto fetch_b = [&](int ch, int i) {
-        const int kchunk = stage_k(ch);
-        int off;
-        bool ok;
-        if (MODE == MODE_FWD) {
-            const int j = n0 + row0 + 64 * i;
-            const int kk = kchunk + kq * 8;
-            ok = j < p.Nn && kk < p.Kd;
-            off = j * p.Kd + kk;
-        } else if (MODE == MODE_BWD_DATA) {
-            const int col = n0 + (t % B_F8) * 8;
-            const int kk = kchunk + t / B_F8 + B_RP * i;
-            const int rs = fdiv(kk, p.fd_k), bk = kk - rs * g.K;
-            const int br = fdiv(rs, p.fd_s), bs = rs - br * g.S;
-            ok = kk < p.Kd && col < p.Nn;
-            off = ((bk * g.R + br) * g.S + bs) * g.C + col;
-        } else {
-            const int col = n0 + (t % B_F8) * 8;
-            const int pix = kchunk + t / B_F8 + B_RP * i;
-            const int img = fdiv(pix, p.fd_howo), pq = pix - img * (g.Ho * g.Wo);
-            const int pp = fdiv(pq, p.fd_wo), q = pq - pp * g.Wo;
-            const int h = pp * g.sh - g.ph + bw_r, w = q * g.sw - g.pw + bw_s;
-            ok = pix < kend && col < p.Nn && (unsigned)h < (unsigned)g.H && (unsigned)w < (unsigned)g.W;
-            off = ((img * g.H + h) * g.W + w) * g.C + bw_c;
-        }
-        rb[i] = ldg16(pb + (ok ? off : 0));
-        okb |= (unsigned)ok << i;
-    };
-
-    auto stash = [&](int buf) {
+        const int kchunk = kbeg + ch * BKH;
 #pragma unroll
         for (int i = 0; i < AV; ++i) {
-            uint4 v = ra[i];
-            if (MODE != MODE_FWD && amask) v = gate8(v, rg[i]);
-            if (!((oka >> i) & 1u)) v = make_uint4(0u, 0u, 0u, 0u);
-            if (MODE == MODE_BWD_WEIGHT) {
-                const int kr = t / A_F8 + A_RP * i, c8 = (t % A_F8) * 8;
-#pragma unroll
-                for (int e = 0; e < 8; ++e) {
-                    As[buf][c8 + e][kr] = h8at(v, e);
-                    if (want_db) dbacc[e] += bf16_to_f32(h8at(v, e));
+            int off;
+            bool ok;
+            if (MODE == MODE_FWD || MODE == MODE_BWD_DATA) {
+                const int CC = (MODE == MODE_FWD) ? g.C : g.K;
+                const int kk = kchunk + kq * 8;
+                const int rs = fdiv(kk, MODE == MODE_FWD ? p.fd_c : p.fd_k), cc = kk - rs * CC;
+                const int ar = fdiv(rs, p.fd_s), as = rs - ar * g.S;
+                if (MODE == MODE_FWD) {
+                    const int h = a_hb[i] + ar, w = a_wb[i] + as;
+                    ok = kk < p.Kd && (unsigned)h < (unsigned)g.H && (unsigned)w < (unsigned)g.W;
+                    off = a_base[i] + (h * g.W + w) * g.C + cc;
+                } else {
+                    int pp, q;
+                    ok = strided_src(a_hb[i] - ar, g.sh, g.Ho, pp);
+                    ok = strided_src(a_wb[i] - as, g.sw, g.Wo, q) && ok && kk < p.Kd;
+                    off = a_base[i] + (pp * g.Wo + q) * g.K + cc;
                 }
             } else {
-                *reinterpret_cast<uint4 *>(&As[buf][row0 + 64 * i][kq * 8]) = v;
+                const int col = m0 + (t % A_F8) * 8;
+                const int pix = kchunk + t / A_F8 + A_RP * i;
+                ok = pix < kend && col < p.M;
+                off = pix * g.K + col;
+            }
+            const uint32_t bo = ok ? (uint32_t)off * 2u : OOB_OFF;
+            ra[set][i] = bload16(rsrc_a, bo);
+            if (MODE != MODE_FWD && amask) rg[set][i] = bload16(rsrc_g, bo);
+        }
+#pragma unroll
+        for (int i = 0; i < BV; ++i) {
+            int off;
+            bool ok;
+            if (MODE == MODE_FWD) {
+                const int j = n0 + row0 + RPP * i;
+                const int kk = kchunk + kq * 8;
+                ok = j < p.Nn && kk < p.Kd;
+                off = j * p.Kd + kk;
+            } else if (MODE == MODE_BWD_DATA) {
+                const int col = n0 + (t % B_F8) * 8;
+                const int kk = kchunk + t / B_F8 + B_RP * i;
+                const int rs = fdiv(kk, p.fd_k), bk = kk - rs * g.K;
+                const int br = fdiv(rs, p.fd_s), bs = rs - br * g.S;
+                ok = kk < p.Kd && col < p.Nn;
+                off = ((bk * g.R + br) * g.S + bs) * g.C + col;
+            } else {
+                const int col = n0 + (t % B_F8) * 8;
+                const int pix = kchunk + t / B_F8 + B_RP * i;
+                const int img = fdiv(pix, p.fd_howo), pq = pix - img * (g.Ho * g.Wo);
+                const int pp = fdiv(pq, p.fd_wo), q = pq - pp * g.Wo;
+                const int h = pp * g.sh - g.ph + bw_r, w = q * g.sw - g.pw + bw_s;
+                ok = pix < kend && col < p.Nn && (unsigned)h < (unsigned)g.H && (unsigned)w < (unsigned)g.W;
+                off = ((img * g.H + h) * g.W + w) * g.C + bw_c;
+            }
+            rb[set][i] = bload16(rsrc_b, ok ? (uint32_t)off * 2u : OOB_OFF);
+        }
+    };
+
+    // Gate and write register set `set` into LDS buffer `buf`.
+    auto stash = [&](auto set_c, int buf) {
+        constexpr int set = decltype(set_c)::value;
+        uint16_t *As = smem + buf * STAGE, *Bs = As + A_ELEMS;
+#pragma unroll
+        for (int i = 0; i < AV; ++i) {
+            uint4 v = ra[set][i];
+            if (MODE != MODE_FWD && amask) v = gate8(v, rg[set][i]);
+            if (A_KMAJ) {
+                *reinterpret_cast<uint4 *>(&As[(t / A_F8 + A_RP * i) * LDAK + (t % A_F8) * 8]) = v;
+                if (want_db) {
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) dbacc[e] += bf16_to_f32(h8at(v, e));
+                }
+            } else {
+                *reinterpret_cast<uint4 *>(&As[(row0 + RPP * i) * LDR + kq * 8]) = v;
             }
         }
 #pragma unroll
         for (int i = 0; i < BV; ++i) {
-            uint4 v = rb[i];
-            if (!((okb >> i) & 1u)) v = make_uint4(0u, 0u, 0u, 0u);
-            if (MODE == MODE_FWD) {
-                *reinterpret_cast<uint4 *>(&Bs[buf][row0 + 64 * i][kq * 8]) = v;
-            } else {
-                const int kr = t / B_F8 + B_RP * i, c8 = (t % B_F8) * 8;
-#pragma unroll
-                for (int e = 0; e < 8; ++e) Bs[buf][c8 + e][kr] = h8at(v, e);
-            }
+            if (B_KMAJ) *reinterpret_cast<uint4 *>(&Bs[(t / B_F8 + B_RP * i) * LDBK + (t % B_F8) * 8]) = rb[set][i];
+            else *reinterpret_cast<uint4 *>(&Bs[(row0 + RPP * i) * LDR + kq * 8]) = rb[set][i];
         }
-        oka = 0;
-        okb = 0;
     };
 
     f32x16 acc[TM][TN];
@@ -235,42 +302,67 @@ __global__ __launch_bounds__(NTHREADS) void igemm_bf16_kernel(const GemmParams p
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-#pragma unroll
-    for (int i = 0; i < AV; ++i) fetch_a(0, i);
-#pragma unroll
-    for (int i = 0; i < BV; ++i) fetch_b(0, i);
-    stash(0);
-    __syncthreads();
-
     const int lrow = lane & 31, lk = lane >> 5;
-    for (int ch = 0; ch < nchunks; ++ch) {
-        const int buf = ch & 1;
-#pragma unroll
-        for (int i = 0; i < AV; ++i) fetch_a(ch + 1, i);
-#pragma unroll
-        for (int i = 0; i < BV; ++i) fetch_b(ch + 1, i);
+    // transpose-read lane roles: 16-lane group G covers tile rows 16*(G&1).. and reduction rows 8*(G>>1)..
+    const int tr_m = 16 * ((lane >> 4) & 1) + 4 * (lane & 3), tr_k = 8 * (lane >> 5) + ((lane >> 2) & 3);
+
+    auto compute = [&](int buf) {
+        const uint16_t *As = smem + buf * STAGE, *Bs = As + A_ELEMS;
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) {
             bf16x8 av[TM], bv[TN];
 #pragma unroll
-            for (int i = 0; i < TM; ++i)
-                av[i] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4 *>(&As[buf][wave_m * WTM + i * 32 + lrow][ks * 16 + lk * 8]));
+            for (int i = 0; i < TM; ++i) {
+                if (A_KMAJ) {
+                    const uint16_t *q = &As[(ks * 16 + tr_k) * LDAK + wave_m * WTM + i * 32 + tr_m];
+                    const s16x4 lo = lds_tr4(q), hi = lds_tr4(q + 4 * LDAK);
+                    av[i] = __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+                } else {
+                    av[i] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4 *>(&As[(wave_m * WTM + i * 32 + lrow) * LDR + ks * 16 + lk * 8]));
+                }
+            }
 #pragma unroll
-            for (int j = 0; j < TN; ++j)
-                bv[j] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4 *>(&Bs[buf][wave_n * WTN + j * 32 + lrow][ks * 16 + lk * 8]));
+            for (int j = 0; j < TN; ++j) {
+                if (B_KMAJ) {
+                    const uint16_t *q = &Bs[(ks * 16 + tr_k) * LDBK + wave_n * WTN + j * 32 + tr_m];
+                    const s16x4 lo = lds_tr4(q), hi = lds_tr4(q + 4 * LDBK);
+                    bv[j] = __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+                } else {
+                    bv[j] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4 *>(&Bs[(wave_n * WTN + j * 32 + lrow) * LDR + ks * 16 + lk * 8]));
+                }
+            }
 #pragma unroll
             for (int i = 0; i < TM; ++i)
 #pragma unroll
                 for (int j = 0; j < TN; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av[i], bv[j], acc[i][j], 0, 0, 0);
+                    acc[i][j] = SWAP ? __builtin_amdgcn_mfma_f32_32x32x16_bf16(bv[j], av[i], acc[i][j], 0, 0, 0)
+                                     : __builtin_amdgcn_mfma_f32_32x32x16_bf16(av[i], bv[j], acc[i][j], 0, 0, 0);
         }
-        stash(buf ^ 1);
+    };
+
+    constexpr std::integral_constant<int, 0> S0{};
+    constexpr std::integral_constant<int, 1> S1{};
+    fetch(0, S0);
+    stash(S0, 0);
+    fetch(1, S1);
+    __syncthreads();
+    for (int ch = 0; ch < nchunks; ch += 2) {
+        fetch(ch + 2, S0);
+        compute(0);
+        stash(S1, 1);
+        __syncthreads();
+        if (ch + 1 >= nchunks) break;
+        fetch(ch + 3, S1);
+        compute(1);
+        stash(S0, 0);
         __syncthreads();
     }
 
     if (MODE == MODE_BWD_WEIGHT && want_db) {
         // threads t, t + A_F8, ... hold partial sums of the same 8 channels: add them in thread order through LDS
-        float *red = reinterpret_cast<float *>(&As[0][0][0]);
+        __syncthreads();
+        float *red = reinterpret_cast<float *>(smem);
+        static_assert(A_RP * BM * 4 <= SMEM * 2, "bias-gradient scratch fits in the stage buffers");
 #pragma unroll
         for (int e = 0; e < 8; ++e) red[(t / A_F8) * BM + (t % A_F8) * 8 + e] = dbacc[e];
         __syncthreads();
@@ -282,36 +374,77 @@ __global__ __launch_bounds__(NTHREADS) void igemm_bf16_kernel(const GemmParams p
         }
     }
 
-    // epilogue: accumulator register r of lane l is row 8*(r/4) + 4*(l/32) + r%4, column l%32 of its 32x32 tile
-    uint16_t *outh = reinterpret_cast<uint16_t *>(p.out);
-    const uint16_t *xm = reinterpret_cast<const uint16_t *>(p.xmask);
-    const size_t split_off = (MODE == MODE_BWD_WEIGHT) ? (size_t)split * p.M * p.Nn : 0;
+    if (!SWAP) {
+        // float32 tile (filter gradient or a reduction slice of it): register r of lane l is row 8*(r/4) + 4*(l/32) + r%4,
+        // column l%32 of its 32x32 tile
+        const size_t split_off = (size_t)split * p.M * p.Nn;
 #pragma unroll
-    for (int j = 0; j < TN; ++j) {
-        const int col = n0 + wave_n * WTN + j * 32 + lrow;
-        if (col >= p.Nn) continue;
-        float bias = 0.f;
-        if (MODE == MODE_FWD && (p.flags & EPI_BIAS)) bias = p.bias[col];
+        for (int j = 0; j < TN; ++j) {
+            const int col = n0 + wave_n * WTN + j * 32 + lrow;
+            if (col >= p.Nn) continue;
 #pragma unroll
-        for (int i = 0; i < TM; ++i) {
+            for (int i = 0; i < TM; ++i) {
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int row = m0 + wave_m * WTM + i * 32 + 8 * (r >> 2) + 4 * lk + (r & 3);
-                if (row >= p.M) continue;
-                const size_t o = (size_t)row * p.Nn + col;
-                float v = acc[i][j][r];
-                if (MODE == MODE_FWD) {
-                    v += bias;
-                    if (p.flags & EPI_RELU) v = fmaxf(v, 0.f);
-                    outh[o] = f32_to_bf16(v);
-                } else if (MODE == MODE_BWD_DATA) {
-                    if (p.flags & EPI_ACCUM) v += bf16_to_f32(outh[o]);
-                    if (p.flags & EPI_XMASK) v = bf16_pos(xm[o]) ? v : 0.f;
-                    outh[o] = f32_to_bf16(v);
-                } else {
-                    p.out[split_off + o] = v;
+                for (int r = 0; r < 16; ++r) {
+                    const int row = m0 + wave_m * WTM + i * 32 + 8 * (r >> 2) + 4 * lk + (r & 3);
+                    if (row < p.M) p.out[split_off + (size_t)row * p.Nn + col] = acc[i][j][r];
                 }
             }
+        }
+        return;
+    }
+
+    // bf16 tile.  Operands were swapped, so register r of lane l is output row l%32, column 8*(r/4) + 4*(l/32) + r%4 of its
+    // 32x32 tile: 4 consecutive columns per register quad.  Bias and ReLU are applied here, the tile is staged in LDS
+    // (CROWS rows at a time), and read back as 16-byte row vectors for the accumulate / mask / store.
+    uint16_t *outh = reinterpret_cast<uint16_t *>(p.out);
+    const uint16_t *xm = reinterpret_cast<const uint16_t *>(p.xmask);
+    constexpr int CH8 = BN / 8, ROWS_PER_PASS = NTHREADS / CH8;
+#pragma unroll
+    for (int half = 0; half < BM / CROWS; ++half) {
+        __syncthreads();
+        if ((wave_m * WTM) / CROWS == half) {
+#pragma unroll
+            for (int j = 0; j < TN; ++j) {
+#pragma unroll
+                for (int q4 = 0; q4 < 4; ++q4) {
+                    const int col_l = wave_n * WTN + j * 32 + 8 * q4 + 4 * lk;
+                    float4 bias = zero4();
+                    if (MODE == MODE_FWD && (p.flags & EPI_BIAS) && n0 + col_l < p.Nn) bias = ldg4(p.bias + n0 + col_l);
+#pragma unroll
+                    for (int i = 0; i < TM; ++i) {
+                        const int row_l = wave_m * WTM + i * 32 + lrow - half * CROWS;
+                        float v0 = acc[i][j][4 * q4 + 0] + bias.x, v1 = acc[i][j][4 * q4 + 1] + bias.y;
+                        float v2 = acc[i][j][4 * q4 + 2] + bias.z, v3 = acc[i][j][4 * q4 + 3] + bias.w;
+                        if (MODE == MODE_FWD && (p.flags & EPI_RELU)) {
+                            v0 = fmaxf(v0, 0.f); v1 = fmaxf(v1, 0.f); v2 = fmaxf(v2, 0.f); v3 = fmaxf(v3, 0.f);
+                        }
+                        if (MODE == MODE_BWD_DATA && (p.flags & EPI_ACCUM)) {
+                            // residual joins only: the previous gradient is added before the one rounding to bf16
+                            const int row = m0 + wave_m * WTM + i * 32 + lrow;
+                            if (row < p.M && n0 + col_l < p.Nn) {
+                                const uint2 old = *reinterpret_cast<const uint2 *>(outh + (size_t)row * p.Nn + n0 + col_l);
+                                v0 += bf16_to_f32((uint16_t)(old.x & 0xffffu)); v1 += bf16_to_f32((uint16_t)(old.x >> 16));
+                                v2 += bf16_to_f32((uint16_t)(old.y & 0xffffu)); v3 += bf16_to_f32((uint16_t)(old.y >> 16));
+                            }
+                        }
+                        *reinterpret_cast<uint2 *>(&smem[row_l * LDC + col_l]) = make_uint2(pack_bf16x2(v0, v1), pack_bf16x2(v2, v3));
+                    }
+                }
+            }
+        }
+        __syncthreads();
+#pragma unroll
+        for (int pass = 0; pass < CROWS / ROWS_PER_PASS; ++pass) {
+            const int row_l = pass * ROWS_PER_PASS + t / CH8, c8 = (t % CH8) * 8;
+            const int row = m0 + half * CROWS + row_l, col = n0 + c8;
+            if (row >= p.M || col >= p.Nn) continue;
+            uint4 v = *reinterpret_cast<const uint4 *>(&smem[row_l * LDC + c8]);
+            const size_t o = (size_t)row * p.Nn + col;
+            if (MODE == MODE_BWD_DATA) {
+                if (p.flags & EPI_XMASK) v = gate8(v, *reinterpret_cast<const uint4 *>(xm + o));
+            }
+            *reinterpret_cast<uint4 *>(outh + o) = v;
         }
     }
 }
