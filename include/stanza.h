@@ -96,8 +96,11 @@ int stanza_version(void);
 /* ---- CONV worker: forward (Sec. 3.2: "each CONV worker processes [its batch] up to the last CONV layer")
  *   y[n,p,q,k] = bias[k] + sum_{r,s,c} x[n, p*stride_h - pad_h + r, q*stride_w - pad_w + s, c] * w[k,r,s,c]
  * followed by max(.,0) with STANZA_CONV_RELU.  bias (float32 [K]) is required iff STANZA_CONV_BIAS.
- * which: 0 forward, 1 backward-data, 2 backward-weight.  Forward and backward-data need no
- * workspace (0 is returned; ws may be NULL). */
+ * which: 0 forward, 1 backward-data, 2 backward-weight.  For forward and backward-data the workspace is OPTIONAL:
+ * with ws == NULL (or fewer bytes than stanza_conv_workspace_bytes reports) every output tile is computed by one
+ * workgroup; with it, the tiles of the last, partly filled round of workgroups (all tiles when there are few) are cut
+ * into reduction slices that are added in a fixed order by a second kernel, so that all compute units finish together.
+ * Results are run-to-run identical either way; the two ways differ in the last bits (summation order). */
 size_t stanza_conv_workspace_bytes(const stanza_conv_desc *desc, int which);
 int stanza_conv_fwd(const stanza_conv_desc *desc, const void *x, const void *w, const float *bias,
                     void *y, void *ws, size_t ws_bytes, void *stream);

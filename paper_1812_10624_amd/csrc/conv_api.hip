@@ -22,15 +22,157 @@ int conv_geometry(const stanza_conv_desc *d, ConvGeo *g)
     return STANZA_OK;
 }
 
-// ------------------------------------------------------------------ tile choice and launch
-template <int MODE, int BM, int BN, int WM, int WN>
-static int launch_tile(GemmParams &p, bool veca, bool vecb, int splits, hipStream_t st)
+// ------------------------------------------------------------------ tile choice, work-item plan and launch
+constexpr int CUS = 256;   // compute units of the MI355X this library is written for
+
+enum TileShape { T256x64, T128x64, T64x64, T64x128, T128x128 };
+struct ShapeDim { int bm, bn; };
+static ShapeDim shape_dim(TileShape s)
 {
-    p.tilesM = cdiv(p.M, BM);
-    p.tilesN = cdiv(p.Nn, BN);
-    p.tiles = p.tilesM * p.tilesN;
-    p.splits = splits;
-    dim3 grid((unsigned)(cdiv(p.tiles * splits, 8) * 8));
+    switch (s) {
+    case T256x64: return {256, 64};
+    case T128x64: return {128, 64};
+    case T64x64: return {64, 64};
+    case T64x128: return {64, 128};
+    default: return {128, 128};
+    }
+}
+
+// Tall tiles while they still give every CU a couple of workgroups; 64-wide when the GEMM is narrow.
+static TileShape pick_shape(int mode, int M, int Nn, int splits)
+{
+    const int want = 512;
+    if (Nn <= 64) {
+        if (mode != MODE_BWD_WEIGHT && (int64_t)cdiv(M, 256) * splits >= want) return T256x64;
+        if ((int64_t)cdiv(M, 128) * splits >= want) return T128x64;
+        return T64x64;
+    }
+    if (M <= 64 || (int64_t)cdiv(M, 128) * cdiv(Nn, 128) * splits < want) {
+        if (M <= 64 || (int64_t)cdiv(M, 64) * cdiv(Nn, 128) * splits < want * 2) return T64x128;
+    }
+    return T128x128;
+}
+
+// How one GEMM is cut into work items.
+struct GemmPlan {
+    TileShape shape;
+    int tilesM, tilesN, tiles;
+    int dp_tiles;          // tiles computed whole by one workgroup
+    int split_tiles;       // the last tiles, each cut into `splits` reduction slices
+    int splits;
+    int chunks_per_split;  // reduction stages (of BK) per slice
+    size_t partial_floats; // FWD / BWD_DATA slice sums: split_tiles * splits * bm * bn
+};
+
+// FWD / BWD_DATA.  Workgroups are handed to the 256 CUs as slots free up, so a launch of T equal tiles takes
+// ceil(T / 256) tile-times and the last round leaves CUs idle unless T is a multiple of 256 (a 14x14x512 layer at batch 64
+// is 3.06 rounds of 64x128 tiles).  The tiles of that last round are cut into s reduction slices, s chosen to minimise
+//   ceil(tail * s / 256) / s  +  s * (tail / 256) * io  +  launch
+// in tile-times, where io = (write + read of one slice's raw tile at a CU's share of the HBM rate) / (one tile's MFMA time)
+// = 123 / Kd.  When the whole launch is less than two rounds every tile is sliced, which also gives each CU the two to three
+// resident workgroups the main loop needs to hide its LDS and barrier latencies.
+static GemmPlan plan_gemm(int mode, int M, int Nn, int Kd, int bw_splits, bool may_slice)
+{
+    GemmPlan pl{};
+    pl.shape = pick_shape(mode, M, Nn, mode == MODE_BWD_WEIGHT ? bw_splits : 1);
+    const ShapeDim sd = shape_dim(pl.shape);
+    pl.tilesM = cdiv(M, sd.bm);
+    pl.tilesN = cdiv(Nn, sd.bn);
+    pl.tiles = pl.tilesM * pl.tilesN;
+    const int chunks = cdiv(Kd, BK);
+    pl.dp_tiles = pl.tiles;
+    pl.splits = 1;
+    pl.chunks_per_split = chunks;
+    if (mode == MODE_BWD_WEIGHT) {
+        if (bw_splits > 1) {
+            pl.dp_tiles = 0;
+            pl.split_tiles = pl.tiles;
+            pl.chunks_per_split = cdiv(chunks, bw_splits);
+            pl.splits = cdiv(chunks, pl.chunks_per_split);
+        }
+        return pl;
+    }
+    if (!may_slice || chunks < 16) return pl;
+    const int full = pl.tiles / CUS;
+    int tail = pl.tiles % CUS;
+    double base = 1.0;                      // cost of the unsliced tail round
+    if (pl.tiles < 2 * CUS) {
+        tail = pl.tiles;
+        base = cdiv(pl.tiles, CUS) / (pl.tiles < 2 * CUS ? 0.75 : 1.0);   // a CU with a single resident workgroup idles on latencies
+    } else if (tail == 0 || full >= 16) {
+        return pl;
+    }
+    const double io = 123.0 / Kd;
+    int best_s = 1;
+    double best = base;
+    for (int s = 2; s <= 16 && chunks / s >= 4; ++s) {
+        const int64_t items = (int64_t)tail * s;
+        double c = (double)cdiv64(items, CUS) / s;
+        if (pl.tiles < 2 * CUS && items < 2 * CUS) c /= 0.75;
+        c += s * ((double)tail / CUS) * io + 0.02;
+        if (c < best * 0.97) { best = c; best_s = s; }
+    }
+    if (best_s > 1) {
+        pl.split_tiles = tail;
+        pl.dp_tiles = pl.tiles - tail;
+        pl.chunks_per_split = cdiv(chunks, best_s);
+        pl.splits = cdiv(chunks, pl.chunks_per_split);
+        pl.partial_floats = (size_t)pl.split_tiles * pl.splits * sd.bm * sd.bn;
+    }
+    return pl;
+}
+
+size_t igemm_partial_floats(int mode, int M, int Nn, int Kd)
+{
+    if (mode == MODE_BWD_WEIGHT || M <= 0 || Nn <= 0 || Kd <= 0) return 0;
+    return plan_gemm(mode, M, Nn, Kd, 1, true).partial_floats;
+}
+
+// Adds the reduction slices of every sliced tile in slice order and applies the epilogue of the main kernel.
+// grid = (split_tiles, bm*bn / 4096); a thread owns 4 consecutive columns of 4 rows.
+__global__ __launch_bounds__(256) void slice_fixup_kernel(const GemmParams p, int mode, int bm, int bn)
+{
+    const int ti = blockIdx.x, tile = p.dp_tiles + ti;
+    const int tile_n = tile % p.tilesN, tile_m = tile / p.tilesN;
+    const int q4 = bn / 4;
+    const size_t tile_floats = (size_t)bm * bn;
+    for (int idx = blockIdx.y * 1024 + threadIdx.x; idx < (blockIdx.y + 1) * 1024; idx += 256) {
+        const int row_l = idx / q4, col_l = (idx - row_l * q4) * 4;
+        const int row = tile_m * bm + row_l, col = tile_n * bn + col_l;
+        if (row >= p.M || col >= p.Nn) continue;
+        float4 acc = zero4();
+        for (int s = 0; s < p.splits; ++s) {
+            const float4 v = ldg4(p.partial + ((size_t)s * p.split_tiles + ti) * tile_floats + (size_t)row_l * bn + col_l);
+            acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w;
+        }
+        const size_t o = (size_t)row * p.Nn + col;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            if (col + e >= p.Nn) break;
+            float v = f4at(acc, e);
+            if (mode == MODE_FWD) {
+                if (p.flags & EPI_BIAS) v += p.bias[col + e];
+                if (p.flags & EPI_RELU) v = fmaxf(v, 0.f);
+            } else {
+                if (p.flags & EPI_ACCUM) v += p.out[o + e];
+                if (p.flags & EPI_XMASK) v = p.xmask[o + e] > 0.f ? v : 0.f;
+            }
+            p.out[o + e] = v;
+        }
+    }
+}
+
+template <int MODE, int BM, int BN, int WM, int WN>
+static int launch_tile(GemmParams &p, const GemmPlan &pl, bool veca, bool vecb, hipStream_t st)
+{
+    p.tilesM = pl.tilesM;
+    p.tilesN = pl.tilesN;
+    p.tiles = pl.tiles;
+    p.dp_tiles = pl.dp_tiles;
+    p.split_tiles = pl.split_tiles;
+    p.splits = pl.splits;
+    p.chunks_per_split = pl.chunks_per_split;
+    dim3 grid((unsigned)(cdiv(pl.dp_tiles, 8) * 8 + cdiv(pl.split_tiles * pl.splits, 8) * 8));
     const ConvGeo &g = p.g;
     const bool fast = veca && vecb &&
                       ((MODE == MODE_FWD && g.C % BK == 0) || (MODE == MODE_BWD_DATA && g.K % BK == 0 && g.sh == 1 && g.sw == 1));
@@ -42,30 +184,33 @@ static int launch_tile(GemmParams &p, bool veca, bool vecb, int splits, hipStrea
         hipLaunchKernelGGL((igemm_kernel<MODE, BM, BN, WM, WN, true, false>), grid, dim3(NTHREADS), 0, st, p);
     else
         hipLaunchKernelGGL((igemm_kernel<MODE, BM, BN, WM, WN, false, false>), grid, dim3(NTHREADS), 0, st, p);
+    int rc = launch_status();
+    if (rc || MODE == MODE_BWD_WEIGHT || pl.split_tiles == 0) return rc;
+    hipLaunchKernelGGL(slice_fixup_kernel, dim3(pl.split_tiles, BM * BN / 4096), dim3(256), 0, st, p, MODE, BM, BN);
     return launch_status();
 }
 
 template <int MODE>
-static int launch_mode(GemmParams &p, bool veca, bool vecb, int splits, hipStream_t st)
+static int launch_mode(GemmParams &p, const GemmPlan &pl, bool veca, bool vecb, hipStream_t st)
 {
-    // Tall tiles while they still give every CU a couple of workgroups; 64-wide when the GEMM is narrow.
-    const int want = 512;
-    if (p.Nn <= 64) {
-        if (MODE != MODE_BWD_WEIGHT && (int64_t)cdiv(p.M, 256) * splits >= want) return launch_tile<MODE, 256, 64, 4, 1>(p, veca, vecb, splits, st);
-        if ((int64_t)cdiv(p.M, 128) * splits >= want) return launch_tile<MODE, 128, 64, 2, 2>(p, veca, vecb, splits, st);
-        return launch_tile<MODE, 64, 64, 2, 2>(p, veca, vecb, splits, st);
+    switch (pl.shape) {
+    case T256x64:
+        if constexpr (MODE != MODE_BWD_WEIGHT) return launch_tile<MODE, 256, 64, 4, 1>(p, pl, veca, vecb, st);
+        return STANZA_EINVAL;
+    case T128x64: return launch_tile<MODE, 128, 64, 2, 2>(p, pl, veca, vecb, st);
+    case T64x64: return launch_tile<MODE, 64, 64, 2, 2>(p, pl, veca, vecb, st);
+    case T64x128: return launch_tile<MODE, 64, 128, 2, 2>(p, pl, veca, vecb, st);
+    default: return launch_tile<MODE, 128, 128, 2, 2>(p, pl, veca, vecb, st);
     }
-    if (p.M <= 64 || (int64_t)cdiv(p.M, 128) * cdiv(p.Nn, 128) * splits < want) {
-        if (p.M <= 64 || (int64_t)cdiv(p.M, 64) * cdiv(p.Nn, 128) * splits < want * 2)
-            return launch_tile<MODE, 64, 128, 2, 2>(p, veca, vecb, splits, st);
-    }
-    return launch_tile<MODE, 128, 128, 2, 2>(p, veca, vecb, splits, st);
 }
 
-int launch_igemm(int mode, GemmParams &p, int splits, hipStream_t st)
+int launch_igemm(int mode, GemmParams &p, int bw_splits, float *partial, size_t partial_floats, hipStream_t st)
 {
     const ConvGeo &g = p.g;
-    if (p.M <= 0 || p.Nn <= 0 || p.Kd <= 0 || splits <= 0) return STANZA_EINVAL;
+    if (p.M <= 0 || p.Nn <= 0 || p.Kd <= 0 || bw_splits <= 0) return STANZA_EINVAL;
+    GemmPlan pl = plan_gemm(mode, p.M, p.Nn, p.Kd, bw_splits, partial != nullptr);
+    if (pl.partial_floats > partial_floats) pl = plan_gemm(mode, p.M, p.Nn, p.Kd, bw_splits, false);
+    p.partial = partial;
     p.fd_c = make_fastdiv(g.C);
     p.fd_k = make_fastdiv(g.K);
     p.fd_s = make_fastdiv(g.S);
@@ -81,9 +226,9 @@ int launch_igemm(int mode, GemmParams &p, int splits, hipStream_t st)
     p.b_bytes = (uint32_t)(bb < lim ? bb : 0);
     const bool small_a = ab < lim, small_b = bb < lim;
     switch (mode) {
-    case MODE_FWD: return launch_mode<MODE_FWD>(p, g.C % 4 == 0 && small_a && small_b, g.C % 4 == 0 && small_a && small_b, 1, st);
-    case MODE_BWD_DATA: return launch_mode<MODE_BWD_DATA>(p, g.K % 4 == 0 && small_a, g.C % 4 == 0 && small_b, 1, st);
-    case MODE_BWD_WEIGHT: return launch_mode<MODE_BWD_WEIGHT>(p, g.K % 4 == 0 && small_a, g.C % 4 == 0 && small_b, splits, st);
+    case MODE_FWD: return launch_mode<MODE_FWD>(p, pl, g.C % 4 == 0 && small_a && small_b, g.C % 4 == 0 && small_a && small_b, st);
+    case MODE_BWD_DATA: return launch_mode<MODE_BWD_DATA>(p, pl, g.K % 4 == 0 && small_a, g.C % 4 == 0 && small_b, st);
+    case MODE_BWD_WEIGHT: return launch_mode<MODE_BWD_WEIGHT>(p, pl, g.K % 4 == 0 && small_a, g.C % 4 == 0 && small_b, st);
     }
     return STANZA_EINVAL;
 }
@@ -246,8 +391,12 @@ using namespace stanza;
 extern "C" size_t stanza_conv_workspace_bytes(const stanza_conv_desc *desc, int which)
 {
     ConvGeo g;
-    if (!desc || which != 2 || conv_geometry(desc, &g) != STANZA_OK) return 0;
-    return plan_wgrad(g, (desc->flags & STANZA_CONV_BIAS) != 0, desc->dtype == STANZA_BF16 ? BKH : BK).bytes;
+    if (!desc || which < 0 || which > 2 || conv_geometry(desc, &g) != STANZA_OK) return 0;
+    if (which == 2) return plan_wgrad(g, (desc->flags & STANZA_CONV_BIAS) != 0, desc->dtype == STANZA_BF16 ? BKH : BK).bytes;
+    if (desc->dtype != STANZA_F32) return 0;
+    const size_t fl = which == 0 ? igemm_partial_floats(MODE_FWD, g.N * g.Ho * g.Wo, g.K, g.R * g.S * g.C)
+                                 : igemm_partial_floats(MODE_BWD_DATA, g.N * g.H * g.W, g.C, g.R * g.S * g.K);
+    return round256(fl * 4);
 }
 
 // float32 always; bfloat16 when both channel counts are multiples of 8 (one 16-byte vector stays inside a tap)
@@ -258,15 +407,17 @@ static int check_dtype(const stanza_conv_desc *d)
     return STANZA_EUNSUPPORTED;
 }
 
-static int launch_any(const stanza_conv_desc *d, int mode, GemmParams &p, int splits, hipStream_t st)
+// ws / ws_bytes: the optional slice workspace of a float32 forward or backward-data call
+static int launch_any(const stanza_conv_desc *d, int mode, GemmParams &p, int splits, void *ws, size_t ws_bytes, hipStream_t st)
 {
-    return d->dtype == STANZA_BF16 ? launch_igemm_bf16(mode, p, splits, st) : launch_igemm(mode, p, splits, st);
+    if (d->dtype == STANZA_BF16) return launch_igemm_bf16(mode, p, splits, st);
+    if (mode == MODE_BWD_WEIGHT) return launch_igemm(mode, p, splits, nullptr, 0, st);
+    return launch_igemm(mode, p, 1, (float *)ws, ws ? ws_bytes / 4 : 0, st);
 }
 
 extern "C" int stanza_conv_fwd(const stanza_conv_desc *desc, const void *x, const void *w, const float *bias, void *y,
                                void *ws, size_t ws_bytes, void *stream)
 {
-    (void)ws; (void)ws_bytes;
     if (!desc) return STANZA_ENULL;
     GemmParams p{};
     int rc = conv_geometry(desc, &p.g);
@@ -274,7 +425,7 @@ extern "C" int stanza_conv_fwd(const stanza_conv_desc *desc, const void *x, cons
     if ((rc = check_dtype(desc))) return rc;
     const bool has_bias = desc->flags & STANZA_CONV_BIAS;
     if (!x || !w || !y || (has_bias && !bias)) return STANZA_ENULL;
-    if (!aligned16(x) || !aligned16(w) || !aligned16(y) || !aligned16(bias)) return STANZA_EALIGN;
+    if (!aligned16(x) || !aligned16(w) || !aligned16(y) || !aligned16(bias) || !aligned16(ws)) return STANZA_EALIGN;
     p.a = (const float *)x;
     p.b = (const float *)w;
     p.out = (float *)y;
@@ -283,20 +434,19 @@ extern "C" int stanza_conv_fwd(const stanza_conv_desc *desc, const void *x, cons
     p.Nn = p.g.K;
     p.Kd = p.g.R * p.g.S * p.g.C;
     p.flags = (has_bias ? EPI_BIAS : 0u) | ((desc->flags & STANZA_CONV_RELU) ? EPI_RELU : 0u);
-    return launch_any(desc, MODE_FWD, p, 1, (hipStream_t)stream);
+    return launch_any(desc, MODE_FWD, p, 1, ws, ws_bytes, (hipStream_t)stream);
 }
 
 extern "C" int stanza_conv_bwd_data(const stanza_conv_desc *desc, const void *dy, const void *y, const void *w,
                                     const void *x_mask, void *dx, void *ws, size_t ws_bytes, void *stream)
 {
-    (void)ws; (void)ws_bytes;
     if (!desc) return STANZA_ENULL;
     GemmParams p{};
     int rc = conv_geometry(desc, &p.g);
     if (rc) return rc;
     if ((rc = check_dtype(desc))) return rc;
     if (!dy || !w || !dx) return STANZA_ENULL;
-    if (!aligned16(dy) || !aligned16(w) || !aligned16(dx) || !aligned16(y) || !aligned16(x_mask)) return STANZA_EALIGN;
+    if (!aligned16(dy) || !aligned16(w) || !aligned16(dx) || !aligned16(y) || !aligned16(x_mask) || !aligned16(ws)) return STANZA_EALIGN;
     p.a = (const float *)dy;
     p.amask = (desc->flags & STANZA_CONV_RELU) ? (const float *)y : nullptr;
     p.b = (const float *)w;
@@ -306,7 +456,7 @@ extern "C" int stanza_conv_bwd_data(const stanza_conv_desc *desc, const void *dy
     p.Nn = p.g.C;
     p.Kd = p.g.R * p.g.S * p.g.K;
     p.flags = ((desc->flags & STANZA_CONV_ACCUM) ? EPI_ACCUM : 0u) | (x_mask ? EPI_XMASK : 0u) | (p.amask ? LOAD_AMASK : 0u);
-    return launch_any(desc, MODE_BWD_DATA, p, 1, (hipStream_t)stream);
+    return launch_any(desc, MODE_BWD_DATA, p, 1, ws, ws_bytes, (hipStream_t)stream);
 }
 
 extern "C" int stanza_conv_bwd_weight(const stanza_conv_desc *desc, const void *x, const void *dy, const void *y, float *dw,
@@ -336,7 +486,7 @@ extern "C" int stanza_conv_bwd_weight(const stanza_conv_desc *desc, const void *
     p.out = pl.splits > 1 ? partial : dw;
     p.dbias = pl.splits > 1 ? dbscratch : dbias;
     p.dbias_stride = p.g.K;
-    rc = launch_any(desc, MODE_BWD_WEIGHT, p, pl.splits, st);
+    rc = launch_any(desc, MODE_BWD_WEIGHT, p, pl.splits, nullptr, 0, st);
     if (rc) return rc;
     if (pl.splits > 1)
         rc = launch_split_reduce(partial, pl.splits, (size_t)p.M * p.Nn, dw, dbscratch, want_bias ? (size_t)p.g.K : 0, dbias, st);

@@ -71,6 +71,8 @@ struct FcLayout {
     size_t dz_off[2];     // two gradient buffers of n * max_width floats
     size_t row_loss_off;
     size_t db_off;        // column-sum scratch: colsum_blocks(n) * max_width
+    size_t partial_off;   // reduction-slice sums of the forward / input-gradient GEMMs that are cut (largest of them)
+    size_t partial_floats;
     size_t floats;
 };
 
@@ -95,6 +97,12 @@ static int fc_layout(const stanza_fc_desc *d, FcLayout *lay)
     lay->dz_off[1] = off; off += dzf;
     lay->row_loss_off = off; off += round256((size_t)d->n_samples * 4) / 4;
     lay->db_off = off; off += round256((size_t)colsum_blocks(d->n_samples) * maxw * 4) / 4;
+    size_t pf = 0;
+    for (int l = 1; l <= d->n_layers; ++l) {
+        pf = max(pf, igemm_partial_floats(MODE_FWD, d->n_samples, d->host_dims[l], d->host_dims[l - 1]));
+        pf = max(pf, igemm_partial_floats(MODE_BWD_DATA, d->n_samples, d->host_dims[l - 1], d->host_dims[l]));
+    }
+    lay->partial_off = off; lay->partial_floats = pf; off += round256(pf * 4) / 4;
     lay->floats = off;
     return STANZA_OK;
 }
@@ -142,7 +150,7 @@ extern "C" int stanza_fc_step(const stanza_fc_desc *desc, const float *feats, co
         p.out = base + lay.act_off[l];
         p.M = n; p.Nn = dims[l]; p.Kd = dims[l - 1];
         p.flags = EPI_BIAS | (l < L ? EPI_RELU : 0u);
-        if ((rc = launch_igemm(MODE_FWD, p, 1, st))) return rc;
+        if ((rc = launch_igemm(MODE_FWD, p, 1, base + lay.partial_off, lay.partial_floats, st))) return rc;
     }
     // loss and its gradient
     float *dz = base + lay.dz_off[0], *dz_next = base + lay.dz_off[1];
@@ -164,7 +172,7 @@ extern "C" int stanza_fc_step(const stanza_fc_desc *desc, const float *feats, co
             p.xmask = (l == 1) ? nullptr : act(l - 1);
             p.M = n; p.Nn = in; p.Kd = out;
             p.flags = p.xmask ? EPI_XMASK : 0u;
-            if ((rc = launch_igemm(MODE_BWD_DATA, p, 1, st))) return rc;
+            if ((rc = launch_igemm(MODE_BWD_DATA, p, 1, base + lay.partial_off, lay.partial_floats, st))) return rc;
         }
         {   // weight gradient fused with the update
             GemmParams p{};
@@ -176,7 +184,7 @@ extern "C" int stanza_fc_step(const stanza_fc_desc *desc, const float *feats, co
             p.flags = EPI_SGD;
             p.sgd_w = host_W[l - 1]; p.sgd_v = host_vW[l - 1];
             p.lr = desc->lr; p.mom = desc->momentum; p.wd = desc->weight_decay;
-            if ((rc = launch_igemm(MODE_BWD_WEIGHT, p, 1, st))) return rc;
+            if ((rc = launch_igemm(MODE_BWD_WEIGHT, p, 1, nullptr, 0, st))) return rc;
         }
         if ((rc = launch_colsum(dz, nullptr, n, out, base + lay.db_off, dbb, nullptr, host_b[l - 1], host_vb[l - 1], desc->lr,
                                 desc->momentum, desc->weight_decay, st)))

@@ -7,13 +7,17 @@
 //   BWD_DATA    C[m=(n,h,w)][j=c]       = sum_{(r,s,k)} dy[n,(h+ph-r)/sh,(w+pw-s)/sw,k] * w[k,r,s,c]
 //   BWD_WEIGHT  C[m=k][j=(r,s,c)]       = sum_{(n,p,q)} dy[n,p,q,k] * x[n,p*sh-ph+r,q*sw-pw+s,c]
 //
-// Both LDS tiles are stored reduction-major ([BK][BM+pad], [BK][BN+pad]) so that the MFMA operand
-// reads (lane -> row = lane%32, k = lane/32) are conflict-free 128-byte rows.  Operands whose
-// reduction index is contiguous in memory (x and w in FWD, dy in BWD_DATA) are fetched as 16-byte
-// vectors along the reduction and transposed on the way into LDS; operands whose GEMM row/column
-// index is contiguous (w in BWD_DATA, dy and x in BWD_WEIGHT) are fetched and stored as 16-byte
-// vectors directly.  Out-of-image taps, ragged tile edges and the reduction tail are predicated
-// loads that yield zero; nothing is padded in memory.
+// An operand whose reduction index is contiguous in memory (x and w in FWD, dy in BWD_DATA) is fetched as
+// 16-byte vectors along the reduction and kept row-major in LDS; an operand whose GEMM row/column index is
+// contiguous (w in BWD_DATA, dy and x in BWD_WEIGHT) is fetched as 16-byte vectors along the tile edge and
+// kept reduction-major.  Out-of-image taps, ragged tile edges and the reduction tail are predicated loads
+// that yield zero; nothing is padded in memory.
+//
+// Work items.  A launch holds `dp_tiles` whole output tiles followed by `split_tiles` tiles whose reduction
+// is cut into `splits` slices (every tile for BWD_WEIGHT with a long reduction; for FWD / BWD_DATA only the
+// last few tiles, so that the final partial round of workgroups is made of short items and the CUs finish
+// together).  A slice item writes its raw accumulators to a workspace; a second kernel adds the slices in
+// slice order and applies the epilogue.  Which tiles are sliced depends on the shape alone.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -25,8 +29,6 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 constexpr int BK = 16;         // reduction depth of one LDS stage
 constexpr int NTHREADS = 256;  // 4 wavefronts
 constexpr int KQ = BK / 4;     // 16-byte vectors along the reduction per tile row
-constexpr int PAD_T = 8 / KQ;  // row pad of a tile written transposed (4 scalar stores per fetched vector): a half-wave's
-                               // KQ reduction vectors x 32/KQ tile rows land on 32 distinct banks (stride = 4*pad mod 32)
 constexpr int PAD_V = 4;  // row pad of a tile written as 16-byte vectors (keeps rows 16-byte aligned)
 
 enum { MODE_FWD = 0, MODE_BWD_DATA = 1, MODE_BWD_WEIGHT = 2 };
@@ -76,8 +78,11 @@ struct GemmParams {
     float lr, mom, wd;
     int M, Nn, Kd;        // GEMM extents (Kd = full reduction length)
     int tilesM, tilesN, tiles;
-    int splits;           // reduction slices (1 except for BWD_WEIGHT)
-    int chunks_per_split; // BWD_WEIGHT: reduction chunks (of BK) per slice
+    int dp_tiles;         // tiles [0, dp_tiles) are computed whole by one workgroup each
+    int split_tiles;      // tiles [dp_tiles, tiles) are cut into `splits` reduction slices
+    int splits;
+    int chunks_per_split; // reduction stages (of BK) per slice
+    float *partial;       // FWD / BWD_DATA slice items: raw accumulators, [slice * split_tiles + tile - dp_tiles][BM*BN]
     uint32_t flags;
     uint32_t a_bytes, b_bytes;   // extent of the a / b tensors (vector fetch paths address them as 32-bit buffer offsets)
 };
@@ -150,10 +155,15 @@ __global__ __launch_bounds__(NTHREADS) void igemm_kernel(const GemmParams p)
     // 8), so give each XCD one contiguous run of work items: neighbours in M share their input halo and the
     // whole weight panel in that XCD's L2, and for BWD_WEIGHT all column tiles of one reduction slice (which
     // read the same dy rows and the same pixels of x, shifted by a tap) run side by side on one XCD.
-    const int per_xcd = gridDim.x >> 3;
-    const int L = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
-    if (L >= p.tiles * p.splits) return;
-    const int split = L / p.tiles, tile = L - split * p.tiles;
+    // The whole tiles come first in launch order and the slice items last, each group spread over the XCDs.
+    const int grid_a = ((p.dp_tiles + 7) >> 3) << 3;
+    const bool sliced = (int)blockIdx.x >= grid_a;
+    const int bid = sliced ? blockIdx.x - grid_a : blockIdx.x;
+    const int per_xcd = (sliced ? gridDim.x - grid_a : grid_a) >> 3;
+    const int L = (bid & 7) * per_xcd + (bid >> 3);
+    if (L >= (sliced ? p.split_tiles * p.splits : p.dp_tiles)) return;
+    const int split = sliced ? L / p.split_tiles : 0;
+    const int tile = sliced ? p.dp_tiles + (L - split * p.split_tiles) : L;
     const int tile_n = tile % p.tilesN, tile_m = tile / p.tilesN;
     const int m0 = tile_m * BM, n0 = tile_n * BN;
 
@@ -161,12 +171,11 @@ __global__ __launch_bounds__(NTHREADS) void igemm_kernel(const GemmParams p)
     const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
     const int wave_m = wave / WN, wave_n = wave % WN;
 
-    int kbeg = 0, kend = p.Kd;
-    if (MODE == MODE_BWD_WEIGHT) {
-        kbeg = split * p.chunks_per_split * BK;
-        kend = min(p.Kd, kbeg + p.chunks_per_split * BK);
-    }
-    const int nchunks = (kend - kbeg + BK - 1) / BK;
+    // reduction stages [ch_beg, ch_end) of this work item
+    const int all_chunks = (p.Kd + BK - 1) / BK;
+    const int ch_beg = sliced ? split * p.chunks_per_split : 0;
+    const int ch_end = sliced ? min(all_chunks, ch_beg + p.chunks_per_split) : all_chunks;
+    const int kend = min(p.Kd, ch_end * BK);
     const bool amask = (p.flags & LOAD_AMASK) != 0;
 
     // ------------------------------------------------------------------ loader state
@@ -248,7 +257,7 @@ __global__ __launch_bounds__(NTHREADS) void igemm_kernel(const GemmParams p)
     // rounding; this one is fixed by the shape alone.
     const bool tap_minor = MODE != MODE_BWD_WEIGHT && (FAST || (p.flags & ORDER_TAP_MINOR));
     auto stage_k = [&](int ch) -> int {
-        if (!tap_minor) return kbeg + ch * BK;
+        if (!tap_minor) return ch * BK;
         const int cblk = fdiv(ch, p.fd_rs), tap = ch - cblk * (g.R * g.S);
         return tap * (MODE == MODE_FWD ? g.C : g.K) + cblk * BK;
     };
@@ -259,7 +268,7 @@ __global__ __launch_bounds__(NTHREADS) void igemm_kernel(const GemmParams p)
             // wavefront-uniform: channel block and tap of the stage
             const int cblk = fdiv(ch, p.fd_rs), tap = ch - cblk * (g.R * g.S);
             const int ar = fdiv(tap, p.fd_s), as = tap - ar * g.S;
-            const bool kok = ch < nchunks;
+            const bool kok = ch < ch_end;
             int off;
             bool ok;
             if (MODE == MODE_FWD) {
@@ -352,7 +361,7 @@ __global__ __launch_bounds__(NTHREADS) void igemm_kernel(const GemmParams p)
     auto fetch_b = [&](int ch, int i) {
         if (FAST) {
             const int cblk = fdiv(ch, p.fd_rs), tap = ch - cblk * (g.R * g.S);
-            bool ok = ch < nchunks;
+            bool ok = ch < ch_end;
             int off;
             if (MODE == MODE_FWD) {
                 ok = ok && n0 + row0 + RPP * i < p.Nn;
@@ -456,17 +465,17 @@ __global__ __launch_bounds__(NTHREADS) void igemm_kernel(const GemmParams p)
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
 #pragma unroll
-    for (int i = 0; i < AV; ++i) fetch_a(0, i);
+    for (int i = 0; i < AV; ++i) fetch_a(ch_beg, i);
 #pragma unroll
-    for (int i = 0; i < BV; ++i) fetch_b(0, i);
+    for (int i = 0; i < BV; ++i) fetch_b(ch_beg, i);
     stash(0);
     __syncthreads();
 
     const int lrow = lane & 31, lk = lane >> 5;
     constexpr int KS = BK / 2;                      // MFMA k-steps per stage
     static_assert(AV + BV <= KS, "one fetch slot per k-step");
-    for (int ch = 0; ch < nchunks; ++ch) {
-        const int buf = ch & 1;
+    for (int ch = ch_beg; ch < ch_end; ++ch) {
+        const int buf = (ch - ch_beg) & 1;
         // Per k-step: (1) LDS reads of the NEXT k-step's operands, (2) this k-step's MFMAs, (3) one slice of the
         // next stage's global fetch (address arithmetic + load issue), which executes in the shadow of the MFMAs.
         // The scheduling barriers pin this order.
@@ -541,6 +550,18 @@ __global__ __launch_bounds__(NTHREADS) void igemm_kernel(const GemmParams p)
     // ------------------------------------------------------------------ epilogue
     // Accumulator register r of lane l holds row 8*(r/4) + 4*(l/32) + r%4, column l%32 of its 32x32 tile.
     const size_t split_off = (MODE == MODE_BWD_WEIGHT && !(p.flags & EPI_SGD)) ? (size_t)split * p.M * p.Nn : 0;
+    if (MODE != MODE_BWD_WEIGHT && sliced) {
+        // raw accumulators of this slice, tile-local [BM][BN]; the fix-up kernel adds the slices and applies the epilogue
+        float *dst = p.partial + (size_t)L * (BM * BN);
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int r = 0; r < 16; ++r)
+                    dst[(wave_m * WTM + i * 32 + 8 * (r >> 2) + 4 * lk + (r & 3)) * BN + wave_n * WTN + j * 32 + lrow] = acc[i][j][r];
+        return;
+    }
 #pragma unroll
     for (int j = 0; j < TN; ++j) {
         const int col = n0 + wave_n * WTN + j * 32 + lrow;

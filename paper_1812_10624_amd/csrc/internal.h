@@ -31,9 +31,15 @@ struct WgradPlan {
 };
 WgradPlan plan_wgrad(const ConvGeo &g, bool want_bias, int bk);   // bk: reduction depth of one LDS stage
 
-// Launch the implicit GEMM in `mode` over p (M, Nn, Kd, pointers and flags already set); picks the tile
-// shape, fills the tile counts.  `splits` > 1 only for MODE_BWD_WEIGHT.
-int launch_igemm(int mode, GemmParams &p, int splits, hipStream_t st);
+// Launch the implicit GEMM in `mode` over p (M, Nn, Kd, pointers and flags already set); picks the tile shape and fills
+// the tile counts.  bw_splits: reduction slices of every tile, MODE_BWD_WEIGHT only (1 otherwise).
+// FWD / BWD_DATA: when `partial` holds at least igemm_partial_floats(mode, M, Nn, Kd) floats, the tiles of the last,
+// partly filled round of workgroups (or all tiles, when there are few) are cut into reduction slices whose raw sums go to
+// `partial`, and a second kernel adds the slices in slice order and applies the epilogue; with partial == nullptr
+// every tile is computed whole by one workgroup.  The cut depends on the GEMM extents alone.
+int launch_igemm(int mode, GemmParams &p, int bw_splits, float *partial, size_t partial_floats, hipStream_t st);
+size_t igemm_partial_floats(int mode, int M, int Nn, int Kd);
+int launch_igemm_bf16(int mode, GemmParams &p, int splits, hipStream_t st);
 
 // out[i] = sum_s partial[s*numel + i], s ascending; likewise out2 from partial2 (numel2 may be 0).
 int launch_split_reduce(const float *partial, int splits, size_t numel, float *out, const float *partial2, size_t numel2, float *out2,

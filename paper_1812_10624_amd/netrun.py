@@ -62,7 +62,9 @@ class ConvWorker:
                        for op in ops if op["op"] == "pool"}
         self.gbuf: Dict[str, torch.Tensor] = {}
         self.grads = {name: (torch.empty_like(w), torch.empty_like(b)) for name, (w, b) in params.items()}
-        ws_bytes = max([api.stanza_conv_workspace_bytes(d, 2) for i, d in self.descs.items() if ops[i]["op"] == "conv"] + [16])
+        # one workspace serves every conv call: the largest need over forward, backward-data and backward-weight
+        ws_bytes = max([api.stanza_conv_workspace_bytes(d, which) for i, d in self.descs.items() if ops[i]["op"] == "conv"
+                        for which in (0, 1, 2)] + [16])
         self.ws = torch.empty(ws_bytes, device=self.dev, dtype=torch.uint8)
         if dtype == api.BF16:
             self.w16 = {op["name"]: torch.empty_like(params[op["name"]][0], dtype=torch.bfloat16)
@@ -84,13 +86,13 @@ class ConvWorker:
                 w, b = self.params[op["name"]]
                 if self.dtype == api.BF16 and not self.f32_layer[i]:
                     api.stanza_cast_f32_to_bf16(w, self.w16[op["name"]])      # this step's bf16 copy of the master filter
-                    api.stanza_conv_fwd(self.descs[i], self.buf[op["src"]], self.w16[op["name"]], b, self.buf[op["dst"]])
+                    api.stanza_conv_fwd(self.descs[i], self.buf[op["src"]], self.w16[op["name"]], b, self.buf[op["dst"]], self.ws)
                 elif self.f32_layer[i]:
                     y32 = self.tmp32[: self.buf[op["dst"]].numel()].view(self.shapes[op["dst"]])
-                    api.stanza_conv_fwd(self.descs[i], self.buf[op["src"]], w, b, y32)
+                    api.stanza_conv_fwd(self.descs[i], self.buf[op["src"]], w, b, y32, self.ws)
                     api.stanza_cast_f32_to_bf16(y32, self.buf[op["dst"]])
                 else:
-                    api.stanza_conv_fwd(self.descs[i], self.buf[op["src"]], w, b, self.buf[op["dst"]])
+                    api.stanza_conv_fwd(self.descs[i], self.buf[op["src"]], w, b, self.buf[op["dst"]], self.ws)
             elif kind == "pool":
                 api.stanza_pool_relu_fwd(self.descs[i], self.buf[op["src"]], self.buf[op["dst"]], self.argmax[op["dst"]], self.dtype)
             elif kind == "add_relu":
@@ -148,7 +150,7 @@ class ConvWorker:
                     else:
                         dx = self._grad_buffer(src)
                         have[src] = dx
-                    api.stanza_conv_bwd_data(dd, dy, y, wk, x_mask, dx)
+                    api.stanza_conv_bwd_data(dd, dy, y, wk, x_mask, dx, self.ws)
                     gated[src] = x_mask is not None
             elif kind == "pool":
                 dx = self._grad_buffer(op["src"])

@@ -70,9 +70,11 @@ def test_conv_layer_full_size(api, o32, name, case):
     dy = _draw((N, g.Ho, g.Wo, K), 4)
     xd, wd, bd, dyd = dev(x), dev(w), dev(b), dev(dy)
     d = api.conv_desc(N, H, W, C, K, R, S, st, pad, api.F32, api.CONV_BIAS | api.CONV_RELU)
+    # the workspace the bench's sequencer passes: with it the last round of tiles is cut into reduction slices
+    ws01 = torch.empty(max(16, api.stanza_conv_workspace_bytes(d, 0), api.stanza_conv_workspace_bytes(d, 1)), dtype=torch.uint8, device="cuda:0")
     # forward (+bias, +ReLU)
     y = torch.empty((N, g.Ho, g.Wo, K), device="cuda:0")
-    api.stanza_conv_fwd(d, xd, wd, bd, y)
+    api.stanza_conv_fwd(d, xd, wd, bd, y, ws01)
     yh = host(y)
     idx = _sample_idx(yh.shape, 10)
     want = [o32.conv_fwd_at(g, x, w, b, True, *i) for i in idx]
@@ -83,7 +85,7 @@ def test_conv_layer_full_size(api, o32, name, case):
     if C > 3:
         d0 = api.conv_desc(N, H, W, C, K, R, S, st, pad, api.F32, 0)
         dx = torch.empty((N, H, W, C), device="cuda:0")
-        api.stanza_conv_bwd_data(d0, dyd, None, wd, None, dx)
+        api.stanza_conv_bwd_data(d0, dyd, None, wd, None, dx, ws01)
         dxh = host(dx)
         idx = _sample_idx(dxh.shape, 11)
         want = [o32.conv_bwd_data_at(g, dy, w, *i) for i in idx]

@@ -121,6 +121,61 @@ def test_conv_backward_weight(api, o32, case):
         assert torch.equal(dw, dw2) and torch.equal(db, db2)
 
 
+# shapes whose forward / backward-data launches are cut into reduction slices when a workspace is given: few tiles (all
+# of them sliced), and several rounds of tiles with a partly filled last round (only the tail sliced)
+SLICED_CASES = [
+    (2, 14, 14, 64, 160, 3, 3, 1, 1),
+    (4, 1, 1, 300, 70, 1, 1, 1, 0),
+    (8, 1, 1, 2048, 256, 1, 1, 1, 0),
+    (2, 27, 27, 12, 20, 5, 5, 1, 2),
+    (16, 56, 56, 32, 128, 3, 3, 1, 1),       # 784 tiles of 64x128: three full rounds + a tail of 16
+    (9, 56, 56, 256, 64, 3, 3, 1, 1),        # 64-wide tiles
+    (2, 29, 29, 16, 32, 3, 3, 2, 1),         # strided: general gather path
+]
+
+
+@pytest.mark.parametrize("case", SLICED_CASES, ids=_ids)
+def test_conv_sliced_launches(api, o32, case):
+    N, H, W, C, K, R, S, st, pad = case
+    g = ConvGeom(N, H, W, C, K, R, S, st, pad)
+    r = rng(4)
+    x = r.standard_normal((N, H, W, C), dtype=np.float32)
+    w = (r.standard_normal((K, R, S, C), dtype=np.float32) / np.sqrt(R * S * C)).astype(np.float32)
+    b = r.standard_normal(K, dtype=np.float32)
+    dy = r.standard_normal((N, g.Ho, g.Wo, K), dtype=np.float32)
+    yfwd = r.standard_normal(dy.shape, dtype=np.float32)
+    prev = r.standard_normal((N, H, W, C), dtype=np.float32)
+    d = api.conv_desc(N, H, W, C, K, R, S, st, pad, api.F32, api.CONV_BIAS | api.CONV_RELU)
+    need = [api.stanza_conv_workspace_bytes(d, k) for k in (0, 1)]
+    assert max(need) > 0, "this shape is expected to be sliced"
+    ws = torch.empty(max(need + [16]), dtype=torch.uint8, device="cuda:0")
+    xd, wd, bd, dyd = dev(x), dev(w), dev(b), dev(dy)
+    if need[0]:
+        ref = o32.conv_fwd(g, x, w, b, relu=True)
+        y = torch.full(ref.shape, float("nan"), device="cuda:0")
+        api.stanza_conv_fwd(d, xd, wd, bd, y, ws)
+        assert rel_err(host(y), ref) < TOL_F32
+        y2 = torch.full(ref.shape, float("nan"), device="cuda:0")
+        api.stanza_conv_fwd(d, xd, wd, bd, y2, ws)
+        assert torch.equal(y, y2)
+        # a workspace that is too small is not an error: the launch is simply not cut
+        y3 = torch.full(ref.shape, float("nan"), device="cuda:0")
+        api.stanza_conv_fwd(d, xd, wd, bd, y3, ws[:256])
+        assert rel_err(host(y3), ref) < TOL_F32
+    if need[1]:
+        ref = o32.conv_bwd_data(g, o32.relu_bwd(dy, yfwd), w)
+        ref = o32.relu_bwd((ref.astype(np.float64) + prev).astype(np.float32), x)
+        d2 = api.conv_desc(N, H, W, C, K, R, S, st, pad, api.F32, api.CONV_RELU | api.CONV_ACCUM)
+        dx = dev(prev)
+        api.stanza_conv_bwd_data(d2, dyd, dev(yfwd), wd, xd, dx, ws)
+        assert rel_err(host(dx), ref) < TOL_F32
+        np.testing.assert_array_equal(host(dx) == 0, ref == 0)
+        d3 = api.conv_desc(N, H, W, C, K, R, S, st, pad, api.F32, 0)
+        dx3 = torch.full(prev.shape, float("nan"), device="cuda:0")
+        api.stanza_conv_bwd_data(d3, dyd, None, wd, None, dx3, ws)
+        assert rel_err(host(dx3), o32.conv_bwd_data(g, dy, w)) < TOL_F32
+
+
 POOL_CASES = [(2, 16, 16, 8, 2, 2, 0, True), (2, 15, 13, 12, 3, 2, 0, True), (2, 14, 15, 16, 3, 2, 1, True),
               (1, 9, 9, 3, 2, 2, 0, True), (1, 11, 11, 5, 3, 2, 1, False), (3, 8, 8, 4, 2, 2, 0, False),
               (1, 12, 12, 4, 3, 1, 1, True)]
