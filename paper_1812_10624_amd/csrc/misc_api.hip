@@ -420,13 +420,22 @@ __global__ __launch_bounds__(256) void ps_aggregate_kernel(const void *ws, int n
 {
     const PsTable tb = ps_table_at(ws, n_tensors);
     const int64_t chunk = blockIdx.x;
-    // binary search: largest t with prefix[t] <= chunk
-    int lo = 0, hi = n_tensors;
-    while (hi - lo > 1) {
-        const int mid = (lo + hi) >> 1;
-        if (tb.prefix[mid] <= chunk) lo = mid; else hi = mid;
+    // Tensor of this chunk: largest t with prefix[t] <= chunk.  Up to 64 tensors (a CNN's conv or FC parameter set) the
+    // lanes of a wavefront test one prefix each and count: one memory latency before the shard loads can be issued instead
+    // of the log2(n) dependent ones of a binary search.
+    int t;
+    if (n_tensors <= 64) {
+        const int lane = threadIdx.x & 63;
+        const bool le = lane < n_tensors && tb.prefix[lane] <= chunk;
+        t = __popcll(__ballot(le)) - 1;
+    } else {
+        int lo = 0, hi = n_tensors;
+        while (hi - lo > 1) {
+            const int mid = (lo + hi) >> 1;
+            if (tb.prefix[mid] <= chunk) lo = mid; else hi = mid;
+        }
+        t = lo;
     }
-    const int t = lo;
     const int64_t numel = tb.numel[t];
     const int64_t base = (chunk - tb.prefix[t]) * PS_CHUNK;
     float *__restrict__ w = tb.w[t];
