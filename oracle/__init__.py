@@ -99,7 +99,7 @@ class Oracle:
         self._l = C.CDLL(os.path.join(_BUILD, f"liboracle_{tag}.so"))
         assert self._l.oracle_real_bytes() == np.dtype(self.dtype).itemsize
         for name in ("oracle_conv_fwd_at", "oracle_conv_bwd_data_at", "oracle_conv_bwd_weight_at",
-                     "oracle_colsum_at", "oracle_fc_fwd_at", "oracle_softmax_ce"):
+                     "oracle_colsum_at", "oracle_fc_fwd_at", "oracle_softmax_ce", "oracle_softmax_ce_part"):
             getattr(self._l, name).restype = C.c_double
 
     def threads(self) -> int:
@@ -215,6 +215,16 @@ class Oracle:
         pred = np.empty((n,), np.int32)
         loss = self._l.oracle_softmax_ce(n, classes, self._p(z), labels.ctypes.data_as(C.c_void_p), self._p(dz),
                                          pred.ctypes.data_as(C.c_void_p))
+        return loss, dz, pred
+
+    def softmax_ce_part(self, z, labels, n_global):
+        """One of several FC workers: its rows' share of the loss and the gradient, both normalised by the global batch."""
+        n, classes = z.shape
+        labels = np.ascontiguousarray(labels, np.int32)
+        dz = np.empty_like(z)
+        pred = np.empty((n,), np.int32)
+        loss = self._l.oracle_softmax_ce_part(n, int(n_global), classes, self._p(z), labels.ctypes.data_as(C.c_void_p), self._p(dz),
+                                              pred.ctypes.data_as(C.c_void_p))
         return loss, dz, pred
 
     # -- optimiser (in place on w, v)

@@ -108,6 +108,65 @@ def fc_step(o: Oracle, feats, labels, fc_params, fc_mom, lr, momentum, wd, updat
     return dict(loss=loss, pred=pred, dfeats=dfeats, acts=acts, grads=grads, dlogits=None)
 
 
+def fc_grads(o: Oracle, feats, labels, fc_params, n_global):
+    """One of several FC workers (Sec. 4.1.3): forward over its own rows, its share of the loss of the global batch,
+    backward.  No update: the FC workers first all-reduce their gradients.  Returns loss part, pred, dfeats, grads."""
+    acts = [feats]
+    L = len(fc_params)
+    for li, (w, b) in enumerate(fc_params):
+        acts.append(o.fc_fwd(acts[-1], w, b, relu=(li < L - 1)))
+    loss, dz, pred = o.softmax_ce_part(acts[-1], labels, n_global)
+    grads = [None] * L
+    for li in range(L - 1, -1, -1):
+        w, _ = fc_params[li]
+        dw, db, da = o.fc_bwd(acts[li], w, dz, need_da=True)
+        grads[li] = (dw, db)
+        if li > 0:
+            dz = o.relu_bwd(da, acts[li])
+        else:
+            dfeats = da
+    return dict(loss=loss, pred=pred, dfeats=dfeats, grads=grads)
+
+
+def multi_fc_split_step(o: Oracle, ops, images: List[np.ndarray], labels, conv_params, conv_mom, fc_params, fc_mom,
+                        lr, momentum, wd, n_f: int):
+    """The layer-separated iteration with n_f FC workers (Sec. 4.1.3): the K CONV workers are split into n_f equal
+    groups, FC worker f serves group f with its own complete copy of the FC layers, the FC workers all-reduce their
+    gradients by recursive doubling and every copy applies the same update; the CONV workers all-reduce theirs the
+    same way (Sec. 4.1.2).  One copy of the FC parameters is kept here because all copies stay identical."""
+    from . import allreduce as ar
+    K = len(images)
+    assert K % n_f == 0
+    per = K // n_f
+    B = images[0].shape[0]
+    n = K * B
+    bufs = [conv_stack_forward(o, ops, o.arr(im), conv_params) for im in images]
+    loss, preds, dfeats, fc_worker_grads = 0.0, [], [], []
+    for f in range(n_f):
+        rows = slice(f * per * B, (f + 1) * per * B)
+        feats = np.concatenate([bufs[k]["feat"].reshape(B, -1) for k in range(f * per, (f + 1) * per)], axis=0)
+        r = fc_grads(o, feats, labels[rows], fc_params, n)
+        loss += r["loss"]
+        preds.append(r["pred"])
+        dfeats.append(r["dfeats"])
+        fc_worker_grads.append(r["grads"])
+    dfeats = np.concatenate(dfeats, axis=0)
+    worker_grads = []
+    for k in range(K):
+        pg, _ = conv_stack_backward(o, ops, bufs[k], conv_params, dfeats[k * B:(k + 1) * B])
+        worker_grads.append(pg)
+    for li, ((w, b), (vw, vb)) in enumerate(zip(fc_params, fc_mom)):
+        ar.ps_aggregate_rd(w.reshape(-1), vw.reshape(-1), [np.ascontiguousarray(g[li][0]).reshape(-1) for g in fc_worker_grads],
+                           1.0, lr, momentum, wd)
+        ar.ps_aggregate_rd(b, vb, [g[li][1] for g in fc_worker_grads], 1.0, lr, momentum, wd)
+    for name, (w, b) in conv_params.items():
+        vw, vb = conv_mom[name]
+        ar.ps_aggregate_rd(w.reshape(-1), vw.reshape(-1), [np.ascontiguousarray(g[name][0]).reshape(-1) for g in worker_grads],
+                           1.0, lr, momentum, wd)
+        ar.ps_aggregate_rd(b, vb, [g[name][1] for g in worker_grads], 1.0, lr, momentum, wd)
+    return dict(loss=loss, pred=np.concatenate(preds), dfeats=dfeats, worker_grads=worker_grads, fc_worker_grads=fc_worker_grads)
+
+
 def split_step(o: Oracle, ops, images: List[np.ndarray], labels, conv_params, conv_mom, fc_params, fc_mom,
                lr, momentum, wd, keep=False):
     """One layer-separated iteration over K = len(images) CONV workers.  Parameters and momentum

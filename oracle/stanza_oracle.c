@@ -386,6 +386,36 @@ double oracle_softmax_ce(int n, int classes, const REAL *z, const int32_t *label
     return total / (double)n;
 }
 
+/* One of several FC workers (Sec. 4.1.3: each FC worker serves an equal share of
+ * the CONV workers and keeps a complete set of FC layers; their gradients are
+ * all-reduced afterwards).  The loss is still the mean over the GLOBAL batch of
+ * Eq. (1), so a worker that holds n_local of the n_global rows contributes
+ *   loss_part = (1/n_global) sum_{local i} [ log sum_j exp(z_ij) - z_i[y_i] ]
+ *   dZ_ij     = (softmax(z_i)_j - [j == y_i]) / n_global
+ * and the parts add up to the single-worker quantities. */
+double oracle_softmax_ce_part(int n_local, int n_global, int classes, const REAL *z, const int32_t *labels, REAL *dz,
+                              int32_t *pred)
+{
+    double total = 0.0;
+    for (int i = 0; i < n_local; ++i) {
+        const REAL *zi = z + (size_t)i * classes;
+        int arg = 0;
+        for (int j = 1; j < classes; ++j)
+            if (zi[j] > zi[arg]) arg = j;
+        const double zmax = (double)zi[arg];
+        double denom = 0.0;
+        for (int j = 0; j < classes; ++j) denom += exp((double)zi[j] - zmax);
+        total += log(denom) + zmax - (double)zi[labels[i]];
+        if (dz)
+            for (int j = 0; j < classes; ++j) {
+                const double sm = exp((double)zi[j] - zmax) / denom;
+                dz[(size_t)i * classes + j] = (REAL)((sm - (j == labels[i] ? 1.0 : 0.0)) / (double)n_global);
+            }
+        if (pred) pred[i] = arg;
+    }
+    return total / (double)n_global;
+}
+
 /* -------------------------------------------------------------- optimiser
  * Momentum SGD with weight decay (Sec. 6.1), in the form of the software stack
  * the paper ran:  g' = g + wd*w ;  v <- m*v + g' ;  w <- w - lr*v. */

@@ -51,6 +51,45 @@ def test_split_equals_monolithic(o64, name, K, B):
         np.testing.assert_allclose(tot, r2["worker_grads"][0][n][0], rtol=1e-9, atol=1e-13)
 
 
+@pytest.mark.parametrize("name,K,B,n_f", [("tiny", 4, 1, 2), ("tiny", 4, 1, 4), ("minimlp", 6, 2, 3), ("minires", 2, 2, 2)])
+def test_several_fc_workers_equal_one(o64, name, K, B, n_f):
+    """Sec. 4.1.3: with the CONV workers split among n_f FC workers whose gradients are all-reduced, the iteration is
+    still the monolithic step on the whole batch (loss parts add up to the global mean, every parameter moves alike)."""
+    wl = wl_mod.get_workload(name)
+    imgs, labels, cp, cm, fp, fm = _setup(o64, wl, 11, K, B)
+    cp2, cm2, fp2, fm2 = (copy.deepcopy(a) for a in (cp, cm, fp, fm))
+    r1 = onet.multi_fc_split_step(o64, wl.ops, imgs, labels, cp, cm, fp, fm, 0.01, 0.9, 1e-4, n_f)
+    r2 = onet.monolithic_step(o64, wl.ops, np.concatenate(imgs, 0), labels, cp2, cm2, fp2, fm2, 0.01, 0.9, 1e-4)
+    assert abs(r1["loss"] - r2["loss"]) < 1e-12
+    np.testing.assert_array_equal(r1["pred"], r2["pred"])
+    for n in cp:
+        for a, b in zip(cp[n], cp2[n]):
+            np.testing.assert_allclose(a, b, rtol=0, atol=1e-12)
+        for a, b in zip(cm[n], cm2[n]):
+            np.testing.assert_allclose(a, b, rtol=1e-9, atol=1e-13)
+    for (w, b), (w2, b2) in zip(fp, fp2):
+        np.testing.assert_allclose(w, w2, rtol=0, atol=1e-13)
+        np.testing.assert_allclose(b, b2, rtol=0, atol=1e-13)
+    for (w, b), (w2, b2) in zip(fm, fm2):
+        np.testing.assert_allclose(w, w2, rtol=1e-9, atol=1e-13)
+        np.testing.assert_allclose(b, b2, rtol=1e-9, atol=1e-13)
+
+
+def test_partial_softmax_ce_parts_add_up(o64):
+    r = np.random.default_rng(3)
+    z = r.standard_normal((12, 7))
+    y = r.integers(0, 7, 12).astype(np.int32)
+    loss, dz, pred = o64.softmax_ce(z, y)
+    parts = [o64.softmax_ce_part(z[a:b], y[a:b], 12) for a, b in ((0, 4), (4, 8), (8, 12))]
+    assert abs(sum(p[0] for p in parts) - loss) < 1e-14
+    np.testing.assert_allclose(np.concatenate([p[1] for p in parts]), dz, rtol=1e-14, atol=0)
+    np.testing.assert_array_equal(np.concatenate([p[2] for p in parts]), pred)
+    # a worker holding every row is the single-worker function
+    l2, dz2, _ = o64.softmax_ce_part(z, y, 12)
+    assert l2 == loss
+    np.testing.assert_array_equal(dz2, dz)
+
+
 def _loss_only(o, wl, imgs, labels, cp, fp):
     feats = np.concatenate([onet.conv_stack_forward(o, wl.ops, im, cp)["feat"].reshape(im.shape[0], -1) for im in imgs], 0)
     a = feats
