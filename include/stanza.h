@@ -168,6 +168,19 @@ int stanza_fc_step(const stanza_fc_desc *desc, const float *feats, const int32_t
                    float *const *host_W, float *const *host_b, float *const *host_vW, float *const *host_vb,
                    float *dfeats, float *loss, int32_t *pred, void *ws, size_t ws_bytes, void *stream);
 
+/* ---- One of several FC workers (Sec. 4.1.3: "each is responsible for an equal number of the CONV workers ... each FC
+ * worker maintains a complete set of FC layers", and the FC workers then exchange their gradients by the same recursive
+ * doubling).  The same forward / loss / backward as stanza_fc_step over this worker's n_samples rows, except that
+ *   - the loss is still the mean over the GLOBAL batch of n_global >= n_samples rows (Eq. 1): loss_part =
+ *     (1/n_global) sum over this worker's rows, dZ_L = (softmax - onehot)/n_global, so that the workers' parts add up;
+ *   - nothing is updated: dW_l and db_l are written to host_gW[l] ([out][in]) and host_gb[l] ([out]), float32, for
+ *     stanza_ps_aggregate_ordered over the FC workers' gradient sets (STANZA_SUM_RECURSIVE_DOUBLING for the paper's order).
+ * desc->lr, momentum, weight_decay are ignored.  n_global < n_samples is STANZA_EINVAL; other errors, workspace size and
+ * ownership as for stanza_fc_step. */
+int stanza_fc_grads(const stanza_fc_desc *desc, int32_t n_global, const float *feats, const int32_t *labels,
+                    float *const *host_W, float *const *host_b, float *const *host_gW, float *const *host_gb,
+                    float *dfeats, float *loss_part, int32_t *pred, void *ws, size_t ws_bytes, void *stream);
+
 /* ---- Gradient aggregation and update (Sec. 3.2: the CONV workers "exchange [their gradients] to get
  * global information sum_x grad l(x, w_conv)" and update; Sec. 2.2: servers aggregate the gradients
  * from all workers and perform the global update).  Per tensor t and element i:

@@ -23,7 +23,7 @@ EXPORTS = (
     "stanza_strerror", "stanza_version", "stanza_conv_workspace_bytes", "stanza_conv_fwd", "stanza_conv_bwd_data",
     "stanza_conv_bwd_weight", "stanza_pool_relu_fwd", "stanza_pool_relu_bwd", "stanza_add_relu_fwd",
     "stanza_add_relu_bwd", "stanza_gap_fwd", "stanza_gap_bwd", "stanza_cast_f32_to_bf16", "stanza_cast_bf16_to_f32",
-    "stanza_fc_workspace_bytes", "stanza_fc_step", "stanza_ps_workspace_bytes", "stanza_ps_plan",
+    "stanza_fc_workspace_bytes", "stanza_fc_step", "stanza_fc_grads", "stanza_ps_workspace_bytes", "stanza_ps_plan",
     "stanza_ps_aggregate_planned", "stanza_ps_aggregate", "stanza_ps_aggregate_ordered_planned", "stanza_ps_aggregate_ordered",
     "stanza_model_allreduce_rounds", "stanza_model_stanza_time", "stanza_model_stanza_throughput", "stanza_model_assign",
     "stanza_model_ps_time", "stanza_model_ps_throughput",
@@ -84,6 +84,7 @@ def load() -> C.CDLL:
     lib.stanza_fc_workspace_bytes.restype = sz
     lib.stanza_fc_workspace_bytes.argtypes = [C.POINTER(FcDesc)]
     lib.stanza_fc_step.argtypes = [C.POINTER(FcDesc), vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.stanza_fc_grads.argtypes = [C.POINTER(FcDesc), i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.stanza_ps_workspace_bytes.restype = sz
     lib.stanza_ps_workspace_bytes.argtypes = [i32, i32]
     lib.stanza_ps_plan.argtypes = [i32, vp, vp, vp, vp, i32, vp, sz, vp]
@@ -215,6 +216,13 @@ def stanza_fc_step(plan: FcPlan, feats, labels, W: List[torch.Tensor], b, vW, vb
     p, n = _ws(ws)
     _check(load().stanza_fc_step(C.byref(plan.desc), _ptr(feats), _ptr(labels), _ptr_array(W), _ptr_array(b), _ptr_array(vW),
                                  _ptr_array(vb), _ptr(dfeats), _ptr(loss), _ptr(pred), p, n, _stream()), "stanza_fc_step")
+
+
+def stanza_fc_grads(plan: FcPlan, n_global: int, feats, labels, W: List[torch.Tensor], b, gW, gb, dfeats, loss_part, pred, ws):
+    p, n = _ws(ws)
+    _check(load().stanza_fc_grads(C.byref(plan.desc), n_global, _ptr(feats), _ptr(labels), _ptr_array(W), _ptr_array(b),
+                                  _ptr_array(gW), _ptr_array(gb), _ptr(dfeats), _ptr(loss_part), _ptr(pred), p, n, _stream()),
+           "stanza_fc_grads")
 
 
 def stanza_ps_workspace_bytes(n_tensors: int, K: int) -> int:

@@ -14,8 +14,9 @@ namespace stanza {
 
 // One wavefront per row: max / argmax (lowest index wins ties), sum of exponentials, then the gradient
 // (softmax - onehot)/n and the row's loss term  log(sum) + max - z[label].
-__global__ __launch_bounds__(256) void softmax_ce_kernel(int n, int classes, const float *__restrict__ z, const int32_t *__restrict__ labels,
-                                                         float *__restrict__ dz, float *__restrict__ row_loss, int32_t *__restrict__ pred)
+__global__ __launch_bounds__(256) void softmax_ce_kernel(int n, int n_global, int classes, const float *__restrict__ z,
+                                                         const int32_t *__restrict__ labels, float *__restrict__ dz,
+                                                         float *__restrict__ row_loss, int32_t *__restrict__ pred)
 {
     const int lane = threadIdx.x & 63;
     const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
@@ -38,7 +39,7 @@ __global__ __launch_bounds__(256) void softmax_ce_kernel(int n, int classes, con
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) sum += __shfl_xor(sum, off);
     const int label = labels[row];
-    const float inv = 1.f / sum, invn = 1.f / (float)n;
+    const float inv = 1.f / sum, invn = 1.f / (float)n_global;
     float *dr = dz + (size_t)row * classes;
     for (int j = lane; j < classes; j += 64) {
         const float sm = expf(zr[j] - best) * inv;
@@ -51,8 +52,8 @@ __global__ __launch_bounds__(256) void softmax_ce_kernel(int n, int classes, con
     }
 }
 
-// Mean of the row losses, summed in a fixed order by one workgroup.
-__global__ __launch_bounds__(256) void mean_loss_kernel(int n, const float *__restrict__ row_loss, float *__restrict__ loss)
+// Sum of the n row losses divided by n_global (the mean when the worker holds the whole batch), in a fixed order.
+__global__ __launch_bounds__(256) void mean_loss_kernel(int n, int n_global, const float *__restrict__ row_loss, float *__restrict__ loss)
 {
     __shared__ float red[256];
     float s = 0.f;
@@ -63,7 +64,7 @@ __global__ __launch_bounds__(256) void mean_loss_kernel(int n, const float *__re
         if (threadIdx.x < w) red[threadIdx.x] += red[threadIdx.x + w];
         __syncthreads();
     }
-    if (threadIdx.x == 0) *loss = red[0] / (float)n;
+    if (threadIdx.x == 0) *loss = red[0] / (float)n_global;
 }
 
 struct FcLayout {
@@ -120,21 +121,27 @@ extern "C" size_t stanza_fc_workspace_bytes(const stanza_fc_desc *desc)
     return lay.floats * 4;
 }
 
-extern "C" int stanza_fc_step(const stanza_fc_desc *desc, const float *feats, const int32_t *labels, float *const *host_W,
-                              float *const *host_b, float *const *host_vW, float *const *host_vb, float *dfeats, float *loss,
-                              int32_t *pred, void *ws, size_t ws_bytes, void *stream)
+// Shared body of stanza_fc_step (update fused, gW == nullptr) and stanza_fc_grads (gradients written to gW / gb, no
+// update, loss and gradient normalised by n_global).
+static int fc_run(const stanza_fc_desc *desc, int n_global, const float *feats, const int32_t *labels, float *const *host_W,
+                  float *const *host_b, float *const *host_vW, float *const *host_vb, float *const *host_gW, float *const *host_gb,
+                  float *dfeats, float *loss, int32_t *pred, void *ws, size_t ws_bytes, void *stream)
 {
+    const bool fused = host_gW == nullptr;
     FcLayout lay;
     int rc = fc_layout(desc, &lay);
     if (rc) return rc;
-    if (!feats || !labels || !host_W || !host_b || !host_vW || !host_vb || !dfeats || !loss || !ws) return STANZA_ENULL;
+    if (n_global < desc->n_samples) return STANZA_EINVAL;
+    if (!feats || !labels || !host_W || !host_b || !dfeats || !loss || !ws) return STANZA_ENULL;
+    if (fused ? (!host_vW || !host_vb) : !host_gb) return STANZA_ENULL;
     if (ws_bytes < lay.floats * 4) return STANZA_EWORKSPACE;
     if (!aligned16(feats) || !aligned16(dfeats) || !aligned16(ws)) return STANZA_EALIGN;
     const int L = desc->n_layers, n = desc->n_samples;
     const int32_t *dims = desc->host_dims;
     for (int l = 0; l < L; ++l) {
-        if (!host_W[l] || !host_b[l] || !host_vW[l] || !host_vb[l]) return STANZA_ENULL;
-        if (!aligned16(host_W[l]) || !aligned16(host_vW[l])) return STANZA_EALIGN;
+        if (!host_W[l] || !host_b[l]) return STANZA_ENULL;
+        if (fused ? (!host_vW[l] || !host_vb[l]) : (!host_gW[l] || !host_gb[l])) return STANZA_ENULL;
+        if (!aligned16(host_W[l]) || !aligned16(fused ? host_vW[l] : host_gW[l])) return STANZA_EALIGN;
     }
     hipStream_t st = (hipStream_t)stream;
     float *base = (float *)ws;
@@ -155,11 +162,11 @@ extern "C" int stanza_fc_step(const stanza_fc_desc *desc, const float *feats, co
     // loss and its gradient
     float *dz = base + lay.dz_off[0], *dz_next = base + lay.dz_off[1];
     float *row_loss = base + lay.row_loss_off;
-    hipLaunchKernelGGL(softmax_ce_kernel, dim3(cdiv(n, 4)), dim3(256), 0, st, n, dims[L], act(L), labels, dz, row_loss, pred);
+    hipLaunchKernelGGL(softmax_ce_kernel, dim3(cdiv(n, 4)), dim3(256), 0, st, n, n_global, dims[L], act(L), labels, dz, row_loss, pred);
     if ((rc = launch_status())) return rc;
-    hipLaunchKernelGGL(mean_loss_kernel, dim3(1), dim3(256), 0, st, n, row_loss, loss);
+    hipLaunchKernelGGL(mean_loss_kernel, dim3(1), dim3(256), 0, st, n, n_global, row_loss, loss);
     if ((rc = launch_status())) return rc;
-    // backward + update, last layer first
+    // backward (+ update), last layer first
     const int dbb = colsum_blocks(n);
     for (int l = L; l >= 1; --l) {
         const int in = dims[l - 1], out = dims[l];
@@ -174,22 +181,47 @@ extern "C" int stanza_fc_step(const stanza_fc_desc *desc, const float *feats, co
             p.flags = p.xmask ? EPI_XMASK : 0u;
             if ((rc = launch_igemm(MODE_BWD_DATA, p, 1, base + lay.partial_off, lay.partial_floats, st))) return rc;
         }
-        {   // weight gradient fused with the update
+        {   // weight gradient: fused with the update, or written out
             GemmParams p{};
             p.g = fc_geo(n, in, out);
             p.a = dz;
             p.b = act(l - 1);
             p.M = out; p.Nn = in; p.Kd = n;
-            p.chunks_per_split = cdiv(n, BK);
-            p.flags = EPI_SGD;
-            p.sgd_w = host_W[l - 1]; p.sgd_v = host_vW[l - 1];
-            p.lr = desc->lr; p.mom = desc->momentum; p.wd = desc->weight_decay;
+            if (fused) {
+                p.flags = EPI_SGD;
+                p.sgd_w = host_W[l - 1]; p.sgd_v = host_vW[l - 1];
+                p.lr = desc->lr; p.mom = desc->momentum; p.wd = desc->weight_decay;
+            } else {
+                p.out = host_gW[l - 1];
+            }
             if ((rc = launch_igemm(MODE_BWD_WEIGHT, p, 1, nullptr, 0, st))) return rc;
         }
-        if ((rc = launch_colsum(dz, nullptr, n, out, base + lay.db_off, dbb, nullptr, host_b[l - 1], host_vb[l - 1], desc->lr,
-                                desc->momentum, desc->weight_decay, st)))
-            return rc;
+        if (fused)
+            rc = launch_colsum(dz, nullptr, n, out, base + lay.db_off, dbb, nullptr, host_b[l - 1], host_vb[l - 1], desc->lr,
+                               desc->momentum, desc->weight_decay, st);
+        else
+            rc = launch_colsum(dz, nullptr, n, out, base + lay.db_off, dbb, host_gb[l - 1], nullptr, nullptr, 0.f, 0.f, 0.f, st);
+        if (rc) return rc;
         float *tmp = dz; dz = dz_next; dz_next = tmp;
     }
     return STANZA_OK;
+}
+
+extern "C" int stanza_fc_step(const stanza_fc_desc *desc, const float *feats, const int32_t *labels, float *const *host_W,
+                              float *const *host_b, float *const *host_vW, float *const *host_vb, float *dfeats, float *loss,
+                              int32_t *pred, void *ws, size_t ws_bytes, void *stream)
+{
+    if (!desc) return STANZA_ENULL;
+    return fc_run(desc, desc->n_samples, feats, labels, host_W, host_b, host_vW, host_vb, nullptr, nullptr, dfeats, loss, pred, ws,
+                  ws_bytes, stream);
+}
+
+extern "C" int stanza_fc_grads(const stanza_fc_desc *desc, int32_t n_global, const float *feats, const int32_t *labels,
+                               float *const *host_W, float *const *host_b, float *const *host_gW, float *const *host_gb,
+                               float *dfeats, float *loss_part, int32_t *pred, void *ws, size_t ws_bytes, void *stream)
+{
+    if (!desc) return STANZA_ENULL;
+    if (!host_gW) return STANZA_ENULL;
+    return fc_run(desc, n_global, feats, labels, host_W, host_b, nullptr, nullptr, host_gW, host_gb, dfeats, loss_part, pred, ws,
+                  ws_bytes, stream);
 }

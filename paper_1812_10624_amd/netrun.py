@@ -195,6 +195,29 @@ class FcWorker:
         return self.dfeats
 
 
+class FcGradWorker:
+    """One of several FC workers: forward, its share of the global-mean loss, backward; gradients are written out
+    (no update) for the all-reduce among the FC workers.  n_samples rows are its own, n_global the whole batch."""
+
+    def __init__(self, dims: List[int], n_samples: int, n_global: int, fc_params, device="cuda:0"):
+        self.dev = torch.device(device)
+        self.plan = api.FcPlan(dims, n_samples, 0.0, 0.0, 0.0)
+        self.n_global = n_global
+        self.W = [w for w, _ in fc_params]
+        self.b = [b for _, b in fc_params]
+        self.gW = [torch.empty_like(w) for w in self.W]
+        self.gb = [torch.empty_like(b) for b in self.b]
+        self.ws = torch.empty(self.plan.workspace_bytes(), device=self.dev, dtype=torch.uint8)
+        self.dfeats = torch.empty((n_samples, dims[0]), device=self.dev, dtype=torch.float32)
+        self.loss = torch.zeros(1, device=self.dev, dtype=torch.float32)
+        self.pred = torch.empty(n_samples, device=self.dev, dtype=torch.int32)
+
+    def step(self, feats: torch.Tensor, labels: torch.Tensor):
+        api.stanza_fc_grads(self.plan, self.n_global, feats, labels, self.W, self.b, self.gW, self.gb, self.dfeats, self.loss,
+                            self.pred, self.ws)
+        return self.dfeats
+
+
 class Aggregator:
     """Sum of K workers' gradient shards + momentum-SGD update over a list of parameter tensors."""
 
@@ -203,5 +226,5 @@ class Aggregator:
         self.ws = torch.empty(api.stanza_ps_workspace_bytes(len(w), len(grads)), device=device, dtype=torch.uint8)
         self.plan = api.stanza_ps_plan(w, v, grads, self.ws)
 
-    def step(self, scale, lr, momentum, weight_decay):
-        api.stanza_ps_aggregate_planned(self.plan, scale, lr, momentum, weight_decay, self.ws)
+    def step(self, scale, lr, momentum, weight_decay, order=api.SUM_INDEX_ORDER):
+        api.stanza_ps_aggregate_ordered_planned(order, self.plan, scale, lr, momentum, weight_decay, self.ws)

@@ -92,6 +92,9 @@ def test_fc_and_ps_errors(api):
     assert lib.stanza_fc_step(C.byref(plan.desc), None, p16, arr, arr, arr, arr, p16, p16, None, p16, need, None) == -2
     nullarr = (C.c_void_p * 2)(0x1000, None)
     assert lib.stanza_fc_step(C.byref(plan.desc), p16, p16, nullarr, arr, arr, arr, p16, p16, None, p16, need, None) == -2
+    assert lib.stanza_fc_grads(C.byref(plan.desc), 7, p16, p16, arr, arr, arr, arr, p16, p16, None, p16, need, None) == -1   # n_global < rows
+    assert lib.stanza_fc_grads(C.byref(plan.desc), 16, p16, p16, arr, arr, None, arr, p16, p16, None, p16, need, None) == -2
+    assert lib.stanza_fc_grads(C.byref(plan.desc), 16, p16, p16, arr, arr, arr, arr, p16, p16, None, p16, need - 1, None) == -5
     bad = api.FcPlan([64, 0, 10], 8, 0.01, 0.9, 0.0)
     assert bad.workspace_bytes() == 0
     assert lib.stanza_ps_workspace_bytes(0, 4) == 0

@@ -468,3 +468,63 @@ def test_error_paths_on_device(api):
     d16 = api.conv_desc(1, 8, 8, 4, 4, 3, 3, 1, 1, api.BF16, 0)
     with pytest.raises(api.StanzaError):
         api.stanza_conv_fwd(d16, x, w, None, y)
+
+
+@pytest.mark.parametrize("name,K,n_f", [("tiny", 4, 2), ("minimlp", 6, 3)])
+def test_several_fc_workers(api, o32, name, K, n_f):
+    """Sec. 4.1.3 on the GPU: K CONV workers in n_f groups, one stanza_fc_grads per FC worker, recursive-doubling
+    aggregation of the FC workers' gradient sets and of the CONV workers', against the checker's same iteration."""
+    from paper_1812_10624_amd.netrun import Aggregator, ConvWorker, FcGradWorker
+    wl = wl_mod.get_workload(name)
+    B, seed = wl.B, 3
+    n, per = K * B, K // n_f
+    imgs = [wl_mod.gen_images(wl, seed, k) for k in range(K)]
+    labels = wl_mod.gen_labels(wl, seed, n)
+    cp, fp = wl_mod.gen_conv_params(wl, seed), wl_mod.gen_fc_params(wl, seed)
+    r = rng(8)
+    cm = {nm: (r.standard_normal(w.shape, dtype=np.float32) * np.float32(1e-2), r.standard_normal(b.shape, dtype=np.float32) * np.float32(1e-2))
+          for nm, (w, b) in cp.items()}
+    fm = [(r.standard_normal(w.shape, dtype=np.float32) * np.float32(1e-2), r.standard_normal(b.shape, dtype=np.float32) * np.float32(1e-2))
+          for w, b in fp]
+    cp_ref, cm_ref, fp_ref, fm_ref = (copy.deepcopy(a) for a in (cp, cm, fp, fm))
+    ref = onet.multi_fc_split_step(o32, wl.ops, imgs, labels, cp_ref, cm_ref, fp_ref, fm_ref, wl.lr, 0.9, 1e-4, n_f)
+
+    gpar, gcm = _gpu_params(cp), _gpu_params(cm)
+    gfp = [(dev(w), dev(b)) for w, b in fp]
+    gfm = [(dev(w), dev(b)) for w, b in fm]
+    workers = [ConvWorker(wl.ops, wl.image, B, gpar) for _ in range(K)]
+    fcs = [FcGradWorker(wl.fc_dims, per * B, n, gfp) for _ in range(n_f)]
+    feats = torch.empty((n, wl.fc_dims[0]), device="cuda:0")
+    for k, wk in enumerate(workers):
+        feats[k * B:(k + 1) * B].copy_(wk.forward(dev(imgs[k])).view(B, -1))
+    glab = dev(labels)
+    loss = 0.0
+    for f, fw in enumerate(fcs):
+        rows = slice(f * per * B, (f + 1) * per * B)
+        fw.step(feats[rows], glab[rows])
+        loss += float(host(fw.loss)[0])
+        np.testing.assert_array_equal(host(fw.pred), ref["pred"][rows])
+        assert rel_err(host(fw.dfeats), ref["dfeats"][rows]) < TOL_F32
+        for li in range(len(fp)):
+            assert rel_err(host(fw.gW[li]), ref["fc_worker_grads"][f][li][0]) < 5 * TOL_F32, (f, li)
+            assert rel_err(host(fw.gb[li]), ref["fc_worker_grads"][f][li][1]) < 5 * TOL_F32, (f, li)
+    assert abs(loss - ref["loss"]) < 1e-5 * max(1.0, abs(ref["loss"]))
+    for k, wk in enumerate(workers):
+        f = k // per
+        wk.backward(fcs[f].dfeats[(k - f * per) * B:(k - f * per + 1) * B])
+    # all-reduce + update among the FC workers, then among the CONV workers, both in recursive-doubling order
+    fc_agg = Aggregator([t for pair in gfp for t in pair], [t for pair in gfm for t in pair],
+                        [[t for li in range(len(fp)) for t in (fw.gW[li], fw.gb[li])] for fw in fcs])
+    fc_agg.step(1.0, wl.lr, 0.9, 1e-4, api.SUM_RECURSIVE_DOUBLING)
+    names = list(cp)
+    agg = Aggregator([gpar[nm][i] for nm in names for i in range(2)], [gcm[nm][i] for nm in names for i in range(2)],
+                     [[wk.grads[nm][i] for nm in names for i in range(2)] for wk in workers])
+    agg.step(1.0, wl.lr, 0.9, 1e-4, api.SUM_RECURSIVE_DOUBLING)
+    for li in range(len(fp)):
+        for i in range(2):
+            assert rel_err(host(gfm[li][i]), fm_ref[li][i]) < 5 * TOL_F32, (li, i)
+            assert rel_err(host(gfp[li][i]) - fp[li][i], fp_ref[li][i] - fp[li][i]) < 10 * TOL_F32, (li, i)
+    for nm in names:
+        for i in range(2):
+            assert rel_err(host(gcm[nm][i]), cm_ref[nm][i]) < 5 * TOL_F32, (nm, i)
+            assert rel_err(host(gpar[nm][i]), cp_ref[nm][i]) < 1e-5, (nm, i)
