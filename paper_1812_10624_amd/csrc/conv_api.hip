@@ -22,6 +22,23 @@ int conv_geometry(const stanza_conv_desc *d, ConvGeo *g)
     return STANZA_OK;
 }
 
+// BWD_DATA: the stride class the rows of a launch stand for.  A caller that leaves p.sub unset gets the single class of a
+// unit-stride layer; the divisors of the tap decode follow the class.
+static int prepare_stride_class(GemmParams &p, int bk)
+{
+    const ConvGeo &g = p.g;
+    if (p.sub.Hc == 0) {
+        if (g.sh != 1 || g.sw != 1) return STANZA_EINVAL;
+        p.sub = StrideClass{0, 0, g.H, g.W, g.ph, g.pw, 0, 0, g.R, g.S};
+    }
+    p.fd_s = make_fastdiv(max(1, p.sub.Sc));
+    p.fd_rs = make_fastdiv(max(1, p.sub.Rc * p.sub.Sc));
+    p.fd_hcwc = make_fastdiv(p.sub.Hc * p.sub.Wc);
+    p.fd_wc = make_fastdiv(p.sub.Wc);
+    if (p.sub.Rc * p.sub.Sc > 1 && g.K % bk == 0) p.flags |= ORDER_TAP_MINOR;
+    return STANZA_OK;
+}
+
 // ------------------------------------------------------------------ tile choice, work-item plan and launch
 constexpr int CUS = 256;   // compute units of the MI355X this library is written for
 
@@ -175,7 +192,7 @@ static int launch_tile(GemmParams &p, const GemmPlan &pl, bool veca, bool vecb, 
     dim3 grid((unsigned)(cdiv(pl.dp_tiles, 8) * 8 + cdiv(pl.split_tiles * pl.splits, 8) * 8));
     const ConvGeo &g = p.g;
     const bool fast = veca && vecb &&
-                      ((MODE == MODE_FWD && g.C % BK == 0) || (MODE == MODE_BWD_DATA && g.K % BK == 0 && g.sh == 1 && g.sw == 1));
+                      ((MODE == MODE_FWD && g.C % BK == 0) || (MODE == MODE_BWD_DATA && g.K % BK == 0));
     if (MODE != MODE_BWD_WEIGHT && fast)
         hipLaunchKernelGGL((igemm_kernel<MODE, BM, BN, WM, WN, true, true, MODE != MODE_BWD_WEIGHT>), grid, dim3(NTHREADS), 0, st, p);
     else if (veca && vecb)
@@ -207,7 +224,9 @@ static int launch_mode(GemmParams &p, const GemmPlan &pl, bool veca, bool vecb, 
 int launch_igemm(int mode, GemmParams &p, int bw_splits, float *partial, size_t partial_floats, hipStream_t st)
 {
     const ConvGeo &g = p.g;
-    if (p.M <= 0 || p.Nn <= 0 || p.Kd <= 0 || bw_splits <= 0) return STANZA_EINVAL;
+    // Kd == 0: a stride class of BWD_DATA that no tap reaches (the result is zero, the epilogue still runs)
+    if (p.M <= 0 || p.Nn <= 0 || p.Kd < 0 || (p.Kd == 0 && mode != MODE_BWD_DATA) || bw_splits <= 0) return STANZA_EINVAL;
+    if (p.flags & OUT_STRIDED) partial = nullptr;      // the fix-up kernel writes dense rows only
     GemmPlan pl = plan_gemm(mode, p.M, p.Nn, p.Kd, bw_splits, partial != nullptr);
     if (pl.partial_floats > partial_floats) pl = plan_gemm(mode, p.M, p.Nn, p.Kd, bw_splits, false);
     p.partial = partial;
@@ -217,7 +236,11 @@ int launch_igemm(int mode, GemmParams &p, int bw_splits, float *partial, size_t 
     p.fd_howo = make_fastdiv(g.Ho * g.Wo);
     p.fd_wo = make_fastdiv(g.Wo);
     p.fd_rs = make_fastdiv(g.R * g.S);
-    if (g.R * g.S > 1 && ((mode == MODE_FWD && g.C % BK == 0) || (mode == MODE_BWD_DATA && g.K % BK == 0))) p.flags |= ORDER_TAP_MINOR;
+    if (g.R * g.S > 1 && mode == MODE_FWD && g.C % BK == 0) p.flags |= ORDER_TAP_MINOR;
+    if (mode == MODE_BWD_DATA) {
+        const int rc = prepare_stride_class(p, BK);
+        if (rc) return rc;
+    }
     // extents of the two gathered tensors; the vector fetch paths address them with 32-bit byte offsets below 2 GiB
     const int64_t xb = (int64_t)g.N * g.H * g.W * g.C * 4, yb = (int64_t)g.N * g.Ho * g.Wo * g.K * 4, wb = (int64_t)g.K * g.R * g.S * g.C * 4;
     const int64_t ab = mode == MODE_FWD ? xb : yb, bb = mode == MODE_BWD_WEIGHT ? xb : wb;
@@ -244,7 +267,7 @@ static int launch_tile_bf16(GemmParams &p, int splits, hipStream_t st)
     dim3 grid((unsigned)(cdiv(p.tiles * splits, 8) * 8));
     const ConvGeo &g = p.g;
     // a stage that stays inside one filter tap: wavefront-uniform tap decode, no per-thread division in the main loop
-    const bool fast = (MODE == MODE_FWD && g.C % BKH == 0) || (MODE == MODE_BWD_DATA && g.K % BKH == 0 && g.sh == 1 && g.sw == 1);
+    const bool fast = (MODE == MODE_FWD && g.C % BKH == 0) || (MODE == MODE_BWD_DATA && g.K % BKH == 0);
     if (MODE != MODE_BWD_WEIGHT && fast)
         hipLaunchKernelGGL((igemm_bf16_kernel<MODE, BM, BN, WM, WN, MODE != MODE_BWD_WEIGHT>), grid, dim3(NTHREADS), 0, st, p);
     else
@@ -266,7 +289,7 @@ static int launch_mode_bf16(GemmParams &p, int splits, hipStream_t st)
 int launch_igemm_bf16(int mode, GemmParams &p, int splits, hipStream_t st)
 {
     const ConvGeo &g = p.g;
-    if (p.M <= 0 || p.Nn <= 0 || p.Kd <= 0 || splits <= 0) return STANZA_EINVAL;
+    if (p.M <= 0 || p.Nn <= 0 || p.Kd < 0 || (p.Kd == 0 && mode != MODE_BWD_DATA) || splits <= 0) return STANZA_EINVAL;
     if (g.C % 8 || g.K % 8) return STANZA_EUNSUPPORTED;
     p.fd_c = make_fastdiv(g.C);
     p.fd_k = make_fastdiv(g.K);
@@ -274,6 +297,10 @@ int launch_igemm_bf16(int mode, GemmParams &p, int splits, hipStream_t st)
     p.fd_howo = make_fastdiv(g.Ho * g.Wo);
     p.fd_wo = make_fastdiv(g.Wo);
     p.fd_rs = make_fastdiv(g.R * g.S);
+    if (mode == MODE_BWD_DATA) {
+        const int rc = prepare_stride_class(p, BKH);
+        if (rc) return rc;
+    }
     // the gathered tensors are addressed with 32-bit byte offsets below 2 GiB (an offset of 2 GiB marks a masked lane)
     const int64_t xb = (int64_t)g.N * g.H * g.W * g.C * 2, yb = (int64_t)g.N * g.Ho * g.Wo * g.K * 2, wb = (int64_t)g.K * g.R * g.S * g.C * 2;
     const int64_t ab = mode == MODE_FWD ? xb : yb, bb = mode == MODE_BWD_WEIGHT ? xb : wb;
@@ -456,11 +483,42 @@ extern "C" int stanza_conv_bwd_data(const stanza_conv_desc *desc, const void *dy
     p.b = (const float *)w;
     p.out = (float *)dx;
     p.xmask = (const float *)x_mask;
-    p.M = p.g.N * p.g.H * p.g.W;
     p.Nn = p.g.C;
-    p.Kd = p.g.R * p.g.S * p.g.K;
     p.flags = ((desc->flags & STANZA_CONV_ACCUM) ? EPI_ACCUM : 0u) | (x_mask ? EPI_XMASK : 0u) | (p.amask ? LOAD_AMASK : 0u);
-    return launch_any(desc, MODE_BWD_DATA, p, 1, ws, ws_bytes, (hipStream_t)stream);
+    const ConvGeo &g = p.g;
+    if (g.sh == 1 && g.sw == 1) {
+        p.M = g.N * g.H * g.W;
+        p.Kd = g.R * g.S * g.K;
+        return launch_any(desc, MODE_BWD_DATA, p, 1, ws, ws_bytes, (hipStream_t)stream);
+    }
+    // Strided layer: one launch per stride class (a, b) = ((h + pad_h) mod stride_h, (w + pad_w) mod stride_w) of the input
+    // pixels.  A pixel of class (a, b) only receives the taps r = a, a + stride_h, ..., s = b, b + stride_w, ...; gathering them
+    // class by class multiplies no zeros (a 3x3 stride-2 layer has classes of 4, 2, 2 and 1 taps instead of 9 taps of which
+    // three quarters miss).  The classes write disjoint pixels and together cover dx.
+    for (int a = 0; a < g.sh; ++a) {
+        for (int b = 0; b < g.sw; ++b) {
+            GemmParams q = p;
+            StrideClass &c = q.sub;
+            c.h0 = ((a - g.ph) % g.sh + g.sh) % g.sh;
+            c.w0 = ((b - g.pw) % g.sw + g.sw) % g.sw;
+            if (c.h0 >= g.H || c.w0 >= g.W) continue;
+            c.Hc = (g.H - c.h0 + g.sh - 1) / g.sh;
+            c.Wc = (g.W - c.w0 + g.sw - 1) / g.sw;
+            c.pa = (c.h0 + g.ph - a) / g.sh;
+            c.qb = (c.w0 + g.pw - b) / g.sw;
+            c.r0 = a;
+            c.s0 = b;
+            c.Rc = a < g.R ? (g.R - a + g.sh - 1) / g.sh : 0;
+            c.Sc = b < g.S ? (g.S - b + g.sw - 1) / g.sw : 0;
+            if (c.Rc == 0 || c.Sc == 0) c.Rc = c.Sc = 0;
+            q.M = g.N * c.Hc * c.Wc;
+            q.Kd = c.Rc * c.Sc * g.K;
+            q.flags |= OUT_STRIDED;
+            rc = launch_any(desc, MODE_BWD_DATA, q, 1, nullptr, 0, (hipStream_t)stream);
+            if (rc) return rc;
+        }
+    }
+    return STANZA_OK;
 }
 
 extern "C" int stanza_conv_bwd_weight(const stanza_conv_desc *desc, const void *x, const void *dy, const void *y, float *dw,

@@ -41,6 +41,7 @@ enum : uint32_t {
     EPI_SGD = 16u,     // BWD_WEIGHT: fused momentum-SGD update of sgd_w / sgd_v with the tile as gradient
     LOAD_AMASK = 32u,  // BWD_*: dy is gated by [amask > 0] as it is read
     EPI_DBIAS = 64u,   // BWD_WEIGHT: column-tile-0 workgroups also sum dy over their reduction slice (bias gradient)
+    OUT_STRIDED = 256u,     // BWD_DATA: the rows of this launch are one stride class of a strided layer (scattered dx pixels)
     ORDER_TAP_MINOR = 128u  // FWD / BWD_DATA: visit the reduction channel-block-major, tap-minor (needs channels % BK == 0)
 };
 
@@ -63,9 +64,20 @@ __host__ inline FastDiv make_fastdiv(uint32_t d)
 }
 __device__ __forceinline__ int fdiv(int n, FastDiv f) { return (int)(((uint64_t)(uint32_t)n * f.mul) >> f.sh); }
 
+// BWD_DATA works on one stride class of the input pixels at a time: the pixels (h0 + i*sh, w0 + j*sw), 0 <= i < Hc, 0 <= j < Wc,
+// all of which receive contributions from the same taps (r0 + tr*sh, s0 + ts*sw), 0 <= tr < Rc, 0 <= ts < Sc, namely from the
+// output pixels (pa + i - tr, qb + j - ts).  Within a class the adjoint is a unit-stride problem and no tap is ever skipped
+// for a stride mismatch.  A unit-stride layer is the single class h0 = w0 = r0 = s0 = 0, Hc = H, Wc = W, Rc = R, Sc = S,
+// pa = pad_h, qb = pad_w.
+struct StrideClass {
+    int h0, w0, Hc, Wc, pa, qb, r0, s0, Rc, Sc;
+};
+
 struct GemmParams {
     ConvGeo g;
-    FastDiv fd_c, fd_k, fd_s, fd_howo, fd_wo, fd_rs;   // divisors C, K, S, Ho*Wo, Wo, R*S
+    StrideClass sub;      // BWD_DATA only
+    FastDiv fd_c, fd_k, fd_s, fd_howo, fd_wo, fd_rs;   // divisors C, K, S, Ho*Wo, Wo, R*S (BWD_DATA: Sc and Rc*Sc of the class)
+    FastDiv fd_hcwc, fd_wc;                            // BWD_DATA epilogue of a strided layer: Hc*Wc, Wc
     const float *a;       // FWD: x      BWD_DATA: dy   BWD_WEIGHT: dy
     const float *amask;   // BWD_*: forward output y gating dy, or nullptr
     const float *b;       // FWD: w      BWD_DATA: w    BWD_WEIGHT: x
@@ -114,17 +126,7 @@ __device__ __forceinline__ float4 gate4(float4 v, float4 m)
     return make_float4(m.x > 0.f ? v.x : 0.f, m.y > 0.f ? v.y : 0.f, m.z > 0.f ? v.z : 0.f, m.w > 0.f ? v.w : 0.f);
 }
 
-// Exact quotient test for the strided adjoint: hp = p*stride with 0 <= p < limit.
-__device__ __forceinline__ bool strided_src(int hp, int stride, int limit, int &p)
-{
-    if (stride == 1) { p = hp; return (unsigned)hp < (unsigned)limit; }
-    if (hp < 0) { p = 0; return false; }
-    if (stride == 2) { p = hp >> 1; return !(hp & 1) && p < limit; }
-    p = hp / stride;
-    return (hp - p * stride == 0) && p < limit;
-}
-
-// FAST (FWD / BWD_DATA with both vector paths, channel count a multiple of BK, unit stride for BWD_DATA): a stage lies
+// FAST (FWD / BWD_DATA with both vector paths, channel count a multiple of BK): a stage lies
 // inside one filter tap, so the tap is wavefront-uniform (scalar registers) and a row's address is a precomputed row
 // offset plus a scalar; no per-thread division or multiplication is left in the main loop.
 template <int MODE, int BM, int BN, int WM, int WN, bool VECA, bool VECB, bool FAST = false>
@@ -168,6 +170,9 @@ __global__ __launch_bounds__(NTHREADS) void igemm_kernel(const GemmParams p)
     const int m0 = tile_m * BM, n0 = tile_n * BN;
 
     const ConvGeo &g = p.g;
+    // taps the reduction runs over: all of them, or those of the stride class (BWD_DATA)
+    const int tapS = MODE == MODE_BWD_DATA ? p.sub.Sc : g.S;
+    const int tapRS = MODE == MODE_BWD_DATA ? p.sub.Rc * p.sub.Sc : g.R * g.S;
     const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
     const int wave_m = wave / WN, wave_n = wave % WN;
 
@@ -211,19 +216,19 @@ __global__ __launch_bounds__(NTHREADS) void igemm_kernel(const GemmParams p)
 #pragma unroll
         for (int i = 0; i < BV; ++i) b_row[i] = (n0 + row0 + RPP * i) * p.Kd + kq * 4;
     } else if (MODE == MODE_BWD_DATA) {
-        const int HW = g.H * g.W;
+        const int HW = p.sub.Hc * p.sub.Wc;
 #pragma unroll
         for (int i = 0; i < AV; ++i) {
             const int m = m0 + row0 + RPP * i;
             if (m < p.M) {
-                const int n = m / HW, hw = m - n * HW, h = hw / g.W, w = hw - h * g.W;
-                a_hb[i] = h + g.ph;
-                a_wb[i] = w + g.pw;
+                const int n = m / HW, hw = m - n * HW, ci = hw / p.sub.Wc, cj = hw - ci * p.sub.Wc;
+                a_hb[i] = ci + p.sub.pa;
+                a_wb[i] = cj + p.sub.qb;
                 a_base[i] = n * g.Ho * g.Wo * g.K;
             } else {
                 a_hb[i] = -(1 << 28); a_wb[i] = 0; a_base[i] = 0;
             }
-            a_row[i] = m < p.M ? a_base[i] + (a_hb[i] * g.Wo + a_wb[i]) * g.K + kq * 4 : 0;   // unit stride: p = h+ph-r, q = w+pw-s
+            a_row[i] = m < p.M ? a_base[i] + (a_hb[i] * g.Wo + a_wb[i]) * g.K + kq * 4 : 0;   // source pixel of tap (0,0) of the class
         }
 #pragma unroll
         for (int i = 0; i < BV; ++i)   // w[k][r][s][c] at k = reduction row of this thread, tap (0,0), its 4 columns
@@ -258,7 +263,7 @@ __global__ __launch_bounds__(NTHREADS) void igemm_kernel(const GemmParams p)
     const bool tap_minor = MODE != MODE_BWD_WEIGHT && (FAST || (p.flags & ORDER_TAP_MINOR));
     auto stage_k = [&](int ch) -> int {
         if (!tap_minor) return ch * BK;
-        const int cblk = fdiv(ch, p.fd_rs), tap = ch - cblk * (g.R * g.S);
+        const int cblk = fdiv(ch, p.fd_rs), tap = ch - cblk * tapRS;
         return tap * (MODE == MODE_FWD ? g.C : g.K) + cblk * BK;
     };
 
@@ -266,8 +271,8 @@ __global__ __launch_bounds__(NTHREADS) void igemm_kernel(const GemmParams p)
     auto fetch_a = [&](int ch, int i) {
         if (FAST) {
             // wavefront-uniform: channel block and tap of the stage
-            const int cblk = fdiv(ch, p.fd_rs), tap = ch - cblk * (g.R * g.S);
-            const int ar = fdiv(tap, p.fd_s), as = tap - ar * g.S;
+            const int cblk = fdiv(ch, p.fd_rs), tap = ch - cblk * tapRS;
+            const int ar = fdiv(tap, p.fd_s), as = tap - ar * tapS;
             const bool kok = ch < ch_end;
             int off;
             bool ok;
@@ -289,7 +294,7 @@ __global__ __launch_bounds__(NTHREADS) void igemm_kernel(const GemmParams p)
             if (VECA) {
                 const int kk = kchunk + kq * 4;
                 const int rs = fdiv(kk, MODE == MODE_FWD ? p.fd_c : p.fd_k), cc = kk - rs * CC;
-                const int ar = fdiv(rs, p.fd_s), as = rs - ar * g.S;
+                const int ar = fdiv(rs, p.fd_s), as = rs - ar * tapS;
                 int off;
                 bool ok;
                 if (MODE == MODE_FWD) {
@@ -297,9 +302,8 @@ __global__ __launch_bounds__(NTHREADS) void igemm_kernel(const GemmParams p)
                     ok = kk < p.Kd && (unsigned)h < (unsigned)g.H && (unsigned)w < (unsigned)g.W;
                     off = a_base[i] + (h * g.W + w) * g.C + cc;
                 } else {
-                    int pp, q;
-                    ok = strided_src(a_hb[i] - ar, g.sh, g.Ho, pp);
-                    ok = strided_src(a_wb[i] - as, g.sw, g.Wo, q) && ok && kk < p.Kd;
+                    const int pp = a_hb[i] - ar, q = a_wb[i] - as;
+                    ok = kk < p.Kd && (unsigned)pp < (unsigned)g.Ho && (unsigned)q < (unsigned)g.Wo;
                     off = a_base[i] + (pp * g.Wo + q) * g.K + cc;
                 }
                 const uint32_t bo = ok ? (uint32_t)off * 4u : OOB_OFF;
@@ -310,7 +314,7 @@ __global__ __launch_bounds__(NTHREADS) void igemm_kernel(const GemmParams p)
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
                     const int kk = kchunk + kq * 4 + e;
-                    const int c = kk % CC, rs = kk / CC, s = rs % g.S, r = rs / g.S;
+                    const int c = kk % CC, rs = kk / CC, s = rs % tapS, r = rs / tapS;
                     int off;
                     bool ok;
                     if (MODE == MODE_FWD) {
@@ -318,9 +322,8 @@ __global__ __launch_bounds__(NTHREADS) void igemm_kernel(const GemmParams p)
                         ok = kk < p.Kd && (unsigned)h < (unsigned)g.H && (unsigned)w < (unsigned)g.W;
                         off = a_base[i] + (h * g.W + w) * g.C + c;
                     } else {
-                        int pp, q;
-                        ok = strided_src(a_hb[i] - r, g.sh, g.Ho, pp);
-                        ok = strided_src(a_wb[i] - s, g.sw, g.Wo, q) && ok && kk < p.Kd;
+                        const int pp = a_hb[i] - r, q = a_wb[i] - s;
+                        ok = kk < p.Kd && (unsigned)pp < (unsigned)g.Ho && (unsigned)q < (unsigned)g.Wo;
                         off = a_base[i] + (pp * g.Wo + q) * g.K + c;
                     }
                     if (ok) {
@@ -360,7 +363,7 @@ __global__ __launch_bounds__(NTHREADS) void igemm_kernel(const GemmParams p)
 
     auto fetch_b = [&](int ch, int i) {
         if (FAST) {
-            const int cblk = fdiv(ch, p.fd_rs), tap = ch - cblk * (g.R * g.S);
+            const int cblk = fdiv(ch, p.fd_rs), tap = ch - cblk * tapRS;
             bool ok = ch < ch_end;
             int off;
             if (MODE == MODE_FWD) {
@@ -368,7 +371,9 @@ __global__ __launch_bounds__(NTHREADS) void igemm_kernel(const GemmParams p)
                 off = b_row[i] + (tap * g.C + cblk * BK);
             } else {
                 ok = ok && n0 + (t % B_F4) * 4 < p.Nn;
-                off = b_row[i] + (cblk * BK * (g.R * g.S) + tap) * g.C;
+                const int tr = fdiv(tap, p.fd_s), ts = tap - tr * tapS;
+                const int wtap = (p.sub.r0 + tr * g.sh) * g.S + p.sub.s0 + ts * g.sw;    // the filter tap this class tap stands for
+                off = b_row[i] + (cblk * BK * (g.R * g.S) + wtap) * g.C;
             }
             rb[i] = bload4(rsrc_b, ok ? (uint32_t)off * 4u : OOB_OFF);
             return;
@@ -393,7 +398,8 @@ __global__ __launch_bounds__(NTHREADS) void igemm_kernel(const GemmParams p)
             const int col = n0 + (t % B_F4) * 4;
             const int kk = kchunk + t / B_F4 + B_RP * i;
             const int rs = fdiv(kk, p.fd_k), bk = kk - rs * g.K;
-            const int br = fdiv(rs, p.fd_s), bs = rs - br * g.S;
+            const int tr = fdiv(rs, p.fd_s), ts = rs - tr * tapS;
+            const int br = p.sub.r0 + tr * g.sh, bs = p.sub.s0 + ts * g.sw;
             const int off = ((bk * g.R + br) * g.S + bs) * g.C + col;
             if (VECB) {
                 const bool ok = kk < p.Kd && col < p.Nn;
@@ -562,6 +568,15 @@ __global__ __launch_bounds__(NTHREADS) void igemm_kernel(const GemmParams p)
                     dst[(wave_m * WTM + i * 32 + 8 * (r >> 2) + 4 * lk + (r & 3)) * BN + wave_n * WTN + j * 32 + lrow] = acc[i][j][r];
         return;
     }
+    // element offset of (row, col) in the output: dense rows, or the scattered pixels of a stride class
+    auto out_index = [&](int row, int col) -> size_t {
+        if (MODE == MODE_BWD_DATA && (p.flags & OUT_STRIDED)) {
+            const int n = fdiv(row, p.fd_hcwc), hw = row - n * (p.sub.Hc * p.sub.Wc);
+            const int ci = fdiv(hw, p.fd_wc), cj = hw - ci * p.sub.Wc;
+            return ((size_t)(n * g.H + p.sub.h0 + ci * g.sh) * g.W + p.sub.w0 + cj * g.sw) * g.C + col;
+        }
+        return (size_t)row * p.Nn + col;
+    };
 #pragma unroll
     for (int j = 0; j < TN; ++j) {
         const int col = n0 + wave_n * WTN + j * 32 + lrow;
@@ -574,7 +589,7 @@ __global__ __launch_bounds__(NTHREADS) void igemm_kernel(const GemmParams p)
             for (int r = 0; r < 16; ++r) {
                 const int row = m0 + wave_m * WTM + i * 32 + 8 * (r >> 2) + 4 * lk + (r & 3);
                 if (row >= p.M) continue;
-                const size_t o = (size_t)row * p.Nn + col;
+                const size_t o = out_index(row, col);
                 float v = acc[i][j][r];
                 if (MODE == MODE_FWD) {
                     v += bias;

@@ -100,6 +100,9 @@ __global__ __launch_bounds__(NTHREADS, 2) void igemm_bf16_kernel(const GemmParam
     const int m0 = tile_m * BM, n0 = tile_n * BN;
 
     const ConvGeo &g = p.g;
+    // taps the reduction runs over: all of them, or those of the stride class (BWD_DATA)
+    const int tapS = MODE == MODE_BWD_DATA ? p.sub.Sc : g.S;
+    const int tapRS = MODE == MODE_BWD_DATA ? p.sub.Rc * p.sub.Sc : g.R * g.S;
     const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
     const int wave_m = wave / WN, wave_n = wave % WN;
 
@@ -132,19 +135,19 @@ __global__ __launch_bounds__(NTHREADS, 2) void igemm_bf16_kernel(const GemmParam
 #pragma unroll
         for (int i = 0; i < BV; ++i) b_row[i] = (n0 + row0 + RPP * i) * p.Kd + kq * 8;
     } else if (MODE == MODE_BWD_DATA) {
-        const int HW = g.H * g.W;
+        const int HW = p.sub.Hc * p.sub.Wc;      // rows are the pixels of one stride class (igemm.h, StrideClass)
 #pragma unroll
         for (int i = 0; i < AV; ++i) {
             const int m = m0 + row0 + RPP * i;
             if (m < p.M) {
-                const int n = m / HW, hw = m - n * HW, h = hw / g.W, w = hw - h * g.W;
-                a_hb[i] = h + g.ph;
-                a_wb[i] = w + g.pw;
+                const int n = m / HW, hw = m - n * HW, ci = hw / p.sub.Wc, cj = hw - ci * p.sub.Wc;
+                a_hb[i] = ci + p.sub.pa;
+                a_wb[i] = cj + p.sub.qb;
                 a_base[i] = n * g.Ho * g.Wo * g.K;
             } else {
                 a_hb[i] = -(1 << 28); a_wb[i] = 0; a_base[i] = 0;
             }
-            a_row[i] = m < p.M ? a_base[i] + (a_hb[i] * g.Wo + a_wb[i]) * g.K + kq * 8 : 0;   // unit stride only (FAST)
+            a_row[i] = m < p.M ? a_base[i] + (a_hb[i] * g.Wo + a_wb[i]) * g.K + kq * 8 : 0;   // source pixel of tap (0,0) of the class
         }
 #pragma unroll
         for (int i = 0; i < BV; ++i)   // w[k][r][s][c] at k = this thread's reduction row, tap (0,0), its 8 columns
@@ -178,8 +181,8 @@ __global__ __launch_bounds__(NTHREADS, 2) void igemm_bf16_kernel(const GemmParam
         const bool kok = ch < nchunks;
         if (FAST) {
             // channel-block-major, tap-minor visiting order: the taps of one channel block re-read the same image rows
-            const int cblk = fdiv(ch, p.fd_rs), tap = ch - cblk * (g.R * g.S);
-            const int ar = fdiv(tap, p.fd_s), as = tap - ar * g.S;
+            const int cblk = fdiv(ch, p.fd_rs), tap = ch - cblk * tapRS;
+            const int ar = fdiv(tap, p.fd_s), as = tap - ar * tapS;
 #pragma unroll
             for (int i = 0; i < AV; ++i) {
                 int off;
@@ -204,7 +207,8 @@ __global__ __launch_bounds__(NTHREADS, 2) void igemm_bf16_kernel(const GemmParam
                     off = b_row[i] + (tap * g.C + cblk * BKH);
                 } else {
                     ok = ok && n0 + (t % B_F8) * 8 < p.Nn;
-                    off = b_row[i] + (cblk * BKH * (g.R * g.S) + tap) * g.C;
+                    const int wtap = (p.sub.r0 + ar * g.sh) * g.S + p.sub.s0 + as * g.sw;    // the filter tap this class tap stands for
+                    off = b_row[i] + (cblk * BKH * (g.R * g.S) + wtap) * g.C;
                 }
                 rb[set][i] = bload16(rsrc_b, ok ? (uint32_t)off * 2u : OOB_OFF);
             }
@@ -219,15 +223,14 @@ __global__ __launch_bounds__(NTHREADS, 2) void igemm_bf16_kernel(const GemmParam
                 const int CC = (MODE == MODE_FWD) ? g.C : g.K;
                 const int kk = kchunk + kq * 8;
                 const int rs = fdiv(kk, MODE == MODE_FWD ? p.fd_c : p.fd_k), cc = kk - rs * CC;
-                const int ar = fdiv(rs, p.fd_s), as = rs - ar * g.S;
+                const int ar = fdiv(rs, p.fd_s), as = rs - ar * tapS;
                 if (MODE == MODE_FWD) {
                     const int h = a_hb[i] + ar, w = a_wb[i] + as;
                     ok = kk < p.Kd && (unsigned)h < (unsigned)g.H && (unsigned)w < (unsigned)g.W;
                     off = a_base[i] + (h * g.W + w) * g.C + cc;
                 } else {
-                    int pp, q;
-                    ok = strided_src(a_hb[i] - ar, g.sh, g.Ho, pp);
-                    ok = strided_src(a_wb[i] - as, g.sw, g.Wo, q) && ok && kk < p.Kd;
+                    const int pp = a_hb[i] - ar, q = a_wb[i] - as;
+                    ok = kk < p.Kd && (unsigned)pp < (unsigned)g.Ho && (unsigned)q < (unsigned)g.Wo;
                     off = a_base[i] + (pp * g.Wo + q) * g.K + cc;
                 }
             } else {
@@ -253,7 +256,8 @@ __global__ __launch_bounds__(NTHREADS, 2) void igemm_bf16_kernel(const GemmParam
                 const int col = n0 + (t % B_F8) * 8;
                 const int kk = kchunk + t / B_F8 + B_RP * i;
                 const int rs = fdiv(kk, p.fd_k), bk = kk - rs * g.K;
-                const int br = fdiv(rs, p.fd_s), bs = rs - br * g.S;
+                const int tr = fdiv(rs, p.fd_s), ts = rs - tr * tapS;
+                const int br = p.sub.r0 + tr * g.sh, bs = p.sub.s0 + ts * g.sw;
                 ok = kk < p.Kd && col < p.Nn;
                 off = ((bk * g.R + br) * g.S + bs) * g.C + col;
             } else {
@@ -400,6 +404,15 @@ __global__ __launch_bounds__(NTHREADS, 2) void igemm_bf16_kernel(const GemmParam
     uint16_t *outh = reinterpret_cast<uint16_t *>(p.out);
     const uint16_t *xm = reinterpret_cast<const uint16_t *>(p.xmask);
     constexpr int CH8 = BN / 8, ROWS_PER_PASS = NTHREADS / CH8;
+    // element offset of (row, col) in the output: dense rows, or the scattered pixels of a stride class
+    auto out_index = [&](int row, int col) -> size_t {
+        if (MODE == MODE_BWD_DATA && (p.flags & OUT_STRIDED)) {
+            const int n = fdiv(row, p.fd_hcwc), hw = row - n * (p.sub.Hc * p.sub.Wc);
+            const int ci = fdiv(hw, p.fd_wc), cj = hw - ci * p.sub.Wc;
+            return ((size_t)(n * g.H + p.sub.h0 + ci * g.sh) * g.W + p.sub.w0 + cj * g.sw) * g.C + col;
+        }
+        return (size_t)row * p.Nn + col;
+    };
 #pragma unroll
     for (int half = 0; half < BM / CROWS; ++half) {
         __syncthreads();
@@ -423,7 +436,7 @@ __global__ __launch_bounds__(NTHREADS, 2) void igemm_bf16_kernel(const GemmParam
                             // residual joins only: the previous gradient is added before the one rounding to bf16
                             const int row = m0 + wave_m * WTM + i * 32 + lrow;
                             if (row < p.M && n0 + col_l < p.Nn) {
-                                const uint2 old = *reinterpret_cast<const uint2 *>(outh + (size_t)row * p.Nn + n0 + col_l);
+                                const uint2 old = *reinterpret_cast<const uint2 *>(outh + out_index(row, n0 + col_l));
                                 v0 += bf16_to_f32((uint16_t)(old.x & 0xffffu)); v1 += bf16_to_f32((uint16_t)(old.x >> 16));
                                 v2 += bf16_to_f32((uint16_t)(old.y & 0xffffu)); v3 += bf16_to_f32((uint16_t)(old.y >> 16));
                             }
@@ -440,7 +453,7 @@ __global__ __launch_bounds__(NTHREADS, 2) void igemm_bf16_kernel(const GemmParam
             const int row = m0 + half * CROWS + row_l, col = n0 + c8;
             if (row >= p.M || col >= p.Nn) continue;
             uint4 v = *reinterpret_cast<const uint4 *>(&smem[row_l * LDC + c8]);
-            const size_t o = (size_t)row * p.Nn + col;
+            const size_t o = out_index(row, col);
             if (MODE == MODE_BWD_DATA) {
                 if (p.flags & EPI_XMASK) v = gate8(v, *reinterpret_cast<const uint4 *>(xm + o));
             }
