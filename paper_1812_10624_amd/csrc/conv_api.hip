@@ -267,11 +267,17 @@ static int launch_tile_bf16(GemmParams &p, int splits, hipStream_t st)
     dim3 grid((unsigned)(cdiv(p.tiles * splits, 8) * 8));
     const ConvGeo &g = p.g;
     // a stage that stays inside one filter tap: wavefront-uniform tap decode, no per-thread division in the main loop
-    const bool fast = (MODE == MODE_FWD && g.C % BKH == 0) || (MODE == MODE_BWD_DATA && g.K % BKH == 0);
-    if (MODE != MODE_BWD_WEIGHT && fast)
-        hipLaunchKernelGGL((igemm_bf16_kernel<MODE, BM, BN, WM, WN, MODE != MODE_BWD_WEIGHT>), grid, dim3(NTHREADS), 0, st, p);
+    const bool fast = g.R * g.S <= 32 && ((MODE == MODE_FWD && g.C % BKH == 0) || (MODE == MODE_BWD_DATA && g.K % BKH == 0));
+    const bool gated = MODE != MODE_FWD && (p.flags & LOAD_AMASK);
+    constexpr bool CAN_FAST = MODE != MODE_BWD_WEIGHT, CAN_GATE = MODE != MODE_FWD;
+    if (fast && !gated)
+        hipLaunchKernelGGL((igemm_bf16_kernel<MODE, BM, BN, WM, WN, CAN_FAST, false>), grid, dim3(NTHREADS), 0, st, p);
+    else if (fast)
+        hipLaunchKernelGGL((igemm_bf16_kernel<MODE, BM, BN, WM, WN, CAN_FAST, CAN_GATE>), grid, dim3(NTHREADS), 0, st, p);
+    else if (!gated)
+        hipLaunchKernelGGL((igemm_bf16_kernel<MODE, BM, BN, WM, WN, false, false>), grid, dim3(NTHREADS), 0, st, p);
     else
-        hipLaunchKernelGGL((igemm_bf16_kernel<MODE, BM, BN, WM, WN, false>), grid, dim3(NTHREADS), 0, st, p);
+        hipLaunchKernelGGL((igemm_bf16_kernel<MODE, BM, BN, WM, WN, false, CAN_GATE>), grid, dim3(NTHREADS), 0, st, p);
     return launch_status();
 }
 

@@ -25,7 +25,7 @@ namespace stanza {
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef short s16x8 __attribute__((ext_vector_type(8)));
-constexpr int BKH = 32;        // reduction depth of one LDS stage (bf16 elements); also the filter-gradient slice unit
+constexpr int BKH = 64;        // reduction depth of one LDS stage (bf16 elements); also the filter-gradient slice unit
 constexpr int KPAD = 32;       // row pad of a reduction-major tile: row stride = 64 bytes mod 256, so the four reduction rows
                                // a 16-lane group reads land on four different 64-byte bank groups
 
@@ -63,7 +63,9 @@ __device__ __forceinline__ s16x4 lds_tr4(const uint16_t *p)
     return __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3))) *)(p));
 }
 
-template <int MODE, int BM, int BN, int WM, int WN, bool FAST>
+// AMASK: dy is gated by [y > 0] as it is read (a second fetch per A vector); without it the registers allow fetching two
+// stages ahead.
+template <int MODE, int BM, int BN, int WM, int WN, bool FAST, bool AMASK>
 __global__ __launch_bounds__(NTHREADS, 2) void igemm_bf16_kernel(const GemmParams p)
 {
     static_assert(WM * WN == 4, "four wavefronts per workgroup");
@@ -74,7 +76,7 @@ __global__ __launch_bounds__(NTHREADS, 2) void igemm_bf16_kernel(const GemmParam
     constexpr int KS = BKH / 16;                         // MFMA k-steps per stage
     constexpr bool A_KMAJ = MODE == MODE_BWD_WEIGHT, B_KMAJ = MODE != MODE_FWD;
     constexpr bool SWAP = MODE != MODE_BWD_WEIGHT;       // bf16 output: accumulate the transposed tile
-    constexpr int LDR = BKH + 8;                         // row-major tile: elements per row (80 bytes)
+    constexpr int LDR = BKH + 8;                         // row-major tile: elements per row (144 bytes: conflict-free 16-byte reads)
     constexpr int LDAK = BM + KPAD, LDBK = BN + KPAD;    // reduction-major tiles: elements per reduction row
     constexpr int A_ELEMS = A_KMAJ ? BKH * LDAK : BM * LDR;
     constexpr int B_ELEMS = B_KMAJ ? BKH * LDBK : BN * LDR;
@@ -112,7 +114,7 @@ __global__ __launch_bounds__(NTHREADS, 2) void igemm_bf16_kernel(const GemmParam
         kend = min(p.Kd, kbeg + p.chunks_per_split * BKH);
     }
     const int nchunks = (kend - kbeg + BKH - 1) / BKH;
-    const bool amask = (p.flags & LOAD_AMASK) != 0;
+    constexpr bool amask = AMASK;
 
     const int kq = t % KQ, row0 = t / KQ;
     int a_hb[AV], a_wb[AV], a_base[AV], a_row[AV], b_row[BV];
@@ -164,12 +166,36 @@ __global__ __launch_bounds__(NTHREADS, 2) void igemm_bf16_kernel(const GemmParam
         for (int i = 0; i < BV; ++i) b_row[i] = 0;
     }
 
+    // FAST path state (see fetch): tap validity mask per A row, static validity per B vector, running stage position
+    // (the host takes this path for at most 32 taps)
+    uint32_t a_mask[AV];
+    bool b_ok[BV];
+    int f_cblk = 0, f_tap = 0, f_ar = 0, f_as = 0;
+    if (FAST) {
+#pragma unroll
+        for (int i = 0; i < AV; ++i) {
+            uint32_t mk = 0;
+            for (int tap = 0, ar = 0, as = 0; tap < tapRS; ++tap) {
+                const bool ok = MODE == MODE_FWD
+                                    ? ((unsigned)(a_hb[i] + ar) < (unsigned)g.H && (unsigned)(a_wb[i] + as) < (unsigned)g.W)
+                                    : ((unsigned)(a_hb[i] - ar) < (unsigned)g.Ho && (unsigned)(a_wb[i] - as) < (unsigned)g.Wo);
+                mk |= (uint32_t)ok << tap;
+                if (++as == tapS) { as = 0; ++ar; }
+            }
+            a_mask[i] = mk;
+        }
+#pragma unroll
+        for (int i = 0; i < BV; ++i) b_ok[i] = MODE == MODE_FWD ? (n0 + row0 + RPP * i < p.Nn) : (n0 + (t % B_F8) * 8 < p.Nn);
+    }
+
     const __amdgpu_buffer_rsrc_t rsrc_a = make_rsrc(p.a, p.a_bytes);
     const __amdgpu_buffer_rsrc_t rsrc_g = make_rsrc(p.amask ? p.amask : p.a, p.a_bytes);
     const __amdgpu_buffer_rsrc_t rsrc_b = make_rsrc(p.b, p.b_bytes);
 
-    // two register sets: set (s & 1) holds stage s from its fetch until it is written to LDS
-    uint4 ra[2][AV], rb[2][BV], rg[2][AV];
+    // two register sets: set (s & 1) holds stage s from its fetch until it is written to LDS; one set when the gate vectors
+    // take the registers of the second
+    constexpr bool PREFETCH2 = !AMASK;
+    uint4 ra[PREFETCH2 ? 2 : 1][AV], rb[PREFETCH2 ? 2 : 1][BV], rg[PREFETCH2 ? 2 : 1][AV];
     const bool want_db = MODE == MODE_BWD_WEIGHT && (p.flags & EPI_DBIAS) && tile_n == 0;
     float dbacc[8];
 #pragma unroll
@@ -180,38 +206,30 @@ __global__ __launch_bounds__(NTHREADS, 2) void igemm_bf16_kernel(const GemmParam
         constexpr int set = decltype(set_c)::value;
         const bool kok = ch < nchunks;
         if (FAST) {
-            // channel-block-major, tap-minor visiting order: the taps of one channel block re-read the same image rows
-            const int cblk = fdiv(ch, p.fd_rs), tap = ch - cblk * tapRS;
-            const int ar = fdiv(tap, p.fd_s), as = tap - ar * tapS;
+            // channel-block-major, tap-minor visiting order: the taps of one channel block re-read the same image rows.
+            // Stages are fetched in ascending order, so (channel block, tap row, tap column) is a running scalar state, a
+            // row's tap validity is one bit of its precomputed mask, and an address is its precomputed row offset plus a scalar.
+            int sa, sb;      // wavefront-uniform byte offsets of this stage
+            if (MODE == MODE_FWD) {
+                sa = ((f_ar * g.W + f_as) * g.C + f_cblk * BKH) * 2;
+                sb = (f_tap * g.C + f_cblk * BKH) * 2;
+            } else {
+                sa = (f_cblk * BKH - (f_ar * g.Wo + f_as) * g.K) * 2;
+                const int wtap = (p.sub.r0 + f_ar * g.sh) * g.S + p.sub.s0 + f_as * g.sw;    // the filter tap this class tap stands for
+                sb = ((f_cblk * BKH * (g.R * g.S) + wtap) * g.C) * 2;
+            }
 #pragma unroll
             for (int i = 0; i < AV; ++i) {
-                int off;
-                bool ok;
-                if (MODE == MODE_FWD) {
-                    ok = kok && (unsigned)(a_hb[i] + ar) < (unsigned)g.H && (unsigned)(a_wb[i] + as) < (unsigned)g.W;
-                    off = a_row[i] + ((ar * g.W + as) * g.C + cblk * BKH);
-                } else {
-                    ok = kok && (unsigned)(a_hb[i] - ar) < (unsigned)g.Ho && (unsigned)(a_wb[i] - as) < (unsigned)g.Wo;
-                    off = a_row[i] + (cblk * BKH - (ar * g.Wo + as) * g.K);
-                }
-                const uint32_t bo = ok ? (uint32_t)off * 2u : OOB_OFF;
+                const bool ok = kok && ((a_mask[i] >> f_tap) & 1u);
+                const uint32_t bo = ok ? (uint32_t)(a_row[i] * 2 + sa) : OOB_OFF;
                 ra[set][i] = bload16(rsrc_a, bo);
                 if (MODE == MODE_BWD_DATA && amask) rg[set][i] = bload16(rsrc_g, bo);
             }
 #pragma unroll
-            for (int i = 0; i < BV; ++i) {
-                bool ok = kok;
-                int off;
-                if (MODE == MODE_FWD) {
-                    ok = ok && n0 + row0 + RPP * i < p.Nn;
-                    off = b_row[i] + (tap * g.C + cblk * BKH);
-                } else {
-                    ok = ok && n0 + (t % B_F8) * 8 < p.Nn;
-                    const int wtap = (p.sub.r0 + ar * g.sh) * g.S + p.sub.s0 + as * g.sw;    // the filter tap this class tap stands for
-                    off = b_row[i] + (cblk * BKH * (g.R * g.S) + wtap) * g.C;
-                }
-                rb[set][i] = bload16(rsrc_b, ok ? (uint32_t)off * 2u : OOB_OFF);
-            }
+            for (int i = 0; i < BV; ++i) rb[set][i] = bload16(rsrc_b, (kok && b_ok[i]) ? (uint32_t)(b_row[i] * 2 + sb) : OOB_OFF);
+            ++f_tap;
+            if (++f_as == tapS) { f_as = 0; ++f_ar; }
+            if (f_tap == tapRS) { f_tap = f_ar = f_as = 0; ++f_cblk; }
             return;
         }
         const int kchunk = kbeg + ch * BKH;
@@ -346,20 +364,32 @@ __global__ __launch_bounds__(NTHREADS, 2) void igemm_bf16_kernel(const GemmParam
 
     constexpr std::integral_constant<int, 0> S0{};
     constexpr std::integral_constant<int, 1> S1{};
-    fetch(0, S0);
-    stash(S0, 0);
-    fetch(1, S1);
-    __syncthreads();
-    for (int ch = 0; ch < nchunks; ch += 2) {
-        fetch(ch + 2, S0);
-        compute(0);
-        stash(S1, 1);
+    if constexpr (PREFETCH2) {
+        fetch(0, S0);
+        stash(S0, 0);
+        fetch(1, S1);
         __syncthreads();
-        if (ch + 1 >= nchunks) break;
-        fetch(ch + 3, S1);
-        compute(1);
+        for (int ch = 0; ch < nchunks; ch += 2) {
+            fetch(ch + 2, S0);
+            compute(0);
+            stash(S1, 1);
+            __syncthreads();
+            if (ch + 1 >= nchunks) break;
+            fetch(ch + 3, S1);
+            compute(1);
+            stash(S0, 0);
+            __syncthreads();
+        }
+    } else {
+        fetch(0, S0);
         stash(S0, 0);
         __syncthreads();
+        for (int ch = 0; ch < nchunks; ++ch) {
+            fetch(ch + 1, S0);
+            compute(ch & 1);
+            stash(S0, (ch + 1) & 1);
+            __syncthreads();
+        }
     }
 
     if (MODE == MODE_BWD_WEIGHT && want_db) {
