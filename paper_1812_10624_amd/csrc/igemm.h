@@ -130,7 +130,7 @@ __device__ __forceinline__ float4 gate4(float4 v, float4 m)
 // inside one filter tap, so the tap is wavefront-uniform (scalar registers) and a row's address is a precomputed row
 // offset plus a scalar; no per-thread division or multiplication is left in the main loop.
 template <int MODE, int BM, int BN, int WM, int WN, bool VECA, bool VECB, bool FAST = false>
-__global__ __launch_bounds__(NTHREADS) void igemm_kernel(const GemmParams p)
+__global__ __launch_bounds__(NTHREADS, (BM >= 256 ? 3 : 4)) void igemm_kernel(const GemmParams p)   // 128 registers: four workgroups per CU
 {
     static_assert(WM * WN == 4, "four wavefronts per workgroup");
     static_assert(BM % 64 == 0 && BN % 64 == 0, "loader granularity");
@@ -204,7 +204,7 @@ __global__ __launch_bounds__(NTHREADS) void igemm_kernel(const GemmParams p)
         for (int i = 0; i < AV; ++i) {
             const int m = m0 + row0 + RPP * i;
             if (m < p.M) {
-                const int n = m / HoWo, pq = m - n * HoWo, pp = pq / g.Wo, q = pq - pp * g.Wo;
+                const int n = fdiv(m, p.fd_howo), pq = m - n * HoWo, pp = fdiv(pq, p.fd_wo), q = pq - pp * g.Wo;
                 a_hb[i] = pp * g.sh - g.ph;
                 a_wb[i] = q * g.sw - g.pw;
                 a_base[i] = n * g.H * g.W * g.C;
@@ -221,7 +221,7 @@ __global__ __launch_bounds__(NTHREADS) void igemm_kernel(const GemmParams p)
         for (int i = 0; i < AV; ++i) {
             const int m = m0 + row0 + RPP * i;
             if (m < p.M) {
-                const int n = m / HW, hw = m - n * HW, ci = hw / p.sub.Wc, cj = hw - ci * p.sub.Wc;
+                const int n = fdiv(m, p.fd_hcwc), hw = m - n * HW, ci = fdiv(hw, p.fd_wc), cj = hw - ci * p.sub.Wc;
                 a_hb[i] = ci + p.sub.pa;
                 a_wb[i] = cj + p.sub.qb;
                 a_base[i] = n * g.Ho * g.Wo * g.K;
@@ -237,10 +237,10 @@ __global__ __launch_bounds__(NTHREADS) void igemm_kernel(const GemmParams p)
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
             const int j = n0 + (t % B_F4) * 4 + e;
-            bw_c[e] = j % g.C;
-            const int rs = j / g.C;
-            bw_s[e] = rs % g.S;
-            bw_r[e] = rs / g.S;         // >= R when j >= Nn: the column predicate below covers it
+            const int rs = fdiv(j, p.fd_c);
+            bw_c[e] = j - rs * g.C;
+            bw_r[e] = fdiv(rs, p.fd_s);         // >= R when j >= Nn: the column predicate below covers it
+            bw_s[e] = rs - bw_r[e] * g.S;
         }
     }
 

@@ -125,7 +125,7 @@ __global__ __launch_bounds__(NTHREADS, 2) void igemm_bf16_kernel(const GemmParam
         for (int i = 0; i < AV; ++i) {
             const int m = m0 + row0 + RPP * i;
             if (m < p.M) {
-                const int n = m / HoWo, pq = m - n * HoWo, pp = pq / g.Wo, q = pq - pp * g.Wo;
+                const int n = fdiv(m, p.fd_howo), pq = m - n * HoWo, pp = fdiv(pq, p.fd_wo), q = pq - pp * g.Wo;
                 a_hb[i] = pp * g.sh - g.ph;
                 a_wb[i] = q * g.sw - g.pw;
                 a_base[i] = n * g.H * g.W * g.C;
@@ -142,7 +142,7 @@ __global__ __launch_bounds__(NTHREADS, 2) void igemm_bf16_kernel(const GemmParam
         for (int i = 0; i < AV; ++i) {
             const int m = m0 + row0 + RPP * i;
             if (m < p.M) {
-                const int n = m / HW, hw = m - n * HW, ci = hw / p.sub.Wc, cj = hw - ci * p.sub.Wc;
+                const int n = fdiv(m, p.fd_hcwc), hw = m - n * HW, ci = fdiv(hw, p.fd_wc), cj = hw - ci * p.sub.Wc;
                 a_hb[i] = ci + p.sub.pa;
                 a_wb[i] = cj + p.sub.qb;
                 a_base[i] = n * g.Ho * g.Wo * g.K;
@@ -156,10 +156,10 @@ __global__ __launch_bounds__(NTHREADS, 2) void igemm_bf16_kernel(const GemmParam
             b_row[i] = (t / B_F8 + B_RP * i) * (g.R * g.S * g.C) + n0 + (t % B_F8) * 8;
     } else {
         const int j = n0 + (t % B_F8) * 8;           // C % 8 == 0: the 8 columns share one tap
-        bw_c = j % g.C;
-        const int rs = j / g.C;
-        bw_s = rs % g.S;
-        bw_r = rs / g.S;                             // >= R when j >= Nn: the column predicate covers it
+        const int rs = fdiv(j, p.fd_c);
+        bw_c = j - rs * g.C;
+        bw_r = fdiv(rs, p.fd_s);                     // >= R when j >= Nn: the column predicate covers it
+        bw_s = rs - bw_r * g.S;
 #pragma unroll
         for (int i = 0; i < AV; ++i) { a_hb[i] = a_wb[i] = a_base[i] = a_row[i] = 0; }
 #pragma unroll
