@@ -140,14 +140,13 @@ __global__ __launch_bounds__(NTHREADS, (BM >= 256 ? 3 : 4)) void igemm_kernel(co
     constexpr int RPP = NTHREADS / KQ;                   // tile rows covered by one pass of a reduction-contiguous fetch
     constexpr int AV = BM * BK / 1024, BV = BN * BK / 1024;  // 16-byte vectors per thread per stage
     // LDS layouts.  An operand whose reduction index is contiguous in memory (x and w in FWD, dy in BWD_DATA) is kept
-    // ROW-MAJOR, [rows][BK+4]: the fetched 16-byte vector is stored as it is, and a lane reads 4 consecutive reduction
-    // elements of its row with one 16-byte read (80-byte rows: 8 consecutive rows cover all 32 banks), which feed 4
-    // MFMAs.  Lanes 0-31 take elements 8g..8g+3 and lanes 32-63 elements 8g+4..8g+7 of reduction group g, so MFMA j of
+    // ROW-MAJOR, [rows][BK] with the 16-byte vectors of a row swizzled (see kq_sw): the fetched vector is stored as it is,
+    // and a lane reads 4 consecutive reduction elements of its row with one 16-byte read, which feed 4 MFMAs.  Lanes 0-31 take elements 8g..8g+3 and lanes 32-63 elements 8g+4..8g+7 of reduction group g, so MFMA j of
     // the group multiplies the element pair (8g+j, 8g+4+j): a permutation of the reduction that both operands follow.
     // An operand whose row/column index is contiguous (w in BWD_DATA, dy and x in BWD_WEIGHT) is kept
     // REDUCTION-MAJOR, [BK][rows+4], stored as 16-byte vectors and read as scalars (conflict-free 128-byte rows).
     constexpr bool A_ROWK = MODE != MODE_BWD_WEIGHT, B_ROWK = MODE == MODE_FWD;
-    constexpr int LDK = BK + 4;
+    constexpr int LDK = BK;      // unpadded 64-byte rows; the four 16-byte vectors of a row are XOR-swizzled (see kq_sw)
     constexpr int LDA = BM + PAD_V, LDB = BN + PAD_V;
     constexpr int A_FLOATS = A_ROWK ? BM * LDK : BK * LDA, B_FLOATS = B_ROWK ? BN * LDK : BK * LDB;
     __shared__ __attribute__((aligned(16))) float As[2][A_FLOATS];
@@ -186,6 +185,11 @@ __global__ __launch_bounds__(NTHREADS, (BM >= 256 ? 3 : 4)) void igemm_kernel(co
     // ------------------------------------------------------------------ loader state
     // "KC" loaders (reduction contiguous in memory): thread -> vector kq of 4 along the reduction, rows row0 + 64*i.
     const int kq = t % KQ, row0 = t / KQ;
+    // Row-major LDS tiles: vector v of row r sits at position v ^ ((r >> 1) & 3) ^ ((r >> 3) & 3).  A group of 8 consecutive
+    // lanes over 32 banks, or of 16 over 64, then touches every bank once both when a stage is written (consecutive rows x 4
+    // vectors) and when operands are read (consecutive rows, one vector each), without padding the rows.  (The LDS
+    // bank-conflict counter reads 4 cycles per 16-byte operand read with this layout and with padded 80-byte rows alike.)
+    const int kq_sw = kq ^ ((row0 >> 1) & 3) ^ ((row0 >> 3) & 3);      // rows row0 + 64*i share the swizzle
     // "MC" loaders (row/column index contiguous): thread -> vector c4 along the tile edge, reduction rows kr0 + RP*i.
     constexpr int A_F4 = BM / 4, A_RP = NTHREADS / A_F4;
     constexpr int B_F4 = BN / 4, B_RP = NTHREADS / B_F4;
@@ -449,13 +453,13 @@ __global__ __launch_bounds__(NTHREADS, (BM >= 256 ? 3 : 4)) void igemm_kernel(co
                 *reinterpret_cast<float4 *>(&As[buf][(t / A_F4 + A_RP * i) * LDA + (t % A_F4) * 4]) = v;
                 if (want_db) { dbacc.x += v.x; dbacc.y += v.y; dbacc.z += v.z; dbacc.w += v.w; }
             } else {
-                *reinterpret_cast<float4 *>(&As[buf][(row0 + RPP * i) * LDK + kq * 4]) = v;
+                *reinterpret_cast<float4 *>(&As[buf][(row0 + RPP * i) * LDK + kq_sw * 4]) = v;
             }
         }
 #pragma unroll
         for (int i = 0; i < BV; ++i) {
             if (MODE == MODE_FWD) {
-                *reinterpret_cast<float4 *>(&Bs[buf][(row0 + RPP * i) * LDK + kq * 4]) = rb[i];
+                *reinterpret_cast<float4 *>(&Bs[buf][(row0 + RPP * i) * LDK + kq_sw * 4]) = rb[i];
             } else {
                 *reinterpret_cast<float4 *>(&Bs[buf][(t / B_F4 + B_RP * i) * LDB + (t % B_F4) * 4]) = rb[i];
             }
@@ -478,6 +482,7 @@ __global__ __launch_bounds__(NTHREADS, (BM >= 256 ? 3 : 4)) void igemm_kernel(co
     __syncthreads();
 
     const int lrow = lane & 31, lk = lane >> 5;
+    const int rd_sw = ((lrow >> 1) & 3) ^ ((lrow >> 3) & 3);   // tile rows of a lane differ by multiples of 32
     constexpr int KS = BK / 2;                      // MFMA k-steps per stage
     static_assert(AV + BV <= KS, "one fetch slot per k-step");
     for (int ch = ch_beg; ch < ch_end; ++ch) {
@@ -494,12 +499,12 @@ __global__ __launch_bounds__(NTHREADS, (BM >= 256 ? 3 : 4)) void igemm_kernel(co
             if (A_ROWK) {
 #pragma unroll
                 for (int i = 0; i < TM; ++i)
-                    a4[slot][i] = *reinterpret_cast<const float4 *>(&As[buf][(wave_m * WTM + i * 32 + lrow) * LDK + gi * 8 + lk * 4]);
+                    a4[slot][i] = *reinterpret_cast<const float4 *>(&As[buf][(wave_m * WTM + i * 32 + lrow) * LDK + ((gi * 2 + lk) ^ rd_sw) * 4]);
             }
             if (B_ROWK) {
 #pragma unroll
                 for (int j = 0; j < TN; ++j)
-                    b4[slot][j] = *reinterpret_cast<const float4 *>(&Bs[buf][(wave_n * WTN + j * 32 + lrow) * LDK + gi * 8 + lk * 4]);
+                    b4[slot][j] = *reinterpret_cast<const float4 *>(&Bs[buf][(wave_n * WTN + j * 32 + lrow) * LDK + ((gi * 2 + lk) ^ rd_sw) * 4]);
             }
         };
         // reduction row that lane half lk multiplies in k-step ks: pairs (8g+j, 8g+4+j) when a row-major operand fixes
