@@ -160,6 +160,21 @@ def main():
                 print(f"  {kind[7:]:16s} {op['name']:8s} {shapes[op['src']][1]:3d}x{shapes[op['src']][2]:<3d} C{c:<4d} K{kk:<4d} "
                       f"R{op['R']} s{op['stride']}  {ms:8.3f} ms  {fl / ms / 1e9:7.1f} TFLOP/s", file=sys.stderr)
 
+    # HBM-bound kernels of the CONV worker: algorithmic bytes (every tensor moved once) over the measured time
+    esz = 2 if args.dtype == "bf16" else 4
+    shapes_all = W.shape_pass(wl)
+    pool_f = pool_b = 0.0
+    for op in wl.ops:
+        if op["op"] == "pool":
+            n_in = float(np.prod(shapes_all[op["src"]])); n_out = float(np.prod(shapes_all[op["dst"]]))
+            pool_f += esz * n_in + esz * n_out + n_out                       # x read, y and argmax written
+            pool_b += esz * n_out + n_out + (esz * n_out if op["relu"] else 0) + esz * n_in   # dy, argmax, y (gate) read, dx written
+    hbm_kernels = {}
+    for tag, by in (("stanza_pool_relu_fwd", pool_f), ("stanza_pool_relu_bwd", pool_b)):
+        if tag in tot and by > 0:
+            gbs = by / (tot[tag] * 1e-3) / 1e9
+            hbm_kernels[tag] = {"algorithmic_bytes_per_step": by, "ms_per_step": tot[tag], "GBps": gbs, "frac_hbm": gbs / HBM_PEAK_GBS}
+
     out = {
         "metric": "conv_worker_train_images_per_sec_per_gpu",
         "value": B / (ms_per_step * 1e-3),
@@ -176,6 +191,7 @@ def main():
         "fc_step_ms": tot["stanza_fc_step"],
         "fc_tflops": W.fc_flops(wl) / (tot["stanza_fc_step"] * 1e-3) / 1e12,
         "ps_aggregate_ms": tot["stanza_ps_aggregate"], "ps_aggregate_GBps": ps_gbs, "ps_aggregate_frac_hbm": ps_gbs / HBM_PEAK_GBS,
+        "hbm_kernels": hbm_kernels,
         "roofline": {"bound": "mfma", "kernel": "stanza::igemm_kernel (all launches of a step: conv fwd / bwd_data / bwd_weight "
                                                  "and the FC worker's GEMMs)",
                      "achieved": gemm_tflops, "peak": MFMA_F32_PEAK_TFLOPS, "unit": "TFLOP/s",

@@ -215,6 +215,106 @@ __global__ __launch_bounds__(256) void pool_bwd_bf16_kernel(const PoolGeo g, con
     *reinterpret_cast<uint4 *>(dx + id * 8) = outv;
 }
 
+// ---- non-overlapping windows (window == stride, no padding, image a whole number of windows: every pool of the
+// VGG-16-shaped and tiny stacks).  One thread per OUTPUT pixel and 16-byte channel vector, in both directions: forward reads
+// its window, backward reads dy / y / argmax once and writes the window's input pixels (the gather form above reads them once
+// per input pixel, four times for a 2x2 window).  grid = (vectors of an output row / 256, N*Ho); 32-bit index arithmetic, one
+// multiply-shift division per thread; every access is non-temporal (each byte is touched once).
+typedef unsigned int pool_u4 __attribute__((ext_vector_type(4)));
+template <bool BF16>
+__global__ __launch_bounds__(256) void pool_fwd_tiled_kernel(const PoolGeo g, FastDiv fd_cv, const void *__restrict__ xv, void *__restrict__ yv,
+                                                             uint8_t *__restrict__ argmax)
+{
+    constexpr int VW = BF16 ? 8 : 4;
+    const int CV = g.C / VW;
+    const int idx = blockIdx.x * 256 + threadIdx.x;
+    if (idx >= g.Wo * CV) return;
+    const int q = fdiv(idx, fd_cv), cv = idx - q * CV;
+    const int np = blockIdx.y, n = np / g.Ho, pp = np - n * g.Ho;
+    const pool_u4 *x = reinterpret_cast<const pool_u4 *>(xv);
+    float best[VW];
+    uint32_t braw[VW];
+    int bidx[VW];
+    for (int i = 0; i < g.wh; ++i) {
+        for (int j = 0; j < g.ww; ++j) {
+            const size_t off = (((size_t)n * g.H + pp * g.sh + i) * g.W + q * g.sw + j) * CV + cv;
+            const pool_u4 t = __builtin_nontemporal_load(x + off);
+#pragma unroll
+            for (int e = 0; e < VW; ++e) {
+                const uint32_t raw = BF16 ? ((t[e >> 1] >> (16 * (e & 1))) & 0xffffu) : t[e];
+                const float v = BF16 ? __uint_as_float(raw << 16) : __uint_as_float(raw);
+                if ((i == 0 && j == 0) || v > best[e]) { best[e] = v; braw[e] = raw; bidx[e] = i * g.ww + j; }
+            }
+        }
+    }
+    const size_t o = ((size_t)np * g.Wo + q) * CV + cv;      // in 16-byte vectors
+    pool_u4 out = {0u, 0u, 0u, 0u};
+    uint32_t am[2] = {0u, 0u};
+#pragma unroll
+    for (int e = 0; e < VW; ++e) {
+        const uint32_t raw = (g.relu && best[e] < 0.f) ? 0u : braw[e];
+        if (BF16) out[e >> 1] |= raw << (16 * (e & 1)); else out[e] = raw;
+        am[e >> 2] |= (uint32_t)bidx[e] << (8 * (e & 3));
+    }
+    __builtin_nontemporal_store(out, reinterpret_cast<pool_u4 *>(yv) + o);
+    if (argmax) {
+        if (BF16) *reinterpret_cast<uint2 *>(argmax + o * 8) = make_uint2(am[0], am[1]);
+        else *reinterpret_cast<uint32_t *>(argmax + o * 4) = am[0];
+    }
+}
+
+template <bool BF16>
+__global__ __launch_bounds__(256) void pool_bwd_tiled_kernel(const PoolGeo g, FastDiv fd_cv, const void *__restrict__ dyv, const void *__restrict__ yv,
+                                                             const uint8_t *__restrict__ argmax, void *__restrict__ dxv)
+{
+    constexpr int VW = BF16 ? 8 : 4;
+    const int CV = g.C / VW;
+    const int idx = blockIdx.x * 256 + threadIdx.x;
+    if (idx >= g.Wo * CV) return;
+    const int q = fdiv(idx, fd_cv), cv = idx - q * CV;
+    const int np = blockIdx.y, n = np / g.Ho, pp = np - n * g.Ho;
+    const size_t o = ((size_t)np * g.Wo + q) * CV + cv;
+    const pool_u4 d = __builtin_nontemporal_load(reinterpret_cast<const pool_u4 *>(dyv) + o);
+    pool_u4 gate = d;
+    if (g.relu) {
+        const pool_u4 yy = __builtin_nontemporal_load(reinterpret_cast<const pool_u4 *>(yv) + o);
+        // keep dy where y > 0: a positive finite float / bfloat16 has a non-zero pattern with the sign bit clear
+#pragma unroll
+        for (int e = 0; e < VW; ++e) {
+            if (BF16) {
+                const uint32_t h = (yy[e >> 1] >> (16 * (e & 1))) & 0xffffu;
+                if (h == 0u || (h & 0x8000u)) gate[e >> 1] &= ~(0xffffu << (16 * (e & 1)));
+            } else {
+                if (!(__uint_as_float(yy[e]) > 0.f)) gate[e] = 0u;
+            }
+        }
+    }
+    uint32_t am[2];
+    if (BF16) { const uint2 a = *reinterpret_cast<const uint2 *>(argmax + o * 8); am[0] = a.x; am[1] = a.y; }
+    else { am[0] = *reinterpret_cast<const uint32_t *>(argmax + o * 4); am[1] = 0u; }
+    pool_u4 *dx = reinterpret_cast<pool_u4 *>(dxv);
+    for (int i = 0; i < g.wh; ++i) {
+        for (int j = 0; j < g.ww; ++j) {
+            const uint32_t code = (uint32_t)(i * g.ww + j);
+            pool_u4 out = {0u, 0u, 0u, 0u};
+#pragma unroll
+            for (int e = 0; e < VW; ++e) {
+                const bool hit = ((am[e >> 2] >> (8 * (e & 3))) & 255u) == code;
+                if (BF16) out[e >> 1] |= hit ? (gate[e >> 1] & (0xffffu << (16 * (e & 1)))) : 0u;
+                else out[e] = hit ? gate[e] : 0u;
+            }
+            const size_t off = (((size_t)n * g.H + pp * g.sh + i) * g.W + q * g.sw + j) * CV + cv;
+            __builtin_nontemporal_store(out, dx + off);
+        }
+    }
+}
+
+static bool pool_is_tiled(const PoolGeo &g, int vw)
+{
+    return g.wh == g.sh && g.ww == g.sw && g.ph == 0 && g.pw == 0 && g.H % g.wh == 0 && g.W % g.ww == 0 && g.C % vw == 0 &&
+           (int64_t)g.N * g.Ho <= 65535;      // rows of the output ride on gridDim.y
+}
+
 static int pool_geometry(const stanza_pool_desc *d, PoolGeo *g)
 {
     if (d->N <= 0 || d->H <= 0 || d->W <= 0 || d->C <= 0 || d->win_h <= 0 || d->win_w <= 0) return STANZA_EINVAL;
@@ -516,6 +616,15 @@ extern "C" int stanza_pool_relu_fwd(const stanza_pool_desc *desc, int32_t dtype,
     if (!aligned16(x) || !aligned16(y) || (reinterpret_cast<uintptr_t>(argmax) & 7u)) return STANZA_EALIGN;
     hipStream_t st = (hipStream_t)stream;
     const size_t outs = (size_t)g.N * g.Ho * g.Wo * g.C;
+    if (pool_is_tiled(g, dtype == STANZA_BF16 ? 8 : 4)) {
+        const int cv = g.C / (dtype == STANZA_BF16 ? 8 : 4);
+        const dim3 grid((unsigned)cdiv(g.Wo * cv, 256), (unsigned)(g.N * g.Ho));
+        if (dtype == STANZA_BF16)
+            hipLaunchKernelGGL(pool_fwd_tiled_kernel<true>, grid, dim3(256), 0, st, g, make_fastdiv(cv), x, y, argmax);
+        else
+            hipLaunchKernelGGL(pool_fwd_tiled_kernel<false>, grid, dim3(256), 0, st, g, make_fastdiv(cv), x, y, argmax);
+        return launch_status();
+    }
     if (dtype == STANZA_BF16) {
         const size_t total = outs / 8;
         hipLaunchKernelGGL(pool_fwd_bf16_kernel, dim3((unsigned)cdiv64(total, 256)), dim3(256), 0, st, g, (const uint16_t *)x, (uint16_t *)y, argmax, total);
@@ -542,6 +651,15 @@ extern "C" int stanza_pool_relu_bwd(const stanza_pool_desc *desc, int32_t dtype,
     if (!aligned16(dy) || !aligned16(dx) || !aligned16(y) || (reinterpret_cast<uintptr_t>(argmax) & 7u)) return STANZA_EALIGN;
     hipStream_t st = (hipStream_t)stream;
     const size_t ins = (size_t)g.N * g.H * g.W * g.C;
+    if (pool_is_tiled(g, dtype == STANZA_BF16 ? 8 : 4)) {
+        const int cv = g.C / (dtype == STANZA_BF16 ? 8 : 4);
+        const dim3 grid((unsigned)cdiv(g.Wo * cv, 256), (unsigned)(g.N * g.Ho));
+        if (dtype == STANZA_BF16)
+            hipLaunchKernelGGL(pool_bwd_tiled_kernel<true>, grid, dim3(256), 0, st, g, make_fastdiv(cv), dy, y, argmax, dx);
+        else
+            hipLaunchKernelGGL(pool_bwd_tiled_kernel<false>, grid, dim3(256), 0, st, g, make_fastdiv(cv), dy, y, argmax, dx);
+        return launch_status();
+    }
     if (dtype == STANZA_BF16) {
         const size_t total = ins / 8;
         hipLaunchKernelGGL(pool_bwd_bf16_kernel, dim3((unsigned)cdiv64(total, 256)), dim3(256), 0, st, g, (const uint16_t *)dy, (const uint16_t *)y, argmax,

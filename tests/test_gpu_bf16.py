@@ -101,7 +101,8 @@ def test_bf16_rejects_odd_channels(api):
         api.stanza_conv_fwd(d, x, w, None, y)
 
 
-@pytest.mark.parametrize("case", [(2, 16, 16, 8, 2, 2, 0, True), (2, 15, 13, 16, 3, 2, 0, True), (1, 14, 15, 24, 3, 2, 1, False)])
+@pytest.mark.parametrize("case", [(2, 16, 16, 8, 2, 2, 0, True), (2, 15, 13, 16, 3, 2, 0, True), (1, 14, 15, 24, 3, 2, 1, False),
+                                  (3, 32, 32, 64, 2, 2, 0, True), (2, 12, 18, 24, 3, 3, 0, False)])
 def test_pool_bf16(api, o32, case):
     N, H, W, C, win, st, pad, relu = case
     g = PoolGeom(N, H, W, C, win, st, pad, relu)

@@ -178,7 +178,9 @@ def test_conv_sliced_launches(api, o32, case):
 
 POOL_CASES = [(2, 16, 16, 8, 2, 2, 0, True), (2, 15, 13, 12, 3, 2, 0, True), (2, 14, 15, 16, 3, 2, 1, True),
               (1, 9, 9, 3, 2, 2, 0, True), (1, 11, 11, 5, 3, 2, 1, False), (3, 8, 8, 4, 2, 2, 0, False),
-              (1, 12, 12, 4, 3, 1, 1, True)]
+              (1, 12, 12, 4, 3, 1, 1, True),
+              # non-overlapping windows over whole images: the one-thread-per-output kernels
+              (2, 12, 18, 24, 3, 3, 0, True), (5, 64, 64, 128, 2, 2, 0, True), (2, 20, 12, 36, 2, 2, 0, False)]
 
 
 @pytest.mark.parametrize("case", POOL_CASES, ids=lambda c: "n{}h{}w{}c{}win{}s{}p{}r{}".format(*c))
