@@ -141,7 +141,7 @@ static int fc_run(const stanza_fc_desc *desc, int n_global, const float *feats, 
     for (int l = 0; l < L; ++l) {
         if (!host_W[l] || !host_b[l]) return STANZA_ENULL;
         if (fused ? (!host_vW[l] || !host_vb[l]) : (!host_gW[l] || !host_gb[l])) return STANZA_ENULL;
-        if (!aligned16(host_W[l]) || !aligned16(fused ? host_vW[l] : host_gW[l])) return STANZA_EALIGN;
+        if (!aligned16(host_W[l]) || !aligned16(host_b[l]) || !aligned16(fused ? host_vW[l] : host_gW[l])) return STANZA_EALIGN;
     }
     hipStream_t st = (hipStream_t)stream;
     float *base = (float *)ws;

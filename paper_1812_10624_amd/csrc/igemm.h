@@ -149,8 +149,12 @@ __global__ __launch_bounds__(NTHREADS, (BM >= 256 ? 3 : 4)) void igemm_kernel(co
     constexpr int LDK = BK;      // unpadded 64-byte rows; the four 16-byte vectors of a row are XOR-swizzled (see kq_sw)
     constexpr int LDA = BM + PAD_V, LDB = BN + PAD_V;
     constexpr int A_FLOATS = A_ROWK ? BM * LDK : BK * LDA, B_FLOATS = B_ROWK ? BN * LDK : BK * LDB;
-    __shared__ __attribute__((aligned(16))) float As[2][A_FLOATS];
-    __shared__ __attribute__((aligned(16))) float Bs[2][B_FLOATS];
+    // one block: [A stage 0][A stage 1][B stage 0][B stage 1]; the epilogue reuses it to stage 32 output rows at a time
+    constexpr int SMEM_FLOATS = 2 * (A_FLOATS + B_FLOATS);
+    static_assert(SMEM_FLOATS >= 32 * BN, "room for 32 staged output rows");
+    __shared__ __attribute__((aligned(16))) float smem[SMEM_FLOATS];
+    auto AsBuf = [&](int buf) -> float * { return smem + buf * A_FLOATS; };
+    auto BsBuf = [&](int buf) -> float * { return smem + 2 * A_FLOATS + buf * B_FLOATS; };
 
     // Workgroup -> (reduction slice, tile).  Consecutive workgroup ids land on different XCDs (round robin over
     // 8), so give each XCD one contiguous run of work items: neighbours in M share their input halo and the
@@ -450,18 +454,18 @@ __global__ __launch_bounds__(NTHREADS, (BM >= 256 ? 3 : 4)) void igemm_kernel(co
             float4 v = ra[i];
             if (MODE != MODE_FWD && amask) v = gate4(v, rg[i]);
             if (MODE == MODE_BWD_WEIGHT) {
-                *reinterpret_cast<float4 *>(&As[buf][(t / A_F4 + A_RP * i) * LDA + (t % A_F4) * 4]) = v;
+                *reinterpret_cast<float4 *>(&AsBuf(buf)[(t / A_F4 + A_RP * i) * LDA + (t % A_F4) * 4]) = v;
                 if (want_db) { dbacc.x += v.x; dbacc.y += v.y; dbacc.z += v.z; dbacc.w += v.w; }
             } else {
-                *reinterpret_cast<float4 *>(&As[buf][(row0 + RPP * i) * LDK + kq_sw * 4]) = v;
+                *reinterpret_cast<float4 *>(&AsBuf(buf)[(row0 + RPP * i) * LDK + kq_sw * 4]) = v;
             }
         }
 #pragma unroll
         for (int i = 0; i < BV; ++i) {
             if (MODE == MODE_FWD) {
-                *reinterpret_cast<float4 *>(&Bs[buf][(row0 + RPP * i) * LDK + kq_sw * 4]) = rb[i];
+                *reinterpret_cast<float4 *>(&BsBuf(buf)[(row0 + RPP * i) * LDK + kq_sw * 4]) = rb[i];
             } else {
-                *reinterpret_cast<float4 *>(&Bs[buf][(t / B_F4 + B_RP * i) * LDB + (t % B_F4) * 4]) = rb[i];
+                *reinterpret_cast<float4 *>(&BsBuf(buf)[(t / B_F4 + B_RP * i) * LDB + (t % B_F4) * 4]) = rb[i];
             }
         }
     };
@@ -499,12 +503,12 @@ __global__ __launch_bounds__(NTHREADS, (BM >= 256 ? 3 : 4)) void igemm_kernel(co
             if (A_ROWK) {
 #pragma unroll
                 for (int i = 0; i < TM; ++i)
-                    a4[slot][i] = *reinterpret_cast<const float4 *>(&As[buf][(wave_m * WTM + i * 32 + lrow) * LDK + ((gi * 2 + lk) ^ rd_sw) * 4]);
+                    a4[slot][i] = *reinterpret_cast<const float4 *>(&AsBuf(buf)[(wave_m * WTM + i * 32 + lrow) * LDK + ((gi * 2 + lk) ^ rd_sw) * 4]);
             }
             if (B_ROWK) {
 #pragma unroll
                 for (int j = 0; j < TN; ++j)
-                    b4[slot][j] = *reinterpret_cast<const float4 *>(&Bs[buf][(wave_n * WTN + j * 32 + lrow) * LDK + ((gi * 2 + lk) ^ rd_sw) * 4]);
+                    b4[slot][j] = *reinterpret_cast<const float4 *>(&BsBuf(buf)[(wave_n * WTN + j * 32 + lrow) * LDK + ((gi * 2 + lk) ^ rd_sw) * 4]);
             }
         };
         // reduction row that lane half lk multiplies in k-step ks: pairs (8g+j, 8g+4+j) when a row-major operand fixes
@@ -513,11 +517,11 @@ __global__ __launch_bounds__(NTHREADS, (BM >= 256 ? 3 : 4)) void igemm_kernel(co
         auto read_scalar = [&](int ks, int slot) {
             if (!A_ROWK) {
 #pragma unroll
-                for (int i = 0; i < TM; ++i) a1[slot][i] = As[buf][krow(ks) * LDA + wave_m * WTM + i * 32 + lrow];
+                for (int i = 0; i < TM; ++i) a1[slot][i] = AsBuf(buf)[krow(ks) * LDA + wave_m * WTM + i * 32 + lrow];
             }
             if (!B_ROWK) {
 #pragma unroll
-                for (int j = 0; j < TN; ++j) b1[slot][j] = Bs[buf][krow(ks) * LDB + wave_n * WTN + j * 32 + lrow];
+                for (int j = 0; j < TN; ++j) b1[slot][j] = BsBuf(buf)[krow(ks) * LDB + wave_n * WTN + j * 32 + lrow];
             }
         };
         read_group(0, 0);
@@ -547,7 +551,7 @@ __global__ __launch_bounds__(NTHREADS, (BM >= 256 ? 3 : 4)) void igemm_kernel(co
     if (MODE == MODE_BWD_WEIGHT && want_db) {
         // The A_RP threads t, t + A_F4, ... hold partial sums of the same 4 channels: add them in thread order
         // through LDS (the last stage barrier has passed, the tiles are free).
-        float *red = &As[0][0];
+        float *red = smem;
         *reinterpret_cast<float4 *>(&red[(t / A_F4) * LDA + (t % A_F4) * 4]) = dbacc;
         __syncthreads();
         if (t < BM && m0 + t < p.M) {
@@ -582,6 +586,51 @@ __global__ __launch_bounds__(NTHREADS, (BM >= 256 ? 3 : 4)) void igemm_kernel(co
         }
         return (size_t)row * p.Nn + col;
     };
+    if (MODE != MODE_BWD_WEIGHT && (p.Nn & 3) == 0) {
+        // Output rows are whole 16-byte vectors: stage the tile in LDS 32 rows at a time and let every thread move float4s of
+        // full row segments (bias / ReLU, or accumulate / mask, on the vectors).  One scalar store per accumulator register
+        // (64 per thread, plus as many mask and accumulate loads in BWD_DATA) cost 9 % of a 64-channel 3x3 layer and a quarter
+        // of a 1x1 layer with 64 input channels.
+        constexpr int CH4 = BN / 4, ROWS_PASS = NTHREADS / CH4;
+        float *Cs = smem;
+#pragma unroll
+        for (int chunk = 0; chunk < BM / 32; ++chunk) {
+            __syncthreads();       // the stage buffers (first chunk) or the previous chunk have been read by everyone
+#pragma unroll
+            for (int i = 0; i < TM; ++i) {
+                if (wave_m * WTM + i * 32 != chunk * 32) continue;
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r)
+                        Cs[(8 * (r >> 2) + 4 * lk + (r & 3)) * BN + wave_n * WTN + j * 32 + lrow] = acc[i][j][r];
+            }
+            __syncthreads();
+#pragma unroll
+            for (int pass = 0; pass < 32 / ROWS_PASS; ++pass) {
+                const int row_l = pass * ROWS_PASS + t / CH4, c4 = (t % CH4) * 4;
+                const int row = m0 + chunk * 32 + row_l, col = n0 + c4;
+                if (row >= p.M || col >= p.Nn) continue;
+                float4 v = *reinterpret_cast<const float4 *>(&Cs[row_l * BN + c4]);
+                const size_t o = out_index(row, col);
+                if (MODE == MODE_FWD) {
+                    if (p.flags & EPI_BIAS) {
+                        const float4 b = ldg4(p.bias + col);
+                        v.x += b.x; v.y += b.y; v.z += b.z; v.w += b.w;
+                    }
+                    if (p.flags & EPI_RELU) v = make_float4(fmaxf(v.x, 0.f), fmaxf(v.y, 0.f), fmaxf(v.z, 0.f), fmaxf(v.w, 0.f));
+                } else {
+                    if (p.flags & EPI_ACCUM) {
+                        const float4 old = ldg4(p.out + o);
+                        v.x += old.x; v.y += old.y; v.z += old.z; v.w += old.w;
+                    }
+                    if (p.flags & EPI_XMASK) v = gate4(v, ldg4(p.xmask + o));
+                }
+                *reinterpret_cast<float4 *>(p.out + o) = v;
+            }
+        }
+        return;
+    }
 #pragma unroll
     for (int j = 0; j < TN; ++j) {
         const int col = n0 + wave_n * WTN + j * 32 + lrow;
