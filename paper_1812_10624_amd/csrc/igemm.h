@@ -130,7 +130,9 @@ __device__ __forceinline__ float4 gate4(float4 v, float4 m)
 // inside one filter tap, so the tap is wavefront-uniform (scalar registers) and a row's address is a precomputed row
 // offset plus a scalar; no per-thread division or multiplication is left in the main loop.
 template <int MODE, int BM, int BN, int WM, int WN, bool VECA, bool VECB, bool FAST = false>
-__global__ __launch_bounds__(NTHREADS, (BM >= 256 ? 3 : 4)) void igemm_kernel(const GemmParams p)   // 128 registers: four workgroups per CU
+// register cap: 128 (four workgroups per CU) for the vector-fetch variants of the 128-row tiles; the scalar-gather variants
+// (3-channel first layers) need more and spill under it
+__global__ __launch_bounds__(NTHREADS, (BM >= 256 ? 3 : (VECA && VECB) ? 4 : 2)) void igemm_kernel(const GemmParams p)
 {
     static_assert(WM * WN == 4, "four wavefronts per workgroup");
     static_assert(BM % 64 == 0 && BN % 64 == 0, "loader granularity");
