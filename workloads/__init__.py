@@ -95,21 +95,21 @@ def _alexnet_ops():
                    ("c", 384, 3, 1, 1), ("c", 384, 3, 1, 1), ("c", 256, 3, 1, 1), ("p", 3, 2, 0)])
 
 
-def _vgg16_ops():
+def _vgg16_ops(reps_per_stage=(2, 2, 3, 3, 3)):
     spec = []
-    for width, reps in ((64, 2), (128, 2), (256, 3), (512, 3), (512, 3)):
+    for width, reps in zip((64, 128, 256, 512, 512), reps_per_stage):
         spec += [("c", width, 3, 1, 1)] * reps + [("p", 2, 2, 0)]
     return _chain(spec)
 
 
-def _resnet50_ops():
+def _resnet50_ops(depths=(3, 4, 6, 3)):
     """Bottleneck residual stack without normalisation layers: stem 7x7/2, 3x3/2 max-pool
-    (pad 1), stages [3,4,6,3] of 1x1 -> 3x3 (carries the stride) -> 1x1 with a projection
-    shortcut in the first block of each stage, global average pool."""
+    (pad 1), stages [3,4,6,3] ([3,8,36,3] for the 152-layer network) of 1x1 -> 3x3 (carries the
+    stride) -> 1x1 with a projection shortcut in the first block of each stage, global average pool."""
     ops = [_conv("stem", "x0", "stem", 64, 7, 2, 3, relu=True),
            _pool("stem", "s0", 3, 2, 1, relu=True)]
     cur = "s0"
-    for si, (width, blocks) in enumerate(((64, 3), (128, 4), (256, 6), (512, 3)), start=1):
+    for si, (width, blocks) in enumerate(zip((64, 128, 256, 512), depths), start=1):
         for bi in range(blocks):
             stride = 2 if (bi == 0 and si > 1) else 1
             tag = f"s{si}b{bi}"
@@ -176,6 +176,13 @@ def get_workload(name: str) -> Workload:
     if name == "minires":
         return Workload("minires", K=2, B=3, image=(33, 35, 3), ops=_mini_res_ops(),
                         fc_dims=[32, 7], notes="small residual stack for exhaustive parity")
+    # two more networks of the paper's table of models, at its per-worker batch sizes
+    if name == "vgg19":
+        return Workload("vgg19", K=8, B=64, image=(224, 224, 3), ops=_vgg16_ops((2, 2, 4, 4, 4)),
+                        fc_dims=[25088, 4096, 4096, 1000])
+    if name == "resnet152":
+        return Workload("resnet152", K=8, B=32, image=(224, 224, 3), ops=_resnet50_ops((3, 8, 36, 3)),
+                        fc_dims=[2048, 1000], notes="without normalisation layers, like resnet50 here")
     if name == "mlp":
         # 3 hidden layers of 1024, 1024, 4096 units on 3x32x32 inputs, separated after the second hidden layer;
         # the largest row of the paper's table: total batch 1024, base learning rate 0.08, vanilla SGD
@@ -188,7 +195,7 @@ def get_workload(name: str) -> Workload:
     raise KeyError(name)
 
 
-WORKLOAD_NAMES = ("tiny", "alexnet", "vgg16", "resnet50", "minires", "mlp", "minimlp")
+WORKLOAD_NAMES = ("tiny", "alexnet", "vgg16", "resnet50", "minires", "mlp", "minimlp", "vgg19", "resnet152")
 
 
 def _out_dim(h, win, stride, pad):
