@@ -165,3 +165,34 @@ def test_ps_aggregate_full_size(api, o32, which):
         assert rel_err(host(gw[t])[:cut], w_ref) < 1e-6, t
         tail_w = host(gw[t])[-8:]
         assert np.isfinite(tail_w).all() and not np.array_equal(tail_w, ws_[t][-8:])
+
+
+def test_conv_input_of_two_gibibytes(api, o32):
+    """Largest case: a 2 GiB float32 input (2^29 elements) is beyond the 32-bit byte offsets of the vector fetch path; the
+    launch falls back to element-wise addressing and must still be right everywhere, the far end of the tensor included."""
+    N, H, W, C, K, R, S, st, pad = 1, 2048, 2048, 128, 8, 3, 3, 1, 1
+    g = ConvGeom(N, H, W, C, K, R, S, st, pad)
+    r = wl_mod.rng_for(41, "huge")
+    x = r.standard_normal((N, H, W, C), dtype=np.float32)
+    w = r.standard_normal((K, R, S, C), dtype=np.float32) * np.float32((2.0 / (R * S * C)) ** 0.5)
+    b = r.standard_normal(K, dtype=np.float32) * np.float32(0.1)
+    assert x.nbytes == 1 << 31
+    xd, wd, bd = dev(x), dev(w), dev(b)
+    d = api.conv_desc(N, H, W, C, K, R, S, st, pad, api.F32, api.CONV_BIAS | api.CONV_RELU)
+    y = torch.empty((N, H, W, K), device="cuda:0")
+    api.stanza_conv_fwd(d, xd, wd, bd, y)
+    yh = host(y)
+    idx = _sample_idx(yh.shape, 14, 32) + [(0, 2047, 2047, 7), (0, 2047, 0, 0), (0, 1024, 2047, 3)]
+    want = [o32.conv_fwd_at(g, x, w, b, True, *i) for i in idx]
+    _check([yh[i] for i in idx], want, float(np.abs(yh).max()), "2 GiB input fwd")
+    # filter gradient over the same input (dy small, x large)
+    dy = r.standard_normal((N, H, W, K), dtype=np.float32)
+    dd = api.conv_desc(N, H, W, C, K, R, S, st, pad, api.F32, api.CONV_BIAS)
+    ws = torch.empty(max(16, api.stanza_conv_workspace_bytes(dd, 2)), dtype=torch.uint8, device="cuda:0")
+    dw = torch.empty((K, R, S, C), device="cuda:0")
+    db = torch.empty((K,), device="cuda:0")
+    api.stanza_conv_bwd_weight(dd, xd, dev(dy), None, dw, db, ws)
+    dwh = host(dw)
+    idx = _sample_idx(dwh.shape, 15, 12)
+    want = [o32.conv_bwd_weight_at(g, x, dy, *i) for i in idx]
+    _check([dwh[i] for i in idx], want, float(np.abs(dwh).max()), "2 GiB input bwd_weight")
