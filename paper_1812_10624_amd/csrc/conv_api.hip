@@ -56,9 +56,11 @@ static ShapeDim shape_dim(TileShape s)
 }
 
 // Tall tiles while they still give every CU a couple of workgroups; 64-wide when the GEMM is narrow.
-static TileShape pick_shape(int mode, int M, int Nn, int splits)
+// can_slice: the launch may cut tiles into reduction slices, so a small tile count is no reason to shrink the tile.
+static TileShape pick_shape(int mode, int M, int Nn, int splits, bool can_slice)
 {
     const int want = 512;
+    if (can_slice && M > 64 && Nn > 64) return T128x128;
     if (Nn <= 64) {
         if (mode != MODE_BWD_WEIGHT && (int64_t)cdiv(M, 256) * splits >= want) return T256x64;
         if ((int64_t)cdiv(M, 128) * splits >= want) return T128x64;
@@ -91,7 +93,7 @@ struct GemmPlan {
 static GemmPlan plan_gemm(int mode, int M, int Nn, int Kd, int bw_splits, bool may_slice)
 {
     GemmPlan pl{};
-    pl.shape = pick_shape(mode, M, Nn, mode == MODE_BWD_WEIGHT ? bw_splits : 1);
+    pl.shape = pick_shape(mode, M, Nn, mode == MODE_BWD_WEIGHT ? bw_splits : 1, mode != MODE_BWD_WEIGHT && may_slice && cdiv(Kd, BK) >= 16);
     const ShapeDim sd = shape_dim(pl.shape);
     pl.tilesM = cdiv(M, sd.bm);
     pl.tilesN = cdiv(Nn, sd.bn);
