@@ -34,6 +34,9 @@ def main():
     ap.add_argument("--dtype", default="f32", choices=["f32", "bf16"], help="conv-stack storage type (accumulation is always f32)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--detail", action="store_true", help="per-call timing table on stderr")
+    ap.add_argument("--graph", action="store_true",
+                    help="replay the step as one HIP graph in the timed region (launch-bound workloads); the per-call breakdown "
+                         "and the roofline figures then come from the eager warm-up steps")
     ap.add_argument("--calibrate", action="store_true",
                     help="also launch one stanza_add_relu_fwd over 3 x 1 GiB (2 GiB read, 1 GiB written): the known-size "
                          "kernel that scales rocprofv3's FETCH_SIZE / WRITE_SIZE counters")
@@ -117,18 +120,33 @@ def main():
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
-    records.clear()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        step()
-    torch.cuda.synchronize()
-    t1 = time.perf_counter()
+    if args.graph:
+        assert args.warmup >= 1, "--graph takes its per-call breakdown from the warm-up steps"
+        n_timed_eager = args.warmup
+        netrun.api = api                       # no event pairs inside the capture
+        graph = netrun.StepGraph(lambda: (feats[:B].copy_(worker.forward().view(B, -1)), fcw.step(feats, labels),
+                                          worker.backward(fcw.dfeats[:B]), agg.step(1.0, wl.lr, wl.momentum, wl.weight_decay)), warmup=0)
+        graph.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            graph.replay()
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+    else:
+        n_timed_eager = args.steps
+        records.clear()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            step()
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / args.steps
 
     per = {}
     for tag, s, e in records:
         per.setdefault(tag, []).append(s.elapsed_time(e))
-    tot = {k: sum(v) / args.steps for k, v in per.items()}      # ms per step per entry point
+    tot = {k: sum(v) / n_timed_eager for k, v in per.items()}      # ms per step per entry point
     conv_ms = sum(tot.get(k, 0.0) for k in ("stanza_conv_fwd", "stanza_conv_bwd_data", "stanza_conv_bwd_weight"))
     conv_worker_ms = sum(v for k, v in tot.items() if k not in ("stanza_fc_step", "stanza_ps_aggregate"))
     fwd_f, bwd_f = W.conv_flops(wl)
@@ -147,12 +165,12 @@ def main():
         shapes = W.shape_pass(wl)
         for kind in ("stanza_conv_fwd", "stanza_conv_bwd_weight", "stanza_conv_bwd_data"):
             v = per.get(kind, [])
-            calls = len(v) // args.steps
+            calls = len(v) // n_timed_eager
             ops_k = conv_ops if kind == "stanza_conv_fwd" else list(reversed(conv_ops))
             if kind == "stanza_conv_bwd_data":
                 ops_k = [op for op in ops_k if op["src"] != "x0"]
             for ci in range(calls):
-                ms = sum(v[ci::calls]) / args.steps
+                ms = sum(v[ci::calls]) / n_timed_eager
                 op = ops_k[ci]
                 nn, ho, wo, kk = shapes[op["dst"]]
                 c = shapes[op["src"]][3]
@@ -182,7 +200,7 @@ def main():
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": args.dtype, "data": "synthetic",
+        "dtype": args.dtype, "data": "synthetic", "launch": "hip_graph_replay" if args.graph else "eager",
         "config": {"workload": f"{wl.name}_shaped_conv_worker_B{B}_fc_worker_n{n}_K{K}_" + ("fp32" if args.dtype == "f32" else "bf16in_fp32acc"),
                    "per_worker_batch": B, "conv_workers_K": K, "fc_rows": n},
         "conv_worker_images_per_s": B / (conv_worker_ms * 1e-3),

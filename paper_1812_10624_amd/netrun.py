@@ -228,3 +228,22 @@ class Aggregator:
 
     def step(self, scale, lr, momentum, weight_decay, order=api.SUM_INDEX_ORDER):
         api.stanza_ps_aggregate_ordered_planned(order, self.plan, scale, lr, momentum, weight_decay, self.ws)
+
+
+class StepGraph:
+    """A fixed sequence of libstanza launches (one training step, or any part of it) captured once as a HIP graph and
+    replayed: for networks made of many short kernels (residual stacks at small batch, the MLP) the launches themselves
+    take a noticeable share of the step.  `fn` must only enqueue work on the current stream over buffers that stay put;
+    it is run `warmup` times first so that lazily created buffers exist before the capture.  The library records no memset
+    nodes, every kernel overwrites or updates its outputs in place, so a replay does exactly what the eager calls do."""
+
+    def __init__(self, fn, warmup: int = 1):
+        for _ in range(warmup):
+            fn()
+        torch.cuda.synchronize()
+        self.graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(self.graph):
+            fn()
+
+    def replay(self):
+        self.graph.replay()

@@ -73,3 +73,59 @@ def test_conv_stack_real_shapes(api, o32, name, B):
             assert e3 < 1e-4, (name, op["name"], e3)
             worst = max(worst, e3)
     print(f"{name}: features E={e_feat:.2e}, worst layer-wise backward E={worst:.2e}")
+
+
+@pytest.mark.parametrize("name", ["tiny", "minires"])
+def test_step_graph_replays_equal_eager_steps(api, name):
+    """The whole layer-separated step captured as a HIP graph: three replays, with eager work and synchronisations between
+    them, leave every parameter bit-identical to three eager steps from the same state (all reductions are fixed-order)."""
+    import copy
+    from paper_1812_10624_amd.netrun import Aggregator, ConvWorker, FcWorker, StepGraph
+    wl = wl_mod.get_workload(name)
+    K, B = wl.K, wl.B
+    cp = {n: (dev(w), dev(b)) for n, (w, b) in wl_mod.gen_conv_params(wl, 0).items()}
+    cm = {n: (torch.zeros_like(w), torch.zeros_like(b)) for n, (w, b) in cp.items()}
+    fp = [(dev(w), dev(b)) for w, b in wl_mod.gen_fc_params(wl, 0)]
+    fm = [(torch.zeros_like(w), torch.zeros_like(b)) for w, b in fp]
+    imgs = [dev(wl_mod.gen_images(wl, 0, k)) for k in range(K)]
+    labels = dev(wl_mod.gen_labels(wl, 0))
+    workers = [ConvWorker(wl.ops, wl.image, B, cp) for _ in range(K)]
+    fcw = FcWorker(wl.fc_dims, K * B, fp, fm, wl.lr, 0.9, 1e-4)  # momentum on, so the velocity buffers are exercised
+    feats = torch.empty((K * B, wl.fc_dims[0]), device="cuda:0")
+    names = list(cp)
+    agg = Aggregator([cp[n][i] for n in names for i in range(2)], [cm[n][i] for n in names for i in range(2)],
+                     [[wk.grads[n][i] for n in names for i in range(2)] for wk in workers])
+
+    def step():
+        for k, wk in enumerate(workers):
+            feats[k * B:(k + 1) * B].copy_(wk.forward(imgs[k]).view(B, -1))
+        fcw.step(feats, labels)
+        for k, wk in enumerate(workers):
+            wk.backward(fcw.dfeats[k * B:(k + 1) * B])
+        agg.step(1.0, wl.lr, 0.9, 1e-4)
+
+    state = [t for pair in list(cp.values()) + list(cm.values()) + fp + fm for t in pair]
+    saved = [t.clone() for t in state]
+
+    def restore():
+        for t, s in zip(state, saved):
+            t.copy_(s)
+
+    for _ in range(3):
+        step()
+    torch.cuda.synchronize()
+    eager = [t.clone() for t in state]
+    eager_loss = float(fcw.loss.cpu()[0])
+    restore()
+    g = StepGraph(step, warmup=1)
+    restore()
+    torch.cuda.synchronize()
+    scratch = torch.zeros(1 << 20, device="cuda:0")
+    for _ in range(3):
+        g.replay()
+        scratch.add_(1.0)                       # the program's own eager work between replays
+        torch.cuda.synchronize()
+    for t, e in zip(state, eager):
+        assert torch.equal(t, e)
+    assert float(fcw.loss.cpu()[0]) == eager_loss
+    assert not torch.equal(state[0], saved[0])
