@@ -186,6 +186,27 @@ class Oracle:
         self._l.oracle_gap_bwd(n, h * w, c, self._p(np.ascontiguousarray(df.reshape(n, c))), self._p(dx))
         return dx
 
+    # -- batch normalisation over the rows of an NHWC tensor (training mode)
+    def bn_fwd(self, x, gamma, beta, eps=1e-5, relu=False, run_mean=None, run_var=None, mom=0.1):
+        """Returns y, mean [C], istd [C]; run_mean / run_var are updated in place when given."""
+        c = x.shape[-1]
+        rows = x.size // c
+        y = np.empty_like(x)
+        mean, istd = np.empty(c, self.dtype), np.empty(c, self.dtype)
+        self._l.oracle_bn_fwd(C.c_size_t(rows), c, self._p(x), self._p(gamma), self._p(beta), C.c_double(eps), int(relu),
+                              self._p(y), self._p(mean), self._p(istd), self._p(run_mean), self._p(run_var), C.c_double(mom))
+        return y, mean, istd
+
+    def bn_bwd(self, x, dy, gamma, mean, istd):
+        """dy: gradient of the pre-ReLU output.  Returns dx, dgamma, dbeta."""
+        c = x.shape[-1]
+        rows = x.size // c
+        dx = np.empty_like(x)
+        dg, db = np.empty(c, self.dtype), np.empty(c, self.dtype)
+        self._l.oracle_bn_bwd(C.c_size_t(rows), c, self._p(x), self._p(dy), self._p(gamma), self._p(mean), self._p(istd),
+                              self._p(dx), self._p(dg), self._p(db))
+        return dx, dg, db
+
     # -- FC
     def fc_fwd(self, a, w, b=None, relu=False):
         n, cin = a.shape

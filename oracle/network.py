@@ -20,8 +20,10 @@ import numpy as np
 from . import ConvGeom, Oracle, PoolGeom
 
 
-def conv_stack_forward(o: Oracle, ops: List[dict], x0, params) -> Dict[str, np.ndarray]:
-    """Run the op list; returns every named buffer plus '<dst>#argmax' for pools."""
+def conv_stack_forward(o: Oracle, ops: List[dict], x0, params, bn_groups: int = 1) -> Dict[str, np.ndarray]:
+    """Run the op list; returns every named buffer plus '<dst>#argmax' for pools and '<dst>#stats' for normalisation
+    layers.  bn_groups > 1: x0 stacks the batches of that many workers, and every normalisation layer takes its
+    statistics over each worker's rows separately (what the workers do when each runs the stack on its own batch)."""
     buf = {"x0": x0}
     for op in ops:
         kind = op["op"]
@@ -36,6 +38,15 @@ def conv_stack_forward(o: Oracle, ops: List[dict], x0, params) -> Dict[str, np.n
             n, h, w, c = x.shape
             g = PoolGeom(n, h, w, c, op["win"], op["stride"], op["pad"], op["relu"])
             buf[op["dst"]], buf[op["dst"] + "#argmax"] = o.pool_relu_fwd(g, x)
+        elif kind == "bn":
+            x = buf[op["src"]]
+            gamma, beta = params[op["name"]]
+            per = x.shape[0] // bn_groups
+            assert per * bn_groups == x.shape[0]
+            parts = [o.bn_fwd(np.ascontiguousarray(x[i * per:(i + 1) * per]), gamma, beta, op["eps"], op["relu"])
+                     for i in range(bn_groups)]
+            buf[op["dst"]] = np.concatenate([p[0] for p in parts], axis=0)
+            buf[op["dst"] + "#stats"] = [(p[1], p[2]) for p in parts]
         elif kind == "add_relu":
             buf[op["dst"]] = o.add_relu_fwd(buf[op["a"]], buf[op["b"]])
         elif kind == "gap":
@@ -63,8 +74,9 @@ def conv_stack_backward(o: Oracle, ops: List[dict], buf, params, dfeat):
             dy = grad[op["dst"]]
             if op["relu"]:
                 dy = o.relu_bwd(dy, buf[op["dst"]])
-            wt, _ = params[op["name"]]
-            pgrads[op["name"]] = o.conv_bwd_weight(g, x, dy)
+            wt, bias = params[op["name"]]
+            dw, db = o.conv_bwd_weight(g, x, dy)
+            pgrads[op["name"]] = (dw, db if bias is not None else None)
             if op["src"] != "x0":
                 give(op["src"], o.conv_bwd_data(g, dy, wt))
         elif kind == "pool":
@@ -72,6 +84,21 @@ def conv_stack_backward(o: Oracle, ops: List[dict], buf, params, dfeat):
             n, h, w, c = x.shape
             g = PoolGeom(n, h, w, c, op["win"], op["stride"], op["pad"], op["relu"])
             give(op["src"], o.pool_relu_bwd(g, grad[op["dst"]], buf[op["dst"]], buf[op["dst"] + "#argmax"]))
+        elif kind == "bn":
+            x, dy = buf[op["src"]], grad[op["dst"]]
+            if op["relu"]:
+                dy = o.relu_bwd(dy, buf[op["dst"]])
+            gamma, _ = params[op["name"]]
+            stats = buf[op["dst"] + "#stats"]
+            per = x.shape[0] // len(stats)
+            dxs, dg, db = [], 0.0, 0.0
+            for i, (mean, istd) in enumerate(stats):
+                rows = slice(i * per, (i + 1) * per)
+                dxi, dgi, dbi = o.bn_bwd(np.ascontiguousarray(x[rows]), np.ascontiguousarray(dy[rows]), gamma, mean, istd)
+                dxs.append(dxi)
+                dg, db = dg + dgi.astype(np.float64), db + dbi.astype(np.float64)
+            pgrads[op["name"]] = (o.arr(dg), o.arr(db))
+            give(op["src"], np.concatenate(dxs, axis=0))
         elif kind == "add_relu":
             dz = o.relu_bwd(grad[op["dst"]], buf[op["dst"]])
             give(op["a"], dz)
@@ -83,14 +110,22 @@ def conv_stack_backward(o: Oracle, ops: List[dict], buf, params, dfeat):
     return pgrads, grad
 
 
-def fc_step(o: Oracle, feats, labels, fc_params, fc_mom, lr, momentum, wd, update=True):
+def fc_step(o: Oracle, feats, labels, fc_params, fc_mom, lr, momentum, wd, update=True, dropout=None):
     """FC worker: forward, mean softmax cross-entropy over all rows of feats, backward with the
     pre-update weights, then the momentum-SGD update in place.  Returns a dict with loss, pred,
-    dfeats, the activations and the raw gradients."""
-    acts = [feats]
+    dfeats, the activations and the raw gradients.
+    dropout = (p, seed, step): every hidden layer's ReLU output passes through seeded dropout (oracle/dropout.py);
+    the next layer reads the dropped activations, and the gradient returns through the mask and then the ReLU."""
+    from . import dropout as dr
+    acts = [feats]            # what each layer reads
+    hidden = [None]           # the ReLU outputs before dropout
     L = len(fc_params)
     for li, (w, b) in enumerate(fc_params):
-        acts.append(o.fc_fwd(acts[-1], w, b, relu=(li < L - 1)))
+        h = o.fc_fwd(acts[-1], w, b, relu=(li < L - 1))
+        hidden.append(h)
+        if dropout is not None and li < L - 1:
+            h = dr.dropout_fwd(h, dropout[0], dropout[1], dr.fc_stream(dropout[2], li))
+        acts.append(h)
     loss, dz, pred = o.softmax_ce(acts[-1], labels)
     grads = [None] * L
     for li in range(L - 1, -1, -1):
@@ -98,7 +133,9 @@ def fc_step(o: Oracle, feats, labels, fc_params, fc_mom, lr, momentum, wd, updat
         dw, db, da = o.fc_bwd(acts[li], w, dz, need_da=True)
         grads[li] = (dw, db)
         if li > 0:
-            dz = o.relu_bwd(da, acts[li])
+            if dropout is not None:
+                da = dr.dropout_bwd(da, dropout[0], dropout[1], dr.fc_stream(dropout[2], li - 1))
+            dz = o.relu_bwd(da, hidden[li])
         else:
             dfeats = da
     if update:
@@ -163,20 +200,21 @@ def multi_fc_split_step(o: Oracle, ops, images: List[np.ndarray], labels, conv_p
         vw, vb = conv_mom[name]
         ar.ps_aggregate_rd(w.reshape(-1), vw.reshape(-1), [np.ascontiguousarray(g[name][0]).reshape(-1) for g in worker_grads],
                            1.0, lr, momentum, wd)
-        ar.ps_aggregate_rd(b, vb, [g[name][1] for g in worker_grads], 1.0, lr, momentum, wd)
+        if b is not None:
+            ar.ps_aggregate_rd(b, vb, [g[name][1] for g in worker_grads], 1.0, lr, momentum, wd)
     return dict(loss=loss, pred=np.concatenate(preds), dfeats=dfeats, worker_grads=worker_grads, fc_worker_grads=fc_worker_grads)
 
 
 def split_step(o: Oracle, ops, images: List[np.ndarray], labels, conv_params, conv_mom, fc_params, fc_mom,
-               lr, momentum, wd, keep=False):
+               lr, momentum, wd, keep=False, bn_groups: int = 1, dropout=None):
     """One layer-separated iteration over K = len(images) CONV workers.  Parameters and momentum
     buffers are updated in place.  Returns loss, pred, per-worker conv gradients and (keep=True)
     all intermediates."""
     K = len(images)
-    bufs = [conv_stack_forward(o, ops, o.arr(im), conv_params) for im in images]
+    bufs = [conv_stack_forward(o, ops, o.arr(im), conv_params, bn_groups) for im in images]
     B = images[0].shape[0]
     feats = np.concatenate([b["feat"].reshape(B, -1) for b in bufs], axis=0)
-    fc = fc_step(o, feats, labels, fc_params, fc_mom, lr, momentum, wd)
+    fc = fc_step(o, feats, labels, fc_params, fc_mom, lr, momentum, wd, dropout=dropout)
     worker_grads, worker_bgrads = [], []
     for k in range(K):
         pg, bg = conv_stack_backward(o, ops, bufs[k], conv_params, fc["dfeats"][k * B:(k + 1) * B])
@@ -186,7 +224,8 @@ def split_step(o: Oracle, ops, images: List[np.ndarray], labels, conv_params, co
         vw, vb = conv_mom[name]
         o.ps_aggregate(w.reshape(-1), vw.reshape(-1), [np.ascontiguousarray(g[name][0]).reshape(-1) for g in worker_grads],
                        1.0, lr, momentum, wd)
-        o.ps_aggregate(b, vb, [g[name][1] for g in worker_grads], 1.0, lr, momentum, wd)
+        if b is not None:
+            o.ps_aggregate(b, vb, [g[name][1] for g in worker_grads], 1.0, lr, momentum, wd)
     out = dict(loss=fc["loss"], pred=fc["pred"], worker_grads=worker_grads, feats=feats, dfeats=fc["dfeats"],
                fc_grads=fc["grads"], fc_acts=fc["acts"])
     if keep:
@@ -195,6 +234,9 @@ def split_step(o: Oracle, ops, images: List[np.ndarray], labels, conv_params, co
     return out
 
 
-def monolithic_step(o: Oracle, ops, images_all, labels, conv_params, conv_mom, fc_params, fc_mom, lr, momentum, wd):
-    """The same iteration as one model on the whole batch (one worker, no hand-offs)."""
-    return split_step(o, ops, [images_all], labels, conv_params, conv_mom, fc_params, fc_mom, lr, momentum, wd)
+def monolithic_step(o: Oracle, ops, images_all, labels, conv_params, conv_mom, fc_params, fc_mom, lr, momentum, wd,
+                    bn_groups: int = 1, dropout=None):
+    """The same iteration as one model on the whole batch (one worker, no hand-offs).  For stacks with normalisation
+    layers, bn_groups = K keeps the statistics per worker batch, which is the model the K workers train together."""
+    return split_step(o, ops, [images_all], labels, conv_params, conv_mom, fc_params, fc_mom, lr, momentum, wd,
+                      bn_groups=bn_groups, dropout=dropout)

@@ -416,6 +416,70 @@ double oracle_softmax_ce_part(int n_local, int n_global, int classes, const REAL
     return total / (double)n_global;
 }
 
+/* -------------------------------------------------------------- batch normalisation
+ * The residual networks of the paper's table of models (Sec. 6.1 "Setup") carry a
+ * normalisation layer after every convolution; the paper never discusses it, so the
+ * transform is taken as published (training mode): over the M = N*H*W rows of an
+ * NHWC tensor viewed as [M][C], per channel c
+ *   mean_c = (1/M) sum_m x[m,c]          var_c = (1/M) sum_m (x[m,c] - mean_c)^2   (biased)
+ *   istd_c = 1 / sqrt(var_c + eps)       xhat  = (x - mean_c) * istd_c
+ *   y[m,c] = gamma_c * xhat[m,c] + beta_c,  then max(.,0) if relu
+ * Each CONV worker normalises over its OWN batch (no exchange of statistics between
+ * workers); running averages, when given, move by
+ *   run_mean <- (1-mom) run_mean + mom mean,   run_var <- (1-mom) run_var + mom var M/(M-1). */
+void oracle_bn_fwd(size_t rows, int C, const REAL *x, const REAL *gamma, const REAL *beta, double eps, int relu,
+                   REAL *y, REAL *mean_out, REAL *istd_out, REAL *run_mean, REAL *run_var, double mom)
+{
+#pragma omp parallel for schedule(static)
+    for (int c = 0; c < C; ++c) {
+        double s = 0.0;
+        for (size_t m = 0; m < rows; ++m) s += (double)x[m * C + c];
+        const double mean = s / (double)rows;
+        double q = 0.0;
+        for (size_t m = 0; m < rows; ++m) {
+            const double d = (double)x[m * C + c] - mean;
+            q += d * d;
+        }
+        const double var = q / (double)rows;
+        const double istd = 1.0 / sqrt(var + eps);
+        for (size_t m = 0; m < rows; ++m) {
+            double v = (double)gamma[c] * (((double)x[m * C + c] - mean) * istd) + (double)beta[c];
+            if (relu && v < 0.0) v = 0.0;
+            y[m * C + c] = (REAL)v;
+        }
+        if (mean_out) mean_out[c] = (REAL)mean;
+        if (istd_out) istd_out[c] = (REAL)istd;
+        if (run_mean) run_mean[c] = (REAL)((1.0 - mom) * (double)run_mean[c] + mom * mean);
+        if (run_var) run_var[c] = (REAL)((1.0 - mom) * (double)run_var[c] + mom * (rows > 1 ? q / (double)(rows - 1) : var));
+    }
+}
+
+/* Backward of the transform above for the gradient dy of its (pre-ReLU) output; a fused
+ * ReLU is undone by the caller with oracle_relu_bwd first.  With xhat as above:
+ *   dbeta_c = sum_m dy[m,c]     dgamma_c = sum_m dy[m,c] xhat[m,c]
+ *   dx[m,c] = gamma_c istd_c ( dy[m,c] - dbeta_c / M - xhat[m,c] dgamma_c / M )
+ * (the mean and the variance both depend on every x of the channel). */
+void oracle_bn_bwd(size_t rows, int C, const REAL *x, const REAL *dy, const REAL *gamma, const REAL *mean, const REAL *istd,
+                   REAL *dx, REAL *dgamma, REAL *dbeta)
+{
+#pragma omp parallel for schedule(static)
+    for (int c = 0; c < C; ++c) {
+        const double mu = (double)mean[c], is = (double)istd[c];
+        double sb = 0.0, sg = 0.0;
+        for (size_t m = 0; m < rows; ++m) {
+            const double g = (double)dy[m * C + c];
+            sb += g;
+            sg += g * (((double)x[m * C + c] - mu) * is);
+        }
+        for (size_t m = 0; m < rows; ++m) {
+            const double xh = ((double)x[m * C + c] - mu) * is;
+            dx[m * C + c] = (REAL)((double)gamma[c] * is * ((double)dy[m * C + c] - sb / (double)rows - xh * sg / (double)rows));
+        }
+        dgamma[c] = (REAL)sg;
+        dbeta[c] = (REAL)sb;
+    }
+}
+
 /* -------------------------------------------------------------- optimiser
  * Momentum SGD with weight decay (Sec. 6.1), in the form of the software stack
  * the paper ran:  g' = g + wd*w ;  v <- m*v + g' ;  w <- w - lr*v. */

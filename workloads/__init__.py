@@ -17,7 +17,8 @@ models and per-worker batch sizes) at ImageNet / CIFAR input shapes; the images
 are N(0,1) noise standing in for those datasets.
 
 A conv stack is an op list over named buffers; every op is a dict:
-  {"op": "conv", "name", "src", "dst", "K","R","S","stride","pad","relu"}
+  {"op": "conv", "name", "src", "dst", "K","R","S","stride","pad","relu","bias"}   bias False: no bias term
+  {"op": "bn", "name", "src", "dst", "relu", "eps"}   batch normalisation over the worker's own batch (+ReLU)
   {"op": "pool", "src", "dst", "win","stride","pad","relu"}
   {"op": "add_relu", "a", "b", "dst"}          dst = max(0, a + b)
   {"op": "gap", "src", "dst"}                  global average pool
@@ -34,7 +35,7 @@ import numpy as np
 __all__ = [
     "Workload", "get_workload", "WORKLOAD_NAMES", "shape_pass", "conv_param_shapes",
     "fc_param_shapes", "gen_images", "gen_labels", "gen_conv_params", "gen_fc_params",
-    "gen_ps_case", "rng_for", "conv_flops", "fc_flops", "count_params",
+    "gen_ps_case", "rng_for", "conv_flops", "fc_flops", "count_params", "bn_param_shapes", "flat_tensors",
 ]
 
 
@@ -60,9 +61,13 @@ class Workload:
         return self.fc_dims[-1]
 
 
-def _conv(name, src, dst, K, R, stride=1, pad=0, relu=True, S=None):
+def _conv(name, src, dst, K, R, stride=1, pad=0, relu=True, S=None, bias=True):
     return dict(op="conv", name=name, src=src, dst=dst, K=K, R=R, S=R if S is None else S,
-                stride=stride, pad=pad, relu=relu)
+                stride=stride, pad=pad, relu=relu, bias=bias)
+
+
+def _bn(name, src, dst, relu, eps=1e-5):
+    return dict(op="bn", name=name, src=src, dst=dst, relu=relu, eps=eps)
 
 
 def _pool(src, dst, win, stride, pad=0, relu=True):
@@ -102,48 +107,58 @@ def _vgg16_ops(reps_per_stage=(2, 2, 3, 3, 3)):
     return _chain(spec)
 
 
-def _resnet50_ops(depths=(3, 4, 6, 3)):
-    """Bottleneck residual stack without normalisation layers: stem 7x7/2, 3x3/2 max-pool
-    (pad 1), stages [3,4,6,3] ([3,8,36,3] for the 152-layer network) of 1x1 -> 3x3 (carries the
-    stride) -> 1x1 with a projection shortcut in the first block of each stage, global average pool."""
-    ops = [_conv("stem", "x0", "stem", 64, 7, 2, 3, relu=True),
-           _pool("stem", "s0", 3, 2, 1, relu=True)]
+def _res_unit(ops, name, src, K, R, stride, pad, relu, bn):
+    """conv (+ReLU), or with bn: bias-free conv -> batch normalisation (+ReLU).  Returns the output buffer's name."""
+    if not bn:
+        ops.append(_conv(name, src, name, K, R, stride, pad, relu=relu))
+        return name
+    ops.append(_conv(name, src, name + "_z", K, R, stride, pad, relu=False, bias=False))
+    ops.append(_bn(name + "_bn", name + "_z", name, relu=relu))
+    return name
+
+
+def _bottleneck_stack(stem_width, stages, bn):
+    """stages: [(width, blocks, stride of the first block)].  Stem 7x7/2, 3x3/2 max-pool (pad 1), bottleneck blocks
+    1x1 -> 3x3 (carries the stride) -> 1x1 with a projection shortcut in the first block of each stage, global
+    average pool.  bn: every convolution is bias-free and followed by batch normalisation (the published network);
+    otherwise the convolutions carry biases and nothing is normalised."""
+    ops = []
+    cur = _res_unit(ops, "stem", "x0", stem_width, 7, 2, 3, True, bn)
+    ops.append(_pool(cur, "s0", 3, 2, 1, relu=True))
     cur = "s0"
-    for si, (width, blocks) in enumerate(zip((64, 128, 256, 512), depths), start=1):
+    for si, (width, blocks, first_stride) in enumerate(stages, start=1):
         for bi in range(blocks):
-            stride = 2 if (bi == 0 and si > 1) else 1
+            stride = first_stride if bi == 0 else 1
             tag = f"s{si}b{bi}"
-            ops.append(_conv(tag + "a", cur, tag + "a", width, 1, 1, 0, relu=True))
-            ops.append(_conv(tag + "b", tag + "a", tag + "b", width, 3, stride, 1, relu=True))
-            ops.append(_conv(tag + "c", tag + "b", tag + "c", 4 * width, 1, 1, 0, relu=False))
-            if bi == 0:
-                ops.append(_conv(tag + "sc", cur, tag + "sc", 4 * width, 1, stride, 0, relu=False))
-                short = tag + "sc"
-            else:
-                short = cur
-            ops.append(dict(op="add_relu", a=tag + "c", b=short, dst=tag + "o"))
+            a = _res_unit(ops, tag + "a", cur, width, 1, 1, 0, True, bn)
+            b = _res_unit(ops, tag + "b", a, width, 3, stride, 1, True, bn)
+            c = _res_unit(ops, tag + "c", b, 4 * width, 1, 1, 0, False, bn)
+            short = _res_unit(ops, tag + "sc", cur, 4 * width, 1, stride, 0, False, bn) if bi == 0 else cur
+            ops.append(dict(op="add_relu", a=c, b=short, dst=tag + "o"))
             cur = tag + "o"
     ops.append(dict(op="gap", src=cur, dst="feat"))
     return ops
 
 
-def _mini_res_ops():
-    """A two-block residual stack small enough for exhaustive checks: exercises 7x7/2,
+def _resnet50_ops(depths=(3, 4, 6, 3), bn=False):
+    """Stages [3,4,6,3] ([3,8,36,3] for the 152-layer network) of widths 64..512, stride 2 from the second stage on."""
+    return _bottleneck_stack(64, [(w, d, 1 if i == 0 else 2) for i, (w, d) in enumerate(zip((64, 128, 256, 512), depths))], bn)
+
+
+def _mini_res_ops(bn=False):
+    """A three-block residual stack small enough for exhaustive checks: exercises 7x7/2,
     padded 3x3/2 pooling, 1x1, strided 3x3, projection and identity shortcuts, GAP."""
-    ops = [_conv("stem", "x0", "stem", 8, 7, 2, 3, relu=True),
-           _pool("stem", "s0", 3, 2, 1, relu=True)]
+    ops = []
+    cur = _res_unit(ops, "stem", "x0", 8, 7, 2, 3, True, bn)
+    ops.append(_pool(cur, "s0", 3, 2, 1, relu=True))
     cur = "s0"
     for bi, (width, stride, proj) in enumerate(((4, 1, True), (4, 1, False), (8, 2, True))):
         tag = f"b{bi}"
-        ops.append(_conv(tag + "a", cur, tag + "a", width, 1, 1, 0, relu=True))
-        ops.append(_conv(tag + "b", tag + "a", tag + "b", width, 3, stride, 1, relu=True))
-        ops.append(_conv(tag + "c", tag + "b", tag + "c", 4 * width, 1, 1, 0, relu=False))
-        if proj:
-            ops.append(_conv(tag + "sc", cur, tag + "sc", 4 * width, 1, stride, 0, relu=False))
-            short = tag + "sc"
-        else:
-            short = cur
-        ops.append(dict(op="add_relu", a=tag + "c", b=short, dst=tag + "o"))
+        a = _res_unit(ops, tag + "a", cur, width, 1, 1, 0, True, bn)
+        b = _res_unit(ops, tag + "b", a, width, 3, stride, 1, True, bn)
+        c = _res_unit(ops, tag + "c", b, 4 * width, 1, 1, 0, False, bn)
+        short = _res_unit(ops, tag + "sc", cur, 4 * width, 1, stride, 0, False, bn) if proj else cur
+        ops.append(dict(op="add_relu", a=c, b=short, dst=tag + "o"))
         cur = tag + "o"
     ops.append(dict(op="gap", src=cur, dst="feat"))
     return ops
@@ -183,6 +198,15 @@ def get_workload(name: str) -> Workload:
     if name == "resnet152":
         return Workload("resnet152", K=8, B=32, image=(224, 224, 3), ops=_resnet50_ops((3, 8, 36, 3)),
                         fc_dims=[2048, 1000], notes="without normalisation layers, like resnet50 here")
+    # the residual networks as published: bias-free convolutions, each followed by batch normalisation
+    if name == "resnet50bn":
+        return Workload("resnet50bn", K=16, B=64, image=(224, 224, 3), ops=_resnet50_ops(bn=True), fc_dims=[2048, 1000])
+    if name == "resnet152bn":
+        return Workload("resnet152bn", K=8, B=32, image=(224, 224, 3), ops=_resnet50_ops((3, 8, 36, 3), bn=True),
+                        fc_dims=[2048, 1000])
+    if name == "miniresbn":
+        return Workload("miniresbn", K=2, B=3, image=(33, 35, 3), ops=_mini_res_ops(bn=True),
+                        fc_dims=[32, 7], notes="small normalised residual stack for exhaustive parity")
     if name == "mlp":
         # 3 hidden layers of 1024, 1024, 4096 units on 3x32x32 inputs, separated after the second hidden layer;
         # the largest row of the paper's table: total batch 1024, base learning rate 0.08, vanilla SGD
@@ -195,7 +219,8 @@ def get_workload(name: str) -> Workload:
     raise KeyError(name)
 
 
-WORKLOAD_NAMES = ("tiny", "alexnet", "vgg16", "resnet50", "minires", "mlp", "minimlp", "vgg19", "resnet152")
+WORKLOAD_NAMES = ("tiny", "alexnet", "vgg16", "resnet50", "minires", "mlp", "minimlp", "vgg19", "resnet152",
+                  "resnet50bn", "resnet152bn", "miniresbn")
 
 
 def _out_dim(h, win, stride, pad):
@@ -215,6 +240,8 @@ def shape_pass(wl: Workload, batch: int | None = None) -> Dict[str, Tuple[int, i
             _, h, w, c = shapes[op["src"]]
             shapes[op["dst"]] = (n, _out_dim(h, op["win"], op["stride"], op["pad"]),
                                  _out_dim(w, op["win"], op["stride"], op["pad"]), c)
+        elif op["op"] == "bn":
+            shapes[op["dst"]] = shapes[op["src"]]
         elif op["op"] == "add_relu":
             assert shapes[op["a"]] == shapes[op["b"]], (op, shapes[op["a"]], shapes[op["b"]])
             shapes[op["dst"]] = shapes[op["a"]]
@@ -239,8 +266,17 @@ def fc_param_shapes(wl: Workload) -> List[Tuple[int, int]]:
     return [(d[i + 1], d[i]) for i in range(len(d) - 1)]
 
 
+def bn_param_shapes(wl: Workload) -> List[Tuple[str, int]]:
+    """[(normalisation layer name, channels)] in op order."""
+    shapes = shape_pass(wl, 1)
+    return [(op["name"], shapes[op["src"]][3]) for op in wl.ops if op["op"] == "bn"]
+
+
 def count_params(wl: Workload) -> Tuple[int, int]:
-    conv = sum(k * r * s * c + k for _, (k, r, s, c) in conv_param_shapes(wl))
+    """(parameters on the CONV workers: filters, biases, normalisation scales and shifts; parameters on the FC worker)."""
+    has_bias = {op["name"]: op.get("bias", True) for op in wl.ops if op["op"] == "conv"}
+    conv = sum(k * r * s * c + (k if has_bias[name] else 0) for name, (k, r, s, c) in conv_param_shapes(wl))
+    conv += sum(2 * c for _, c in bn_param_shapes(wl))
     fc = sum(o * i + o for o, i in fc_param_shapes(wl))
     return conv, fc
 
@@ -306,13 +342,31 @@ def _bias(rng, n, fan_in):
 
 
 def gen_conv_params(wl: Workload, seed: int):
-    """{name: (W [K,R,S,C], b [K])}: normal weights with variance 2/fan_in, uniform biases."""
+    """Parameters held by a CONV worker, in op order.  Convolutions: {name: (W [K,R,S,C], b [K] or None)}, normal
+    weights with variance 2/fan_in, uniform biases.  Normalisation layers: {name: (gamma [C], beta [C])} drawn around
+    1 and 0 (a trained state rather than the initial one, so that neither drops out of the arithmetic)."""
+    has_bias = {op["name"]: op.get("bias", True) for op in wl.ops if op["op"] == "conv"}
+    conv_shapes = dict(conv_param_shapes(wl))
+    bn_shapes = dict(bn_param_shapes(wl))
     out = {}
-    for name, (k, r, s, c) in conv_param_shapes(wl):
-        fan = r * s * c
-        out[name] = (_kaiming(rng_for(seed, "cw", name), (k, r, s, c), fan),
-                     _bias(rng_for(seed, "cb", name), k, fan))
+    for op in wl.ops:
+        name = op.get("name")
+        if op["op"] == "conv":
+            k, r, s, c = conv_shapes[name]
+            fan = r * s * c
+            out[name] = (_kaiming(rng_for(seed, "cw", name), (k, r, s, c), fan),
+                         _bias(rng_for(seed, "cb", name), k, fan) if has_bias[name] else None)
+        elif op["op"] == "bn":
+            c = bn_shapes[name]
+            g = rng_for(seed, "bng", name).standard_normal(c, dtype=np.float32) * np.float32(0.2) + np.float32(1.0)
+            b = rng_for(seed, "bnb", name).standard_normal(c, dtype=np.float32) * np.float32(0.2)
+            out[name] = (g, b)
     return out
+
+
+def flat_tensors(d):
+    """The tensors of a {name: (a, b)} dict in order, skipping absent biases (None)."""
+    return [t for pair in d.values() for t in pair if t is not None]
 
 
 def gen_fc_params(wl: Workload, seed: int):
@@ -347,9 +401,13 @@ def param_tensor_numels(wl: Workload, which: str) -> Tuple[List[int], List[int]]
     """(numels, fan_ins) of the per-layer parameter tensors (W then b per layer)."""
     numels, fans = [], []
     if which == "conv":
-        for _, (k, r, s, c) in conv_param_shapes(wl):
-            numels += [k * r * s * c, k]
-            fans += [r * s * c, r * s * c]
+        has_bias = {op["name"]: op.get("bias", True) for op in wl.ops if op["op"] == "conv"}
+        for name, (k, r, s, c) in conv_param_shapes(wl):
+            numels += [k * r * s * c] + ([k] if has_bias[name] else [])
+            fans += [r * s * c] * (2 if has_bias[name] else 1)
+        for _, c in bn_param_shapes(wl):
+            numels += [c, c]
+            fans += [1, 1]
     else:
         for o, i in fc_param_shapes(wl):
             numels += [o * i, o]
