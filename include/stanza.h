@@ -144,6 +144,33 @@ int stanza_add_relu_bwd(int64_t numel, int32_t dtype, const void *dout, const vo
 int stanza_gap_fwd(int32_t N, int32_t HW, int32_t C, int32_t dtype, const void *x, float *f, void *stream);
 int stanza_gap_bwd(int32_t N, int32_t HW, int32_t C, int32_t dtype, const float *df, void *dx, void *stream);
 
+/* ---- Batch normalisation in training mode, on the CONV worker (the residual networks of the paper's table of models,
+ * Sec. 6.1, carry one after every convolution; the paper does not describe the layer, so the published transform is
+ * used, and every worker takes the statistics over its OWN batch: nothing is exchanged between workers).
+ * x, y, dy, dx are [rows][C] (an NHWC tensor with rows = N*H*W), float32 or bfloat16 (then C % 8 == 0); gamma, beta,
+ * the statistics and the parameter gradients are float32 [C].
+ *   fwd   mean_c = (1/rows) sum_m x[m,c];  var_c = (1/rows) sum_m (x[m,c] - mean_c)^2;  istd_c = 1/sqrt(var_c + eps)
+ *         y[m,c] = ((x[m,c] - mean_c) * s_c) + beta_c  with  s_c = gamma_c istd_c  (each operation rounded to float32
+ *         on its own), then max(.,0) when relu != 0.  save_mean and save_istd receive the statistics.
+ *         running_mean / running_var (both optional, NULL to skip) move by r <- (1 - momentum) r + momentum * stat, the
+ *         variance entering with the factor rows/(rows-1).
+ *   bwd   g = dy, or dy * [((x - mean_c) s_c) + beta_c > 0] when relu != 0 (the sign of the forward output, recomputed from x with the
+ *         same float32 operations, so y is not an argument);  xhat = (x - mean_c) istd_c
+ *         dbeta_c = sum_m g[m,c];  dgamma_c = sum_m g[m,c] xhat[m,c]
+ *         dx[m,c] = s_c (g[m,c] - dbeta_c/rows - xhat[m,c] dgamma_c/rows)
+ *         save_mean / save_istd are the forward call's outputs; dgamma, dbeta are overwritten.
+ * Sums over rows are taken per workgroup and then over workgroups in a fixed order (run-to-run identical results).
+ * ws must hold stanza_bn_workspace_bytes(rows, C, dtype) bytes (0 is returned for invalid arguments).
+ * Errors: rows < 1, C < 1, rows*C >= 2^31, eps <= 0, momentum outside [0,1] -> STANZA_EINVAL; bfloat16 with C % 8 != 0 or
+ * an unknown dtype -> STANZA_EUNSUPPORTED; NULL, alignment and workspace errors as elsewhere. */
+size_t stanza_bn_workspace_bytes(int64_t rows, int32_t C, int32_t dtype);
+int stanza_bn_fwd(int64_t rows, int32_t C, int32_t dtype, float eps, int32_t relu, const void *x, const float *gamma,
+                  const float *beta, void *y, float *save_mean, float *save_istd, float *running_mean, float *running_var,
+                  float momentum, void *ws, size_t ws_bytes, void *stream);
+int stanza_bn_bwd(int64_t rows, int32_t C, int32_t dtype, int32_t relu, const void *x, const void *dy, const float *gamma,
+                  const float *beta, const float *save_mean, const float *save_istd, void *dx, float *dgamma, float *dbeta,
+                  void *ws, size_t ws_bytes, void *stream);
+
 /* float32 -> bfloat16 (round to nearest even) and back, for feeding the STANZA_BF16 conv path from
  * float32 master weights and images. */
 int stanza_cast_f32_to_bf16(int64_t numel, const float *src, void *dst, void *stream);

@@ -23,6 +23,7 @@ EXPORTS = (
     "stanza_strerror", "stanza_version", "stanza_conv_workspace_bytes", "stanza_conv_fwd", "stanza_conv_bwd_data",
     "stanza_conv_bwd_weight", "stanza_pool_relu_fwd", "stanza_pool_relu_bwd", "stanza_add_relu_fwd",
     "stanza_add_relu_bwd", "stanza_gap_fwd", "stanza_gap_bwd", "stanza_cast_f32_to_bf16", "stanza_cast_bf16_to_f32",
+    "stanza_bn_workspace_bytes", "stanza_bn_fwd", "stanza_bn_bwd",
     "stanza_fc_workspace_bytes", "stanza_fc_step", "stanza_fc_grads", "stanza_ps_workspace_bytes", "stanza_ps_plan",
     "stanza_ps_aggregate_planned", "stanza_ps_aggregate", "stanza_ps_aggregate_ordered_planned", "stanza_ps_aggregate_ordered",
     "stanza_model_allreduce_rounds", "stanza_model_stanza_time", "stanza_model_stanza_throughput", "stanza_model_assign",
@@ -81,6 +82,10 @@ def load() -> C.CDLL:
     lib.stanza_gap_bwd.argtypes = [i32, i32, i32, i32, vp, vp, vp]
     lib.stanza_cast_f32_to_bf16.argtypes = [i64, vp, vp, vp]
     lib.stanza_cast_bf16_to_f32.argtypes = [i64, vp, vp, vp]
+    lib.stanza_bn_workspace_bytes.restype = sz
+    lib.stanza_bn_workspace_bytes.argtypes = [i64, i32, i32]
+    lib.stanza_bn_fwd.argtypes = [i64, i32, i32, f32, i32, vp, vp, vp, vp, vp, vp, vp, vp, f32, vp, sz, vp]
+    lib.stanza_bn_bwd.argtypes = [i64, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.stanza_fc_workspace_bytes.restype = sz
     lib.stanza_fc_workspace_bytes.argtypes = [C.POINTER(FcDesc)]
     lib.stanza_fc_step.argtypes = [C.POINTER(FcDesc), vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
@@ -193,6 +198,25 @@ def stanza_cast_f32_to_bf16(src, dst):
 
 def stanza_cast_bf16_to_f32(src, dst):
     _check(load().stanza_cast_bf16_to_f32(src.numel(), _ptr(src), _ptr(dst), _stream()), "stanza_cast_bf16_to_f32")
+
+
+def stanza_bn_workspace_bytes(rows: int, channels: int, dtype=F32) -> int:
+    return int(load().stanza_bn_workspace_bytes(rows, channels, dtype))
+
+
+def stanza_bn_fwd(x, gamma, beta, y, save_mean, save_istd, ws, eps=1e-5, relu=False, running_mean=None, running_var=None,
+                  momentum=0.1, dtype=F32):
+    c = x.shape[-1]
+    p, n = _ws(ws)
+    _check(load().stanza_bn_fwd(x.numel() // c, c, dtype, eps, int(relu), _ptr(x), _ptr(gamma), _ptr(beta), _ptr(y), _ptr(save_mean),
+                                _ptr(save_istd), _ptr(running_mean), _ptr(running_var), momentum, p, n, _stream()), "stanza_bn_fwd")
+
+
+def stanza_bn_bwd(x, dy, gamma, beta, save_mean, save_istd, dx, dgamma, dbeta, ws, relu=False, dtype=F32):
+    c = x.shape[-1]
+    p, n = _ws(ws)
+    _check(load().stanza_bn_bwd(x.numel() // c, c, dtype, int(relu), _ptr(x), _ptr(dy), _ptr(gamma), _ptr(beta), _ptr(save_mean),
+                                _ptr(save_istd), _ptr(dx), _ptr(dgamma), _ptr(dbeta), p, n, _stream()), "stanza_bn_bwd")
 
 
 class FcPlan:

@@ -1,0 +1,387 @@
+// Batch normalisation (training mode) on the CONV worker, for the residual networks of the paper's table of models
+// (Sec. 6.1 "Setup"), which carry a normalisation layer after every convolution.  The paper does not describe the layer;
+// the transform is the published one, with the statistics taken over the worker's own batch.
+//
+// An NHWC tensor is a [rows][C] matrix with the channel contiguous, so every kernel here is a column-wise pass over a
+// row-major matrix, bound by HBM: a thread owns one 16-byte channel vector and walks down the rows, a workgroup of 256
+// threads covers TX vectors of a row and TY = 256 / TX consecutive rows per pass (one contiguous stretch of memory when
+// the row fits), and a grid of row slabs x column blocks covers the matrix.  Reductions over rows are done per thread,
+// then over the workgroup's TY rows through LDS, then over the slabs by a small second kernel, each in a fixed order:
+// results are run-to-run identical.
+//   forward   stats pass (read x) -> finalise (mean, 1/std, running averages) -> apply pass (read x, write y)
+//   backward  reduce pass (read x, dy) -> finalise (dgamma, dbeta) -> apply pass (read x, dy, write dx)
+// A fused ReLU is undone in the backward passes by recomputing the sign of the forward output from x (the same
+// float32 expression, operation by operation, as the forward apply pass), so y is never read back.
+#include "internal.h"
+
+namespace stanza {
+
+struct BnGeo {
+    int rows, C, cv;       // cv: channel vectors per row
+    int TX, TY;            // threads across a row, rows per pass (TX * TY <= 256)
+    int rows_per_slab;     // rows of one blockIdx.x
+};
+
+typedef unsigned int bn_u4 __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ uint32_t bn_bf16_rne(float f)
+{
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (u >> 16) | 0x40u;
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return u >> 16;
+}
+
+// VW consecutive channels starting at vector index `vec` (in units of VW elements).
+template <int VW, bool BF16, bool NT>
+__device__ __forceinline__ void bn_load(const void *base, size_t vec, float (&v)[VW])
+{
+    if constexpr (VW == 1) {
+        v[0] = reinterpret_cast<const float *>(base)[vec];
+    } else {
+        const bn_u4 *p = reinterpret_cast<const bn_u4 *>(base) + vec;
+        const bn_u4 t = NT ? __builtin_nontemporal_load(p) : *p;
+#pragma unroll
+        for (int e = 0; e < VW; ++e)
+            v[e] = BF16 ? __uint_as_float(((t[e >> 1] >> (16 * (e & 1))) & 0xffffu) << 16) : __uint_as_float(t[e]);
+    }
+}
+
+template <int VW, bool BF16>
+__device__ __forceinline__ void bn_store(void *base, size_t vec, const float (&v)[VW])
+{
+    if constexpr (VW == 1) {
+        reinterpret_cast<float *>(base)[vec] = v[0];
+    } else {
+        bn_u4 t = {0u, 0u, 0u, 0u};
+#pragma unroll
+        for (int e = 0; e < VW; ++e) {
+            if (BF16) t[e >> 1] |= bn_bf16_rne(v[e]) << (16 * (e & 1));
+            else t[e] = __float_as_uint(v[e]);
+        }
+        __builtin_nontemporal_store(t, reinterpret_cast<bn_u4 *>(base) + vec);
+    }
+}
+
+// Forward output before the ReLU, ((x - mean) * s) + beta with s = gamma * istd, written out operation by operation (no
+// contraction into a fused multiply-add) so that the forward pass and the sign test of the backward passes take the same
+// roundings.  Subtracting the mean first keeps the result accurate for channels whose mean is large against their spread.
+__device__ __forceinline__ float bn_affine(float x, float mean, float sc, float beta)
+{
+#pragma clang fp contract(off)
+    const float d = x - mean;
+    const float t = d * sc;
+    return t + beta;
+}
+__device__ __forceinline__ float bn_scale(float gamma, float istd) { return gamma * istd; }
+__device__ __forceinline__ float bn_xhat(float x, float mean, float istd) { return (x - mean) * istd; }
+
+// Per-thread sums over the rows r0 + ty, r0 + ty + TY, ... of its slab, four rows in flight, then the workgroup's TY
+// rows in row order through LDS.  BWD = false: a = sum (x - k), b = sum (x - k)^2 with k = x[0][c] (a shift inside the
+// data's range keeps the variance free of cancellation).  BWD = true: a = sum g, b = sum g * xhat with
+// g = dy * [forward output > 0] (relu) or dy.  partial: [slab][2][C].
+template <int VW, bool BF16, bool BWD>
+__global__ __launch_bounds__(256) void bn_reduce_kernel(const BnGeo g, const void *__restrict__ xv, const void *__restrict__ dyv,
+                                                        const float *__restrict__ gamma, const float *__restrict__ beta,
+                                                        const float *__restrict__ mean, const float *__restrict__ istd, int relu,
+                                                        float *__restrict__ partial)
+{
+    __shared__ float red[256 * 2 * VW];
+    const int ty = threadIdx.x / g.TX, tx = threadIdx.x - ty * g.TX;
+    const int col = blockIdx.y * g.TX + tx;
+    const bool active = ty < g.TY && col < g.cv;
+    float a[VW], b[VW], k[VW], is[VW], sc[VW], sh[VW];
+#pragma unroll
+    for (int e = 0; e < VW; ++e) a[e] = b[e] = k[e] = is[e] = sc[e] = sh[e] = 0.f;
+    if (active) {
+        if (BWD) {
+#pragma unroll
+            for (int e = 0; e < VW; ++e) {
+                const int c = col * VW + e;
+                k[e] = mean[c];
+                is[e] = istd[c];
+                sc[e] = bn_scale(gamma[c], is[e]);
+                sh[e] = beta[c];
+            }
+        } else {
+            bn_load<VW, BF16, false>(xv, (size_t)col, k);
+        }
+        const int r0 = blockIdx.x * g.rows_per_slab;
+        const int r1 = min(r0 + g.rows_per_slab, g.rows);
+        auto take = [&](const float (&x)[VW], const float (&dy)[VW]) {
+#pragma unroll
+            for (int e = 0; e < VW; ++e) {
+                if (BWD) {
+                    const float gr = (relu && !(bn_affine(x[e], k[e], sc[e], sh[e]) > 0.f)) ? 0.f : dy[e];
+                    const float xh = bn_xhat(x[e], k[e], is[e]);
+                    a[e] += gr;
+                    b[e] = fmaf(gr, xh, b[e]);
+                } else {
+                    const float d = x[e] - k[e];
+                    a[e] += d;
+                    b[e] = fmaf(d, d, b[e]);
+                }
+            }
+        };
+        int r = r0 + ty;
+        for (; r + 3 * g.TY < r1; r += 4 * g.TY) {
+            float x[4][VW], dy[4][VW];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const size_t vec = (size_t)(r + u * g.TY) * g.cv + col;
+                bn_load<VW, BF16, false>(xv, vec, x[u]);
+                if (BWD) bn_load<VW, BF16, false>(dyv, vec, dy[u]);
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) take(x[u], BWD ? dy[u] : x[u]);
+        }
+        for (; r < r1; r += g.TY) {
+            float x[VW], dy[VW];
+            const size_t vec = (size_t)r * g.cv + col;
+            bn_load<VW, BF16, false>(xv, vec, x);
+            if (BWD) bn_load<VW, BF16, false>(dyv, vec, dy);
+            take(x, BWD ? dy : x);
+        }
+    }
+#pragma unroll
+    for (int e = 0; e < VW; ++e) {
+        red[threadIdx.x * 2 * VW + e] = a[e];
+        red[threadIdx.x * 2 * VW + VW + e] = b[e];
+    }
+    __syncthreads();
+    if (ty == 0 && col < g.cv) {
+        for (int t = 1; t < g.TY; ++t) {
+#pragma unroll
+            for (int e = 0; e < VW; ++e) {
+                a[e] += red[(t * g.TX + tx) * 2 * VW + e];
+                b[e] += red[(t * g.TX + tx) * 2 * VW + VW + e];
+            }
+        }
+        float *out = partial + (size_t)blockIdx.x * 2 * g.C + (size_t)col * VW;
+#pragma unroll
+        for (int e = 0; e < VW; ++e) {
+            out[e] = a[e];
+            out[g.C + e] = b[e];
+        }
+    }
+}
+
+// Sums the slabs' partial sums per channel: 64 channels x 4 interleaved groups of slabs per workgroup, each group in
+// slab order, then the four groups in group order.
+// BWD = false: mean, 1/std and (when given) the running averages.  BWD = true: out_a = dbeta, out_b = dgamma.
+template <bool BWD, bool BF16>
+__global__ __launch_bounds__(256) void bn_finalize_kernel(int C, int slabs, int rows, const float *__restrict__ partial,
+                                                          const void *__restrict__ x_row0, float eps, float *__restrict__ out_a,
+                                                          float *__restrict__ out_b, float *__restrict__ run_mean,
+                                                          float *__restrict__ run_var, float mom)
+{
+    __shared__ float red[4][64][2];
+    const int lane = threadIdx.x & 63, grp = threadIdx.x >> 6;
+    const int c = blockIdx.x * 64 + lane;
+    float a = 0.f, b = 0.f;
+    if (c < C) {
+        for (int s = grp; s < slabs; s += 4) {
+            a += partial[(size_t)s * 2 * C + c];
+            b += partial[(size_t)s * 2 * C + C + c];
+        }
+    }
+    red[grp][lane][0] = a;
+    red[grp][lane][1] = b;
+    __syncthreads();
+    if (grp != 0 || c >= C) return;
+    for (int t = 1; t < 4; ++t) {
+        a += red[t][lane][0];
+        b += red[t][lane][1];
+    }
+    if (BWD) {
+        out_a[c] = a;
+        out_b[c] = b;
+        return;
+    }
+    const float k = BF16 ? __uint_as_float((uint32_t)reinterpret_cast<const uint16_t *>(x_row0)[c] << 16)
+                         : reinterpret_cast<const float *>(x_row0)[c];
+    const float inv = 1.f / (float)rows;
+    const float m1 = a * inv;
+    const float var = fmaxf(fmaf(-m1, m1, b * inv), 0.f);
+    const float mu = k + m1;
+    out_a[c] = mu;
+    out_b[c] = 1.f / sqrtf(var + eps);
+    if (run_mean) run_mean[c] = (1.f - mom) * run_mean[c] + mom * mu;
+    if (run_var) run_var[c] = (1.f - mom) * run_var[c] + mom * (rows > 1 ? var * ((float)rows / (float)(rows - 1)) : var);
+}
+
+// BWD = false: y = gamma * xhat + beta (+ReLU).  BWD = true: dx = gamma istd (g - dbeta/M - xhat dgamma/M).
+template <int VW, bool BF16, bool BWD>
+__global__ __launch_bounds__(256) void bn_apply_kernel(const BnGeo g, const void *__restrict__ xv, const void *__restrict__ dyv,
+                                                       const float *__restrict__ gamma, const float *__restrict__ beta,
+                                                       const float *__restrict__ mean, const float *__restrict__ istd,
+                                                       const float *__restrict__ dgamma, const float *__restrict__ dbeta, int relu,
+                                                       void *__restrict__ outv)
+{
+    const int ty = threadIdx.x / g.TX, tx = threadIdx.x - ty * g.TX;
+    const int col = blockIdx.y * g.TX + tx;
+    if (ty >= g.TY || col >= g.cv) return;
+    float mu[VW], is[VW], sc[VW], sh[VW], c1[VW], c2[VW];
+    const float inv = 1.f / (float)g.rows;
+#pragma unroll
+    for (int e = 0; e < VW; ++e) {
+        const int c = col * VW + e;
+        mu[e] = mean[c];
+        is[e] = istd[c];
+        sc[e] = bn_scale(gamma[c], is[e]);
+        sh[e] = beta[c];
+        c1[e] = BWD ? dbeta[c] * inv : 0.f;
+        c2[e] = BWD ? dgamma[c] * inv : 0.f;
+    }
+    const int r0 = blockIdx.x * g.rows_per_slab;
+    const int r1 = min(r0 + g.rows_per_slab, g.rows);
+    auto emit = [&](size_t vec, const float (&x)[VW], const float (&dy)[VW]) {
+        float o[VW];
+#pragma unroll
+        for (int e = 0; e < VW; ++e) {
+            const float yv = bn_affine(x[e], mu[e], sc[e], sh[e]);
+            if (BWD) {
+                const float gr = (relu && !(yv > 0.f)) ? 0.f : dy[e];
+                const float xh = bn_xhat(x[e], mu[e], is[e]);
+                o[e] = sc[e] * fmaf(-xh, c2[e], gr - c1[e]);
+            } else {
+                o[e] = (relu && !(yv > 0.f)) ? 0.f : yv;
+            }
+        }
+        bn_store<VW, BF16>(outv, vec, o);
+    };
+    int r = r0 + ty;
+    for (; r + 3 * g.TY < r1; r += 4 * g.TY) {
+        float x[4][VW], dy[4][VW];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const size_t vec = (size_t)(r + u * g.TY) * g.cv + col;
+            bn_load<VW, BF16, true>(xv, vec, x[u]);
+            if (BWD) bn_load<VW, BF16, true>(dyv, vec, dy[u]);
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) emit((size_t)(r + u * g.TY) * g.cv + col, x[u], BWD ? dy[u] : x[u]);
+    }
+    for (; r < r1; r += g.TY) {
+        float x[VW], dy[VW];
+        const size_t vec = (size_t)r * g.cv + col;
+        bn_load<VW, BF16, true>(xv, vec, x);
+        if (BWD) bn_load<VW, BF16, true>(dyv, vec, dy);
+        emit(vec, x, BWD ? dy : x);
+    }
+}
+
+// ------------------------------------------------------------------ host side
+struct BnPlan {
+    BnGeo reduce, apply;
+    int vw, col_blocks, slabs, slabs_apply;
+    size_t ws_floats;
+};
+
+static int bn_plan(int64_t rows, int32_t C, int32_t dtype, BnPlan *p)
+{
+    if (rows < 1 || C < 1 || rows * (int64_t)C >= (int64_t(1) << 31)) return STANZA_EINVAL;
+    if (dtype != STANZA_F32 && dtype != STANZA_BF16) return STANZA_EUNSUPPORTED;
+    if (dtype == STANZA_BF16 && C % 8 != 0) return STANZA_EUNSUPPORTED;
+    p->vw = dtype == STANZA_BF16 ? 8 : (C % 4 == 0 ? 4 : 1);
+    BnGeo g;
+    g.rows = (int)rows;
+    g.C = C;
+    g.cv = C / p->vw;
+    g.TX = g.cv < 256 ? g.cv : 256;
+    g.TY = 256 / g.TX;
+    p->col_blocks = cdiv(g.cv, g.TX);
+    // reduction passes: about 1024 workgroups, each with at least eight passes over its TY rows
+    const int64_t wanted = cdiv64(rows, (int64_t)g.TY * 8);
+    const int64_t cap = 1024 / p->col_blocks > 0 ? 1024 / p->col_blocks : 1;
+    p->slabs = (int)(wanted < 1 ? 1 : (wanted > cap ? cap : wanted));
+    g.rows_per_slab = (int)cdiv64(rows, p->slabs);
+    p->slabs = (int)cdiv64(rows, g.rows_per_slab);
+    p->reduce = g;
+    // element-wise passes: four passes per workgroup
+    g.rows_per_slab = g.TY * 4;
+    p->slabs_apply = (int)cdiv64(rows, g.rows_per_slab);
+    p->apply = g;
+    p->ws_floats = (size_t)p->slabs * 2 * C;
+    return STANZA_OK;
+}
+
+template <bool BWD>
+static void bn_launch_reduce(const BnPlan &p, int dtype, hipStream_t st, const void *x, const void *dy, const float *gamma, const float *beta,
+                             const float *mean, const float *istd, int relu, float *partial)
+{
+    const dim3 grid((unsigned)p.slabs, (unsigned)p.col_blocks);
+    if (dtype == STANZA_BF16)
+        hipLaunchKernelGGL((bn_reduce_kernel<8, true, BWD>), grid, dim3(256), 0, st, p.reduce, x, dy, gamma, beta, mean, istd, relu, partial);
+    else if (p.vw == 4)
+        hipLaunchKernelGGL((bn_reduce_kernel<4, false, BWD>), grid, dim3(256), 0, st, p.reduce, x, dy, gamma, beta, mean, istd, relu, partial);
+    else
+        hipLaunchKernelGGL((bn_reduce_kernel<1, false, BWD>), grid, dim3(256), 0, st, p.reduce, x, dy, gamma, beta, mean, istd, relu, partial);
+}
+
+template <bool BWD>
+static void bn_launch_apply(const BnPlan &p, int dtype, hipStream_t st, const void *x, const void *dy, const float *gamma, const float *beta,
+                            const float *mean, const float *istd, const float *dgamma, const float *dbeta, int relu, void *out)
+{
+    const dim3 grid((unsigned)p.slabs_apply, (unsigned)p.col_blocks);
+    if (dtype == STANZA_BF16)
+        hipLaunchKernelGGL((bn_apply_kernel<8, true, BWD>), grid, dim3(256), 0, st, p.apply, x, dy, gamma, beta, mean, istd, dgamma, dbeta, relu, out);
+    else if (p.vw == 4)
+        hipLaunchKernelGGL((bn_apply_kernel<4, false, BWD>), grid, dim3(256), 0, st, p.apply, x, dy, gamma, beta, mean, istd, dgamma, dbeta, relu, out);
+    else
+        hipLaunchKernelGGL((bn_apply_kernel<1, false, BWD>), grid, dim3(256), 0, st, p.apply, x, dy, gamma, beta, mean, istd, dgamma, dbeta, relu, out);
+}
+
+}  // namespace stanza
+
+using namespace stanza;
+
+extern "C" size_t stanza_bn_workspace_bytes(int64_t rows, int32_t C, int32_t dtype)
+{
+    BnPlan p;
+    if (bn_plan(rows, C, dtype, &p)) return 0;
+    return round256(p.ws_floats * sizeof(float));
+}
+
+extern "C" int stanza_bn_fwd(int64_t rows, int32_t C, int32_t dtype, float eps, int32_t relu, const void *x, const float *gamma,
+                             const float *beta, void *y, float *save_mean, float *save_istd, float *running_mean, float *running_var,
+                             float momentum, void *ws, size_t ws_bytes, void *stream)
+{
+    BnPlan p;
+    int rc = bn_plan(rows, C, dtype, &p);
+    if (rc) return rc;
+    if (!(eps > 0.f) || !(momentum >= 0.f && momentum <= 1.f)) return STANZA_EINVAL;
+    if (!x || !gamma || !beta || !y || !save_mean || !save_istd || !ws) return STANZA_ENULL;
+    if (!aligned16(x) || !aligned16(y) || !aligned16(ws)) return STANZA_EALIGN;
+    if (ws_bytes < p.ws_floats * sizeof(float)) return STANZA_EWORKSPACE;
+    hipStream_t st = (hipStream_t)stream;
+    float *partial = reinterpret_cast<float *>(ws);
+    bn_launch_reduce<false>(p, dtype, st, x, nullptr, nullptr, nullptr, nullptr, nullptr, 0, partial);
+    if (dtype == STANZA_BF16)
+        hipLaunchKernelGGL((bn_finalize_kernel<false, true>), dim3((unsigned)cdiv(C, 64)), dim3(256), 0, st, C, p.slabs, (int)rows, partial, x, eps,
+                           save_mean, save_istd, running_mean, running_var, momentum);
+    else
+        hipLaunchKernelGGL((bn_finalize_kernel<false, false>), dim3((unsigned)cdiv(C, 64)), dim3(256), 0, st, C, p.slabs, (int)rows, partial, x, eps,
+                           save_mean, save_istd, running_mean, running_var, momentum);
+    bn_launch_apply<false>(p, dtype, st, x, nullptr, gamma, beta, save_mean, save_istd, nullptr, nullptr, relu ? 1 : 0, y);
+    return launch_status();
+}
+
+extern "C" int stanza_bn_bwd(int64_t rows, int32_t C, int32_t dtype, int32_t relu, const void *x, const void *dy, const float *gamma,
+                             const float *beta, const float *save_mean, const float *save_istd, void *dx, float *dgamma, float *dbeta,
+                             void *ws, size_t ws_bytes, void *stream)
+{
+    BnPlan p;
+    int rc = bn_plan(rows, C, dtype, &p);
+    if (rc) return rc;
+    if (!x || !dy || !gamma || !beta || !save_mean || !save_istd || !dx || !dgamma || !dbeta || !ws) return STANZA_ENULL;
+    if (!aligned16(x) || !aligned16(dy) || !aligned16(dx) || !aligned16(ws)) return STANZA_EALIGN;
+    if (ws_bytes < p.ws_floats * sizeof(float)) return STANZA_EWORKSPACE;
+    hipStream_t st = (hipStream_t)stream;
+    float *partial = reinterpret_cast<float *>(ws);
+    bn_launch_reduce<true>(p, dtype, st, x, dy, gamma, beta, save_mean, save_istd, relu ? 1 : 0, partial);
+    hipLaunchKernelGGL((bn_finalize_kernel<true, false>), dim3((unsigned)cdiv(C, 64)), dim3(256), 0, st, C, p.slabs, (int)rows, partial, nullptr, 0.f,
+                       dbeta, dgamma, nullptr, nullptr, 0.f);
+    bn_launch_apply<true>(p, dtype, st, x, dy, gamma, beta, save_mean, save_istd, dgamma, dbeta, relu ? 1 : 0, dx);
+    return launch_status();
+}

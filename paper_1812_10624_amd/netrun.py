@@ -34,7 +34,7 @@ class ConvWorker:
             kind = op["op"]
             if kind == "conv":
                 n, h, w, c = self.shapes[op["src"]]
-                flags = api.CONV_BIAS | (api.CONV_RELU if op["relu"] else 0)
+                flags = (api.CONV_BIAS if op.get("bias", True) else 0) | (api.CONV_RELU if op["relu"] else 0)
                 low = dtype == api.BF16 and c % 8 == 0 and op["K"] % 8 == 0
                 self.f32_layer[i] = dtype == api.BF16 and not low
                 d = api.conv_desc(n, h, w, c, op["K"], op["R"], op["S"], op["stride"], op["pad"], api.BF16 if low else api.F32, flags)
@@ -48,6 +48,8 @@ class ConvWorker:
                 wo = (w + 2 * op["pad"] - op["win"]) // op["stride"] + 1
                 self.shapes[op["dst"]] = (n, ho, wo, c)
                 self.descs[i] = d
+            elif kind == "bn":
+                self.shapes[op["dst"]] = self.shapes[op["src"]]
             elif kind == "add_relu":
                 self.shapes[op["dst"]] = self.shapes[op["a"]]
             elif kind == "gap":
@@ -61,7 +63,17 @@ class ConvWorker:
         self.argmax = {op["dst"]: torch.empty(self.shapes[op["dst"]], device=self.dev, dtype=torch.uint8)
                        for op in ops if op["op"] == "pool"}
         self.gbuf: Dict[str, torch.Tensor] = {}
-        self.grads = {name: (torch.empty_like(w), torch.empty_like(b)) for name, (w, b) in params.items()}
+        self.grads = {name: (torch.empty_like(w), None if b is None else torch.empty_like(b)) for name, (w, b) in params.items()}
+        # normalisation layers: saved statistics per layer, one workspace for all
+        self.bn_stats = {}
+        bn_ws = 16
+        for op in ops:
+            if op["op"] == "bn":
+                shp = self.shapes[op["src"]]
+                rows, c = shp[0] * shp[1] * shp[2], shp[3]
+                self.bn_stats[op["name"]] = (torch.empty(c, device=self.dev), torch.empty(c, device=self.dev))
+                bn_ws = max(bn_ws, api.stanza_bn_workspace_bytes(rows, c, dtype))
+        self.bn_ws = torch.empty(bn_ws, device=self.dev, dtype=torch.uint8) if self.bn_stats else None
         # one workspace serves every conv call: the largest need over forward, backward-data and backward-weight
         ws_bytes = max([api.stanza_conv_workspace_bytes(d, which) for i, d in self.descs.items() if ops[i]["op"] == "conv"
                         for which in (0, 1, 2)] + [16])
@@ -95,6 +107,11 @@ class ConvWorker:
                     api.stanza_conv_fwd(self.descs[i], self.buf[op["src"]], w, b, self.buf[op["dst"]], self.ws)
             elif kind == "pool":
                 api.stanza_pool_relu_fwd(self.descs[i], self.buf[op["src"]], self.buf[op["dst"]], self.argmax[op["dst"]], self.dtype)
+            elif kind == "bn":
+                gamma, beta = self.params[op["name"]]
+                mean, istd = self.bn_stats[op["name"]]
+                api.stanza_bn_fwd(self.buf[op["src"]], gamma, beta, self.buf[op["dst"]], mean, istd, self.bn_ws, op["eps"], op["relu"],
+                                  dtype=self.dtype)
             elif kind == "add_relu":
                 api.stanza_add_relu_fwd(self.buf[op["a"]], self.buf[op["b"]], self.buf[op["dst"]])
             elif kind == "gap":
@@ -152,6 +169,17 @@ class ConvWorker:
                         have[src] = dx
                     api.stanza_conv_bwd_data(dd, dy, y, wk, x_mask, dx, self.ws)
                     gated[src] = x_mask is not None
+            elif kind == "bn":
+                # the layer undoes its own ReLU from x, whether or not the incoming gradient is gated already
+                gamma, beta = self.params[op["name"]]
+                mean, istd = self.bn_stats[op["name"]]
+                dgamma, dbeta = self.grads[op["name"]]
+                dx = self._grad_buffer(op["src"])
+                assert op["src"] not in have
+                api.stanza_bn_bwd(self.buf[op["src"]], have.pop(op["dst"]), gamma, beta, mean, istd, dx, dgamma, dbeta, self.bn_ws,
+                                  op["relu"], dtype=self.dtype)
+                have[op["src"]] = dx
+                gated[op["src"]] = False
             elif kind == "pool":
                 dx = self._grad_buffer(op["src"])
                 assert op["src"] not in have

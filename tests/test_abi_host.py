@@ -111,3 +111,19 @@ def test_fc_and_ps_errors(api):
     assert lib.stanza_ps_aggregate_ordered_planned(7, 2, numel, 3, 1.0, 0.1, 0.9, 0.0, p16, need, None) == -1   # unknown order
     assert lib.stanza_ps_aggregate_ordered_planned(1, 2, numel, 3, 1.0, 0.1, 0.9, 0.0, None, need, None) == -2
     assert lib.stanza_ps_aggregate_ordered(9, 2, numel, w, w, g, 3, 1.0, 0.1, 0.9, 0.0, p16, need, None) == -1
+
+
+def test_bn_errors(api):
+    import ctypes as C
+    lib = api.load()
+    p16, p4 = C.c_void_p(0x1000), C.c_void_p(0x1004)
+    need = lib.stanza_bn_workspace_bytes(100, 8, api.F32)
+    assert need > 0
+    call = lambda rows=100, c=8, dt=api.F32, eps=1e-5, x=p16, ws=p16, nbytes=need, mom=0.1: lib.stanza_bn_fwd(
+        rows, c, dt, eps, 0, x, p16, p16, p16, p16, p16, None, None, mom, ws, nbytes, None)
+    assert call(rows=0) == -1 and call(c=0) == -1 and call(eps=0.0) == -1 and call(mom=1.5) == -1
+    assert call(rows=1 << 29, c=8) == -1
+    assert call(dt=api.BF16, c=12) == -4 and call(dt=9) == -4
+    assert call(x=None) == -2 and call(x=p4) == -3 and call(nbytes=8) == -5
+    assert lib.stanza_bn_workspace_bytes(0, 8, api.F32) == 0
+    assert lib.stanza_bn_bwd(100, 8, api.F32, 0, p16, None, p16, p16, p16, p16, p16, p16, p16, p16, need, None) == -2

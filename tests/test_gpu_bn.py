@@ -1,0 +1,190 @@
+"""Batch normalisation on the GPU against the CPU checker: forward, statistics, running averages and backward
+per call on shapes that span every thread mapping (scalar and 16-byte channel vectors, rows that fill a
+fraction of / exactly / several workgroups' widths, one and many row slabs), then the whole layer-separated
+step of the small normalised residual stack."""
+import copy
+
+import numpy as np
+import pytest
+import torch
+
+import workloads as wl_mod
+from gpu_util import TOL_BF16, TOL_F32, dev, host, rel_err
+from oracle import network as onet
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def api():
+    from paper_1812_10624_amd import api as a
+    a.load()
+    assert torch.cuda.is_available()
+    return a
+
+
+def _case(seed, rows, c):
+    rng = wl_mod.rng_for(seed, "bn", rows, c)
+    x = rng.standard_normal((rows, c), dtype=np.float32) * rng.uniform(0.5, 3.0, c).astype(np.float32) \
+        + rng.uniform(-4, 4, c).astype(np.float32)
+    gamma = rng.uniform(0.5, 1.5, c).astype(np.float32)
+    beta = (rng.standard_normal(c) * 0.5).astype(np.float32)
+    dy = rng.standard_normal((rows, c), dtype=np.float32)
+    return x, gamma, beta, dy
+
+
+def _gate32(x, gamma, beta, mean, istd):
+    """Sign of the forward output as the library's contract states it: ((x - mean) * s) + beta with s = gamma * istd,
+    every operation rounded to float32 (the decision is taken in the kernel's precision on both sides)."""
+    f = np.float32
+    s = (gamma.astype(f) * istd.astype(f)).astype(f)
+    return (((x.astype(f) - mean.astype(f)).astype(f) * s).astype(f) + beta.astype(f)).astype(f) > 0
+
+
+# rows, channels: scalar path (C % 4 != 0), a row narrower than / equal to / wider than 256 vectors, ragged slabs
+SHAPES = [(1, 4), (33, 3), (175, 4), (243, 7), (442, 48), (784, 512), (98, 2048), (300, 1028), (40000, 64), (12545, 256)]
+
+
+@pytest.mark.parametrize("rows,c", SHAPES)
+@pytest.mark.parametrize("relu", [False, True])
+def test_bn_forward_backward(api, o32, rows, c, relu):
+    x, gamma, beta, dy = _case(1, rows, c)
+    eps = 1e-5
+    rm0, rv0 = np.full(c, 0.25, np.float32), np.full(c, 1.5, np.float32)
+    rm_ref, rv_ref = rm0.copy(), rv0.copy()
+    y_ref, mean_ref, istd_ref = o32.bn_fwd(x, gamma, beta, eps, relu, rm_ref, rv_ref, 0.1)
+    xd, gd, bd = dev(x), dev(gamma), dev(beta)
+    y = torch.full((rows, c), float("nan"), device="cuda:0")
+    mean, istd = torch.empty(c, device="cuda:0"), torch.empty(c, device="cuda:0")
+    rm, rv = dev(rm0), dev(rv0)
+    ws = torch.empty(max(16, api.stanza_bn_workspace_bytes(rows, c)), dtype=torch.uint8, device="cuda:0")
+    api.stanza_bn_fwd(xd, gd, bd, y, mean, istd, ws, eps, relu, rm, rv, 0.1)
+    assert rel_err(host(mean), mean_ref) < 1e-5
+    if rows > 1:
+        assert rel_err(host(istd), istd_ref) < TOL_F32
+        assert rel_err(host(y), y_ref) < TOL_F32
+        assert rel_err(host(rv), rv_ref) < TOL_F32
+    else:
+        assert np.allclose(host(istd), 1 / np.sqrt(eps), rtol=1e-5)       # one row: zero variance
+    assert rel_err(host(rm), rm_ref) < 1e-5
+    if rows == 1:
+        return
+    # backward on the checker's statistics
+    gate = _gate32(x, gamma, beta, mean_ref, istd_ref) if relu else np.ones_like(x, bool)
+    if relu:
+        assert 0.05 < gate.mean() < 0.95
+    g_in = np.where(gate, dy, np.float32(0))
+    dx_ref, dg_ref, db_ref = o32.bn_bwd(x, np.ascontiguousarray(g_in), gamma, mean_ref, istd_ref)
+    dx = torch.full((rows, c), float("nan"), device="cuda:0")
+    dg, db = torch.empty(c, device="cuda:0"), torch.empty(c, device="cuda:0")
+    api.stanza_bn_bwd(xd, dev(dy), gd, bd, dev(mean_ref), dev(istd_ref), dx, dg, db, ws, relu)
+    assert rel_err(host(dg), dg_ref) < TOL_F32
+    assert rel_err(host(db), db_ref) < TOL_F32
+    assert rel_err(host(dx), dx_ref) < TOL_F32
+    # the forward output's sign is what the backward pass recomputes
+    if relu:
+        np.testing.assert_array_equal(host(y) > 0, _gate32(x, gamma, beta, host(mean), host(istd)))
+
+
+def test_bn_constant_and_offset_columns(api, o32):
+    """A constant channel has zero variance (istd = 1/sqrt(eps), output beta); a channel with a large offset keeps its
+    variance (the sums are taken about a value inside the data's range)."""
+    rows, c = 4096, 8
+    rng = wl_mod.rng_for(2, "bnconst")
+    x = rng.standard_normal((rows, c), dtype=np.float32)
+    x[:, 1] = 3.5
+    x[:, 2] += 1000.0
+    x[:, 3] = x[:, 3] * 1e-3 - 50.0
+    gamma, beta = np.ones(c, np.float32), np.linspace(-1, 1, c).astype(np.float32)
+    y_ref, mean_ref, istd_ref = o32.bn_fwd(x, gamma, beta, 1e-5, False)
+    y = torch.empty((rows, c), device="cuda:0")
+    mean, istd = torch.empty(c, device="cuda:0"), torch.empty(c, device="cuda:0")
+    ws = torch.empty(api.stanza_bn_workspace_bytes(rows, c), dtype=torch.uint8, device="cuda:0")
+    api.stanza_bn_fwd(dev(x), dev(gamma), dev(beta), y, mean, istd, ws, 1e-5, False)
+    assert rel_err(host(istd), istd_ref) < TOL_F32
+    assert np.all(host(y)[:, 1] == beta[1])
+    # an offset of 1000 (50000) sigma costs the input itself ten (sixteen) bits: those channels are compared at that accuracy
+    assert np.abs(host(y)[:, 2] - y_ref[:, 2]).max() < 2e-3 and np.abs(host(y)[:, 3] - y_ref[:, 3]).max() < 2e-2
+    assert rel_err(host(y)[:, [0, 4, 5, 6, 7]], y_ref[:, [0, 4, 5, 6, 7]]) < TOL_F32
+
+
+@pytest.mark.parametrize("rows,c", [(175, 8), (784, 512), (98, 2048), (40000, 64)])
+def test_bn_bf16(api, o32, rows, c):
+    x, gamma, beta, dy = _case(3, rows, c)
+    x, dy = wl_mod.round_bf16(x), wl_mod.round_bf16(dy)
+    y_ref, mean_ref, istd_ref = o32.bn_fwd(x, gamma, beta, 1e-5, True)
+    xd = dev(x, torch.bfloat16)
+    y = torch.empty((rows, c), device="cuda:0", dtype=torch.bfloat16)
+    mean, istd = torch.empty(c, device="cuda:0"), torch.empty(c, device="cuda:0")
+    ws = torch.empty(api.stanza_bn_workspace_bytes(rows, c, api.BF16), dtype=torch.uint8, device="cuda:0")
+    api.stanza_bn_fwd(xd, dev(gamma), dev(beta), y, mean, istd, ws, 1e-5, True, dtype=api.BF16)
+    assert rel_err(host(mean), mean_ref) < 1e-5 and rel_err(host(istd), istd_ref) < TOL_F32
+    assert rel_err(host(y.float()), y_ref) < TOL_BF16
+    gate = _gate32(x, gamma, beta, mean_ref, istd_ref)
+    dx_ref, dg_ref, db_ref = o32.bn_bwd(x, np.ascontiguousarray(np.where(gate, dy, np.float32(0))), gamma, mean_ref, istd_ref)
+    dx = torch.empty((rows, c), device="cuda:0", dtype=torch.bfloat16)
+    dg, db = torch.empty(c, device="cuda:0"), torch.empty(c, device="cuda:0")
+    api.stanza_bn_bwd(xd, dev(dy, torch.bfloat16), dev(gamma), dev(beta), dev(mean_ref), dev(istd_ref), dx, dg, db, ws, True, dtype=api.BF16)
+    assert rel_err(host(dg), dg_ref) < TOL_F32 and rel_err(host(db), db_ref) < TOL_F32
+    assert rel_err(host(dx.float()), dx_ref) < TOL_BF16
+
+
+def _none_or(fn, t):
+    return None if t is None else fn(t)
+
+
+@pytest.mark.parametrize("K,B", [(2, 3), (3, 4)])
+def test_normalised_residual_step(api, o32, K, B):
+    """The layer-separated step of the small normalised residual stack: features, loss, handed-back gradient, every
+    worker's filter / scale / shift gradients, the aggregated update."""
+    from paper_1812_10624_amd.netrun import Aggregator, ConvWorker, FcWorker
+    wl = wl_mod.get_workload("miniresbn")
+    seed = 4
+    imgs = [wl_mod.gen_images(wl, seed, k, B) for k in range(K)]
+    labels = wl_mod.gen_labels(wl, seed, K * B)
+    cp = wl_mod.gen_conv_params(wl, seed)
+    fp = wl_mod.gen_fc_params(wl, seed)
+    cm = {n: (np.zeros_like(w), _none_or(np.zeros_like, b)) for n, (w, b) in cp.items()}
+    fm = [(np.zeros_like(w), np.zeros_like(b)) for w, b in fp]
+    cp_ref, cm_ref, fp_ref, fm_ref = (copy.deepcopy(a) for a in (cp, cm, fp, fm))
+    lr, mom, wd = 0.05, 0.9, 1e-4
+    ref = onet.split_step(o32, wl.ops, imgs, labels, cp_ref, cm_ref, fp_ref, fm_ref, lr, mom, wd, keep=True)
+
+    gpar = {n: (dev(w), _none_or(dev, b)) for n, (w, b) in cp.items()}
+    gcm = {n: (dev(w), _none_or(dev, b)) for n, (w, b) in cm.items()}
+    gfp = [(dev(w), dev(b)) for w, b in fp]
+    gfm = [(dev(w), dev(b)) for w, b in fm]
+    workers = [ConvWorker(wl.ops, wl.image, B, gpar) for _ in range(K)]
+    fcw = FcWorker(wl.fc_dims, K * B, gfp, gfm, lr, mom, wd)
+    feats = torch.empty((K * B, wl.fc_dims[0]), device="cuda:0")
+    for k, wk in enumerate(workers):
+        feats[k * B:(k + 1) * B].copy_(wk.forward(dev(imgs[k])).view(B, -1))
+    assert rel_err(host(feats), ref["feats"]) < TOL_F32
+    # every normalisation layer's saved statistics on worker 0
+    for op in wl.ops:
+        if op["op"] == "bn":
+            mean_ref, istd_ref = ref["bufs"][0][op["dst"] + "#stats"][0]
+            mean, istd = workers[0].bn_stats[op["name"]]
+            assert np.abs(host(mean) - mean_ref).max() < 1e-5 * max(1.0, np.abs(mean_ref).max()), op["name"]
+            assert rel_err(host(istd), istd_ref) < TOL_F32, op["name"]
+    dfeats = fcw.step(feats, dev(labels))
+    assert abs(float(host(fcw.loss)[0]) - ref["loss"]) < 1e-5 * max(1.0, abs(ref["loss"]))
+    assert rel_err(host(dfeats), ref["dfeats"]) < TOL_F32
+    for k, wk in enumerate(workers):
+        wk.backward(dfeats[k * B:(k + 1) * B])
+        for nme in cp:
+            for i in range(2):
+                if cp[nme][i] is None:
+                    assert wk.grads[nme][i] is None
+                    continue
+                assert rel_err(host(wk.grads[nme][i]), ref["worker_grads"][k][nme][i]) < 5 * TOL_F32, (k, nme, i)
+    flat = lambda d: [t for pair in d.values() for t in pair if t is not None]
+    agg = Aggregator(flat(gpar), flat(gcm), [flat(wk.grads) for wk in workers])
+    agg.step(1.0, lr, mom, wd)
+    for nme in cp:
+        for i in range(2):
+            if cp[nme][i] is None:
+                continue
+            assert rel_err(host(gcm[nme][i]), cm_ref[nme][i]) < 5 * TOL_F32, (nme, i)
+            assert rel_err(host(gpar[nme][i]) - cp[nme][i], cp_ref[nme][i] - cp[nme][i]) < 5 * TOL_F32, (nme, i)
+            assert not np.array_equal(host(gpar[nme][i]), cp[nme][i])
