@@ -7,7 +7,7 @@ A step is one pass of the whole hot path over one batch of synthetic input:
   ->  aggregation of K gradient shards + momentum-SGD update of the conv parameters.
 Inputs are resident in HBM before the timed region.  Prints ONE JSON line.
 
-  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload vgg16|alexnet|resnet50|tiny]
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload vgg16|alexnet|resnet50|resnet50bn|resnet152|resnet152bn|vgg19|mlp|tiny]
 """
 from __future__ import annotations
 
@@ -64,8 +64,8 @@ def main():
     # ---- inputs, resident before timing
     images = to_dev(W.gen_images(wl, seed, 0))
     labels = to_dev(W.gen_labels(wl, seed))
-    cp = {nm: (to_dev(w), to_dev(b)) for nm, (w, b) in W.gen_conv_params(wl, seed).items()}
-    cm = {nm: (torch.zeros_like(w), torch.zeros_like(b)) for nm, (w, b) in cp.items()}
+    cp = {nm: (to_dev(w), None if b is None else to_dev(b)) for nm, (w, b) in W.gen_conv_params(wl, seed).items()}
+    cm = {nm: (torch.zeros_like(w), None if b is None else torch.zeros_like(b)) for nm, (w, b) in cp.items()}
     gen = torch.Generator(device=dev)
     gen.manual_seed(seed)
     fp, fm = [], []
@@ -76,25 +76,24 @@ def main():
     worker = ConvWorker(wl.ops, wl.image, B, cp, dtype=api.BF16 if args.dtype == "bf16" else api.F32)
     fcw = FcWorker(wl.fc_dims, n, fp, fm, wl.lr, wl.momentum, wl.weight_decay)
     feats = torch.randn((n, wl.fc_dims[0]), device=dev, generator=gen).clamp_(min=0)   # filler rows of the other workers
-    names = list(cp)
-    shard0 = [worker.grads[nm][i] for nm in names for i in range(2)]
+    shard0 = W.flat_tensors(worker.grads)
     shards = [shard0] + [[torch.randn(t.shape, device=dev, generator=gen) * 1e-3 for t in shard0] for _ in range(K - 1)]
-    agg = Aggregator([cp[nm][i] for nm in names for i in range(2)], [cm[nm][i] for nm in names for i in range(2)], shards)
+    agg = Aggregator(W.flat_tensors(cp), W.flat_tensors(cm), shards)
     worker.buf["x0"].copy_(images)
 
     # ---- per-call instrumentation (HIP events on the stream the kernels are launched on)
     records = []     # (tag, start_event, end_event)
 
-    def timed(tag, fn, *a):
+    def timed(tag, fn, *a, **kw):
         s, e = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         s.record()
-        fn(*a)
+        fn(*a, **kw)
         e.record()
         records.append((tag, s, e))
 
     real = {k: getattr(api, k) for k in ("stanza_conv_fwd", "stanza_conv_bwd_data", "stanza_conv_bwd_weight",
                                          "stanza_pool_relu_fwd", "stanza_pool_relu_bwd", "stanza_add_relu_fwd",
-                                         "stanza_add_relu_bwd", "stanza_gap_fwd", "stanza_gap_bwd", "stanza_cast_f32_to_bf16",
+                                         "stanza_add_relu_bwd", "stanza_gap_fwd", "stanza_gap_bwd", "stanza_bn_fwd", "stanza_bn_bwd", "stanza_cast_f32_to_bf16",
                                          "stanza_cast_bf16_to_f32")}
     import paper_1812_10624_amd.netrun as netrun
 
@@ -187,8 +186,11 @@ def main():
             n_in = float(np.prod(shapes_all[op["src"]])); n_out = float(np.prod(shapes_all[op["dst"]]))
             pool_f += esz * n_in + esz * n_out + n_out                       # x read, y and argmax written
             pool_b += esz * n_out + n_out + (esz * n_out if op["relu"] else 0) + esz * n_in   # dy, argmax, y (gate) read, dx written
+    # normalisation layers: forward reads x twice (statistics, then apply) and writes y; backward reads x and dy twice, writes dx
+    bn_elems = sum(float(np.prod(shapes_all[op["src"]])) for op in wl.ops if op["op"] == "bn")
     hbm_kernels = {}
-    for tag, by in (("stanza_pool_relu_fwd", pool_f), ("stanza_pool_relu_bwd", pool_b)):
+    for tag, by in (("stanza_pool_relu_fwd", pool_f), ("stanza_pool_relu_bwd", pool_b),
+                    ("stanza_bn_fwd", 3 * esz * bn_elems), ("stanza_bn_bwd", 5 * esz * bn_elems)):
         if tag in tot and by > 0:
             gbs = by / (tot[tag] * 1e-3) / 1e9
             hbm_kernels[tag] = {"algorithmic_bytes_per_step": by, "ms_per_step": tot[tag], "GBps": gbs, "frac_hbm": gbs / HBM_PEAK_GBS}

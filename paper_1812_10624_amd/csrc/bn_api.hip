@@ -166,32 +166,47 @@ __global__ __launch_bounds__(256) void bn_reduce_kernel(const BnGeo g, const voi
     }
 }
 
-// Sums the slabs' partial sums per channel: 64 channels x 4 interleaved groups of slabs per workgroup, each group in
-// slab order, then the four groups in group order.
+// Sums the slabs' partial sums per channel: a workgroup takes 8 channels x 32 interleaved groups of slabs (eight loads in
+// flight per thread: the pass is bound by latency, not by bytes), each group in slab order, then the groups in group order.
 // BWD = false: mean, 1/std and (when given) the running averages.  BWD = true: out_a = dbeta, out_b = dgamma.
+constexpr int BN_FIN_CH = 8, BN_FIN_LANES = 32;
 template <bool BWD, bool BF16>
 __global__ __launch_bounds__(256) void bn_finalize_kernel(int C, int slabs, int rows, const float *__restrict__ partial,
                                                           const void *__restrict__ x_row0, float eps, float *__restrict__ out_a,
                                                           float *__restrict__ out_b, float *__restrict__ run_mean,
                                                           float *__restrict__ run_var, float mom)
 {
-    __shared__ float red[4][64][2];
-    const int lane = threadIdx.x & 63, grp = threadIdx.x >> 6;
-    const int c = blockIdx.x * 64 + lane;
+    __shared__ float red[BN_FIN_LANES][BN_FIN_CH][2];
+    const int cl = threadIdx.x % BN_FIN_CH, lane = threadIdx.x / BN_FIN_CH;
+    const int c = blockIdx.x * BN_FIN_CH + cl;
     float a = 0.f, b = 0.f;
     if (c < C) {
-        for (int s = grp; s < slabs; s += 4) {
+        int s = lane;
+        for (; s + 7 * BN_FIN_LANES < slabs; s += 8 * BN_FIN_LANES) {
+            float va[8], vb[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                va[u] = partial[(size_t)(s + u * BN_FIN_LANES) * 2 * C + c];
+                vb[u] = partial[(size_t)(s + u * BN_FIN_LANES) * 2 * C + C + c];
+            }
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                a += va[u];
+                b += vb[u];
+            }
+        }
+        for (; s < slabs; s += BN_FIN_LANES) {
             a += partial[(size_t)s * 2 * C + c];
             b += partial[(size_t)s * 2 * C + C + c];
         }
     }
-    red[grp][lane][0] = a;
-    red[grp][lane][1] = b;
+    red[lane][cl][0] = a;
+    red[lane][cl][1] = b;
     __syncthreads();
-    if (grp != 0 || c >= C) return;
-    for (int t = 1; t < 4; ++t) {
-        a += red[t][lane][0];
-        b += red[t][lane][1];
+    if (lane != 0 || c >= C) return;
+    for (int t = 1; t < BN_FIN_LANES; ++t) {
+        a += red[t][cl][0];
+        b += red[t][cl][1];
     }
     if (BWD) {
         out_a[c] = a;
@@ -358,10 +373,10 @@ extern "C" int stanza_bn_fwd(int64_t rows, int32_t C, int32_t dtype, float eps, 
     float *partial = reinterpret_cast<float *>(ws);
     bn_launch_reduce<false>(p, dtype, st, x, nullptr, nullptr, nullptr, nullptr, nullptr, 0, partial);
     if (dtype == STANZA_BF16)
-        hipLaunchKernelGGL((bn_finalize_kernel<false, true>), dim3((unsigned)cdiv(C, 64)), dim3(256), 0, st, C, p.slabs, (int)rows, partial, x, eps,
+        hipLaunchKernelGGL((bn_finalize_kernel<false, true>), dim3((unsigned)cdiv(C, BN_FIN_CH)), dim3(256), 0, st, C, p.slabs, (int)rows, partial, x, eps,
                            save_mean, save_istd, running_mean, running_var, momentum);
     else
-        hipLaunchKernelGGL((bn_finalize_kernel<false, false>), dim3((unsigned)cdiv(C, 64)), dim3(256), 0, st, C, p.slabs, (int)rows, partial, x, eps,
+        hipLaunchKernelGGL((bn_finalize_kernel<false, false>), dim3((unsigned)cdiv(C, BN_FIN_CH)), dim3(256), 0, st, C, p.slabs, (int)rows, partial, x, eps,
                            save_mean, save_istd, running_mean, running_var, momentum);
     bn_launch_apply<false>(p, dtype, st, x, nullptr, gamma, beta, save_mean, save_istd, nullptr, nullptr, relu ? 1 : 0, y);
     return launch_status();
@@ -380,7 +395,7 @@ extern "C" int stanza_bn_bwd(int64_t rows, int32_t C, int32_t dtype, int32_t rel
     hipStream_t st = (hipStream_t)stream;
     float *partial = reinterpret_cast<float *>(ws);
     bn_launch_reduce<true>(p, dtype, st, x, dy, gamma, beta, save_mean, save_istd, relu ? 1 : 0, partial);
-    hipLaunchKernelGGL((bn_finalize_kernel<true, false>), dim3((unsigned)cdiv(C, 64)), dim3(256), 0, st, C, p.slabs, (int)rows, partial, nullptr, 0.f,
+    hipLaunchKernelGGL((bn_finalize_kernel<true, false>), dim3((unsigned)cdiv(C, BN_FIN_CH)), dim3(256), 0, st, C, p.slabs, (int)rows, partial, nullptr, 0.f,
                        dbeta, dgamma, nullptr, nullptr, 0.f);
     bn_launch_apply<true>(p, dtype, st, x, dy, gamma, beta, save_mean, save_istd, dgamma, dbeta, relu ? 1 : 0, dx);
     return launch_status();
