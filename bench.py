@@ -34,6 +34,7 @@ def main():
     ap.add_argument("--dtype", default="f32", choices=["f32", "bf16"], help="conv-stack storage type (accumulation is always f32)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--detail", action="store_true", help="per-call timing table on stderr")
+    ap.add_argument("--dropout", type=float, default=0.0, help="seeded dropout after the FC worker's hidden layers (0: none)")
     ap.add_argument("--graph", action="store_true",
                     help="replay the step as one HIP graph in the timed region (launch-bound workloads); the per-call breakdown "
                          "and the roofline figures then come from the eager warm-up steps")
@@ -74,7 +75,7 @@ def main():
                    (torch.rand(o, device=dev, generator=gen) * 2 - 1) / i ** 0.5))
         fm.append((torch.zeros((o, i), device=dev), torch.zeros(o, device=dev)))
     worker = ConvWorker(wl.ops, wl.image, B, cp, dtype=api.BF16 if args.dtype == "bf16" else api.F32)
-    fcw = FcWorker(wl.fc_dims, n, fp, fm, wl.lr, wl.momentum, wl.weight_decay)
+    fcw = FcWorker(wl.fc_dims, n, fp, fm, wl.lr, wl.momentum, wl.weight_decay, dropout=(args.dropout, seed) if args.dropout > 0 else None)
     feats = torch.randn((n, wl.fc_dims[0]), device=dev, generator=gen).clamp_(min=0)   # filler rows of the other workers
     shard0 = W.flat_tensors(worker.grads)
     shards = [shard0] + [[torch.randn(t.shape, device=dev, generator=gen) * 1e-3 for t in shard0] for _ in range(K - 1)]
@@ -204,7 +205,7 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": args.dtype, "data": "synthetic", "launch": "hip_graph_replay" if args.graph else "eager",
         "config": {"workload": f"{wl.name}_shaped_conv_worker_B{B}_fc_worker_n{n}_K{K}_" + ("fp32" if args.dtype == "f32" else "bf16in_fp32acc"),
-                   "per_worker_batch": B, "conv_workers_K": K, "fc_rows": n},
+                   "per_worker_batch": B, "conv_workers_K": K, "fc_rows": n, "fc_dropout": args.dropout},
         "conv_worker_images_per_s": B / (conv_worker_ms * 1e-3),
         "conv_worker_ms": conv_worker_ms,
         "fc_worker_samples_per_s": n / (tot["stanza_fc_step"] * 1e-3),

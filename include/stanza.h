@@ -88,6 +88,9 @@ typedef struct {
     const int32_t *host_dims;
     int32_t n_samples;
     float lr, momentum, weight_decay;
+    float dropout_p;          /* 0: none; otherwise every hidden layer's ReLU output passes through stanza_dropout with */
+    uint64_t dropout_seed;    /* this seed and stream_id = (dropout_step << 8) | index of the layer (0-based), so that */
+    uint64_t dropout_step;    /* layers and iterations draw different masks; dropout_step < 2^56 */
 } stanza_fc_desc;
 
 const char *stanza_strerror(int status);
@@ -187,6 +190,8 @@ int stanza_cast_bf16_to_f32(int64_t numel, const void *src, float *dst, void *st
  *             dA_{l-1} = (dZ_l W_l) * [A_{l-1} > 0], all with the weights as they were BEFORE this call;
  *             dfeats = dZ_1 W_1 (no gate)
  *   update    for every W_l, b_l:  g += weight_decay*p;  v = momentum*v + g;  p -= lr*v   (Sec. 6.1)
+ * With desc->dropout_p > 0:  A_l = dropout(max(Z_l, 0)) for l < n_layers, and dA_{l-1} passes back through the same mask
+ * and scale before the ReLU gate (stanza_dropout below; the caller advances desc->dropout_step every iteration).
  * host_W, host_b, host_vW, host_vb: host arrays of n_layers device pointers; parameters and momentum
  * buffers are updated in place.  dfeats [n][A] and loss (1 float) are outputs; pred [n] may be NULL.
  * ws must hold stanza_fc_workspace_bytes(desc) bytes. */
@@ -194,6 +199,15 @@ size_t stanza_fc_workspace_bytes(const stanza_fc_desc *desc);
 int stanza_fc_step(const stanza_fc_desc *desc, const float *feats, const int32_t *labels,
                    float *const *host_W, float *const *host_b, float *const *host_vW, float *const *host_vb,
                    float *dfeats, float *loss, int32_t *pred, void *ws, size_t ws_bytes, void *stream);
+
+/* ---- Seeded dropout (the FC layers of the AlexNet- and VGG-shaped models of Sec. 6.1 are trained with it; the paper does
+ * not describe it, so the published inverted form is used):  y[i] = keep_i ? x[i] / (1 - p) : 0, float32, x == y allowed.
+ * keep_i is drawn from the counter-based Philox-4x32 generator with ten rounds (Salmon, Moraes, Dror, Shaw, SC 2011):
+ * element i takes word (i mod 4) of the block with counter words (i/4 low, i/4 high, stream_id low, stream_id high) and key
+ * words (seed low, seed high), and is kept iff the word is >= floor(p * 2^32).  The operation is its own transpose: the
+ * backward pass is the same call on the gradient.  Nothing is stored between the two.
+ * Errors: numel < 1 or >= 2^31, p outside [0, 1) -> STANZA_EINVAL; NULL / alignment as elsewhere. */
+int stanza_dropout(int64_t numel, float p, uint64_t seed, uint64_t stream_id, const float *x, float *y, void *stream);
 
 /* ---- One of several FC workers (Sec. 4.1.3: "each is responsible for an equal number of the CONV workers ... each FC
  * worker maintains a complete set of FC layers", and the FC workers then exchange their gradients by the same recursive

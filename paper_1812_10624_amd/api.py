@@ -24,7 +24,7 @@ EXPORTS = (
     "stanza_conv_bwd_weight", "stanza_pool_relu_fwd", "stanza_pool_relu_bwd", "stanza_add_relu_fwd",
     "stanza_add_relu_bwd", "stanza_gap_fwd", "stanza_gap_bwd", "stanza_cast_f32_to_bf16", "stanza_cast_bf16_to_f32",
     "stanza_bn_workspace_bytes", "stanza_bn_fwd", "stanza_bn_bwd",
-    "stanza_fc_workspace_bytes", "stanza_fc_step", "stanza_fc_grads", "stanza_ps_workspace_bytes", "stanza_ps_plan",
+    "stanza_fc_workspace_bytes", "stanza_fc_step", "stanza_fc_grads", "stanza_dropout", "stanza_ps_workspace_bytes", "stanza_ps_plan",
     "stanza_ps_aggregate_planned", "stanza_ps_aggregate", "stanza_ps_aggregate_ordered_planned", "stanza_ps_aggregate_ordered",
     "stanza_model_allreduce_rounds", "stanza_model_stanza_time", "stanza_model_stanza_throughput", "stanza_model_assign",
     "stanza_model_ps_time", "stanza_model_ps_throughput",
@@ -51,7 +51,8 @@ class ModelParams(C.Structure):
 
 class FcDesc(C.Structure):
     _fields_ = [("n_layers", C.c_int32), ("host_dims", C.POINTER(C.c_int32)), ("n_samples", C.c_int32),
-                ("lr", C.c_float), ("momentum", C.c_float), ("weight_decay", C.c_float)]
+                ("lr", C.c_float), ("momentum", C.c_float), ("weight_decay", C.c_float),
+                ("dropout_p", C.c_float), ("dropout_seed", C.c_uint64), ("dropout_step", C.c_uint64)]
 
 
 _lib = None
@@ -90,6 +91,7 @@ def load() -> C.CDLL:
     lib.stanza_fc_workspace_bytes.argtypes = [C.POINTER(FcDesc)]
     lib.stanza_fc_step.argtypes = [C.POINTER(FcDesc), vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.stanza_fc_grads.argtypes = [C.POINTER(FcDesc), i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.stanza_dropout.argtypes = [i64, f32, C.c_uint64, C.c_uint64, vp, vp, vp]
     lib.stanza_ps_workspace_bytes.restype = sz
     lib.stanza_ps_workspace_bytes.argtypes = [i32, i32]
     lib.stanza_ps_plan.argtypes = [i32, vp, vp, vp, vp, i32, vp, sz, vp]
@@ -222,9 +224,10 @@ def stanza_bn_bwd(x, dy, gamma, beta, save_mean, save_istd, dx, dgamma, dbeta, w
 class FcPlan:
     """Host-side descriptor of an FC stack plus its keep-alive arrays."""
 
-    def __init__(self, dims: Sequence[int], n_samples: int, lr: float, momentum: float, weight_decay: float):
+    def __init__(self, dims: Sequence[int], n_samples: int, lr: float, momentum: float, weight_decay: float,
+                 dropout_p: float = 0.0, dropout_seed: int = 0, dropout_step: int = 0):
         self.dims = (C.c_int32 * len(dims))(*dims)
-        self.desc = FcDesc(len(dims) - 1, self.dims, n_samples, lr, momentum, weight_decay)
+        self.desc = FcDesc(len(dims) - 1, self.dims, n_samples, lr, momentum, weight_decay, dropout_p, dropout_seed, dropout_step)
 
     def workspace_bytes(self) -> int:
         return int(load().stanza_fc_workspace_bytes(C.byref(self.desc)))
@@ -247,6 +250,10 @@ def stanza_fc_grads(plan: FcPlan, n_global: int, feats, labels, W: List[torch.Te
     _check(load().stanza_fc_grads(C.byref(plan.desc), n_global, _ptr(feats), _ptr(labels), _ptr_array(W), _ptr_array(b),
                                   _ptr_array(gW), _ptr_array(gb), _ptr(dfeats), _ptr(loss_part), _ptr(pred), p, n, _stream()),
            "stanza_fc_grads")
+
+
+def stanza_dropout(x, y, p: float, seed: int, stream_id: int):
+    _check(load().stanza_dropout(x.numel(), p, seed, stream_id, _ptr(x), _ptr(y), _stream()), "stanza_dropout")
 
 
 def stanza_ps_workspace_bytes(n_tensors: int, K: int) -> int:

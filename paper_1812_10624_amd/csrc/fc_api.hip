@@ -67,6 +67,69 @@ __global__ __launch_bounds__(256) void mean_loss_kernel(int n, int n_global, con
     if (threadIdx.x == 0) *loss = red[0] / (float)n_global;
 }
 
+// Seeded dropout of hidden activations (the FC layers of the paper's AlexNet- and VGG-shaped models, Sec. 6.1, are trained
+// with it; the paper does not describe the operation, so the published inverted form is used).  The mask comes from the
+// counter-based Philox-4x32 generator with ten rounds (Salmon et al., SC 2011): element i takes word i mod 4 of the
+// block whose counter is (i / 4, stream) under the key `seed`, and is kept iff that word is >= thr = floor(p * 2^32).
+// Nothing is stored: the backward pass draws the same words again.
+struct PhiloxKey {
+    uint32_t k0, k1, s0, s1;   // seed (low, high), stream (low, high)
+};
+
+__device__ __forceinline__ void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3, uint32_t k0, uint32_t k1, uint32_t (&out)[4])
+{
+#pragma unroll
+    for (int round = 0; round < 10; ++round) {
+        const uint32_t hi0 = __umulhi(0xD2511F53u, c0), lo0 = 0xD2511F53u * c0;
+        const uint32_t hi1 = __umulhi(0xCD9E8D57u, c2), lo1 = 0xCD9E8D57u * c2;
+        const uint32_t n0 = hi1 ^ c1 ^ k0, n2 = hi0 ^ c3 ^ k1;
+        c0 = n0; c1 = lo1; c2 = n2; c3 = lo0;
+        k0 += 0x9E3779B9u;
+        k1 += 0xBB67AE85u;
+    }
+    out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
+}
+
+// y[i] = keep_i ? x[i] * scale : 0 (x == y allowed).  One thread per generator block of four elements.
+__global__ __launch_bounds__(256) void dropout_kernel(size_t numel, uint32_t thr, float scale, PhiloxKey key, const float *x, float *y)
+{
+    const size_t blk = (size_t)blockIdx.x * 256 + threadIdx.x;
+    const size_t i0 = blk * 4;
+    if (i0 >= numel) return;
+    uint32_t r[4];
+    philox4x32_10((uint32_t)blk, (uint32_t)(blk >> 32), key.s0, key.s1, key.k0, key.k1, r);
+    if (i0 + 4 <= numel) {
+        const float4 v = *reinterpret_cast<const float4 *>(x + i0);
+        float4 o;
+        o.x = r[0] >= thr ? v.x * scale : 0.f;
+        o.y = r[1] >= thr ? v.y * scale : 0.f;
+        o.z = r[2] >= thr ? v.z * scale : 0.f;
+        o.w = r[3] >= thr ? v.w * scale : 0.f;
+        *reinterpret_cast<float4 *>(y + i0) = o;
+    } else {
+        for (int e = 0; i0 + e < numel; ++e) y[i0 + e] = r[e] >= thr ? x[i0 + e] * scale : 0.f;
+    }
+}
+
+__global__ __launch_bounds__(256) void scale_kernel(size_t numel, float scale, float *y)
+{
+    const size_t i0 = ((size_t)blockIdx.x * 256 + threadIdx.x) * 4;
+    if (i0 + 4 <= numel) {
+        float4 v = *reinterpret_cast<float4 *>(y + i0);
+        v.x *= scale; v.y *= scale; v.z *= scale; v.w *= scale;
+        *reinterpret_cast<float4 *>(y + i0) = v;
+    } else {
+        for (size_t i = i0; i < numel; ++i) y[i] *= scale;
+    }
+}
+
+static bool dropout_valid(float p) { return p >= 0.f && p < 1.f; }
+static uint32_t dropout_threshold(float p) { return (uint32_t)((double)p * 4294967296.0); }
+static PhiloxKey dropout_key(uint64_t seed, uint64_t stream_id)
+{
+    return PhiloxKey{(uint32_t)seed, (uint32_t)(seed >> 32), (uint32_t)stream_id, (uint32_t)(stream_id >> 32)};
+}
+
 struct FcLayout {
     size_t act_off[32];   // float offset of A_l (l = 1..L) in the workspace
     size_t dz_off[2];     // two gradient buffers of n * max_width floats
@@ -132,6 +195,7 @@ static int fc_run(const stanza_fc_desc *desc, int n_global, const float *feats, 
     int rc = fc_layout(desc, &lay);
     if (rc) return rc;
     if (n_global < desc->n_samples) return STANZA_EINVAL;
+    if (!dropout_valid(desc->dropout_p) || desc->dropout_step >= (uint64_t(1) << 56)) return STANZA_EINVAL;
     if (!feats || !labels || !host_W || !host_b || !dfeats || !loss || !ws) return STANZA_ENULL;
     if (fused ? (!host_vW || !host_vb) : !host_gb) return STANZA_ENULL;
     if (ws_bytes < lay.floats * 4) return STANZA_EWORKSPACE;
@@ -145,6 +209,9 @@ static int fc_run(const stanza_fc_desc *desc, int n_global, const float *feats, 
     }
     hipStream_t st = (hipStream_t)stream;
     float *base = (float *)ws;
+    const bool drop = desc->dropout_p > 0.f;
+    const uint32_t drop_thr = dropout_threshold(desc->dropout_p);
+    const float drop_scale = 1.f / (1.f - desc->dropout_p);
     auto act = [&](int l) -> const float * { return l == 0 ? feats : base + lay.act_off[l]; };
 
     // forward
@@ -158,6 +225,12 @@ static int fc_run(const stanza_fc_desc *desc, int n_global, const float *feats, 
         p.M = n; p.Nn = dims[l]; p.Kd = dims[l - 1];
         p.flags = EPI_BIAS | (l < L ? EPI_RELU : 0u);
         if ((rc = launch_igemm(MODE_FWD, p, 1, base + lay.partial_off, lay.partial_floats, st))) return rc;
+        if (drop && l < L) {   // hidden layer: the next layer (and the backward pass) sees the dropped activations
+            const size_t numel = (size_t)n * dims[l];
+            hipLaunchKernelGGL(dropout_kernel, dim3((unsigned)cdiv64(cdiv64(numel, 4), 256)), dim3(256), 0, st, numel, drop_thr, drop_scale,
+                               dropout_key(desc->dropout_seed, (desc->dropout_step << 8) | (uint64_t)(l - 1)), p.out, p.out);
+            if ((rc = launch_status())) return rc;
+        }
     }
     // loss and its gradient
     float *dz = base + lay.dz_off[0], *dz_next = base + lay.dz_off[1];
@@ -180,6 +253,13 @@ static int fc_run(const stanza_fc_desc *desc, int n_global, const float *feats, 
             p.M = n; p.Nn = in; p.Kd = out;
             p.flags = p.xmask ? EPI_XMASK : 0u;
             if ((rc = launch_igemm(MODE_BWD_DATA, p, 1, base + lay.partial_off, lay.partial_floats, st))) return rc;
+            if (drop && l > 1) {
+                // the gate [A > 0] above used the dropped activations, so dropped units are zero already (ReLU and mask
+                // in one test); what remains of the mask's backward is the scale of the kept units
+                const size_t numel = (size_t)n * in;
+                hipLaunchKernelGGL(scale_kernel, dim3((unsigned)cdiv64(cdiv64(numel, 4), 256)), dim3(256), 0, st, numel, drop_scale, dz_next);
+                if ((rc = launch_status())) return rc;
+            }
         }
         {   // weight gradient: fused with the update, or written out
             GemmParams p{};
@@ -224,4 +304,14 @@ extern "C" int stanza_fc_grads(const stanza_fc_desc *desc, int32_t n_global, con
     if (!host_gW) return STANZA_ENULL;
     return fc_run(desc, n_global, feats, labels, host_W, host_b, nullptr, nullptr, host_gW, host_gb, dfeats, loss_part, pred, ws,
                   ws_bytes, stream);
+}
+
+extern "C" int stanza_dropout(int64_t numel, float p, uint64_t seed, uint64_t stream_id, const float *x, float *y, void *stream)
+{
+    if (numel < 1 || numel >= (int64_t(1) << 31) || !dropout_valid(p)) return STANZA_EINVAL;
+    if (!x || !y) return STANZA_ENULL;
+    if (!aligned16(x) || !aligned16(y)) return STANZA_EALIGN;
+    hipLaunchKernelGGL(dropout_kernel, dim3((unsigned)cdiv64(cdiv64(numel, 4), 256)), dim3(256), 0, (hipStream_t)stream, (size_t)numel,
+                       dropout_threshold(p), 1.f / (1.f - p), dropout_key(seed, stream_id), x, y);
+    return launch_status();
 }

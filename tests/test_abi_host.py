@@ -127,3 +127,17 @@ def test_bn_errors(api):
     assert call(x=None) == -2 and call(x=p4) == -3 and call(nbytes=8) == -5
     assert lib.stanza_bn_workspace_bytes(0, 8, api.F32) == 0
     assert lib.stanza_bn_bwd(100, 8, api.F32, 0, p16, None, p16, p16, p16, p16, p16, p16, p16, p16, need, None) == -2
+
+
+def test_dropout_errors(api):
+    lib = api.load()
+    p16, p4 = C.c_void_p(0x1000), C.c_void_p(0x1004)
+    assert lib.stanza_dropout(0, 0.5, 1, 1, p16, p16, None) == -1
+    assert lib.stanza_dropout(16, 1.0, 1, 1, p16, p16, None) == -1
+    assert lib.stanza_dropout(16, -0.1, 1, 1, p16, p16, None) == -1
+    assert lib.stanza_dropout(16, 0.5, 1, 1, None, p16, None) == -2
+    assert lib.stanza_dropout(16, 0.5, 1, 1, p16, p4, None) == -3
+    plan = api.FcPlan([64, 32, 10], 8, 0.01, 0.9, 0.0, dropout_p=1.0)
+    arr = (C.c_void_p * 2)(0x1000, 0x2000)
+    need = plan.workspace_bytes()
+    assert lib.stanza_fc_step(C.byref(plan.desc), p16, p16, arr, arr, arr, arr, p16, p16, None, p16, need, None) == -1
