@@ -52,6 +52,11 @@ class ConvGeom:
     S: int
     stride: int = 1
     pad: int = 0
+    pad_w: int = -1             # horizontal padding when it differs from the vertical one (1xn / nx1 filters); -1: same
+
+    @property
+    def pw(self):
+        return self.pad if self.pad_w < 0 else self.pad_w
 
     @property
     def Ho(self):
@@ -59,10 +64,10 @@ class ConvGeom:
 
     @property
     def Wo(self):
-        return (self.W + 2 * self.pad - self.S) // self.stride + 1
+        return (self.W + 2 * self.pw - self.S) // self.stride + 1
 
     def c(self):
-        return _ConvD(self.N, self.H, self.W, self.C, self.K, self.R, self.S, self.stride, self.stride, self.pad, self.pad)
+        return _ConvD(self.N, self.H, self.W, self.C, self.K, self.R, self.S, self.stride, self.stride, self.pad, self.pw)
 
 
 @dataclass(frozen=True)
@@ -166,6 +171,18 @@ class Oracle:
         assert dy.shape == (g.N, g.Ho, g.Wo, g.C) and am.dtype == np.uint8
         dx = np.empty((g.N, g.H, g.W, g.C), self.dtype)
         self._l.oracle_pool_relu_bwd(C.byref(g.c()), self._p(dy), self._p(y), am.ctypes.data_as(C.c_void_p), self._p(dx))
+        return dx
+
+    def avgpool_fwd(self, g: PoolGeom, x):
+        assert x.shape == (g.N, g.H, g.W, g.C)
+        y = np.empty((g.N, g.Ho, g.Wo, g.C), self.dtype)
+        self._l.oracle_avgpool_fwd(C.byref(g.c()), self._p(x), self._p(y))
+        return y
+
+    def avgpool_bwd(self, g: PoolGeom, dy):
+        assert dy.shape == (g.N, g.Ho, g.Wo, g.C)
+        dx = np.empty((g.N, g.H, g.W, g.C), self.dtype)
+        self._l.oracle_avgpool_bwd(C.byref(g.c()), self._p(dy), self._p(dx))
         return dx
 
     # -- residual add, global average pool

@@ -30,7 +30,7 @@ def conv_stack_forward(o: Oracle, ops: List[dict], x0, params, bn_groups: int = 
         if kind == "conv":
             x = buf[op["src"]]
             n, h, w, c = x.shape
-            g = ConvGeom(n, h, w, c, op["K"], op["R"], op["S"], op["stride"], op["pad"])
+            g = ConvGeom(n, h, w, c, op["K"], op["R"], op["S"], op["stride"], op["pad"], op.get("pad_w", -1))
             wt, b = params[op["name"]]
             buf[op["dst"]] = o.conv_fwd(g, x, wt, b, relu=op["relu"])
         elif kind == "pool":
@@ -38,6 +38,12 @@ def conv_stack_forward(o: Oracle, ops: List[dict], x0, params, bn_groups: int = 
             n, h, w, c = x.shape
             g = PoolGeom(n, h, w, c, op["win"], op["stride"], op["pad"], op["relu"])
             buf[op["dst"]], buf[op["dst"] + "#argmax"] = o.pool_relu_fwd(g, x)
+        elif kind == "avgpool":
+            x = buf[op["src"]]
+            n, h, w, c = x.shape
+            buf[op["dst"]] = o.avgpool_fwd(PoolGeom(n, h, w, c, op["win"], op["stride"], op["pad"], False), x)
+        elif kind == "concat":
+            buf[op["dst"]] = np.concatenate([buf[sname] for sname in op["srcs"]], axis=3)
         elif kind == "bn":
             x = buf[op["src"]]
             gamma, beta = params[op["name"]]
@@ -70,7 +76,7 @@ def conv_stack_backward(o: Oracle, ops: List[dict], buf, params, dfeat):
         if kind == "conv":
             x = buf[op["src"]]
             n, h, w, c = x.shape
-            g = ConvGeom(n, h, w, c, op["K"], op["R"], op["S"], op["stride"], op["pad"])
+            g = ConvGeom(n, h, w, c, op["K"], op["R"], op["S"], op["stride"], op["pad"], op.get("pad_w", -1))
             dy = grad[op["dst"]]
             if op["relu"]:
                 dy = o.relu_bwd(dy, buf[op["dst"]])
@@ -84,6 +90,15 @@ def conv_stack_backward(o: Oracle, ops: List[dict], buf, params, dfeat):
             n, h, w, c = x.shape
             g = PoolGeom(n, h, w, c, op["win"], op["stride"], op["pad"], op["relu"])
             give(op["src"], o.pool_relu_bwd(g, grad[op["dst"]], buf[op["dst"]], buf[op["dst"] + "#argmax"]))
+        elif kind == "avgpool":
+            n, h, w, c = buf[op["src"]].shape
+            give(op["src"], o.avgpool_bwd(PoolGeom(n, h, w, c, op["win"], op["stride"], op["pad"], False), np.ascontiguousarray(grad[op["dst"]])))
+        elif kind == "concat":
+            at = 0
+            for sname in op["srcs"]:
+                cs = buf[sname].shape[3]
+                give(sname, np.ascontiguousarray(grad[op["dst"]][..., at:at + cs]))
+                at += cs
         elif kind == "bn":
             x, dy = buf[op["src"]], grad[op["dst"]]
             if op["relu"]:

@@ -416,6 +416,58 @@ double oracle_softmax_ce_part(int n_local, int n_global, int classes, const REAL
     return total / (double)n_global;
 }
 
+/* -------------------------------------------------------------- average pool
+ * The pooling branch of the Inception blocks (the paper trains Inception-V3, Sec. 6.1,
+ * without describing its layers): the mean over the part of the window that lies inside
+ * the image (padding is not counted), and its transpose for the backward pass:
+ *   y[n,p,q,c]  = (1/cnt(p,q)) sum over valid (i,j) of x[n, p*s-pad+i, q*s-pad+j, c]
+ *   dx[n,h,w,c] = sum over windows (p,q) containing (h,w) of dy[n,p,q,c] / cnt(p,q) */
+void oracle_avgpool_fwd(const opool_t *d, const REAL *x, REAL *y)
+{
+    const int Ho = out_dim(d->H, d->win_h, d->stride_h, d->pad_h), Wo = out_dim(d->W, d->win_w, d->stride_w, d->pad_w);
+#pragma omp parallel for schedule(static)
+    for (int np = 0; np < d->N * Ho; ++np) {
+        const int n = np / Ho, p = np % Ho;
+        for (int q = 0; q < Wo; ++q)
+            for (int c = 0; c < d->C; ++c) {
+                double s = 0.0;
+                int cnt = 0;
+                for (int i = 0; i < d->win_h; ++i)
+                    for (int j = 0; j < d->win_w; ++j) {
+                        const int h = p * d->stride_h - d->pad_h + i, w = q * d->stride_w - d->pad_w + j;
+                        if (h < 0 || h >= d->H || w < 0 || w >= d->W) continue;
+                        s += (double)x[(((size_t)n * d->H + h) * d->W + w) * d->C + c];
+                        ++cnt;
+                    }
+                y[(((size_t)n * Ho + p) * Wo + q) * d->C + c] = (REAL)(s / (double)cnt);
+            }
+    }
+}
+
+void oracle_avgpool_bwd(const opool_t *d, const REAL *dy, REAL *dx)
+{
+    const int Ho = out_dim(d->H, d->win_h, d->stride_h, d->pad_h), Wo = out_dim(d->W, d->win_w, d->stride_w, d->pad_w);
+#pragma omp parallel for schedule(static)
+    for (int nh = 0; nh < d->N * d->H; ++nh) {
+        const int n = nh / d->H, h = nh % d->H;
+        for (int w = 0; w < d->W; ++w)
+            for (int c = 0; c < d->C; ++c) {
+                double s = 0.0;
+                for (int p = 0; p < Ho; ++p)
+                    for (int q = 0; q < Wo; ++q) {
+                        const int h0 = p * d->stride_h - d->pad_h, w0 = q * d->stride_w - d->pad_w;
+                        if (h < h0 || h >= h0 + d->win_h || w < w0 || w >= w0 + d->win_w) continue;
+                        int cnt = 0;   /* valid elements of window (p,q) */
+                        for (int i = 0; i < d->win_h; ++i)
+                            for (int j = 0; j < d->win_w; ++j)
+                                if (h0 + i >= 0 && h0 + i < d->H && w0 + j >= 0 && w0 + j < d->W) ++cnt;
+                        s += (double)dy[(((size_t)n * Ho + p) * Wo + q) * d->C + c] / (double)cnt;
+                    }
+                dx[(((size_t)n * d->H + h) * d->W + w) * d->C + c] = (REAL)s;
+            }
+    }
+}
+
 /* -------------------------------------------------------------- batch normalisation
  * The residual networks of the paper's table of models (Sec. 6.1 "Setup") carry a
  * normalisation layer after every convolution; the paper never discusses it, so the

@@ -118,6 +118,79 @@ def test_bn_float_storage_agrees_with_double(o32, o64):
     np.testing.assert_allclose(dx32, dx64, rtol=1e-4, atol=1e-5)
 
 
+# ------------------------------------------------------------------ average pool, concatenation
+@pytest.mark.parametrize("geom", [(2, 7, 6, 3, 3, 1, 1), (1, 8, 8, 2, 3, 2, 0), (2, 5, 5, 4, 2, 2, 1), (1, 6, 7, 2, 5, 3, 2)])
+def test_avgpool_against_masked_library_sums(o64, geom):
+    """Window sums of x and of the image's indicator through scipy's correlation: the mean over the valid part of
+    each window is their ratio; the backward pass is the transpose (adjoint identity) and sums to sum(dy)."""
+    import scipy.signal
+    from oracle import PoolGeom
+    n, h, w, c, win, stride, pad = geom
+    g = PoolGeom(n, h, w, c, win, stride, pad, False)
+    rng = np.random.default_rng(7)
+    x = rng.standard_normal((n, h, w, c))
+    y = o64.avgpool_fwd(g, x)
+    ones = np.ones((win, win))
+    cnt = scipy.signal.correlate2d(np.pad(np.ones((h, w)), pad), ones, mode="valid")[::stride, ::stride]
+    assert cnt.shape == (g.Ho, g.Wo) and cnt.min() >= 1
+    for i in range(n):
+        for ch in range(c):
+            tot = scipy.signal.correlate2d(np.pad(x[i, :, :, ch], pad), ones, mode="valid")[::stride, ::stride]
+            np.testing.assert_allclose(y[i, :, :, ch], tot / cnt, rtol=1e-12, atol=1e-13)
+    dy = rng.standard_normal(y.shape)
+    dx = o64.avgpool_bwd(g, dy)
+    assert abs(np.vdot(y, dy) - np.vdot(x, dx)) < 1e-11
+    np.testing.assert_allclose(dx.sum(axis=(1, 2)), dy.sum(axis=(1, 2)), rtol=1e-11, atol=1e-12)
+    # a constant image stays constant, padding or not
+    np.testing.assert_allclose(o64.avgpool_fwd(g, np.full_like(x, 2.5)), 2.5, rtol=1e-13)
+
+
+def test_inception_table_matches_published_network():
+    """Main tower of the published network: 23.8M parameters (the 27M the paper prints, Sec. 2.3 table of models,
+    include its auxiliary classifier, which is not built), 5.7 G multiply-adds per 299x299 image, 35/17/8 grids of
+    288/768/2048 channels."""
+    wl = wl_mod.get_workload("inception3")
+    conv, fc = wl_mod.count_params(wl)
+    assert conv + fc == 23_834_568
+    assert 0.85 < (conv + fc) / 27e6 < 0.9
+    sh = wl_mod.shape_pass(wl, 1)
+    assert sh["a2"] == (1, 35, 35, 288) and sh["c3x"] == (1, 17, 17, 768) and sh["e1"] == (1, 8, 8, 2048)
+    assert abs(wl_mod.conv_flops(wl, 1)[0] / 2 / 5.71e9 - 1) < 0.01
+
+
+def test_mini_inception_gradients_match_finite_differences(o64):
+    """Every kind of block (branches, concatenation, average and max pooling branches, 1xn / nx1 filters, grid
+    reductions) through the chained gradients of the whole small stack."""
+    wl = wl_mod.get_workload("miniinception")
+    B = 2
+    imgs, labels, cp, cm, fp, fm = _setup(o64, wl, 6, 1, B)
+
+    def loss_of(params):
+        buf = onet.conv_stack_forward(o64, wl.ops, imgs[0], params)
+        return onet.fc_step(o64, buf["feat"].reshape(B, -1), labels, fp, fm, 0, 0, 0, update=False)["loss"]
+
+    buf = onet.conv_stack_forward(o64, wl.ops, imgs[0], cp)
+    fc = onet.fc_step(o64, buf["feat"].reshape(B, -1), labels, fp, fm, 0, 0, 0, update=False)
+    pg, _ = onet.conv_stack_backward(o64, wl.ops, buf, cp, fc["dfeats"])
+    rng = np.random.default_rng(3)
+    names = [n for n in cp if not n.endswith("_bn")]
+    for name in [names[i] for i in rng.choice(len(names), 16, replace=False)] + ["c1a", "a0_pool", "b_dblc", "c0x_d3", "d_7d", "e0_d3b"]:
+        t = cp[name][0]
+        idx = tuple(rng.integers(0, s) for s in t.shape)
+        old = t[idx]
+        got = pg[name][0][idx]
+        errs = []
+        for h in (1e-6, 1e-7):       # an early filter reaches so many units that the wider step may cross a ReLU kink
+            t[idx] = old + h
+            lp = loss_of(cp)
+            t[idx] = old - h
+            lm = loss_of(cp)
+            t[idx] = old
+            fd = (lp - lm) / (2 * h)
+            errs.append(abs(fd - got) / max(abs(fd), 1e-2))
+        assert min(errs) < 5e-6, (name, errs, got)
+
+
 # ------------------------------------------------------------------ whole normalised residual step
 def _arr(o, t):
     return None if t is None else o.arr(t)

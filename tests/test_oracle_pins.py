@@ -21,6 +21,9 @@ GEOMS = [
     ConvGeom(1, 7, 7, 3, 4, 1, 1, 2, 0),     # strided pointwise (projection shortcut)
     ConvGeom(1, 23, 23, 1, 2, 11, 11, 4, 2),  # large filter, stride 4
     ConvGeom(2, 4, 4, 2, 3, 3, 3, 1, 0),     # no padding
+    ConvGeom(2, 6, 9, 3, 4, 1, 7, 1, 0, 3),  # 1x7 filter, padded along the width only
+    ConvGeom(1, 9, 6, 2, 3, 7, 1, 1, 3, 0),  # 7x1 filter, padded along the height only
+    ConvGeom(2, 5, 4, 3, 2, 3, 1, 1, 1, 0),  # 3x1
 ]
 
 
@@ -38,14 +41,14 @@ def toeplitz(g: ConvGeom, w):
                     row = ((n * g.Ho + p) * g.Wo + q) * g.K + k
                     for r in range(g.R):
                         for s in range(g.S):
-                            h, ww = p * g.stride - g.pad + r, q * g.stride - g.pad + s
+                            h, ww = p * g.stride - g.pad + r, q * g.stride - g.pw + s
                             if 0 <= h < g.H and 0 <= ww < g.W:
                                 for c in range(g.C):
                                     T[row, ((n * g.H + h) * g.W + ww) * g.C + c] += w[k, r, s, c]
     return T
 
 
-@pytest.mark.parametrize("g", GEOMS, ids=lambda g: f"{g.H}x{g.W}x{g.C}k{g.K}r{g.R}s{g.stride}p{g.pad}")
+@pytest.mark.parametrize("g", GEOMS, ids=lambda g: f"{g.H}x{g.W}x{g.C}k{g.K}r{g.R}x{g.S}s{g.stride}p{g.pad}x{g.pw}")
 def test_conv_against_dense_operator(o64, g):
     x, w, b = rnd((g.N, g.H, g.W, g.C)), rnd((g.K, g.R, g.S, g.C)), rnd((g.K,))
     dy = rnd((g.N, g.Ho, g.Wo, g.K))
@@ -107,7 +110,7 @@ def test_conv_special_cases(o64):
     np.testing.assert_array_equal(y[0, -1, :, 0], 0)
 
 
-@pytest.mark.parametrize("g", GEOMS[:6], ids=lambda g: f"r{g.R}s{g.stride}p{g.pad}")
+@pytest.mark.parametrize("g", GEOMS[:6] + GEOMS[8:], ids=lambda g: f"r{g.R}x{g.S}s{g.stride}p{g.pad}x{g.pw}")
 def test_conv_adjoint_identities(o64, g):
     x, w = rnd((g.N, g.H, g.W, g.C)), rnd((g.K, g.R, g.S, g.C))
     w2 = rnd(w.shape)

@@ -20,7 +20,10 @@ A conv stack is an op list over named buffers; every op is a dict:
   {"op": "conv", "name", "src", "dst", "K","R","S","stride","pad","relu","bias"}   bias False: no bias term
   {"op": "bn", "name", "src", "dst", "relu", "eps"}   batch normalisation over the worker's own batch (+ReLU)
   {"op": "pool", "src", "dst", "win","stride","pad","relu"}
+  {"op": "avgpool", "src", "dst", "win","stride","pad"}   mean over the part of the window inside the image
+  {"op": "concat", "srcs": [...], "dst"}       channel concatenation, in the order listed
   {"op": "add_relu", "a", "b", "dst"}          dst = max(0, a + b)
+A conv may carry "pad_w" (and S != R) for the 1xn / nx1 filters of the Inception blocks: "pad" is then the vertical padding.
   {"op": "gap", "src", "dst"}                  global average pool
 The first buffer is "x0" (the images) and the last op writes "feat".
 """
@@ -61,9 +64,12 @@ class Workload:
         return self.fc_dims[-1]
 
 
-def _conv(name, src, dst, K, R, stride=1, pad=0, relu=True, S=None, bias=True):
-    return dict(op="conv", name=name, src=src, dst=dst, K=K, R=R, S=R if S is None else S,
-                stride=stride, pad=pad, relu=relu, bias=bias)
+def _conv(name, src, dst, K, R, stride=1, pad=0, relu=True, S=None, bias=True, pad_w=None):
+    d = dict(op="conv", name=name, src=src, dst=dst, K=K, R=R, S=R if S is None else S,
+             stride=stride, pad=pad, relu=relu, bias=bias)
+    if pad_w is not None and pad_w != pad:
+        d["pad_w"] = pad_w
+    return d
 
 
 def _bn(name, src, dst, relu, eps=1e-5):
@@ -164,6 +170,84 @@ def _mini_res_ops(bn=False):
     return ops
 
 
+def _inception_v3_ops(width_div=1, blocks=(3, 4, 2)):
+    """The Inception-V3 conv stack as published (Szegedy et al., "Rethinking the Inception architecture"; the variant
+    with factorised 7x7 filters and the expanded 8x8 blocks), main tower only: every convolution is bias-free and
+    followed by batch normalisation (eps 1e-3) and ReLU.  Stem 3x3/2, 3x3, 3x3 (padded), 3x3/2 max-pool, 1x1, 3x3,
+    3x3/2 max-pool; three 35x35 blocks; a grid reduction; four 17x17 blocks with 1x7 / 7x1 filters; a grid reduction;
+    two 8x8 blocks with split 1x3 / 3x1 filters; global average pool.  In every block the pooling branch comes last.
+    width_div divides every channel count and `blocks` sets how many blocks of each kind: small stacks for exhaustive
+    checks."""
+    ops = []
+    wd = lambda c: max(c // width_div, 2)
+
+    def unit(name, src, K, R, S=None, stride=1, pad=0, pad_w=None):
+        ops.append(_conv(name, src, name + "_z", wd(K), R, stride, pad, relu=False, S=S, bias=False, pad_w=pad_w))
+        ops.append(_bn(name + "_bn", name + "_z", name, relu=True, eps=1e-3))
+        return name
+
+    cur = unit("c1a", "x0", 32, 3, stride=2)
+    cur = unit("c2a", cur, 32, 3)
+    cur = unit("c2b", cur, 64, 3, pad=1)
+    ops.append(_pool(cur, "p1", 3, 2, 0, relu=False)); cur = "p1"
+    cur = unit("c3b", cur, 80, 1)
+    cur = unit("c4a", cur, 192, 3)
+    ops.append(_pool(cur, "p2", 3, 2, 0, relu=False)); cur = "p2"
+
+    def avg(src, dst):
+        ops.append(dict(op="avgpool", src=src, dst=dst, win=3, stride=1, pad=1))
+        return dst
+
+    def cat(tag, srcs):
+        ops.append(dict(op="concat", srcs=srcs, dst=tag))
+        return tag
+
+    for i, pf in enumerate((32, 64, 64)[:blocks[0]]):          # 35x35 blocks
+        t = f"a{i}"
+        b1 = unit(t + "_1x1", cur, 64, 1)
+        b5 = unit(t + "_5x5b", unit(t + "_5x5a", cur, 48, 1), 64, 5, pad=2)
+        b3 = unit(t + "_3x3c", unit(t + "_3x3b", unit(t + "_3x3a", cur, 64, 1), 96, 3, pad=1), 96, 3, pad=1)
+        bp = unit(t + "_pool", avg(cur, t + "_avg"), pf, 1)
+        cur = cat(t, [b1, b5, b3, bp])
+    # grid reduction 35 -> 17
+    b3 = unit("b_3x3", cur, 384, 3, stride=2)
+    bd = unit("b_dblc", unit("b_dblb", unit("b_dbla", cur, 64, 1), 96, 3, pad=1), 96, 3, stride=2)
+    ops.append(_pool(cur, "b_max", 3, 2, 0, relu=False))
+    cur = cat("b", [b3, bd, "b_max"])
+    for i, c7 in enumerate((128, 160, 160, 192)[:blocks[1]]):  # 17x17 blocks
+        t = f"c{i}x"
+        b1 = unit(t + "_1x1", cur, 192, 1)
+        b7 = unit(t + "_7c", unit(t + "_7b", unit(t + "_7a", cur, c7, 1), c7, 1, S=7, pad=0, pad_w=3), 192, 7, S=1, pad=3, pad_w=0)
+        d = unit(t + "_d1", cur, c7, 1)
+        d = unit(t + "_d2", d, c7, 7, S=1, pad=3, pad_w=0)
+        d = unit(t + "_d3", d, c7, 1, S=7, pad=0, pad_w=3)
+        d = unit(t + "_d4", d, c7, 7, S=1, pad=3, pad_w=0)
+        d = unit(t + "_d5", d, 192, 1, S=7, pad=0, pad_w=3)
+        bp = unit(t + "_pool", avg(cur, t + "_avg"), 192, 1)
+        cur = cat(t, [b1, b7, d, bp])
+    # grid reduction 17 -> 8
+    b3 = unit("d_3b", unit("d_3a", cur, 192, 1), 320, 3, stride=2)
+    b7 = unit("d_7a", cur, 192, 1)
+    b7 = unit("d_7b", b7, 192, 1, S=7, pad=0, pad_w=3)
+    b7 = unit("d_7c", b7, 192, 7, S=1, pad=3, pad_w=0)
+    b7 = unit("d_7d", b7, 192, 3, stride=2)
+    ops.append(_pool(cur, "d_max", 3, 2, 0, relu=False))
+    cur = cat("d", [b3, b7, "d_max"])
+    for i in range(blocks[2]):                                  # 8x8 blocks
+        t = f"e{i}"
+        b1 = unit(t + "_1x1", cur, 320, 1)
+        m = unit(t + "_3a", cur, 384, 1)
+        m1 = unit(t + "_3b1", m, 384, 1, S=3, pad=0, pad_w=1)
+        m2 = unit(t + "_3b2", m, 384, 3, S=1, pad=1, pad_w=0)
+        d = unit(t + "_d2", unit(t + "_d1", cur, 448, 1), 384, 3, pad=1)
+        d1 = unit(t + "_d3a", d, 384, 1, S=3, pad=0, pad_w=1)
+        d2 = unit(t + "_d3b", d, 384, 3, S=1, pad=1, pad_w=0)
+        bp = unit(t + "_pool", avg(cur, t + "_avg"), 192, 1)
+        cur = cat(t, [b1, m1, m2, d1, d2, bp])
+    ops.append(dict(op="gap", src=cur, dst="feat"))
+    return ops
+
+
 def _mlp_front_ops(widths):
     """The front part of a layer-separated multilayer perceptron (Discussion, "Beyond CNNs"): fully connected
     layers with ReLU, written as 1x1 convolutions over a 1x1 "image" whose channels are the input vector, so that
@@ -204,6 +288,13 @@ def get_workload(name: str) -> Workload:
     if name == "resnet152bn":
         return Workload("resnet152bn", K=8, B=32, image=(224, 224, 3), ops=_resnet50_ops((3, 8, 36, 3), bn=True),
                         fc_dims=[2048, 1000])
+    if name == "inception3":
+        return Workload("inception3", K=8, B=32, image=(299, 299, 3), ops=_inception_v3_ops(), fc_dims=[2048, 1000],
+                        notes="main tower; the auxiliary classifier of the published network is not built")
+    if name == "miniinception":
+        ops = _inception_v3_ops(width_div=16, blocks=(1, 1, 1))
+        return Workload("miniinception", K=2, B=2, image=(139, 139, 3), ops=ops, fc_dims=[2048 // 16, 10],
+                        notes="one block of each kind at a sixteenth of the widths, for exhaustive parity")
     if name == "miniresbn":
         return Workload("miniresbn", K=2, B=3, image=(33, 35, 3), ops=_mini_res_ops(bn=True),
                         fc_dims=[32, 7], notes="small normalised residual stack for exhaustive parity")
@@ -220,7 +311,7 @@ def get_workload(name: str) -> Workload:
 
 
 WORKLOAD_NAMES = ("tiny", "alexnet", "vgg16", "resnet50", "minires", "mlp", "minimlp", "vgg19", "resnet152",
-                  "resnet50bn", "resnet152bn", "miniresbn")
+                  "resnet50bn", "resnet152bn", "miniresbn", "inception3", "miniinception")
 
 
 def _out_dim(h, win, stride, pad):
@@ -235,8 +326,12 @@ def shape_pass(wl: Workload, batch: int | None = None) -> Dict[str, Tuple[int, i
         if op["op"] == "conv":
             _, h, w, _ = shapes[op["src"]]
             shapes[op["dst"]] = (n, _out_dim(h, op["R"], op["stride"], op["pad"]),
-                                 _out_dim(w, op["S"], op["stride"], op["pad"]), op["K"])
-        elif op["op"] == "pool":
+                                 _out_dim(w, op["S"], op["stride"], op.get("pad_w", op["pad"])), op["K"])
+        elif op["op"] == "concat":
+            parts = [shapes[sname] for sname in op["srcs"]]
+            assert all(p[:3] == parts[0][:3] for p in parts), (op, parts)
+            shapes[op["dst"]] = parts[0][:3] + (sum(p[3] for p in parts),)
+        elif op["op"] in ("pool", "avgpool"):
             _, h, w, c = shapes[op["src"]]
             shapes[op["dst"]] = (n, _out_dim(h, op["win"], op["stride"], op["pad"]),
                                  _out_dim(w, op["win"], op["stride"], op["pad"]), c)
