@@ -7,7 +7,7 @@ A step is one pass of the whole hot path over one batch of synthetic input:
   ->  aggregation of K gradient shards + momentum-SGD update of the conv parameters.
 Inputs are resident in HBM before the timed region.  Prints ONE JSON line.
 
-  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload vgg16|alexnet|resnet50|resnet50bn|resnet152|resnet152bn|vgg19|mlp|tiny]
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload vgg16|alexnet|resnet50|resnet50bn|resnet152|resnet152bn|inception3|vgg19|mlp|tiny]
 """
 from __future__ import annotations
 
@@ -94,7 +94,8 @@ def main():
 
     real = {k: getattr(api, k) for k in ("stanza_conv_fwd", "stanza_conv_bwd_data", "stanza_conv_bwd_weight",
                                          "stanza_pool_relu_fwd", "stanza_pool_relu_bwd", "stanza_add_relu_fwd",
-                                         "stanza_add_relu_bwd", "stanza_gap_fwd", "stanza_gap_bwd", "stanza_bn_fwd", "stanza_bn_bwd", "stanza_cast_f32_to_bf16",
+                                         "stanza_add_relu_bwd", "stanza_gap_fwd", "stanza_gap_bwd", "stanza_bn_fwd", "stanza_bn_bwd", "stanza_avgpool_fwd",
+                                         "stanza_avgpool_bwd", "stanza_copy_channels", "stanza_cast_f32_to_bf16",
                                          "stanza_cast_bf16_to_f32")}
     import paper_1812_10624_amd.netrun as netrun
 

@@ -147,6 +147,19 @@ int stanza_add_relu_bwd(int64_t numel, int32_t dtype, const void *dout, const vo
 int stanza_gap_fwd(int32_t N, int32_t HW, int32_t C, int32_t dtype, const void *x, float *f, void *stream);
 int stanza_gap_bwd(int32_t N, int32_t HW, int32_t C, int32_t dtype, const float *df, void *dx, void *stream);
 
+/* ---- Average-pool branch and channel concatenation of the Inception blocks (the paper trains Inception-V3, Sec. 6.1,
+ * without describing its layers: plain definitions).  float32 only.
+ *   avgpool_fwd: y[n,p,q,c] = mean of x over the part of the window inside the image (padding is not counted);
+ *   avgpool_bwd: dx[n,h,w,c] = sum over the windows (p,q) containing (h,w) of dy[n,p,q,c] / (valid elements of (p,q)).
+ *   desc as for the max-pool (flags ignored; any window size; every window must reach the image).
+ *   copy2d: dst[r*dst_ld + j] = src[r*src_ld + j] for r < rows, j < cols (lengths in floats): with src a branch's
+ *   [rows][cols] output and dst = wide + channel offset, dst_ld = the wide tensor's channels, it writes one slice of a
+ *   concatenation; with the roles swapped it cuts the slice of the gradient back out.  src, dst 4-byte aligned (16-byte
+ *   accesses are used when pointers, cols and both lds allow); rows*ld < 2^31; ld < cols is STANZA_EINVAL. */
+int stanza_avgpool_fwd(const stanza_pool_desc *desc, int32_t dtype, const void *x, void *y, void *stream);
+int stanza_avgpool_bwd(const stanza_pool_desc *desc, int32_t dtype, const void *dy, void *dx, void *stream);
+int stanza_copy2d(int64_t rows, int32_t cols, const float *src, int64_t src_ld, float *dst, int64_t dst_ld, void *stream);
+
 /* ---- Batch normalisation in training mode, on the CONV worker (the residual networks of the paper's table of models,
  * Sec. 6.1, carry one after every convolution; the paper does not describe the layer, so the published transform is
  * used, and every worker takes the statistics over its OWN batch: nothing is exchanged between workers).

@@ -23,7 +23,7 @@ EXPORTS = (
     "stanza_strerror", "stanza_version", "stanza_conv_workspace_bytes", "stanza_conv_fwd", "stanza_conv_bwd_data",
     "stanza_conv_bwd_weight", "stanza_pool_relu_fwd", "stanza_pool_relu_bwd", "stanza_add_relu_fwd",
     "stanza_add_relu_bwd", "stanza_gap_fwd", "stanza_gap_bwd", "stanza_cast_f32_to_bf16", "stanza_cast_bf16_to_f32",
-    "stanza_bn_workspace_bytes", "stanza_bn_fwd", "stanza_bn_bwd",
+    "stanza_bn_workspace_bytes", "stanza_bn_fwd", "stanza_bn_bwd", "stanza_avgpool_fwd", "stanza_avgpool_bwd", "stanza_copy2d",
     "stanza_fc_workspace_bytes", "stanza_fc_step", "stanza_fc_grads", "stanza_dropout", "stanza_ps_workspace_bytes", "stanza_ps_plan",
     "stanza_ps_aggregate_planned", "stanza_ps_aggregate", "stanza_ps_aggregate_ordered_planned", "stanza_ps_aggregate_ordered",
     "stanza_model_allreduce_rounds", "stanza_model_stanza_time", "stanza_model_stanza_throughput", "stanza_model_assign",
@@ -83,6 +83,9 @@ def load() -> C.CDLL:
     lib.stanza_gap_bwd.argtypes = [i32, i32, i32, i32, vp, vp, vp]
     lib.stanza_cast_f32_to_bf16.argtypes = [i64, vp, vp, vp]
     lib.stanza_cast_bf16_to_f32.argtypes = [i64, vp, vp, vp]
+    lib.stanza_avgpool_fwd.argtypes = [C.POINTER(PoolDesc), i32, vp, vp, vp]
+    lib.stanza_avgpool_bwd.argtypes = [C.POINTER(PoolDesc), i32, vp, vp, vp]
+    lib.stanza_copy2d.argtypes = [i64, i32, vp, i64, vp, i64, vp]
     lib.stanza_bn_workspace_bytes.restype = sz
     lib.stanza_bn_workspace_bytes.argtypes = [i64, i32, i32]
     lib.stanza_bn_fwd.argtypes = [i64, i32, i32, f32, i32, vp, vp, vp, vp, vp, vp, vp, vp, f32, vp, sz, vp]
@@ -135,8 +138,8 @@ def _ws(t: Optional[torch.Tensor]):
     return (None, 0) if t is None else (_ptr(t), t.numel() * t.element_size())
 
 
-def conv_desc(N, H, W, Cin, K, R, S, stride, pad, dtype=F32, flags=0) -> ConvDesc:
-    return ConvDesc(N, H, W, Cin, K, R, S, stride, stride, pad, pad, dtype, flags)
+def conv_desc(N, H, W, Cin, K, R, S, stride, pad, dtype=F32, flags=0, pad_w=None) -> ConvDesc:
+    return ConvDesc(N, H, W, Cin, K, R, S, stride, stride, pad, pad if pad_w is None else pad_w, dtype, flags)
 
 
 def pool_desc(N, H, W, Cc, win, stride, pad, relu=True) -> PoolDesc:
@@ -200,6 +203,24 @@ def stanza_cast_f32_to_bf16(src, dst):
 
 def stanza_cast_bf16_to_f32(src, dst):
     _check(load().stanza_cast_bf16_to_f32(src.numel(), _ptr(src), _ptr(dst), _stream()), "stanza_cast_bf16_to_f32")
+
+
+def stanza_avgpool_fwd(d: PoolDesc, x, y, dtype=F32):
+    _check(load().stanza_avgpool_fwd(C.byref(d), dtype, _ptr(x), _ptr(y), _stream()), "stanza_avgpool_fwd")
+
+
+def stanza_avgpool_bwd(d: PoolDesc, dy, dx, dtype=F32):
+    _check(load().stanza_avgpool_bwd(C.byref(d), dtype, _ptr(dy), _ptr(dx), _stream()), "stanza_avgpool_bwd")
+
+
+def stanza_copy_channels(src, src_off: int, dst, dst_off: int, cols: int):
+    """Copy `cols` channels of every pixel: src[..., src_off:src_off+cols] -> dst[..., dst_off:dst_off+cols] (float32, C fastest)."""
+    assert src.is_cuda and dst.is_cuda and src.is_contiguous() and dst.is_contiguous() and src.dtype == dst.dtype == torch.float32
+    cs, cd = src.shape[-1], dst.shape[-1]
+    rows = src.numel() // cs
+    assert rows == dst.numel() // cd and src_off + cols <= cs and dst_off + cols <= cd
+    _check(load().stanza_copy2d(rows, cols, C.c_void_p(src.data_ptr() + 4 * src_off), cs, C.c_void_p(dst.data_ptr() + 4 * dst_off), cd, _stream()),
+           "stanza_copy2d")
 
 
 def stanza_bn_workspace_bytes(rows: int, channels: int, dtype=F32) -> int:

@@ -8,7 +8,7 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libstanza.so")
-SOURCES = ("conv_api.hip", "fc_api.hip", "misc_api.hip", "model_api.hip", "bn_api.hip")
+SOURCES = ("conv_api.hip", "fc_api.hip", "misc_api.hip", "model_api.hip", "bn_api.hip", "blocks_api.hip")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wno-unknown-warning-option", "-Wno-unused-command-line-argument"]

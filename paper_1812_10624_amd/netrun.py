@@ -37,19 +37,23 @@ class ConvWorker:
                 flags = (api.CONV_BIAS if op.get("bias", True) else 0) | (api.CONV_RELU if op["relu"] else 0)
                 low = dtype == api.BF16 and c % 8 == 0 and op["K"] % 8 == 0
                 self.f32_layer[i] = dtype == api.BF16 and not low
-                d = api.conv_desc(n, h, w, c, op["K"], op["R"], op["S"], op["stride"], op["pad"], api.BF16 if low else api.F32, flags)
+                d = api.conv_desc(n, h, w, c, op["K"], op["R"], op["S"], op["stride"], op["pad"], api.BF16 if low else api.F32, flags,
+                                  pad_w=op.get("pad_w"))
                 ho, wo = api.conv_out_hw(d)
                 self.shapes[op["dst"]] = (n, ho, wo, op["K"])
                 self.descs[i] = d
-            elif kind == "pool":
+            elif kind in ("pool", "avgpool"):
                 n, h, w, c = self.shapes[op["src"]]
-                d = api.pool_desc(n, h, w, c, op["win"], op["stride"], op["pad"], op["relu"])
+                d = api.pool_desc(n, h, w, c, op["win"], op["stride"], op["pad"], op.get("relu", False))
                 ho = (h + 2 * op["pad"] - op["win"]) // op["stride"] + 1
                 wo = (w + 2 * op["pad"] - op["win"]) // op["stride"] + 1
                 self.shapes[op["dst"]] = (n, ho, wo, c)
                 self.descs[i] = d
             elif kind == "bn":
                 self.shapes[op["dst"]] = self.shapes[op["src"]]
+            elif kind == "concat":
+                parts = [self.shapes[sname] for sname in op["srcs"]]
+                self.shapes[op["dst"]] = parts[0][:3] + (sum(p[3] for p in parts),)
             elif kind == "add_relu":
                 self.shapes[op["dst"]] = self.shapes[op["a"]]
             elif kind == "gap":
@@ -107,6 +111,14 @@ class ConvWorker:
                     api.stanza_conv_fwd(self.descs[i], self.buf[op["src"]], w, b, self.buf[op["dst"]], self.ws)
             elif kind == "pool":
                 api.stanza_pool_relu_fwd(self.descs[i], self.buf[op["src"]], self.buf[op["dst"]], self.argmax[op["dst"]], self.dtype)
+            elif kind == "avgpool":
+                api.stanza_avgpool_fwd(self.descs[i], self.buf[op["src"]], self.buf[op["dst"]])
+            elif kind == "concat":
+                at = 0
+                for sname in op["srcs"]:
+                    cs = self.shapes[sname][3]
+                    api.stanza_copy_channels(self.buf[sname], 0, self.buf[op["dst"]], at, cs)
+                    at += cs
             elif kind == "bn":
                 gamma, beta = self.params[op["name"]]
                 mean, istd = self.bn_stats[op["name"]]
@@ -169,6 +181,23 @@ class ConvWorker:
                         have[src] = dx
                     api.stanza_conv_bwd_data(dd, dy, y, wk, x_mask, dx, self.ws)
                     gated[src] = x_mask is not None
+            elif kind == "avgpool":
+                dx = self._grad_buffer(op["src"])
+                assert op["src"] not in have, "a pooling branch must be the last reader of its input in the op list"
+                api.stanza_avgpool_bwd(self.descs[i], have.pop(op["dst"]), dx)
+                have[op["src"]] = dx
+                gated[op["src"]] = False
+            elif kind == "concat":
+                wide = have.pop(op["dst"])
+                at = 0
+                for sname in op["srcs"]:
+                    cs = self.shapes[sname][3]
+                    part = self._grad_buffer(sname)
+                    assert sname not in have
+                    api.stanza_copy_channels(wide, at, part, 0, cs)
+                    have[sname] = part
+                    gated[sname] = False
+                    at += cs
             elif kind == "bn":
                 # the layer undoes its own ReLU from x, whether or not the incoming gradient is gated already
                 gamma, beta = self.params[op["name"]]

@@ -141,3 +141,19 @@ def test_dropout_errors(api):
     arr = (C.c_void_p * 2)(0x1000, 0x2000)
     need = plan.workspace_bytes()
     assert lib.stanza_fc_step(C.byref(plan.desc), p16, p16, arr, arr, arr, arr, p16, p16, None, p16, need, None) == -1
+
+
+def test_avgpool_and_copy_errors(api):
+    lib = api.load()
+    p16, p4, p2 = C.c_void_p(0x1000), C.c_void_p(0x1004), C.c_void_p(0x1002)
+    d = api.pool_desc(1, 8, 8, 4, 3, 1, 1, False)
+    assert lib.stanza_avgpool_fwd(C.byref(d), api.F32, None, p16, None) == -2
+    assert lib.stanza_avgpool_fwd(C.byref(d), api.BF16, p16, p16, None) == -4
+    assert lib.stanza_avgpool_bwd(C.byref(d), api.F32, p16, p4, None) == -3
+    d.pad_h = 3
+    assert lib.stanza_avgpool_fwd(C.byref(d), api.F32, p16, p16, None) == -1
+    assert lib.stanza_copy2d(0, 4, p16, 4, p16, 4, None) == -1
+    assert lib.stanza_copy2d(4, 8, p16, 4, p16, 8, None) == -1          # leading dimension shorter than a row
+    assert lib.stanza_copy2d(1 << 30, 4, p16, 4, p16, 4, None) == -1
+    assert lib.stanza_copy2d(4, 4, None, 4, p16, 4, None) == -2
+    assert lib.stanza_copy2d(4, 4, p2, 4, p16, 4, None) == -3

@@ -1,0 +1,195 @@
+"""The Inception pieces on the GPU against the CPU checker: average pool, channel-slice copies, 1xn / nx1 filters
+with per-axis padding, the whole layer-separated step of a small stack with one block of every kind, and the
+Inception-V3-shaped stack at its real layer shapes with a reduced batch."""
+import copy
+
+import numpy as np
+import pytest
+import torch
+
+import workloads as wl_mod
+from gpu_util import TOL_F32, dev, host, rel_err
+from oracle import ConvGeom, PoolGeom
+from oracle import network as onet
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def api():
+    from paper_1812_10624_amd import api as a
+    a.load()
+    assert torch.cuda.is_available()
+    return a
+
+
+@pytest.mark.parametrize("geom", [(2, 35, 35, 48, 3, 1, 1), (3, 17, 17, 7, 3, 1, 1), (2, 8, 8, 64, 3, 1, 1), (1, 9, 11, 4, 5, 3, 2),
+                                   (2, 12, 12, 8, 2, 2, 0), (1, 6, 7, 3, 3, 2, 1)])
+def test_avgpool(api, o32, geom):
+    n, h, w, c, win, stride, pad = geom
+    g = PoolGeom(n, h, w, c, win, stride, pad, False)
+    rng = wl_mod.rng_for(1, "avg", *geom)
+    x = rng.standard_normal((n, h, w, c), dtype=np.float32)
+    d = api.pool_desc(n, h, w, c, win, stride, pad, False)
+    y = torch.full((n, g.Ho, g.Wo, c), float("nan"), device="cuda:0")
+    api.stanza_avgpool_fwd(d, dev(x), y)
+    assert rel_err(host(y), o32.avgpool_fwd(g, x)) < TOL_F32
+    dy = rng.standard_normal((n, g.Ho, g.Wo, c), dtype=np.float32)
+    dx = torch.full((n, h, w, c), float("nan"), device="cuda:0")
+    api.stanza_avgpool_bwd(d, dev(dy), dx)
+    assert rel_err(host(dx), o32.avgpool_bwd(g, dy)) < TOL_F32
+
+
+@pytest.mark.parametrize("rows,cs,cd,cols,so,do", [(50, 16, 48, 16, 0, 32), (50, 48, 16, 16, 32, 0), (7, 5, 12, 3, 2, 9), (1000, 64, 288, 64, 0, 224),
+                                                    (33, 8, 20, 6, 2, 6), (5, 4, 4, 4, 0, 0)])
+def test_copy_channels(api, rows, cs, cd, cols, so, do):
+    rng = wl_mod.rng_for(2, "copy", rows, cs, cd)
+    src = rng.standard_normal((rows, cs), dtype=np.float32)
+    dst0 = rng.standard_normal((rows, cd), dtype=np.float32)
+    dst = dev(dst0)
+    api.stanza_copy_channels(dev(src), so, dst, do, cols)
+    ref = dst0.copy()
+    ref[:, do:do + cols] = src[:, so:so + cols]
+    np.testing.assert_array_equal(host(dst), ref)                   # byte work: bit-exact, nothing else touched
+
+
+ASYM = [(2, 17, 17, 16, 24, 1, 7, 0, 3), (2, 17, 17, 16, 24, 7, 1, 3, 0), (3, 8, 8, 32, 48, 1, 3, 0, 1), (3, 8, 8, 32, 48, 3, 1, 1, 0),
+        (1, 9, 12, 5, 6, 1, 7, 0, 3), (2, 13, 7, 12, 10, 7, 1, 3, 0)]
+
+
+@pytest.mark.parametrize("N,H,W,C,K,R,S,ph,pw", ASYM)
+def test_conv_one_by_n_filters(api, o32, N, H, W, C, K, R, S, ph, pw):
+    g = ConvGeom(N, H, W, C, K, R, S, 1, ph, pw)
+    rng = wl_mod.rng_for(3, "asym", N, H, W, C, K, R, S)
+    x = rng.standard_normal((N, H, W, C), dtype=np.float32)
+    w = rng.standard_normal((K, R, S, C), dtype=np.float32) * np.float32((2.0 / (R * S * C)) ** 0.5)
+    dy = rng.standard_normal((N, g.Ho, g.Wo, K), dtype=np.float32)
+    assert (g.Ho, g.Wo) == (H, W)
+    d = api.conv_desc(N, H, W, C, K, R, S, 1, ph, api.F32, 0, pad_w=pw)
+    ws = torch.empty(max(16, max(api.stanza_conv_workspace_bytes(d, i) for i in range(3))), dtype=torch.uint8, device="cuda:0")
+    y = torch.full((N, H, W, K), float("nan"), device="cuda:0")
+    api.stanza_conv_fwd(d, dev(x), dev(w), None, y, ws)
+    assert rel_err(host(y), o32.conv_fwd(g, x, w)) < TOL_F32
+    dx = torch.full((N, H, W, C), float("nan"), device="cuda:0")
+    api.stanza_conv_bwd_data(d, dev(dy), None, dev(w), None, dx, ws)
+    assert rel_err(host(dx), o32.conv_bwd_data(g, dy, w)) < TOL_F32
+    dw = torch.full((K, R, S, C), float("nan"), device="cuda:0")
+    api.stanza_conv_bwd_weight(d, dev(x), dev(dy), None, dw, None, ws)
+    assert rel_err(host(dw), o32.conv_bwd_weight(g, x, dy)[0]) < TOL_F32
+
+
+def _none_or(fn, t):
+    return None if t is None else fn(t)
+
+
+def test_mini_inception_step(api, o32):
+    """One block of every kind at a sixteenth of the widths: the whole layer-separated step."""
+    from paper_1812_10624_amd.netrun import Aggregator, ConvWorker, FcWorker
+    wl = wl_mod.get_workload("miniinception")
+    K, B, seed = wl.K, wl.B, 2
+    imgs = [wl_mod.gen_images(wl, seed, k, B) for k in range(K)]
+    labels = wl_mod.gen_labels(wl, seed, K * B)
+    cp = wl_mod.gen_conv_params(wl, seed)
+    fp = wl_mod.gen_fc_params(wl, seed)
+    cm = {n: (np.zeros_like(w), _none_or(np.zeros_like, b)) for n, (w, b) in cp.items()}
+    fm = [(np.zeros_like(w), np.zeros_like(b)) for w, b in fp]
+    cp_ref, cm_ref, fp_ref, fm_ref = (copy.deepcopy(a) for a in (cp, cm, fp, fm))
+    lr, mom, wd = 0.05, 0.9, 1e-4
+    ref = onet.split_step(o32, wl.ops, imgs, labels, cp_ref, cm_ref, fp_ref, fm_ref, lr, mom, wd, keep=True)
+    gpar = {n: (dev(w), _none_or(dev, b)) for n, (w, b) in cp.items()}
+    gcm = {n: (dev(w), _none_or(dev, b)) for n, (w, b) in cm.items()}
+    gfp = [(dev(w), dev(b)) for w, b in fp]
+    gfm = [(dev(w), dev(b)) for w, b in fm]
+    workers = [ConvWorker(wl.ops, wl.image, B, gpar) for _ in range(K)]
+    fcw = FcWorker(wl.fc_dims, K * B, gfp, gfm, lr, mom, wd)
+    feats = torch.empty((K * B, wl.fc_dims[0]), device="cuda:0")
+    for k, wk in enumerate(workers):
+        feats[k * B:(k + 1) * B].copy_(wk.forward(dev(imgs[k])).view(B, -1))
+    # every buffer of worker 0 along the way
+    for name, t in workers[0].buf.items():
+        assert rel_err(host(t), ref["bufs"][0][name]) < 2 * TOL_F32, name
+    assert rel_err(host(feats), ref["feats"]) < 2 * TOL_F32
+    dfeats = fcw.step(feats, dev(labels))
+    assert abs(float(host(fcw.loss)[0]) - ref["loss"]) < 1e-5 * max(1.0, abs(ref["loss"]))
+    assert rel_err(host(dfeats), ref["dfeats"]) < 5 * TOL_F32
+    dfeats.copy_(dev(ref["dfeats"]))
+    for k, wk in enumerate(workers):
+        wk.backward(dfeats[k * B:(k + 1) * B])
+        for nme in cp:
+            for i in range(2):
+                if cp[nme][i] is None:
+                    continue
+                # the chain is ~40 layers deep through normalisation over few rows: direction and size per tensor ...
+                a, b = host(wk.grads[nme][i]).ravel().astype(np.float64), ref["worker_grads"][k][nme][i].ravel().astype(np.float64)
+                cos = float(a @ b / (np.linalg.norm(a) * np.linalg.norm(b) + 1e-300))
+                assert cos > 0.9999 and abs(np.linalg.norm(a) / np.linalg.norm(b) - 1) < 1e-2, (k, nme, i, cos)
+    # ... and element-wise for the layers next to the output, where no rounding has been amplified yet
+    for nme in ("e0_1x1", "e0_1x1_bn", "e0_pool", "e0_d3b_bn"):
+        for i in range(2):
+            if cp[nme][i] is not None:
+                assert rel_err(host(workers[0].grads[nme][i]), ref["worker_grads"][0][nme][i]) < 10 * TOL_F32, (nme, i)
+    flat = wl_mod.flat_tensors
+    agg = Aggregator(flat(gpar), flat(gcm), [flat(wk.grads) for wk in workers])
+    agg.step(1.0, lr, mom, wd)
+    moved = 0
+    for nme in cp:
+        for i in range(2):
+            if cp[nme][i] is None:
+                continue
+            a, b = (host(gpar[nme][i]) - cp[nme][i]).ravel().astype(np.float64), (cp_ref[nme][i] - cp[nme][i]).ravel().astype(np.float64)
+            assert a @ b / (np.linalg.norm(a) * np.linalg.norm(b) + 1e-300) > 0.9999, (nme, i)
+            moved += 1
+    assert moved == 2 * sum(1 for op in wl.ops if op["op"] == "bn") + sum(1 for op in wl.ops if op["op"] == "conv")
+
+
+def test_inception3_real_shapes(api, o32):
+    """All 94 convolutions, normalisation layers, pooling branches and concatenations at 299 x 299, batch 2: every buffer
+    of the forward pass, then each normalised convolution's backward on the checker's own inputs for three blocks."""
+    from paper_1812_10624_amd.netrun import ConvWorker
+    wl = wl_mod.get_workload("inception3")
+    B = 2
+    img = wl_mod.gen_images(wl, 0, 0, B)
+    cp = wl_mod.gen_conv_params(wl, 0)
+    bufs = onet.conv_stack_forward(o32, wl.ops, img, cp)
+    gcp = {n: (dev(w), _none_or(dev, b)) for n, (w, b) in cp.items()}
+    wk = ConvWorker(wl.ops, wl.image, B, gcp)
+    feat = wk.forward(dev(img)).view(B, -1)
+    # end to end the roundings of ~45 normalised layers compound (statistics over 2 x 8 x 8 rows amplify them) ...
+    for name, t in wk.buf.items():
+        assert rel_err(host(t), bufs[name]) < 2e-2, name
+    assert rel_err(host(feat), bufs["feat"].reshape(B, -1)) < 2e-2
+    # ... so each layer is also run on the checker's own input for that layer and held to the bound by itself
+    worst = 0.0
+    ws = wk.ws
+    for i, op in enumerate(wl.ops):
+        kind = op["op"]
+        if kind not in ("conv", "bn", "avgpool", "pool"):
+            continue
+        xin = dev(bufs[op["src"]])
+        out = torch.full(bufs[op["dst"]].shape, float("nan"), device="cuda:0")
+        if kind == "conv":
+            api.stanza_conv_fwd(wk.descs[i], xin, gcp[op["name"]][0], None, out, ws)
+        elif kind == "bn":
+            c = out.shape[-1]
+            m, s_ = torch.empty(c, device="cuda:0"), torch.empty(c, device="cuda:0")
+            api.stanza_bn_fwd(xin, gcp[op["name"]][0], gcp[op["name"]][1], out, m, s_, wk.bn_ws, op["eps"], op["relu"])
+        elif kind == "avgpool":
+            api.stanza_avgpool_fwd(wk.descs[i], xin, out)
+        else:
+            am = torch.empty(out.shape, dtype=torch.uint8, device="cuda:0")
+            api.stanza_pool_relu_fwd(wk.descs[i], xin, out, am)
+        e = rel_err(host(out), bufs[op["dst"]])
+        worst = max(worst, e)
+        assert e < TOL_F32, (op.get("name", op["dst"]), e)
+    # whole backward chain: direction and size
+    dfeat = wl_mod.rng_for(5, "dfeat", "inc").standard_normal(feat.shape, dtype=np.float32) / np.float32(B)
+    pg, _ = onet.conv_stack_backward(o32, wl.ops, bufs, cp, dfeat)
+    wk.backward(dev(dfeat))
+    for n in cp:
+        for which in range(2):
+            if cp[n][which] is None:
+                continue
+            a, b = host(wk.grads[n][which]).ravel().astype(np.float64), pg[n][which].ravel().astype(np.float64)
+            cos = float(a @ b / (np.linalg.norm(a) * np.linalg.norm(b) + 1e-300))
+            assert cos > 0.999, (n, which, cos)
+    print(f"inception3: worst layer-wise forward E={worst:.2e}")
