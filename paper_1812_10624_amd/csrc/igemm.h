@@ -516,14 +516,28 @@ __global__ __launch_bounds__(NTHREADS, (BM >= 256 ? 3 : (VECA && VECB) ? 4 : 2))
         // reduction row that lane half lk multiplies in k-step ks: pairs (8g+j, 8g+4+j) when a row-major operand fixes
         // the order, (2ks, 2ks+1) otherwise
         auto krow = [&](int ks) -> int { return (A_ROWK || B_ROWK) ? (ks >> 2) * 8 + lk * 4 + (ks & 3) : ks * 2 + lk; };
+        // A reduction-major operand gives lane lrow the TM (TN) CONSECUTIVE rows TM*lrow + i of its wavefront tile, one per
+        // MFMA tile i, so that one 8-byte read serves two tiles; the epilogue maps accumulators back the same way.
         auto read_scalar = [&](int ks, int slot) {
             if (!A_ROWK) {
+                const float *src = &AsBuf(buf)[krow(ks) * LDA + wave_m * WTM + TM * lrow];
+                if constexpr (TM == 2) {
+                    const float2 v = *reinterpret_cast<const float2 *>(src);
+                    a1[slot][0] = v.x; a1[slot][1] = v.y;
+                } else {
 #pragma unroll
-                for (int i = 0; i < TM; ++i) a1[slot][i] = AsBuf(buf)[krow(ks) * LDA + wave_m * WTM + i * 32 + lrow];
+                    for (int i = 0; i < TM; ++i) a1[slot][i] = src[i];
+                }
             }
             if (!B_ROWK) {
+                const float *src = &BsBuf(buf)[krow(ks) * LDB + wave_n * WTN + TN * lrow];
+                if constexpr (TN == 2) {
+                    const float2 v = *reinterpret_cast<const float2 *>(src);
+                    b1[slot][0] = v.x; b1[slot][1] = v.y;
+                } else {
 #pragma unroll
-                for (int j = 0; j < TN; ++j) b1[slot][j] = BsBuf(buf)[krow(ks) * LDB + wave_n * WTN + j * 32 + lrow];
+                    for (int j = 0; j < TN; ++j) b1[slot][j] = src[j];
+                }
             }
         };
         read_group(0, 0);
@@ -566,6 +580,10 @@ __global__ __launch_bounds__(NTHREADS, (BM >= 256 ? 3 : (VECA && VECB) ? 4 : 2))
 
     // ------------------------------------------------------------------ epilogue
     // Accumulator register r of lane l holds row 8*(r/4) + 4*(l/32) + r%4, column l%32 of its 32x32 tile.
+    // With a reduction-major operand, MFMA row (column) index x of tile i stands for row (column) TM*x + i (TN*x + i) of the
+    // wavefront tile, see read_scalar.
+    auto wrow = [&](int i, int x) -> int { return A_ROWK ? i * 32 + x : TM * x + i; };
+    auto wcol = [&](int j, int x) -> int { return B_ROWK ? j * 32 + x : TN * x + j; };
     const size_t split_off = (MODE == MODE_BWD_WEIGHT && !(p.flags & EPI_SGD)) ? (size_t)split * p.M * p.Nn : 0;
     if (MODE != MODE_BWD_WEIGHT && sliced) {
         // raw accumulators of this slice, tile-local [BM][BN]; the fix-up kernel adds the slices and applies the epilogue
@@ -576,7 +594,7 @@ __global__ __launch_bounds__(NTHREADS, (BM >= 256 ? 3 : (VECA && VECB) ? 4 : 2))
             for (int i = 0; i < TM; ++i)
 #pragma unroll
                 for (int r = 0; r < 16; ++r)
-                    dst[(wave_m * WTM + i * 32 + 8 * (r >> 2) + 4 * lk + (r & 3)) * BN + wave_n * WTN + j * 32 + lrow] = acc[i][j][r];
+                    dst[(wave_m * WTM + wrow(i, 8 * (r >> 2) + 4 * lk + (r & 3))) * BN + wave_n * WTN + wcol(j, lrow)] = acc[i][j][r];
         return;
     }
     // element offset of (row, col) in the output: dense rows, or the scattered pixels of a stride class
@@ -605,7 +623,7 @@ __global__ __launch_bounds__(NTHREADS, (BM >= 256 ? 3 : (VECA && VECB) ? 4 : 2))
                 for (int j = 0; j < TN; ++j)
 #pragma unroll
                     for (int r = 0; r < 16; ++r)
-                        Cs[(8 * (r >> 2) + 4 * lk + (r & 3)) * BN + wave_n * WTN + j * 32 + lrow] = acc[i][j][r];
+                        Cs[(8 * (r >> 2) + 4 * lk + (r & 3)) * BN + wave_n * WTN + wcol(j, lrow)] = acc[i][j][r];
             }
             __syncthreads();
 #pragma unroll
@@ -635,7 +653,7 @@ __global__ __launch_bounds__(NTHREADS, (BM >= 256 ? 3 : (VECA && VECB) ? 4 : 2))
     }
 #pragma unroll
     for (int j = 0; j < TN; ++j) {
-        const int col = n0 + wave_n * WTN + j * 32 + lrow;
+        const int col = n0 + wave_n * WTN + wcol(j, lrow);
         if (col >= p.Nn) continue;
         float bias = 0.f;
         if (MODE == MODE_FWD && (p.flags & EPI_BIAS)) bias = p.bias[col];
@@ -643,7 +661,7 @@ __global__ __launch_bounds__(NTHREADS, (BM >= 256 ? 3 : (VECA && VECB) ? 4 : 2))
         for (int i = 0; i < TM; ++i) {
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
-                const int row = m0 + wave_m * WTM + i * 32 + 8 * (r >> 2) + 4 * lk + (r & 3);
+                const int row = m0 + wave_m * WTM + wrow(i, 8 * (r >> 2) + 4 * lk + (r & 3));
                 if (row >= p.M) continue;
                 const size_t o = out_index(row, col);
                 float v = acc[i][j][r];
