@@ -86,6 +86,28 @@ def test_bn_forward_backward(api, o32, rows, c, relu):
         np.testing.assert_array_equal(host(y) > 0, _gate32(x, gamma, beta, host(mean), host(istd)))
 
 
+def test_bn_largest_layer_of_the_residual_network(api, o32):
+    """The first normalisation layer of the ResNet-50-shaped stack at the paper's per-worker batch (64 x 112 x 112 pixels,
+    64 channels: 1024 row slabs), every element against the checker."""
+    rows, c = 64 * 112 * 112, 64
+    x, gamma, beta, dy = _case(7, rows, c)
+    y_ref, mean_ref, istd_ref = o32.bn_fwd(x, gamma, beta, 1e-5, True)
+    xd = dev(x)
+    y = torch.empty((rows, c), device="cuda:0")
+    mean, istd = torch.empty(c, device="cuda:0"), torch.empty(c, device="cuda:0")
+    ws = torch.empty(api.stanza_bn_workspace_bytes(rows, c), dtype=torch.uint8, device="cuda:0")
+    api.stanza_bn_fwd(xd, dev(gamma), dev(beta), y, mean, istd, ws, 1e-5, True)
+    assert rel_err(host(mean), mean_ref) < 1e-5 and rel_err(host(istd), istd_ref) < TOL_F32
+    assert rel_err(host(y), y_ref) < TOL_F32
+    gate = _gate32(x, gamma, beta, mean_ref, istd_ref)
+    dx_ref, dg_ref, db_ref = o32.bn_bwd(x, np.ascontiguousarray(np.where(gate, dy, np.float32(0))), gamma, mean_ref, istd_ref)
+    dx = torch.empty((rows, c), device="cuda:0")
+    dg, db = torch.empty(c, device="cuda:0"), torch.empty(c, device="cuda:0")
+    api.stanza_bn_bwd(xd, dev(dy), dev(gamma), dev(beta), dev(mean_ref), dev(istd_ref), dx, dg, db, ws, True)
+    assert rel_err(host(dg), dg_ref) < TOL_F32 and rel_err(host(db), db_ref) < TOL_F32
+    assert rel_err(host(dx), dx_ref) < TOL_F32
+
+
 def test_bn_constant_and_offset_columns(api, o32):
     """A constant channel has zero variance (istd = 1/sqrt(eps), output beta); a channel with a large offset keeps its
     variance (the sums are taken about a value inside the data's range)."""

@@ -22,7 +22,7 @@ def api():
     return a
 
 
-@pytest.mark.parametrize("numel", [1, 3, 4, 5, 1023, 4096, 100003])
+@pytest.mark.parametrize("numel", [1, 3, 4, 5, 1023, 4096, 100003, 512 * 4096])      # the last: a VGG-16 hidden layer at n = 512
 @pytest.mark.parametrize("p,seed,stream", [(0.5, 0, 0), (0.1, 0x1234567890ABCDEF, (7 << 8) | 1), (0.9, 2 ** 64 - 1, 2 ** 56 + 5), (0.0, 5, 5)])
 def test_dropout_mask_and_scale(api, numel, p, seed, stream):
     x = wl_mod.rng_for(1, "drop", numel).standard_normal(numel, dtype=np.float32)
