@@ -324,27 +324,61 @@ int launch_igemm_bf16(int mode, GemmParams &p, int splits, hipStream_t st)
 }
 
 // ------------------------------------------------------------------ fixed-order reductions
-// Threads [0, numel) reduce the first segment, threads [numel, numel + numel2) the second (bias gradient).
-__global__ void split_reduce_kernel(const float *__restrict__ partial, int splits, size_t numel, float *__restrict__ out,
-                                    const float *__restrict__ partial2, size_t numel2, float *__restrict__ out2)
+// out[i] = sum over slices of partial[slice][i]; likewise the second segment (bias gradient).  Output i is shared by LANES
+// threads: thread l adds the slices l, l + LANES, ... in ascending order (four loads in flight) and the LANES sums are added in
+// lane order through LDS.  A short output with hundreds of slices (a 1x1 filter gradient) would otherwise be one
+// long dependent chain per thread on a handful of workgroups.
+template <int LANES>
+__global__ __launch_bounds__(256) void split_reduce_kernel(const float *__restrict__ partial, int splits, size_t numel, float *__restrict__ out,
+                                                           const float *__restrict__ partial2, size_t numel2, float *__restrict__ out2)
 {
-    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < numel) {
-        float s = 0.f;
-        for (int k = 0; k < splits; ++k) s += partial[(size_t)k * numel + i];
-        out[i] = s;
-    } else if ((i -= numel) < numel2) {
-        float s = 0.f;
-        for (int k = 0; k < splits; ++k) s += partial2[(size_t)k * numel2 + i];
-        out2[i] = s;
+    constexpr int OUTS = 256 / LANES;          // outputs per workgroup (consecutive: coalesced rows of every slice)
+    __shared__ float red[LANES][OUTS];
+    const int ol = threadIdx.x % OUTS, lane = threadIdx.x / OUTS;
+    size_t i = (size_t)blockIdx.x * OUTS + ol;
+    const float *src = partial;
+    float *dst = out;
+    size_t n = numel;
+    bool live = true;
+    if (i >= numel) {
+        i -= numel;
+        src = partial2; dst = out2; n = numel2;
+        live = i < numel2;
+    }
+    float s = 0.f;
+    if (live) {
+        int k = lane;
+        for (; k + 3 * LANES < splits; k += 4 * LANES) {
+            const float v0 = src[(size_t)k * n + i], v1 = src[(size_t)(k + LANES) * n + i];
+            const float v2 = src[(size_t)(k + 2 * LANES) * n + i], v3 = src[(size_t)(k + 3 * LANES) * n + i];
+            s += v0; s += v1; s += v2; s += v3;
+        }
+        for (; k < splits; k += LANES) s += src[(size_t)k * n + i];
+    }
+    if (LANES == 1) {
+        if (live) dst[i] = s;
+        return;
+    }
+    red[lane][ol] = s;
+    __syncthreads();
+    if (lane == 0 && live) {
+        for (int l = 1; l < LANES; ++l) s += red[l][ol];
+        dst[i] = s;
     }
 }
 
 int launch_split_reduce(const float *partial, int splits, size_t numel, float *out, const float *partial2, size_t numel2, float *out2,
                         hipStream_t st)
 {
-    hipLaunchKernelGGL(split_reduce_kernel, dim3((unsigned)cdiv64(numel + numel2, 256)), dim3(256), 0, st, partial, splits, numel, out,
-                       partial2, numel2, out2);
+    // enough threads to fill the GPU: more lanes per output the shorter the output and the more slices there are
+    const size_t total = numel + numel2;
+    const int lanes = (splits >= 64 && total < (size_t(1) << 18)) ? 16 : (splits >= 16 && total < (size_t(1) << 20)) ? 4 : 1;
+    if (lanes == 16)
+        hipLaunchKernelGGL(split_reduce_kernel<16>, dim3((unsigned)cdiv64(total, 16)), dim3(256), 0, st, partial, splits, numel, out, partial2, numel2, out2);
+    else if (lanes == 4)
+        hipLaunchKernelGGL(split_reduce_kernel<4>, dim3((unsigned)cdiv64(total, 64)), dim3(256), 0, st, partial, splits, numel, out, partial2, numel2, out2);
+    else
+        hipLaunchKernelGGL(split_reduce_kernel<1>, dim3((unsigned)cdiv64(total, 256)), dim3(256), 0, st, partial, splits, numel, out, partial2, numel2, out2);
     return launch_status();
 }
 
