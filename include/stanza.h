@@ -91,6 +91,10 @@ typedef struct {
     float dropout_p;          /* 0: none; otherwise every hidden layer's ReLU output passes through stanza_dropout with */
     uint64_t dropout_seed;    /* this seed and stream_id = (dropout_step << 8) | index of the layer (0-based), so that */
     uint64_t dropout_step;    /* layers and iterations draw different masks; dropout_step < 2^56 */
+    int32_t compute_dtype;    /* STANZA_F32, or STANZA_BF16: the hidden layers' GEMMs read bfloat16 copies of the features, */
+                              /* activations, gradients and weights (products accumulate in float32); the last layer, the */
+                              /* loss, all parameters, momentum buffers, gradients written out and dfeats stay float32. */
+                              /* Needs every width but the last to be a multiple of 8; not combined with dropout. */
 } stanza_fc_desc;
 
 const char *stanza_strerror(int status);

@@ -52,7 +52,7 @@ class ModelParams(C.Structure):
 class FcDesc(C.Structure):
     _fields_ = [("n_layers", C.c_int32), ("host_dims", C.POINTER(C.c_int32)), ("n_samples", C.c_int32),
                 ("lr", C.c_float), ("momentum", C.c_float), ("weight_decay", C.c_float),
-                ("dropout_p", C.c_float), ("dropout_seed", C.c_uint64), ("dropout_step", C.c_uint64)]
+                ("dropout_p", C.c_float), ("dropout_seed", C.c_uint64), ("dropout_step", C.c_uint64), ("compute_dtype", C.c_int32)]
 
 
 _lib = None
@@ -246,9 +246,10 @@ class FcPlan:
     """Host-side descriptor of an FC stack plus its keep-alive arrays."""
 
     def __init__(self, dims: Sequence[int], n_samples: int, lr: float, momentum: float, weight_decay: float,
-                 dropout_p: float = 0.0, dropout_seed: int = 0, dropout_step: int = 0):
+                 dropout_p: float = 0.0, dropout_seed: int = 0, dropout_step: int = 0, compute_dtype: int = F32):
         self.dims = (C.c_int32 * len(dims))(*dims)
-        self.desc = FcDesc(len(dims) - 1, self.dims, n_samples, lr, momentum, weight_decay, dropout_p, dropout_seed, dropout_step)
+        self.desc = FcDesc(len(dims) - 1, self.dims, n_samples, lr, momentum, weight_decay, dropout_p, dropout_seed, dropout_step,
+                           compute_dtype)
 
     def workspace_bytes(self) -> int:
         return int(load().stanza_fc_workspace_bytes(C.byref(self.desc)))

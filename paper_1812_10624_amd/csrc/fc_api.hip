@@ -123,6 +123,29 @@ __global__ __launch_bounds__(256) void scale_kernel(size_t numel, float scale, f
     }
 }
 
+// Momentum-SGD update from a gradient in memory (the bf16 hidden layers: their filter-gradient kernel has no fused update).
+__global__ __launch_bounds__(256) void sgd_update_kernel(size_t numel, float *__restrict__ w, float *__restrict__ v, const float *__restrict__ g,
+                                                         float lr, float mom, float wd)
+{
+    const size_t i0 = ((size_t)blockIdx.x * 256 + threadIdx.x) * 4;
+    if (i0 + 4 <= numel) {
+        float4 ww = *reinterpret_cast<float4 *>(w + i0), vv = *reinterpret_cast<float4 *>(v + i0);
+        const float4 gg = *reinterpret_cast<const float4 *>(g + i0);
+        vv.x = mom * vv.x + (gg.x + wd * ww.x); ww.x -= lr * vv.x;
+        vv.y = mom * vv.y + (gg.y + wd * ww.y); ww.y -= lr * vv.y;
+        vv.z = mom * vv.z + (gg.z + wd * ww.z); ww.z -= lr * vv.z;
+        vv.w = mom * vv.w + (gg.w + wd * ww.w); ww.w -= lr * vv.w;
+        *reinterpret_cast<float4 *>(v + i0) = vv;
+        *reinterpret_cast<float4 *>(w + i0) = ww;
+    } else {
+        for (size_t i = i0; i < numel; ++i) {
+            const float vel = mom * v[i] + (g[i] + wd * w[i]);
+            v[i] = vel;
+            w[i] -= lr * vel;
+        }
+    }
+}
+
 static bool dropout_valid(float p) { return p >= 0.f && p < 1.f; }
 static uint32_t dropout_threshold(float p) { return (uint32_t)((double)p * 4294967296.0); }
 static PhiloxKey dropout_key(uint64_t seed, uint64_t stream_id)
@@ -137,8 +160,22 @@ struct FcLayout {
     size_t db_off;        // column-sum scratch: colsum_blocks(n) * max_width
     size_t partial_off;   // reduction-slice sums of the forward / input-gradient GEMMs that are cut (largest of them)
     size_t partial_floats;
+    // bf16 hidden layers (compute_dtype == STANZA_BF16), offsets in floats like the rest:
+    size_t a16_off[32];   // bf16 A_l, l = 0 .. L-1 (n * dims[l] halves)
+    size_t w16_off[32];   // bf16 copy of W_l, l = 1 .. L-1
+    size_t dz16_off[2];   // two bf16 gradient buffers of n * max_width halves
+    size_t dfeats16_off;  // bf16 gradient of the features before it is widened
+    size_t dw_off;        // float32 weight gradient of one hidden layer (the largest)
+    size_t dbh_off;       // float32 bias gradient of one hidden layer
+    size_t wgrad_off;     // workspace of the bf16 filter-gradient calls
+    size_t wgrad_bytes;
     size_t floats;
 };
+
+static stanza_conv_desc fc_conv_desc(int n, int in, int out, int dtype, uint32_t flags)
+{
+    return stanza_conv_desc{n, 1, 1, in, out, 1, 1, 1, 1, 0, 0, dtype, flags};
+}
 
 static int fc_layout(const stanza_fc_desc *d, FcLayout *lay)
 {
@@ -167,6 +204,33 @@ static int fc_layout(const stanza_fc_desc *d, FcLayout *lay)
         pf = max(pf, igemm_partial_floats(MODE_BWD_DATA, d->n_samples, d->host_dims[l - 1], d->host_dims[l]));
     }
     lay->partial_off = off; lay->partial_floats = pf; off += round256(pf * 4) / 4;
+    if (d->compute_dtype == STANZA_BF16) {
+        const int L = d->n_layers, n = d->n_samples;
+        size_t dwf = 0;
+        int maxh = 0;
+        lay->wgrad_bytes = 0;
+        for (int l = 0; l < L; ++l) {
+            if (d->host_dims[l] % 8) return STANZA_EUNSUPPORTED;
+            lay->a16_off[l] = off; off += round256((size_t)n * d->host_dims[l] * 2) / 4;
+        }
+        for (int l = 1; l < L; ++l) {
+            const int in = d->host_dims[l - 1], out = d->host_dims[l];
+            lay->w16_off[l] = off; off += round256((size_t)out * in * 2) / 4;
+            dwf = max(dwf, (size_t)out * in);
+            maxh = max(maxh, max(in, out));
+            const stanza_conv_desc cd = fc_conv_desc(n, in, out, STANZA_BF16, STANZA_CONV_BIAS);
+            lay->wgrad_bytes = max(lay->wgrad_bytes, stanza_conv_workspace_bytes(&cd, 2));
+        }
+        const size_t dz16f = round256((size_t)n * max(maxh, 8) * 2) / 4;
+        lay->dz16_off[0] = off; off += dz16f;
+        lay->dz16_off[1] = off; off += dz16f;
+        lay->dfeats16_off = off; off += round256((size_t)n * d->host_dims[0] * 2) / 4;
+        lay->dw_off = off; off += round256(dwf * 4) / 4;
+        lay->dbh_off = off; off += round256((size_t)max(maxh, 8) * 4) / 4;
+        lay->wgrad_off = off; off += round256(lay->wgrad_bytes) / 4;
+    } else if (d->compute_dtype != STANZA_F32) {
+        return STANZA_EUNSUPPORTED;
+    }
     lay->floats = off;
     return STANZA_OK;
 }
@@ -209,13 +273,26 @@ static int fc_run(const stanza_fc_desc *desc, int n_global, const float *feats, 
     }
     hipStream_t st = (hipStream_t)stream;
     float *base = (float *)ws;
+    const bool half = desc->compute_dtype == STANZA_BF16;   // hidden layers in bf16, the last layer and the loss in float32
+    if (half && desc->dropout_p > 0.f) return STANZA_EUNSUPPORTED;
     const bool drop = desc->dropout_p > 0.f;
     const uint32_t drop_thr = dropout_threshold(desc->dropout_p);
     const float drop_scale = 1.f / (1.f - desc->dropout_p);
     auto act = [&](int l) -> const float * { return l == 0 ? feats : base + lay.act_off[l]; };
 
     // forward
-    for (int l = 1; l <= L; ++l) {
+    auto a16 = [&](int l) -> void * { return base + lay.a16_off[l]; };
+    auto w16 = [&](int l) -> void * { return base + lay.w16_off[l]; };
+    if (half) {
+        if ((rc = stanza_cast_f32_to_bf16((int64_t)n * dims[0], feats, a16(0), stream))) return rc;
+        for (int l = 1; l < L; ++l) {
+            const stanza_conv_desc cd = fc_conv_desc(n, dims[l - 1], dims[l], STANZA_BF16, STANZA_CONV_BIAS | STANZA_CONV_RELU);
+            if ((rc = stanza_cast_f32_to_bf16((int64_t)dims[l] * dims[l - 1], host_W[l - 1], w16(l), stream))) return rc;   // this step's copy
+            if ((rc = stanza_conv_fwd(&cd, a16(l - 1), w16(l), host_b[l - 1], a16(l), nullptr, 0, stream))) return rc;
+        }
+        if (L > 1 && (rc = stanza_cast_bf16_to_f32((int64_t)n * dims[L - 1], a16(L - 1), base + lay.act_off[L - 1], stream))) return rc;
+    }
+    for (int l = half ? L : 1; l <= L; ++l) {
         GemmParams p{};
         p.g = fc_geo(n, dims[l - 1], dims[l]);
         p.a = act(l - 1);
@@ -243,6 +320,27 @@ static int fc_run(const stanza_fc_desc *desc, int n_global, const float *feats, 
     const int dbb = colsum_blocks(n);
     for (int l = L; l >= 1; --l) {
         const int in = dims[l - 1], out = dims[l];
+        if (half && l < L) {
+            // hidden layer in bf16: dz arrives as float32 from the last layer (l == L-1) or as bf16 from the layer above
+            void *dz16 = base + lay.dz16_off[(L - 1 - l) & 1], *dz16_next = base + lay.dz16_off[(L - l) & 1];
+            if (l == L - 1 && (rc = stanza_cast_f32_to_bf16((int64_t)n * out, dz, dz16, stream))) return rc;
+            const stanza_conv_desc cd = fc_conv_desc(n, in, out, STANZA_BF16, STANZA_CONV_BIAS);
+            void *dx16 = l == 1 ? (void *)(base + lay.dfeats16_off) : dz16_next;
+            if ((rc = stanza_conv_bwd_data(&cd, dz16, nullptr, w16(l), l == 1 ? nullptr : a16(l - 1), dx16, nullptr, 0, stream))) return rc;
+            if (l == 1 && (rc = stanza_cast_bf16_to_f32((int64_t)n * in, dx16, dfeats, stream))) return rc;
+            float *dw = fused ? base + lay.dw_off : host_gW[l - 1];
+            float *db = fused ? base + lay.dbh_off : host_gb[l - 1];
+            if ((rc = stanza_conv_bwd_weight(&cd, a16(l - 1), dz16, nullptr, dw, db, base + lay.wgrad_off, lay.wgrad_bytes, stream))) return rc;
+            if (fused) {
+                const size_t nw = (size_t)out * in;
+                hipLaunchKernelGGL(sgd_update_kernel, dim3((unsigned)cdiv64(cdiv64(nw, 4), 256)), dim3(256), 0, st, nw, host_W[l - 1], host_vW[l - 1],
+                                   (const float *)dw, desc->lr, desc->momentum, desc->weight_decay);
+                hipLaunchKernelGGL(sgd_update_kernel, dim3((unsigned)cdiv64(cdiv64(out, 4), 256)), dim3(256), 0, st, (size_t)out, host_b[l - 1], host_vb[l - 1],
+                                   (const float *)db, desc->lr, desc->momentum, desc->weight_decay);
+                if ((rc = launch_status())) return rc;
+            }
+            continue;
+        }
         {   // gradient of the layer input, with the weights as they still are
             GemmParams p{};
             p.g = fc_geo(n, in, out);

@@ -235,12 +235,12 @@ class ConvWorker:
 class FcWorker:
     """The FC worker: owns the FC parameters and momentum buffers and runs stanza_fc_step."""
 
-    def __init__(self, dims, n_samples, fc_params, fc_mom, lr, momentum, weight_decay, device="cuda:0", dropout=None):
+    def __init__(self, dims, n_samples, fc_params, fc_mom, lr, momentum, weight_decay, device="cuda:0", dropout=None, dtype=api.F32):
         """dropout = (p, seed): seeded dropout after every hidden layer; the iteration counter that separates the
         masks of successive steps is kept here (a captured HIP graph replays the step it was captured with)."""
         self.dev = torch.device(device)
         p, seed = dropout if dropout is not None else (0.0, 0)
-        self.plan = api.FcPlan(dims, n_samples, lr, momentum, weight_decay, p, seed, 0)
+        self.plan = api.FcPlan(dims, n_samples, lr, momentum, weight_decay, p, seed, 0, dtype)
         self.W = [w for w, _ in fc_params]
         self.b = [b for _, b in fc_params]
         self.vW = [w for w, _ in fc_mom]

@@ -5,7 +5,7 @@ import pytest
 import torch
 
 import workloads as wl_mod
-from gpu_util import TOL_BF16, host, rel_err
+from gpu_util import TOL_BF16, dev, host, rel_err
 from oracle import ConvGeom, PoolGeom
 
 pytestmark = pytest.mark.gpu
@@ -201,3 +201,42 @@ def test_conv_worker_bf16_stack(api, o32):
             cos = float(got @ want / (np.linalg.norm(got) * np.linalg.norm(want)))
             assert cos > 0.97, (n, which, cos)
             assert abs(np.linalg.norm(got) / np.linalg.norm(want) - 1) < 0.1, (n, which)
+
+
+@pytest.mark.parametrize("dims,n", [([256, 128, 64, 10], 64), ([512, 264, 10], 40), ([64, 10], 16)])
+def test_fc_worker_with_bf16_hidden_layers(api, o32, dims, n):
+    """Hidden FC layers computed from bfloat16 copies of features, activations, gradients and weights (float32 sums), last
+    layer, loss, parameters and momentum in float32: against the float32 checker on the same (bf16-representable) features."""
+    import copy
+    from oracle import network as onet
+    from paper_1812_10624_amd.netrun import FcWorker
+    rng = wl_mod.rng_for(9, "fc16", *dims)
+    feats = wl_mod.round_bf16(np.abs(rng.standard_normal((n, dims[0]), dtype=np.float32)))
+    labels = rng.integers(0, dims[-1], size=n, dtype=np.int32)
+    # Biases of +-1 against pre-activation spreads of 0.15 keep every hidden unit well away from zero: which units a ReLU passes
+    # is then the same in bfloat16 and in float32 arithmetic, and the comparison is about the arithmetic, not about ties
+    # (a unit that flips for one of a few dozen samples moves a whole row of its layer's weight gradient).
+    fp = [((rng.standard_normal((o, i), dtype=np.float32) * np.float32(0.15 / i ** 0.5)),
+           (rng.choice([-1.0, 1.0], size=o) + rng.standard_normal(o) * 0.05).astype(np.float32)) for i, o in zip(dims[:-1], dims[1:])]
+    fm = [(np.zeros_like(w), np.zeros_like(b)) for w, b in fp]
+    fp_ref, fm_ref = copy.deepcopy(fp), copy.deepcopy(fm)
+    ref = onet.fc_step(o32, feats, labels, fp_ref, fm_ref, 0.05, 0.9, 1e-4)
+    for h in ref["acts"][1:-1]:
+        z_pos = h[h > 0]
+        assert 0.2 < (h > 0).mean() < 0.8 and z_pos.min() > 0.05          # both kinds of unit, none near the kink
+    gfp = [(dev(w), dev(b)) for w, b in fp]
+    gfm = [(dev(w), dev(b)) for w, b in fm]
+    fcw = FcWorker(dims, n, gfp, gfm, 0.05, 0.9, 1e-4, dtype=api.BF16)
+    dfeats = fcw.step(dev(feats), dev(labels))
+    assert abs(float(host(fcw.loss)[0]) - ref["loss"]) < 2e-2 * max(1.0, abs(ref["loss"]))
+    # four to six bfloat16 roundings lie between the features and each of these results (activations forward, gradients
+    # backward, the weights' copies): chained results are held to five times the single-operation bound, as in float32
+    chain = 5 * TOL_BF16
+    assert rel_err(host(dfeats), ref["dfeats"]) < chain
+    for li in range(len(fp)):
+        for i in range(2):
+            assert rel_err(host(gfm[li][i]), fm_ref[li][i]) < chain, (li, i)          # momentum after one step = the gradient
+            assert rel_err(host(gfp[li][i]) - fp[li][i], fp_ref[li][i] - fp[li][i]) < chain, (li, i)
+            a, b = host(gfm[li][i]).ravel().astype(np.float64), fm_ref[li][i].ravel().astype(np.float64)
+            assert a @ b / (np.linalg.norm(a) * np.linalg.norm(b)) > 0.9995 and abs(np.linalg.norm(a) / np.linalg.norm(b) - 1) < 5e-3, (li, i)
+    assert (host(fcw.pred) == ref["pred"]).mean() > 0.9
