@@ -17,8 +17,9 @@ class ConvWorker:
     backward pass from the gradient of those activations to per-layer filter/bias gradients.
 
     dtype=api.BF16 keeps activations, activation gradients and a per-step copy of the filters in bfloat16
-    (master filters, filter/bias gradients, images, features and feature gradients stay float32); a conv
-    whose channel counts are not multiples of 8 (the first layer, C = 3) runs in float32 between casts."""
+    (master filters, filter/bias gradients, images, features and feature gradients stay float32); the image
+    layer (C = 3) runs with its channels zero-padded to 8; any other conv whose channel counts are not multiples of 8 runs in
+    float32 between casts."""
 
     def __init__(self, ops: List[dict], image_shape, batch: int, params: Dict[str, tuple], device="cuda:0", dtype=api.F32):
         self.ops = ops
@@ -30,11 +31,18 @@ class ConvWorker:
         self.producer = {}
         self.descs = {}
         self.f32_layer = {}                       # op index -> True when a conv runs in float32 inside a bf16 stack
+        self.padded = {}                          # op index -> true channel count of an image layer run with padded channels
         for i, op in enumerate(ops):
             kind = op["op"]
             if kind == "conv":
                 n, h, w, c = self.shapes[op["src"]]
                 flags = (api.CONV_BIAS if op.get("bias", True) else 0) | (api.CONV_RELU if op["relu"] else 0)
+                # the image layer of a bf16 stack (3 channels): channels padded with zeros to a multiple of 8, so that it runs
+                # through the bf16 kernels like every other layer instead of in float32 between casts of its output
+                pad_c = dtype == api.BF16 and op["src"] == "x0" and c % 8 != 0 and op["K"] % 8 == 0
+                if pad_c:
+                    self.padded[i] = c
+                    c = (c + 7) // 8 * 8
                 low = dtype == api.BF16 and c % 8 == 0 and op["K"] % 8 == 0
                 self.f32_layer[i] = dtype == api.BF16 and not low
                 d = api.conv_desc(n, h, w, c, op["K"], op["R"], op["S"], op["stride"], op["pad"], api.BF16 if low else api.F32, flags,
@@ -84,7 +92,15 @@ class ConvWorker:
         self.ws = torch.empty(ws_bytes, device=self.dev, dtype=torch.uint8)
         if dtype == api.BF16:
             self.w16 = {op["name"]: torch.empty_like(params[op["name"]][0], dtype=torch.bfloat16)
-                        for i, op in enumerate(ops) if op["op"] == "conv" and not self.f32_layer[i]}
+                        for i, op in enumerate(ops) if op["op"] == "conv" and not self.f32_layer[i] and i not in self.padded}
+            for i in self.padded:
+                name, cp = ops[i]["name"], self.descs[i].C
+                k, r, s_, _ = params[name][0].shape
+                self.w16[name] = torch.empty((k, r, s_, cp), device=self.dev, dtype=torch.bfloat16)
+                self.wpad32 = torch.zeros((k, r, s_, cp), device=self.dev)          # pad channels stay zero
+                self.dwpad32 = torch.empty((k, r, s_, cp), device=self.dev)
+                self.x0pad32 = torch.zeros(self.shapes["x0"][:3] + (cp,), device=self.dev)
+                self.x0pad16 = torch.empty(self.shapes["x0"][:3] + (cp,), device=self.dev, dtype=torch.bfloat16)
             big = max(int(torch.tensor(self.shapes[op["dst"]]).prod()) for i, op in enumerate(ops) if op["op"] == "conv" and self.f32_layer[i]) \
                 if any(self.f32_layer.values()) else 0
             self.tmp32 = torch.empty(max(big, 1), device=self.dev, dtype=torch.float32)   # float32 staging of a mixed layer's y / dy
@@ -100,7 +116,14 @@ class ConvWorker:
             kind = op["op"]
             if kind == "conv":
                 w, b = self.params[op["name"]]
-                if self.dtype == api.BF16 and not self.f32_layer[i]:
+                if i in self.padded:
+                    c = self.padded[i]
+                    api.stanza_copy_channels(self.buf["x0"], 0, self.x0pad32, 0, c)
+                    api.stanza_cast_f32_to_bf16(self.x0pad32, self.x0pad16)
+                    api.stanza_copy_channels(w, 0, self.wpad32, 0, c)
+                    api.stanza_cast_f32_to_bf16(self.wpad32, self.w16[op["name"]])
+                    api.stanza_conv_fwd(self.descs[i], self.x0pad16, self.w16[op["name"]], b, self.buf[op["dst"]], self.ws)
+                elif self.dtype == api.BF16 and not self.f32_layer[i]:
                     api.stanza_cast_f32_to_bf16(w, self.w16[op["name"]])      # this step's bf16 copy of the master filter
                     api.stanza_conv_fwd(self.descs[i], self.buf[op["src"]], self.w16[op["name"]], b, self.buf[op["dst"]], self.ws)
                 elif self.f32_layer[i]:
@@ -157,6 +180,10 @@ class ConvWorker:
                 y = None if (gated.get(op["dst"], False) or not op["relu"]) else self.buf[op["dst"]]
                 w, _ = self.params[op["name"]]
                 dw, db = self.grads[op["name"]]
+                if i in self.padded:
+                    api.stanza_conv_bwd_weight(d, self.x0pad16, dy, y, self.dwpad32, db, self.ws)
+                    api.stanza_copy_channels(self.dwpad32, 0, dw, 0, self.padded[i])
+                    continue
                 if self.f32_layer.get(i, False):
                     # mixed layer (first conv of a bf16 stack): float32 filter gradient from a float32 copy of dy
                     assert op["src"] == "x0", "a float32 conv inside a bf16 stack must be the first layer"
