@@ -39,10 +39,12 @@ class ConvWorker:
                 flags = (api.CONV_BIAS if op.get("bias", True) else 0) | (api.CONV_RELU if op["relu"] else 0)
                 # the image layer of a bf16 stack (3 channels): channels padded with zeros to a multiple of 8, so that it runs
                 # through the bf16 kernels like every other layer instead of in float32 between casts of its output
-                pad_c = dtype == api.BF16 and op["src"] == "x0" and c % 8 != 0 and op["K"] % 8 == 0
+                # (float32 stacks: to a multiple of 4, so that the image and the filter are fetched as 16-byte vectors)
+                vec = 8 if dtype == api.BF16 else 4
+                pad_c = op["src"] == "x0" and c % vec != 0 and (dtype != api.BF16 or op["K"] % 8 == 0)
                 if pad_c:
                     self.padded[i] = c
-                    c = (c + 7) // 8 * 8
+                    c = (c + vec - 1) // vec * vec
                 low = dtype == api.BF16 and c % 8 == 0 and op["K"] % 8 == 0
                 self.f32_layer[i] = dtype == api.BF16 and not low
                 d = api.conv_desc(n, h, w, c, op["K"], op["R"], op["S"], op["stride"], op["pad"], api.BF16 if low else api.F32, flags,
@@ -90,17 +92,19 @@ class ConvWorker:
         ws_bytes = max([api.stanza_conv_workspace_bytes(d, which) for i, d in self.descs.items() if ops[i]["op"] == "conv"
                         for which in (0, 1, 2)] + [16])
         self.ws = torch.empty(ws_bytes, device=self.dev, dtype=torch.uint8)
+        for i in self.padded:
+            cp = self.descs[i].C
+            k, r, s_, _ = params[ops[i]["name"]][0].shape
+            self.wpad32 = torch.zeros((k, r, s_, cp), device=self.dev)          # pad channels stay zero
+            self.dwpad32 = torch.empty((k, r, s_, cp), device=self.dev)
+            self.x0pad32 = torch.zeros(self.shapes["x0"][:3] + (cp,), device=self.dev)
         if dtype == api.BF16:
             self.w16 = {op["name"]: torch.empty_like(params[op["name"]][0], dtype=torch.bfloat16)
                         for i, op in enumerate(ops) if op["op"] == "conv" and not self.f32_layer[i] and i not in self.padded}
             for i in self.padded:
-                name, cp = ops[i]["name"], self.descs[i].C
-                k, r, s_, _ = params[name][0].shape
-                self.w16[name] = torch.empty((k, r, s_, cp), device=self.dev, dtype=torch.bfloat16)
-                self.wpad32 = torch.zeros((k, r, s_, cp), device=self.dev)          # pad channels stay zero
-                self.dwpad32 = torch.empty((k, r, s_, cp), device=self.dev)
-                self.x0pad32 = torch.zeros(self.shapes["x0"][:3] + (cp,), device=self.dev)
-                self.x0pad16 = torch.empty(self.shapes["x0"][:3] + (cp,), device=self.dev, dtype=torch.bfloat16)
+                name = ops[i]["name"]
+                self.w16[name] = torch.empty(self.wpad32.shape, device=self.dev, dtype=torch.bfloat16)
+                self.x0pad16 = torch.empty(self.x0pad32.shape, device=self.dev, dtype=torch.bfloat16)
             big = max(int(torch.tensor(self.shapes[op["dst"]]).prod()) for i, op in enumerate(ops) if op["op"] == "conv" and self.f32_layer[i]) \
                 if any(self.f32_layer.values()) else 0
             self.tmp32 = torch.empty(max(big, 1), device=self.dev, dtype=torch.float32)   # float32 staging of a mixed layer's y / dy
@@ -119,10 +123,13 @@ class ConvWorker:
                 if i in self.padded:
                     c = self.padded[i]
                     api.stanza_copy_channels(self.buf["x0"], 0, self.x0pad32, 0, c)
-                    api.stanza_cast_f32_to_bf16(self.x0pad32, self.x0pad16)
                     api.stanza_copy_channels(w, 0, self.wpad32, 0, c)
-                    api.stanza_cast_f32_to_bf16(self.wpad32, self.w16[op["name"]])
-                    api.stanza_conv_fwd(self.descs[i], self.x0pad16, self.w16[op["name"]], b, self.buf[op["dst"]], self.ws)
+                    if self.dtype == api.BF16:
+                        api.stanza_cast_f32_to_bf16(self.x0pad32, self.x0pad16)
+                        api.stanza_cast_f32_to_bf16(self.wpad32, self.w16[op["name"]])
+                        api.stanza_conv_fwd(self.descs[i], self.x0pad16, self.w16[op["name"]], b, self.buf[op["dst"]], self.ws)
+                    else:
+                        api.stanza_conv_fwd(self.descs[i], self.x0pad32, self.wpad32, b, self.buf[op["dst"]], self.ws)
                 elif self.dtype == api.BF16 and not self.f32_layer[i]:
                     api.stanza_cast_f32_to_bf16(w, self.w16[op["name"]])      # this step's bf16 copy of the master filter
                     api.stanza_conv_fwd(self.descs[i], self.buf[op["src"]], self.w16[op["name"]], b, self.buf[op["dst"]], self.ws)
@@ -181,7 +188,7 @@ class ConvWorker:
                 w, _ = self.params[op["name"]]
                 dw, db = self.grads[op["name"]]
                 if i in self.padded:
-                    api.stanza_conv_bwd_weight(d, self.x0pad16, dy, y, self.dwpad32, db, self.ws)
+                    api.stanza_conv_bwd_weight(d, self.x0pad16 if self.dtype == api.BF16 else self.x0pad32, dy, y, self.dwpad32, db, self.ws)
                     api.stanza_copy_channels(self.dwpad32, 0, dw, 0, self.padded[i])
                     continue
                 if self.f32_layer.get(i, False):
