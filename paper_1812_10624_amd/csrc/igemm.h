@@ -588,6 +588,16 @@ __global__ __launch_bounds__(NTHREADS, (BM >= 256 ? 3 : (VECA && VECB) ? 4 : 2))
     if (MODE != MODE_BWD_WEIGHT && sliced) {
         // raw accumulators of this slice, tile-local [BM][BN]; the fix-up kernel adds the slices and applies the epilogue
         float *dst = p.partial + (size_t)L * (BM * BN);
+        if constexpr (!B_ROWK && TN == 2) {
+            // a lane's two column tiles are neighbouring columns: one 8-byte store, whole rows per instruction
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int r = 0; r < 16; ++r)
+                    *reinterpret_cast<float2 *>(&dst[(wave_m * WTM + wrow(i, 8 * (r >> 2) + 4 * lk + (r & 3))) * BN + wave_n * WTN + 2 * lrow]) =
+                        make_float2(acc[i][0][r], acc[i][1][r]);
+            return;
+        }
 #pragma unroll
         for (int j = 0; j < TN; ++j)
 #pragma unroll
@@ -650,6 +660,35 @@ __global__ __launch_bounds__(NTHREADS, (BM >= 256 ? 3 : (VECA && VECB) ? 4 : 2))
             }
         }
         return;
+    }
+    if constexpr (MODE == MODE_BWD_WEIGHT && TN == 2) {
+        // A lane's two column tiles are the neighbouring columns 2*lrow, 2*lrow + 1: with an even row length they leave as one
+        // 8-byte store (whole 256-byte row segments per instruction instead of every other float twice).
+        const int col = n0 + wave_n * WTN + 2 * lrow;
+        if ((p.Nn & 1) == 0) {
+            if (col >= p.Nn) return;
+#pragma unroll
+            for (int i = 0; i < TM; ++i) {
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int row = m0 + wave_m * WTM + wrow(i, 8 * (r >> 2) + 4 * lk + (r & 3));
+                    if (row >= p.M) continue;
+                    const size_t o = (size_t)row * p.Nn + col;
+                    float2 v = make_float2(acc[i][0][r], acc[i][1][r]);
+                    if (p.flags & EPI_SGD) {
+                        const float2 w = *reinterpret_cast<const float2 *>(p.sgd_w + o);
+                        float2 vel = *reinterpret_cast<const float2 *>(p.sgd_v + o);
+                        vel.x = p.mom * vel.x + (v.x + p.wd * w.x);
+                        vel.y = p.mom * vel.y + (v.y + p.wd * w.y);
+                        *reinterpret_cast<float2 *>(p.sgd_v + o) = vel;
+                        *reinterpret_cast<float2 *>(p.sgd_w + o) = make_float2(w.x - p.lr * vel.x, w.y - p.lr * vel.y);
+                    } else {
+                        *reinterpret_cast<float2 *>(p.out + split_off + o) = v;
+                    }
+                }
+            }
+            return;
+        }
     }
 #pragma unroll
     for (int j = 0; j < TN; ++j) {
