@@ -213,14 +213,20 @@ def stanza_avgpool_bwd(d: PoolDesc, dy, dx, dtype=F32):
     _check(load().stanza_avgpool_bwd(C.byref(d), dtype, _ptr(dy), _ptr(dx), _stream()), "stanza_avgpool_bwd")
 
 
-def stanza_copy_channels(src, src_off: int, dst, dst_off: int, cols: int):
-    """Copy `cols` channels of every pixel: src[..., src_off:src_off+cols] -> dst[..., dst_off:dst_off+cols] (float32, C fastest)."""
+def stanza_copy2d(rows: int, cols: int, src, src_off: int, src_ld: int, dst, dst_off: int, dst_ld: int):
+    """dst[dst_off + r*dst_ld + j] = src[src_off + r*src_ld + j] for r < rows, j < cols (float32 elements)."""
     assert src.is_cuda and dst.is_cuda and src.is_contiguous() and dst.is_contiguous() and src.dtype == dst.dtype == torch.float32
+    assert src_off + (rows - 1) * src_ld + cols <= src.numel() and dst_off + (rows - 1) * dst_ld + cols <= dst.numel()
+    _check(load().stanza_copy2d(rows, cols, C.c_void_p(src.data_ptr() + 4 * src_off), src_ld, C.c_void_p(dst.data_ptr() + 4 * dst_off), dst_ld,
+                                _stream()), "stanza_copy2d")
+
+
+def stanza_copy_channels(src, src_off: int, dst, dst_off: int, cols: int):
+    """stanza_copy2d over NHWC tensors: src[..., src_off:src_off+cols] -> dst[..., dst_off:dst_off+cols] (C fastest)."""
     cs, cd = src.shape[-1], dst.shape[-1]
     rows = src.numel() // cs
     assert rows == dst.numel() // cd and src_off + cols <= cs and dst_off + cols <= cd
-    _check(load().stanza_copy2d(rows, cols, C.c_void_p(src.data_ptr() + 4 * src_off), cs, C.c_void_p(dst.data_ptr() + 4 * dst_off), cd, _stream()),
-           "stanza_copy2d")
+    stanza_copy2d(rows, cols, src, src_off, cs, dst, dst_off, cd)
 
 
 def stanza_bn_workspace_bytes(rows: int, channels: int, dtype=F32) -> int:
