@@ -42,7 +42,7 @@ def _gate32(x, gamma, beta, mean, istd):
 
 
 # rows, channels: scalar path (C % 4 != 0), a row narrower than / equal to / wider than 256 vectors, ragged slabs
-SHAPES = [(1, 4), (33, 3), (175, 4), (243, 7), (442, 48), (784, 512), (98, 2048), (300, 1028), (40000, 64), (12545, 256)]
+SHAPES = [(1, 4), (33, 3), (61, 1030), (175, 4), (243, 7), (442, 48), (784, 512), (98, 2048), (300, 1028), (40000, 64), (12545, 256)]
 
 
 @pytest.mark.parametrize("rows,c", SHAPES)
