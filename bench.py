@@ -74,10 +74,10 @@ def main():
         fp.append((torch.randn((o, i), device=dev, generator=gen) * (2.0 / i) ** 0.5,
                    (torch.rand(o, device=dev, generator=gen) * 2 - 1) / i ** 0.5))
         fm.append((torch.zeros((o, i), device=dev), torch.zeros(o, device=dev)))
-    worker = ConvWorker(wl.ops, wl.image, B, cp, dtype=api.BF16 if args.dtype == "bf16" else api.F32)
+    feats = torch.randn((n, wl.fc_dims[0]), device=dev, generator=gen).clamp_(min=0)   # filler rows of the other workers
+    worker = ConvWorker(wl.ops, wl.image, B, cp, dtype=api.BF16 if args.dtype == "bf16" else api.F32, feat_out=feats[:B])
     fcw = FcWorker(wl.fc_dims, n, fp, fm, wl.lr, wl.momentum, wl.weight_decay, dropout=(args.dropout, seed) if args.dropout > 0 else None,
                    dtype=api.BF16 if (args.dtype == "bf16" and args.dropout == 0 and all(d % 8 == 0 for d in wl.fc_dims[:-1])) else api.F32)
-    feats = torch.randn((n, wl.fc_dims[0]), device=dev, generator=gen).clamp_(min=0)   # filler rows of the other workers
     shard0 = W.flat_tensors(worker.grads)
     shards = [shard0] + [[torch.randn(t.shape, device=dev, generator=gen) * 1e-3 for t in shard0] for _ in range(K - 1)]
     agg = Aggregator(W.flat_tensors(cp), W.flat_tensors(cm), shards)
@@ -109,7 +109,7 @@ def main():
     netrun.api = _Tap()
 
     def step():
-        feats[:B].copy_(worker.forward().view(B, -1))          # hand-off: this worker's rows of the FC input
+        worker.forward()                                        # hand-off: written straight into this worker's rows of the FC input
         timed("stanza_fc_step", fcw.step, feats, labels)
         worker.backward(fcw.dfeats[:B])                         # hand-back: this worker's slice of the gradient
         timed("stanza_ps_aggregate", agg.step, 1.0, wl.lr, wl.momentum, wl.weight_decay)
@@ -126,7 +126,7 @@ def main():
         assert args.warmup >= 1, "--graph takes its per-call breakdown from the warm-up steps"
         n_timed_eager = args.warmup
         netrun.api = api                       # no event pairs inside the capture
-        graph = netrun.StepGraph(lambda: (feats[:B].copy_(worker.forward().view(B, -1)), fcw.step(feats, labels),
+        graph = netrun.StepGraph(lambda: (worker.forward(), fcw.step(feats, labels),
                                           worker.backward(fcw.dfeats[:B]), agg.step(1.0, wl.lr, wl.momentum, wl.weight_decay)), warmup=0)
         graph.replay()
         torch.cuda.synchronize()

@@ -21,7 +21,10 @@ class ConvWorker:
     layer (C = 3) runs with its channels zero-padded to 8; any other conv whose channel counts are not multiples of 8 runs in
     float32 between casts."""
 
-    def __init__(self, ops: List[dict], image_shape, batch: int, params: Dict[str, tuple], device="cuda:0", dtype=api.F32):
+    def __init__(self, ops: List[dict], image_shape, batch: int, params: Dict[str, tuple], device="cuda:0", dtype=api.F32,
+                 feat_out: Optional[torch.Tensor] = None):
+        """feat_out: this worker's rows of the FC worker's [n, A] feature buffer (float32, contiguous).  The last op of the stack
+        then writes the hand-off straight into it and no copy is made; without it the worker owns its feature buffer."""
         self.ops = ops
         self.dev = torch.device(device)
         self.dtype = dtype
@@ -74,6 +77,10 @@ class ConvWorker:
             assert all(op["op"] in ("conv", "pool") for op in ops), "bf16 stacks: conv and pool ops only"
         self.buf = {name: torch.empty(shape, device=self.dev, dtype=torch.float32 if name == "x0" else self.tdt)
                     for name, shape in self.shapes.items()}
+        if feat_out is not None:
+            assert feat_out.is_contiguous() and feat_out.dtype == torch.float32 and feat_out.numel() == self.buf["feat"].numel()
+            if dtype == api.F32:
+                self.buf["feat"] = feat_out.view(self.shapes["feat"])
         self.argmax = {op["dst"]: torch.empty(self.shapes[op["dst"]], device=self.dev, dtype=torch.uint8)
                        for op in ops if op["op"] == "pool"}
         self.gbuf: Dict[str, torch.Tensor] = {}
@@ -108,7 +115,8 @@ class ConvWorker:
             big = max(int(torch.tensor(self.shapes[op["dst"]]).prod()) for i, op in enumerate(ops) if op["op"] == "conv" and self.f32_layer[i]) \
                 if any(self.f32_layer.values()) else 0
             self.tmp32 = torch.empty(max(big, 1), device=self.dev, dtype=torch.float32)   # float32 staging of a mixed layer's y / dy
-            self.feat32 = torch.empty(self.shapes["feat"], device=self.dev, dtype=torch.float32)
+            self.feat32 = feat_out.view(self.shapes["feat"]) if feat_out is not None else \
+                torch.empty(self.shapes["feat"], device=self.dev, dtype=torch.float32)
             self.dfeat16 = torch.empty(self.shapes["feat"], device=self.dev, dtype=torch.bfloat16)
 
     # ------------------------------------------------------------------ forward

@@ -173,7 +173,8 @@ def test_conv_bf16_full_size_sampled(api, o32):
 
 
 def test_conv_worker_bf16_stack(api, o32):
-    """The tiny CNN run as a bf16 stack (first layer in float32 between casts, bf16 copies of the master filters):
+    """The tiny CNN run as a bf16 stack (image layer with its channels zero-padded to 8, bf16 copies of the master filters,
+    features widened straight into the caller's float32 buffer):
     features and per-layer gradients against the float32 checker run on the same float32 inputs."""
     from oracle import network as onet
     from paper_1812_10624_amd.netrun import ConvWorker
@@ -185,16 +186,18 @@ def test_conv_worker_bf16_stack(api, o32):
     dfeat = np.random.default_rng(12).standard_normal(bufs["feat"].shape, dtype=np.float32)
     pg, _ = onet.conv_stack_backward(o32, wl.ops, bufs, cp, dfeat)
     gcp = {n: (dev32(w), dev32(b)) for n, (w, b) in cp.items()}
-    wk = ConvWorker(wl.ops, wl.image, B, gcp, dtype=api.BF16)
+    fc_rows = torch.full((3 * B, int(np.prod(bufs["feat"].shape[1:]))), float("nan"), device="cuda:0")
+    wk = ConvWorker(wl.ops, wl.image, B, gcp, dtype=api.BF16, feat_out=fc_rows[B:2 * B])
     feat = wk.forward(dev32(img))
-    assert feat.dtype == torch.float32
+    assert feat.dtype == torch.float32 and feat.data_ptr() == fc_rows[B:2 * B].data_ptr()
+    assert bool(torch.isnan(fc_rows[:B]).all()) and bool(torch.isnan(fc_rows[2 * B:]).all())      # the neighbours' rows are untouched
     # a chain of layers: images and filters are rounded on the way in, every activation is rounded again, so the
     # single-layer bound (2e-2, held by the layer-wise tests above) does not apply to the end of the stack
     assert rel_err(host(feat), bufs["feat"]) < 3 * TOL_BF16
     wk.backward(dev32(dfeat).view(B, -1))
     # Down the chain an element-wise bound no longer applies: a bf16 rounding upstream flips some pool argmaxes
     # (near-ties) and ReLU masks, which moves whole gradient entries.  The layer-wise tests above are the parity
-    # gate; here the sequencing (casts, masks, mixed first layer) is checked through direction and size.
+    # gate; here the sequencing (casts, masks, padded image layer) is checked through direction and size.
     for n in cp:
         for which in range(2):
             got, want = host(wk.grads[n][which]).ravel().astype(np.float64), pg[n][which].ravel().astype(np.float64)

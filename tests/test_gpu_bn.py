@@ -176,11 +176,11 @@ def test_normalised_residual_step(api, o32, K, B):
     gcm = {n: (dev(w), _none_or(dev, b)) for n, (w, b) in cm.items()}
     gfp = [(dev(w), dev(b)) for w, b in fp]
     gfm = [(dev(w), dev(b)) for w, b in fm]
-    workers = [ConvWorker(wl.ops, wl.image, B, gpar) for _ in range(K)]
+    feats = torch.full((K * B, wl.fc_dims[0]), float("nan"), device="cuda:0")
+    workers = [ConvWorker(wl.ops, wl.image, B, gpar, feat_out=feats[k * B:(k + 1) * B]) for k in range(K)]   # hand-off without a copy
     fcw = FcWorker(wl.fc_dims, K * B, gfp, gfm, lr, mom, wd)
-    feats = torch.empty((K * B, wl.fc_dims[0]), device="cuda:0")
     for k, wk in enumerate(workers):
-        feats[k * B:(k + 1) * B].copy_(wk.forward(dev(imgs[k])).view(B, -1))
+        wk.forward(dev(imgs[k]))
     assert rel_err(host(feats), ref["feats"]) < TOL_F32
     # every normalisation layer's saved statistics on worker 0
     for op in wl.ops:

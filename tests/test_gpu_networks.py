@@ -89,16 +89,17 @@ def test_step_graph_replays_equal_eager_steps(api, name):
     fm = [(torch.zeros_like(w), torch.zeros_like(b)) for w, b in fp]
     imgs = [dev(wl_mod.gen_images(wl, 0, k)) for k in range(K)]
     labels = dev(wl_mod.gen_labels(wl, 0))
-    workers = [ConvWorker(wl.ops, wl.image, B, cp) for _ in range(K)]
-    fcw = FcWorker(wl.fc_dims, K * B, fp, fm, wl.lr, 0.9, 1e-4)  # momentum on, so the velocity buffers are exercised
     feats = torch.empty((K * B, wl.fc_dims[0]), device="cuda:0")
+    # every worker writes its hand-off straight into its rows of the FC worker's feature buffer
+    workers = [ConvWorker(wl.ops, wl.image, B, cp, feat_out=feats[k * B:(k + 1) * B]) for k in range(K)]
+    fcw = FcWorker(wl.fc_dims, K * B, fp, fm, wl.lr, 0.9, 1e-4)  # momentum on, so the velocity buffers are exercised
     names = list(cp)
     agg = Aggregator([cp[n][i] for n in names for i in range(2)], [cm[n][i] for n in names for i in range(2)],
                      [[wk.grads[n][i] for n in names for i in range(2)] for wk in workers])
 
     def step():
         for k, wk in enumerate(workers):
-            feats[k * B:(k + 1) * B].copy_(wk.forward(imgs[k]).view(B, -1))
+            wk.forward(imgs[k])
         fcw.step(feats, labels)
         for k, wk in enumerate(workers):
             wk.backward(fcw.dfeats[k * B:(k + 1) * B])
