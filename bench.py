@@ -130,20 +130,28 @@ def main():
                                           worker.backward(fcw.dfeats[:B]), agg.step(1.0, wl.lr, wl.momentum, wl.weight_decay)), warmup=0)
         graph.replay()
         torch.cuda.synchronize()
+        marks = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
         t0 = time.perf_counter()
-        for _ in range(args.steps):
+        marks[0].record()
+        for i in range(args.steps):
             graph.replay()
+            marks[i + 1].record()
         torch.cuda.synchronize()
         t1 = time.perf_counter()
     else:
         n_timed_eager = args.steps
         records.clear()
+        marks = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
         t0 = time.perf_counter()
-        for _ in range(args.steps):
+        marks[0].record()
+        for i in range(args.steps):
             step()
+            marks[i + 1].record()
         torch.cuda.synchronize()
         t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / args.steps
+    step_ms = sorted(marks[i].elapsed_time(marks[i + 1]) for i in range(args.steps))     # each step between events on the stream
+    props = torch.cuda.get_device_properties(0)
 
     per = {}
     for tag, s, e in records:
@@ -204,6 +212,9 @@ def main():
         "unit": "images/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step,
+        "step_ms_median": step_ms[len(step_ms) // 2], "step_ms_min": step_ms[0], "step_ms_max": step_ms[-1],
+        "device": {"name": props.name, "compute_units": props.multi_processor_count,
+                   "note": "clocks and power state as the box provides them (not set or read by this run)"},
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": args.dtype, "data": "synthetic", "launch": "hip_graph_replay" if args.graph else "eager",
         "config": {"workload": f"{wl.name}_shaped_conv_worker_B{B}_fc_worker_n{n}_K{K}_" + ("fp32" if args.dtype == "f32" else "bf16in_fp32acc"),
@@ -325,7 +336,8 @@ def cpu_baseline(wl, seed):
     for nm, (w, b) in cp.items():
         shards_w = [np.ascontiguousarray(pg[nm][0]).reshape(-1)] * K
         o.ps_aggregate(w.reshape(-1), np.zeros(w.size, np.float32), shards_w, 1.0, wl.lr, wl.momentum, wl.weight_decay)
-        o.ps_aggregate(b, np.zeros_like(b), [pg[nm][1]] * K, 1.0, wl.lr, wl.momentum, wl.weight_decay)
+        if b is not None:
+            o.ps_aggregate(b, np.zeros_like(b), [pg[nm][1]] * K, 1.0, wl.lr, wl.momentum, wl.weight_decay)
     dt = time.perf_counter() - t0
     return {"value": b1 / dt, "unit": "images/s", "cores": o.threads(),
             "kind": "oracle", "seconds": dt,
