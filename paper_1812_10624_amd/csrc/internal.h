@@ -41,7 +41,8 @@ int launch_igemm(int mode, GemmParams &p, int bw_splits, float *partial, size_t 
 size_t igemm_partial_floats(int mode, int M, int Nn, int Kd);
 int launch_igemm_bf16(int mode, GemmParams &p, int splits, hipStream_t st);
 
-// out[i] = sum_s partial[s*numel + i], s ascending; likewise out2 from partial2 (numel2 may be 0).
+// out[i] = sum_s partial[s*numel + i] in a fixed order (1, 4 or 16 interleaved groups of slices, each ascending, then the
+// groups in order: the grouping depends on the sizes alone); likewise out2 from partial2 (numel2 may be 0).
 int launch_split_reduce(const float *partial, int splits, size_t numel, float *out, const float *partial2, size_t numel2, float *out2,
                         hipStream_t st);
 
