@@ -169,7 +169,7 @@ __global__ __launch_bounds__(NTHREADS, 2) void igemm_bf16_kernel(const GemmParam
     // FAST path state (see fetch): tap validity mask per A row, static validity per B vector, running stage position
     // (the host takes this path for at most 32 taps)
     uint32_t a_mask[AV];
-    bool b_ok[BV];
+    uint32_t b_oob[BV];          // 0, or OOB_OFF for a B vector beyond the column range
     int f_cblk = 0, f_tap = 0, f_ar = 0, f_as = 0;
     if (FAST) {
 #pragma unroll
@@ -185,7 +185,7 @@ __global__ __launch_bounds__(NTHREADS, 2) void igemm_bf16_kernel(const GemmParam
             a_mask[i] = mk;
         }
 #pragma unroll
-        for (int i = 0; i < BV; ++i) b_ok[i] = MODE == MODE_FWD ? (n0 + row0 + RPP * i < p.Nn) : (n0 + (t % B_F8) * 8 < p.Nn);
+        for (int i = 0; i < BV; ++i) b_oob[i] = (MODE == MODE_FWD ? (n0 + row0 + RPP * i < p.Nn) : (n0 + (t % B_F8) * 8 < p.Nn)) ? 0u : OOB_OFF;
     }
 
     const __amdgpu_buffer_rsrc_t rsrc_a = make_rsrc(p.a, p.a_bytes);
@@ -218,18 +218,27 @@ __global__ __launch_bounds__(NTHREADS, 2) void igemm_bf16_kernel(const GemmParam
                 const int wtap = (p.sub.r0 + f_ar * g.sh) * g.S + p.sub.s0 + f_as * g.sw;    // the filter tap this class tap stands for
                 sb = ((f_cblk * BKH * (g.R * g.S) + wtap) * g.C) * 2;
             }
+            // A masked lane gets bit 31 of its offset set (any such offset is past the end of the buffer, whose size is below
+            // 2 GiB, so the load returns zero); written as arithmetic on purpose: selects here made the compiler wrap every
+            // load in its own branch, which cut the loop into pieces it could not schedule across.
+            const uint32_t koff = kok ? 0u : OOB_OFF;
 #pragma unroll
             for (int i = 0; i < AV; ++i) {
-                const bool ok = kok && ((a_mask[i] >> f_tap) & 1u);
-                const uint32_t bo = ok ? (uint32_t)(a_row[i] * 2 + sa) : OOB_OFF;
+                const uint32_t bo = (uint32_t)(a_row[i] * 2 + sa) | koff | ((~(a_mask[i] >> f_tap) & 1u) << 31);
                 ra[set][i] = bload16(rsrc_a, bo);
                 if (MODE == MODE_BWD_DATA && amask) rg[set][i] = bload16(rsrc_g, bo);
             }
 #pragma unroll
-            for (int i = 0; i < BV; ++i) rb[set][i] = bload16(rsrc_b, (kok && b_ok[i]) ? (uint32_t)(b_row[i] * 2 + sb) : OOB_OFF);
+            for (int i = 0; i < BV; ++i) rb[set][i] = bload16(rsrc_b, (uint32_t)(b_row[i] * 2 + sb) | koff | b_oob[i]);
             ++f_tap;
-            if (++f_as == tapS) { f_as = 0; ++f_ar; }
-            if (f_tap == tapRS) { f_tap = f_ar = f_as = 0; ++f_cblk; }
+            ++f_as;
+            const int wrap_s = f_as == tapS, wrap_t = f_tap == tapRS;
+            f_as = wrap_s ? 0 : f_as;
+            f_ar += wrap_s;
+            f_as = wrap_t ? 0 : f_as;
+            f_ar = wrap_t ? 0 : f_ar;
+            f_tap = wrap_t ? 0 : f_tap;
+            f_cblk += wrap_t;
             return;
         }
         const int kchunk = kbeg + ch * BKH;
