@@ -194,7 +194,8 @@ __global__ __launch_bounds__(NTHREADS, 2) void igemm_bf16_kernel(const GemmParam
 
     // two register sets: set (s & 1) holds stage s from its fetch until it is written to LDS; one set when the gate vectors
     // take the registers of the second
-    constexpr bool PREFETCH2 = !AMASK;
+    constexpr bool PREFETCH2 = !AMASK && (FAST || MODE == MODE_BWD_WEIGHT);   // (the per-element address arithmetic of the general
+                                                                             // forward / backward-data path needs the registers)
     uint4 ra[PREFETCH2 ? 2 : 1][AV], rb[PREFETCH2 ? 2 : 1][BV], rg[PREFETCH2 ? 2 : 1][AV];
     const bool want_db = MODE == MODE_BWD_WEIGHT && (p.flags & EPI_DBIAS) && tile_n == 0;
     float dbacc[8];
@@ -243,9 +244,10 @@ __global__ __launch_bounds__(NTHREADS, 2) void igemm_bf16_kernel(const GemmParam
         }
         const int kchunk = kbeg + ch * BKH;
 #pragma unroll
+        // (validity as 0 / 1 integers combined with &, and masked lanes by setting bit 31 of the offset: see the fast path)
         for (int i = 0; i < AV; ++i) {
             int off;
-            bool ok;
+            uint32_t ok;
             if (MODE == MODE_FWD || MODE == MODE_BWD_DATA) {
                 const int CC = (MODE == MODE_FWD) ? g.C : g.K;
                 const int kk = kchunk + kq * 8;
@@ -253,31 +255,31 @@ __global__ __launch_bounds__(NTHREADS, 2) void igemm_bf16_kernel(const GemmParam
                 const int ar = fdiv(rs, p.fd_s), as = rs - ar * tapS;
                 if (MODE == MODE_FWD) {
                     const int h = a_hb[i] + ar, w = a_wb[i] + as;
-                    ok = kk < p.Kd && (unsigned)h < (unsigned)g.H && (unsigned)w < (unsigned)g.W;
+                    ok = (uint32_t)(kk < p.Kd) & (uint32_t)((unsigned)h < (unsigned)g.H) & (uint32_t)((unsigned)w < (unsigned)g.W);
                     off = a_base[i] + (h * g.W + w) * g.C + cc;
                 } else {
                     const int pp = a_hb[i] - ar, q = a_wb[i] - as;
-                    ok = kk < p.Kd && (unsigned)pp < (unsigned)g.Ho && (unsigned)q < (unsigned)g.Wo;
+                    ok = (uint32_t)(kk < p.Kd) & (uint32_t)((unsigned)pp < (unsigned)g.Ho) & (uint32_t)((unsigned)q < (unsigned)g.Wo);
                     off = a_base[i] + (pp * g.Wo + q) * g.K + cc;
                 }
             } else {
                 const int col = m0 + (t % A_F8) * 8;
                 const int pix = kchunk + t / A_F8 + A_RP * i;
-                ok = pix < kend && col < p.M;
+                ok = (uint32_t)(pix < kend) & (uint32_t)(col < p.M);
                 off = pix * g.K + col;
             }
-            const uint32_t bo = ok ? (uint32_t)off * 2u : OOB_OFF;
+            const uint32_t bo = ((uint32_t)off * 2u & 0x7fffffffu) | ((ok ^ 1u) << 31);
             ra[set][i] = bload16(rsrc_a, bo);
             if (MODE != MODE_FWD && amask) rg[set][i] = bload16(rsrc_g, bo);
         }
 #pragma unroll
         for (int i = 0; i < BV; ++i) {
             int off;
-            bool ok;
+            uint32_t ok;
             if (MODE == MODE_FWD) {
                 const int j = n0 + row0 + RPP * i;
                 const int kk = kchunk + kq * 8;
-                ok = j < p.Nn && kk < p.Kd;
+                ok = (uint32_t)(j < p.Nn) & (uint32_t)(kk < p.Kd);
                 off = j * p.Kd + kk;
             } else if (MODE == MODE_BWD_DATA) {
                 const int col = n0 + (t % B_F8) * 8;
@@ -285,7 +287,7 @@ __global__ __launch_bounds__(NTHREADS, 2) void igemm_bf16_kernel(const GemmParam
                 const int rs = fdiv(kk, p.fd_k), bk = kk - rs * g.K;
                 const int tr = fdiv(rs, p.fd_s), ts = rs - tr * tapS;
                 const int br = p.sub.r0 + tr * g.sh, bs = p.sub.s0 + ts * g.sw;
-                ok = kk < p.Kd && col < p.Nn;
+                ok = (uint32_t)(kk < p.Kd) & (uint32_t)(col < p.Nn);
                 off = ((bk * g.R + br) * g.S + bs) * g.C + col;
             } else {
                 const int col = n0 + (t % B_F8) * 8;
@@ -293,10 +295,10 @@ __global__ __launch_bounds__(NTHREADS, 2) void igemm_bf16_kernel(const GemmParam
                 const int img = fdiv(pix, p.fd_howo), pq = pix - img * (g.Ho * g.Wo);
                 const int pp = fdiv(pq, p.fd_wo), q = pq - pp * g.Wo;
                 const int h = pp * g.sh - g.ph + bw_r, w = q * g.sw - g.pw + bw_s;
-                ok = pix < kend && col < p.Nn && (unsigned)h < (unsigned)g.H && (unsigned)w < (unsigned)g.W;
+                ok = (uint32_t)(pix < kend) & (uint32_t)(col < p.Nn) & (uint32_t)((unsigned)h < (unsigned)g.H) & (uint32_t)((unsigned)w < (unsigned)g.W);
                 off = ((img * g.H + h) * g.W + w) * g.C + bw_c;
             }
-            rb[set][i] = bload16(rsrc_b, ok ? (uint32_t)off * 2u : OOB_OFF);
+            rb[set][i] = bload16(rsrc_b, ((uint32_t)off * 2u & 0x7fffffffu) | ((ok ^ 1u) << 31));
         }
     };
 
@@ -310,10 +312,7 @@ __global__ __launch_bounds__(NTHREADS, 2) void igemm_bf16_kernel(const GemmParam
             if (MODE != MODE_FWD && amask) v = gate8(v, rg[set][i]);
             if (A_KMAJ) {
                 *reinterpret_cast<uint4 *>(&As[(t / A_F8 + A_RP * i) * LDAK + (t % A_F8) * 8]) = v;
-                if (want_db) {
-#pragma unroll
-                    for (int e = 0; e < 8; ++e) dbacc[e] += bf16_to_f32(h8at(v, e));
-                }
+                ra[set][i] = v;      // the gated vector, for the bias-gradient sums below
             } else {
                 *reinterpret_cast<uint4 *>(&As[(row0 + RPP * i) * LDR + kq * 8]) = v;
             }
@@ -322,6 +321,12 @@ __global__ __launch_bounds__(NTHREADS, 2) void igemm_bf16_kernel(const GemmParam
         for (int i = 0; i < BV; ++i) {
             if (B_KMAJ) *reinterpret_cast<uint4 *>(&Bs[(t / B_F8 + B_RP * i) * LDBK + (t % B_F8) * 8]) = rb[set][i];
             else *reinterpret_cast<uint4 *>(&Bs[(row0 + RPP * i) * LDR + kq * 8]) = rb[set][i];
+        }
+        if (A_KMAJ && want_db) {      // one workgroup-uniform branch per stage, after the stores
+#pragma unroll
+            for (int i = 0; i < AV; ++i)
+#pragma unroll
+                for (int e = 0; e < 8; ++e) dbacc[e] += bf16_to_f32(h8at(ra[set][i], e));
         }
     };
 
