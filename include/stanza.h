@@ -145,7 +145,9 @@ int stanza_pool_relu_bwd(const stanza_pool_desc *desc, int32_t dtype, const void
 /* ---- Residual join and global average pool of the residual-network-shaped workload (the paper trains
  * such a network, Sec. 6.1 table of models, without describing these layers: plain definitions).
  *   add_relu_fwd: o = max(a + b, 0);  add_relu_bwd: dz = dout * [o > 0] (the gradient of both a and b)
- *   gap_fwd: f[n,c] = mean_{h,w} x[n,h,w,c];  gap_bwd: dx[n,h,w,c] = df[n,c] / (H*W) */
+ *   gap_fwd: f[n,c] = mean_{h,w} x[n,h,w,c];  gap_bwd: dx[n,h,w,c] = df[n,c] / (H*W)
+ * dtype: STANZA_F32, or STANZA_BF16 for a, b, o, dout, dz (numel % 8 == 0) and for x / dx of the global average pool
+ * (f and df, the features handed to the FC worker and their gradient, are always float32). */
 int stanza_add_relu_fwd(int64_t numel, int32_t dtype, const void *a, const void *b, void *o, void *stream);
 int stanza_add_relu_bwd(int64_t numel, int32_t dtype, const void *dout, const void *o, void *dz, void *stream);
 int stanza_gap_fwd(int32_t N, int32_t HW, int32_t C, int32_t dtype, const void *x, float *f, void *stream);

@@ -375,6 +375,61 @@ __global__ void gap_bwd_kernel(size_t total, int HW, int C, const float *__restr
     dx[i] = df[n * C + c] / (float)HW;
 }
 
+// bf16 forms (numel % 8 == 0: channel counts of a bf16 stack are multiples of 8): 8 elements per thread, float32 arithmetic,
+// one rounding on store.
+__global__ __launch_bounds__(256) void add_relu_fwd_bf16_kernel(size_t n8, const uint4 *__restrict__ a, const uint4 *__restrict__ b, uint4 *__restrict__ o)
+{
+    const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= n8) return;
+    const uint4 x = a[i], y = b[i];
+    const uint32_t *px = reinterpret_cast<const uint32_t *>(&x), *py = reinterpret_cast<const uint32_t *>(&y);
+    uint4 r;
+    uint32_t *pr = reinterpret_cast<uint32_t *>(&r);
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+        const float lo = fmaxf(__uint_as_float(px[w] << 16) + __uint_as_float(py[w] << 16), 0.f);
+        const float hi = fmaxf(__uint_as_float(px[w] & 0xffff0000u) + __uint_as_float(py[w] & 0xffff0000u), 0.f);
+        pr[w] = (uint32_t)f32_to_bf16_rne(lo) | ((uint32_t)f32_to_bf16_rne(hi) << 16);
+    }
+    o[i] = r;
+}
+
+__global__ __launch_bounds__(256) void add_relu_bwd_bf16_kernel(size_t n8, const uint4 *__restrict__ dout, const uint4 *__restrict__ o, uint4 *__restrict__ dz)
+{
+    const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= n8) return;
+    uint4 d = dout[i];
+    const uint4 y = o[i];
+    uint32_t *pd = reinterpret_cast<uint32_t *>(&d);
+    const uint32_t *py = reinterpret_cast<const uint32_t *>(&y);
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+        // o = max(.,0) is never negative: an element is positive iff its bits are non-zero (and not -0)
+        const uint32_t lo = (py[w] & 0x7fffu) != 0 && !(py[w] & 0x8000u) ? 0x0000ffffu : 0u;
+        const uint32_t hi = (py[w] & 0x7fff0000u) != 0 && !(py[w] & 0x80000000u) ? 0xffff0000u : 0u;
+        pd[w] &= lo | hi;
+    }
+    dz[i] = d;
+}
+
+__global__ void gap_fwd_bf16_kernel(int N, int HW, int C, const uint16_t *__restrict__ x, float *__restrict__ f)
+{
+    const int c = blockIdx.x * blockDim.x + threadIdx.x, n = blockIdx.y;
+    if (c >= C) return;
+    float s = 0.f;
+    for (int i = 0; i < HW; ++i) s += __uint_as_float((uint32_t)x[((size_t)n * HW + i) * C + c] << 16);
+    f[(size_t)n * C + c] = s / (float)HW;
+}
+
+__global__ void gap_bwd_bf16_kernel(size_t total, int HW, int C, const float *__restrict__ df, uint16_t *__restrict__ dx)
+{
+    const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= total) return;
+    const int c = (int)(i % C);
+    const size_t n = i / ((size_t)HW * C);
+    dx[i] = f32_to_bf16_rne(df[n * C + c] / (float)HW);
+}
+
 // ------------------------------------------------------------------ bf16 casts
 __global__ void cast_f32_bf16_kernel(size_t numel, const float *__restrict__ src, uint16_t *__restrict__ dst)
 {
@@ -680,7 +735,7 @@ extern "C" int stanza_pool_relu_bwd(const stanza_pool_desc *desc, int32_t dtype,
 static int ew_check(int64_t numel, int32_t dtype, const void *a, const void *b, const void *c)
 {
     if (numel <= 0 || numel >= (int64_t(1) << 31)) return STANZA_EINVAL;
-    if (dtype != STANZA_F32) return STANZA_EUNSUPPORTED;
+    if (dtype != STANZA_F32 && !(dtype == STANZA_BF16 && numel % 8 == 0)) return STANZA_EUNSUPPORTED;
     if (!a || !b || !c) return STANZA_ENULL;
     if (!aligned16(a) || !aligned16(b) || !aligned16(c)) return STANZA_EALIGN;
     return STANZA_OK;
@@ -690,6 +745,12 @@ extern "C" int stanza_add_relu_fwd(int64_t numel, int32_t dtype, const void *a, 
 {
     int rc = ew_check(numel, dtype, a, b, o);
     if (rc) return rc;
+    if (dtype == STANZA_BF16) {
+        const size_t n8 = (size_t)numel / 8;
+        hipLaunchKernelGGL(add_relu_fwd_bf16_kernel, dim3((unsigned)cdiv64(n8, 256)), dim3(256), 0, (hipStream_t)stream, n8, (const uint4 *)a,
+                           (const uint4 *)b, (uint4 *)o);
+        return launch_status();
+    }
     const size_t n4 = (size_t)numel / 4;
     hipLaunchKernelGGL(add_relu_fwd_kernel, dim3((unsigned)cdiv64(n4 + 1, 256)), dim3(256), 0, (hipStream_t)stream, n4, (size_t)numel,
                        (const float *)a, (const float *)b, (float *)o);
@@ -700,6 +761,12 @@ extern "C" int stanza_add_relu_bwd(int64_t numel, int32_t dtype, const void *dou
 {
     int rc = ew_check(numel, dtype, dout, o, dz);
     if (rc) return rc;
+    if (dtype == STANZA_BF16) {
+        const size_t n8 = (size_t)numel / 8;
+        hipLaunchKernelGGL(add_relu_bwd_bf16_kernel, dim3((unsigned)cdiv64(n8, 256)), dim3(256), 0, (hipStream_t)stream, n8, (const uint4 *)dout,
+                           (const uint4 *)o, (uint4 *)dz);
+        return launch_status();
+    }
     const size_t n4 = (size_t)numel / 4;
     hipLaunchKernelGGL(add_relu_bwd_kernel, dim3((unsigned)cdiv64(n4 + 1, 256)), dim3(256), 0, (hipStream_t)stream, n4, (size_t)numel,
                        (const float *)dout, (const float *)o, (float *)dz);
@@ -709,19 +776,25 @@ extern "C" int stanza_add_relu_bwd(int64_t numel, int32_t dtype, const void *dou
 extern "C" int stanza_gap_fwd(int32_t N, int32_t HW, int32_t C, int32_t dtype, const void *x, float *f, void *stream)
 {
     if (N <= 0 || HW <= 0 || C <= 0 || (int64_t)N * HW * C >= (int64_t(1) << 31)) return STANZA_EINVAL;
-    if (dtype != STANZA_F32) return STANZA_EUNSUPPORTED;
+    if (dtype != STANZA_F32 && dtype != STANZA_BF16) return STANZA_EUNSUPPORTED;
     if (!x || !f) return STANZA_ENULL;
-    hipLaunchKernelGGL(gap_fwd_kernel, dim3(cdiv(C, 256), N), dim3(256), 0, (hipStream_t)stream, N, HW, C, (const float *)x, f);
+    if (dtype == STANZA_BF16)
+        hipLaunchKernelGGL(gap_fwd_bf16_kernel, dim3(cdiv(C, 256), N), dim3(256), 0, (hipStream_t)stream, N, HW, C, (const uint16_t *)x, f);
+    else
+        hipLaunchKernelGGL(gap_fwd_kernel, dim3(cdiv(C, 256), N), dim3(256), 0, (hipStream_t)stream, N, HW, C, (const float *)x, f);
     return launch_status();
 }
 
 extern "C" int stanza_gap_bwd(int32_t N, int32_t HW, int32_t C, int32_t dtype, const float *df, void *dx, void *stream)
 {
     if (N <= 0 || HW <= 0 || C <= 0 || (int64_t)N * HW * C >= (int64_t(1) << 31)) return STANZA_EINVAL;
-    if (dtype != STANZA_F32) return STANZA_EUNSUPPORTED;
+    if (dtype != STANZA_F32 && dtype != STANZA_BF16) return STANZA_EUNSUPPORTED;
     if (!df || !dx) return STANZA_ENULL;
     const size_t total = (size_t)N * HW * C;
-    hipLaunchKernelGGL(gap_bwd_kernel, dim3((unsigned)cdiv64(total, 256)), dim3(256), 0, (hipStream_t)stream, total, HW, C, df, (float *)dx);
+    if (dtype == STANZA_BF16)
+        hipLaunchKernelGGL(gap_bwd_bf16_kernel, dim3((unsigned)cdiv64(total, 256)), dim3(256), 0, (hipStream_t)stream, total, HW, C, df, (uint16_t *)dx);
+    else
+        hipLaunchKernelGGL(gap_bwd_kernel, dim3((unsigned)cdiv64(total, 256)), dim3(256), 0, (hipStream_t)stream, total, HW, C, df, (float *)dx);
     return launch_status();
 }
 

@@ -74,7 +74,7 @@ class ConvWorker:
                 self.shapes[op["dst"]] = (n, 1, 1, c)
             self.producer[op["dst"]] = op
         if dtype == api.BF16:
-            assert all(op["op"] in ("conv", "pool") for op in ops), "bf16 stacks: conv and pool ops only"
+            assert all(op["op"] in ("conv", "pool", "bn", "add_relu", "gap") for op in ops), "bf16 stacks: no Inception branches"
         self.buf = {name: torch.empty(shape, device=self.dev, dtype=torch.float32 if name == "x0" else self.tdt)
                     for name, shape in self.shapes.items()}
         if feat_out is not None:
@@ -163,11 +163,13 @@ class ConvWorker:
                 api.stanza_bn_fwd(self.buf[op["src"]], gamma, beta, self.buf[op["dst"]], mean, istd, self.bn_ws, op["eps"], op["relu"],
                                   dtype=self.dtype)
             elif kind == "add_relu":
-                api.stanza_add_relu_fwd(self.buf[op["a"]], self.buf[op["b"]], self.buf[op["dst"]])
+                api.stanza_add_relu_fwd(self.buf[op["a"]], self.buf[op["b"]], self.buf[op["dst"]], self.dtype)
             elif kind == "gap":
-                api.stanza_gap_fwd(self.buf[op["src"]], self.buf[op["dst"]])
+                # the features are float32 in every stack: a bf16 stack's global average pool widens as it sums
+                api.stanza_gap_fwd(self.buf[op["src"]], self.feat32 if self.dtype == api.BF16 else self.buf[op["dst"]], self.dtype)
         if self.dtype == api.BF16:
-            api.stanza_cast_bf16_to_f32(self.buf["feat"], self.feat32)
+            if self.producer["feat"]["op"] != "gap":
+                api.stanza_cast_bf16_to_f32(self.buf["feat"], self.feat32)
             return self.feat32
         return self.buf["feat"]
 
@@ -180,7 +182,7 @@ class ConvWorker:
     def backward(self, dfeat: torch.Tensor):
         """dfeat: float32 gradient of the activations handed to the FC worker, [B, A] or the buffer's own shape."""
         dfeat = dfeat.reshape(self.shapes["feat"])
-        if self.dtype == api.BF16:
+        if self.dtype == api.BF16 and self.producer["feat"]["op"] != "gap":
             api.stanza_cast_f32_to_bf16(dfeat.contiguous(), self.dfeat16)
             dfeat = self.dfeat16
         have: Dict[str, torch.Tensor] = {"feat": dfeat}
@@ -259,7 +261,7 @@ class ConvWorker:
                 gated[op["src"]] = bool(op["relu"])   # [P>0] at the argmax equals [Y>0] there
             elif kind == "add_relu":
                 dz = self._grad_buffer(op["dst"] + "#dz", like=op["dst"])
-                api.stanza_add_relu_bwd(have.pop(op["dst"]), self.buf[op["dst"]], dz)
+                api.stanza_add_relu_bwd(have.pop(op["dst"]), self.buf[op["dst"]], dz, self.dtype)
                 # Both addends receive dz.  They share one tensor: in the reversed op order every reader of
                 # the main-branch gradient runs before the first accumulation into the shortcut's gradient.
                 for name in (op["a"], op["b"]):
@@ -268,7 +270,7 @@ class ConvWorker:
                     gated[name] = False
             elif kind == "gap":
                 dx = self._grad_buffer(op["src"])
-                api.stanza_gap_bwd(have.pop(op["dst"]).view(self.shapes[op["dst"]][0], -1), dx)
+                api.stanza_gap_bwd(have.pop(op["dst"]).view(self.shapes[op["dst"]][0], -1), dx, self.dtype)
                 have[op["src"]] = dx
                 gated[op["src"]] = False
         return self.grads

@@ -243,3 +243,57 @@ def test_fc_worker_with_bf16_hidden_layers(api, o32, dims, n):
             a, b = host(gfm[li][i]).ravel().astype(np.float64), fm_ref[li][i].ravel().astype(np.float64)
             assert a @ b / (np.linalg.norm(a) * np.linalg.norm(b)) > 0.9995 and abs(np.linalg.norm(a) / np.linalg.norm(b) - 1) < 5e-3, (li, i)
     assert (host(fcw.pred) == ref["pred"]).mean() > 0.9
+
+
+@pytest.mark.parametrize("shape", [(2, 5, 7, 8), (3, 14, 14, 256), (1, 1, 1, 2048)])
+def test_residual_join_and_global_average_pool_bf16(api, o32, shape):
+    rng = wl_mod.rng_for(4, "join16", *shape)
+    a = wl_mod.round_bf16(rng.standard_normal(shape, dtype=np.float32))
+    b = wl_mod.round_bf16(rng.standard_normal(shape, dtype=np.float32))
+    o = torch.empty(shape, device="cuda:0", dtype=torch.bfloat16)
+    api.stanza_add_relu_fwd(dev16(a), dev16(b), o, api.BF16)
+    ref = o32.add_relu_fwd(a, b)
+    assert rel_err(host16(o), ref) < TOL_BF16
+    np.testing.assert_array_equal(host16(o) > 0, wl_mod.round_bf16(ref) > 0)
+    dout = wl_mod.round_bf16(rng.standard_normal(shape, dtype=np.float32))
+    dz = torch.empty(shape, device="cuda:0", dtype=torch.bfloat16)
+    api.stanza_add_relu_bwd(dev16(dout), o, dz, api.BF16)
+    np.testing.assert_array_equal(host16(dz), np.where(host16(o) > 0, dout, np.float32(0)))      # a selection: bit-exact
+    n, h, w, c = shape
+    f = torch.empty((n, c), device="cuda:0")
+    api.stanza_gap_fwd(dev16(a), f, api.BF16)
+    assert rel_err(host(f), o32.gap_fwd(a).reshape(n, c)) < 1e-5
+    df = rng.standard_normal((n, c), dtype=np.float32)
+    dx = torch.empty(shape, device="cuda:0", dtype=torch.bfloat16)
+    api.stanza_gap_bwd(dev32(df), dx, api.BF16)
+    assert rel_err(host16(dx), o32.gap_bwd(df, shape)) < TOL_BF16
+
+
+def test_normalised_residual_stack_bf16(api, o32):
+    """The small normalised residual stack (every width a multiple of 8) as a bf16 stack: padded image layer, bias-free
+    convolutions, batch normalisation, residual joins and the global average pool in bf16, features and parameter
+    gradients in float32.  A chain of ~25 bf16 operations: features to a few bf16 roundings, gradients to direction and size."""
+    from oracle import network as onet
+    from paper_1812_10624_amd.netrun import ConvWorker
+    wl = wl_mod.get_workload("miniresbn16")
+    B = 6
+    img = wl_mod.gen_images(wl, 1, 0, B)
+    cp = wl_mod.gen_conv_params(wl, 1)
+    bufs = onet.conv_stack_forward(o32, wl.ops, img, cp)
+    dfeat = np.random.default_rng(13).standard_normal(bufs["feat"].shape, dtype=np.float32)
+    pg, _ = onet.conv_stack_backward(o32, wl.ops, bufs, cp, dfeat)
+    gcp = {n: (dev32(w), None if b is None else dev32(b)) for n, (w, b) in cp.items()}
+    wk = ConvWorker(wl.ops, wl.image, B, gcp, dtype=api.BF16)
+    feat = wk.forward(dev32(img))
+    assert feat.dtype == torch.float32
+    assert rel_err(host(feat), bufs["feat"]) < 5 * TOL_BF16
+    wk.backward(dev32(dfeat).view(B, -1))
+    for n in cp:
+        for which in range(2):
+            if cp[n][which] is None:
+                continue
+            got, want = host(wk.grads[n][which]).ravel().astype(np.float64), pg[n][which].ravel().astype(np.float64)
+            cos = float(got @ want / (np.linalg.norm(got) * np.linalg.norm(want)))
+            # (a normalisation layer's shift gradient here is a vector of 8 to 32 sums: a few flipped ReLU gates move it visibly)
+            assert cos > (0.95 if got.size >= 64 else 0.8), (n, which, cos)
+            assert abs(np.linalg.norm(got) / np.linalg.norm(want) - 1) < (0.15 if got.size >= 64 else 0.3), (n, which)

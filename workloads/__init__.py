@@ -151,14 +151,15 @@ def _resnet50_ops(depths=(3, 4, 6, 3), bn=False):
     return _bottleneck_stack(64, [(w, d, 1 if i == 0 else 2) for i, (w, d) in enumerate(zip((64, 128, 256, 512), depths))], bn)
 
 
-def _mini_res_ops(bn=False):
+def _mini_res_ops(bn=False, mult=1):
     """A three-block residual stack small enough for exhaustive checks: exercises 7x7/2,
-    padded 3x3/2 pooling, 1x1, strided 3x3, projection and identity shortcuts, GAP."""
+    padded 3x3/2 pooling, 1x1, strided 3x3, projection and identity shortcuts, GAP.  mult scales every width
+    (2: all channel counts are multiples of 8, as a bf16 stack needs)."""
     ops = []
-    cur = _res_unit(ops, "stem", "x0", 8, 7, 2, 3, True, bn)
+    cur = _res_unit(ops, "stem", "x0", 8 * mult, 7, 2, 3, True, bn)
     ops.append(_pool(cur, "s0", 3, 2, 1, relu=True))
     cur = "s0"
-    for bi, (width, stride, proj) in enumerate(((4, 1, True), (4, 1, False), (8, 2, True))):
+    for bi, (width, stride, proj) in enumerate(((4 * mult, 1, True), (4 * mult, 1, False), (8 * mult, 2, True))):
         tag = f"b{bi}"
         a = _res_unit(ops, tag + "a", cur, width, 1, 1, 0, True, bn)
         b = _res_unit(ops, tag + "b", a, width, 3, stride, 1, True, bn)
@@ -298,6 +299,9 @@ def get_workload(name: str) -> Workload:
     if name == "miniresbn":
         return Workload("miniresbn", K=2, B=3, image=(33, 35, 3), ops=_mini_res_ops(bn=True),
                         fc_dims=[32, 7], notes="small normalised residual stack for exhaustive parity")
+    if name == "miniresbn16":
+        return Workload("miniresbn16", K=2, B=3, image=(33, 35, 3), ops=_mini_res_ops(bn=True, mult=2),
+                        fc_dims=[64, 7], notes="the small normalised residual stack with every width doubled (multiples of 8)")
     if name == "mlp":
         # 3 hidden layers of 1024, 1024, 4096 units on 3x32x32 inputs, separated after the second hidden layer;
         # the largest row of the paper's table: total batch 1024, base learning rate 0.08, vanilla SGD
@@ -311,7 +315,7 @@ def get_workload(name: str) -> Workload:
 
 
 WORKLOAD_NAMES = ("tiny", "alexnet", "vgg16", "resnet50", "minires", "mlp", "minimlp", "vgg19", "resnet152",
-                  "resnet50bn", "resnet152bn", "miniresbn", "inception3", "miniinception")
+                  "resnet50bn", "resnet152bn", "miniresbn", "miniresbn16", "inception3", "miniinception")
 
 
 def _out_dim(h, win, stride, pad):
