@@ -304,9 +304,9 @@ class FcGradWorker:
     """One of several FC workers: forward, its share of the global-mean loss, backward; gradients are written out
     (no update) for the all-reduce among the FC workers.  n_samples rows are its own, n_global the whole batch."""
 
-    def __init__(self, dims: List[int], n_samples: int, n_global: int, fc_params, device="cuda:0"):
+    def __init__(self, dims: List[int], n_samples: int, n_global: int, fc_params, device="cuda:0", dtype=api.F32):
         self.dev = torch.device(device)
-        self.plan = api.FcPlan(dims, n_samples, 0.0, 0.0, 0.0)
+        self.plan = api.FcPlan(dims, n_samples, 0.0, 0.0, 0.0, compute_dtype=dtype)
         self.n_global = n_global
         self.W = [w for w, _ in fc_params]
         self.b = [b for _, b in fc_params]

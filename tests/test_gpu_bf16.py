@@ -243,6 +243,16 @@ def test_fc_worker_with_bf16_hidden_layers(api, o32, dims, n):
             a, b = host(gfm[li][i]).ravel().astype(np.float64), fm_ref[li][i].ravel().astype(np.float64)
             assert a @ b / (np.linalg.norm(a) * np.linalg.norm(b)) > 0.9995 and abs(np.linalg.norm(a) / np.linalg.norm(b) - 1) < 5e-3, (li, i)
     assert (host(fcw.pred) == ref["pred"]).mean() > 0.9
+    # one of several FC workers (gradients written out, loss normalised by a larger global batch): same arithmetic
+    from paper_1812_10624_amd.netrun import FcGradWorker
+    part = onet.fc_grads(o32, feats, labels, copy.deepcopy(fp), 2 * n)
+    fgw = FcGradWorker(dims, n, 2 * n, [(dev(w), dev(b)) for w, b in fp], dtype=api.BF16)
+    dfe = fgw.step(dev(feats), dev(labels))
+    assert abs(float(host(fgw.loss)[0]) - part["loss"]) < 2e-2 * max(1.0, abs(part["loss"]))
+    assert rel_err(host(dfe), part["dfeats"]) < chain
+    for li in range(len(fp)):
+        assert rel_err(host(fgw.gW[li]), part["grads"][li][0]) < chain, li
+        assert rel_err(host(fgw.gb[li]), part["grads"][li][1]) < chain, li
 
 
 @pytest.mark.parametrize("shape", [(2, 5, 7, 8), (3, 14, 14, 256), (1, 1, 1, 2048)])
