@@ -443,10 +443,10 @@ WgradPlan plan_wgrad(const ConvGeo &g, bool want_bias, int bk)
     const int chunks = (int)cdiv64(red, bk);
     const int bm = M <= 64 ? 64 : 128, bn = Nn <= 64 ? 64 : 128;
     const int tiles = cdiv(M, bm) * cdiv(Nn, bn);
-    // A whole number of rounds of workgroups and never a few items more: 1026 items on 256 CUs take as long as 1280.  The float32
-    // kernel keeps three workgroups resident per CU and runs best as exactly one such round; the bf16 one, whose items are
-    // several times shorter, as four per CU (measured over the VGG-16-shaped layers, 2 to 12 per CU).
-    const int resident = (bk == BKH ? 4 : 3) * CUS;
+    // A whole number of rounds of workgroups and never a few items more: 1026 items on 256 CUs take as long as 1280.  Both kernels
+    // keep four workgroups resident per CU and run best as exactly one such round (measured over the VGG-16-shaped layers, 2 to
+    // 12 items per CU: five is slower than four, eight equals it at twice the partial sums).
+    const int resident = 4 * CUS;
     int splits = resident / tiles;
     splits = max(1, min(splits, chunks / 8));
     pl.chunks_per_split = cdiv(chunks, splits);
