@@ -202,8 +202,9 @@ __global__ __launch_bounds__(NTHREADS, 2) void igemm_bf16_kernel(const GemmParam
 #pragma unroll
     for (int e = 0; e < 8; ++e) dbacc[e] = 0.f;
 
-    // Issue the global loads of stage `ch` into register set `set`.  Stages past the end are fetched fully masked.
-    auto fetch = [&](int ch, auto set_c) {
+    // Issue part `part` of `nparts` of the global loads of stage `ch` into register set `set` (vector i belongs to part
+    // i % nparts; the running state of the fast path moves on with the last part).  Stages past the end are fetched fully masked.
+    auto fetch = [&](int ch, auto set_c, int part, int nparts) {
         constexpr int set = decltype(set_c)::value;
         const bool kok = ch < nchunks;
         if (FAST) {
@@ -225,12 +226,17 @@ __global__ __launch_bounds__(NTHREADS, 2) void igemm_bf16_kernel(const GemmParam
             const uint32_t koff = kok ? 0u : OOB_OFF;
 #pragma unroll
             for (int i = 0; i < AV; ++i) {
+                if (i % nparts != part) continue;
                 const uint32_t bo = (uint32_t)(a_row[i] * 2 + sa) | koff | ((~(a_mask[i] >> f_tap) & 1u) << 31);
                 ra[set][i] = bload16(rsrc_a, bo);
                 if (MODE == MODE_BWD_DATA && amask) rg[set][i] = bload16(rsrc_g, bo);
             }
 #pragma unroll
-            for (int i = 0; i < BV; ++i) rb[set][i] = bload16(rsrc_b, (uint32_t)(b_row[i] * 2 + sb) | koff | b_oob[i]);
+            for (int i = 0; i < BV; ++i) {
+                if (i % nparts != part) continue;
+                rb[set][i] = bload16(rsrc_b, (uint32_t)(b_row[i] * 2 + sb) | koff | b_oob[i]);
+            }
+            if (part != nparts - 1) return;
             ++f_tap;
             ++f_as;
             const int wrap_s = f_as == tapS, wrap_t = f_tap == tapRS;
@@ -246,6 +252,7 @@ __global__ __launch_bounds__(NTHREADS, 2) void igemm_bf16_kernel(const GemmParam
 #pragma unroll
         // (validity as 0 / 1 integers combined with &, and masked lanes by setting bit 31 of the offset: see the fast path)
         for (int i = 0; i < AV; ++i) {
+            if (i % nparts != part) continue;
             int off;
             uint32_t ok;
             if (MODE == MODE_FWD || MODE == MODE_BWD_DATA) {
@@ -274,6 +281,7 @@ __global__ __launch_bounds__(NTHREADS, 2) void igemm_bf16_kernel(const GemmParam
         }
 #pragma unroll
         for (int i = 0; i < BV; ++i) {
+            if (i % nparts != part) continue;
             int off;
             uint32_t ok;
             if (MODE == MODE_FWD) {
@@ -302,12 +310,14 @@ __global__ __launch_bounds__(NTHREADS, 2) void igemm_bf16_kernel(const GemmParam
         }
     };
 
-    // Gate and write register set `set` into LDS buffer `buf`.
-    auto stash = [&](auto set_c, int buf) {
+    // Gate and write part `part` of `nparts` of register set `set` into LDS buffer `buf` (vector v of the AV + BV vectors
+    // belongs to part v * nparts / (AV + BV)).
+    auto stash = [&](auto set_c, int buf, int part, int nparts) {
         constexpr int set = decltype(set_c)::value;
         uint16_t *As = smem + buf * STAGE, *Bs = As + A_ELEMS;
 #pragma unroll
         for (int i = 0; i < AV; ++i) {
+            if (i * nparts / (AV + BV) != part) continue;
             uint4 v = ra[set][i];
             if (MODE != MODE_FWD && amask) v = gate8(v, rg[set][i]);
             if (A_KMAJ) {
@@ -319,10 +329,11 @@ __global__ __launch_bounds__(NTHREADS, 2) void igemm_bf16_kernel(const GemmParam
         }
 #pragma unroll
         for (int i = 0; i < BV; ++i) {
+            if ((AV + i) * nparts / (AV + BV) != part) continue;
             if (B_KMAJ) *reinterpret_cast<uint4 *>(&Bs[(t / B_F8 + B_RP * i) * LDBK + (t % B_F8) * 8]) = rb[set][i];
             else *reinterpret_cast<uint4 *>(&Bs[(row0 + RPP * i) * LDR + kq * 8]) = rb[set][i];
         }
-        if (A_KMAJ && want_db) {      // one workgroup-uniform branch per stage, after the stores
+        if (A_KMAJ && want_db && part == nparts - 1) {      // one workgroup-uniform branch per stage, after the stores
 #pragma unroll
             for (int i = 0; i < AV; ++i)
 #pragma unroll
@@ -342,66 +353,128 @@ __global__ __launch_bounds__(NTHREADS, 2) void igemm_bf16_kernel(const GemmParam
     // transpose-read lane roles: 16-lane group G covers tile rows 16*(G&1).. and reduction rows 8*(G>>1)..
     const int tr_m = 16 * ((lane >> 4) & 1) + 4 * (lane & 3), tr_k = 8 * (lane >> 5) + ((lane >> 2) & 3);
 
-    auto compute = [&](int buf) {
+    // MFMA operands of one k-step, two register slots: slot (ks & 1) is multiplied while the other is being read.
+    bf16x8 av[2][TM], bv[2][TN];
+    auto load_ops = [&](int buf, int ks, auto slot_c) {
+        constexpr int slot = decltype(slot_c)::value;
         const uint16_t *As = smem + buf * STAGE, *Bs = As + A_ELEMS;
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks) {
-            bf16x8 av[TM], bv[TN];
-#pragma unroll
-            for (int i = 0; i < TM; ++i) {
-                if (A_KMAJ) {
-                    const uint16_t *q = &As[(ks * 16 + tr_k) * LDAK + wave_m * WTM + i * 32 + tr_m];
-                    const s16x4 lo = lds_tr4(q), hi = lds_tr4(q + 4 * LDAK);
-                    av[i] = __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
-                } else {
-                    av[i] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4 *>(&As[(wave_m * WTM + i * 32 + lrow) * LDR + ks * 16 + lk * 8]));
-                }
+        for (int i = 0; i < TM; ++i) {
+            if (A_KMAJ) {
+                const uint16_t *q = &As[(ks * 16 + tr_k) * LDAK + wave_m * WTM + i * 32 + tr_m];
+                const s16x4 lo = lds_tr4(q), hi = lds_tr4(q + 4 * LDAK);
+                av[slot][i] = __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+            } else {
+                av[slot][i] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4 *>(&As[(wave_m * WTM + i * 32 + lrow) * LDR + ks * 16 + lk * 8]));
             }
-#pragma unroll
-            for (int j = 0; j < TN; ++j) {
-                if (B_KMAJ) {
-                    const uint16_t *q = &Bs[(ks * 16 + tr_k) * LDBK + wave_n * WTN + j * 32 + tr_m];
-                    const s16x4 lo = lds_tr4(q), hi = lds_tr4(q + 4 * LDBK);
-                    bv[j] = __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
-                } else {
-                    bv[j] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4 *>(&Bs[(wave_n * WTN + j * 32 + lrow) * LDR + ks * 16 + lk * 8]));
-                }
-            }
-#pragma unroll
-            for (int i = 0; i < TM; ++i)
-#pragma unroll
-                for (int j = 0; j < TN; ++j)
-                    acc[i][j] = SWAP ? __builtin_amdgcn_mfma_f32_32x32x16_bf16(bv[j], av[i], acc[i][j], 0, 0, 0)
-                                     : __builtin_amdgcn_mfma_f32_32x32x16_bf16(av[i], bv[j], acc[i][j], 0, 0, 0);
         }
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+            if (B_KMAJ) {
+                const uint16_t *q = &Bs[(ks * 16 + tr_k) * LDBK + wave_n * WTN + j * 32 + tr_m];
+                const s16x4 lo = lds_tr4(q), hi = lds_tr4(q + 4 * LDBK);
+                bv[slot][j] = __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+            } else {
+                bv[slot][j] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4 *>(&Bs[(wave_n * WTN + j * 32 + lrow) * LDR + ks * 16 + lk * 8]));
+            }
+        }
+    };
+    auto mfma = [&](auto slot_c, int i, int j) {
+        constexpr int slot = decltype(slot_c)::value;
+        acc[i][j] = SWAP ? __builtin_amdgcn_mfma_f32_32x32x16_bf16(bv[slot][j], av[slot][i], acc[i][j], 0, 0, 0)
+                         : __builtin_amdgcn_mfma_f32_32x32x16_bf16(av[slot][i], bv[slot][j], acc[i][j], 0, 0, 0);
     };
 
     constexpr std::integral_constant<int, 0> S0{};
     constexpr std::integral_constant<int, 1> S1{};
-    if constexpr (PREFETCH2) {
-        fetch(0, S0);
-        stash(S0, 0);
-        fetch(1, S1);
-        __syncthreads();
+    static_assert(KS % 2 == 0 && KS >= 4, "operand slots alternate by k-step and a stage ends on slot 1");
+    // One stage = KS k-steps.  K-step ks: read the operands of k-step ks + 1 (of the NEXT stage's k-step 0 in the last one), then
+    // its MFMAs with a slice of the global fetch after the first and a slice of the LDS writes of the next stage after the
+    // second.  The LDS writes end with k-step KS - 2, whose MFMAs are followed by the stage's one barrier: after it the next
+    // stage's buffer is complete (so its k-step 0 can be read under the last k-step's MFMAs) and nobody reads the buffer that
+    // the stage after it will overwrite (a stage's last LDS reads are issued before its barrier).
+    auto stage = [&](int ch, auto par_c) {
+        constexpr int par = decltype(par_c)::value;
+        constexpr std::integral_constant<int, PREFETCH2 ? par : 0> set_f{};          // fetch target
+        constexpr std::integral_constant<int, PREFETCH2 ? (par ^ 1) : 0> set_s{};    // register set written to LDS
+        const int fch = ch + (PREFETCH2 ? 2 : 1);
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            if (ks < KS - 1) {
+                if (ks & 1) load_ops(par, ks + 1, S0); else load_ops(par, ks + 1, S1);
+            } else {
+                load_ops(par ^ 1, 0, S0);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            int n = 0;
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j) {
+                    if (ks & 1) mfma(S1, i, j); else mfma(S0, i, j);
+                    __builtin_amdgcn_sched_barrier(0);
+                    if (n == 0) {
+                        // two register sets: the fetch is spread over the k-steps; one set: all of it first, its LDS writes last
+                        if (PREFETCH2) fetch(fch, set_f, ks, KS);
+                        else if (ks == 0) fetch(fch, set_f, 0, 1);
+                        __builtin_amdgcn_sched_barrier(0);
+                    }
+                    if (n == (TM * TN > 1 ? 1 : 0)) {
+                        if (PREFETCH2) { if (ks < KS - 1) stash(set_s, par ^ 1, ks, KS - 1); }
+                        else if (ks == KS - 2) stash(set_s, par ^ 1, 0, 1);
+                        __builtin_amdgcn_sched_barrier(0);
+                    }
+                    ++n;
+                }
+            if (ks == KS - 2) {
+                __syncthreads();
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+    };
+
+    // A stage left to the compiler's own schedule: used when a wavefront has fewer than four MFMAs per k-step (64-row or
+    // 64-column tiles), too few to cover a k-step's reads one step ahead; there the pinned order above is the slower one.
+    auto compute = [&](int buf) {
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            load_ops(buf, ks, S0);
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j) mfma(S0, i, j);
+        }
+    };
+
+    fetch(0, S0, 0, 1);
+    stash(S0, 0, 0, 1);
+    if constexpr (PREFETCH2) fetch(1, S1, 0, 1);
+    __syncthreads();
+    if constexpr (TM * TN >= 4) {
+        load_ops(0, 0, S0);
+        __builtin_amdgcn_sched_barrier(0);
         for (int ch = 0; ch < nchunks; ch += 2) {
-            fetch(ch + 2, S0);
+            stage(ch, S0);
+            if (ch + 1 >= nchunks) break;
+            stage(ch + 1, S1);
+        }
+    } else if constexpr (PREFETCH2) {
+        for (int ch = 0; ch < nchunks; ch += 2) {
+            fetch(ch + 2, S0, 0, 1);
             compute(0);
-            stash(S1, 1);
+            stash(S1, 1, 0, 1);
             __syncthreads();
             if (ch + 1 >= nchunks) break;
-            fetch(ch + 3, S1);
+            fetch(ch + 3, S1, 0, 1);
             compute(1);
-            stash(S0, 0);
+            stash(S0, 0, 0, 1);
             __syncthreads();
         }
     } else {
-        fetch(0, S0);
-        stash(S0, 0);
-        __syncthreads();
         for (int ch = 0; ch < nchunks; ++ch) {
-            fetch(ch + 1, S0);
+            fetch(ch + 1, S0, 0, 1);
             compute(ch & 1);
-            stash(S0, (ch + 1) & 1);
+            stash(S0, (ch + 1) & 1, 0, 1);
             __syncthreads();
         }
     }
