@@ -154,7 +154,9 @@ int stanza_gap_fwd(int32_t N, int32_t HW, int32_t C, int32_t dtype, const void *
 int stanza_gap_bwd(int32_t N, int32_t HW, int32_t C, int32_t dtype, const float *df, void *dx, void *stream);
 
 /* ---- Average-pool branch and channel concatenation of the Inception blocks (the paper trains Inception-V3, Sec. 6.1,
- * without describing its layers: plain definitions).  float32 only.
+ * without describing its layers: plain definitions).  The average pool takes dtype = STANZA_F32 or STANZA_BF16 (then
+ * C % 8 == 0; sums in float32, one rounding at the store); the copy moves 4-byte elements, so a bfloat16 tensor is copied as
+ * pairs (even lengths and offsets).
  *   avgpool_fwd: y[n,p,q,c] = mean of x over the part of the window inside the image (padding is not counted);
  *   avgpool_bwd: dx[n,h,w,c] = sum over the windows (p,q) containing (h,w) of dy[n,p,q,c] / (valid elements of (p,q)).
  *   desc as for the max-pool (flags ignored; any window size; every window must reach the image).

@@ -214,9 +214,14 @@ def stanza_avgpool_bwd(d: PoolDesc, dy, dx, dtype=F32):
 
 
 def stanza_copy2d(rows: int, cols: int, src, src_off: int, src_ld: int, dst, dst_off: int, dst_ld: int):
-    """dst[dst_off + r*dst_ld + j] = src[src_off + r*src_ld + j] for r < rows, j < cols (float32 elements)."""
-    assert src.is_cuda and dst.is_cuda and src.is_contiguous() and dst.is_contiguous() and src.dtype == dst.dtype == torch.float32
+    """dst[dst_off + r*dst_ld + j] = src[src_off + r*src_ld + j] for r < rows, j < cols, in elements of the tensors' type.
+    The library copies 4-byte elements: bfloat16 tensors go as pairs, so every length and offset must be even."""
+    assert src.is_cuda and dst.is_cuda and src.is_contiguous() and dst.is_contiguous() and src.dtype == dst.dtype
+    assert src.dtype in (torch.float32, torch.bfloat16)
     assert src_off + (rows - 1) * src_ld + cols <= src.numel() and dst_off + (rows - 1) * dst_ld + cols <= dst.numel()
+    if src.dtype == torch.bfloat16:
+        assert cols % 2 == 0 and src_off % 2 == 0 and src_ld % 2 == 0 and dst_off % 2 == 0 and dst_ld % 2 == 0
+        cols, src_off, src_ld, dst_off, dst_ld = cols // 2, src_off // 2, src_ld // 2, dst_off // 2, dst_ld // 2
     _check(load().stanza_copy2d(rows, cols, C.c_void_p(src.data_ptr() + 4 * src_off), src_ld, C.c_void_p(dst.data_ptr() + 4 * dst_off), dst_ld,
                                 _stream()), "stanza_copy2d")
 

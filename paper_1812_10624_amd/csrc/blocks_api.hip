@@ -86,6 +86,72 @@ __global__ __launch_bounds__(256) void avgpool_bwd_kernel(const AvgGeo g, const 
     else dst[0] = acc[0];
 }
 
+// bfloat16 forms of the two kernels above: 8 channels (16 bytes) per thread, sums in float32, one rounding at the store.
+__device__ __forceinline__ float bf16_up(uint32_t h) { return __uint_as_float(h << 16); }
+__device__ __forceinline__ uint32_t bf16_down(float f)
+{
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (u >> 16) | 0x40u;
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return u >> 16;
+}
+__device__ __forceinline__ void acc8(float (&acc)[8], const uint4 &v, float scale)
+{
+    const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        acc[2 * e] = fmaf(bf16_up(w[e] & 0xffffu), scale, acc[2 * e]);
+        acc[2 * e + 1] = fmaf(bf16_up(w[e] >> 16), scale, acc[2 * e + 1]);
+    }
+}
+__device__ __forceinline__ uint4 pack8(const float (&a)[8], float scale)
+{
+    return make_uint4(bf16_down(a[0] * scale) | (bf16_down(a[1] * scale) << 16), bf16_down(a[2] * scale) | (bf16_down(a[3] * scale) << 16),
+                      bf16_down(a[4] * scale) | (bf16_down(a[5] * scale) << 16), bf16_down(a[6] * scale) | (bf16_down(a[7] * scale) << 16));
+}
+
+__global__ __launch_bounds__(256) void avgpool_fwd_bf16_kernel(const AvgGeo g, const uint4 *__restrict__ x, uint4 *__restrict__ y, size_t total)
+{
+    const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= total) return;
+    const int cv = g.C / 8;
+    const int c = (int)(idx % cv);
+    size_t t = idx / cv;
+    const int q = (int)(t % g.Wo); t /= g.Wo;
+    const int p = (int)(t % g.Ho);
+    const int n = (int)(t / g.Ho);
+    const int h0 = p * g.sh - g.ph, w0 = q * g.sw - g.pw;
+    float acc[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) acc[e] = 0.f;
+    for (int i = max(h0, 0); i < min(h0 + g.wh, g.H); ++i)
+        for (int j = max(w0, 0); j < min(w0 + g.ww, g.W); ++j) acc8(acc, x[(((size_t)n * g.H + i) * g.W + j) * cv + c], 1.f);
+    y[idx] = pack8(acc, 1.f / (float)(avg_valid(p, g.sh, g.ph, g.wh, g.H) * avg_valid(q, g.sw, g.pw, g.ww, g.W)));
+}
+
+__global__ __launch_bounds__(256) void avgpool_bwd_bf16_kernel(const AvgGeo g, const uint4 *__restrict__ dy, uint4 *__restrict__ dx, size_t total)
+{
+    const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= total) return;
+    const int cv = g.C / 8;
+    const int c = (int)(idx % cv);
+    size_t t = idx / cv;
+    const int w = (int)(t % g.W); t /= g.W;
+    const int h = (int)(t % g.H);
+    const int n = (int)(t / g.H);
+    const int p_lo = max((h + g.ph - g.wh + g.sh) / g.sh, 0), p_hi = min((h + g.ph) / g.sh, g.Ho - 1);
+    const int q_lo = max((w + g.pw - g.ww + g.sw) / g.sw, 0), q_hi = min((w + g.pw) / g.sw, g.Wo - 1);
+    float acc[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) acc[e] = 0.f;
+    for (int p = p_lo; p <= p_hi; ++p) {
+        const int nh = avg_valid(p, g.sh, g.ph, g.wh, g.H);
+        for (int q = q_lo; q <= q_hi; ++q)
+            acc8(acc, dy[(((size_t)n * g.Ho + p) * g.Wo + q) * cv + c], 1.f / (float)(nh * avg_valid(q, g.sw, g.pw, g.ww, g.W)));
+    }
+    dx[idx] = pack8(acc, 1.f);
+}
+
 // dst[r*dst_ld + j] = src[r*src_ld + j], j < cols (all in elements of VW floats).
 template <int VW>
 __global__ __launch_bounds__(256) void copy2d_kernel(size_t total, int cols, size_t src_ld, size_t dst_ld, const float *__restrict__ src,
@@ -126,10 +192,15 @@ extern "C" int stanza_avgpool_fwd(const stanza_pool_desc *desc, int32_t dtype, c
     AvgGeo g;
     int rc = avg_geometry(desc, &g);
     if (rc) return rc;
-    if (dtype != STANZA_F32) return STANZA_EUNSUPPORTED;
+    if (dtype != STANZA_F32 && !(dtype == STANZA_BF16 && g.C % 8 == 0)) return STANZA_EUNSUPPORTED;
     if (!x || !y) return STANZA_ENULL;
     if (!aligned16(x) || !aligned16(y)) return STANZA_EALIGN;
     const size_t outs = (size_t)g.N * g.Ho * g.Wo * g.C;
+    if (dtype == STANZA_BF16) {
+        hipLaunchKernelGGL(avgpool_fwd_bf16_kernel, dim3((unsigned)cdiv64(outs / 8, 256)), dim3(256), 0, (hipStream_t)stream, g, (const uint4 *)x, (uint4 *)y,
+                           outs / 8);
+        return launch_status();
+    }
     if (g.C % 4 == 0)
         hipLaunchKernelGGL(avgpool_fwd_kernel<4>, dim3((unsigned)cdiv64(outs / 4, 256)), dim3(256), 0, (hipStream_t)stream, g, (const float *)x, (float *)y, outs / 4);
     else
@@ -143,10 +214,15 @@ extern "C" int stanza_avgpool_bwd(const stanza_pool_desc *desc, int32_t dtype, c
     AvgGeo g;
     int rc = avg_geometry(desc, &g);
     if (rc) return rc;
-    if (dtype != STANZA_F32) return STANZA_EUNSUPPORTED;
+    if (dtype != STANZA_F32 && !(dtype == STANZA_BF16 && g.C % 8 == 0)) return STANZA_EUNSUPPORTED;
     if (!dy || !dx) return STANZA_ENULL;
     if (!aligned16(dy) || !aligned16(dx)) return STANZA_EALIGN;
     const size_t ins = (size_t)g.N * g.H * g.W * g.C;
+    if (dtype == STANZA_BF16) {
+        hipLaunchKernelGGL(avgpool_bwd_bf16_kernel, dim3((unsigned)cdiv64(ins / 8, 256)), dim3(256), 0, (hipStream_t)stream, g, (const uint4 *)dy, (uint4 *)dx,
+                           ins / 8);
+        return launch_status();
+    }
     if (g.C % 4 == 0)
         hipLaunchKernelGGL(avgpool_bwd_kernel<4>, dim3((unsigned)cdiv64(ins / 4, 256)), dim3(256), 0, (hipStream_t)stream, g, (const float *)dy, (float *)dx, ins / 4);
     else

@@ -74,7 +74,7 @@ class ConvWorker:
                 self.shapes[op["dst"]] = (n, 1, 1, c)
             self.producer[op["dst"]] = op
         if dtype == api.BF16:
-            assert all(op["op"] in ("conv", "pool", "bn", "add_relu", "gap") for op in ops), "bf16 stacks: no Inception branches"
+            assert all(op["op"] in ("conv", "pool", "avgpool", "concat", "bn", "add_relu", "gap") for op in ops)
         self.buf = {name: torch.empty(shape, device=self.dev, dtype=torch.float32 if name == "x0" else self.tdt)
                     for name, shape in self.shapes.items()}
         if feat_out is not None:
@@ -150,7 +150,7 @@ class ConvWorker:
             elif kind == "pool":
                 api.stanza_pool_relu_fwd(self.descs[i], self.buf[op["src"]], self.buf[op["dst"]], self.argmax[op["dst"]], self.dtype)
             elif kind == "avgpool":
-                api.stanza_avgpool_fwd(self.descs[i], self.buf[op["src"]], self.buf[op["dst"]])
+                api.stanza_avgpool_fwd(self.descs[i], self.buf[op["src"]], self.buf[op["dst"]], self.dtype)
             elif kind == "concat":
                 at = 0
                 for sname in op["srcs"]:
@@ -228,7 +228,7 @@ class ConvWorker:
             elif kind == "avgpool":
                 dx = self._grad_buffer(op["src"])
                 assert op["src"] not in have, "a pooling branch must be the last reader of its input in the op list"
-                api.stanza_avgpool_bwd(self.descs[i], have.pop(op["dst"]), dx)
+                api.stanza_avgpool_bwd(self.descs[i], have.pop(op["dst"]), dx, self.dtype)
                 have[op["src"]] = dx
                 gated[op["src"]] = False
             elif kind == "concat":

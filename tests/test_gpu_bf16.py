@@ -307,3 +307,79 @@ def test_normalised_residual_stack_bf16(api, o32):
             # (a normalisation layer's shift gradient here is a vector of 8 to 32 sums: a few flipped ReLU gates move it visibly)
             assert cos > (0.95 if got.size >= 64 else 0.8), (n, which, cos)
             assert abs(np.linalg.norm(got) / np.linalg.norm(want) - 1) < (0.15 if got.size >= 64 else 0.3), (n, which)
+
+
+@pytest.mark.parametrize("geom", [(2, 35, 35, 48, 3, 1, 1), (2, 8, 8, 64, 3, 1, 1), (1, 9, 11, 8, 5, 3, 2), (2, 12, 12, 8, 2, 2, 0)])
+def test_avgpool_bf16(api, o32, geom):
+    n, h, w, c, win, stride, pad = geom
+    g = PoolGeom(n, h, w, c, win, stride, pad, False)
+    x = _draw((n, h, w, c), 31)
+    d = api.pool_desc(n, h, w, c, win, stride, pad, False)
+    y = torch.empty((n, g.Ho, g.Wo, c), dtype=torch.bfloat16, device="cuda:0")
+    api.stanza_avgpool_fwd(d, dev16(x), y, api.BF16)
+    # float32 sums of exact bf16 values, one rounding at the store: half a bf16 step
+    assert rel_err(host16(y), o32.avgpool_fwd(g, x)) < 2.0 ** -8 * 1.01
+    dy = _draw((n, g.Ho, g.Wo, c), 32)
+    dx = torch.empty((n, h, w, c), dtype=torch.bfloat16, device="cuda:0")
+    api.stanza_avgpool_bwd(d, dev16(dy), dx, api.BF16)
+    assert rel_err(host16(dx), o32.avgpool_bwd(g, dy)) < 2.0 ** -8 * 1.01
+    with pytest.raises(api.StanzaError):      # 8 channels per 16-byte vector
+        api.stanza_avgpool_fwd(api.pool_desc(1, 8, 8, 12, 3, 1, 1, False), dev16(_draw((1, 8, 8, 12), 33)),
+                               torch.empty((1, 8, 8, 12), dtype=torch.bfloat16, device="cuda:0"), api.BF16)
+
+
+@pytest.mark.parametrize("rows,cs,cd,cols,so,do", [(50, 16, 48, 16, 0, 32), (50, 48, 16, 16, 32, 0), (1000, 64, 288, 64, 0, 224), (33, 8, 20, 6, 2, 6)])
+def test_copy_channels_bf16(api, rows, cs, cd, cols, so, do):
+    src, dst0 = _draw((rows, cs), 34), _draw((rows, cd), 35)
+    dst = dev16(dst0)
+    api.stanza_copy_channels(dev16(src), so, dst, do, cols)
+    ref = dst0.copy()
+    ref[:, do:do + cols] = src[:, so:so + cols]
+    np.testing.assert_array_equal(host16(dst), ref)                 # byte work: bit-exact, nothing else touched
+
+
+def test_inception_stack_bf16(api, o32):
+    """One Inception block of every kind at half the published widths as a bf16 stack (average-pool branches and channel
+    concatenations in bf16 too), at the published image size.  Every op of the stack has its own bf16 parity test and the
+    float32 stack, which shares the sequencing, matches the checker to 1e-4; this is the whole chain: ~45 bf16 layers.
+    Features: direction and size.  Parameter gradients: size to 15 % (filters), direction loosely: behind the global average pool the
+    gradient is constant over the 8x8 positions of an image, the normalisation layers' backward pass subtracts its mean over
+    the 128 values of a channel, and what is left is a small difference of large numbers that carries the bf16 rounding of
+    everything before it (the first normalisation layer alone takes the cosine from 1.00 to 0.94, the same stack in float32
+    stays at 1.0000)."""
+    import dataclasses
+    from oracle import network as onet
+    from paper_1812_10624_amd.netrun import ConvWorker
+    wl = dataclasses.replace(wl_mod.get_workload("miniinception8"), image=(299, 299, 3))
+    B = 2
+    img = wl_mod.gen_images(wl, 1, 0, B)
+    cp = wl_mod.gen_conv_params(wl, 1)
+    bufs = onet.conv_stack_forward(o32, wl.ops, img, cp)
+    dfeat = np.random.default_rng(14).standard_normal(bufs["feat"].shape, dtype=np.float32)
+    pg, _ = onet.conv_stack_backward(o32, wl.ops, bufs, cp, dfeat)
+    gcp = {n: (dev32(w), None if b is None else dev32(b)) for n, (w, b) in cp.items()}
+    wk = ConvWorker(wl.ops, wl.image, B, gcp, dtype=api.BF16)
+    feat = wk.forward(dev32(img))
+    assert feat.dtype == torch.float32
+    got, want = host(feat).ravel().astype(np.float64), bufs["feat"].ravel().astype(np.float64)
+    fcos = float(got @ want / (np.linalg.norm(got) * np.linalg.norm(want)))
+    fl2 = float(np.linalg.norm(got - want) / np.linalg.norm(want))
+    assert fcos > 0.998 and fl2 < 0.06, (fcos, fl2)
+    # every intermediate activation keeps its direction
+    for op in wl.ops:
+        if op["dst"] == "feat":
+            continue
+        a, b = host16(wk.buf[op["dst"]]).ravel().astype(np.float64), bufs[op["dst"]].ravel().astype(np.float64)
+        assert float(a @ b / (np.linalg.norm(a) * np.linalg.norm(b))) > 0.98, op["dst"]
+    wk.backward(dev32(dfeat).view(B, -1))
+    for n in cp:
+        for which in range(2):
+            if cp[n][which] is None:
+                continue
+            got, want = host(wk.grads[n][which]).ravel().astype(np.float64), pg[n][which].ravel().astype(np.float64)
+            assert np.isfinite(got).all(), (n, which)
+            if got.size >= 64:
+                cos = float(got @ want / (np.linalg.norm(got) * np.linalg.norm(want)))
+                assert cos > 0.65, (n, which, cos)
+                # (a normalisation layer's 64 to 224 sums move more than a filter's thousands)
+                assert abs(np.linalg.norm(got) / np.linalg.norm(want) - 1) < (0.15 if got.size >= 1024 else 0.3), (n, which)

@@ -296,6 +296,10 @@ def get_workload(name: str) -> Workload:
         ops = _inception_v3_ops(width_div=16, blocks=(1, 1, 1))
         return Workload("miniinception", K=2, B=2, image=(139, 139, 3), ops=ops, fc_dims=[2048 // 16, 10],
                         notes="one block of each kind at a sixteenth of the widths, for exhaustive parity")
+    if name == "miniinception8":
+        ops = _inception_v3_ops(width_div=2, blocks=(1, 1, 1))
+        return Workload("miniinception8", K=2, B=2, image=(139, 139, 3), ops=ops, fc_dims=[2048 // 2, 10],
+                        notes="one block of each kind at half the widths (every width a multiple of 8), for the bf16 stack")
     if name == "miniresbn":
         return Workload("miniresbn", K=2, B=3, image=(33, 35, 3), ops=_mini_res_ops(bn=True),
                         fc_dims=[32, 7], notes="small normalised residual stack for exhaustive parity")
@@ -315,7 +319,7 @@ def get_workload(name: str) -> Workload:
 
 
 WORKLOAD_NAMES = ("tiny", "alexnet", "vgg16", "resnet50", "minires", "mlp", "minimlp", "vgg19", "resnet152",
-                  "resnet50bn", "resnet152bn", "miniresbn", "miniresbn16", "inception3", "miniinception")
+                  "resnet50bn", "resnet152bn", "miniresbn", "miniresbn16", "inception3", "miniinception", "miniinception8")
 
 
 def _out_dim(h, win, stride, pad):
