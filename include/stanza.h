@@ -94,7 +94,8 @@ typedef struct {
     int32_t compute_dtype;    /* STANZA_F32, or STANZA_BF16: the hidden layers' GEMMs read bfloat16 copies of the features, */
                               /* activations, gradients and weights (products accumulate in float32); the last layer, the */
                               /* loss, all parameters, momentum buffers, gradients written out and dfeats stay float32. */
-                              /* Needs every width but the last to be a multiple of 8; not combined with dropout. */
+                              /* Needs every width but the last to be a multiple of 8.  Dropout then acts on the bfloat16 */
+                              /* activations: same masks, kept units scaled in float32 and rounded once. */
 } stanza_fc_desc;
 
 const char *stanza_strerror(int status);

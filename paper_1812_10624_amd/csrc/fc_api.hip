@@ -123,6 +123,50 @@ __global__ __launch_bounds__(256) void scale_kernel(size_t numel, float scale, f
     }
 }
 
+// bfloat16 forms for the hidden layers kept in bf16: the same generator blocks (element i takes word i % 4 of block i / 4), two
+// blocks = 8 elements = one 16-byte vector per thread; kept elements are scaled in float32 and rounded once.  numel % 8 == 0.
+__device__ __forceinline__ uint32_t bf16_scale_pair(uint32_t pair, float s_lo, float s_hi)
+{
+    auto one = [](uint32_t h, float s) -> uint32_t {
+        uint32_t u = __float_as_uint(__uint_as_float(h << 16) * s);
+        if ((u & 0x7fffffffu) > 0x7f800000u) return (u >> 16) | 0x40u;
+        u += 0x7fffu + ((u >> 16) & 1u);
+        return u >> 16;
+    };
+    return one(pair & 0xffffu, s_lo) | (one(pair >> 16, s_hi) << 16);
+}
+__global__ __launch_bounds__(256) void dropout_bf16_kernel(size_t numel, uint32_t thr, float scale, PhiloxKey key, uint4 *y)
+{
+    const size_t v = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (v * 8 >= numel) return;
+    uint32_t r0[4], r1[4];
+    philox4x32_10((uint32_t)(2 * v), (uint32_t)((2 * v) >> 32), key.s0, key.s1, key.k0, key.k1, r0);
+    philox4x32_10((uint32_t)(2 * v + 1), (uint32_t)((2 * v + 1) >> 32), key.s0, key.s1, key.k0, key.k1, r1);
+    float sc[8];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        sc[e] = r0[e] >= thr ? scale : 0.f;
+        sc[4 + e] = r1[e] >= thr ? scale : 0.f;
+    }
+    uint4 x = y[v];
+    x.x = bf16_scale_pair(x.x, sc[0], sc[1]);
+    x.y = bf16_scale_pair(x.y, sc[2], sc[3]);
+    x.z = bf16_scale_pair(x.z, sc[4], sc[5]);
+    x.w = bf16_scale_pair(x.w, sc[6], sc[7]);
+    y[v] = x;
+}
+__global__ __launch_bounds__(256) void scale_bf16_kernel(size_t numel, float scale, uint4 *y)
+{
+    const size_t v = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (v * 8 >= numel) return;
+    uint4 x = y[v];
+    x.x = bf16_scale_pair(x.x, scale, scale);
+    x.y = bf16_scale_pair(x.y, scale, scale);
+    x.z = bf16_scale_pair(x.z, scale, scale);
+    x.w = bf16_scale_pair(x.w, scale, scale);
+    y[v] = x;
+}
+
 // Momentum-SGD update from a gradient in memory (the bf16 hidden layers: their filter-gradient kernel has no fused update).
 __global__ __launch_bounds__(256) void sgd_update_kernel(size_t numel, float *__restrict__ w, float *__restrict__ v, const float *__restrict__ g,
                                                          float lr, float mom, float wd)
@@ -274,7 +318,6 @@ static int fc_run(const stanza_fc_desc *desc, int n_global, const float *feats, 
     hipStream_t st = (hipStream_t)stream;
     float *base = (float *)ws;
     const bool half = desc->compute_dtype == STANZA_BF16;   // hidden layers in bf16, the last layer and the loss in float32
-    if (half && desc->dropout_p > 0.f) return STANZA_EUNSUPPORTED;
     const bool drop = desc->dropout_p > 0.f;
     const uint32_t drop_thr = dropout_threshold(desc->dropout_p);
     const float drop_scale = 1.f / (1.f - desc->dropout_p);
@@ -289,6 +332,12 @@ static int fc_run(const stanza_fc_desc *desc, int n_global, const float *feats, 
             const stanza_conv_desc cd = fc_conv_desc(n, dims[l - 1], dims[l], STANZA_BF16, STANZA_CONV_BIAS | STANZA_CONV_RELU);
             if ((rc = stanza_cast_f32_to_bf16((int64_t)dims[l] * dims[l - 1], host_W[l - 1], w16(l), stream))) return rc;   // this step's copy
             if ((rc = stanza_conv_fwd(&cd, a16(l - 1), w16(l), host_b[l - 1], a16(l), nullptr, 0, stream))) return rc;
+            if (drop) {    // the next layer, the float32 copy for the last layer and the backward pass see the dropped activations
+                const size_t numel = (size_t)n * dims[l];
+                hipLaunchKernelGGL(dropout_bf16_kernel, dim3((unsigned)cdiv64(numel / 8, 256)), dim3(256), 0, st, numel, drop_thr, drop_scale,
+                                   dropout_key(desc->dropout_seed, (desc->dropout_step << 8) | (uint64_t)(l - 1)), (uint4 *)a16(l));
+                if ((rc = launch_status())) return rc;
+            }
         }
         if (L > 1 && (rc = stanza_cast_bf16_to_f32((int64_t)n * dims[L - 1], a16(L - 1), base + lay.act_off[L - 1], stream))) return rc;
     }
@@ -327,6 +376,11 @@ static int fc_run(const stanza_fc_desc *desc, int n_global, const float *feats, 
             const stanza_conv_desc cd = fc_conv_desc(n, in, out, STANZA_BF16, STANZA_CONV_BIAS);
             void *dx16 = l == 1 ? (void *)(base + lay.dfeats16_off) : dz16_next;
             if ((rc = stanza_conv_bwd_data(&cd, dz16, nullptr, w16(l), l == 1 ? nullptr : a16(l - 1), dx16, nullptr, 0, stream))) return rc;
+            if (drop && l > 1) {   // the gate used the dropped activations (see the float32 path below): the kept units' scale remains
+                const size_t numel = (size_t)n * in;
+                hipLaunchKernelGGL(scale_bf16_kernel, dim3((unsigned)cdiv64(numel / 8, 256)), dim3(256), 0, st, numel, drop_scale, (uint4 *)dx16);
+                if ((rc = launch_status())) return rc;
+            }
             if (l == 1 && (rc = stanza_cast_bf16_to_f32((int64_t)n * in, dx16, dfeats, stream))) return rc;
             float *dw = fused ? base + lay.dw_off : host_gW[l - 1];
             float *db = fused ? base + lay.dbh_off : host_gb[l - 1];

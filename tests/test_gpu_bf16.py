@@ -383,3 +383,34 @@ def test_inception_stack_bf16(api, o32):
                 assert cos > 0.65, (n, which, cos)
                 # (a normalisation layer's 64 to 224 sums move more than a filter's thousands)
                 assert abs(np.linalg.norm(got) / np.linalg.norm(want) - 1) < (0.15 if got.size >= 1024 else 0.3), (n, which)
+
+
+def test_fc_worker_bf16_hidden_layers_with_dropout(api, o32):
+    """Seeded dropout on the bf16 hidden activations: the same masks as the float32 worker draws (they depend on seed, step,
+    layer and element index alone), kept units scaled by 1/(1-p); two steps, so that the step counter moves the masks."""
+    import copy
+    from oracle import network as onet
+    from paper_1812_10624_amd.netrun import FcWorker
+    dims, n, p, seed = [64, 96, 48, 10], 24, 0.4, 1234
+    rng = wl_mod.rng_for(10, "fc16drop", *dims)
+    feats = wl_mod.round_bf16(np.abs(rng.standard_normal((n, dims[0]), dtype=np.float32)))
+    labels = rng.integers(0, dims[-1], size=n, dtype=np.int32)
+    fp = [((rng.standard_normal((o, i), dtype=np.float32) * np.float32(0.15 / i ** 0.5)),
+           (rng.choice([-1.0, 1.0], size=o) + rng.standard_normal(o) * 0.05).astype(np.float32)) for i, o in zip(dims[:-1], dims[1:])]
+    fm = [(np.zeros_like(w), np.zeros_like(b)) for w, b in fp]
+    fp_ref, fm_ref = copy.deepcopy(fp), copy.deepcopy(fm)
+    gfp = [(dev(w), dev(b)) for w, b in fp]
+    gfm = [(dev(w), dev(b)) for w, b in fm]
+    fcw = FcWorker(dims, n, gfp, gfm, 0.05, 0.9, 1e-4, dropout=(p, seed), dtype=api.BF16)
+    chain = 5 * TOL_BF16
+    for step in range(2):
+        ref = onet.fc_step(o32, feats, labels, fp_ref, fm_ref, 0.05, 0.9, 1e-4, dropout=(p, seed, step))
+        dfeats = fcw.step(dev(feats), dev(labels))
+        assert abs(float(host(fcw.loss)[0]) - ref["loss"]) < 2e-2 * max(1.0, abs(ref["loss"])), step
+        assert rel_err(host(dfeats), ref["dfeats"]) < chain, step
+        for li in range(len(fp)):
+            for i in range(2):
+                assert rel_err(host(gfm[li][i]), fm_ref[li][i]) < chain, (step, li, i)
+    # a dropped unit's column of the next layer's weight gradient is exactly zero: the masks themselves agree
+    drop0 = ref["acts"][1] == 0
+    assert 0.3 < drop0.mean() < 0.9
