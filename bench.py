@@ -77,7 +77,7 @@ def main():
     feats = torch.randn((n, wl.fc_dims[0]), device=dev, generator=gen).clamp_(min=0)   # filler rows of the other workers
     worker = ConvWorker(wl.ops, wl.image, B, cp, dtype=api.BF16 if args.dtype == "bf16" else api.F32, feat_out=feats[:B])
     fcw = FcWorker(wl.fc_dims, n, fp, fm, wl.lr, wl.momentum, wl.weight_decay, dropout=(args.dropout, seed) if args.dropout > 0 else None,
-                   dtype=api.BF16 if (args.dtype == "bf16" and args.dropout == 0 and all(d % 8 == 0 for d in wl.fc_dims[:-1])) else api.F32)
+                   dtype=api.BF16 if (args.dtype == "bf16" and all(d % 8 == 0 for d in wl.fc_dims[:-1])) else api.F32)
     shard0 = W.flat_tensors(worker.grads)
     shards = [shard0] + [[torch.randn(t.shape, device=dev, generator=gen) * 1e-3 for t in shard0] for _ in range(K - 1)]
     agg = Aggregator(W.flat_tensors(cp), W.flat_tensors(cm), shards)
