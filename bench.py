@@ -250,7 +250,7 @@ def main():
     out["ps_aggregate_k16"] = ps_config5(torch, api, W, dev)
     if args.dtype == "bf16":
         # the conv GEMMs run on the bf16 matrix pipe (the 3-channel first layer and the FC worker stay f32)
-        out["roofline"] = {"bound": "mfma", "kernel": "stanza::igemm_bf16_kernel (conv fwd / bwd_data / bwd_weight launches; first layer in f32)",
+        out["roofline"] = {"bound": "mfma", "kernel": "stanza::igemm_bf16_kernel (conv fwd / bwd_data / bwd_weight launches of the conv stack)",
                            "achieved": conv_tflops, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                            "frac": conv_tflops / MFMA_BF16_PEAK_TFLOPS, "traffic": None,
                            "algorithmic_gflop_per_step": (fwd_f + bwd_f) / 1e9, "kernel_ms_per_step": conv_ms}
