@@ -135,3 +135,60 @@ def test_random_large_conv_f32(api, o32, seed):
 @pytest.mark.parametrize("seed", range(6))
 def test_random_large_conv_bf16(api, o32, seed):
     _run(api, o32, 900 + seed, True, big=True)
+
+
+def _pool_case(seed):
+    r = np.random.default_rng(3000 + seed)
+    win = int(r.choice([2, 2, 3, 3, 4, 5]))
+    st = int(r.integers(1, win + 1))
+    pad = int(r.integers(0, (win + 1) // 2)) if r.random() < 0.5 else 0       # pad <= win / 2: every window reaches the image
+    H, W = int(r.integers(win, 40)), int(r.integers(win, 40))
+    N = int(r.integers(1, 5))
+    C = int(r.integers(1, 70))
+    return N, H, W, C, win, st, pad, bool(r.random() < 0.5)
+
+
+@pytest.mark.parametrize("seed", range(40))
+def test_random_pools(api, o32, seed):
+    """Max pool (+ReLU) with its argmax byte and backward pass, and the average pool, float32 and (C % 8 == 0) bfloat16."""
+    from oracle import PoolGeom
+    N, H, W, C, win, st, pad, relu = _pool_case(seed)
+    half = seed % 3 == 2
+    if half:
+        C = 8 * ((C + 7) // 8)
+    g = PoolGeom(N, H, W, C, win, st, pad, relu)
+    r = np.random.default_rng(4000 + seed)
+    q = wl_mod.round_bf16 if half else (lambda a: a)
+    x = q(r.standard_normal((N, H, W, C), dtype=np.float32))
+    dy = q(r.standard_normal((N, g.Ho, g.Wo, C), dtype=np.float32))
+    DT, tdt = (api.BF16, torch.bfloat16) if half else (api.F32, torch.float32)
+    what = (seed, N, H, W, C, win, st, pad, relu, half)
+
+    def up(a):
+        if not half:
+            return dev(a)
+        return torch.from_numpy(wl_mod.bf16_bits(a).view(np.int16)).to("cuda:0").view(torch.bfloat16).reshape(a.shape)
+
+    def down(t):
+        if not half:
+            return host(t)
+        torch.cuda.synchronize()
+        return wl_mod.bf16_to_f32(t.view(torch.int16).cpu().numpy().view(np.uint16)).reshape(tuple(t.shape))
+
+    d = api.pool_desc(N, H, W, C, win, st, pad, relu)
+    y_ref, am_ref = o32.pool_relu_fwd(g, x)
+    y = torch.full(y_ref.shape, float("nan"), device="cuda:0").to(tdt)
+    am = torch.full(y_ref.shape, 255, dtype=torch.uint8, device="cuda:0")
+    api.stanza_pool_relu_fwd(d, up(x), y, am, DT)
+    np.testing.assert_array_equal(down(y), y_ref, err_msg=str(what))            # a selection: bit-exact
+    np.testing.assert_array_equal(host(am), am_ref, err_msg=str(what))
+    dx = torch.full(x.shape, float("nan"), device="cuda:0").to(tdt)
+    api.stanza_pool_relu_bwd(d, up(dy), y, am, dx, DT)
+    # overlapping windows add their gradients: float32 sums in both dtypes, one rounding to bf16
+    assert rel_err(down(dx), o32.pool_relu_bwd(g, dy, y_ref, am_ref)) < (2.0 ** -8 * 1.01 if half else 1e-5), what
+    ya = torch.full(y_ref.shape, float("nan"), device="cuda:0").to(tdt)
+    api.stanza_avgpool_fwd(d, up(x), ya, DT)
+    assert rel_err(down(ya), o32.avgpool_fwd(g, x)) < (2.0 ** -8 * 1.01 if half else 1e-5), what
+    dxa = torch.full(x.shape, float("nan"), device="cuda:0").to(tdt)
+    api.stanza_avgpool_bwd(d, up(dy), dxa, DT)
+    assert rel_err(down(dxa), o32.avgpool_bwd(g, dy)) < (2.0 ** -8 * 1.01 if half else 1e-5), what
