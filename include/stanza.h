@@ -112,6 +112,13 @@ int stanza_version(void);
 size_t stanza_conv_workspace_bytes(const stanza_conv_desc *desc, int which);
 int stanza_conv_fwd(const stanza_conv_desc *desc, const void *x, const void *w, const float *bias,
                     void *y, void *ws, size_t ws_bytes, void *stream);
+/* The same with a residual join in the epilogue (the residual networks of the paper's table of models, Sec. 6.1; the join itself
+ * is not described there: the published one):  y = conv(x, w) + bias + res, then max(.,0) with STANZA_CONV_RELU, i.e. the
+ * convolution followed by stanza_add_relu_fwd without the intermediate tensor.  res: [N,Ho,Wo,K] of the dtype of y, 16-byte
+ * aligned, must not overlap y; required (NULL is STANZA_ENULL).  The backward pass of the join is stanza_add_relu_bwd on y as
+ * before; the convolution's own backward calls then take that gradient ungated. */
+int stanza_conv_fwd_res(const stanza_conv_desc *desc, const void *x, const void *w, const float *bias, const void *res,
+                        void *y, void *ws, size_t ws_bytes, void *stream);
 
 /* ---- CONV worker: backpropagation to the layer input (Sec. 3.2: "CONV workers then continue the
  * backpropagation"):

@@ -20,7 +20,7 @@ CONV_BIAS, CONV_RELU, CONV_ACCUM = 1, 2, 4
 POOL_RELU = 1
 
 EXPORTS = (
-    "stanza_strerror", "stanza_version", "stanza_conv_workspace_bytes", "stanza_conv_fwd", "stanza_conv_bwd_data",
+    "stanza_strerror", "stanza_version", "stanza_conv_workspace_bytes", "stanza_conv_fwd", "stanza_conv_fwd_res", "stanza_conv_bwd_data",
     "stanza_conv_bwd_weight", "stanza_pool_relu_fwd", "stanza_pool_relu_bwd", "stanza_add_relu_fwd",
     "stanza_add_relu_bwd", "stanza_gap_fwd", "stanza_gap_bwd", "stanza_cast_f32_to_bf16", "stanza_cast_bf16_to_f32",
     "stanza_bn_workspace_bytes", "stanza_bn_fwd", "stanza_bn_bwd", "stanza_avgpool_fwd", "stanza_avgpool_bwd", "stanza_copy2d",
@@ -73,6 +73,7 @@ def load() -> C.CDLL:
     lib.stanza_conv_workspace_bytes.restype = sz
     lib.stanza_conv_workspace_bytes.argtypes = [C.POINTER(ConvDesc), C.c_int]
     lib.stanza_conv_fwd.argtypes = [C.POINTER(ConvDesc), vp, vp, vp, vp, vp, sz, vp]
+    lib.stanza_conv_fwd_res.argtypes = [C.POINTER(ConvDesc), vp, vp, vp, vp, vp, vp, sz, vp]
     lib.stanza_conv_bwd_data.argtypes = [C.POINTER(ConvDesc), vp, vp, vp, vp, vp, vp, sz, vp]
     lib.stanza_conv_bwd_weight.argtypes = [C.POINTER(ConvDesc), vp, vp, vp, vp, vp, vp, sz, vp]
     lib.stanza_pool_relu_fwd.argtypes = [C.POINTER(PoolDesc), i32, vp, vp, vp, vp]
@@ -157,6 +158,11 @@ def stanza_conv_workspace_bytes(d: ConvDesc, which: int) -> int:
 def stanza_conv_fwd(d: ConvDesc, x, w, bias, y, ws=None):
     p, n = _ws(ws)
     _check(load().stanza_conv_fwd(C.byref(d), _ptr(x), _ptr(w), _ptr(bias), _ptr(y), p, n, _stream()), "stanza_conv_fwd")
+
+
+def stanza_conv_fwd_res(d: ConvDesc, x, w, bias, res, y, ws=None):
+    p, n = _ws(ws)
+    _check(load().stanza_conv_fwd_res(C.byref(d), _ptr(x), _ptr(w), _ptr(bias), _ptr(res), _ptr(y), p, n, _stream()), "stanza_conv_fwd_res")
 
 
 def stanza_conv_bwd_data(d: ConvDesc, dy, y, w, x_mask, dx, ws=None):

@@ -178,6 +178,7 @@ __global__ __launch_bounds__(256) void slice_fixup_kernel(const GemmParams p, in
         float v = f4at(acc, e);
         if (mode == MODE_FWD) {
             if (p.flags & EPI_BIAS) v += p.bias[col + e];
+            if (p.flags & EPI_RESIDUAL) v += p.res[o + e];
             if (p.flags & EPI_RELU) v = fmaxf(v, 0.f);
         } else {
             if (p.flags & EPI_ACCUM) v += p.out[o + e];
@@ -498,8 +499,8 @@ static int launch_any(const stanza_conv_desc *d, int mode, GemmParams &p, int sp
     return launch_igemm(mode, p, 1, (float *)ws, ws ? ws_bytes / 4 : 0, st);
 }
 
-extern "C" int stanza_conv_fwd(const stanza_conv_desc *desc, const void *x, const void *w, const float *bias, void *y,
-                               void *ws, size_t ws_bytes, void *stream)
+static int conv_fwd_any(const stanza_conv_desc *desc, const void *x, const void *w, const float *bias, const void *res, bool want_res, void *y,
+                        void *ws, size_t ws_bytes, void *stream)
 {
     if (!desc) return STANZA_ENULL;
     GemmParams p{};
@@ -507,17 +508,30 @@ extern "C" int stanza_conv_fwd(const stanza_conv_desc *desc, const void *x, cons
     if (rc) return rc;
     if ((rc = check_dtype(desc))) return rc;
     const bool has_bias = desc->flags & STANZA_CONV_BIAS;
-    if (!x || !w || !y || (has_bias && !bias)) return STANZA_ENULL;
-    if (!aligned16(x) || !aligned16(w) || !aligned16(y) || !aligned16(bias) || !aligned16(ws)) return STANZA_EALIGN;
+    if (!x || !w || !y || (has_bias && !bias) || (want_res && !res)) return STANZA_ENULL;
+    if (!aligned16(x) || !aligned16(w) || !aligned16(y) || !aligned16(bias) || !aligned16(ws) || !aligned16(res)) return STANZA_EALIGN;
     p.a = (const float *)x;
     p.b = (const float *)w;
     p.out = (float *)y;
     p.bias = bias;
+    p.res = (const float *)res;
     p.M = p.g.N * p.g.Ho * p.g.Wo;
     p.Nn = p.g.K;
     p.Kd = p.g.R * p.g.S * p.g.C;
-    p.flags = (has_bias ? EPI_BIAS : 0u) | ((desc->flags & STANZA_CONV_RELU) ? EPI_RELU : 0u);
+    p.flags = (has_bias ? EPI_BIAS : 0u) | ((desc->flags & STANZA_CONV_RELU) ? EPI_RELU : 0u) | (want_res ? EPI_RESIDUAL : 0u);
     return launch_any(desc, MODE_FWD, p, 1, ws, ws_bytes, (hipStream_t)stream);
+}
+
+extern "C" int stanza_conv_fwd(const stanza_conv_desc *desc, const void *x, const void *w, const float *bias, void *y,
+                               void *ws, size_t ws_bytes, void *stream)
+{
+    return conv_fwd_any(desc, x, w, bias, nullptr, false, y, ws, ws_bytes, stream);
+}
+
+extern "C" int stanza_conv_fwd_res(const stanza_conv_desc *desc, const void *x, const void *w, const float *bias, const void *res,
+                                   void *y, void *ws, size_t ws_bytes, void *stream)
+{
+    return conv_fwd_any(desc, x, w, bias, res, true, y, ws, ws_bytes, stream);
 }
 
 extern "C" int stanza_conv_bwd_data(const stanza_conv_desc *desc, const void *dy, const void *y, const void *w,

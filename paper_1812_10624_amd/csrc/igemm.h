@@ -36,6 +36,7 @@ enum { MODE_FWD = 0, MODE_BWD_DATA = 1, MODE_BWD_WEIGHT = 2 };
 enum : uint32_t {
     EPI_BIAS = 1u,     // FWD: + bias[j]
     EPI_RELU = 2u,     // FWD: max(.,0)
+    EPI_RESIDUAL = 512u,   // FWD: + res[row][col] (a residual join: the shortcut's tensor, same shape as the output) before the ReLU
     EPI_ACCUM = 4u,    // BWD_DATA: += previous contents
     EPI_XMASK = 8u,    // BWD_DATA: * [xmask > 0]
     EPI_SGD = 16u,     // BWD_WEIGHT: fused momentum-SGD update of sgd_w / sgd_v with the tile as gradient
@@ -87,6 +88,7 @@ struct GemmParams {
     float *dbias;         // EPI_DBIAS: [M] or split partials (stride dbias_stride floats per slice)
     size_t dbias_stride;
     float *sgd_w, *sgd_v; // EPI_SGD
+    const float *res;     // EPI_RESIDUAL (element type of the output)
     float lr, mom, wd;
     int M, Nn, Kd;        // GEMM extents (Kd = full reduction length)
     int tilesM, tilesN, tiles;
@@ -648,6 +650,10 @@ __global__ __launch_bounds__(NTHREADS, (BM >= 256 ? 3 : (VECA && VECB) ? 4 : 2))
                         const float4 b = ldg4(p.bias + col);
                         v.x += b.x; v.y += b.y; v.z += b.z; v.w += b.w;
                     }
+                    if (p.flags & EPI_RESIDUAL) {
+                        const float4 rr = ldg4(p.res + o);
+                        v.x += rr.x; v.y += rr.y; v.z += rr.z; v.w += rr.w;
+                    }
                     if (p.flags & EPI_RELU) v = make_float4(fmaxf(v.x, 0.f), fmaxf(v.y, 0.f), fmaxf(v.z, 0.f), fmaxf(v.w, 0.f));
                 } else {
                     if (p.flags & EPI_ACCUM) {
@@ -706,6 +712,7 @@ __global__ __launch_bounds__(NTHREADS, (BM >= 256 ? 3 : (VECA && VECB) ? 4 : 2))
                 float v = acc[i][j][r];
                 if (MODE == MODE_FWD) {
                     v += bias;
+                    if (p.flags & EPI_RESIDUAL) v += p.res[o];
                     if (p.flags & EPI_RELU) v = fmaxf(v, 0.f);
                     p.out[o] = v;
                 } else if (MODE == MODE_BWD_DATA) {

@@ -546,6 +546,15 @@ __global__ __launch_bounds__(NTHREADS, 2) void igemm_bf16_kernel(const GemmParam
                         const int row_l = wave_m * WTM + i * 32 + lrow - half * CROWS;
                         float v0 = acc[i][j][4 * q4 + 0] + bias.x, v1 = acc[i][j][4 * q4 + 1] + bias.y;
                         float v2 = acc[i][j][4 * q4 + 2] + bias.z, v3 = acc[i][j][4 * q4 + 3] + bias.w;
+                        if (MODE == MODE_FWD && (p.flags & EPI_RESIDUAL)) {
+                            // residual join: the shortcut's bf16 tensor is added in float32, before the ReLU and the one rounding
+                            const int row = m0 + wave_m * WTM + i * 32 + lrow;
+                            if (row < p.M && n0 + col_l < p.Nn) {
+                                const uint2 rr = *reinterpret_cast<const uint2 *>(reinterpret_cast<const uint16_t *>(p.res) + out_index(row, n0 + col_l));
+                                v0 += bf16_to_f32((uint16_t)(rr.x & 0xffffu)); v1 += bf16_to_f32((uint16_t)(rr.x >> 16));
+                                v2 += bf16_to_f32((uint16_t)(rr.y & 0xffffu)); v3 += bf16_to_f32((uint16_t)(rr.y >> 16));
+                            }
+                        }
                         if (MODE == MODE_FWD && (p.flags & EPI_RELU)) {
                             v0 = fmaxf(v0, 0.f); v1 = fmaxf(v1, 0.f); v2 = fmaxf(v2, 0.f); v3 = fmaxf(v3, 0.f);
                         }

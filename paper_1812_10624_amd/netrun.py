@@ -73,6 +73,23 @@ class ConvWorker:
                 n, h, w, c = self.shapes[op["src"]]
                 self.shapes[op["dst"]] = (n, 1, 1, c)
             self.producer[op["dst"]] = op
+        # A convolution without ReLU whose only reader is the residual join that follows it in the op list runs as
+        # stanza_conv_fwd_res: the join's output is written by the convolution's epilogue and its own output never exists.
+        # (Backward is unchanged: the join's gate reads the join's output, the convolution takes the gated gradient as it is.)
+        self.joined = {}                          # conv op index -> (join op index, name of the other addend)
+        self.join_desc = {}                       # conv op index -> its descriptor with the join's ReLU
+        for i, op in enumerate(ops[:-1]):
+            nxt = ops[i + 1]
+            if op["op"] != "conv" or op["relu"] or nxt["op"] != "add_relu" or op["dst"] not in (nxt["a"], nxt["b"]) or nxt["a"] == nxt["b"]:
+                continue
+            readers = sum(1 for o in ops if op["dst"] in (o.get("src"), o.get("a"), o.get("b")) or op["dst"] in o.get("srcs", ()))
+            if readers != 1 or i in self.padded or self.f32_layer[i]:
+                continue
+            other = nxt["b"] if nxt["a"] == op["dst"] else nxt["a"]
+            self.joined[i] = (i + 1, other)
+            self.join_desc[i] = api.ConvDesc.from_buffer_copy(self.descs[i])
+            self.join_desc[i].flags |= api.CONV_RELU
+        self.skip_fwd = {j for j, _ in self.joined.values()}
         if dtype == api.BF16:
             assert all(op["op"] in ("conv", "pool", "avgpool", "concat", "bn", "add_relu", "gap") for op in ops)
         self.buf = {name: torch.empty(shape, device=self.dev, dtype=torch.float32 if name == "x0" else self.tdt)
@@ -126,7 +143,16 @@ class ConvWorker:
             self.buf["x0"].copy_(images)
         for i, op in enumerate(self.ops):
             kind = op["op"]
-            if kind == "conv":
+            if i in self.skip_fwd:                  # a residual join computed by the preceding convolution's epilogue
+                continue
+            if kind == "conv" and i in self.joined:
+                w, b = self.params[op["name"]]
+                j, other = self.joined[i]
+                if self.dtype == api.BF16:
+                    api.stanza_cast_f32_to_bf16(w, self.w16[op["name"]])
+                    w = self.w16[op["name"]]
+                api.stanza_conv_fwd_res(self.join_desc[i], self.buf[op["src"]], w, b, self.buf[other], self.buf[self.ops[j]["dst"]], self.ws)
+            elif kind == "conv":
                 w, b = self.params[op["name"]]
                 if i in self.padded:
                     c = self.padded[i]

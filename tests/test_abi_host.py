@@ -55,6 +55,10 @@ def test_conv_errors_before_launch(api):
     assert lib.stanza_conv_fwd(C.byref(big), p16, p16, None, p16, None, 0, None) == -1
     bad_dtype = api.conv_desc(2, 8, 8, 4, 8, 3, 3, 1, 1, 7, 0)
     assert lib.stanza_conv_fwd(C.byref(bad_dtype), p16, p16, None, p16, None, 0, None) == -4
+    # residual join in the epilogue: the residual is required and aligned like every tensor
+    assert lib.stanza_conv_fwd_res(C.byref(good), p16, p16, p16, None, p16, None, 0, None) == -2
+    assert lib.stanza_conv_fwd_res(C.byref(good), p16, p16, p16, p4, p16, None, 0, None) == -3
+    assert lib.stanza_conv_fwd_res(None, p16, p16, p16, p16, p16, None, 0, None) == -2
     assert lib.stanza_conv_bwd_data(C.byref(good), p16, None, p16, None, None, None, 0, None) == -2
     assert lib.stanza_conv_bwd_data(C.byref(good), p16, None, p16, p4, p16, None, 0, None) == -3
     # filter gradient: workspace is mandatory and sized by the query

@@ -414,3 +414,19 @@ def test_fc_worker_bf16_hidden_layers_with_dropout(api, o32):
     # a dropped unit's column of the next layer's weight gradient is exactly zero: the masks themselves agree
     drop0 = ref["acts"][1] == 0
     assert 0.3 < drop0.mean() < 0.9
+
+
+@pytest.mark.parametrize("case", [(2, 14, 14, 64, 160, 1, 1, 1, 0), (3, 13, 13, 32, 72, 3, 3, 1, 1), (16, 56, 56, 32, 128, 1, 1, 1, 0)],
+                         ids=lambda c: "n{}h{}w{}c{}k{}r{}s{}st{}p{}".format(*c))
+def test_conv_bf16_with_residual_join(api, o32, case):
+    N, H, W, C, K, R, S, st, pad = case
+    g = ConvGeom(N, H, W, C, K, R, S, st, pad)
+    x, w = _draw((N, H, W, C), 41), _draw((K, R, S, C), 42, (1.0 / (R * S * C)) ** 0.5)
+    b = np.random.default_rng(43).standard_normal(K, dtype=np.float32)
+    res = _draw((N, g.Ho, g.Wo, K), 44)
+    ref = np.maximum(o32.conv_fwd(g, x, w, b, relu=False).astype(np.float64) + res, 0).astype(np.float32)
+    d = api.conv_desc(N, H, W, C, K, R, S, st, pad, api.BF16, api.CONV_BIAS | api.CONV_RELU)
+    y = torch.empty((N, g.Ho, g.Wo, K), dtype=torch.bfloat16, device="cuda:0")
+    api.stanza_conv_fwd_res(d, dev16(x), dev16(w), dev32(b), dev16(res), y)
+    assert rel_err(host16(y), ref) < TOL_BF16
+    assert (host16(y) >= 0).all()

@@ -530,3 +530,34 @@ def test_several_fc_workers(api, o32, name, K, n_f):
         for i in range(2):
             assert rel_err(host(gcm[nm][i]), cm_ref[nm][i]) < 5 * TOL_F32, (nm, i)
             assert rel_err(host(gpar[nm][i]), cp_ref[nm][i]) < 1e-5, (nm, i)
+
+
+# residual join in the convolution's epilogue: vector and scalar output paths, sliced tiles (workspace), 64- and 128-wide tiles
+@pytest.mark.parametrize("case", [(2, 14, 14, 64, 160, 1, 1, 1, 0), (3, 13, 13, 16, 72, 3, 3, 1, 1), (2, 9, 9, 6, 10, 3, 3, 1, 0),
+                                  (2, 15, 15, 24, 40, 1, 1, 2, 0), (16, 56, 56, 32, 128, 1, 1, 1, 0), (8, 1, 1, 2048, 256, 1, 1, 1, 0)], ids=_ids)
+@pytest.mark.parametrize("relu", [True, False])
+def test_conv_forward_with_residual_join(api, o32, case, relu):
+    N, H, W, C, K, R, S, st, pad = case
+    g = ConvGeom(N, H, W, C, K, R, S, st, pad)
+    r = rng(21)
+    x = r.standard_normal((N, H, W, C), dtype=np.float32)
+    w = (r.standard_normal((K, R, S, C), dtype=np.float32) / np.sqrt(R * S * C)).astype(np.float32)
+    b = r.standard_normal(K, dtype=np.float32)
+    res = r.standard_normal((N, g.Ho, g.Wo, K), dtype=np.float32)
+    z = (o32.conv_fwd(g, x, w, b, relu=False).astype(np.float64) + res).astype(np.float32)
+    ref = np.maximum(z, 0) if relu else z
+    d = api.conv_desc(N, H, W, C, K, R, S, st, pad, api.F32, api.CONV_BIAS | (api.CONV_RELU if relu else 0))
+    for with_ws in (False, True):
+        ws = torch.empty(max(16, api.stanza_conv_workspace_bytes(d, 0)), dtype=torch.uint8, device="cuda:0") if with_ws else None
+        y = torch.full(ref.shape, float("nan"), device="cuda:0")
+        api.stanza_conv_fwd_res(d, dev(x), dev(w), dev(b), dev(res), y, ws)
+        assert rel_err(host(y), ref) < TOL_F32, (case, relu, with_ws)
+    if relu:      # the same thing as the convolution followed by the join
+        y1 = torch.empty(ref.shape, device="cuda:0")
+        d0 = api.conv_desc(N, H, W, C, K, R, S, st, pad, api.F32, api.CONV_BIAS)
+        api.stanza_conv_fwd(d0, dev(x), dev(w), dev(b), y1)
+        o = torch.empty_like(y1)
+        api.stanza_add_relu_fwd(y1, dev(res), o)
+        y2 = torch.empty_like(y1)
+        api.stanza_conv_fwd_res(d, dev(x), dev(w), dev(b), dev(res), y2)
+        assert torch.equal(o, y2)
