@@ -80,6 +80,7 @@ def main():
     worker = ConvWorker(wl.ops, wl.image, B, cp, dtype=api.BF16 if args.dtype == "bf16" else api.F32, feat_out=feats[:B])
     fcw = FcWorker(wl.fc_dims, n, fp, fm, wl.lr, wl.momentum, wl.weight_decay, dropout=(args.dropout, seed) if args.dropout > 0 else None,
                    dtype=api.BF16 if (args.dtype == "bf16" and all(d % 8 == 0 for d in wl.fc_dims[:-1])) else api.F32)
+    joined_ops = sorted(worker.joined)           # ops that run with the residual join fused into their epilogue
     shard0 = W.flat_tensors(worker.grads)
     shards = [shard0] + [[torch.randn(t.shape, device=dev, generator=gen) * 1e-3 for t in shard0] for _ in range(K - 1)]
     agg = Aggregator(W.flat_tensors(cp), W.flat_tensors(cm), shards)
@@ -109,6 +110,8 @@ def main():
                 return lambda *a, **kw: timed(k, real[k], *a, **kw)
             if k == "stanza_conv_fwd_res":      # a forward convolution with the residual join in its epilogue: counted with the others
                 return lambda *a, **kw: timed("stanza_conv_fwd", api.stanza_conv_fwd_res, *a, **kw)
+            if k == "stanza_bn_fwd_res":        # likewise a normalisation layer with the join fused in
+                return lambda *a, **kw: timed("stanza_bn_fwd", api.stanza_bn_fwd_res, *a, **kw)
             return getattr(api, k)
     tap = _Tap()
 
@@ -212,9 +215,11 @@ def main():
             pool_b += esz * n_out + n_out + (esz * n_out if op["relu"] else 0) + esz * n_in   # dy, argmax, y (gate) read, dx written
     # normalisation layers: forward reads x twice (statistics, then apply) and writes y; backward reads x and dy twice, writes dx
     bn_elems = sum(float(np.prod(shapes_all[op["src"]])) for op in wl.ops if op["op"] == "bn")
+    # (a layer with the residual join fused in also reads the shortcut's tensor)
+    bn_join_elems = sum(float(np.prod(shapes_all[wl.ops[i]["src"]])) for i in joined_ops if wl.ops[i]["op"] == "bn")
     hbm_kernels = {}
     for tag, by in (("stanza_pool_relu_fwd", pool_f), ("stanza_pool_relu_bwd", pool_b),
-                    ("stanza_bn_fwd", 3 * esz * bn_elems), ("stanza_bn_bwd", 5 * esz * bn_elems)):
+                    ("stanza_bn_fwd", 3 * esz * bn_elems + esz * bn_join_elems), ("stanza_bn_bwd", 5 * esz * bn_elems)):
         if tag in tot and by > 0:
             gbs = by / (tot[tag] * 1e-3) / 1e9
             hbm_kernels[tag] = {"algorithmic_bytes_per_step": by, "ms_per_step": tot[tag], "GBps": gbs, "frac_hbm": gbs / HBM_PEAK_GBS}

@@ -199,6 +199,12 @@ size_t stanza_bn_workspace_bytes(int64_t rows, int32_t C, int32_t dtype);
 int stanza_bn_fwd(int64_t rows, int32_t C, int32_t dtype, float eps, int32_t relu, const void *x, const float *gamma,
                   const float *beta, void *y, float *save_mean, float *save_istd, float *running_mean, float *running_var,
                   float momentum, void *ws, size_t ws_bytes, void *stream);
+/* Forward with a residual join fused in (the residual blocks of the published networks end in normalisation, join, ReLU):
+ *   y = bn(x) + res, then max(.,0) when relu != 0; res [rows][C] of the dtype of x, 16-byte aligned, not overlapping y, required.
+ * Statistics and running averages as in stanza_bn_fwd.  Backward: stanza_add_relu_bwd on y, then stanza_bn_bwd with relu = 0. */
+int stanza_bn_fwd_res(int64_t rows, int32_t C, int32_t dtype, float eps, int32_t relu, const void *x, const float *gamma,
+                      const float *beta, const void *res, void *y, float *save_mean, float *save_istd, float *running_mean,
+                      float *running_var, float momentum, void *ws, size_t ws_bytes, void *stream);
 int stanza_bn_bwd(int64_t rows, int32_t C, int32_t dtype, int32_t relu, const void *x, const void *dy, const float *gamma,
                   const float *beta, const float *save_mean, const float *save_istd, void *dx, float *dgamma, float *dbeta,
                   void *ws, size_t ws_bytes, void *stream);

@@ -23,7 +23,7 @@ EXPORTS = (
     "stanza_strerror", "stanza_version", "stanza_conv_workspace_bytes", "stanza_conv_fwd", "stanza_conv_fwd_res", "stanza_conv_bwd_data",
     "stanza_conv_bwd_weight", "stanza_pool_relu_fwd", "stanza_pool_relu_bwd", "stanza_add_relu_fwd",
     "stanza_add_relu_bwd", "stanza_gap_fwd", "stanza_gap_bwd", "stanza_cast_f32_to_bf16", "stanza_cast_bf16_to_f32",
-    "stanza_bn_workspace_bytes", "stanza_bn_fwd", "stanza_bn_bwd", "stanza_avgpool_fwd", "stanza_avgpool_bwd", "stanza_copy2d",
+    "stanza_bn_workspace_bytes", "stanza_bn_fwd", "stanza_bn_fwd_res", "stanza_bn_bwd", "stanza_avgpool_fwd", "stanza_avgpool_bwd", "stanza_copy2d",
     "stanza_fc_workspace_bytes", "stanza_fc_step", "stanza_fc_grads", "stanza_dropout", "stanza_ps_workspace_bytes", "stanza_ps_plan",
     "stanza_ps_aggregate_planned", "stanza_ps_aggregate", "stanza_ps_aggregate_ordered_planned", "stanza_ps_aggregate_ordered",
     "stanza_model_allreduce_rounds", "stanza_model_stanza_time", "stanza_model_stanza_throughput", "stanza_model_assign",
@@ -90,6 +90,7 @@ def load() -> C.CDLL:
     lib.stanza_bn_workspace_bytes.restype = sz
     lib.stanza_bn_workspace_bytes.argtypes = [i64, i32, i32]
     lib.stanza_bn_fwd.argtypes = [i64, i32, i32, f32, i32, vp, vp, vp, vp, vp, vp, vp, vp, f32, vp, sz, vp]
+    lib.stanza_bn_fwd_res.argtypes = [i64, i32, i32, f32, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, f32, vp, sz, vp]
     lib.stanza_bn_bwd.argtypes = [i64, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.stanza_fc_workspace_bytes.restype = sz
     lib.stanza_fc_workspace_bytes.argtypes = [C.POINTER(FcDesc)]
@@ -250,6 +251,15 @@ def stanza_bn_fwd(x, gamma, beta, y, save_mean, save_istd, ws, eps=1e-5, relu=Fa
     p, n = _ws(ws)
     _check(load().stanza_bn_fwd(x.numel() // c, c, dtype, eps, int(relu), _ptr(x), _ptr(gamma), _ptr(beta), _ptr(y), _ptr(save_mean),
                                 _ptr(save_istd), _ptr(running_mean), _ptr(running_var), momentum, p, n, _stream()), "stanza_bn_fwd")
+
+
+def stanza_bn_fwd_res(x, gamma, beta, res, y, save_mean, save_istd, ws, eps=1e-5, relu=True, running_mean=None, running_var=None,
+                      momentum=0.1, dtype=F32):
+    c = x.shape[-1]
+    p, n = _ws(ws)
+    _check(load().stanza_bn_fwd_res(x.numel() // c, c, dtype, eps, int(relu), _ptr(x), _ptr(gamma), _ptr(beta), _ptr(res), _ptr(y),
+                                    _ptr(save_mean), _ptr(save_istd), _ptr(running_mean), _ptr(running_var), momentum, p, n, _stream()),
+           "stanza_bn_fwd_res")
 
 
 def stanza_bn_bwd(x, dy, gamma, beta, save_mean, save_istd, dx, dgamma, dbeta, ws, relu=False, dtype=F32):

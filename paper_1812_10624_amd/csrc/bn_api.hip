@@ -225,7 +225,8 @@ __global__ __launch_bounds__(256) void bn_finalize_kernel(int C, int slabs, int 
     if (run_var) run_var[c] = (1.f - mom) * run_var[c] + mom * (rows > 1 ? var * ((float)rows / (float)(rows - 1)) : var);
 }
 
-// BWD = false: y = gamma * xhat + beta (+ReLU).  BWD = true: dx = gamma istd (g - dbeta/M - xhat dgamma/M).
+// BWD = false: y = gamma * xhat + beta (+ReLU); with dyv != nullptr it holds a residual tensor that is added before the ReLU (a
+// residual join fused into the layer: y = max(bn(x) + res, 0)).  BWD = true: dx = gamma istd (g - dbeta/M - xhat dgamma/M).
 template <int VW, bool BF16, bool BWD>
 __global__ __launch_bounds__(256) void bn_apply_kernel(const BnGeo g, const void *__restrict__ xv, const void *__restrict__ dyv,
                                                        const float *__restrict__ gamma, const float *__restrict__ beta,
@@ -250,6 +251,7 @@ __global__ __launch_bounds__(256) void bn_apply_kernel(const BnGeo g, const void
     }
     const int r0 = blockIdx.x * g.rows_per_slab;
     const int r1 = min(r0 + g.rows_per_slab, g.rows);
+    const bool with_res = !BWD && dyv != nullptr;
     auto emit = [&](size_t vec, const float (&x)[VW], const float (&dy)[VW]) {
         float o[VW];
 #pragma unroll
@@ -260,7 +262,8 @@ __global__ __launch_bounds__(256) void bn_apply_kernel(const BnGeo g, const void
                 const float xh = bn_xhat(x[e], mu[e], is[e]);
                 o[e] = sc[e] * fmaf(-xh, c2[e], gr - c1[e]);
             } else {
-                o[e] = (relu && !(yv > 0.f)) ? 0.f : yv;
+                const float z = with_res ? yv + dy[e] : yv;
+                o[e] = (relu && !(z > 0.f)) ? 0.f : z;
             }
         }
         bn_store<VW, BF16>(outv, vec, o);
@@ -272,17 +275,17 @@ __global__ __launch_bounds__(256) void bn_apply_kernel(const BnGeo g, const void
         for (int u = 0; u < 4; ++u) {
             const size_t vec = (size_t)(r + u * g.TY) * g.cv + col;
             bn_load<VW, BF16, true>(xv, vec, x[u]);
-            if (BWD) bn_load<VW, BF16, true>(dyv, vec, dy[u]);
+            if (BWD || with_res) bn_load<VW, BF16, true>(dyv, vec, dy[u]);
         }
 #pragma unroll
-        for (int u = 0; u < 4; ++u) emit((size_t)(r + u * g.TY) * g.cv + col, x[u], BWD ? dy[u] : x[u]);
+        for (int u = 0; u < 4; ++u) emit((size_t)(r + u * g.TY) * g.cv + col, x[u], (BWD || with_res) ? dy[u] : x[u]);
     }
     for (; r < r1; r += g.TY) {
         float x[VW], dy[VW];
         const size_t vec = (size_t)r * g.cv + col;
         bn_load<VW, BF16, true>(xv, vec, x);
-        if (BWD) bn_load<VW, BF16, true>(dyv, vec, dy);
-        emit(vec, x, BWD ? dy : x);
+        if (BWD || with_res) bn_load<VW, BF16, true>(dyv, vec, dy);
+        emit(vec, x, (BWD || with_res) ? dy : x);
     }
 }
 
@@ -358,16 +361,16 @@ extern "C" size_t stanza_bn_workspace_bytes(int64_t rows, int32_t C, int32_t dty
     return round256(p.ws_floats * sizeof(float));
 }
 
-extern "C" int stanza_bn_fwd(int64_t rows, int32_t C, int32_t dtype, float eps, int32_t relu, const void *x, const float *gamma,
-                             const float *beta, void *y, float *save_mean, float *save_istd, float *running_mean, float *running_var,
-                             float momentum, void *ws, size_t ws_bytes, void *stream)
+static int bn_fwd_any(int64_t rows, int32_t C, int32_t dtype, float eps, int32_t relu, const void *x, const float *gamma,
+                      const float *beta, const void *res, bool want_res, void *y, float *save_mean, float *save_istd, float *running_mean,
+                      float *running_var, float momentum, void *ws, size_t ws_bytes, void *stream)
 {
     BnPlan p;
     int rc = bn_plan(rows, C, dtype, &p);
     if (rc) return rc;
     if (!(eps > 0.f) || !(momentum >= 0.f && momentum <= 1.f)) return STANZA_EINVAL;
-    if (!x || !gamma || !beta || !y || !save_mean || !save_istd || !ws) return STANZA_ENULL;
-    if (!aligned16(x) || !aligned16(y) || !aligned16(ws)) return STANZA_EALIGN;
+    if (!x || !gamma || !beta || !y || !save_mean || !save_istd || !ws || (want_res && !res)) return STANZA_ENULL;
+    if (!aligned16(x) || !aligned16(y) || !aligned16(ws) || !aligned16(res)) return STANZA_EALIGN;
     if (ws_bytes < p.ws_floats * sizeof(float)) return STANZA_EWORKSPACE;
     hipStream_t st = (hipStream_t)stream;
     float *partial = reinterpret_cast<float *>(ws);
@@ -378,8 +381,24 @@ extern "C" int stanza_bn_fwd(int64_t rows, int32_t C, int32_t dtype, float eps, 
     else
         hipLaunchKernelGGL((bn_finalize_kernel<false, false>), dim3((unsigned)cdiv(C, BN_FIN_CH)), dim3(256), 0, st, C, p.slabs, (int)rows, partial, x, eps,
                            save_mean, save_istd, running_mean, running_var, momentum);
-    bn_launch_apply<false>(p, dtype, st, x, nullptr, gamma, beta, save_mean, save_istd, nullptr, nullptr, relu ? 1 : 0, y);
+    bn_launch_apply<false>(p, dtype, st, x, want_res ? res : nullptr, gamma, beta, save_mean, save_istd, nullptr, nullptr, relu ? 1 : 0, y);
     return launch_status();
+}
+
+extern "C" int stanza_bn_fwd(int64_t rows, int32_t C, int32_t dtype, float eps, int32_t relu, const void *x, const float *gamma,
+                             const float *beta, void *y, float *save_mean, float *save_istd, float *running_mean, float *running_var,
+                             float momentum, void *ws, size_t ws_bytes, void *stream)
+{
+    return bn_fwd_any(rows, C, dtype, eps, relu, x, gamma, beta, nullptr, false, y, save_mean, save_istd, running_mean, running_var, momentum, ws,
+                      ws_bytes, stream);
+}
+
+extern "C" int stanza_bn_fwd_res(int64_t rows, int32_t C, int32_t dtype, float eps, int32_t relu, const void *x, const float *gamma,
+                                 const float *beta, const void *res, void *y, float *save_mean, float *save_istd, float *running_mean,
+                                 float *running_var, float momentum, void *ws, size_t ws_bytes, void *stream)
+{
+    return bn_fwd_any(rows, C, dtype, eps, relu, x, gamma, beta, res, true, y, save_mean, save_istd, running_mean, running_var, momentum, ws,
+                      ws_bytes, stream);
 }
 
 extern "C" int stanza_bn_bwd(int64_t rows, int32_t C, int32_t dtype, int32_t relu, const void *x, const void *dy, const float *gamma,

@@ -73,22 +73,24 @@ class ConvWorker:
                 n, h, w, c = self.shapes[op["src"]]
                 self.shapes[op["dst"]] = (n, 1, 1, c)
             self.producer[op["dst"]] = op
-        # A convolution without ReLU whose only reader is the residual join that follows it in the op list runs as
-        # stanza_conv_fwd_res: the join's output is written by the convolution's epilogue and its own output never exists.
-        # (Backward is unchanged: the join's gate reads the join's output, the convolution takes the gated gradient as it is.)
-        self.joined = {}                          # conv op index -> (join op index, name of the other addend)
+        # A convolution (or normalisation layer) without ReLU whose only reader is the residual join that follows it in the op list
+        # runs as stanza_conv_fwd_res (stanza_bn_fwd_res): the join's output is written by its epilogue and its own output never
+        # exists.  (Backward is unchanged: the join's gate reads the join's output, the layer takes the gated gradient as it is.)
+        self.joined = {}                          # op index -> (join op index, name of the other addend)
         self.join_desc = {}                       # conv op index -> its descriptor with the join's ReLU
         for i, op in enumerate(ops[:-1]):
             nxt = ops[i + 1]
-            if op["op"] != "conv" or op["relu"] or nxt["op"] != "add_relu" or op["dst"] not in (nxt["a"], nxt["b"]) or nxt["a"] == nxt["b"]:
+            if op["op"] not in ("conv", "bn") or op["relu"] or nxt["op"] != "add_relu" or op["dst"] not in (nxt["a"], nxt["b"]) \
+                    or nxt["a"] == nxt["b"]:
                 continue
             readers = sum(1 for o in ops if op["dst"] in (o.get("src"), o.get("a"), o.get("b")) or op["dst"] in o.get("srcs", ()))
-            if readers != 1 or i in self.padded or self.f32_layer[i]:
+            if readers != 1 or (op["op"] == "conv" and (i in self.padded or self.f32_layer[i])):
                 continue
             other = nxt["b"] if nxt["a"] == op["dst"] else nxt["a"]
             self.joined[i] = (i + 1, other)
-            self.join_desc[i] = api.ConvDesc.from_buffer_copy(self.descs[i])
-            self.join_desc[i].flags |= api.CONV_RELU
+            if op["op"] == "conv":
+                self.join_desc[i] = api.ConvDesc.from_buffer_copy(self.descs[i])
+                self.join_desc[i].flags |= api.CONV_RELU
         self.skip_fwd = {j for j, _ in self.joined.values()}
         if dtype == api.BF16:
             assert all(op["op"] in ("conv", "pool", "avgpool", "concat", "bn", "add_relu", "gap") for op in ops)
@@ -183,6 +185,12 @@ class ConvWorker:
                     cs = self.shapes[sname][3]
                     api.stanza_copy_channels(self.buf[sname], 0, self.buf[op["dst"]], at, cs)
                     at += cs
+            elif kind == "bn" and i in self.joined:
+                gamma, beta = self.params[op["name"]]
+                mean, istd = self.bn_stats[op["name"]]
+                j, other = self.joined[i]
+                api.stanza_bn_fwd_res(self.buf[op["src"]], gamma, beta, self.buf[other], self.buf[self.ops[j]["dst"]], mean, istd, self.bn_ws,
+                                      op["eps"], True, dtype=self.dtype)
             elif kind == "bn":
                 gamma, beta = self.params[op["name"]]
                 mean, istd = self.bn_stats[op["name"]]

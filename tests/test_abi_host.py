@@ -131,6 +131,9 @@ def test_bn_errors(api):
     assert call(x=None) == -2 and call(x=p4) == -3 and call(nbytes=8) == -5
     assert lib.stanza_bn_workspace_bytes(0, 8, api.F32) == 0
     assert lib.stanza_bn_bwd(100, 8, api.F32, 0, p16, None, p16, p16, p16, p16, p16, p16, p16, p16, need, None) == -2
+    # the residual-join forward: the residual is required and aligned like x
+    assert lib.stanza_bn_fwd_res(100, 8, api.F32, 1e-5, 1, p16, p16, p16, None, p16, p16, p16, None, None, 0.1, p16, need, None) == -2
+    assert lib.stanza_bn_fwd_res(100, 8, api.F32, 1e-5, 1, p16, p16, p16, p4, p16, p16, p16, None, None, 0.1, p16, need, None) == -3
 
 
 def test_dropout_errors(api):

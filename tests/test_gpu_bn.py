@@ -210,3 +210,42 @@ def test_normalised_residual_step(api, o32, K, B):
             assert rel_err(host(gcm[nme][i]), cm_ref[nme][i]) < 5 * TOL_F32, (nme, i)
             assert rel_err(host(gpar[nme][i]) - cp[nme][i], cp_ref[nme][i] - cp[nme][i]) < 5 * TOL_F32, (nme, i)
             assert not np.array_equal(host(gpar[nme][i]), cp[nme][i])
+
+
+@pytest.mark.parametrize("rows,c,half", [(257, 12, False), (4096, 64, False), (33, 3, False), (3 * 14 * 14, 256, True), (4097, 24, True)])
+def test_bn_forward_with_residual_join(api, o32, rows, c, half):
+    """y = max(bn(x) + res, 0) in one call: against the checker's normalisation followed by its residual join, and (float32)
+    bit for bit against the two library calls it replaces."""
+    import workloads as wl_mod
+    x, gamma, beta, _ = _case(11, rows, c)
+    res = np.random.default_rng(12).standard_normal((rows, c), dtype=np.float32)
+    if half:
+        x, res = wl_mod.round_bf16(x), wl_mod.round_bf16(res)
+    y_ref, mean_ref, istd_ref = o32.bn_fwd(x, gamma, beta, 1e-5, False)
+    ref = o32.add_relu_fwd(y_ref.reshape(1, 1, rows, c), res.reshape(1, 1, rows, c)).reshape(rows, c)
+    DT = api.BF16 if half else api.F32
+
+    def up(a):
+        if not half:
+            return dev(a)
+        return torch.from_numpy(wl_mod.bf16_bits(a).view(np.int16)).to("cuda:0").view(torch.bfloat16).reshape(a.shape)
+
+    def down(t):
+        if not half:
+            return host(t)
+        torch.cuda.synchronize()
+        return wl_mod.bf16_to_f32(t.view(torch.int16).cpu().numpy().view(np.uint16)).reshape(tuple(t.shape))
+
+    xd, rd, gd, bd = up(x), up(res), dev(gamma), dev(beta)
+    y = torch.full((rows, c), float("nan"), device="cuda:0").to(torch.bfloat16 if half else torch.float32)
+    mean, istd = torch.empty(c, device="cuda:0"), torch.empty(c, device="cuda:0")
+    ws = torch.empty(max(16, api.stanza_bn_workspace_bytes(rows, c, DT)), dtype=torch.uint8, device="cuda:0")
+    api.stanza_bn_fwd_res(xd, gd, bd, rd, y, mean, istd, ws, 1e-5, True, dtype=DT)
+    assert rel_err(host(mean), mean_ref) < 1e-5 and rel_err(host(istd), istd_ref) < TOL_F32
+    assert rel_err(down(y), ref) < (2e-2 if half else TOL_F32)
+    assert (down(y) >= 0).all()
+    if not half:
+        y1, o = torch.empty_like(y), torch.empty_like(y)
+        api.stanza_bn_fwd(xd, gd, bd, y1, mean, istd, ws, 1e-5, False)
+        api.stanza_add_relu_fwd(y1, rd, o)
+        assert torch.equal(o, y)
