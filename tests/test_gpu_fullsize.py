@@ -196,3 +196,39 @@ def test_conv_input_of_two_gibibytes(api, o32):
     idx = _sample_idx(dwh.shape, 15, 12)
     want = [o32.conv_bwd_weight_at(g, x, dy, *i) for i in idx]
     _check([dwh[i] for i in idx], want, float(np.abs(dwh).max()), "2 GiB input bwd_weight")
+
+
+def test_conv_tensor_beyond_2_gib(api, o32):
+    """A layer whose input (and input gradient) is larger than 2 GiB: the vector fetch addresses tensors with 32-bit byte
+    offsets, so the launch must fall back to element-indexed gathers; sampled against the checker in all three directions."""
+    N, H, W, C, K = 86, 224, 224, 128, 8
+    g = ConvGeom(N, H, W, C, K, 1, 1, 1, 0)
+    r = np.random.default_rng(5)
+    x = r.standard_normal((N, H, W, C), dtype=np.float32)
+    assert x.nbytes > (1 << 31)
+    w = (r.standard_normal((K, 1, 1, C), dtype=np.float32) / np.sqrt(C)).astype(np.float32)
+    b = r.standard_normal(K, dtype=np.float32)
+    dy = r.standard_normal((N, H, W, K), dtype=np.float32)
+    xd, wd, dyd = dev(x), dev(w), dev(dy)
+    d = api.conv_desc(N, H, W, C, K, 1, 1, 1, 0, api.F32, api.CONV_BIAS | api.CONV_RELU)
+    y = torch.full((N, H, W, K), float("nan"), device="cuda:0")
+    api.stanza_conv_fwd(d, xd, wd, dev(b), y)
+    yh = host(y)
+    assert np.isfinite(yh).all()
+    idx = _sample_idx(yh.shape, 20)
+    _check([yh[i] for i in idx], [o32.conv_fwd_at(g, x, w, b, True, *i) for i in idx], float(np.abs(yh).max()), "fwd > 2 GiB")
+    del y, yh
+    d0 = api.conv_desc(N, H, W, C, K, 1, 1, 1, 0, api.F32, 0)
+    dx = torch.full((N, H, W, C), float("nan"), device="cuda:0")
+    api.stanza_conv_bwd_data(d0, dyd, None, wd, None, dx)
+    dxh = host(dx)
+    assert np.isfinite(dxh).all()
+    idx = _sample_idx(dxh.shape, 21)
+    _check([dxh[i] for i in idx], [o32.conv_bwd_data_at(g, dy, w, *i) for i in idx], float(np.abs(dxh).max()), "bwd_data > 2 GiB")
+    del dx, dxh
+    ws = torch.empty(max(16, api.stanza_conv_workspace_bytes(d0, 2)), dtype=torch.uint8, device="cuda:0")
+    dw = torch.full((K, 1, 1, C), float("nan"), device="cuda:0")
+    api.stanza_conv_bwd_weight(d0, xd, dyd, None, dw, None, ws)
+    dwh = host(dw)
+    idx = [(0, 0, 0, 0), (K - 1, 0, 0, C - 1), (3, 0, 0, 77), (5, 0, 0, 1)]
+    _check([dwh[i] for i in idx], [o32.conv_bwd_weight_at(g, x, dy, *i) for i in idx], float(np.abs(dwh).max()), "bwd_weight > 2 GiB")
