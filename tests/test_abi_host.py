@@ -53,6 +53,9 @@ def test_conv_errors_before_launch(api):
         assert lib.stanza_conv_fwd(C.byref(d), p16, p16, None, p16, None, 0, None) == -1, field
     big = api.conv_desc(4096, 1024, 1024, 64, 8, 3, 3, 1, 1, api.F32, 0)                       # >= 2^31 elements
     assert lib.stanza_conv_fwd(C.byref(big), p16, p16, None, p16, None, 0, None) == -1
+    # bfloat16 tensors are addressed with 32-bit byte offsets: 2 GiB and more is refused before any launch
+    big16 = api.conv_desc(2048, 256, 256, 8, 8, 1, 1, 1, 0, api.BF16, 0)                       # 2^30 elements = 2 GiB
+    assert lib.stanza_conv_fwd(C.byref(big16), p16, p16, None, p16, None, 0, None) == -4
     bad_dtype = api.conv_desc(2, 8, 8, 4, 8, 3, 3, 1, 1, 7, 0)
     assert lib.stanza_conv_fwd(C.byref(bad_dtype), p16, p16, None, p16, None, 0, None) == -4
     # residual join in the epilogue: the residual is required and aligned like every tensor
