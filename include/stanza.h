@@ -28,7 +28,8 @@
  *   - Element type: float32 everywhere for STANZA_F32.  For STANZA_BF16 the tensors x, w, y,
  *     dy, dx of the conv calls are bfloat16 (products accumulate in float32); bias, dw, dbias
  *     and everything in fc_step / ps_aggregate stay float32.
- *   - Every tensor must have fewer than 2^31 elements and a 16-byte aligned base pointer.
+ *   - Every tensor must have fewer than 2^31 elements and a 16-byte aligned base pointer.  float32 tensors of 2 GiB and more
+ *     are gathered element by element (correct, slower); the bfloat16 conv calls refuse them (STANZA_EUNSUPPORTED).
  *   - Return value: STANZA_OK (0) or a negative stanza_status.  Errors are decided before
  *     any launch (nothing has been written) except STANZA_EHIP, which reports a launch
  *     failure.  No C++ exception crosses this boundary.
