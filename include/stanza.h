@@ -214,6 +214,15 @@ int stanza_bn_bwd(int64_t rows, int32_t C, int32_t dtype, int32_t relu, const vo
  * float32 master weights and images. */
 int stanza_cast_f32_to_bf16(int64_t numel, const float *src, void *dst, void *stream);
 int stanza_cast_bf16_to_f32(int64_t numel, const void *src, float *dst, void *stream);
+/* The same cast over many tensors in one launch (a CONV worker's per-step bfloat16 copies of all its master filters).
+ *   stanza_cast_plan writes a table of the n tensors (host_numel[t] elements from host_src[t] to host_dst[t]; device pointers, 16-byte
+ *   aligned, held in host arrays) into ws (stanza_cast_workspace_bytes(n) bytes, caller-owned) and waits for that copy;
+ *   stanza_cast_f32_to_bf16_planned then converts all of them, any number of times, with the same n and host_numel.
+ * Errors: n < 1, a tensor with numel < 1 -> STANZA_EINVAL; NULL / alignment / workspace size as elsewhere. */
+size_t stanza_cast_workspace_bytes(int32_t n_tensors);
+int stanza_cast_plan(int32_t n_tensors, const int64_t *host_numel, const float *const *host_src, void *const *host_dst, void *ws,
+                     size_t ws_bytes, void *stream);
+int stanza_cast_f32_to_bf16_planned(int32_t n_tensors, const int64_t *host_numel, const void *ws, size_t ws_bytes, void *stream);
 
 /* ---- FC worker step (Sec. 3.2: the FC worker collects the activations of all workers, continues the
  * forward pass to the loss, backpropagates through the FC layers and "the last CONV layer"'s

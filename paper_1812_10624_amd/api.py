@@ -23,6 +23,7 @@ EXPORTS = (
     "stanza_strerror", "stanza_version", "stanza_conv_workspace_bytes", "stanza_conv_fwd", "stanza_conv_fwd_res", "stanza_conv_bwd_data",
     "stanza_conv_bwd_weight", "stanza_pool_relu_fwd", "stanza_pool_relu_bwd", "stanza_add_relu_fwd",
     "stanza_add_relu_bwd", "stanza_gap_fwd", "stanza_gap_bwd", "stanza_cast_f32_to_bf16", "stanza_cast_bf16_to_f32",
+    "stanza_cast_workspace_bytes", "stanza_cast_plan", "stanza_cast_f32_to_bf16_planned",
     "stanza_bn_workspace_bytes", "stanza_bn_fwd", "stanza_bn_fwd_res", "stanza_bn_bwd", "stanza_avgpool_fwd", "stanza_avgpool_bwd", "stanza_copy2d",
     "stanza_fc_workspace_bytes", "stanza_fc_step", "stanza_fc_grads", "stanza_dropout", "stanza_ps_workspace_bytes", "stanza_ps_plan",
     "stanza_ps_aggregate_planned", "stanza_ps_aggregate", "stanza_ps_aggregate_ordered_planned", "stanza_ps_aggregate_ordered",
@@ -83,6 +84,10 @@ def load() -> C.CDLL:
     lib.stanza_gap_fwd.argtypes = [i32, i32, i32, i32, vp, vp, vp]
     lib.stanza_gap_bwd.argtypes = [i32, i32, i32, i32, vp, vp, vp]
     lib.stanza_cast_f32_to_bf16.argtypes = [i64, vp, vp, vp]
+    lib.stanza_cast_workspace_bytes.restype = sz
+    lib.stanza_cast_workspace_bytes.argtypes = [i32]
+    lib.stanza_cast_plan.argtypes = [i32, vp, vp, vp, vp, sz, vp]
+    lib.stanza_cast_f32_to_bf16_planned.argtypes = [i32, vp, vp, sz, vp]
     lib.stanza_cast_bf16_to_f32.argtypes = [i64, vp, vp, vp]
     lib.stanza_avgpool_fwd.argtypes = [C.POINTER(PoolDesc), i32, vp, vp, vp]
     lib.stanza_avgpool_bwd.argtypes = [C.POINTER(PoolDesc), i32, vp, vp, vp]
@@ -206,6 +211,27 @@ def stanza_gap_bwd(df, dx, dtype=F32):
 
 def stanza_cast_f32_to_bf16(src, dst):
     _check(load().stanza_cast_f32_to_bf16(src.numel(), _ptr(src), _ptr(dst), _stream()), "stanza_cast_f32_to_bf16")
+
+
+class CastPlan:
+    """float32 -> bfloat16 copies of a list of tensors in one launch (stanza_cast_plan + stanza_cast_f32_to_bf16_planned)."""
+
+    def __init__(self, srcs, dsts):
+        import torch
+        assert len(srcs) == len(dsts) and len(srcs) > 0
+        for a, b in zip(srcs, dsts):
+            assert a.is_cuda and b.is_cuda and a.is_contiguous() and b.is_contiguous() and a.numel() == b.numel()
+            assert a.dtype == torch.float32 and b.dtype == torch.bfloat16
+        self.n = len(srcs)
+        self.numel = (C.c_int64 * self.n)(*[t.numel() for t in srcs])
+        self.keep = (list(srcs), list(dsts))                 # the table holds their addresses
+        self.ws = torch.empty(int(load().stanza_cast_workspace_bytes(self.n)), dtype=torch.uint8, device=srcs[0].device)
+        _check(load().stanza_cast_plan(self.n, self.numel, _ptr_array(srcs), _ptr_array(dsts), _ptr(self.ws), self.ws.numel(), _stream()),
+               "stanza_cast_plan")
+
+    def run(self):
+        _check(load().stanza_cast_f32_to_bf16_planned(self.n, self.numel, _ptr(self.ws), self.ws.numel(), _stream()),
+               "stanza_cast_f32_to_bf16_planned")
 
 
 def stanza_cast_bf16_to_f32(src, dst):

@@ -443,6 +443,45 @@ __global__ void cast_bf16_f32_kernel(size_t numel, const uint16_t *__restrict__ 
     if (i < numel) dst[i] = __uint_as_float((uint32_t)src[i] << 16);
 }
 
+// Many tensors in one launch (the per-step bf16 copies of all master filters of a CONV worker: one launch instead of one per
+// layer).  Table in device memory, built by stanza_cast_plan:
+//   int64 chunk_prefix[n + 1]   exclusive prefix of per-tensor chunk counts (CAST_CHUNK elements each)
+//   int64 numel[n];  const float *src[n];  uint16 *dst[n]
+constexpr int CAST_CHUNK = 4096;
+__global__ __launch_bounds__(256) void cast_f32_bf16_multi_kernel(const void *ws, int n)
+{
+    const int64_t *prefix = (const int64_t *)ws;
+    const int64_t *numel = prefix + (n + 1);
+    const float *const *src = (const float *const *)(numel + n);
+    uint16_t *const *dst = (uint16_t *const *)(src + n);
+    const int64_t chunk = blockIdx.x;
+    int lo = 0, hi = n;                      // largest t with prefix[t] <= chunk
+    while (hi - lo > 1) {
+        const int mid = (lo + hi) >> 1;
+        if (prefix[mid] <= chunk) lo = mid; else hi = mid;
+    }
+    const int64_t base = (chunk - prefix[lo]) * CAST_CHUNK, len = numel[lo];
+    const float *__restrict__ s = src[lo] + base;
+    uint16_t *__restrict__ d = dst[lo] + base;
+    const int64_t left = len - base;
+    if (left >= CAST_CHUNK) {
+        // 16 elements per thread as two runs of 8: four 16-byte loads, two 16-byte stores, every access of a wavefront contiguous
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            const int e0 = h * 2048 + threadIdx.x * 8;
+            const float4 a = *reinterpret_cast<const float4 *>(s + e0), b = *reinterpret_cast<const float4 *>(s + e0 + 4);
+            uint4 o;
+            o.x = (uint32_t)f32_to_bf16_rne(a.x) | ((uint32_t)f32_to_bf16_rne(a.y) << 16);
+            o.y = (uint32_t)f32_to_bf16_rne(a.z) | ((uint32_t)f32_to_bf16_rne(a.w) << 16);
+            o.z = (uint32_t)f32_to_bf16_rne(b.x) | ((uint32_t)f32_to_bf16_rne(b.y) << 16);
+            o.w = (uint32_t)f32_to_bf16_rne(b.z) | ((uint32_t)f32_to_bf16_rne(b.w) << 16);
+            *reinterpret_cast<uint4 *>(d + e0) = o;
+        }
+    } else {
+        for (int64_t i = threadIdx.x; i < left; i += 256) d[i] = f32_to_bf16_rne(s[i]);
+    }
+}
+
 // ------------------------------------------------------------------ aggregation + momentum SGD
 // Table in device memory (built by stanza_ps_plan):
 //   int64 chunk_prefix[n_tensors + 1]   exclusive prefix of per-tensor chunk counts (PS_CHUNK elements each)
@@ -811,6 +850,65 @@ extern "C" int stanza_cast_bf16_to_f32(int64_t numel, const void *src, float *ds
     if (numel <= 0) return STANZA_EINVAL;
     if (!src || !dst) return STANZA_ENULL;
     hipLaunchKernelGGL(cast_bf16_f32_kernel, dim3((unsigned)cdiv64(numel, 256)), dim3(256), 0, (hipStream_t)stream, (size_t)numel, (const uint16_t *)src, dst);
+    return launch_status();
+}
+
+extern "C" size_t stanza_cast_workspace_bytes(int32_t n_tensors)
+{
+    if (n_tensors <= 0) return 0;
+    return round256(sizeof(int64_t) * (2 * (size_t)n_tensors + 1) + sizeof(void *) * 2 * (size_t)n_tensors);
+}
+
+extern "C" int stanza_cast_plan(int32_t n_tensors, const int64_t *host_numel, const float *const *host_src, void *const *host_dst, void *ws,
+                                size_t ws_bytes, void *stream)
+{
+    if (n_tensors <= 0 || n_tensors > (1 << 20)) return STANZA_EINVAL;
+    if (!host_numel || !host_src || !host_dst || !ws) return STANZA_ENULL;
+    const size_t need = stanza_cast_workspace_bytes(n_tensors);
+    if (ws_bytes < need) return STANZA_EWORKSPACE;
+    if (!aligned16(ws)) return STANZA_EALIGN;
+    int64_t acc = 0;
+    for (int t = 0; t < n_tensors; ++t) {
+        if (host_numel[t] <= 0) return STANZA_EINVAL;
+        if (!host_src[t] || !host_dst[t]) return STANZA_ENULL;
+        if (!aligned16(host_src[t]) || !aligned16(host_dst[t])) return STANZA_EALIGN;
+        acc += cdiv64(host_numel[t], CAST_CHUNK);
+    }
+    if (acc >= (int64_t(1) << 31)) return STANZA_EINVAL;
+    char *stage = (char *)malloc(need);
+    if (!stage) return STANZA_EINVAL;
+    int64_t *prefix = (int64_t *)stage;
+    int64_t *numel = prefix + (n_tensors + 1);
+    const void **src = (const void **)(numel + n_tensors);
+    void **dst = (void **)(src + n_tensors);
+    acc = 0;
+    for (int t = 0; t < n_tensors; ++t) {
+        prefix[t] = acc;
+        acc += cdiv64(host_numel[t], CAST_CHUNK);
+        numel[t] = host_numel[t];
+        src[t] = host_src[t];
+        dst[t] = host_dst[t];
+    }
+    prefix[n_tensors] = acc;
+    // Pageable source: the runtime has consumed `stage` when this returns, so it can be freed at once.
+    hipError_t e = hipMemcpyAsync(ws, stage, need, hipMemcpyHostToDevice, (hipStream_t)stream);
+    if (e == hipSuccess) e = hipStreamSynchronize((hipStream_t)stream);
+    free(stage);
+    return hip_status(e);
+}
+
+extern "C" int stanza_cast_f32_to_bf16_planned(int32_t n_tensors, const int64_t *host_numel, const void *ws, size_t ws_bytes, void *stream)
+{
+    if (n_tensors <= 0) return STANZA_EINVAL;
+    if (!host_numel || !ws) return STANZA_ENULL;
+    if (ws_bytes < stanza_cast_workspace_bytes(n_tensors)) return STANZA_EWORKSPACE;
+    int64_t total = 0;
+    for (int t = 0; t < n_tensors; ++t) {
+        if (host_numel[t] <= 0) return STANZA_EINVAL;
+        total += cdiv64(host_numel[t], CAST_CHUNK);
+    }
+    if (total >= (int64_t(1) << 31)) return STANZA_EINVAL;
+    hipLaunchKernelGGL(cast_f32_bf16_multi_kernel, dim3((unsigned)total), dim3(256), 0, (hipStream_t)stream, ws, n_tensors);
     return launch_status();
 }
 

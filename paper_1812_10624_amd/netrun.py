@@ -127,6 +127,8 @@ class ConvWorker:
         if dtype == api.BF16:
             self.w16 = {op["name"]: torch.empty_like(params[op["name"]][0], dtype=torch.bfloat16)
                         for i, op in enumerate(ops) if op["op"] == "conv" and not self.f32_layer[i] and i not in self.padded}
+            plain = list(self.w16)                   # every bf16 filter copy of a step is written by one launch
+            self.cast_plan = api.CastPlan([params[n][0] for n in plain], [self.w16[n] for n in plain]) if plain else None
             for i in self.padded:
                 name = ops[i]["name"]
                 self.w16[name] = torch.empty(self.wpad32.shape, device=self.dev, dtype=torch.bfloat16)
@@ -143,6 +145,8 @@ class ConvWorker:
         """Returns the float32 activations handed to the FC worker."""
         if images is not None:
             self.buf["x0"].copy_(images)
+        if self.dtype == api.BF16 and self.cast_plan is not None:
+            self.cast_plan.run()                     # this step's bf16 copies of the master filters
         for i, op in enumerate(self.ops):
             kind = op["op"]
             if i in self.skip_fwd:                  # a residual join computed by the preceding convolution's epilogue
@@ -151,7 +155,6 @@ class ConvWorker:
                 w, b = self.params[op["name"]]
                 j, other = self.joined[i]
                 if self.dtype == api.BF16:
-                    api.stanza_cast_f32_to_bf16(w, self.w16[op["name"]])
                     w = self.w16[op["name"]]
                 api.stanza_conv_fwd_res(self.join_desc[i], self.buf[op["src"]], w, b, self.buf[other], self.buf[self.ops[j]["dst"]], self.ws)
             elif kind == "conv":
@@ -167,7 +170,6 @@ class ConvWorker:
                     else:
                         api.stanza_conv_fwd(self.descs[i], self.x0pad32, self.wpad32, b, self.buf[op["dst"]], self.ws)
                 elif self.dtype == api.BF16 and not self.f32_layer[i]:
-                    api.stanza_cast_f32_to_bf16(w, self.w16[op["name"]])      # this step's bf16 copy of the master filter
                     api.stanza_conv_fwd(self.descs[i], self.buf[op["src"]], self.w16[op["name"]], b, self.buf[op["dst"]], self.ws)
                 elif self.f32_layer[i]:
                     y32 = self.tmp32[: self.buf[op["dst"]].numel()].view(self.shapes[op["dst"]])

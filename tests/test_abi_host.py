@@ -120,6 +120,30 @@ def test_fc_and_ps_errors(api):
     assert lib.stanza_ps_aggregate_ordered(9, 2, numel, w, w, g, 3, 1.0, 0.1, 0.9, 0.0, p16, need, None) == -1
 
 
+def test_cast_plan_errors(api):
+    lib = api.load()
+    p16, p4 = C.c_void_p(0x1000), C.c_void_p(0x1004)
+    assert lib.stanza_cast_workspace_bytes(0) == 0 and lib.stanza_cast_workspace_bytes(-3) == 0
+    need = lib.stanza_cast_workspace_bytes(2)
+    assert need >= 8 * (2 * 2 + 1) + 8 * 2 * 2 and need % 256 == 0
+    numel = (C.c_int64 * 2)(100, 50)
+    ok = (C.c_void_p * 2)(0x1000, 0x2000)
+    assert lib.stanza_cast_plan(0, numel, ok, ok, p16, need, None) == -1
+    assert lib.stanza_cast_plan(2, (C.c_int64 * 2)(100, 0), ok, ok, p16, need, None) == -1        # empty tensor
+    assert lib.stanza_cast_plan(2, None, ok, ok, p16, need, None) == -2
+    assert lib.stanza_cast_plan(2, numel, ok, ok, None, need, None) == -2
+    assert lib.stanza_cast_plan(2, numel, (C.c_void_p * 2)(0x1000, 0), ok, p16, need, None) == -2
+    assert lib.stanza_cast_plan(2, numel, ok, (C.c_void_p * 2)(0x1000, 0x2004), p16, need, None) == -3
+    assert lib.stanza_cast_plan(2, numel, ok, ok, p4, need, None) == -3
+    assert lib.stanza_cast_plan(2, numel, ok, ok, p16, need - 1, None) == -5
+    assert lib.stanza_cast_plan(2, (C.c_int64 * 2)(1 << 42, 1 << 42), ok, ok, p16, need, None) == -1   # more blocks than a grid holds
+    assert lib.stanza_cast_f32_to_bf16_planned(0, numel, p16, need, None) == -1
+    assert lib.stanza_cast_f32_to_bf16_planned(2, None, p16, need, None) == -2
+    assert lib.stanza_cast_f32_to_bf16_planned(2, numel, None, need, None) == -2
+    assert lib.stanza_cast_f32_to_bf16_planned(2, numel, p16, need - 1, None) == -5
+    assert lib.stanza_cast_f32_to_bf16_planned(2, (C.c_int64 * 2)(100, -1), p16, need, None) == -1
+
+
 def test_bn_errors(api):
     import ctypes as C
     lib = api.load()

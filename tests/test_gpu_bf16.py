@@ -133,6 +133,29 @@ def test_cast_round_trip(api):
     np.testing.assert_array_equal(host(back), wl_mod.round_bf16(a))
 
 
+def test_cast_many_tensors_in_one_launch(api):
+    """The planned multi-tensor cast: bit-exact round-to-nearest-even on tensors of ragged sizes (below, at and across the kernel's
+    4096-element blocks), dst guard elements untouched, and a second run after the sources changed."""
+    sizes = [1, 7, 4095, 4096, 4097, 8192, 3 * 4096 + 5, 100003, 12, 64 * 3 * 3 * 3]
+    rng = np.random.default_rng(12)
+    host_src = [(rng.standard_normal(n, dtype=np.float32) * 10.0 ** rng.integers(-3, 4)).astype(np.float32) for n in sizes]
+    host_src[2][:4] = [0.0, -0.0, 1.0 + 2 ** -8, 1.0 + 3 * 2 ** -9]
+    srcs = [dev32(a) for a in host_src]
+    guard = 16
+    full = [torch.full((n + guard,), 1.5, dtype=torch.bfloat16, device="cuda:0") for n in sizes]
+    dsts = [f[:n] for f, n in zip(full, sizes)]
+    plan = api.CastPlan(srcs, dsts)
+    for trial in range(2):
+        plan.run()
+        for a, f, n in zip(host_src, full, sizes):
+            bits = f.view(torch.int16).cpu().numpy().view(np.uint16)
+            np.testing.assert_array_equal(bits[:n], wl_mod.bf16_bits(a))
+            np.testing.assert_array_equal(bits[n:], np.full(guard, 0x3FC0, np.uint16))
+        for t, a in enumerate(host_src):                 # new values at the same addresses
+            a *= np.float32(-0.37)
+            srcs[t].copy_(torch.from_numpy(a))
+
+
 def test_conv_bf16_full_size_sampled(api, o32):
     """VGG-16-shaped conv2 (64 x 224 x 224 x 64 -> 64) at the real batch size, sampled outputs."""
     N, H, W, C, K, R, S, st, pad = 64, 224, 224, 64, 64, 3, 3, 1, 1
