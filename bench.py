@@ -239,25 +239,50 @@ def main():
     ps_bytes = (K + 4) * 4 * conv_params
     ps_gbs = ps_bytes / (tot["stanza_ps_aggregate"] * 1e-3) / 1e9
 
+    # ---- per layer and direction: flops, algorithmic bytes (input, filter and output each moved once; the forward output too where
+    # the backward pass gates on it), time.  Layers at or below the ridge of the roofline (peak flops / peak bytes) are bound by HBM,
+    # not by the matrix pipes: they are also reported against the HBM peak.
+    esz_c = 2 if args.dtype == "bf16" else 4
+    ridge = (MFMA_BF16_PEAK_TFLOPS if args.dtype == "bf16" else MFMA_F32_PEAK_TFLOPS) * 1e12 / (HBM_PEAK_GBS * 1e9)
+    conv_ops = [(i, op) for i, op in enumerate(wl.ops) if op["op"] == "conv"]
+    shapes = W.shape_pass(wl)
+    layer_rows = []
+    for kind in ("stanza_conv_fwd", "stanza_conv_bwd_weight", "stanza_conv_bwd_data"):
+        v = per.get(kind, [])
+        calls = len(v) // n_timed_eager
+        ops_k = conv_ops if kind == "stanza_conv_fwd" else list(reversed(conv_ops))
+        if kind == "stanza_conv_bwd_data":
+            ops_k = [(i, op) for i, op in ops_k if op["src"] != "x0"]
+        if calls != len(ops_k):
+            continue
+        for ci, (oi, op) in enumerate(ops_k):
+            ms = sum(v[ci::calls]) / n_timed_eager
+            nn, ho, wo, kk = shapes[op["dst"]]
+            _, hi, wi, c = shapes[op["src"]]
+            fl = 2.0 * nn * ho * wo * kk * c * op["R"] * op["S"]
+            n_in, n_out, n_w = float(nn * hi * wi * c), float(nn * ho * wo * kk), float(kk * op["R"] * op["S"] * c)
+            gated = bool(op.get("relu")) and oi not in worker.joined
+            if kind == "stanza_conv_fwd":
+                by = esz_c * (n_in + n_w + n_out) + (esz_c * n_out if oi in worker.joined else 0.0)      # a fused join reads the other addend
+            elif kind == "stanza_conv_bwd_data":
+                by = esz_c * (n_out + n_w + n_in) + (esz_c * n_out if gated else 0.0)
+            else:
+                by = esz_c * (n_in + n_out) + 4.0 * n_w + (esz_c * n_out if gated else 0.0)             # the filter gradient is float32
+            layer_rows.append({"kind": kind[7:], "layer": op["name"], "in": f"{hi}x{wi}x{c}", "K": kk, "R": op["R"], "S": op["S"],
+                               "stride": op["stride"], "ms": ms, "flops": fl, "bytes": by})
+    low = [r for r in layer_rows if r["flops"] / r["bytes"] <= ridge]
+    conv_at_ridge = None
+    if low:
+        lb, lms, lf = sum(r["bytes"] for r in low), sum(r["ms"] for r in low), sum(r["flops"] for r in low)
+        conv_at_ridge = {"ridge_flop_per_byte": ridge, "calls_per_step": len(low), "algorithmic_bytes_per_step": lb, "ms_per_step": lms,
+                         "GBps": lb / (lms * 1e-3) / 1e9, "frac_hbm": lb / (lms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                         "TFLOPs": lf / (lms * 1e-3) / 1e12, "share_of_conv_ms": lms / conv_ms}
     if args.detail:
-        nconv = sum(1 for op in wl.ops if op["op"] == "conv")
         print(f"per entry point, ms/step: " + ", ".join(f"{k}={v:.3f}" for k, v in sorted(tot.items())), file=sys.stderr)
-        conv_ops = [op for op in wl.ops if op["op"] == "conv"]
-        shapes = W.shape_pass(wl)
-        for kind in ("stanza_conv_fwd", "stanza_conv_bwd_weight", "stanza_conv_bwd_data"):
-            v = per.get(kind, [])
-            calls = len(v) // n_timed_eager
-            ops_k = conv_ops if kind == "stanza_conv_fwd" else list(reversed(conv_ops))
-            if kind == "stanza_conv_bwd_data":
-                ops_k = [op for op in ops_k if op["src"] != "x0"]
-            for ci in range(calls):
-                ms = sum(v[ci::calls]) / n_timed_eager
-                op = ops_k[ci]
-                nn, ho, wo, kk = shapes[op["dst"]]
-                c = shapes[op["src"]][3]
-                fl = 2.0 * nn * ho * wo * kk * c * op["R"] * op["S"]
-                print(f"  {kind[7:]:16s} {op['name']:8s} {shapes[op['src']][1]:3d}x{shapes[op['src']][2]:<3d} C{c:<4d} K{kk:<4d} "
-                      f"R{op['R']} s{op['stride']}  {ms:8.3f} ms  {fl / ms / 1e9:7.1f} TFLOP/s", file=sys.stderr)
+        for r in layer_rows:
+            print(f"  {r['kind']:16s} {r['layer']:8s} {r['in']:>12s} K{r['K']:<4d} R{r['R']} S{r['S']} s{r['stride']}  {r['ms']:8.3f} ms  "
+                  f"{r['flops'] / r['ms'] / 1e9:7.1f} TFLOP/s  {r['flops'] / r['bytes']:7.1f} flop/B  {r['bytes'] / r['ms'] / 1e6:7.0f} GB/s",
+                  file=sys.stderr)
 
     # HBM-bound kernels of the CONV worker: algorithmic bytes (every tensor moved once) over the measured time
     esz = 2 if args.dtype == "bf16" else 4
@@ -303,6 +328,7 @@ def main():
         "fc_tflops": W.fc_flops(wl) / (tot["stanza_fc_step"] * 1e-3) / 1e12,
         "ps_aggregate_ms": tot["stanza_ps_aggregate"], "ps_aggregate_GBps": ps_gbs, "ps_aggregate_frac_hbm": ps_gbs / HBM_PEAK_GBS,
         "hbm_kernels": hbm_kernels,
+        "conv_layers_at_or_below_ridge": conv_at_ridge,            # convolution calls that HBM bounds, not the matrix pipes
         "roofline": {"bound": "mfma", "kernel": "stanza::igemm_kernel (all launches of a step: conv fwd / bwd_data / bwd_weight "
                                                  "and the FC worker's GEMMs)",
                      "achieved": gemm_tflops, "peak": MFMA_F32_PEAK_TFLOPS, "unit": "TFLOP/s",
