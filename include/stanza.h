@@ -211,7 +211,8 @@ int stanza_bn_bwd(int64_t rows, int32_t C, int32_t dtype, int32_t relu, const vo
                   void *ws, size_t ws_bytes, void *stream);
 
 /* float32 -> bfloat16 (round to nearest even) and back, for feeding the STANZA_BF16 conv path from
- * float32 master weights and images. */
+ * float32 master weights and images.  Any element-aligned pointers; 16-byte-aligned ones take the vector path.
+ * Errors: numel < 1 or beyond 2^43 -> STANZA_EINVAL; NULL -> STANZA_ENULL. */
 int stanza_cast_f32_to_bf16(int64_t numel, const float *src, void *dst, void *stream);
 int stanza_cast_bf16_to_f32(int64_t numel, const void *src, float *dst, void *stream);
 /* The same cast over many tensors in one launch (a CONV worker's per-step bfloat16 copies of all its master filters).

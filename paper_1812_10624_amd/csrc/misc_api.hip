@@ -431,41 +431,13 @@ __global__ void gap_bwd_bf16_kernel(size_t total, int HW, int C, const float *__
 }
 
 // ------------------------------------------------------------------ bf16 casts
-__global__ void cast_f32_bf16_kernel(size_t numel, const float *__restrict__ src, uint16_t *__restrict__ dst)
-{
-    const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < numel) dst[i] = f32_to_bf16_rne(src[i]);
-}
-
-__global__ void cast_bf16_f32_kernel(size_t numel, const uint16_t *__restrict__ src, float *__restrict__ dst)
-{
-    const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < numel) dst[i] = __uint_as_float((uint32_t)src[i] << 16);
-}
-
-// Many tensors in one launch (the per-step bf16 copies of all master filters of a CONV worker: one launch instead of one per
-// layer).  Table in device memory, built by stanza_cast_plan:
-//   int64 chunk_prefix[n + 1]   exclusive prefix of per-tensor chunk counts (CAST_CHUNK elements each)
-//   int64 numel[n];  const float *src[n];  uint16 *dst[n]
+// A workgroup converts one block of CAST_CHUNK elements.  A full block of 16-byte-aligned tensors: 16 elements per thread as two
+// runs of 8 (four 16-byte loads and two 16-byte stores, or the reverse), every access of a wavefront contiguous.  The last block
+// of a tensor, and tensors that are not 16-byte aligned: element by element.
 constexpr int CAST_CHUNK = 4096;
-__global__ __launch_bounds__(256) void cast_f32_bf16_multi_kernel(const void *ws, int n)
+__device__ __forceinline__ void cast_block_f32_bf16(const float *__restrict__ s, uint16_t *__restrict__ d, int64_t left, bool vec)
 {
-    const int64_t *prefix = (const int64_t *)ws;
-    const int64_t *numel = prefix + (n + 1);
-    const float *const *src = (const float *const *)(numel + n);
-    uint16_t *const *dst = (uint16_t *const *)(src + n);
-    const int64_t chunk = blockIdx.x;
-    int lo = 0, hi = n;                      // largest t with prefix[t] <= chunk
-    while (hi - lo > 1) {
-        const int mid = (lo + hi) >> 1;
-        if (prefix[mid] <= chunk) lo = mid; else hi = mid;
-    }
-    const int64_t base = (chunk - prefix[lo]) * CAST_CHUNK, len = numel[lo];
-    const float *__restrict__ s = src[lo] + base;
-    uint16_t *__restrict__ d = dst[lo] + base;
-    const int64_t left = len - base;
-    if (left >= CAST_CHUNK) {
-        // 16 elements per thread as two runs of 8: four 16-byte loads, two 16-byte stores, every access of a wavefront contiguous
+    if (vec && left >= CAST_CHUNK) {
 #pragma unroll
         for (int h = 0; h < 2; ++h) {
             const int e0 = h * 2048 + threadIdx.x * 8;
@@ -478,8 +450,57 @@ __global__ __launch_bounds__(256) void cast_f32_bf16_multi_kernel(const void *ws
             *reinterpret_cast<uint4 *>(d + e0) = o;
         }
     } else {
-        for (int64_t i = threadIdx.x; i < left; i += 256) d[i] = f32_to_bf16_rne(s[i]);
+        const int n = (int)(left < CAST_CHUNK ? left : CAST_CHUNK);
+        for (int i = threadIdx.x; i < n; i += 256) d[i] = f32_to_bf16_rne(s[i]);
     }
+}
+
+__global__ __launch_bounds__(256) void cast_f32_bf16_kernel(size_t numel, const float *__restrict__ src, uint16_t *__restrict__ dst, int vec)
+{
+    const size_t base = (size_t)blockIdx.x * CAST_CHUNK;
+    cast_block_f32_bf16(src + base, dst + base, (int64_t)(numel - base), vec != 0);
+}
+
+__global__ __launch_bounds__(256) void cast_bf16_f32_kernel(size_t numel, const uint16_t *__restrict__ src, float *__restrict__ dst, int vec)
+{
+    const size_t base = (size_t)blockIdx.x * CAST_CHUNK;
+    const uint16_t *__restrict__ s = src + base;
+    float *__restrict__ d = dst + base;
+    const size_t left = numel - base;
+    if (vec && left >= CAST_CHUNK) {
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            const int e0 = h * 2048 + threadIdx.x * 8;
+            const uint4 v = *reinterpret_cast<const uint4 *>(s + e0);
+            *reinterpret_cast<float4 *>(d + e0) = make_float4(__uint_as_float(v.x << 16), __uint_as_float(v.x & 0xffff0000u),
+                                                              __uint_as_float(v.y << 16), __uint_as_float(v.y & 0xffff0000u));
+            *reinterpret_cast<float4 *>(d + e0 + 4) = make_float4(__uint_as_float(v.z << 16), __uint_as_float(v.z & 0xffff0000u),
+                                                                  __uint_as_float(v.w << 16), __uint_as_float(v.w & 0xffff0000u));
+        }
+    } else {
+        const int n = (int)(left < CAST_CHUNK ? left : CAST_CHUNK);
+        for (int i = threadIdx.x; i < n; i += 256) d[i] = __uint_as_float((uint32_t)s[i] << 16);
+    }
+}
+
+// Many tensors in one launch (the per-step bf16 copies of all master filters of a CONV worker: one launch instead of one per
+// layer).  Table in device memory, built by stanza_cast_plan:
+//   int64 chunk_prefix[n + 1]   exclusive prefix of per-tensor block counts (CAST_CHUNK elements each)
+//   int64 numel[n];  const float *src[n];  uint16 *dst[n]          (16-byte aligned: checked by stanza_cast_plan)
+__global__ __launch_bounds__(256) void cast_f32_bf16_multi_kernel(const void *ws, int n)
+{
+    const int64_t *prefix = (const int64_t *)ws;
+    const int64_t *numel = prefix + (n + 1);
+    const float *const *src = (const float *const *)(numel + n);
+    uint16_t *const *dst = (uint16_t *const *)(src + n);
+    const int64_t chunk = blockIdx.x;
+    int lo = 0, hi = n;                      // largest t with prefix[t] <= chunk
+    while (hi - lo > 1) {
+        const int mid = (lo + hi) >> 1;
+        if (prefix[mid] <= chunk) lo = mid; else hi = mid;
+    }
+    const int64_t base = (chunk - prefix[lo]) * CAST_CHUNK;
+    cast_block_f32_bf16(src[lo] + base, dst[lo] + base, numel[lo] - base, true);
 }
 
 // ------------------------------------------------------------------ aggregation + momentum SGD
@@ -841,7 +862,9 @@ extern "C" int stanza_cast_f32_to_bf16(int64_t numel, const float *src, void *ds
 {
     if (numel <= 0) return STANZA_EINVAL;
     if (!src || !dst) return STANZA_ENULL;
-    hipLaunchKernelGGL(cast_f32_bf16_kernel, dim3((unsigned)cdiv64(numel, 256)), dim3(256), 0, (hipStream_t)stream, (size_t)numel, src, (uint16_t *)dst);
+    if (cdiv64(numel, CAST_CHUNK) >= (int64_t(1) << 31)) return STANZA_EINVAL;
+    hipLaunchKernelGGL(cast_f32_bf16_kernel, dim3((unsigned)cdiv64(numel, CAST_CHUNK)), dim3(256), 0, (hipStream_t)stream, (size_t)numel, src,
+                       (uint16_t *)dst, (int)(aligned16(src) && aligned16(dst)));
     return launch_status();
 }
 
@@ -849,7 +872,9 @@ extern "C" int stanza_cast_bf16_to_f32(int64_t numel, const void *src, float *ds
 {
     if (numel <= 0) return STANZA_EINVAL;
     if (!src || !dst) return STANZA_ENULL;
-    hipLaunchKernelGGL(cast_bf16_f32_kernel, dim3((unsigned)cdiv64(numel, 256)), dim3(256), 0, (hipStream_t)stream, (size_t)numel, (const uint16_t *)src, dst);
+    if (cdiv64(numel, CAST_CHUNK) >= (int64_t(1) << 31)) return STANZA_EINVAL;
+    hipLaunchKernelGGL(cast_bf16_f32_kernel, dim3((unsigned)cdiv64(numel, CAST_CHUNK)), dim3(256), 0, (hipStream_t)stream, (size_t)numel,
+                       (const uint16_t *)src, dst, (int)(aligned16(src) && aligned16(dst)));
     return launch_status();
 }
 

@@ -137,6 +137,9 @@ def test_cast_plan_errors(api):
     assert lib.stanza_cast_plan(2, numel, ok, ok, p4, need, None) == -3
     assert lib.stanza_cast_plan(2, numel, ok, ok, p16, need - 1, None) == -5
     assert lib.stanza_cast_plan(2, (C.c_int64 * 2)(1 << 42, 1 << 42), ok, ok, p16, need, None) == -1   # more blocks than a grid holds
+    assert lib.stanza_cast_f32_to_bf16(0, p16, p16, None) == -1 and lib.stanza_cast_bf16_to_f32(-5, p16, p16, None) == -1
+    assert lib.stanza_cast_f32_to_bf16(1 << 44, p16, p16, None) == -1 and lib.stanza_cast_bf16_to_f32(1 << 44, p16, p16, None) == -1
+    assert lib.stanza_cast_f32_to_bf16(16, None, p16, None) == -2 and lib.stanza_cast_bf16_to_f32(16, p16, None, None) == -2
     assert lib.stanza_cast_f32_to_bf16_planned(0, numel, p16, need, None) == -1
     assert lib.stanza_cast_f32_to_bf16_planned(2, None, p16, need, None) == -2
     assert lib.stanza_cast_f32_to_bf16_planned(2, numel, None, need, None) == -2

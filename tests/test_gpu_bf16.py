@@ -133,6 +133,28 @@ def test_cast_round_trip(api):
     np.testing.assert_array_equal(host(back), wl_mod.round_bf16(a))
 
 
+@pytest.mark.parametrize("numel", [1, 255, 4095, 4096, 4097, 3 * 4096, 5 * 4096 + 17])
+@pytest.mark.parametrize("shift", [0, 1])
+def test_cast_sizes_and_alignment(api, numel, shift):
+    """Both casts around the kernel's 4096-element blocks, from 16-byte-aligned and from merely element-aligned pointers;
+    the elements behind the end stay untouched."""
+    a = np.random.default_rng(numel + shift).standard_normal(numel, dtype=np.float32)
+    src = torch.zeros(numel + shift, dtype=torch.float32, device="cuda:0")
+    src[shift:].copy_(torch.from_numpy(a))
+    full = torch.full((numel + shift + 8,), 1.5, dtype=torch.bfloat16, device="cuda:0")
+    api.stanza_cast_f32_to_bf16(src[shift:], full[shift:shift + numel])
+    bits = full.view(torch.int16).cpu().numpy().view(np.uint16)
+    np.testing.assert_array_equal(bits[shift:shift + numel], wl_mod.bf16_bits(a))
+    np.testing.assert_array_equal(bits[shift + numel:], np.full(8, 0x3FC0, np.uint16))
+    np.testing.assert_array_equal(bits[:shift], np.full(shift, 0x3FC0, np.uint16))
+    back = torch.full((numel + shift + 8,), -7.0, dtype=torch.float32, device="cuda:0")
+    api.stanza_cast_bf16_to_f32(full[shift:shift + numel], back[shift:shift + numel])
+    got = back.cpu().numpy()
+    np.testing.assert_array_equal(got[shift:shift + numel], wl_mod.round_bf16(a))
+    np.testing.assert_array_equal(got[shift + numel:], np.full(8, -7.0, np.float32))
+    np.testing.assert_array_equal(got[:shift], np.full(shift, -7.0, np.float32))
+
+
 def test_cast_many_tensors_in_one_launch(api):
     """The planned multi-tensor cast: bit-exact round-to-nearest-even on tensors of ragged sizes (below, at and across the kernel's
     4096-element blocks), dst guard elements untouched, and a second run after the sources changed."""
