@@ -153,9 +153,12 @@ __global__ __launch_bounds__(NTHREADS, (BM >= 256 ? 3 : (VECA && VECB) ? 4 : 2))
     constexpr int LDK = BK;      // unpadded 64-byte rows; the four 16-byte vectors of a row are XOR-swizzled (see kq_sw)
     constexpr int LDA = BM + PAD_V, LDB = BN + PAD_V;
     constexpr int A_FLOATS = A_ROWK ? BM * LDK : BK * LDA, B_FLOATS = B_ROWK ? BN * LDK : BK * LDB;
-    // one block: [A stage 0][A stage 1][B stage 0][B stage 1]; the epilogue reuses it to stage 32 output rows at a time
+    // one block: [A stage 0][A stage 1][B stage 0][B stage 1]; the epilogue reuses it to stage CROWS output rows at a time
     constexpr int SMEM_FLOATS = 2 * (A_FLOATS + B_FLOATS);
     static_assert(SMEM_FLOATS >= 32 * BN, "room for 32 staged output rows");
+    // output rows staged per epilogue pass: as many as the stage buffers hold (fewer barriers, more stores in flight)
+    constexpr int CROWS = BM * BN <= SMEM_FLOATS ? BM : (BM / 2) * BN <= SMEM_FLOATS ? BM / 2 : (BM / 4) * BN <= SMEM_FLOATS && BM / 4 >= 32 ? BM / 4 : 32;
+    static_assert(CROWS % 32 == 0 && BM % CROWS == 0 && CROWS * BN <= SMEM_FLOATS, "staged rows");
     __shared__ __attribute__((aligned(16))) float smem[SMEM_FLOATS];
     auto AsBuf = [&](int buf) -> float * { return smem + buf * A_FLOATS; };
     auto BsBuf = [&](int buf) -> float * { return smem + 2 * A_FLOATS + buf * B_FLOATS; };
@@ -619,29 +622,30 @@ __global__ __launch_bounds__(NTHREADS, (BM >= 256 ? 3 : (VECA && VECB) ? 4 : 2))
         return (size_t)row * p.Nn + col;
     };
     if (MODE != MODE_BWD_WEIGHT && (p.Nn & 3) == 0) {
-        // Output rows are whole 16-byte vectors: stage the tile in LDS 32 rows at a time and let every thread move float4s of
+        // Output rows are whole 16-byte vectors: stage the tile in LDS CROWS rows at a time and let every thread move float4s of
         // full row segments (bias / ReLU, or accumulate / mask, on the vectors).  One scalar store per accumulator register
         // (64 per thread, plus as many mask and accumulate loads in BWD_DATA) cost 9 % of a 64-channel 3x3 layer and a quarter
         // of a 1x1 layer with 64 input channels.
         constexpr int CH4 = BN / 4, ROWS_PASS = NTHREADS / CH4;
         float *Cs = smem;
 #pragma unroll
-        for (int chunk = 0; chunk < BM / 32; ++chunk) {
+        for (int chunk = 0; chunk < BM / CROWS; ++chunk) {
             __syncthreads();       // the stage buffers (first chunk) or the previous chunk have been read by everyone
 #pragma unroll
             for (int i = 0; i < TM; ++i) {
-                if (wave_m * WTM + i * 32 != chunk * 32) continue;
+                const int tile_row = wave_m * WTM + i * 32;          // rows of MFMA tile i are 32 consecutive tile rows here
+                if (tile_row / CROWS != chunk) continue;
 #pragma unroll
                 for (int j = 0; j < TN; ++j)
 #pragma unroll
                     for (int r = 0; r < 16; ++r)
-                        Cs[(8 * (r >> 2) + 4 * lk + (r & 3)) * BN + wave_n * WTN + wcol(j, lrow)] = acc[i][j][r];
+                        Cs[(tile_row % CROWS + 8 * (r >> 2) + 4 * lk + (r & 3)) * BN + wave_n * WTN + wcol(j, lrow)] = acc[i][j][r];
             }
             __syncthreads();
 #pragma unroll
-            for (int pass = 0; pass < 32 / ROWS_PASS; ++pass) {
+            for (int pass = 0; pass < CROWS / ROWS_PASS; ++pass) {
                 const int row_l = pass * ROWS_PASS + t / CH4, c4 = (t % CH4) * 4;
-                const int row = m0 + chunk * 32 + row_l, col = n0 + c4;
+                const int row = m0 + chunk * CROWS + row_l, col = n0 + c4;
                 if (row >= p.M || col >= p.Nn) continue;
                 float4 v = *reinterpret_cast<const float4 *>(&Cs[row_l * BN + c4]);
                 const size_t o = out_index(row, col);
