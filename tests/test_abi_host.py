@@ -201,3 +201,14 @@ def test_fc_compute_dtype_errors(api):
     assert api.FcPlan([64, 36, 10], 8, 0.01, 0.9, 0.0, compute_dtype=api.BF16).workspace_bytes() == 0     # width not a multiple of 8
     f32 = api.FcPlan([64, 32, 10], 8, 0.01, 0.9, 0.0).workspace_bytes()
     assert api.FcPlan([64, 32, 10], 8, 0.01, 0.9, 0.0, compute_dtype=api.BF16).workspace_bytes() > f32
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """One GPU's share is what this build measures: the bench script says so and exits before touching a device."""
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=120)
+    assert r.returncode == 2
+    assert "one GPU" in r.stderr and r.stdout.strip() == ""
+
