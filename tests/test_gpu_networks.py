@@ -75,27 +75,28 @@ def test_conv_stack_real_shapes(api, o32, name, B):
     print(f"{name}: features E={e_feat:.2e}, worst layer-wise backward E={worst:.2e}")
 
 
-@pytest.mark.parametrize("name", ["tiny", "minires"])
-def test_step_graph_replays_equal_eager_steps(api, name):
+@pytest.mark.parametrize("name,half", [("tiny", False), ("minires", False), ("miniresbn16", True), ("miniinception8", True)])
+def test_step_graph_replays_equal_eager_steps(api, name, half):
     """The whole layer-separated step captured as a HIP graph: three replays, with eager work and synchronisations between
     them, leave every parameter bit-identical to three eager steps from the same state (all reductions are fixed-order)."""
     import copy
     from paper_1812_10624_amd.netrun import Aggregator, ConvWorker, FcWorker, StepGraph
     wl = wl_mod.get_workload(name)
     K, B = wl.K, wl.B
-    cp = {n: (dev(w), dev(b)) for n, (w, b) in wl_mod.gen_conv_params(wl, 0).items()}
-    cm = {n: (torch.zeros_like(w), torch.zeros_like(b)) for n, (w, b) in cp.items()}
+    cp = {n: (dev(w), None if b is None else dev(b)) for n, (w, b) in wl_mod.gen_conv_params(wl, 0).items()}   # bias-free convolutions: None
+    cm = {n: (torch.zeros_like(w), None if b is None else torch.zeros_like(b)) for n, (w, b) in cp.items()}
     fp = [(dev(w), dev(b)) for w, b in wl_mod.gen_fc_params(wl, 0)]
     fm = [(torch.zeros_like(w), torch.zeros_like(b)) for w, b in fp]
     imgs = [dev(wl_mod.gen_images(wl, 0, k)) for k in range(K)]
     labels = dev(wl_mod.gen_labels(wl, 0))
     feats = torch.empty((K * B, wl.fc_dims[0]), device="cuda:0")
     # every worker writes its hand-off straight into its rows of the FC worker's feature buffer
-    workers = [ConvWorker(wl.ops, wl.image, B, cp, feat_out=feats[k * B:(k + 1) * B]) for k in range(K)]
-    fcw = FcWorker(wl.fc_dims, K * B, fp, fm, wl.lr, 0.9, 1e-4)  # momentum on, so the velocity buffers are exercised
-    names = list(cp)
-    agg = Aggregator([cp[n][i] for n in names for i in range(2)], [cm[n][i] for n in names for i in range(2)],
-                     [[wk.grads[n][i] for n in names for i in range(2)] for wk in workers])
+    # (half: the bf16 stacks, whose per-step filter copies are one planned multi-tensor cast inside the captured step)
+    dt = api.BF16 if half else api.F32
+    workers = [ConvWorker(wl.ops, wl.image, B, cp, dtype=dt, feat_out=feats[k * B:(k + 1) * B]) for k in range(K)]
+    fc_dt = api.BF16 if half and all(d % 8 == 0 for d in wl.fc_dims[:-1]) else api.F32
+    fcw = FcWorker(wl.fc_dims, K * B, fp, fm, wl.lr, 0.9, 1e-4, dtype=fc_dt)  # momentum on, so the velocity buffers are exercised
+    agg = Aggregator(wl_mod.flat_tensors(cp), wl_mod.flat_tensors(cm), [wl_mod.flat_tensors(wk.grads) for wk in workers])
 
     def step():
         for k, wk in enumerate(workers):
@@ -105,7 +106,7 @@ def test_step_graph_replays_equal_eager_steps(api, name):
             wk.backward(fcw.dfeats[k * B:(k + 1) * B])
         agg.step(1.0, wl.lr, 0.9, 1e-4)
 
-    state = [t for pair in list(cp.values()) + list(cm.values()) + fp + fm for t in pair]
+    state = [t for pair in list(cp.values()) + list(cm.values()) + fp + fm for t in pair if t is not None]
     saved = [t.clone() for t in state]
 
     def restore():
