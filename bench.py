@@ -137,8 +137,12 @@ def main():
     # ---- per-call instrumentation (HIP events on the stream the kernels are launched on)
     records = []     # (tag, start_event, end_event)
 
+    pool = []        # event pairs, reused by every step: a step's times are read before the next step records into them again
+
     def timed(tag, fn, *a, **kw):
-        s, e = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        if len(records) == len(pool):
+            pool.append((torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)))
+        s, e = pool[len(records)]
         s.record()
         fn(*a, **kw)
         e.record()
@@ -209,14 +213,36 @@ def main():
         plan_run = plan.run
         plan.run = lambda: timed("stanza_cast_f32_to_bf16", plan_run)
     n_timed_eager = args.steps
+    # The host must stay ahead of the GPU here, or the time the GPU waits for the next launch lands inside an event pair (a
+    # bf16 AlexNet-shaped step is 2.7 ms of GPU work behind some sixty calls, each now with two event records).  So every
+    # instrumented step starts with a bounded spin on the GPU (torch's own sleep kernel), a little longer than the host needs to
+    # issue the whole step: all of the step is queued before its first kernel starts.  The spin is outside every event pair.
+    t_issue = time.perf_counter()
     step_instrumented()
+    t_issue = time.perf_counter() - t_issue              # host time to issue one instrumented step (the GPU may still be running)
     torch.cuda.synchronize()
     records.clear()
-    t2 = time.perf_counter()
-    for i in range(args.steps):
-        step_instrumented()
+    ev_a, ev_b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    ev_a.record()
+    torch.cuda._sleep(1 << 20)
+    ev_b.record()
     torch.cuda.synchronize()
-    ms_per_step_instrumented = (time.perf_counter() - t2) * 1e3 / args.steps
+    ticks_per_ms = (1 << 20) / max(ev_a.elapsed_time(ev_b), 1e-3)
+    spin_ticks = int(min(1.5 * t_issue * 1e3 + 0.2, 50.0) * ticks_per_ms)       # at most 50 ms
+    inst_marks = []
+    per = {}         # entry point -> its calls' times in issue order, step after step
+    for i in range(args.steps):
+        torch.cuda._sleep(spin_ticks)
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        step_instrumented()
+        b.record()
+        inst_marks.append((a, b))
+        torch.cuda.synchronize()
+        for tag, s, e in records:
+            per.setdefault(tag, []).append(s.elapsed_time(e))
+        records.clear()
+    ms_per_step_instrumented = sum(a.elapsed_time(b) for a, b in inst_marks) / args.steps      # GPU time of a step, spin excluded
     netrun.api = api
     if plan is not None:
         plan.run = plan_run
@@ -224,9 +250,6 @@ def main():
     step_ms = sorted(marks[i].elapsed_time(marks[i + 1]) for i in range(args.steps))     # each step between events on the stream
     props = torch.cuda.get_device_properties(0)
 
-    per = {}
-    for tag, s, e in records:
-        per.setdefault(tag, []).append(s.elapsed_time(e))
     tot = {k: sum(v) / n_timed_eager for k, v in per.items()}      # ms per step per entry point
     conv_ms = sum(tot.get(k, 0.0) for k in ("stanza_conv_fwd", "stanza_conv_bwd_data", "stanza_conv_bwd_weight"))
     conv_worker_ms = sum(v for k, v in tot.items() if k not in ("stanza_fc_step", "stanza_ps_aggregate"))
