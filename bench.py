@@ -88,6 +88,9 @@ def main():
     ap.add_argument("--graph", action="store_true",
                     help="replay the step as one HIP graph in the timed region (launch-bound workloads); the per-call breakdown "
                          "and the roofline figures then come from the eager warm-up steps")
+    ap.add_argument("--only", default=None, choices=["ps"],
+                    help="ps: run only the K = 16 aggregation of BASELINE.json's config 5 (conv set and FC set) and print its figures; "
+                         "with --calibrate the known-size launch that scales the profiler's HBM counters runs first")
     ap.add_argument("--calibrate", action="store_true",
                     help="also launch one stanza_add_relu_fwd over 3 x 1 GiB (2 GiB read, 1 GiB written): the known-size "
                          "kernel that scales rocprofv3's FETCH_SIZE / WRITE_SIZE counters")
@@ -107,6 +110,15 @@ def main():
     api.load()
     assert torch.cuda.is_available(), "bench.py needs the GPU (there is no CPU path)"
     dev = torch.device("cuda:0")
+    if args.only == "ps":
+        if args.calibrate:
+            ca, cb, cc = (torch.ones(1 << 28, device=dev) for _ in range(3))
+            api.stanza_add_relu_fwd(ca, cb, cc)
+            torch.cuda.synchronize()
+            del ca, cb, cc
+            torch.cuda.empty_cache()
+        print(json.dumps({"ps_aggregate_k16": ps_config5(torch, api, W, dev, iters=args.steps)}))
+        return
     wl = W.get_workload(args.workload)
     K, B, n = wl.K, wl.B, wl.n
     seed = 0
@@ -204,8 +216,18 @@ def main():
         for i in range(args.steps):
             run_step()
             marks[i + 1].record()
+            if i == 0:
+                loss_first = fcw.loss.clone()      # one 4-byte device copy inside the timed region
         torch.cuda.synchronize()
         t1 = time.perf_counter()
+    # The timed data is live: every step is a real SGD step on the same batch, so the loss is finite and moves, and the features
+    # this worker hands over keep about half of their units active (a stack whose activations had died would time faster).
+    import math
+    live = {"loss_after_first_timed_step": float(loss_first.item()), "loss_after_last_timed_step": float(fcw.loss.item()),
+            "handed_over_features_nonzero_fraction": float((feats[:B] != 0).float().mean().item()),
+            "fc_gradient_handed_back_abs_max": float(fcw.dfeats[:B].abs().max().item())}
+    assert all(math.isfinite(v) for v in live.values()), live
+    assert live["loss_after_first_timed_step"] != live["loss_after_last_timed_step"] and live["handed_over_features_nonzero_fraction"] > 0.01, live
     # ---- the same K steps again, eager, with an event pair around every entry-point call: per-call times, roofline
     netrun.api = tap
     plan = getattr(worker, "cast_plan", None)          # the one-launch cast of all bf16 filter copies is a method of its plan object
@@ -344,6 +366,7 @@ def main():
         "dtype": args.dtype, "data": "synthetic", "launch": "hip_graph_replay" if args.graph else "eager",
         "config": {"workload": f"{wl.name}_shaped_conv_worker_B{B}_fc_worker_n{n}_K{K}_" + ("fp32" if args.dtype == "f32" else "bf16in_fp32acc"),
                    "per_worker_batch": B, "conv_workers_K": K, "fc_rows": n, "fc_dropout": args.dropout},
+        "timed_data_is_live": live,
         "conv_worker_images_per_s": B / (conv_worker_ms * 1e-3),
         "conv_worker_ms": conv_worker_ms,
         "fc_worker_samples_per_s": n / (tot["stanza_fc_step"] * 1e-3),
@@ -397,7 +420,7 @@ def traffic_from_profile(workload):
         return None
 
 
-def ps_config5(torch, api, W, dev):
+def ps_config5(torch, api, W, dev, iters=20):
     """Benchmark config 5: K = 16 gradient shards over the VGG-16-shaped conv parameter set (26 tensors) and
     over the FC set (6 tensors); one launch each, timed with HIP events, three buffer sets rotated for the conv
     set so that w and v do not stay in the 256 MB Infinity Cache between repetitions."""
@@ -415,7 +438,6 @@ def ps_config5(torch, api, W, dev):
         for i in range(3):
             api.stanza_ps_aggregate_planned(sets[i % nsets][1], 1.0, 0.01, 0.9, 5e-4, sets[i % nsets][0])
         torch.cuda.synchronize()
-        iters = 20
         s, e = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         s.record()
         for i in range(iters):

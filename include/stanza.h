@@ -17,9 +17,10 @@
  *   - Pointers are DEVICE pointers unless the name starts with host_; descriptor structs
  *     are read on the host during the call and may be freed after it returns.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls only
- *     enqueue work and return; nothing synchronises.  Scalar results stay in device memory.
- *   - The caller owns every buffer, workspace included.  The library allocates no device
- *     memory and keeps no state between calls.
+ *     enqueue kernel launches and return: nothing synchronises, nothing is copied by the runtime, so every
+ *     call may be recorded in a stream capture.  Scalar results stay in device memory.
+ *   - The caller owns every buffer, workspace included.  The library allocates no memory, on
+ *     the device or the host, and keeps no state between calls.
  *   - Layouts: activations NHWC ([N][H][W][C], C fastest); conv weights [K][R][S][C];
  *     FC weights [out][in]; features [n][A] with A the NHWC flattening (h*W + w)*C + c of
  *     the last pooled map, worker k owning rows k*B .. (k+1)*B-1.
@@ -102,7 +103,7 @@ typedef struct {
 const char *stanza_strerror(int status);
 int stanza_version(void);
 
-/* ---- CONV worker: forward (Sec. 3.2: "each CONV worker processes [its batch] up to the last CONV layer")
+/* ---- CONV worker: forward pass of one layer of its conv stack (Sec. 3.1, Sec. 3.2)
  *   y[n,p,q,k] = bias[k] + sum_{r,s,c} x[n, p*stride_h - pad_h + r, q*stride_w - pad_w + s, c] * w[k,r,s,c]
  * followed by max(.,0) with STANZA_CONV_RELU.  bias (float32 [K]) is required iff STANZA_CONV_BIAS.
  * which: 0 forward, 1 backward-data, 2 backward-weight.  For forward and backward-data the workspace is OPTIONAL:
@@ -121,8 +122,8 @@ int stanza_conv_fwd(const stanza_conv_desc *desc, const void *x, const void *w, 
 int stanza_conv_fwd_res(const stanza_conv_desc *desc, const void *x, const void *w, const float *bias, const void *res,
                         void *y, void *ws, size_t ws_bytes, void *stream);
 
-/* ---- CONV worker: backpropagation to the layer input (Sec. 3.2: "CONV workers then continue the
- * backpropagation"):
+/* ---- CONV worker: backpropagation to the layer input, run once the FC worker has handed back the gradient of the
+ * worker's activations (Sec. 3.2):
  *   dx[n,h,w,c] = sum_{k,r,s} g[n,(h+pad_h-r)/stride_h,(w+pad_w-s)/stride_w,k] * w[k,r,s,c]
  * over the taps where both divisions are exact and in range, with g = dy, or dy*[y>0] when
  * STANZA_CONV_RELU is set and y (the forward output) is not NULL.
@@ -132,7 +133,7 @@ int stanza_conv_fwd_res(const stanza_conv_desc *desc, const void *x, const void 
 int stanza_conv_bwd_data(const stanza_conv_desc *desc, const void *dy, const void *y, const void *w,
                          const void *x_mask, void *dx, void *ws, size_t ws_bytes, void *stream);
 
-/* ---- CONV worker: filter and bias gradients ("time to compute CONV layer gradients", T_c of Sec. 4.2.1)
+/* ---- CONV worker: filter and bias gradients (part of the conv compute time T_c of Sec. 4.2.1)
  *   dw[k,r,s,c] = sum_{n,p,q} g[n,p,q,k] * x[n, p*stride_h - pad_h + r, q*stride_w - pad_w + s, c]
  *   dbias[k]    = sum_{n,p,q} g[n,p,q,k]           (written iff STANZA_CONV_BIAS; then dbias != NULL)
  * g as above.  dw, dbias are float32 and overwritten.  The long reduction is split over workgroups
@@ -217,7 +218,9 @@ int stanza_cast_f32_to_bf16(int64_t numel, const float *src, void *dst, void *st
 int stanza_cast_bf16_to_f32(int64_t numel, const void *src, float *dst, void *stream);
 /* The same cast over many tensors in one launch (a CONV worker's per-step bfloat16 copies of all its master filters).
  *   stanza_cast_plan writes a table of the n tensors (host_numel[t] elements from host_src[t] to host_dst[t]; device pointers, 16-byte
- *   aligned, held in host arrays) into ws (stanza_cast_workspace_bytes(n) bytes, caller-owned) and waits for that copy;
+ *   aligned, held in host arrays) into ws (stanza_cast_workspace_bytes(n) bytes, caller-owned).  The table travels inside the
+ *   arguments of small fill launches on `stream` (one per 480 table words): the call only enqueues, the host arrays may be freed
+ *   when it returns, and it may be recorded in a stream capture like every other call;
  *   stanza_cast_f32_to_bf16_planned then converts all of them, any number of times, with the same n and host_numel.
  * Errors: n < 1, a tensor with numel < 1 -> STANZA_EINVAL; NULL / alignment / workspace size as elsewhere. */
 size_t stanza_cast_workspace_bytes(int32_t n_tensors);
@@ -226,7 +229,7 @@ int stanza_cast_plan(int32_t n_tensors, const int64_t *host_numel, const float *
 int stanza_cast_f32_to_bf16_planned(int32_t n_tensors, const int64_t *host_numel, const void *ws, size_t ws_bytes, void *stream);
 
 /* ---- FC worker step (Sec. 3.2: the FC worker collects the activations of all workers, continues the
- * forward pass to the loss, backpropagates through the FC layers and "the last CONV layer"'s
+ * forward pass to the loss, backpropagates through the FC layers down to the gradient of the received
  * activations, sends those gradients back and updates the FC parameters).
  *   forward   Z_l = A_{l-1} W_l^T + b_l, A_l = max(Z_l, 0) for l < n_layers, A_0 = feats
  *   loss      (1/n) sum_i [logsumexp(Z_L[i,:]) - Z_L[i, labels[i]]]   (mean over the GLOBAL batch n, which
@@ -255,9 +258,8 @@ int stanza_fc_step(const stanza_fc_desc *desc, const float *feats, const int32_t
  * Errors: numel < 1 or >= 2^31, p outside [0, 1) -> STANZA_EINVAL; NULL / alignment as elsewhere. */
 int stanza_dropout(int64_t numel, float p, uint64_t seed, uint64_t stream_id, const float *x, float *y, void *stream);
 
-/* ---- One of several FC workers (Sec. 4.1.3: "each is responsible for an equal number of the CONV workers ... each FC
- * worker maintains a complete set of FC layers", and the FC workers then exchange their gradients by the same recursive
- * doubling).  The same forward / loss / backward as stanza_fc_step over this worker's n_samples rows, except that
+/* ---- One of several FC workers (Sec. 4.1.3: the CONV workers are divided evenly among the FC workers, every FC worker holds
+ * its own full copy of the FC layers, and the FC workers then exchange their gradients by the same recursive doubling).  The same forward / loss / backward as stanza_fc_step over this worker's n_samples rows, except that
  *   - the loss is still the mean over the GLOBAL batch of n_global >= n_samples rows (Eq. 1): loss_part =
  *     (1/n_global) sum over this worker's rows, dZ_L = (softmax - onehot)/n_global, so that the workers' parts add up;
  *   - nothing is updated: dW_l and db_l are written to host_gW[l] ([out][in]) and host_gb[l] ([out]), float32, for
@@ -268,20 +270,21 @@ int stanza_fc_grads(const stanza_fc_desc *desc, int32_t n_global, const float *f
                     float *const *host_W, float *const *host_b, float *const *host_gW, float *const *host_gb,
                     float *dfeats, float *loss_part, int32_t *pred, void *ws, size_t ws_bytes, void *stream);
 
-/* ---- Gradient aggregation and update (Sec. 3.2: the CONV workers "exchange [their gradients] to get
- * global information sum_x grad l(x, w_conv)" and update; Sec. 2.2: servers aggregate the gradients
- * from all workers and perform the global update).  Per tensor t and element i:
+/* ---- Gradient aggregation and update (Sec. 3.2: the CONV workers combine their gradients into the gradient of the
+ * whole batch, sum_x grad l(x, w_conv), and update their replicas; Sec. 2.2: the servers add up the workers' gradients
+ * and apply the update).  Per tensor t and element i:
  *   g = scale * (g_0[i] + g_1[i] + ... + g_{K-1}[i]) + weight_decay * w[i]   (shards added in index order)
  *   v[i] = momentum * v[i] + g;   w[i] -= lr * v[i]
  * host_numel [n_tensors]; host_w, host_v [n_tensors] device pointers (updated in place);
  * host_grads [K * n_tensors] device pointers, shard-major: host_grads[k*n_tensors + t].
- * One launch covers all tensors.  ws receives the pointer table
- * (stanza_ps_workspace_bytes(n_tensors, K) bytes, uploaded on `stream` from the host arrays, which
- * may be freed when the call returns).
- * stanza_ps_plan uploads the table only; it is the one call that waits (for its own small copy on
- * `stream`).  stanza_ps_aggregate_planned runs the launch on a table a previous stanza_ps_plan /
- * stanza_ps_aggregate put into ws (same n_tensors, host_numel, K), for callers whose buffers stay put
- * from one iteration to the next; it only enqueues. */
+ * One launch covers all tensors.  ws receives the pointer table (stanza_ps_workspace_bytes(n_tensors, K) bytes).  The
+ * table travels inside the arguments of small fill launches on `stream`, one per 480 table words (n_tensors*(K + 4) + 1
+ * words in all: two launches for a 26-tensor set at K = 16), which precede the aggregation launch on the same stream:
+ * nothing is allocated, no copy is issued and nothing waits, the host arrays may be freed when the call returns, and the
+ * call may be recorded in a stream capture.
+ * stanza_ps_plan writes the table only.  stanza_ps_aggregate_planned runs the aggregation launch on a table a previous
+ * stanza_ps_plan / stanza_ps_aggregate put into ws (same n_tensors, host_numel, K), for callers whose buffers stay put
+ * from one iteration to the next. */
 size_t stanza_ps_workspace_bytes(int32_t n_tensors, int32_t K);
 int stanza_ps_plan(int32_t n_tensors, const int64_t *host_numel, float *const *host_w, float *const *host_v,
                    const float *const *host_grads, int32_t K, void *ws, size_t ws_bytes, void *stream);

@@ -3,8 +3,8 @@
  *
  * Plain, slow, definition-level C for every operation of one training iteration
  * with the CONV and FC layers trained on separate workers (paper: Sec. 3.2,
- * "Training Process with Layer Separation"; update rule Eq. (1) of Sec. 2.1;
- * momentum SGD with weight decay per Sec. 6.1 "Setup").  The method reaches
+ * the training process with separated layers; update rule Eq. (1) of Sec. 2.1;
+ * momentum SGD with weight decay per the experimental setup of Sec. 6.1).  The method reaches
  * exactly an ordinary mini-batch SGD step, so each function below is the plain
  * definition of its operation written as nested loops.  No blocking, no
  * vector intrinsics, no BLAS; OpenMP splits only the outermost independent loop.
@@ -152,7 +152,7 @@ double oracle_conv_bwd_data_at(const oconv_t *d, const REAL *dy, const REAL *w, 
     return bwd_data_at(d, dy, w, Ho, Wo, n, h, ww, c);
 }
 
-/* Gradient w.r.t. the filter and the bias ("CONV layer gradients", Sec. 3.2 / T_c in Sec. 4.2.1):
+/* Gradient w.r.t. the filter and the bias (the conv gradients of Sec. 3.2; part of T_c in Sec. 4.2.1):
  *   dW[k,r,s,c] = sum_{n,p,q} dY[n,p,q,k] * X[n, p*sh - ph + r, q*sw - pw + s, c]
  *   db[k]       = sum_{n,p,q} dY[n,p,q,k] */
 static double bwd_weight_at(const oconv_t *d, const REAL *x, const REAL *dy, int Ho, int Wo, int k, int r, int s, int c)
@@ -311,7 +311,7 @@ void oracle_gap_bwd(int N, int HW, int C, const REAL *df, REAL *dx)
 }
 
 /* ------------------------------------------------------------------ FC layers
- * "Neurons in an FC layer have connections to all outputs in the previous layer"
+ * Every output unit of an FC layer reads every output of the layer before it
  * (Sec. 3.1):  Z[i,o] = b[o] + sum_j A[i,j] * Wt[o,j], optional ReLU. */
 void oracle_fc_fwd(int n, int in, int out, const REAL *a, const REAL *w, const REAL *b, int relu, REAL *z)
 {
@@ -469,7 +469,7 @@ void oracle_avgpool_bwd(const opool_t *d, const REAL *dy, REAL *dx)
 }
 
 /* -------------------------------------------------------------- batch normalisation
- * The residual networks of the paper's table of models (Sec. 6.1 "Setup") carry a
+ * The residual networks of the paper's table of models (Sec. 6.1) carry a
  * normalisation layer after every convolution; the paper never discusses it, so the
  * transform is taken as published (training mode): over the M = N*H*W rows of an
  * NHWC tensor viewed as [M][C], per channel c

@@ -1,5 +1,5 @@
 // Batch normalisation (training mode) on the CONV worker, for the residual networks of the paper's table of models
-// (Sec. 6.1 "Setup"), which carry a normalisation layer after every convolution.  The paper does not describe the layer;
+// (Sec. 6.1), which carry a normalisation layer after every convolution.  The paper does not describe the layer;
 // the transform is the published one, with the statistics taken over the worker's own batch.
 //
 // An NHWC tensor is a [rows][C] matrix with the channel contiguous, so every kernel here is a column-wise pass over a

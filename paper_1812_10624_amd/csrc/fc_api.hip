@@ -253,8 +253,12 @@ static int fc_layout(const stanza_fc_desc *d, FcLayout *lay)
         size_t dwf = 0;
         int maxh = 0;
         lay->wgrad_bytes = 0;
+        // Everything the nested bfloat16 convolution calls could refuse is refused here, before the first launch: widths that are
+        // not multiples of 8, and operands of 2 GiB and more (those calls address them with 32-bit byte offsets).
         for (int l = 0; l < L; ++l) {
             if (d->host_dims[l] % 8) return STANZA_EUNSUPPORTED;
+            if ((int64_t)n * d->host_dims[l] * 2 >= (int64_t(1) << 31)) return STANZA_EUNSUPPORTED;
+            if (l > 0 && (int64_t)d->host_dims[l] * d->host_dims[l - 1] * 2 >= (int64_t(1) << 31)) return STANZA_EUNSUPPORTED;
             lay->a16_off[l] = off; off += round256((size_t)n * d->host_dims[l] * 2) / 4;
         }
         for (int l = 1; l < L; ++l) {
@@ -313,7 +317,9 @@ static int fc_run(const stanza_fc_desc *desc, int n_global, const float *feats, 
     for (int l = 0; l < L; ++l) {
         if (!host_W[l] || !host_b[l]) return STANZA_ENULL;
         if (fused ? (!host_vW[l] || !host_vb[l]) : (!host_gW[l] || !host_gb[l])) return STANZA_ENULL;
-        if (!aligned16(host_W[l]) || !aligned16(host_b[l]) || !aligned16(fused ? host_vW[l] : host_gW[l])) return STANZA_EALIGN;
+        if (!aligned16(host_W[l]) || !aligned16(host_b[l]) || !aligned16(fused ? host_vW[l] : host_gW[l]) ||
+            !aligned16(fused ? host_vb[l] : host_gb[l]))
+            return STANZA_EALIGN;
     }
     hipStream_t st = (hipStream_t)stream;
     float *base = (float *)ws;

@@ -1,8 +1,7 @@
 // HBM-bound entry points: max-pool(+ReLU) forward/backward kept on the CONV worker (paper Sec. 3.2,
 // note on the split point), the residual join and global average pool of the residual-network-shaped
-// workload, bf16 casts, and the gradient aggregation + momentum-SGD update (Sec. 3.2 "exchange
-// [gradients] among all CONV workers ... and perform CONV layer parameter update"; Sec. 2.2 server-side
-// aggregation).  Every kernel moves each byte once with 16-byte accesses along the contiguous axis.
+// workload, bf16 casts, and the gradient aggregation + momentum-SGD update (Sec. 3.2: the CONV workers combine
+// their gradients and update their replicas of the conv parameters; Sec. 2.2: server-side aggregation).  Every kernel moves each byte once with 16-byte accesses along the contiguous axis.
 #include "internal.h"
 
 namespace stanza {
@@ -483,6 +482,44 @@ __global__ __launch_bounds__(256) void cast_bf16_f32_kernel(size_t numel, const 
     }
 }
 
+// A small table of 8-byte words (element counts and device pointers) reaches device memory INSIDE kernel arguments: the launch
+// copies them into its argument buffer, so the host arrays may be freed when the call returns, nothing is allocated or staged
+// on the host, no copy engine is involved and nothing waits; under stream capture the words become part of the graph node.
+// A table longer than one launch's argument space goes out in several launches, in order, on the same stream.
+constexpr int FILL_WORDS = 480;            // 3,840 bytes of the 4 KB a launch may carry
+struct FillChunk {
+    uint64_t w[FILL_WORDS];
+};
+
+__global__ __launch_bounds__(256) void table_fill_kernel(uint64_t *__restrict__ dst, int count, const FillChunk c)
+{
+    for (int i = threadIdx.x; i < count; i += 256) dst[i] = c.w[i];
+}
+
+class TableWriter {
+public:
+    TableWriter(void *dst, hipStream_t st) : dst_((uint64_t *)dst), st_(st) {}
+    void push(uint64_t word)
+    {
+        chunk_.w[n_++] = word;
+        if (n_ == FILL_WORDS) flush();
+    }
+    void push_ptr(const void *ptr) { push((uint64_t)reinterpret_cast<uintptr_t>(ptr)); }
+    void flush()
+    {
+        if (n_ == 0) return;
+        hipLaunchKernelGGL(table_fill_kernel, dim3(1), dim3(256), 0, st_, dst_, n_, chunk_);
+        dst_ += n_;
+        n_ = 0;
+    }
+
+private:
+    uint64_t *dst_;
+    hipStream_t st_;
+    int n_ = 0;
+    FillChunk chunk_;
+};
+
 // Many tensors in one launch (the per-step bf16 copies of all master filters of a CONV worker: one launch instead of one per
 // layer).  Table in device memory, built by stanza_cast_plan:
 //   int64 chunk_prefix[n + 1]   exclusive prefix of per-tensor block counts (CAST_CHUNK elements each)
@@ -900,26 +937,19 @@ extern "C" int stanza_cast_plan(int32_t n_tensors, const int64_t *host_numel, co
         acc += cdiv64(host_numel[t], CAST_CHUNK);
     }
     if (acc >= (int64_t(1) << 31)) return STANZA_EINVAL;
-    char *stage = (char *)malloc(need);
-    if (!stage) return STANZA_EINVAL;
-    int64_t *prefix = (int64_t *)stage;
-    int64_t *numel = prefix + (n_tensors + 1);
-    const void **src = (const void **)(numel + n_tensors);
-    void **dst = (void **)(src + n_tensors);
+    // table layout: prefix[n + 1], numel[n], src[n], dst[n]
+    TableWriter tw(ws, (hipStream_t)stream);
     acc = 0;
     for (int t = 0; t < n_tensors; ++t) {
-        prefix[t] = acc;
+        tw.push((uint64_t)acc);
         acc += cdiv64(host_numel[t], CAST_CHUNK);
-        numel[t] = host_numel[t];
-        src[t] = host_src[t];
-        dst[t] = host_dst[t];
     }
-    prefix[n_tensors] = acc;
-    // Pageable source: the runtime has consumed `stage` when this returns, so it can be freed at once.
-    hipError_t e = hipMemcpyAsync(ws, stage, need, hipMemcpyHostToDevice, (hipStream_t)stream);
-    if (e == hipSuccess) e = hipStreamSynchronize((hipStream_t)stream);
-    free(stage);
-    return hip_status(e);
+    tw.push((uint64_t)acc);
+    for (int t = 0; t < n_tensors; ++t) tw.push((uint64_t)host_numel[t]);
+    for (int t = 0; t < n_tensors; ++t) tw.push_ptr(host_src[t]);
+    for (int t = 0; t < n_tensors; ++t) tw.push_ptr(host_dst[t]);
+    tw.flush();
+    return launch_status();
 }
 
 extern "C" int stanza_cast_f32_to_bf16_planned(int32_t n_tensors, const int64_t *host_numel, const void *ws, size_t ws_bytes, void *stream)
@@ -956,6 +986,24 @@ static int ps_total_chunks(int32_t n_tensors, const int64_t *host_numel, int64_t
     return STANZA_OK;
 }
 
+// The table of ps_aggregate_kernel (prefix[n + 1], numel[n], w[n], v[n], grads[K * n]) written to `table` by launches on `st`.
+static void ps_write_table(int32_t n_tensors, const int64_t *host_numel, float *const *host_w, float *const *host_v,
+                           const float *const *host_grads, int32_t K, void *table, hipStream_t st)
+{
+    TableWriter tw(table, st);
+    int64_t acc = 0;
+    for (int t = 0; t < n_tensors; ++t) {
+        tw.push((uint64_t)acc);
+        acc += cdiv64(host_numel[t], PS_CHUNK);
+    }
+    tw.push((uint64_t)acc);
+    for (int t = 0; t < n_tensors; ++t) tw.push((uint64_t)host_numel[t]);
+    for (int t = 0; t < n_tensors; ++t) tw.push_ptr(host_w[t]);
+    for (int t = 0; t < n_tensors; ++t) tw.push_ptr(host_v[t]);
+    for (size_t i = 0; i < (size_t)K * n_tensors; ++i) tw.push_ptr(host_grads[i]);
+    tw.flush();
+}
+
 extern "C" int stanza_ps_plan(int32_t n_tensors, const int64_t *host_numel, float *const *host_w, float *const *host_v,
                               const float *const *host_grads, int32_t K, void *ws, size_t ws_bytes, void *stream)
 {
@@ -976,29 +1024,8 @@ extern "C" int stanza_ps_plan(int32_t n_tensors, const int64_t *host_numel, floa
             if (!aligned16(gp)) return STANZA_EALIGN;
         }
     }
-    // Assemble the table on the host in the device layout, then one copy.
-    char *stage = (char *)malloc(need);
-    if (!stage) return STANZA_EINVAL;
-    int64_t *prefix = (int64_t *)stage;
-    int64_t *numel = prefix + (n_tensors + 1);
-    void **w = (void **)(numel + n_tensors);
-    void **v = w + n_tensors;
-    const void **grads = (const void **)(v + n_tensors);
-    int64_t acc = 0;
-    for (int t = 0; t < n_tensors; ++t) {
-        prefix[t] = acc;
-        acc += cdiv64(host_numel[t], PS_CHUNK);
-        numel[t] = host_numel[t];
-        w[t] = host_w[t];
-        v[t] = host_v[t];
-    }
-    prefix[n_tensors] = acc;
-    for (size_t i = 0; i < (size_t)K * n_tensors; ++i) grads[i] = host_grads[i];
-    // Pageable source: the runtime has consumed `stage` when this returns, so it can be freed at once.
-    hipError_t e = hipMemcpyAsync(ws, stage, need, hipMemcpyHostToDevice, (hipStream_t)stream);
-    if (e == hipSuccess) e = hipStreamSynchronize((hipStream_t)stream);
-    free(stage);
-    return hip_status(e);
+    ps_write_table(n_tensors, host_numel, host_w, host_v, host_grads, K, ws, (hipStream_t)stream);
+    return launch_status();
 }
 
 template <int ORDER>

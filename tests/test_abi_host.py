@@ -102,6 +102,13 @@ def test_fc_and_ps_errors(api):
     assert lib.stanza_fc_grads(C.byref(plan.desc), 7, p16, p16, arr, arr, arr, arr, p16, p16, None, p16, need, None) == -1   # n_global < rows
     assert lib.stanza_fc_grads(C.byref(plan.desc), 16, p16, p16, arr, arr, None, arr, p16, p16, None, p16, need, None) == -2
     assert lib.stanza_fc_grads(C.byref(plan.desc), 16, p16, p16, arr, arr, arr, arr, p16, p16, None, p16, need - 1, None) == -5
+    # every parameter and momentum pointer is checked for 16-byte alignment before any launch, the bias momentum included
+    odd = (C.c_void_p * 2)(0x1000, 0x2004)
+    for pos in range(4):
+        args = [arr, arr, arr, arr]
+        args[pos] = odd
+        assert lib.stanza_fc_step(C.byref(plan.desc), p16, p16, *args, p16, p16, None, p16, need, None) == -3, pos
+        assert lib.stanza_fc_grads(C.byref(plan.desc), 16, p16, p16, *args, p16, p16, None, p16, need, None) == -3, pos
     bad = api.FcPlan([64, 0, 10], 8, 0.01, 0.9, 0.0)
     assert bad.workspace_bytes() == 0
     assert lib.stanza_ps_workspace_bytes(0, 4) == 0
@@ -199,6 +206,9 @@ def test_avgpool_and_copy_errors(api):
 def test_fc_compute_dtype_errors(api):
     assert api.FcPlan([64, 32, 10], 8, 0.01, 0.9, 0.0, compute_dtype=7).workspace_bytes() == 0
     assert api.FcPlan([64, 36, 10], 8, 0.01, 0.9, 0.0, compute_dtype=api.BF16).workspace_bytes() == 0     # width not a multiple of 8
+    # bfloat16 hidden layers: an operand of 2 GiB and more is refused by the layout query, before anything runs
+    assert api.FcPlan([1 << 20, 1024, 10], 1024, 0.01, 0.9, 0.0, compute_dtype=api.BF16).workspace_bytes() == 0
+    assert api.FcPlan([1 << 20, 1024, 10], 512, 0.01, 0.9, 0.0, compute_dtype=api.BF16).workspace_bytes() == 0   # the weights
     f32 = api.FcPlan([64, 32, 10], 8, 0.01, 0.9, 0.0).workspace_bytes()
     assert api.FcPlan([64, 32, 10], 8, 0.01, 0.9, 0.0, compute_dtype=api.BF16).workspace_bytes() > f32
 

@@ -160,8 +160,14 @@ def test_normalised_residual_step(api, o32, K, B):
     """The layer-separated step of the small normalised residual stack: features, loss, handed-back gradient, every
     worker's filter / scale / shift gradients, the aggregated update."""
     from paper_1812_10624_amd.netrun import Aggregator, ConvWorker, FcWorker
+    from gpu_util import param_update_err
     wl = wl_mod.get_workload("miniresbn")
     seed = 4
+    # Whole-chain bound.  Every normalisation layer (gated at 1e-4 on its own in test_bn_forward_backward) divides by a standard
+    # deviation taken over as few as B*4 values per channel in the last stage, and its backward pass subtracts two means:
+    # the rounding of everything upstream is amplified by gamma*istd at each of the 13 layers.  Measured whole-chain
+    # E(tau = 0.05) = 4.1e-4 (K=2, B=3) and 4.5e-4 (K=3, B=4); the same chain without normalisation (minires) stays at 1.3e-5.
+    chain = 6e-4
     imgs = [wl_mod.gen_images(wl, seed, k, B) for k in range(K)]
     labels = wl_mod.gen_labels(wl, seed, K * B)
     cp = wl_mod.gen_conv_params(wl, seed)
@@ -199,7 +205,7 @@ def test_normalised_residual_step(api, o32, K, B):
                 if cp[nme][i] is None:
                     assert wk.grads[nme][i] is None
                     continue
-                assert rel_err(host(wk.grads[nme][i]), ref["worker_grads"][k][nme][i]) < 5 * TOL_F32, (k, nme, i)
+                assert rel_err(host(wk.grads[nme][i]), ref["worker_grads"][k][nme][i]) < chain, (k, nme, i)
     flat = lambda d: [t for pair in d.values() for t in pair if t is not None]
     agg = Aggregator(flat(gpar), flat(gcm), [flat(wk.grads) for wk in workers])
     agg.step(1.0, lr, mom, wd)
@@ -207,8 +213,8 @@ def test_normalised_residual_step(api, o32, K, B):
         for i in range(2):
             if cp[nme][i] is None:
                 continue
-            assert rel_err(host(gcm[nme][i]), cm_ref[nme][i]) < 5 * TOL_F32, (nme, i)
-            assert rel_err(host(gpar[nme][i]) - cp[nme][i], cp_ref[nme][i] - cp[nme][i]) < 5 * TOL_F32, (nme, i)
+            assert rel_err(host(gcm[nme][i]), cm_ref[nme][i]) < chain, (nme, i)
+            assert param_update_err(host(gpar[nme][i]), cp_ref[nme][i], cp[nme][i]) < chain, (nme, i)
             assert not np.array_equal(host(gpar[nme][i]), cp[nme][i])
 
 

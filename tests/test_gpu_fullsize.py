@@ -1,12 +1,16 @@
 """GPU parity at the full sizes of the benchmark's configurations, in the launch configuration the bench
-times: each layer is run whole on the GPU and compared with the CPU checker on sampled outputs that the
-checker computes one by one (plus corners and edges, where padding and ragged tiles live)."""
+times: each layer is run whole on the GPU and compared with the CPU checker on outputs that the checker
+computes one by one: at least one in every 64 x 64 block of the output seen as the GEMM's matrix (every tile
+shape of the kernels is a multiple of that, so every workgroup of the first round, of the last full round and of the
+sliced tail is sampled), the corners, and the first and last image whole."""
+import copy
+
 import numpy as np
 import pytest
 import torch
 
 import workloads as wl_mod
-from gpu_util import TOL_F32, dev, host
+from gpu_util import TOL_F32, dev, host, note, param_update_err, rel_err
 from oracle import ConvGeom
 
 pytestmark = pytest.mark.gpu
@@ -38,10 +42,23 @@ def _sample_idx(shape, seed, n=NSAMP):
     return idx
 
 
+def _block_idx(shape, ncols, seed, block=64):
+    """One index in every block x block tile of the tensor seen as a [numel / ncols, ncols] matrix (rows x columns of
+    the GEMM that produces it), as tuples into `shape`."""
+    numel = int(np.prod(shape))
+    rows = numel // ncols
+    r = np.random.default_rng(seed)
+    rb, cb = (rows + block - 1) // block, (ncols + block - 1) // block
+    r0 = (np.arange(rb) * block)[:, None] + np.zeros((1, cb), np.int64)
+    c0 = np.zeros((rb, 1), np.int64) + (np.arange(cb) * block)[None, :]
+    rr = r0 + r.integers(0, np.minimum(block, rows - r0))
+    cc = c0 + r.integers(0, np.minimum(block, ncols - c0))
+    flat = (rr * ncols + cc).ravel()
+    return [tuple(int(v) for v in np.unravel_index(f, shape)) for f in flat]
+
+
 def _check(got, want, scale_ref, what):
-    got, want = np.asarray(got, np.float64), np.asarray(want, np.float64)
-    floor = 0.05 * scale_ref
-    e = float((np.abs(got - want) / np.maximum(np.abs(want), floor)).max())
+    e = note(got, want, scale_ref)
     assert e < TOL_F32, (what, e)
 
 
@@ -60,10 +77,15 @@ FULL_CASES = [
 ]
 
 
+def _whole_image(N):
+    return sorted({0, N - 1})
+
+
 @pytest.mark.parametrize("name,case", FULL_CASES, ids=[c[0] for c in FULL_CASES])
 def test_conv_layer_full_size(api, o32, name, case):
     N, H, W, C, K, R, S, st, pad = case
     g = ConvGeom(N, H, W, C, K, R, S, st, pad)
+    g1 = ConvGeom(1, H, W, C, K, R, S, st, pad)
     x = _draw((N, H, W, C), 1)
     w = _draw((K, R, S, C), 2, (2.0 / (R * S * C)) ** 0.5)
     b = _draw((K,), 3, 0.1)
@@ -76,9 +98,12 @@ def test_conv_layer_full_size(api, o32, name, case):
     y = torch.empty((N, g.Ho, g.Wo, K), device="cuda:0")
     api.stanza_conv_fwd(d, xd, wd, bd, y, ws01)
     yh = host(y)
-    idx = _sample_idx(yh.shape, 10)
+    idx = _sample_idx(yh.shape, 10) + _block_idx(yh.shape, K, 110)
     want = [o32.conv_fwd_at(g, x, w, b, True, *i) for i in idx]
-    _check([yh[i] for i in idx], want, float(np.abs(yh).max()), name + " fwd")
+    scale = float(np.abs(yh).max())
+    _check([yh[i] for i in idx], want, scale, name + " fwd")
+    for n in _whole_image(N):        # first and last image whole
+        _check(yh[n], o32.conv_fwd(g1, np.ascontiguousarray(x[n:n + 1]), w, b, relu=True)[0], scale, name + " fwd image %d" % n)
     assert (yh >= 0).all()
     del y
     # backward-data (plain; the gating variants are covered at small sizes)
@@ -87,9 +112,12 @@ def test_conv_layer_full_size(api, o32, name, case):
         dx = torch.empty((N, H, W, C), device="cuda:0")
         api.stanza_conv_bwd_data(d0, dyd, None, wd, None, dx, ws01)
         dxh = host(dx)
-        idx = _sample_idx(dxh.shape, 11)
+        idx = _sample_idx(dxh.shape, 11) + _block_idx(dxh.shape, C, 111)
         want = [o32.conv_bwd_data_at(g, dy, w, *i) for i in idx]
-        _check([dxh[i] for i in idx], want, float(np.abs(dxh).max()), name + " bwd_data")
+        scale = float(np.abs(dxh).max())
+        _check([dxh[i] for i in idx], want, scale, name + " bwd_data")
+        for n in _whole_image(N):
+            _check(dxh[n], o32.conv_bwd_data(g1, np.ascontiguousarray(dy[n:n + 1]), w)[0], scale, name + " bwd_data image %d" % n)
         del dx, dxh
     # backward-weight + bias gradient (ungated dy)
     db_desc = api.conv_desc(N, H, W, C, K, R, S, st, pad, api.F32, api.CONV_BIAS)
@@ -98,73 +126,83 @@ def test_conv_layer_full_size(api, o32, name, case):
     db = torch.empty((K,), device="cuda:0")
     api.stanza_conv_bwd_weight(db_desc, xd, dyd, None, dw, db, ws)
     dwh, dbh = host(dw), host(db)
-    idx = _sample_idx(dwh.shape, 12, 24)
+    idx = _sample_idx(dwh.shape, 12, 24) + _block_idx(dwh.shape, R * S * C, 112)
     want = [o32.conv_bwd_weight_at(g, x, dy, *i) for i in idx]
     _check([dwh[i] for i in idx], want, float(np.abs(dwh).max()), name + " bwd_weight")
-    cols = [0, K - 1, K // 2]
-    _check([dbh[j] for j in cols], [o32.colsum_at(dy.reshape(-1, K), j) for j in cols], float(np.abs(dbh).max()), name + " dbias")
+    dy2 = dy.reshape(-1, K)
+    _check(dbh, [o32.colsum_at(dy2, j) for j in range(K)], float(np.abs(dbh).max()), name + " dbias")
 
 
-def test_fc_layers_full_size(api, o32):
-    """The VGG-16-shaped FC worker's first layer (512 x 25088 -> 4096) through the engine the FC step uses,
-    and a whole FC step at the ResNet-50-shaped size (1024 x 2048 -> 1000), sampled."""
-    import copy
+def _fc_step_against_checker(api, o32, dims, n, seed, lr=0.01, momentum=0.9, wd=5e-4):
+    """One whole stanza_fc_step against the checker's fc_step, element by element: loss, predicted classes (bit-exact),
+    the gradient handed back to the CONV workers, every momentum buffer and every parameter."""
+    import fc_cases
     from oracle import network as onet
     from paper_1812_10624_amd.netrun import FcWorker
-    n, A, O = 512, 25088, 4096
-    feats = np.maximum(_draw((n, A), 5), 0)
-    w = _draw((O, A), 6, (2.0 / A) ** 0.5)
-    b = _draw((O,), 7, 0.01)
-    d = api.conv_desc(n, 1, 1, A, O, 1, 1, 1, 0, api.F32, api.CONV_BIAS | api.CONV_RELU)
-    z = torch.empty((n, O), device="cuda:0")
-    api.stanza_conv_fwd(d, dev(feats), dev(w), dev(b), z)
-    zh = host(z)
-    idx = _sample_idx(zh.shape, 13)
-    _check([zh[i] for i in idx], [o32.fc_fwd_at(feats, w, b, i, o, relu=True) for i, o in idx], float(np.abs(zh).max()), "fc1 fwd")
-    # whole step, ResNet-50-shaped FC worker
-    dims, n2 = [2048, 1000], 1024
-    f2 = np.maximum(_draw((n2, dims[0]), 8), 0)
-    lab = wl_mod.rng_for(9, "lab").integers(0, dims[1], n2).astype(np.int32)
-    p = [(_draw((dims[1], dims[0]), 9, (2.0 / dims[0]) ** 0.5), _draw((dims[1],), 10, 0.01))]
-    m = [(np.zeros_like(p[0][0]), np.zeros_like(p[0][1]))]
-    p_ref, m_ref = copy.deepcopy(p), copy.deepcopy(m)
-    ref = onet.fc_step(o32, f2, lab, p_ref, m_ref, 0.01, 0.9, 0.0)
-    gp, gm = [(dev(p[0][0]), dev(p[0][1]))], [(dev(m[0][0]), dev(m[0][1]))]
-    fw = FcWorker(dims, n2, gp, gm, 0.01, 0.9, 0.0)
-    fw.step(dev(f2), dev(lab))
-    assert abs(float(host(fw.loss)[0]) - ref["loss"]) < 1e-5 * abs(ref["loss"])
+    feats, labels, params, mom, _ = fc_cases.fc_case(dims, n, seed)
+    p_ref, m_ref = copy.deepcopy(params), copy.deepcopy(mom)
+    ref = onet.fc_step(o32, feats, labels, p_ref, m_ref, lr, momentum, wd)
+    for li, (dw, _) in enumerate(ref["grads"]):      # momentum buffers and gradients of like size: neither hides the other
+        assert 0.1 < float(mom[li][0].std()) / float(dw.std()) < 10.0, li
+    gp = [(dev(w), dev(b)) for w, b in params]
+    gm = [(dev(w), dev(b)) for w, b in mom]
+    fw = FcWorker(dims, n, gp, gm, lr, momentum, wd)
+    fw.step(dev(feats), dev(labels))
+    assert abs(float(host(fw.loss)[0]) - ref["loss"]) < 1e-5 * max(1.0, abs(ref["loss"]))
     np.testing.assert_array_equal(host(fw.pred), ref["pred"])
-    from gpu_util import rel_err
     assert rel_err(host(fw.dfeats), ref["dfeats"]) < TOL_F32
-    assert rel_err(host(gm[0][0]), m_ref[0][0]) < TOL_F32
-    assert rel_err(host(gm[0][1]), m_ref[0][1]) < TOL_F32
-    assert rel_err(host(gp[0][0]), p_ref[0][0]) < 1e-5
+    for li in range(len(params)):
+        for which in range(2):
+            e_v = rel_err(host(gm[li][which]), m_ref[li][which])
+            assert e_v < TOL_F32, ("momentum", li, which, e_v)
+            e_p = param_update_err(host(gp[li][which]), p_ref[li][which], params[li][which])
+            assert e_p < TOL_F32, ("parameter", li, which, e_p)
+            assert not np.array_equal(p_ref[li][which], params[li][which])
+
+
+def test_fc_step_vgg16_full_size(api, o32):
+    """The FC worker of the VGG-16-shaped configuration at the size the bench times: 512 rows (8 CONV workers x 64),
+    25088 -> 4096 -> 4096 -> 1000, non-zero momentum buffers and weight decay."""
+    _fc_step_against_checker(api, o32, [25088, 4096, 4096, 1000], 512, seed=33)
+
+
+def test_fc_step_alexnet_full_size(api, o32):
+    """The FC worker of the AlexNet-shaped configuration: 512 rows (4 CONV workers x 128), 9216 -> 4096 -> 4096 -> 1000."""
+    _fc_step_against_checker(api, o32, [9216, 4096, 4096, 1000], 512, seed=31)
+
+
+def test_fc_step_resnet50_full_size(api, o32):
+    """The FC worker of the ResNet-50-shaped configuration: 1024 rows (16 CONV workers x 64), 2048 -> 1000."""
+    _fc_step_against_checker(api, o32, [2048, 1000], 1024, seed=35)
 
 
 @pytest.mark.parametrize("which", ["conv", "fc"])
 def test_ps_aggregate_full_size(api, o32, which):
-    """Config 5: K = 16 shards over the VGG-16-shaped conv set (26 tensors, 14.7 M parameters), whole-tensor
-    comparison; for the 123.6 M-parameter FC set the two largest tensors are cut to their first 4 M elements
-    on the checker side (the GPU still runs the full set)."""
-    from gpu_util import rel_err
+    """Config 5: K = 16 shards over the VGG-16-shaped conv set (26 tensors, 14.7 M parameters) and over the FC set
+    (6 tensors, 123.6 M parameters), one launch per set as the bench runs it, every tensor compared whole.  The host holds
+    one tensor's shards at a time: they are drawn, uploaded and dropped, and drawn again for the checker."""
     wl = wl_mod.get_workload("vgg16")
     numels, fans = wl_mod.param_tensor_numels(wl, which)
-    K = 16
-    if which == "fc":
-        K = 4      # host memory: 123.6 M x K shards
-    ws_, vs_, gs_ = wl_mod.gen_ps_case(numels, K, seed=21, fan_ins=fans)
-    gw, gv = [dev(a) for a in ws_], [dev(a) for a in vs_]
-    gg = [[dev(gs_[t][k]) for t in range(len(numels))] for k in range(K)]
+    K, seed = 16, 21
+    gw, gv, gg = [], [], [[] for _ in range(K)]
+    for t, ne in enumerate(numels):
+        w0, v0, shards = wl_mod.gen_ps_tensor(t, ne, K, seed, fans[t])
+        gw.append(dev(w0))
+        gv.append(dev(v0))
+        for k in range(K):
+            gg[k].append(dev(shards[k]))
+        del w0, v0, shards
     ws = torch.empty(api.stanza_ps_workspace_bytes(len(numels), K), dtype=torch.uint8, device="cuda:0")
     api.stanza_ps_aggregate(gw, gv, gg, 1.0, 0.01, 0.9, 5e-4, ws)
+    torch.cuda.synchronize()
     for t, ne in enumerate(numels):
-        cut = min(ne, 4 << 20)
-        w_ref, v_ref = ws_[t][:cut].copy(), vs_[t][:cut].copy()
-        o32.ps_aggregate(w_ref, v_ref, [np.ascontiguousarray(gs_[t][k][:cut]) for k in range(K)], 1.0, 0.01, 0.9, 5e-4)
-        assert rel_err(host(gv[t])[:cut], v_ref) < 1e-5, t
-        assert rel_err(host(gw[t])[:cut], w_ref) < 1e-6, t
-        tail_w = host(gw[t])[-8:]
-        assert np.isfinite(tail_w).all() and not np.array_equal(tail_w, ws_[t][-8:])
+        w_ref, v_ref, shards = wl_mod.gen_ps_tensor(t, ne, K, seed, fans[t])
+        w0 = w_ref.copy()
+        o32.ps_aggregate(w_ref, v_ref, shards, 1.0, 0.01, 0.9, 5e-4)
+        del shards
+        assert rel_err(host(gv[t]), v_ref) < 1e-5, t
+        assert param_update_err(host(gw[t]), w_ref, w0) < TOL_F32, t
+        assert rel_err(host(gw[t]), w_ref) < 1e-6, t
 
 
 def test_conv_input_of_two_gibibytes(api, o32):

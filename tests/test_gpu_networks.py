@@ -6,7 +6,7 @@ import pytest
 import torch
 
 import workloads as wl_mod
-from gpu_util import dev, host, rel_err
+from gpu_util import dev, host, note, rel_err
 from oracle import network as onet
 
 pytestmark = pytest.mark.gpu
@@ -44,6 +44,7 @@ def test_conv_stack_real_shapes(api, o32, name, B):
             cos = float(a @ b / (np.linalg.norm(a) * np.linalg.norm(b) + 1e-300))
             assert cos > 0.9999, (name, n, which, cos)
             assert abs(np.linalg.norm(a) / np.linalg.norm(b) - 1) < 1e-2, (name, n, which)
+            note(a, b, tag="#chain")         # element-wise E of the whole chain: reported, not gated (see above)
     # ... and every conv layer's backward is held to the 1e-4 bound on the checker's own inputs for that layer.
     from oracle import ConvGeom
     worst = 0.0
@@ -131,3 +132,40 @@ def test_step_graph_replays_equal_eager_steps(api, name, half):
         assert torch.equal(t, e)
     assert float(fcw.loss.cpu()[0]) == eager_loss
     assert not torch.equal(state[0], saved[0])
+
+
+@pytest.mark.parametrize("K,numels", [(16, [4096 * 3, 1000, 64 * 27, 64, 4097, 8]), (3, [300] * 70)], ids=["k16", "k3_70tensors"])
+def test_plain_aggregation_call_inside_a_graph_capture(api, o32, K, numels):
+    """stanza_ps_aggregate itself (pointer table written by its own fill launches, then the aggregation launch) recorded in
+    a stream capture: nothing in it allocates, copies through the runtime or waits.  Three replays with eager work and
+    synchronisations between them; every replay is compared with the checker's step from the same state.  The second
+    case's table (70 tensors: 491 words) needs two fill launches."""
+    import copy
+    from gpu_util import host, param_update_err, rel_err
+    ws_, vs_, gs_ = wl_mod.gen_ps_case(numels, K, seed=77)
+    gw, gv = [dev(a) for a in ws_], [dev(a) for a in vs_]
+    gg = [[dev(gs_[t][k]) for t in range(len(numels))] for k in range(K)]
+    ws = torch.empty(api.stanza_ps_workspace_bytes(len(numels), K), dtype=torch.uint8, device="cuda:0")
+    ws.fill_(0xAB)                       # the capture must bring its own table
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        api.stanza_ps_aggregate(gw, gv, gg, 1.0, 0.01, 0.9, 5e-4, ws)
+    torch.cuda.synchronize()
+    # capture launches nothing: the state is still the initial one
+    for t in range(len(numels)):
+        np.testing.assert_array_equal(host(gw[t]), ws_[t])
+    w_ref, v_ref = copy.deepcopy(ws_), copy.deepcopy(vs_)
+    for rep in range(3):
+        before = [w.copy() for w in w_ref]
+        ws.fill_(0)                      # eager work between replays, on the table itself
+        scratch = torch.randn(1 << 16, device="cuda:0").sum()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.isfinite(scratch)
+        for t in range(len(numels)):
+            o32.ps_aggregate(w_ref[t], v_ref[t], gs_[t], 1.0, 0.01, 0.9, 5e-4)
+            assert rel_err(host(gv[t]), v_ref[t]) < 1e-5, (rep, t)
+            assert param_update_err(host(gw[t]), w_ref[t], before[t]) < 1e-4, (rep, t)
+            assert rel_err(host(gw[t]), w_ref[t]) < 1e-6, (rep, t)

@@ -38,7 +38,7 @@ import numpy as np
 __all__ = [
     "Workload", "get_workload", "WORKLOAD_NAMES", "shape_pass", "conv_param_shapes",
     "fc_param_shapes", "gen_images", "gen_labels", "gen_conv_params", "gen_fc_params",
-    "gen_ps_case", "rng_for", "conv_flops", "fc_flops", "count_params", "bn_param_shapes", "flat_tensors",
+    "gen_ps_case", "gen_ps_tensor", "rng_for", "conv_flops", "fc_flops", "count_params", "bn_param_shapes", "flat_tensors",
 ]
 
 
@@ -481,21 +481,28 @@ def gen_fc_params(wl: Workload, seed: int):
     return out
 
 
+def gen_ps_tensor(ti: int, ne: int, K: int, seed: int, fan_in: int = 64, shards: bool = True):
+    """Aggregation inputs of ONE tensor (index ti of its set): w (normal, variance 2/fan_in), momentum v ~ N(0, 1e-3^2)
+    and (shards=True) the K gradient shards ~ N(0, 1e-3^2).  Every array has its own stream, so a set can be drawn
+    tensor by tensor, in any order, and a tensor's shards drawn again later without holding the whole set."""
+    w = _kaiming(rng_for(seed, "psw", ti), (ne,), fan_in)
+    v = rng_for(seed, "psv", ti).standard_normal(ne, dtype=np.float32)
+    v *= np.float32(1e-3)
+    shard = []
+    for k in range(K if shards else 0):
+        g = rng_for(seed, "psg", ti, k).standard_normal(ne, dtype=np.float32)
+        g *= np.float32(1e-3)
+        shard.append(g)
+    return w, v, shard
+
+
 def gen_ps_case(numels: List[int], K: int, seed: int, fan_ins: List[int] | None = None):
-    """Parameter-server aggregation inputs: per tensor w (normal, variance 2/fan_in),
-    momentum v ~ N(0, 1e-3^2), and K gradient shards ~ N(0, 1e-3^2)."""
+    """Parameter-server aggregation inputs of a whole set: lists over tensors of w, v and the K shards (gen_ps_tensor)."""
     ws, vs, gs = [], [], []
     for ti, ne in enumerate(numels):
-        fan = fan_ins[ti] if fan_ins is not None else 64
-        ws.append(_kaiming(rng_for(seed, "psw", ti), (ne,), fan))
-        v = rng_for(seed, "psv", ti).standard_normal(ne, dtype=np.float32)
-        v *= np.float32(1e-3)
+        w, v, shard = gen_ps_tensor(ti, ne, K, seed, fan_ins[ti] if fan_ins is not None else 64)
+        ws.append(w)
         vs.append(v)
-        shard = []
-        for k in range(K):
-            g = rng_for(seed, "psg", ti, k).standard_normal(ne, dtype=np.float32)
-            g *= np.float32(1e-3)
-            shard.append(g)
         gs.append(shard)
     return ws, vs, gs
 
