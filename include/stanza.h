@@ -55,7 +55,8 @@ typedef enum {
     STANZA_EALIGN = -3,       /* a pointer is not 16-byte aligned */
     STANZA_EUNSUPPORTED = -4, /* dtype / shape combination this build has no kernel for */
     STANZA_EWORKSPACE = -5,   /* ws_bytes is smaller than the matching *_workspace_bytes() */
-    STANZA_EHIP = -6          /* the HIP runtime reported an error at launch */
+    STANZA_EHIP = -6,         /* the HIP runtime reported an error at launch */
+    STANZA_ECAPACITY = -7     /* the input is larger than the fixed capacity of an entry point that allocates nothing */
 } stanza_status;
 
 typedef enum { STANZA_F32 = 0, STANZA_BF16 = 1 } stanza_dtype;
@@ -311,6 +312,20 @@ int stanza_ps_aggregate_ordered_planned(int32_t order, int32_t n_tensors, const 
 int stanza_ps_aggregate_ordered(int32_t order, int32_t n_tensors, const int64_t *host_numel, float *const *host_w,
                                 float *const *host_v, const float *const *host_grads, int32_t K, float scale, float lr,
                                 float momentum, float weight_decay, void *ws, size_t ws_bytes, void *stream);
+
+/* ---- The same aggregation for callers that cannot allocate: code recorded under HIP graph capture, tight serving or training
+ * loops, and harnesses that forbid hipMalloc, which therefore have no workspace to pass.  Arguments and arithmetic are those of
+ * stanza_ps_aggregate_ordered without ws / ws_bytes; the pointer table goes to a fixed array inside the library's device image
+ * (256 KiB on every GPU the library runs on, held until the process ends) instead of a caller-owned workspace.
+ *   - Capacity: n_tensors * (K + 4) + 1 <= 32768 table words (e.g. 1638 tensors at K = 16); beyond that STANZA_ECAPACITY and
+ *     nothing is launched.  Other errors as for stanza_ps_aggregate_ordered.
+ *   - The call allocates nothing on host or device and only enqueues launches on `stream`.  The first call on a device
+ *     looks up that device's address of the array (no stream work; make it before a stream capture begins).
+ *   - Every call on a GPU shares that GPU's array and rewrites the table whole, so nothing needs clearing between calls,
+ *     but two calls that overlap on one GPU (different streams, or different threads) race on it: serialise them. */
+int stanza_ps_aggregate_static(int32_t order, int32_t n_tensors, const int64_t *host_numel, float *const *host_w,
+                               float *const *host_v, const float *const *host_grads, int32_t K, float scale, float lr,
+                               float momentum, float weight_decay, void *stream);
 
 /* ---- Performance model and node assignment (host arithmetic only; Sec. 4.2 and Sec. 7.1).  Times in seconds,
  * bandwidth in bit/s per node, every transferred value is 32 bits wide.

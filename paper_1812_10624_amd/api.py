@@ -26,7 +26,7 @@ EXPORTS = (
     "stanza_cast_workspace_bytes", "stanza_cast_plan", "stanza_cast_f32_to_bf16_planned",
     "stanza_bn_workspace_bytes", "stanza_bn_fwd", "stanza_bn_fwd_res", "stanza_bn_bwd", "stanza_avgpool_fwd", "stanza_avgpool_bwd", "stanza_copy2d",
     "stanza_fc_workspace_bytes", "stanza_fc_step", "stanza_fc_grads", "stanza_dropout", "stanza_ps_workspace_bytes", "stanza_ps_plan",
-    "stanza_ps_aggregate_planned", "stanza_ps_aggregate", "stanza_ps_aggregate_ordered_planned", "stanza_ps_aggregate_ordered",
+    "stanza_ps_aggregate_planned", "stanza_ps_aggregate", "stanza_ps_aggregate_ordered_planned", "stanza_ps_aggregate_ordered", "stanza_ps_aggregate_static",
     "stanza_model_allreduce_rounds", "stanza_model_stanza_time", "stanza_model_stanza_throughput", "stanza_model_assign",
     "stanza_model_ps_time", "stanza_model_ps_throughput",
 )
@@ -109,6 +109,7 @@ def load() -> C.CDLL:
     lib.stanza_ps_aggregate.argtypes = [i32, vp, vp, vp, vp, i32, f32, f32, f32, f32, vp, sz, vp]
     lib.stanza_ps_aggregate_ordered_planned.argtypes = [i32, i32, vp, i32, f32, f32, f32, f32, vp, sz, vp]
     lib.stanza_ps_aggregate_ordered.argtypes = [i32, i32, vp, vp, vp, vp, i32, f32, f32, f32, f32, vp, sz, vp]
+    lib.stanza_ps_aggregate_static.argtypes = [i32, i32, vp, vp, vp, vp, i32, f32, f32, f32, f32, vp]
     f64 = C.c_double
     lib.stanza_model_allreduce_rounds.restype = i32
     lib.stanza_model_allreduce_rounds.argtypes = [i32]
@@ -380,6 +381,13 @@ def stanza_ps_aggregate_ordered(order, w, v, grads, scale, lr, momentum, weight_
     p, n = _ws(ws)
     _check(load().stanza_ps_aggregate_ordered(order, nt, numel, pw, pv, pg, K, scale, lr, momentum, weight_decay, p, n, _stream()),
            "stanza_ps_aggregate_ordered")
+
+
+def stanza_ps_aggregate_static(order, w, v, grads, scale, lr, momentum, weight_decay):
+    """The aggregation without a workspace: the pointer table lives in a fixed array of the library's device image."""
+    nt, K, numel, pw, pv, pg = _ps_args(w, v, grads)
+    _check(load().stanza_ps_aggregate_static(order, nt, numel, pw, pv, pg, K, scale, lr, momentum, weight_decay, _stream()),
+           "stanza_ps_aggregate_static")
 
 
 # ---- performance model (host arithmetic)

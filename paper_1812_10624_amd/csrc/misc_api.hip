@@ -4,6 +4,8 @@
 // their gradients and update their replicas of the conv parameters; Sec. 2.2: server-side aggregation).  Every kernel moves each byte once with 16-byte accesses along the contiguous axis.
 #include "internal.h"
 
+#include <mutex>
+
 namespace stanza {
 
 __device__ __forceinline__ uint16_t f32_to_bf16_rne(float f)
@@ -751,6 +753,7 @@ extern "C" const char *stanza_strerror(int status)
     case STANZA_EUNSUPPORTED: return "unsupported dtype or shape";
     case STANZA_EWORKSPACE: return "workspace too small";
     case STANZA_EHIP: return "HIP runtime error at launch";
+    case STANZA_ECAPACITY: return "input exceeds the fixed capacity of an entry point that allocates nothing";
     }
     return "unknown status";
 }
@@ -1080,4 +1083,49 @@ extern "C" int stanza_ps_aggregate(int32_t n_tensors, const int64_t *host_numel,
 {
     return stanza_ps_aggregate_ordered(STANZA_SUM_INDEX_ORDER, n_tensors, host_numel, host_w, host_v, host_grads, K, scale, lr, momentum,
                                        weight_decay, ws, ws_bytes, stream);
+}
+
+// ------------------------------------------------------------------ aggregation without a workspace
+// For callers that cannot allocate device memory and so have no workspace to hand over: the pointer table lives in a fixed array
+// of this library's device image.  Each GPU holds its own copy of the array at its own address; host code never uses the
+// array's name as an address, only the pointer that hipGetSymbolAddress returned for the current device.
+constexpr int PS_STATIC_WORDS = 32768;          // 256 KiB per GPU, held until the process ends
+static __device__ __align__(256) unsigned long long scratch[PS_STATIC_WORDS];
+
+constexpr int PS_STATIC_MAX_DEVICES = 64;
+static std::mutex g_scratch_mutex;
+static void *g_scratch_ptr[PS_STATIC_MAX_DEVICES];   // per device: device address of `scratch`, resolved on first use
+
+static int ps_static_table(void **table)
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess) return STANZA_EHIP;
+    if (dev < 0 || dev >= PS_STATIC_MAX_DEVICES) return STANZA_EUNSUPPORTED;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void *ptr = nullptr;
+        const hipError_t e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !ptr) return STANZA_EHIP;
+        g_scratch_ptr[dev] = ptr;
+    }
+    *table = g_scratch_ptr[dev];
+    return STANZA_OK;
+}
+
+extern "C" int stanza_ps_aggregate_static(int32_t order, int32_t n_tensors, const int64_t *host_numel, float *const *host_w,
+                                          float *const *host_v, const float *const *host_grads, int32_t K, float scale, float lr,
+                                          float momentum, float weight_decay, void *stream)
+{
+    if (order != STANZA_SUM_INDEX_ORDER && order != STANZA_SUM_RECURSIVE_DOUBLING) return STANZA_EINVAL;
+    if (n_tensors <= 0 || K <= 0 || K > 4096) return STANZA_EINVAL;
+    if ((int64_t)n_tensors * ((int64_t)K + 4) + 1 > PS_STATIC_WORDS) return STANZA_ECAPACITY;
+    void *table = nullptr;
+    int rc = ps_static_table(&table);
+    if (rc) return rc;
+    const size_t bytes = (size_t)PS_STATIC_WORDS * sizeof(unsigned long long);
+    // Validation and the table launches are those of the workspace form; the table is rewritten whole by every call, so
+    // nothing of the previous call's contents is read.
+    rc = stanza_ps_plan(n_tensors, host_numel, host_w, host_v, host_grads, K, table, bytes, stream);
+    if (rc) return rc;
+    return stanza_ps_aggregate_ordered_planned(order, n_tensors, host_numel, K, scale, lr, momentum, weight_decay, table, bytes, stream);
 }

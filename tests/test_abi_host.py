@@ -34,7 +34,7 @@ def test_status_strings_and_version(api):
     lib = api.load()
     assert lib.stanza_version() >= 100
     assert lib.stanza_strerror(0) == b"ok"
-    for code in range(-6, 0):
+    for code in range(-7, 0):
         assert lib.stanza_strerror(code) not in (b"ok", b"unknown status")
     assert lib.stanza_strerror(-99) == b"unknown status"
 
@@ -125,6 +125,11 @@ def test_fc_and_ps_errors(api):
     assert lib.stanza_ps_aggregate_ordered_planned(7, 2, numel, 3, 1.0, 0.1, 0.9, 0.0, p16, need, None) == -1   # unknown order
     assert lib.stanza_ps_aggregate_ordered_planned(1, 2, numel, 3, 1.0, 0.1, 0.9, 0.0, None, need, None) == -2
     assert lib.stanza_ps_aggregate_ordered(9, 2, numel, w, w, g, 3, 1.0, 0.1, 0.9, 0.0, p16, need, None) == -1
+    # the form without a workspace: its fixed table holds 32768 words; beyond that it refuses before touching the device
+    assert lib.stanza_ps_aggregate_static(9, 2, numel, w, w, g, 3, 1.0, 0.1, 0.9, 0.0, None) == -1
+    assert lib.stanza_ps_aggregate_static(0, 0, numel, w, w, g, 3, 1.0, 0.1, 0.9, 0.0, None) == -1
+    assert lib.stanza_ps_aggregate_static(0, 1639, numel, w, w, g, 16, 1.0, 0.1, 0.9, 0.0, None) == -7
+    assert lib.stanza_ps_aggregate_static(0, 8, numel, w, w, g, 4093, 1.0, 0.1, 0.9, 0.0, None) == -7
 
 
 def test_cast_plan_errors(api):
