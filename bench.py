@@ -227,7 +227,8 @@ def main():
             "handed_over_features_nonzero_fraction": float((feats[:B] != 0).float().mean().item()),
             "fc_gradient_handed_back_abs_max": float(fcw.dfeats[:B].abs().max().item())}
     assert all(math.isfinite(v) for v in live.values()), live
-    assert live["loss_after_first_timed_step"] != live["loss_after_last_timed_step"] and live["handed_over_features_nonzero_fraction"] > 0.01, live
+    assert (args.steps < 2 or live["loss_after_first_timed_step"] != live["loss_after_last_timed_step"]) \
+        and live["handed_over_features_nonzero_fraction"] > 0.01, live
     # ---- the same K steps again, eager, with an event pair around every entry-point call: per-call times, roofline
     netrun.api = tap
     plan = getattr(worker, "cast_plan", None)          # the one-launch cast of all bf16 filter copies is a method of its plan object

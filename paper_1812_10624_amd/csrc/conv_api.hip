@@ -448,9 +448,77 @@ int launch_colsum(const float *a, const float *mask, int rows, int cols, float *
     return launch_status();
 }
 
+// The nine-tap kernel takes float32 3x3 / stride 1 / pad 1 layers whose channel counts fill most of a 64 x 64 tile.
+// Strip width SW <= 28 output pixels; a stage is RP rows of XW = SW + 2 (even) pixel slots, RP > 1 only when one strip
+// spans the image; limits: RP * XW <= 32 slots per stage, (2 RP + 4) * XW <= 186 slots in the ring of x rows.
+bool plan_wgrad_taps(const ConvGeo &g, TapsParams *tp)
+{
+    if (g.R != 3 || g.S != 3 || g.sh != 1 || g.sw != 1 || g.ph != 1 || g.pw != 1) return false;
+    if (g.C % 4 || g.K % 4 || g.C < 48 || g.K < 48) return false;
+    const int64_t lim = int64_t(1) << 31;
+    if ((int64_t)g.N * g.H * g.W * g.C * 4 >= lim || (int64_t)g.N * g.H * g.W * g.K * 4 >= lim) return false;
+    TapsParams t{};
+    t.N = g.N; t.H = g.H; t.W = g.W; t.C = g.C; t.K = g.K;
+    t.strips = cdiv(g.W, 28);
+    t.SW = cdiv(g.W, t.strips);
+    t.XW = (t.SW + 2 + 1) & ~1;
+    t.RP = 1;
+    if (t.strips == 1) {
+        t.RP = max(1, min(TAPS_J / t.XW, g.H));
+        while (t.RP > 1 && (2 * t.RP + 4) * t.XW > TAPS_XSLOTS) --t.RP;
+    }
+    if (t.RP * t.XW > TAPS_J || (2 * t.RP + 4) * t.XW > TAPS_XSLOTS) return false;
+    t.NR = 2 * t.RP + 4;
+    t.KS = t.RP * t.XW / 2 - 1;
+    t.rowblocks = cdiv(g.H, t.RP);
+    t.total_stages = g.N * t.strips * t.rowblocks;
+    t.tiles_c = cdiv(g.C, TAPS_T);
+    t.tiles = cdiv(g.K, TAPS_T) * t.tiles_c;
+    // one round of resident workgroups (two per CU: 144 accumulator registers per lane), slices of at least 4 stages
+    int slices = max(1, 2 * CUS / t.tiles);
+    slices = max(1, min(slices, t.total_stages / 4));
+    t.stages_per_item = cdiv(t.total_stages, slices);
+    t.slices = cdiv(t.total_stages, t.stages_per_item);
+    t.fd_xw = make_fastdiv(t.XW);
+    t.fd_rowblocks = make_fastdiv(t.rowblocks);
+    t.fd_strips = make_fastdiv(t.strips);
+    t.fd_tiles = make_fastdiv(t.tiles);
+    t.fd_tiles_c = make_fastdiv(t.tiles_c);
+    t.dy_bytes = (uint32_t)((int64_t)g.N * g.H * g.W * g.K * 4);
+    t.x_bytes = (uint32_t)((int64_t)g.N * g.H * g.W * g.C * 4);
+    *tp = t;
+    return true;
+}
+
+// The stage geometries of the 224- to 28-pixel-wide, the 14- and the 7-pixel-wide layers have kernels of their own with
+// the geometry compiled in; anything else runs the kernel that reads it from the parameters.
+template <bool GATED>
+static void launch_wgrad_taps_g(const TapsParams &tp, dim3 grid, hipStream_t st)
+{
+    if (tp.XW == 30 && tp.RP == 1) hipLaunchKernelGGL((wgrad_taps_kernel<GATED, 30, 1>), grid, dim3(256), 0, st, tp);
+    else if (tp.XW == 16 && tp.RP == 2) hipLaunchKernelGGL((wgrad_taps_kernel<GATED, 16, 2>), grid, dim3(256), 0, st, tp);
+    else if (tp.XW == 10 && tp.RP == 3) hipLaunchKernelGGL((wgrad_taps_kernel<GATED, 10, 3>), grid, dim3(256), 0, st, tp);
+    else hipLaunchKernelGGL((wgrad_taps_kernel<GATED, 0, 0>), grid, dim3(256), 0, st, tp);
+}
+static void launch_wgrad_taps(const TapsParams &tp, dim3 grid, hipStream_t st)
+{
+    if (tp.amask) launch_wgrad_taps_g<true>(tp, grid, st);
+    else launch_wgrad_taps_g<false>(tp, grid, st);
+}
+
 WgradPlan plan_wgrad(const ConvGeo &g, bool want_bias, int bk)
 {
     WgradPlan pl{};
+    TapsParams tp;
+    if (bk == BK && plan_wgrad_taps(g, &tp)) {
+        pl.taps = true;
+        pl.splits = tp.slices;
+        pl.chunks_per_split = tp.stages_per_item;
+        pl.partial_floats = pl.splits > 1 ? (size_t)pl.splits * g.K * 9 * g.C : 0;
+        pl.db_floats = (want_bias && pl.splits > 1) ? (size_t)pl.splits * g.K : 0;
+        pl.bytes = round256(pl.partial_floats * 4) + round256(pl.db_floats * 4);
+        return pl;
+    }
     const int M = g.K, Nn = g.R * g.S * g.C;
     const int64_t red = (int64_t)g.N * g.Ho * g.Wo;
     const int chunks = (int)cdiv64(red, bk);
@@ -609,6 +677,21 @@ extern "C" int stanza_conv_bwd_weight(const stanza_conv_desc *desc, const void *
     hipStream_t st = (hipStream_t)stream;
     float *partial = (float *)ws;
     float *dbscratch = (float *)((char *)ws + round256(pl.partial_floats * 4));
+    if (pl.taps) {
+        TapsParams tp;
+        if (!plan_wgrad_taps(p.g, &tp)) return STANZA_EINVAL;
+        tp.dy = (const float *)dy;
+        tp.amask = (desc->flags & STANZA_CONV_RELU) ? (const float *)y : nullptr;
+        tp.x = (const float *)x;
+        tp.out = pl.splits > 1 ? partial : dw;
+        tp.dbias = want_bias ? (pl.splits > 1 ? dbscratch : dbias) : nullptr;
+        const dim3 grid((unsigned)(cdiv(tp.tiles * tp.slices, 8) * 8));
+        launch_wgrad_taps(tp, grid, st);
+        if ((rc = launch_status())) return rc;
+        if (pl.splits > 1)
+            rc = launch_split_reduce(partial, pl.splits, (size_t)p.g.K * 9 * p.g.C, dw, dbscratch, want_bias ? (size_t)p.g.K : 0, dbias, st);
+        return rc;
+    }
     p.a = (const float *)dy;
     p.amask = (desc->flags & STANZA_CONV_RELU) ? (const float *)y : nullptr;
     p.b = (const float *)x;

@@ -6,6 +6,7 @@
 
 #include "../../include/stanza.h"
 #include "igemm.h"
+#include "wgrad_taps.h"
 
 namespace stanza {
 
@@ -23,13 +24,16 @@ int conv_geometry(const stanza_conv_desc *d, ConvGeo *g);
 // How the filter-gradient reduction is cut into workgroups; the same plan sizes the workspace and drives
 // the launch, so the two can never disagree.
 struct WgradPlan {
-    int splits;            // reduction slices (blockIdx.y)
-    int chunks_per_split;  // BK-deep stages per slice
+    bool taps;             // float32 3x3 stride-1 pad-1 layers: the kernel that keeps all nine taps in one workgroup (wgrad_taps.h)
+    int splits;            // reduction slices (blockIdx.y); for taps: pixel slices
+    int chunks_per_split;  // BK-deep stages per slice; for taps: stages per slice
     size_t partial_floats; // splits * K * R*S*C when splits > 1, else 0
     size_t db_floats;      // splits * K bias-gradient partials when splits > 1 and a bias gradient is wanted
     size_t bytes;
 };
 WgradPlan plan_wgrad(const ConvGeo &g, bool want_bias, int bk);   // bk: reduction depth of one LDS stage
+// Stage geometry and work split of the nine-tap filter-gradient kernel; false when the layer is not one it handles.
+bool plan_wgrad_taps(const ConvGeo &g, TapsParams *tp);
 
 // Launch the implicit GEMM in `mode` over p (M, Nn, Kd, pointers and flags already set); picks the tile shape and fills
 // the tile counts.  bw_splits: reduction slices of every tile, MODE_BWD_WEIGHT only (1 otherwise).

@@ -121,6 +121,43 @@ def test_conv_backward_weight(api, o32, case):
         assert torch.equal(dw, dw2) and torch.equal(db, db2)
 
 
+# 3x3 / stride 1 / pad 1 layers with at least 48 channels on both sides take the nine-tap filter-gradient kernel: strips of
+# 28 pixels (56, 112), one strip per row (28, 17, 30), ragged strips (31 = 16 + 15, 33 = 17 + 16), several rows per stage
+# (14: 2 rows, 7: 3 rows with a last block of 1, 5: 4 rows + 1, 3, 1), channel counts that do not fill the 64-wide tiles
+# (52, 68, 100, 132), one image and many, slices that start in the middle of a column strip
+NINE_TAP_CASES = [
+    (2, 56, 56, 64, 64), (1, 28, 28, 128, 64), (3, 14, 14, 64, 128), (5, 7, 7, 64, 64), (2, 5, 5, 48, 52), (1, 3, 3, 64, 64),
+    (4, 1, 1, 64, 64), (2, 31, 31, 52, 68), (1, 33, 17, 68, 52), (2, 17, 33, 100, 48), (1, 30, 30, 64, 132), (2, 9, 60, 48, 48),
+    (7, 12, 10, 56, 60), (1, 112, 112, 64, 64), (16, 14, 14, 256, 192), (3, 8, 8, 512, 64),
+]
+
+
+@pytest.mark.parametrize("case", NINE_TAP_CASES, ids=lambda c: "n{}h{}w{}c{}k{}".format(*c))
+def test_conv_backward_weight_nine_tap_kernel(api, o32, case):
+    N, H, W, C, K = case
+    g = ConvGeom(N, H, W, C, K, 3, 3, 1, 1)
+    r = rng(31)
+    x = r.standard_normal((N, H, W, C), dtype=np.float32)
+    dy = r.standard_normal((N, H, W, K), dtype=np.float32)
+    yfwd = r.standard_normal(dy.shape, dtype=np.float32)
+    for gate, bias in ((False, True), (True, True), (False, False)):
+        dye = o32.relu_bwd(dy, yfwd) if gate else dy
+        ref_dw, ref_db = o32.conv_bwd_weight(g, x, dye)
+        d = api.conv_desc(N, H, W, C, K, 3, 3, 1, 1, api.F32, (api.CONV_BIAS if bias else 0) | (api.CONV_RELU if gate else 0))
+        ws = torch.empty(max(16, api.stanza_conv_workspace_bytes(d, 2)), dtype=torch.uint8, device="cuda:0")
+        ws.fill_(0xFF)                                               # NaN bit patterns: every partial sum that is read was written
+        dw = torch.full(ref_dw.shape, float("nan"), device="cuda:0")
+        db = torch.full(ref_db.shape, float("nan"), device="cuda:0") if bias else None
+        xd, dyd, yd = dev(x), dev(dy), dev(yfwd) if gate else None
+        api.stanza_conv_bwd_weight(d, xd, dyd, yd, dw, db, ws)
+        assert rel_err(host(dw), ref_dw) < TOL_F32, (case, gate, bias)
+        if bias:
+            assert rel_err(host(db), ref_db) < TOL_F32, (case, gate)
+        dw2 = torch.empty_like(dw)                                   # fixed-order reductions: run-to-run identical
+        api.stanza_conv_bwd_weight(d, xd, dyd, yd, dw2, torch.empty_like(db) if bias else None, ws)
+        assert torch.equal(dw, dw2)
+
+
 # shapes whose forward / backward-data launches are cut into reduction slices when a workspace is given: few tiles (all
 # of them sliced), and several rounds of tiles with a partly filled last round (only the tail sliced)
 SLICED_CASES = [
