@@ -149,6 +149,7 @@ def main():
     # ---- per-call instrumentation (HIP events on the stream the kernels are launched on)
     records = []     # (tag, start_event, end_event)
 
+    call_reads = {}  # entry point -> per call (reads y as gate, reads the x mask, reads dx to accumulate), in issue order
     pool = []        # event pairs, reused by every step: a step's times are read before the next step records into them again
 
     def timed(tag, fn, *a, **kw):
@@ -159,6 +160,12 @@ def main():
         fn(*a, **kw)
         e.record()
         records.append((tag, s, e))
+        # which optional tensors this call reads (they count in its algorithmic bytes): the forward output that gates dy, the
+        # layer input that gates dx, the previous dx of an accumulating call
+        if tag == "stanza_conv_bwd_weight":
+            call_reads.setdefault(tag, []).append((a[3] is not None, False, False))
+        elif tag == "stanza_conv_bwd_data":
+            call_reads.setdefault(tag, []).append((a[2] is not None, a[4] is not None, bool(a[0].flags & api.CONV_ACCUM)))
 
     real = {k: getattr(api, k) for k in ("stanza_conv_fwd", "stanza_conv_bwd_data", "stanza_conv_bwd_weight",
                                          "stanza_pool_relu_fwd", "stanza_pool_relu_bwd", "stanza_add_relu_fwd",
@@ -307,13 +314,13 @@ def main():
             _, hi, wi, c = shapes[op["src"]]
             fl = 2.0 * nn * ho * wo * kk * c * op["R"] * op["S"]
             n_in, n_out, n_w = float(nn * hi * wi * c), float(nn * ho * wo * kk), float(kk * op["R"] * op["S"] * c)
-            gated = bool(op.get("relu")) and oi not in worker.joined
+            reads_y, reads_mask, reads_dx = call_reads[kind][ci] if kind in call_reads else (False, False, False)
             if kind == "stanza_conv_fwd":
                 by = esz_c * (n_in + n_w + n_out) + (esz_c * n_out if oi in worker.joined else 0.0)      # a fused join reads the other addend
             elif kind == "stanza_conv_bwd_data":
-                by = esz_c * (n_out + n_w + n_in) + (esz_c * n_out if gated else 0.0)
+                by = esz_c * (n_out + n_w + n_in) + esz_c * (n_out * reads_y + n_in * reads_mask + n_in * reads_dx)
             else:
-                by = esz_c * (n_in + n_out) + 4.0 * n_w + (esz_c * n_out if gated else 0.0)             # the filter gradient is float32
+                by = esz_c * (n_in + n_out) + 4.0 * n_w + esz_c * n_out * reads_y                        # the filter gradient is float32
             layer_rows.append({"kind": kind[7:], "layer": op["name"], "in": f"{hi}x{wi}x{c}", "K": kk, "R": op["R"], "S": op["S"],
                                "stride": op["stride"], "ms": ms, "flops": fl, "bytes": by})
     low = [r for r in layer_rows if r["flops"] / r["bytes"] <= ridge]

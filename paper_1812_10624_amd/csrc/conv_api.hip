@@ -490,6 +490,54 @@ bool plan_wgrad_taps(const ConvGeo &g, TapsParams *tp)
     return true;
 }
 
+// The image-layer form: 4 input channels (an RGB image padded to 4), any width (strips of at most 56 pixels).
+bool plan_wgrad_taps_c4(const ConvGeo &g, TapsC4Params *tp)
+{
+    if (g.R != 3 || g.S != 3 || g.sh != 1 || g.sw != 1 || g.ph != 1 || g.pw != 1 || g.C != 4 || g.K % 4) return false;
+    const int64_t lim = int64_t(1) << 31;
+    if ((int64_t)g.N * g.H * g.W * g.K * 4 >= lim) return false;
+    TapsC4Params t{};
+    t.N = g.N; t.H = g.H; t.W = g.W; t.K = g.K;
+    t.strips = cdiv(g.W, C4_SW);
+    t.SW = cdiv(g.W, t.strips);
+    t.total_stages = g.N * t.strips * g.H;
+    t.tiles = cdiv(g.K, TAPS_T);
+    int slices = max(1, 4 * CUS / t.tiles);          // four resident workgroups per CU
+    slices = max(1, min(slices, t.total_stages / 4));
+    t.stages_per_item = cdiv(t.total_stages, slices);
+    t.slices = cdiv(t.total_stages, t.stages_per_item);
+    t.fd_h = make_fastdiv(g.H);
+    t.fd_strips = make_fastdiv(t.strips);
+    t.fd_tiles = make_fastdiv(t.tiles);
+    t.dy_bytes = (uint32_t)((int64_t)g.N * g.H * g.W * g.K * 4);
+    t.x_bytes = (uint32_t)((int64_t)g.N * g.H * g.W * 4 * 4);
+    *tp = t;
+    return true;
+}
+
+// Forward pass of an image layer (4 input channels, 3x3, stride 1, pad 1): the kernel that keeps the filter in registers.
+bool plan_fwd_c4(const ConvGeo &g, FwdC4Params *fp)
+{
+    if (g.R != 3 || g.S != 3 || g.sh != 1 || g.sw != 1 || g.ph != 1 || g.pw != 1 || g.C != 4 || g.K % 4) return false;
+    if ((int64_t)g.N * g.H * g.W * 16 >= (int64_t(1) << 31)) return false;
+    FwdC4Params f{};
+    f.N = g.N; f.H = g.H; f.W = g.W; f.K = g.K;
+    f.strips = cdiv(g.W, F4_COLS);
+    f.rowblocks = cdiv(g.H, F4_ROWS);
+    f.total_stages = g.N * f.strips * f.rowblocks;
+    f.tiles = cdiv(g.K, TAPS_T);
+    int slices = max(1, 8 * CUS / f.tiles);          // two rounds of four resident workgroups per CU
+    slices = max(1, min(slices, f.total_stages / 4));
+    f.stages_per_item = cdiv(f.total_stages, slices);
+    f.slices = cdiv(f.total_stages, f.stages_per_item);
+    f.fd_rowblocks = make_fastdiv(f.rowblocks);
+    f.fd_strips = make_fastdiv(f.strips);
+    f.fd_tiles = make_fastdiv(f.tiles);
+    f.x_bytes = (uint32_t)((int64_t)g.N * g.H * g.W * 16);
+    *fp = f;
+    return true;
+}
+
 // The stage geometries of the 224- to 28-pixel-wide, the 14- and the 7-pixel-wide layers have kernels of their own with
 // the geometry compiled in; anything else runs the kernel that reads it from the parameters.
 template <bool GATED>
@@ -510,10 +558,12 @@ WgradPlan plan_wgrad(const ConvGeo &g, bool want_bias, int bk)
 {
     WgradPlan pl{};
     TapsParams tp;
-    if (bk == BK && plan_wgrad_taps(g, &tp)) {
-        pl.taps = true;
-        pl.splits = tp.slices;
-        pl.chunks_per_split = tp.stages_per_item;
+    TapsC4Params tp4;
+    const bool nine = bk == BK && plan_wgrad_taps(g, &tp), nine4 = bk == BK && !nine && plan_wgrad_taps_c4(g, &tp4);
+    if (nine || nine4) {
+        pl.taps = nine ? 1 : 2;
+        pl.splits = nine ? tp.slices : tp4.slices;
+        pl.chunks_per_split = nine ? tp.stages_per_item : tp4.stages_per_item;
         pl.partial_floats = pl.splits > 1 ? (size_t)pl.splits * g.K * 9 * g.C : 0;
         pl.db_floats = (want_bias && pl.splits > 1) ? (size_t)pl.splits * g.K : 0;
         pl.bytes = round256(pl.partial_floats * 4) + round256(pl.db_floats * 4);
@@ -584,6 +634,17 @@ static int conv_fwd_any(const stanza_conv_desc *desc, const void *x, const void 
     const bool has_bias = desc->flags & STANZA_CONV_BIAS;
     if (!x || !w || !y || (has_bias && !bias) || (want_res && !res)) return STANZA_ENULL;
     if (!aligned16(x) || !aligned16(w) || !aligned16(y) || !aligned16(bias) || !aligned16(ws) || !aligned16(res)) return STANZA_EALIGN;
+    FwdC4Params f4;
+    if (desc->dtype == STANZA_F32 && !want_res && plan_fwd_c4(p.g, &f4)) {
+        f4.x = (const float *)x;
+        f4.w = (const float *)w;
+        f4.bias = has_bias ? bias : nullptr;
+        f4.y = (float *)y;
+        const dim3 grid((unsigned)(cdiv(f4.tiles * f4.slices, 8) * 8));
+        if (desc->flags & STANZA_CONV_RELU) hipLaunchKernelGGL(fwd_c4_kernel<true>, grid, dim3(256), 0, (hipStream_t)stream, f4);
+        else hipLaunchKernelGGL(fwd_c4_kernel<false>, grid, dim3(256), 0, (hipStream_t)stream, f4);
+        return launch_status();
+    }
     p.a = (const float *)x;
     p.b = (const float *)w;
     p.out = (float *)y;
@@ -677,6 +738,22 @@ extern "C" int stanza_conv_bwd_weight(const stanza_conv_desc *desc, const void *
     hipStream_t st = (hipStream_t)stream;
     float *partial = (float *)ws;
     float *dbscratch = (float *)((char *)ws + round256(pl.partial_floats * 4));
+    if (pl.taps == 2) {
+        TapsC4Params tp;
+        if (!plan_wgrad_taps_c4(p.g, &tp)) return STANZA_EINVAL;
+        tp.dy = (const float *)dy;
+        tp.amask = (desc->flags & STANZA_CONV_RELU) ? (const float *)y : nullptr;
+        tp.x = (const float *)x;
+        tp.out = pl.splits > 1 ? partial : dw;
+        tp.dbias = want_bias ? (pl.splits > 1 ? dbscratch : dbias) : nullptr;
+        const dim3 grid((unsigned)(cdiv(tp.tiles * tp.slices, 8) * 8));
+        if (tp.amask) hipLaunchKernelGGL(wgrad_taps_c4_kernel<true>, grid, dim3(256), 0, st, tp);
+        else hipLaunchKernelGGL(wgrad_taps_c4_kernel<false>, grid, dim3(256), 0, st, tp);
+        if ((rc = launch_status())) return rc;
+        if (pl.splits > 1)
+            rc = launch_split_reduce(partial, pl.splits, (size_t)p.g.K * 36, dw, dbscratch, want_bias ? (size_t)p.g.K : 0, dbias, st);
+        return rc;
+    }
     if (pl.taps) {
         TapsParams tp;
         if (!plan_wgrad_taps(p.g, &tp)) return STANZA_EINVAL;

@@ -24,7 +24,8 @@ int conv_geometry(const stanza_conv_desc *d, ConvGeo *g);
 // How the filter-gradient reduction is cut into workgroups; the same plan sizes the workspace and drives
 // the launch, so the two can never disagree.
 struct WgradPlan {
-    bool taps;             // float32 3x3 stride-1 pad-1 layers: the kernel that keeps all nine taps in one workgroup (wgrad_taps.h)
+    int taps;              // float32 3x3 stride-1 pad-1 layers: 1 = the kernel that keeps all nine taps in one workgroup, 2 = its
+                           // image-layer form for 4 input channels (wgrad_taps.h); 0 = the implicit-GEMM engine
     int splits;            // reduction slices (blockIdx.y); for taps: pixel slices
     int chunks_per_split;  // BK-deep stages per slice; for taps: stages per slice
     size_t partial_floats; // splits * K * R*S*C when splits > 1, else 0
@@ -34,6 +35,8 @@ struct WgradPlan {
 WgradPlan plan_wgrad(const ConvGeo &g, bool want_bias, int bk);   // bk: reduction depth of one LDS stage
 // Stage geometry and work split of the nine-tap filter-gradient kernel; false when the layer is not one it handles.
 bool plan_wgrad_taps(const ConvGeo &g, TapsParams *tp);
+bool plan_wgrad_taps_c4(const ConvGeo &g, TapsC4Params *tp);
+bool plan_fwd_c4(const ConvGeo &g, FwdC4Params *fp);
 
 // Launch the implicit GEMM in `mode` over p (M, Nn, Kd, pointers and flags already set); picks the tile shape and fills
 // the tile counts.  bw_splits: reduction slices of every tile, MODE_BWD_WEIGHT only (1 otherwise).

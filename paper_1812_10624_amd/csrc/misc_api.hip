@@ -561,7 +561,11 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t ps_rsrc(const float *ptr)
 {
     return __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(ptr), 0, STANZA_PS_CHUNK * 4, 0x00020000);
 }
-constexpr int PS_CHUNK = STANZA_PS_CHUNK;  // elements per workgroup: 256 threads x PS_CHUNK/1024 vectors of 4
+#ifndef STANZA_PS_THREADS
+#define STANZA_PS_THREADS 256
+#endif
+constexpr int PS_T = STANZA_PS_THREADS;    // threads per workgroup
+constexpr int PS_CHUNK = STANZA_PS_CHUNK;  // elements per workgroup: PS_T threads x PS_CHUNK/(4 PS_T) vectors of 4
 
 struct PsTable {
     const int64_t *prefix;
@@ -670,7 +674,7 @@ struct PsPack {
 };
 
 template <int KFIX, int ORDER>
-__global__ __launch_bounds__(256) void ps_aggregate_kernel(const void *ws, int n_tensors, int K, float scale, float lr, float mom, float wd)
+__global__ __launch_bounds__(PS_T) void ps_aggregate_kernel(const void *ws, int n_tensors, int K, float scale, float lr, float mom, float wd)
 {
     const PsTable tb = ps_table_at(ws, n_tensors);
     const int64_t chunk = blockIdx.x;
@@ -695,7 +699,7 @@ __global__ __launch_bounds__(256) void ps_aggregate_kernel(const void *ws, int n
     float *__restrict__ w = tb.w[t];
     float *__restrict__ v = tb.v[t];
     const float *const *gp = tb.grads + t;   // shard k at gp[k * n_tensors]
-    constexpr int U = PS_CHUNK / 1024;   // vectors per thread; all of their loads are issued before any store
+    constexpr int U = PS_CHUNK / (4 * PS_T);   // vectors per thread; all of their loads are issued before any store
     if (base + PS_CHUNK <= numel) {
         // One buffer descriptor per stream, based at this workgroup's chunk (wavefront-uniform), so tensors of any size
         // are addressed with a 32-bit in-chunk offset.
@@ -703,7 +707,7 @@ __global__ __launch_bounds__(256) void ps_aggregate_kernel(const void *ws, int n
         auto leaf = [&](int k, PsPack<U> &out) {
             const __amdgpu_buffer_rsrc_t rg = ps_rsrc(gp[(size_t)k * n_tensors] + base);
 #pragma unroll
-            for (int u = 0; u < U; ++u) out.x[u] = __builtin_bit_cast(v4f, __builtin_amdgcn_raw_buffer_load_b128(rg, off + u * 4096u, 0, PS_NT));
+            for (int u = 0; u < U; ++u) out.x[u] = __builtin_bit_cast(v4f, __builtin_amdgcn_raw_buffer_load_b128(rg, off + u * (PS_T * 16u), 0, PS_NT));
         };
         PsPack<U> s;
         ps_shard_sum<KFIX, ORDER>(K, leaf, s);
@@ -711,8 +715,8 @@ __global__ __launch_bounds__(256) void ps_aggregate_kernel(const void *ws, int n
         const __amdgpu_buffer_rsrc_t rw = ps_rsrc(w + base), rv = ps_rsrc(v + base);
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            wv[u] = __builtin_bit_cast(v4f, __builtin_amdgcn_raw_buffer_load_b128(rw, off + u * 4096u, 0, PS_NT));
-            vv[u] = __builtin_bit_cast(v4f, __builtin_amdgcn_raw_buffer_load_b128(rv, off + u * 4096u, 0, PS_NT));
+            wv[u] = __builtin_bit_cast(v4f, __builtin_amdgcn_raw_buffer_load_b128(rw, off + u * (PS_T * 16u), 0, PS_NT));
+            vv[u] = __builtin_bit_cast(v4f, __builtin_amdgcn_raw_buffer_load_b128(rv, off + u * (PS_T * 16u), 0, PS_NT));
         }
 #pragma unroll
         for (int u = 0; u < U; ++u) {
@@ -722,12 +726,12 @@ __global__ __launch_bounds__(256) void ps_aggregate_kernel(const void *ws, int n
                 a[e] = mom * a[e] + (scale * s.x[u][e] + wd * b[e]);
                 b[e] -= lr * a[e];
             }
-            __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(v4u, a), rv, off + u * 4096u, 0, PS_NT);
-            __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(v4u, b), rw, off + u * 4096u, 0, PS_NT);
+            __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(v4u, a), rv, off + u * (PS_T * 16u), 0, PS_NT);
+            __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(v4u, b), rw, off + u * (PS_T * 16u), 0, PS_NT);
         }
     } else {
         // ragged last chunk of a tensor: scalar, same summation order
-        for (int64_t j = base + threadIdx.x; j < numel; j += 256) {
+        for (int64_t j = base + threadIdx.x; j < numel; j += PS_T) {
             auto leaf = [&](int k, float &out) { out = gp[(size_t)k * n_tensors][j]; };
             float sum;
             ps_shard_sum<0, ORDER>(K, leaf, sum);
@@ -1034,7 +1038,7 @@ extern "C" int stanza_ps_plan(int32_t n_tensors, const int64_t *host_numel, floa
 template <int ORDER>
 static void ps_launch(int32_t K, dim3 grid, hipStream_t st, const void *ws, int32_t n_tensors, float scale, float lr, float momentum, float weight_decay)
 {
-    const dim3 block(256);
+    const dim3 block(PS_T);
     switch (K) {
     case 2: hipLaunchKernelGGL((ps_aggregate_kernel<2, ORDER>), grid, block, 0, st, ws, n_tensors, K, scale, lr, momentum, weight_decay); break;
     case 4: hipLaunchKernelGGL((ps_aggregate_kernel<4, ORDER>), grid, block, 0, st, ws, n_tensors, K, scale, lr, momentum, weight_decay); break;

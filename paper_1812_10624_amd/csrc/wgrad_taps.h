@@ -297,4 +297,305 @@ __global__ __launch_bounds__(256, 2) void wgrad_taps_kernel(const TapsParams p)
     }
 }
 
+
+// ---------------------------------------------------------------------------------------------------------------------
+// The same filter gradient for an image layer: C = 4 input channels (3 padded to 4), 3x3, stride 1, pad 1.  With so few
+// channels the layer is bound by the one pass over dy (its arithmetic is 2*27 flops per dy element), and the generic tiles
+// spend their time on loader arithmetic for operands that are mostly padding.  Here the GEMM's column index is (tap, c):
+// 36 columns, three 16-wide MFMA tiles (v_mfma_f32_16x16x4_f32; the twelve columns beyond 36 read zeros).  A workgroup owns
+// 64 output channels (16 per wavefront) and walks over row segments of up to 56 output pixels: dy of the segment (56 x 64
+// floats) and the three image rows around it (58 pixels x 4 channels each) are staged in LDS, double-buffered; a k-step is
+// 4 pixels: one dy read, three window reads (each lane at its own tap's shift), three MFMAs, all at immediate offsets.
+constexpr int C4_SW = 56;                 // output pixels per stage
+constexpr int C4_XW = C4_SW + 2;          // window pixels per row
+constexpr int C4_KS = C4_SW / 4;          // k-steps per stage
+constexpr int C4_WIN = 3 * C4_XW * 4;     // floats of one window
+constexpr int C4_ZERO = C4_KS * 16 + 16;  // zero floats behind it (columns 36..47)
+
+struct TapsC4Params {
+    const float *dy, *amask, *x;   // x: [N,H,W,4]
+    float *out, *dbias;            // dW [K][3][3][4] or the slices' partial sums; db or its partial sums (nullptr: not wanted)
+    int N, H, W, K;
+    int SW, strips;                // strip width (<= 56) and strips per row
+    int tiles, slices, stages_per_item, total_stages;
+    FastDiv fd_h, fd_strips, fd_tiles;
+    uint32_t dy_bytes, x_bytes;
+};
+
+template <bool GATED>
+__global__ __launch_bounds__(256, 4) void wgrad_taps_c4_kernel(const TapsC4Params p)
+{
+    __shared__ __attribute__((aligned(16))) float dyL[2 * C4_SW * TAPS_T];
+    __shared__ __attribute__((aligned(16))) float xW[2 * (C4_WIN + C4_ZERO)];
+
+    const int per_xcd = gridDim.x >> 3;
+    const int L = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+    if (L >= p.tiles * p.slices) return;
+    const int slice = fdiv(L, p.fd_tiles), tk = L - slice * p.tiles;
+    const int k0 = tk * TAPS_T;
+    const int t = threadIdx.x, lane = t & 63, wave = t >> 6, l16 = lane & 15, lq = lane >> 4;
+    const int g4 = (t & 15) * 4;
+    const int W = p.W, H = p.H, K = p.K;
+
+    for (int i = t; i < 2 * (C4_WIN + C4_ZERO); i += 256) xW[i] = 0.f;     // the zero columns stay zero; the windows are rewritten
+
+    // stages [sid, send): (image, strip, row) with the row fastest
+    int sid = slice * p.stages_per_item;
+    const int send = min(p.total_stages, sid + p.stages_per_item);
+    int row, strip, n;
+    {
+        const int q = fdiv(sid, p.fd_h);
+        row = sid - q * H;
+        n = fdiv(q, p.fd_strips);
+        strip = q - n * p.strips;
+    }
+    const __amdgpu_buffer_rsrc_t rs_dy = make_rsrc(p.dy, p.dy_bytes), rs_m = make_rsrc(GATED ? p.amask : p.dy, p.dy_bytes);
+    const __amdgpu_buffer_rsrc_t rs_x = make_rsrc(p.x, p.x_bytes);
+    const bool kch = k0 + g4 < K;
+    const int wrow = t / C4_XW, wcol = t - wrow * C4_XW;      // window loader: thread -> (row 0..2, pixel), t < 3 * XW
+
+    float4 r_dy[4], r_m[4], r_x;
+    auto fetch = [&](int n_, int row_, int strip_, bool live) {
+        const int q0 = strip_ * p.SW;
+        const int pix0 = (n_ * H + row_) * W + q0;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int px = (t >> 4) + 16 * i;
+            const bool ok = live && kch && px < p.SW && q0 + px < W;
+            const uint32_t bo = ok ? (uint32_t)((pix0 + px) * K + k0 + g4) * 4u : OOB_OFF;
+            r_dy[i] = bload4(rs_dy, bo);
+            if (GATED) r_m[i] = bload4(rs_m, bo);
+        }
+        const int h = row_ - 1 + wrow, w = q0 - 1 + wcol;
+        const bool okx = live && t < 3 * C4_XW && (unsigned)h < (unsigned)H && (unsigned)w < (unsigned)W;
+        r_x = bload4(rs_x, okx ? (uint32_t)(((n_ * H + h) * W + w) * 4) * 4u : OOB_OFF);
+    };
+    const bool want_db = p.dbias != nullptr;
+    float4 dbacc = zero4();
+    auto stash = [&](int buf) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int px = (t >> 4) + 16 * i;
+            if (px >= C4_SW) continue;
+            float4 v = r_dy[i];
+            if (GATED) v = gate4(v, r_m[i]);
+            // the 16-channel quarters of a pixel row are rotated by the pixel's position in its group of four: the four
+            // pixels of a k-step then lie in four different quarters of the banks
+            *reinterpret_cast<float4 *>(&dyL[(buf * C4_SW + px) * TAPS_T + (g4 ^ ((px & 3) << 4))]) = v;
+            if (want_db) { dbacc.x += v.x; dbacc.y += v.y; dbacc.z += v.z; dbacc.w += v.w; }
+        }
+        if (t < 3 * C4_XW) *reinterpret_cast<float4 *>(&xW[buf * (C4_WIN + C4_ZERO) + t * 4]) = r_x;
+    };
+
+    typedef float f32x4 __attribute__((ext_vector_type(4)));
+    f32x4 acc[3];
+#pragma unroll
+    for (int i = 0; i < 3; ++i) acc[i] = (f32x4){0.f, 0.f, 0.f, 0.f};
+
+    // operand offsets of this lane (floats): dy at pixel lq of the k-step, channel 16*wave + l16;
+    // window column j = 16*nt + l16 = (tap, c): pixel lq + s of row r, or the zero area for j >= 36
+    const int a_off = lq * TAPS_T + ((wave * 16 + l16) ^ (lq << 4));
+    int b_off[3];
+#pragma unroll
+    for (int nt = 0; nt < 3; ++nt) {
+        const int j = nt * 16 + l16, tap = j >> 2, c = j & 3, r = tap / 3, s = tap - r * 3;
+        b_off[nt] = tap < 9 ? (r * C4_XW + s + lq) * 4 + c : C4_WIN + lq * 4 + c;
+    }
+
+    int buf = 0;
+    fetch(n, row, strip, sid < send);
+    __syncthreads();
+    stash(0);
+    __syncthreads();
+    for (; sid < send; ++sid) {
+        int row2 = row + 1, strip2 = strip, n2 = n;
+        if (row2 == H) {
+            row2 = 0;
+            if (++strip2 == p.strips) { strip2 = 0; ++n2; }
+        }
+        const bool live2 = sid + 1 < send;
+        fetch(n2, row2, strip2, live2);
+        const float *dyA = dyL + buf * (C4_SW * TAPS_T) + a_off;
+        const float *xB = xW + buf * (C4_WIN + C4_ZERO);
+        float a[2], b[2][3];
+        auto read = [&](int ks, int set) {
+            a[set] = dyA[ks * (4 * TAPS_T)];
+#pragma unroll
+            for (int nt = 0; nt < 3; ++nt) b[set][nt] = xB[b_off[nt] + ks * 16];
+        };
+        read(0, 0);
+#pragma unroll
+        for (int ks = 0; ks < C4_KS; ++ks) {
+            if (ks + 1 < C4_KS) read(ks + 1, (ks + 1) & 1);
+            TAPS_FENCE;
+#pragma unroll
+            for (int nt = 0; nt < 3; ++nt) acc[nt] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[ks & 1], b[ks & 1][nt], acc[nt], 0, 0, 0);
+            TAPS_FENCE;
+        }
+        buf ^= 1;
+        if (live2) stash(buf);
+        __syncthreads();
+        row = row2; strip = strip2; n = n2;
+    }
+
+    if (want_db) {
+        float *red = dyL;
+        *reinterpret_cast<float4 *>(&red[(t >> 4) * TAPS_T + g4]) = dbacc;
+        __syncthreads();
+        if (t < TAPS_T && k0 + t < K) {
+            float s = 0.f;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) s += red[r * TAPS_T + t];
+            p.dbias[(size_t)slice * K + k0 + t] = s;
+        }
+    }
+    // accumulator register r of lane l: row 4*(l/16) + r, column l%16 of a 16x16 tile
+    float *dst = p.out + (size_t)slice * K * 36;
+#pragma unroll
+    for (int nt = 0; nt < 3; ++nt) {
+        const int j = nt * 16 + l16;
+        if (j >= 36) continue;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const int k = k0 + wave * 16 + 4 * lq + r;
+            if (k < K) dst[(size_t)k * 36 + j] = acc[nt][r];
+        }
+    }
+}
+
+
+// ---------------------------------------------------------------------------------------------------------------------
+// Forward pass of the same image layer (C = 4, 3x3, stride 1, pad 1): y[pix][k] = bias[k] + sum_{tap,c} x[pix (+) tap][c] w[k][tap][c].
+// The layer writes 16 output floats for every input float: it is bound by the one pass over y.  A k-step of
+// v_mfma_f32_16x16x4_f32 is exactly one tap (4 channels), so the filter is nine registers per 16 output channels and
+// lives in registers for the whole kernel; the image window (6 rows x 34 pixels x 4 channels for a stage of 4 rows x 32
+// output pixels) is the only operand staged in LDS.  Each wavefront owns one output row of the stage (two groups of 16
+// pixels) x 64 output channels: 72 MFMAs, then bias / ReLU, and the tile leaves through a private LDS patch as 16-byte
+// vectors of whole pixel rows (1 KB contiguous per store instruction).
+constexpr int F4_ROWS = 4, F4_COLS = 32;                       // output pixels of a stage
+constexpr int F4_WR = F4_ROWS + 2, F4_WC = F4_COLS + 2;        // window
+constexpr int F4_WIN = F4_WR * F4_WC * 4;                      // floats
+constexpr int F4_LDC = TAPS_T + 4;                             // row stride of the output patch (floats)
+
+struct FwdC4Params {
+    const float *x, *w, *bias;     // x [N,H,W,4], w [K][3][3][4], bias [K] or nullptr
+    float *y;                      // [N,H,W,K]
+    int N, H, W, K;
+    int strips, rowblocks;         // per image
+    int tiles, slices, stages_per_item, total_stages;
+    FastDiv fd_rowblocks, fd_strips, fd_tiles;
+    uint32_t x_bytes;
+};
+
+template <bool RELU>
+__global__ __launch_bounds__(256, 4) void fwd_c4_kernel(const FwdC4Params p)
+{
+    __shared__ __attribute__((aligned(16))) float xW[2 * F4_WIN];
+    __shared__ __attribute__((aligned(16))) float patch[4 * 16 * F4_LDC];
+
+    const int per_xcd = gridDim.x >> 3;
+    const int L = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+    if (L >= p.tiles * p.slices) return;
+    const int slice = fdiv(L, p.fd_tiles), tk = L - slice * p.tiles;
+    const int k0 = tk * TAPS_T;
+    const int t = threadIdx.x, lane = t & 63, wave = t >> 6, l16 = lane & 15, lq = lane >> 4;
+    const int W = p.W, H = p.H, K = p.K;
+
+    // the filter: b[kt][tap] = w[k0 + 16*kt + l16][tap][c = lq]
+    float b[4][9];
+#pragma unroll
+    for (int kt = 0; kt < 4; ++kt) {
+        const int k = k0 + kt * 16 + l16;
+#pragma unroll
+        for (int tap = 0; tap < 9; ++tap) b[kt][tap] = k < K ? p.w[((size_t)k * 9 + tap) * 4 + lq] : 0.f;
+    }
+    float bias4[4];      // this lane's 4 consecutive output channels in the store phase
+#pragma unroll
+    for (int e = 0; e < 4; ++e) bias4[e] = (p.bias && k0 + l16 * 4 + e < K) ? p.bias[k0 + l16 * 4 + e] : 0.f;
+
+    int sid = slice * p.stages_per_item;
+    const int send = min(p.total_stages, sid + p.stages_per_item);
+    int rb, strip, n;
+    {
+        const int q = fdiv(sid, p.fd_rowblocks);
+        rb = sid - q * p.rowblocks;
+        n = fdiv(q, p.fd_strips);
+        strip = q - n * p.strips;
+    }
+    const __amdgpu_buffer_rsrc_t rs_x = make_rsrc(p.x, p.x_bytes);
+    const int wrow = t / F4_WC, wcol = t - wrow * F4_WC;          // window loader, t < F4_WR * F4_WC
+    float4 r_x;
+    auto fetch = [&](int n_, int rb_, int strip_, bool live) {
+        const int h = rb_ * F4_ROWS - 1 + wrow, w = strip_ * F4_COLS - 1 + wcol;
+        const bool ok = live && t < F4_WR * F4_WC && (unsigned)h < (unsigned)H && (unsigned)w < (unsigned)W;
+        r_x = bload4(rs_x, ok ? (uint32_t)(((n_ * H + h) * W + w) * 4) * 4u : OOB_OFF);
+    };
+    auto stash = [&](int buf) {
+        if (t < F4_WR * F4_WC) *reinterpret_cast<float4 *>(&xW[buf * F4_WIN + t * 4]) = r_x;
+    };
+
+    typedef float f32x4 __attribute__((ext_vector_type(4)));
+    // A operand of pixel group g (16 pixels of this wavefront's row), tap (r,s): window[(wave + r)][16*g + l16 + s][c = lq]
+    const int a_off = (wave * F4_WC + l16) * 4 + lq;
+    float *mine = patch + wave * (16 * F4_LDC);
+
+    int buf = 0;
+    fetch(n, rb, strip, sid < send);
+    stash(0);
+    __syncthreads();
+    for (; sid < send; ++sid) {
+        int rb2 = rb + 1, strip2 = strip, n2 = n;
+        if (rb2 == p.rowblocks) {
+            rb2 = 0;
+            if (++strip2 == p.strips) { strip2 = 0; ++n2; }
+        }
+        const bool live2 = sid + 1 < send;
+        fetch(n2, rb2, strip2, live2);
+        const float *win = xW + buf * F4_WIN + a_off;
+        f32x4 acc[2][4];
+#pragma unroll
+        for (int g = 0; g < 2; ++g)
+#pragma unroll
+            for (int kt = 0; kt < 4; ++kt) acc[g][kt] = (f32x4){0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int g = 0; g < 2; ++g)
+#pragma unroll
+            for (int tap = 0; tap < 9; ++tap) {
+                const float a = win[((tap / 3) * F4_WC + 16 * g + tap % 3) * 4];
+#pragma unroll
+                for (int kt = 0; kt < 4; ++kt) acc[g][kt] = __builtin_amdgcn_mfma_f32_16x16x4f32(a, b[kt][tap], acc[g][kt], 0, 0, 0);
+            }
+        // accumulator register r of lane l: pixel 4*(l/16) + r, channel 16*kt + l%16.  Through this wavefront's LDS patch the
+        // tile turns into whole pixel rows: lane l then holds 4 consecutive channels (4*(l%16) ..) of pixel l/16 + 4*j.
+        const int prow = rb * F4_ROWS + wave;
+#pragma unroll
+        for (int g = 0; g < 2; ++g) {
+#pragma unroll
+            for (int kt = 0; kt < 4; ++kt)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) mine[(4 * lq + r) * F4_LDC + kt * 16 + l16] = acc[g][kt][r];
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int px = lq + 4 * j;
+                float4 v = *reinterpret_cast<const float4 *>(&mine[px * F4_LDC + l16 * 4]);
+                v.x += bias4[0]; v.y += bias4[1]; v.z += bias4[2]; v.w += bias4[3];
+                if (RELU) v = make_float4(fmaxf(v.x, 0.f), fmaxf(v.y, 0.f), fmaxf(v.z, 0.f), fmaxf(v.w, 0.f));
+                const int q = strip * F4_COLS + 16 * g + px;
+                if (prow < H && q < W && k0 + l16 * 4 < K)
+                    *reinterpret_cast<float4 *>(p.y + ((size_t)(n * H + prow) * W + q) * K + k0 + l16 * 4) = v;
+            }
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        }
+        buf ^= 1;
+        if (live2) stash(buf);
+        __syncthreads();
+        rb = rb2; strip = strip2; n = n2;
+    }
+}
+
 }  // namespace stanza

@@ -129,6 +129,9 @@ NINE_TAP_CASES = [
     (2, 56, 56, 64, 64), (1, 28, 28, 128, 64), (3, 14, 14, 64, 128), (5, 7, 7, 64, 64), (2, 5, 5, 48, 52), (1, 3, 3, 64, 64),
     (4, 1, 1, 64, 64), (2, 31, 31, 52, 68), (1, 33, 17, 68, 52), (2, 17, 33, 100, 48), (1, 30, 30, 64, 132), (2, 9, 60, 48, 48),
     (7, 12, 10, 56, 60), (1, 112, 112, 64, 64), (16, 14, 14, 256, 192), (3, 8, 8, 512, 64),
+    # image layers (4 input channels: an RGB image padded to 4) take the 36-column form of the kernel: strips of 56 pixels
+    # (224 = 4 x 56), one short strip (32), ragged strips (61 = 31 + 30, 115 = 39 + 38 + 38), K that does not fill a tile
+    (2, 32, 32, 4, 16), (1, 60, 61, 4, 64), (3, 9, 115, 4, 68), (2, 224, 224, 4, 64), (5, 3, 2, 4, 8), (1, 1, 1, 4, 132),
 ]
 
 
@@ -156,6 +159,28 @@ def test_conv_backward_weight_nine_tap_kernel(api, o32, case):
         dw2 = torch.empty_like(dw)                                   # fixed-order reductions: run-to-run identical
         api.stanza_conv_bwd_weight(d, xd, dyd, yd, dw2, torch.empty_like(db) if bias else None, ws)
         assert torch.equal(dw, dw2)
+
+
+# forward pass of an image layer (4 input channels, 3x3 / stride 1 / pad 1): the kernel that keeps the filter in registers.
+# Stages of 4 rows x 32 pixels: whole (224, 32), ragged in both directions (61 x 60, 9 x 115, 3 x 2, 1 x 1), K below, at and
+# above one 64-channel tile and not a multiple of 16
+@pytest.mark.parametrize("case", [(2, 32, 32, 16), (1, 60, 61, 64), (3, 9, 115, 68), (1, 224, 224, 64), (5, 3, 2, 8), (2, 1, 1, 132), (2, 17, 33, 20)],
+                         ids=lambda c: "n{}h{}w{}k{}".format(*c))
+def test_conv_forward_image_layer_kernel(api, o32, case):
+    N, H, W, K = case
+    g = ConvGeom(N, H, W, 4, K, 3, 3, 1, 1)
+    r = rng(32)
+    x = r.standard_normal((N, H, W, 4), dtype=np.float32)
+    w = (r.standard_normal((K, 3, 3, 4), dtype=np.float32) / 6).astype(np.float32)
+    b = r.standard_normal(K, dtype=np.float32)
+    for bias, relu in ((True, True), (False, False), (True, False)):
+        ref = o32.conv_fwd(g, x, w, b if bias else None, relu=relu)
+        d = api.conv_desc(N, H, W, 4, K, 3, 3, 1, 1, api.F32, (api.CONV_BIAS if bias else 0) | (api.CONV_RELU if relu else 0))
+        y = torch.full(ref.shape, float("nan"), device="cuda:0")
+        api.stanza_conv_fwd(d, dev(x), dev(w), dev(b) if bias else None, y)
+        assert rel_err(host(y), ref) < TOL_F32, (case, bias, relu)
+        if relu:
+            np.testing.assert_array_equal(host(y) == 0, ref == 0)
 
 
 # shapes whose forward / backward-data launches are cut into reduction slices when a workspace is given: few tiles (all
