@@ -446,19 +446,35 @@ def _bias(rng, n, fan_in):
 
 def gen_conv_params(wl: Workload, seed: int):
     """Parameters held by a CONV worker, in op order.  Convolutions: {name: (W [K,R,S,C], b [K] or None)}, normal
-    weights with variance 2/fan_in, uniform biases.  Normalisation layers: {name: (gamma [C], beta [C])} drawn around
+    weights with variance 2/fan_in (scaled down at the joins of a residual stack without normalisation, see below), uniform biases.  Normalisation layers: {name: (gamma [C], beta [C])} drawn around
     1 and 0 (a trained state rather than the initial one, so that neither drops out of the arithmetic)."""
     has_bias = {op["name"]: op.get("bias", True) for op in wl.ops if op["op"] == "conv"}
     conv_shapes = dict(conv_param_shapes(wl))
     bn_shapes = dict(bn_param_shapes(wl))
+    # Residual stacks WITHOUT normalisation: with variance-2/fan_in filters everywhere the activations' energy triples at
+    # every join (16 joins: features of a few thousand, a loss of hundreds, and momentum SGD at lr 0.01 overflows within
+    # two steps).  As in the usual normalisation-free initialisations, the last convolution of a residual branch is
+    # scaled by (2 J)^-1/2 (J joins in the stack: the energy then grows by about e over the whole stack) and a projection
+    # shortcut by 2^-1/2 (it has no ReLU behind it to halve its output).
+    joins = [op for op in wl.ops if op["op"] == "add_relu"]
+    scale = {}
+    if joins and not bn_shapes:
+        produced_by = {op["dst"]: op for op in wl.ops if op["op"] == "conv"}
+        for j in joins:
+            if j["a"] in produced_by:
+                scale[produced_by[j["a"]]["name"]] = (2.0 * len(joins)) ** -0.5
+            if j["b"] in produced_by:
+                scale[produced_by[j["b"]]["name"]] = 2.0 ** -0.5
     out = {}
     for op in wl.ops:
         name = op.get("name")
         if op["op"] == "conv":
             k, r, s, c = conv_shapes[name]
             fan = r * s * c
-            out[name] = (_kaiming(rng_for(seed, "cw", name), (k, r, s, c), fan),
-                         _bias(rng_for(seed, "cb", name), k, fan) if has_bias[name] else None)
+            w = _kaiming(rng_for(seed, "cw", name), (k, r, s, c), fan)
+            if name in scale:
+                w *= np.float32(scale[name])
+            out[name] = (w, _bias(rng_for(seed, "cb", name), k, fan) if has_bias[name] else None)
         elif op["op"] == "bn":
             c = bn_shapes[name]
             g = rng_for(seed, "bng", name).standard_normal(c, dtype=np.float32) * np.float32(0.2) + np.float32(1.0)
