@@ -309,7 +309,7 @@ def main():
         if calls != len(ops_k):
             continue
         for ci, (oi, op) in enumerate(ops_k):
-            ms = sum(v[ci::calls]) / n_timed_eager
+            ms = float(np.median(v[ci::calls]))          # median over the steps: one stalled call must not set a layer's figure
             nn, ho, wo, kk = shapes[op["dst"]]
             _, hi, wi, c = shapes[op["src"]]
             fl = 2.0 * nn * ho * wo * kk * c * op["R"] * op["S"]
