@@ -183,6 +183,10 @@ def main():
                 return lambda *a, **kw: timed("stanza_conv_fwd", api.stanza_conv_fwd_res, *a, **kw)
             if k == "stanza_bn_fwd_res":        # likewise a normalisation layer with the join fused in
                 return lambda *a, **kw: timed("stanza_bn_fwd", api.stanza_bn_fwd_res, *a, **kw)
+            if k == "stanza_conv_fwd_stats":    # a forward convolution that leaves its output's column sums behind
+                return lambda *a, **kw: timed("stanza_conv_fwd", api.stanza_conv_fwd_stats, *a, **kw)
+            if k == "stanza_bn_fwd_stats":      # the normalisation layer that takes them (no statistics pass of its own)
+                return lambda *a, **kw: timed("stanza_bn_fwd", api.stanza_bn_fwd_stats, *a, **kw)
             return getattr(api, k)
     tap = _Tap()
 
@@ -346,13 +350,15 @@ def main():
             n_in = float(np.prod(shapes_all[op["src"]])); n_out = float(np.prod(shapes_all[op["dst"]]))
             pool_f += esz * n_in + esz * n_out + n_out                       # x read, y and argmax written
             pool_b += esz * n_out + n_out + (esz * n_out if op["relu"] else 0) + esz * n_in   # dy, argmax, y (gate) read, dx written
-    # normalisation layers: forward reads x twice (statistics, then apply) and writes y; backward reads x and dy twice, writes dx
+    # normalisation layers: forward reads x twice (statistics, then apply) and writes y; backward reads x and dy twice, writes dx.
+    # A layer that takes its statistics from the producing convolution's epilogue reads x once.
     bn_elems = sum(float(np.prod(shapes_all[op["src"]])) for op in wl.ops if op["op"] == "bn")
+    bn_fused_elems = sum(float(np.prod(shapes_all[wl.ops[i]["src"]])) for i in getattr(worker, "stats_bn", ()))
     # (a layer with the residual join fused in also reads the shortcut's tensor)
     bn_join_elems = sum(float(np.prod(shapes_all[wl.ops[i]["src"]])) for i in joined_ops if wl.ops[i]["op"] == "bn")
     hbm_kernels = {}
     for tag, by in (("stanza_pool_relu_fwd", pool_f), ("stanza_pool_relu_bwd", pool_b),
-                    ("stanza_bn_fwd", 3 * esz * bn_elems + esz * bn_join_elems), ("stanza_bn_bwd", 5 * esz * bn_elems)):
+                    ("stanza_bn_fwd", 3 * esz * bn_elems - esz * bn_fused_elems + esz * bn_join_elems), ("stanza_bn_bwd", 5 * esz * bn_elems)):
         if tag in tot and by > 0:
             gbs = by / (tot[tag] * 1e-3) / 1e9
             hbm_kernels[tag] = {"algorithmic_bytes_per_step": by, "ms_per_step": tot[tag], "GBps": gbs, "frac_hbm": gbs / HBM_PEAK_GBS}

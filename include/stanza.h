@@ -208,6 +208,25 @@ int stanza_bn_fwd(int64_t rows, int32_t C, int32_t dtype, float eps, int32_t rel
 int stanza_bn_fwd_res(int64_t rows, int32_t C, int32_t dtype, float eps, int32_t relu, const void *x, const float *gamma,
                       const float *beta, const void *res, void *y, float *save_mean, float *save_istd, float *running_mean,
                       float *running_var, float momentum, void *ws, size_t ws_bytes, void *stream);
+/* A convolution followed by a normalisation layer (every convolution of the residual and Inception networks of the paper's table
+ * of models, Sec. 6.1; the fusion is not in the paper): the convolution's epilogue leaves per-tile column sums of its output in
+ * `stats`, and the normalisation layer takes mean and variance from them instead of reading the tensor once more (two passes over
+ * the tensor instead of three).
+ *   stanza_conv_fwd_stats  = stanza_conv_fwd (same arguments, same y) that also fills stats; float32 only, K % 4 == 0 and no
+ *       STANZA_CONV_RELU (otherwise STANZA_EUNSUPPORTED).  stats: device memory of stanza_conv_stats_bytes(desc) bytes (0 for
+ *       a descriptor this call does not take), 16-byte aligned, contents opaque (a header, then per tile and column the sums of
+ *       (y - k) and (y - k)^2 about the tile's first row k); fewer bytes -> STANZA_EWORKSPACE.
+ *   stanza_bn_fwd_stats    = stanza_bn_fwd / stanza_bn_fwd_res (res != NULL: y = bn(x) + res before the ReLU) for float32 x
+ *       = the y of that convolution call (rows = N*Ho*Wo, C = K; C % 4 == 0), with stats as that call left it; needs no workspace.
+ *       The variance is the shifted two-sum form of stanza_bn_fwd about one row of the data, summed in a fixed order; mean and
+ *       1/std agree with stanza_bn_fwd to rounding.  A stats buffer that was not written for this [rows][C] matrix, or is
+ *       shorter than its own header says, gives NaN statistics (detected on the device: no error code). */
+size_t stanza_conv_stats_bytes(const stanza_conv_desc *desc);
+int stanza_conv_fwd_stats(const stanza_conv_desc *desc, const void *x, const void *w, const float *bias, void *y, void *stats,
+                          size_t stats_bytes, void *ws, size_t ws_bytes, void *stream);
+int stanza_bn_fwd_stats(int64_t rows, int32_t C, float eps, int32_t relu, const void *x, const void *stats, size_t stats_bytes,
+                        const float *gamma, const float *beta, const void *res, void *y, float *save_mean, float *save_istd,
+                        float *running_mean, float *running_var, float momentum, void *stream);
 int stanza_bn_bwd(int64_t rows, int32_t C, int32_t dtype, int32_t relu, const void *x, const void *dy, const float *gamma,
                   const float *beta, const float *save_mean, const float *save_istd, void *dx, float *dgamma, float *dbeta,
                   void *ws, size_t ws_bytes, void *stream);

@@ -24,7 +24,8 @@ EXPORTS = (
     "stanza_conv_bwd_weight", "stanza_pool_relu_fwd", "stanza_pool_relu_bwd", "stanza_add_relu_fwd",
     "stanza_add_relu_bwd", "stanza_gap_fwd", "stanza_gap_bwd", "stanza_cast_f32_to_bf16", "stanza_cast_bf16_to_f32",
     "stanza_cast_workspace_bytes", "stanza_cast_plan", "stanza_cast_f32_to_bf16_planned",
-    "stanza_bn_workspace_bytes", "stanza_bn_fwd", "stanza_bn_fwd_res", "stanza_bn_bwd", "stanza_avgpool_fwd", "stanza_avgpool_bwd", "stanza_copy2d",
+    "stanza_bn_workspace_bytes", "stanza_bn_fwd", "stanza_bn_fwd_res", "stanza_bn_bwd", "stanza_conv_stats_bytes", "stanza_conv_fwd_stats",
+    "stanza_bn_fwd_stats", "stanza_avgpool_fwd", "stanza_avgpool_bwd", "stanza_copy2d",
     "stanza_fc_workspace_bytes", "stanza_fc_step", "stanza_fc_grads", "stanza_dropout", "stanza_ps_workspace_bytes", "stanza_ps_plan",
     "stanza_ps_aggregate_planned", "stanza_ps_aggregate", "stanza_ps_aggregate_ordered_planned", "stanza_ps_aggregate_ordered", "stanza_ps_aggregate_static",
     "stanza_model_allreduce_rounds", "stanza_model_stanza_time", "stanza_model_stanza_throughput", "stanza_model_assign",
@@ -96,6 +97,10 @@ def load() -> C.CDLL:
     lib.stanza_bn_workspace_bytes.argtypes = [i64, i32, i32]
     lib.stanza_bn_fwd.argtypes = [i64, i32, i32, f32, i32, vp, vp, vp, vp, vp, vp, vp, vp, f32, vp, sz, vp]
     lib.stanza_bn_fwd_res.argtypes = [i64, i32, i32, f32, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, f32, vp, sz, vp]
+    lib.stanza_conv_stats_bytes.argtypes = [C.POINTER(ConvDesc)]
+    lib.stanza_conv_stats_bytes.restype = sz
+    lib.stanza_conv_fwd_stats.argtypes = [C.POINTER(ConvDesc), vp, vp, vp, vp, vp, sz, vp, sz, vp]
+    lib.stanza_bn_fwd_stats.argtypes = [i64, i32, f32, i32, vp, vp, sz, vp, vp, vp, vp, vp, vp, vp, vp, f32, vp]
     lib.stanza_bn_bwd.argtypes = [i64, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.stanza_fc_workspace_bytes.restype = sz
     lib.stanza_fc_workspace_bytes.argtypes = [C.POINTER(FcDesc)]
@@ -287,6 +292,24 @@ def stanza_bn_fwd_res(x, gamma, beta, res, y, save_mean, save_istd, ws, eps=1e-5
     _check(load().stanza_bn_fwd_res(x.numel() // c, c, dtype, eps, int(relu), _ptr(x), _ptr(gamma), _ptr(beta), _ptr(res), _ptr(y),
                                     _ptr(save_mean), _ptr(save_istd), _ptr(running_mean), _ptr(running_var), momentum, p, n, _stream()),
            "stanza_bn_fwd_res")
+
+
+def stanza_conv_stats_bytes(d: ConvDesc) -> int:
+    return int(load().stanza_conv_stats_bytes(C.byref(d)))
+
+
+def stanza_conv_fwd_stats(d: ConvDesc, x, w, bias, y, stats, ws=None):
+    p, n = _ws(ws)
+    _check(load().stanza_conv_fwd_stats(C.byref(d), _ptr(x), _ptr(w), _ptr(bias), _ptr(y), _ptr(stats), stats.numel() * stats.element_size(),
+                                        p, n, _stream()), "stanza_conv_fwd_stats")
+
+
+def stanza_bn_fwd_stats(x, stats, gamma, beta, y, save_mean, save_istd, eps=1e-5, relu=False, res=None, running_mean=None, running_var=None,
+                        momentum=0.1):
+    c = x.shape[-1]
+    _check(load().stanza_bn_fwd_stats(x.numel() // c, c, eps, int(relu), _ptr(x), _ptr(stats), stats.numel() * stats.element_size(),
+                                      _ptr(gamma), _ptr(beta), _ptr(res), _ptr(y), _ptr(save_mean), _ptr(save_istd), _ptr(running_mean),
+                                      _ptr(running_var), momentum, _stream()), "stanza_bn_fwd_stats")
 
 
 def stanza_bn_bwd(x, dy, gamma, beta, save_mean, save_istd, dx, dgamma, dbeta, ws, relu=False, dtype=F32):

@@ -225,6 +225,117 @@ __global__ __launch_bounds__(256) void bn_finalize_kernel(int C, int slabs, int 
     if (run_var) run_var[c] = (1.f - mom) * run_var[c] + mom * (rows > 1 ? var * ((float)rows / (float)(rows - 1)) : var);
 }
 
+// Mean and 1/std from the column statistics that a forward convolution left behind (StatsHeader in igemm.h): per entry and
+// column the sums of (y - k) and (y - k)^2 about the entry's own first row k.  Re-based on one shift per column, kref = k of the
+// column's first entry, an entry of n rows contributes  n d + a  and  b + d (2 a + n d)  with d = k - kref  (the expansion of
+// sum (y - kref) and sum (y - kref)^2 over its rows), so the result is the shifted two-sum variance that the statistics pass
+// computes, in a fixed order: a workgroup takes CH columns x 256 / CH lanes, a lane every (256 / CH)-th entry in entry order (four
+// entries in flight: the pass is bound by latency), then the lanes by halving.  CH = 1 for the tall matrices of the first stages
+// (a thousand and more entries per column), 16 for the short ones.  A header that does not describe this matrix or does not fit
+// the buffer gives NaN.
+template <int CH>
+__global__ __launch_bounds__(256) void bn_finalize_tiles_kernel(int C, int rows, const float *__restrict__ stats, size_t stats_floats, float eps,
+                                                                float *__restrict__ out_mean, float *__restrict__ out_istd,
+                                                                float *__restrict__ run_mean, float *__restrict__ run_var, float mom)
+{
+    constexpr int LANES = 256 / CH;
+    __shared__ float red[LANES][CH][2];
+    const StatsHeader h = *reinterpret_cast<const StatsHeader *>(stats);
+    const int cl = threadIdx.x % CH, lane = threadIdx.x / CH;
+    const int c = blockIdx.x * CH + cl;
+    bool ok = h.magic == STATS_MAGIC && h.M == rows && h.Nn == C && (h.bm == 64 || h.bm == 128 || h.bm == 256) && (h.bn == 64 || h.bn == 128);
+    int sub = 1, rows_sub = 1;
+    if (ok) {
+        sub = h.bm * h.bn / 1024;
+        rows_sub = 1024 / h.bn;
+        const long long tiles = (long long)h.tilesM * h.tilesN;
+        ok = h.tilesM == (rows + h.bm - 1) / h.bm && h.tilesN == (C + h.bn - 1) / h.bn && h.dp_tiles >= 0 && h.dp_tiles <= tiles &&
+             (unsigned long long)STATS_HEADER_FLOATS + ((unsigned long long)h.dp_tiles + (unsigned long long)(tiles - h.dp_tiles) * sub) * 3ull * h.bn <=
+                 (unsigned long long)stats_floats;
+    }
+    if (!ok) {
+        if (lane == 0 && c < C) out_mean[c] = out_istd[c] = __uint_as_float(0x7fc00000u);
+        return;
+    }
+    float s1 = 0.f, s2 = 0.f, kref = 0.f;
+    if (c < C) {
+        const int bn = h.bn, tile_n = c / bn;
+        const float *col = stats + STATS_HEADER_FLOATS + (c - tile_n * bn);
+        const size_t estride = (size_t)3 * bn;
+        // tile rows of this column whose tile is computed whole: tile_m * tilesN + tile_n < dp_tiles
+        const int mdp = h.dp_tiles > tile_n ? min(h.tilesM, (h.dp_tiles - tile_n + h.tilesN - 1) / h.tilesN) : 0;
+        auto entry_of = [&](int tile_m, int s) -> size_t {
+            const int tile = tile_m * h.tilesN + tile_n;
+            return tile < h.dp_tiles ? (size_t)tile : (size_t)h.dp_tiles + (size_t)(tile - h.dp_tiles) * sub + s;
+        };
+        kref = col[entry_of(0, 0) * estride + 2 * bn];
+        auto take = [&](int n, float a, float b, float k) {
+            const float d = k - kref, nf = (float)n;
+            s1 += fmaf(nf, d, a);
+            s2 += fmaf(d, fmaf(nf, d, 2.f * a), b);
+        };
+        for (int tm = lane; tm < mdp; tm += 4 * LANES) {
+            float a[4], b[4], k[4];
+            int n[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int tmu = tm + u * LANES;
+                n[u] = tmu < mdp ? min(h.bm, rows - tmu * h.bm) : 0;
+                if (n[u] > 0) {
+                    const float *q = col + entry_of(tmu, 0) * estride;
+                    a[u] = q[0]; b[u] = q[bn]; k[u] = q[2 * bn];
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+                if (n[u] > 0) take(n[u], a[u], b[u], k[u]);
+        }
+        const int split_entries = (h.tilesM - mdp) * sub;
+        for (int j = lane; j < split_entries; j += 4 * LANES) {
+            float a[4], b[4], k[4];
+            int n[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int ju = j + u * LANES;
+                n[u] = 0;
+                if (ju < split_entries) {
+                    const int tm = mdp + ju / sub, sidx = ju % sub;
+                    n[u] = min(rows_sub, rows - tm * h.bm - sidx * rows_sub);
+                    if (n[u] > 0) {
+                        const float *q = col + entry_of(tm, sidx) * estride;
+                        a[u] = q[0]; b[u] = q[bn]; k[u] = q[2 * bn];
+                    }
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+                if (n[u] > 0) take(n[u], a[u], b[u], k[u]);
+        }
+    }
+    red[lane][cl][0] = s1;
+    red[lane][cl][1] = s2;
+    __syncthreads();
+#pragma unroll
+    for (int half = LANES / 2; half > 0; half >>= 1) {
+        if (lane < half) {
+            red[lane][cl][0] += red[lane + half][cl][0];
+            red[lane][cl][1] += red[lane + half][cl][1];
+        }
+        __syncthreads();
+    }
+    if (lane != 0 || c >= C) return;
+    s1 = red[0][cl][0];
+    s2 = red[0][cl][1];
+    const float inv = 1.f / (float)rows;
+    const float m1 = s1 * inv;
+    const float var = fmaxf(fmaf(-m1, m1, s2 * inv), 0.f);
+    const float mu = kref + m1;
+    out_mean[c] = mu;
+    out_istd[c] = 1.f / sqrtf(var + eps);
+    if (run_mean) run_mean[c] = (1.f - mom) * run_mean[c] + mom * mu;
+    if (run_var) run_var[c] = (1.f - mom) * run_var[c] + mom * (rows > 1 ? var * ((float)rows / (float)(rows - 1)) : var);
+}
+
 // BWD = false: y = gamma * xhat + beta (+ReLU); with dyv != nullptr it holds a residual tensor that is added before the ReLU (a
 // residual join fused into the layer: y = max(bn(x) + res, 0)).  BWD = true: dx = gamma istd (g - dbeta/M - xhat dgamma/M).
 template <int VW, bool BF16, bool BWD>
@@ -399,6 +510,35 @@ extern "C" int stanza_bn_fwd_res(int64_t rows, int32_t C, int32_t dtype, float e
 {
     return bn_fwd_any(rows, C, dtype, eps, relu, x, gamma, beta, res, true, y, save_mean, save_istd, running_mean, running_var, momentum, ws,
                       ws_bytes, stream);
+}
+
+extern "C" int stanza_bn_fwd_stats(int64_t rows, int32_t C, float eps, int32_t relu, const void *x, const void *stats, size_t stats_bytes,
+                                   const float *gamma, const float *beta, const void *res, void *y, float *save_mean, float *save_istd,
+                                   float *running_mean, float *running_var, float momentum, void *stream)
+{
+    BnPlan p;
+    int rc = bn_plan(rows, C, STANZA_F32, &p);
+    if (rc) return rc;
+    if (C % 4 != 0) return STANZA_EUNSUPPORTED;
+    if (!(eps > 0.f) || !(momentum >= 0.f && momentum <= 1.f)) return STANZA_EINVAL;
+    if (!x || !stats || !gamma || !beta || !y || !save_mean || !save_istd) return STANZA_ENULL;
+    if (!aligned16(x) || !aligned16(y) || !aligned16(stats) || !aligned16(res)) return STANZA_EALIGN;
+    if (stats_bytes < STATS_HEADER_FLOATS * sizeof(float)) return STANZA_EWORKSPACE;
+    hipStream_t st = (hipStream_t)stream;
+    // lanes per column by the number of entries a column has (a tile has 64 to 256 rows)
+    const float *sf = (const float *)stats;
+    const size_t sfl = stats_bytes / sizeof(float);
+    if (rows >= 32768)
+        hipLaunchKernelGGL(bn_finalize_tiles_kernel<1>, dim3((unsigned)C), dim3(256), 0, st, C, (int)rows, sf, sfl, eps, save_mean, save_istd,
+                           running_mean, running_var, momentum);
+    else if (rows >= 4096)
+        hipLaunchKernelGGL(bn_finalize_tiles_kernel<4>, dim3((unsigned)cdiv(C, 4)), dim3(256), 0, st, C, (int)rows, sf, sfl, eps, save_mean,
+                           save_istd, running_mean, running_var, momentum);
+    else
+        hipLaunchKernelGGL(bn_finalize_tiles_kernel<16>, dim3((unsigned)cdiv(C, 16)), dim3(256), 0, st, C, (int)rows, sf, sfl, eps, save_mean,
+                           save_istd, running_mean, running_var, momentum);
+    bn_launch_apply<false>(p, STANZA_F32, st, x, res, gamma, beta, save_mean, save_istd, nullptr, nullptr, relu ? 1 : 0, y);
+    return launch_status();
 }
 
 extern "C" int stanza_bn_bwd(int64_t rows, int32_t C, int32_t dtype, int32_t relu, const void *x, const void *dy, const float *gamma,

@@ -147,6 +147,21 @@ static GemmPlan plan_gemm(int mode, int M, int Nn, int Kd, int bw_splits, bool m
     return pl;
 }
 
+// Floats of the column-statistics buffer of a forward GEMM (header + entries), for whichever of the two plans the launch takes.
+size_t igemm_stats_floats(int M, int Nn, int Kd)
+{
+    if (M <= 0 || Nn <= 0 || Kd <= 0) return 0;
+    size_t most = 0;
+    for (int may = 0; may < 2; ++may) {
+        const GemmPlan pl = plan_gemm(MODE_FWD, M, Nn, Kd, 1, may != 0);
+        const ShapeDim sd = shape_dim(pl.shape);
+        const size_t entries = (size_t)pl.dp_tiles + (size_t)pl.split_tiles * (sd.bm * sd.bn / 1024);
+        const size_t fl = entries * 3 * sd.bn;
+        if (fl > most) most = fl;
+    }
+    return STATS_HEADER_FLOATS + most;
+}
+
 size_t igemm_partial_floats(int mode, int M, int Nn, int Kd)
 {
     if (mode == MODE_BWD_WEIGHT || M <= 0 || Nn <= 0 || Kd <= 0) return 0;
@@ -158,6 +173,7 @@ size_t igemm_partial_floats(int mode, int M, int Nn, int Kd)
 // (one load per dependent add made a tile of 8 slices cost 8 memory latencies: 14 us per launch on the 1x1 layers).
 __global__ __launch_bounds__(256) void slice_fixup_kernel(const GemmParams p, int mode, int bm, int bn)
 {
+    __shared__ float4 sv[256];
     const int ti = blockIdx.x, tile = p.dp_tiles + ti;
     const int tile_n = tile % p.tilesN, tile_m = tile / p.tilesN;
     const int q4 = bn / 4;
@@ -165,33 +181,63 @@ __global__ __launch_bounds__(256) void slice_fixup_kernel(const GemmParams p, in
     const int idx = blockIdx.y * 256 + threadIdx.x;
     const int row_l = idx / q4, col_l = (idx - row_l * q4) * 4;
     const int row = tile_m * bm + row_l, col = tile_n * bn + col_l;
-    if (row >= p.M || col >= p.Nn) return;
-    const float *src = p.partial + (size_t)ti * tile_floats + (size_t)row_l * bn + col_l;
-    const size_t slice_stride = (size_t)p.split_tiles * tile_floats;
+    const bool stats = mode == MODE_FWD && (p.flags & EPI_STATS);
+    const bool valid = row < p.M && col < p.Nn;
+    if (!valid && !stats) return;
     float4 acc = zero4();
-    auto add = [&](const float4 &v) { acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w; };
-    int sl = 0;
-    for (; sl + 4 <= p.splits; sl += 4) {
-        const float4 v0 = ldg4(src + sl * slice_stride), v1 = ldg4(src + (sl + 1) * slice_stride);
-        const float4 v2 = ldg4(src + (sl + 2) * slice_stride), v3 = ldg4(src + (sl + 3) * slice_stride);
-        add(v0); add(v1); add(v2); add(v3);
-    }
-    for (; sl < p.splits; ++sl) add(ldg4(src + sl * slice_stride));
-    const size_t o = (size_t)row * p.Nn + col;
-#pragma unroll
-    for (int e = 0; e < 4; ++e) {
-        if (col + e >= p.Nn) break;
-        float v = f4at(acc, e);
-        if (mode == MODE_FWD) {
-            if (p.flags & EPI_BIAS) v += p.bias[col + e];
-            if (p.flags & EPI_RESIDUAL) v += p.res[o + e];
-            if (p.flags & EPI_RELU) v = fmaxf(v, 0.f);
-        } else {
-            if (p.flags & EPI_ACCUM) v += p.out[o + e];
-            if (p.flags & EPI_XMASK) v = p.xmask[o + e] > 0.f ? v : 0.f;
+    if (valid) {
+        const float *src = p.partial + (size_t)ti * tile_floats + (size_t)row_l * bn + col_l;
+        const size_t slice_stride = (size_t)p.split_tiles * tile_floats;
+        auto add = [&](const float4 &v) { acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w; };
+        int sl = 0;
+        for (; sl + 4 <= p.splits; sl += 4) {
+            const float4 v0 = ldg4(src + sl * slice_stride), v1 = ldg4(src + (sl + 1) * slice_stride);
+            const float4 v2 = ldg4(src + (sl + 2) * slice_stride), v3 = ldg4(src + (sl + 3) * slice_stride);
+            add(v0); add(v1); add(v2); add(v3);
         }
-        p.out[o + e] = v;
+        for (; sl < p.splits; ++sl) add(ldg4(src + sl * slice_stride));
+        const size_t o = (size_t)row * p.Nn + col;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            if (col + e >= p.Nn) break;
+            float v = f4at(acc, e);
+            if (mode == MODE_FWD) {
+                if (p.flags & EPI_BIAS) v += p.bias[col + e];
+                if (p.flags & EPI_RESIDUAL) v += p.res[o + e];
+                if (p.flags & EPI_RELU) v = fmaxf(v, 0.f);
+            } else {
+                if (p.flags & EPI_ACCUM) v += p.out[o + e];
+                if (p.flags & EPI_XMASK) v = p.xmask[o + e] > 0.f ? v : 0.f;
+            }
+            p.out[o + e] = v;
+            f4at(acc, e) = v;
+        }
     }
+    if (!stats) return;
+    // EPI_STATS (Nn % 4 == 0): the block's 1024 / bn rows are one entry; the first q4 threads walk down their 4 columns in row order
+    if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) {
+        StatsHeader h{STATS_MAGIC, p.tilesM, p.tilesN, p.dp_tiles, bm, bn, p.M, p.Nn};
+        *reinterpret_cast<StatsHeader *>(p.stats) = h;
+    }
+    sv[threadIdx.x] = acc;
+    __syncthreads();
+    const int rows_blk = 256 / q4;
+    const int r_first = tile_m * bm + (int)blockIdx.y * rows_blk;
+    const int n_rows = min(rows_blk, p.M - r_first);
+    if ((int)threadIdx.x >= q4 || n_rows <= 0 || tile_n * bn + (int)threadIdx.x * 4 >= p.Nn) return;
+    const float4 k = sv[threadIdx.x];
+    float4 a = zero4(), b = zero4();
+    for (int r = 0; r < n_rows; ++r) {
+        const float4 v = sv[r * q4 + threadIdx.x];
+        const float4 d = make_float4(v.x - k.x, v.y - k.y, v.z - k.z, v.w - k.w);
+        a.x += d.x; a.y += d.y; a.z += d.z; a.w += d.w;
+        b.x = fmaf(d.x, d.x, b.x); b.y = fmaf(d.y, d.y, b.y); b.z = fmaf(d.z, d.z, b.z); b.w = fmaf(d.w, d.w, b.w);
+    }
+    const int sub = bm * bn / 1024;
+    float *e = p.stats + STATS_HEADER_FLOATS + ((size_t)p.dp_tiles + (size_t)ti * sub + blockIdx.y) * (3 * bn) + threadIdx.x * 4;
+    *reinterpret_cast<float4 *>(e) = a;
+    *reinterpret_cast<float4 *>(e + bn) = b;
+    *reinterpret_cast<float4 *>(e + 2 * bn) = k;
 }
 
 template <int MODE, int BM, int BN, int WM, int WN>
@@ -624,7 +670,7 @@ static int launch_any(const stanza_conv_desc *d, int mode, GemmParams &p, int sp
 }
 
 static int conv_fwd_any(const stanza_conv_desc *desc, const void *x, const void *w, const float *bias, const void *res, bool want_res, void *y,
-                        void *ws, size_t ws_bytes, void *stream)
+                        void *ws, size_t ws_bytes, void *stream, float *stats = nullptr)
 {
     if (!desc) return STANZA_ENULL;
     GemmParams p{};
@@ -635,7 +681,7 @@ static int conv_fwd_any(const stanza_conv_desc *desc, const void *x, const void 
     if (!x || !w || !y || (has_bias && !bias) || (want_res && !res)) return STANZA_ENULL;
     if (!aligned16(x) || !aligned16(w) || !aligned16(y) || !aligned16(bias) || !aligned16(ws) || !aligned16(res)) return STANZA_EALIGN;
     FwdC4Params f4;
-    if (desc->dtype == STANZA_F32 && !want_res && plan_fwd_c4(p.g, &f4)) {
+    if (desc->dtype == STANZA_F32 && !want_res && !stats && plan_fwd_c4(p.g, &f4)) {
         f4.x = (const float *)x;
         f4.w = (const float *)w;
         f4.bias = has_bias ? bias : nullptr;
@@ -653,8 +699,33 @@ static int conv_fwd_any(const stanza_conv_desc *desc, const void *x, const void 
     p.M = p.g.N * p.g.Ho * p.g.Wo;
     p.Nn = p.g.K;
     p.Kd = p.g.R * p.g.S * p.g.C;
-    p.flags = (has_bias ? EPI_BIAS : 0u) | ((desc->flags & STANZA_CONV_RELU) ? EPI_RELU : 0u) | (want_res ? EPI_RESIDUAL : 0u);
+    p.flags = (has_bias ? EPI_BIAS : 0u) | ((desc->flags & STANZA_CONV_RELU) ? EPI_RELU : 0u) | (want_res ? EPI_RESIDUAL : 0u) |
+              (stats ? EPI_STATS : 0u);
+    p.stats = stats;
     return launch_any(desc, MODE_FWD, p, 1, ws, ws_bytes, (hipStream_t)stream);
+}
+
+extern "C" size_t stanza_conv_stats_bytes(const stanza_conv_desc *desc)
+{
+    ConvGeo g;
+    if (!desc || conv_geometry(desc, &g) || desc->dtype != STANZA_F32 || g.K % 4 != 0 || (desc->flags & STANZA_CONV_RELU)) return 0;
+    return round256(igemm_stats_floats(g.N * g.Ho * g.Wo, g.K, g.R * g.S * g.C) * sizeof(float));
+}
+
+extern "C" int stanza_conv_fwd_stats(const stanza_conv_desc *desc, const void *x, const void *w, const float *bias, void *y, void *stats,
+                                     size_t stats_bytes, void *ws, size_t ws_bytes, void *stream)
+{
+    if (!desc) return STANZA_ENULL;
+    const size_t need = stanza_conv_stats_bytes(desc);
+    if (need == 0) {
+        ConvGeo g;
+        const int rc = conv_geometry(desc, &g);
+        return rc ? rc : STANZA_EUNSUPPORTED;       // float32, output channels a multiple of 4, no fused ReLU
+    }
+    if (!stats) return STANZA_ENULL;
+    if (!aligned16(stats)) return STANZA_EALIGN;
+    if (stats_bytes < need) return STANZA_EWORKSPACE;
+    return conv_fwd_any(desc, x, w, bias, nullptr, false, y, ws, ws_bytes, stream, (float *)stats);
 }
 
 extern "C" int stanza_conv_fwd(const stanza_conv_desc *desc, const void *x, const void *w, const float *bias, void *y,

@@ -43,8 +43,21 @@ enum : uint32_t {
     LOAD_AMASK = 32u,  // BWD_*: dy is gated by [amask > 0] as it is read
     EPI_DBIAS = 64u,   // BWD_WEIGHT: column-tile-0 workgroups also sum dy over their reduction slice (bias gradient)
     OUT_STRIDED = 256u,     // BWD_DATA: the rows of this launch are one stride class of a strided layer (scattered dx pixels)
-    ORDER_TAP_MINOR = 128u  // FWD / BWD_DATA: visit the reduction channel-block-major, tap-minor (needs channels % BK == 0)
+    ORDER_TAP_MINOR = 128u, // FWD / BWD_DATA: visit the reduction channel-block-major, tap-minor (needs channels % BK == 0)
+    EPI_STATS = 1024u       // FWD (Nn % 4 == 0, no ReLU / residual): also write per-tile column sums of the output, see StatsHeader
 };
+
+// Column statistics of a forward output, written by the epilogue so that a normalisation layer that follows need not read the
+// tensor once more to get them.  The buffer starts with this header (8 words), then one entry of [3][bn] floats per whole tile
+// (entry index = tile index, tile = tile_m * tilesN + tile_n) and, for a tile that was cut into reduction slices, one entry per
+// 1024 / bn of its rows (entry index = dp_tiles + (tile - dp_tiles) * (bm * bn / 1024) + row block), written by the fix-up
+// kernel.  An entry holds, for each of the tile's columns: sum (y - k), sum (y - k)^2 and k, where k is the entry's first row
+// (a shift inside the data's range, so that the squares do not cancel).  The row count of an entry follows from the header.
+struct StatsHeader {
+    int magic, tilesM, tilesN, dp_tiles, bm, bn, M, Nn;
+};
+constexpr int STATS_MAGIC = 0x53544154;
+constexpr int STATS_HEADER_FLOATS = 8;
 
 struct ConvGeo {
     int N, H, W, C, K, R, S, sh, sw, ph, pw, Ho, Wo;
@@ -89,6 +102,7 @@ struct GemmParams {
     size_t dbias_stride;
     float *sgd_w, *sgd_v; // EPI_SGD
     const float *res;     // EPI_RESIDUAL (element type of the output)
+    float *stats;         // EPI_STATS: header + entries
     float lr, mom, wd;
     int M, Nn, Kd;        // GEMM extents (Kd = full reduction length)
     int tilesM, tilesN, tiles;
@@ -628,6 +642,13 @@ __global__ __launch_bounds__(NTHREADS, (BM >= 256 ? 3 : (VECA && VECB) ? 4 : 2))
         // of a 1x1 layer with 64 input channels.
         constexpr int CH4 = BN / 4, ROWS_PASS = NTHREADS / CH4;
         float *Cs = smem;
+        // EPI_STATS: a thread meets the same 4 columns in every pass, so it keeps their sums about the tile's first row
+        const bool stats = MODE == MODE_FWD && (p.flags & EPI_STATS);
+        float4 sk = zero4(), sa = zero4(), sb = zero4();
+        if (stats && blockIdx.x == 0 && t == 0) {
+            StatsHeader h{STATS_MAGIC, p.tilesM, p.tilesN, p.dp_tiles, BM, BN, p.M, p.Nn};
+            *reinterpret_cast<StatsHeader *>(p.stats) = h;
+        }
 #pragma unroll
         for (int chunk = 0; chunk < BM / CROWS; ++chunk) {
             __syncthreads();       // the stage buffers (first chunk) or the previous chunk have been read by everyone
@@ -654,6 +675,18 @@ __global__ __launch_bounds__(NTHREADS, (BM >= 256 ? 3 : (VECA && VECB) ? 4 : 2))
                         const float4 b = ldg4(p.bias + col);
                         v.x += b.x; v.y += b.y; v.z += b.z; v.w += b.w;
                     }
+                    if (stats) {
+                        if (chunk == 0 && pass == 0) {       // the tile's first row (always inside the matrix), with the bias
+                            sk = *reinterpret_cast<const float4 *>(&Cs[c4]);
+                            if (p.flags & EPI_BIAS) {
+                                const float4 b = ldg4(p.bias + col);
+                                sk.x += b.x; sk.y += b.y; sk.z += b.z; sk.w += b.w;
+                            }
+                        }
+                        const float4 d = make_float4(v.x - sk.x, v.y - sk.y, v.z - sk.z, v.w - sk.w);
+                        sa.x += d.x; sa.y += d.y; sa.z += d.z; sa.w += d.w;
+                        sb.x = fmaf(d.x, d.x, sb.x); sb.y = fmaf(d.y, d.y, sb.y); sb.z = fmaf(d.z, d.z, sb.z); sb.w = fmaf(d.w, d.w, sb.w);
+                    }
                     if (p.flags & EPI_RESIDUAL) {
                         const float4 rr = ldg4(p.res + o);
                         v.x += rr.x; v.y += rr.y; v.z += rr.z; v.w += rr.w;
@@ -667,6 +700,28 @@ __global__ __launch_bounds__(NTHREADS, (BM >= 256 ? 3 : (VECA && VECB) ? 4 : 2))
                     if (p.flags & EPI_XMASK) v = gate4(v, ldg4(p.xmask + o));
                 }
                 *reinterpret_cast<float4 *>(p.out + o) = v;
+            }
+        }
+        if (stats) {
+            // the ROWS_PASS threads of a column group, in row order; layout [ROWS_PASS][2][BN] then the shifts [BN]
+            static_assert((2 * ROWS_PASS + 1) * BN <= SMEM_FLOATS, "room for the column sums");
+            __syncthreads();
+            const int rp = t / CH4, c4 = (t % CH4) * 4;
+            *reinterpret_cast<float4 *>(&Cs[(2 * rp) * BN + c4]) = sa;
+            *reinterpret_cast<float4 *>(&Cs[(2 * rp + 1) * BN + c4]) = sb;
+            if (rp == 0) *reinterpret_cast<float4 *>(&Cs[2 * ROWS_PASS * BN + c4]) = sk;
+            __syncthreads();
+            if (t < BN && n0 + t < p.Nn) {
+                float a = 0.f, b = 0.f;
+#pragma unroll
+                for (int r = 0; r < ROWS_PASS; ++r) {
+                    a += Cs[(2 * r) * BN + t];
+                    b += Cs[(2 * r + 1) * BN + t];
+                }
+                float *e = p.stats + STATS_HEADER_FLOATS + (size_t)tile * (3 * BN);
+                e[t] = a;
+                e[BN + t] = b;
+                e[2 * BN + t] = Cs[2 * ROWS_PASS * BN + t];
             }
         }
         return;

@@ -92,6 +92,21 @@ class ConvWorker:
                 self.join_desc[i] = api.ConvDesc.from_buffer_copy(self.descs[i])
                 self.join_desc[i].flags |= api.CONV_RELU
         self.skip_fwd = {j for j, _ in self.joined.values()}
+        # A float32 convolution whose output goes to a normalisation layer leaves the column statistics of its output behind
+        # (stanza_conv_fwd_stats), and the layer reads them instead of making a pass of its own over the tensor.
+        self.stats_conv = {}                      # conv op index -> index of the normalisation layer that takes its statistics
+        stats_bytes = 0
+        if dtype == api.F32:
+            for i, op in enumerate(ops[:-1]):
+                nxt = ops[i + 1]
+                if op["op"] != "conv" or nxt["op"] != "bn" or nxt["src"] != op["dst"] or op["relu"] or i in self.joined or i in self.padded:
+                    continue
+                need = api.stanza_conv_stats_bytes(self.descs[i])
+                if need:
+                    self.stats_conv[i] = i + 1
+                    stats_bytes = max(stats_bytes, need)
+        self.stats_bn = set(self.stats_conv.values())
+        self.stats_buf = torch.empty(stats_bytes, device=self.dev, dtype=torch.uint8) if stats_bytes else None
         if dtype == api.BF16:
             assert all(op["op"] in ("conv", "pool", "avgpool", "concat", "bn", "add_relu", "gap") for op in ops)
         self.buf = {name: torch.empty(shape, device=self.dev, dtype=torch.float32 if name == "x0" else self.tdt)
@@ -175,6 +190,8 @@ class ConvWorker:
                     y32 = self.tmp32[: self.buf[op["dst"]].numel()].view(self.shapes[op["dst"]])
                     api.stanza_conv_fwd(self.descs[i], self.buf[op["src"]], w, b, y32, self.ws)
                     api.stanza_cast_f32_to_bf16(y32, self.buf[op["dst"]])
+                elif i in self.stats_conv:
+                    api.stanza_conv_fwd_stats(self.descs[i], self.buf[op["src"]], w, b, self.buf[op["dst"]], self.stats_buf, self.ws)
                 else:
                     api.stanza_conv_fwd(self.descs[i], self.buf[op["src"]], w, b, self.buf[op["dst"]], self.ws)
             elif kind == "pool":
@@ -187,6 +204,16 @@ class ConvWorker:
                     cs = self.shapes[sname][3]
                     api.stanza_copy_channels(self.buf[sname], 0, self.buf[op["dst"]], at, cs)
                     at += cs
+            elif kind == "bn" and i in self.stats_bn:
+                gamma, beta = self.params[op["name"]]
+                mean, istd = self.bn_stats[op["name"]]
+                if i in self.joined:
+                    j, other = self.joined[i]
+                    api.stanza_bn_fwd_stats(self.buf[op["src"]], self.stats_buf, gamma, beta, self.buf[self.ops[j]["dst"]], mean, istd,
+                                            op["eps"], True, res=self.buf[other])
+                else:
+                    api.stanza_bn_fwd_stats(self.buf[op["src"]], self.stats_buf, gamma, beta, self.buf[op["dst"]], mean, istd, op["eps"],
+                                            op["relu"])
             elif kind == "bn" and i in self.joined:
                 gamma, beta = self.params[op["name"]]
                 mean, istd = self.bn_stats[op["name"]]

@@ -178,6 +178,34 @@ def test_bn_errors(api):
     assert lib.stanza_bn_fwd_res(100, 8, api.F32, 1e-5, 1, p16, p16, p16, p4, p16, p16, p16, None, None, 0.1, p16, need, None) == -3
 
 
+def test_conv_statistics_errors(api):
+    lib = api.load()
+    p16, p4 = C.c_void_p(0x1000), C.c_void_p(0x1004)
+    good = api.conv_desc(2, 8, 8, 4, 8, 3, 3, 1, 1, api.F32, 0)
+    need = lib.stanza_conv_stats_bytes(C.byref(good))
+    assert need >= 32 and need % 256 == 0
+    # float32, output channels a multiple of 4, no fused ReLU: everything else has no statistics form
+    for d in (api.conv_desc(2, 8, 8, 8, 8, 3, 3, 1, 1, api.BF16, 0), api.conv_desc(2, 8, 8, 4, 6, 3, 3, 1, 1, api.F32, 0),
+              api.conv_desc(2, 8, 8, 4, 8, 3, 3, 1, 1, api.F32, api.CONV_RELU)):
+        assert lib.stanza_conv_stats_bytes(C.byref(d)) == 0
+        assert lib.stanza_conv_fwd_stats(C.byref(d), p16, p16, None, p16, p16, 1 << 20, None, 0, None) == -4
+    bad = api.conv_desc(0, 8, 8, 4, 8, 3, 3, 1, 1, api.F32, 0)
+    assert lib.stanza_conv_stats_bytes(C.byref(bad)) == 0 and lib.stanza_conv_stats_bytes(None) == 0
+    assert lib.stanza_conv_fwd_stats(C.byref(bad), p16, p16, None, p16, p16, 1 << 20, None, 0, None) == -1
+    assert lib.stanza_conv_fwd_stats(None, p16, p16, None, p16, p16, need, None, 0, None) == -2
+    assert lib.stanza_conv_fwd_stats(C.byref(good), p16, p16, None, p16, None, need, None, 0, None) == -2
+    assert lib.stanza_conv_fwd_stats(C.byref(good), p16, p16, None, p16, p4, need, None, 0, None) == -3
+    assert lib.stanza_conv_fwd_stats(C.byref(good), p16, p16, None, p16, p16, need - 1, None, 0, None) == -5
+    assert lib.stanza_conv_fwd_stats(C.byref(good), None, p16, None, p16, p16, need, None, 0, None) == -2
+    call = lambda rows=128, c=8, eps=1e-5, x=p16, st=p16, nbytes=need, res=None, mom=0.1: lib.stanza_bn_fwd_stats(
+        rows, c, eps, 0, x, st, nbytes, p16, p16, res, p16, p16, p16, None, None, mom, None)
+    assert call(rows=0) == -1 and call(eps=0.0) == -1 and call(mom=-0.1) == -1
+    assert call(c=6) == -4
+    assert call(x=None) == -2 and call(st=None) == -2
+    assert call(x=p4) == -3 and call(st=p4) == -3 and call(res=p4) == -3
+    assert call(nbytes=16) == -5
+
+
 def test_dropout_errors(api):
     lib = api.load()
     p16, p4 = C.c_void_p(0x1000), C.c_void_p(0x1004)

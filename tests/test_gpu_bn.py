@@ -255,3 +255,87 @@ def test_bn_forward_with_residual_join(api, o32, rows, c, half):
         api.stanza_bn_fwd(xd, gd, bd, y1, mean, istd, ws, 1e-5, False)
         api.stanza_add_relu_fwd(y1, rd, o)
         assert torch.equal(o, y)
+
+
+# N, H, W, C, K, R, stride, pad, bias, offset: tiles of 64 / 128 / 256 rows and 64 / 128 columns, ragged last tiles in both
+# directions, launches whose tiles are all whole / all cut into reduction slices / both, a column mean far from zero
+FUSED_CASES = [
+    (2, 19, 17, 16, 64, 3, 1, 1, False, 0.0),       # 646 rows: a few 64-row tiles, ragged
+    (4, 28, 28, 64, 256, 1, 1, 0, False, 0.0),      # short reduction: whole tiles only
+    (8, 14, 14, 64, 128, 3, 1, 1, True, 0.0),       # under two rounds of tiles: every tile sliced (with a workspace)
+    (3, 14, 14, 32, 192, 3, 1, 1, False, 0.0),      # three 64-wide column tiles
+    (2, 15, 15, 48, 160, 3, 2, 1, True, 30.0),      # ragged column tile, stride 2, channel means 30 standard deviations out
+    (16, 56, 56, 64, 64, 1, 1, 0, False, 0.0),      # 256-row tiles
+    (25, 56, 56, 32, 128, 3, 1, 1, False, 0.0),     # 613 tiles: two whole rounds and a sliced tail
+    (1, 7, 7, 512, 2048, 1, 1, 0, False, 0.0),      # 49 rows
+]
+
+
+@pytest.mark.parametrize("case", FUSED_CASES, ids=lambda c: "n%dh%dw%dc%dk%dr%ds%d" % c[:7])
+@pytest.mark.parametrize("with_ws", [False, True])
+def test_conv_statistics_feed_the_normalisation_layer(api, o32, case, with_ws):
+    """stanza_conv_fwd_stats + stanza_bn_fwd_stats against stanza_conv_fwd + the checker's normalisation of that output: the
+    convolution's output is bit for bit the plain call's, and the statistics taken from the epilogue's column sums agree with
+    the checker's pass over the tensor."""
+    from oracle import ConvGeom
+    N, H, W, C, K, R, stride, pad, bias, offset = case
+    rng = wl_mod.rng_for(21, "convbn", *case[:7])
+    x = rng.standard_normal((N, H, W, C), dtype=np.float32)
+    w = (rng.standard_normal((K, R, R, C), dtype=np.float32) * np.sqrt(2.0 / (R * R * C))).astype(np.float32)
+    b = (rng.standard_normal(K) * 0.5 + offset).astype(np.float32) if bias else None
+    gamma = rng.uniform(0.5, 1.5, K).astype(np.float32)
+    beta = (rng.standard_normal(K) * 0.5).astype(np.float32)
+    d = api.conv_desc(N, H, W, C, K, R, R, stride, pad, flags=api.CONV_BIAS if bias else 0)
+    ho, wo = api.conv_out_hw(d)
+    rows = N * ho * wo
+    need = api.stanza_conv_stats_bytes(d)
+    assert need > 0
+    ws = torch.empty(max(16, api.stanza_conv_workspace_bytes(d, 0)), dtype=torch.uint8, device="cuda:0") if with_ws else None
+    xd, wd, bd = dev(x), dev(w), None if b is None else dev(b)
+    y_plain = torch.empty((N, ho, wo, K), device="cuda:0")
+    api.stanza_conv_fwd(d, xd, wd, bd, y_plain, ws)
+    y = torch.full((N, ho, wo, K), float("nan"), device="cuda:0")
+    stats = torch.full((need,), 0xFF, dtype=torch.uint8, device="cuda:0")
+    api.stanza_conv_fwd_stats(d, xd, wd, bd, y, stats, ws)
+    assert torch.equal(y, y_plain)
+    y_conv = host(y)
+    if rows <= 4000:
+        assert rel_err(y_conv, o32.conv_fwd(ConvGeom(N, H, W, C, K, R, R, stride, pad), x, w, b)) < TOL_F32
+    for relu in (False, True):
+        rm0, rv0 = np.full(K, 0.25, np.float32), np.full(K, 1.5, np.float32)
+        rm_ref, rv_ref = rm0.copy(), rv0.copy()
+        z_ref, mean_ref, istd_ref = o32.bn_fwd(y_conv.reshape(rows, K), gamma, beta, 1e-5, relu, rm_ref, rv_ref, 0.1)
+        z = torch.full((rows, K), float("nan"), device="cuda:0")
+        mean, istd = torch.empty(K, device="cuda:0"), torch.empty(K, device="cuda:0")
+        rm, rv = dev(rm0), dev(rv0)
+        api.stanza_bn_fwd_stats(y.view(rows, K), stats, dev(gamma), dev(beta), z, mean, istd, 1e-5, relu, running_mean=rm, running_var=rv)
+        # the mean to a hundred-thousandth of the column's spread (these columns are centred near zero: an error relative to the
+        # largest mean would measure nothing)
+        assert (np.abs(host(mean) - mean_ref) * istd_ref).max() < 1e-5
+        assert rel_err(host(istd), istd_ref) < TOL_F32
+        assert rel_err(host(z), z_ref) < TOL_F32
+        assert rel_err(host(rm), rm_ref) < 1e-5 and rel_err(host(rv), rv_ref) < TOL_F32
+    # with the residual join, and bit for bit against the unfused layer given the same statistics
+    res = rng.standard_normal((rows, K), dtype=np.float32)
+    z2 = torch.empty((rows, K), device="cuda:0")
+    api.stanza_bn_fwd_stats(y.view(rows, K), stats, dev(gamma), dev(beta), z2, mean, istd, 1e-5, True, res=dev(res))
+    ref2 = o32.add_relu_fwd(o32.bn_fwd(y_conv.reshape(rows, K), gamma, beta, 1e-5, False)[0].reshape(1, 1, rows, K), res.reshape(1, 1, rows, K))
+    assert rel_err(host(z2), ref2.reshape(rows, K)) < TOL_F32
+
+
+def test_statistics_buffer_of_another_matrix_gives_nan(api):
+    """The normalisation call checks the header that the convolution left: a buffer that was never written, or that describes
+    another matrix, yields NaN statistics instead of reads outside it."""
+    rows, c = 300, 64
+    x = torch.randn((rows, c), device="cuda:0")
+    y = torch.empty_like(x)
+    mean, istd = torch.zeros(c, device="cuda:0"), torch.zeros(c, device="cuda:0")
+    g, b = torch.ones(c, device="cuda:0"), torch.zeros(c, device="cuda:0")
+    api.stanza_bn_fwd_stats(x, torch.zeros(4096, dtype=torch.uint8, device="cuda:0"), g, b, y, mean, istd)
+    assert bool(torch.isnan(mean).all()) and bool(torch.isnan(istd).all())
+    d = api.conv_desc(1, 10, 10, 16, 64, 1, 1, 1, 0)                     # a 100 x 64 matrix
+    stats = torch.zeros(api.stanza_conv_stats_bytes(d), dtype=torch.uint8, device="cuda:0")
+    api.stanza_conv_fwd_stats(d, torch.randn((1, 10, 10, 16), device="cuda:0"), torch.randn((64, 1, 1, 16), device="cuda:0"), None,
+                              torch.empty((1, 10, 10, 64), device="cuda:0"), stats)
+    api.stanza_bn_fwd_stats(x, stats, g, b, y, mean, istd)               # x has 300 rows
+    assert bool(torch.isnan(mean).all())
