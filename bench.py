@@ -152,7 +152,11 @@ def main():
     call_reads = {}  # entry point -> per call (reads y as gate, reads the x mask, reads dx to accumulate), in issue order
     pool = []        # event pairs, reused by every step: a step's times are read before the next step records into them again
 
+    recording = [True]
+
     def timed(tag, fn, *a, **kw):
+        if not recording[0]:
+            return fn(*a, **kw)
         if len(records) == len(pool):
             pool.append((torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)))
         s, e = pool[len(records)]
@@ -249,8 +253,18 @@ def main():
     n_timed_eager = args.steps
     # The host must stay ahead of the GPU here, or the time the GPU waits for the next launch lands inside an event pair (a
     # bf16 AlexNet-shaped step is 2.7 ms of GPU work behind some sixty calls, each now with two event records).  So every
-    # instrumented step starts with a bounded spin on the GPU (torch's own sleep kernel), a little longer than the host needs to
-    # issue the whole step: all of the step is queued before its first kernel starts.  The spin is outside every event pair.
+    # instrumented step is queued behind untimed work that keeps the GPU busy a little longer than the host needs to issue the
+    # whole step: all of the step is queued before its first kernel starts.  That work is the worker's own forward pass, repeated
+    # as often as needed, and not a spin kernel: behind a spin of one wavefront the driver drops the shader clock, and the forward
+    # convolutions, first in the step, then ran 8 to 26 % slower than in the timed steps (16.9 against 15.0 ms for the
+    # VGG-16-shaped stack), which understated every figure taken from this pass.  The blocker is outside every event pair.
+    def blocker(times):
+        recording[0] = False
+        for _ in range(times):
+            worker.forward()
+        recording[0] = True
+
+    blocker(1)
     t_issue = time.perf_counter()
     step_instrumented()
     t_issue = time.perf_counter() - t_issue              # host time to issue one instrumented step (the GPU may still be running)
@@ -258,15 +272,14 @@ def main():
     records.clear()
     ev_a, ev_b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     ev_a.record()
-    torch.cuda._sleep(1 << 20)
+    blocker(1)
     ev_b.record()
     torch.cuda.synchronize()
-    ticks_per_ms = (1 << 20) / max(ev_a.elapsed_time(ev_b), 1e-3)
-    spin_ticks = int(min(1.5 * t_issue * 1e3 + 0.2, 50.0) * ticks_per_ms)       # at most 50 ms
+    n_block = int(min(max(1.0, np.ceil(1.5 * t_issue * 1e3 / max(ev_a.elapsed_time(ev_b), 1e-3))), 64))
     inst_marks = []
     per = {}         # entry point -> its calls' times in issue order, step after step
     for i in range(args.steps):
-        torch.cuda._sleep(spin_ticks)
+        blocker(n_block)
         a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         a.record()
         step_instrumented()
@@ -276,7 +289,7 @@ def main():
         for tag, s, e in records:
             per.setdefault(tag, []).append(s.elapsed_time(e))
         records.clear()
-    ms_per_step_instrumented = sum(a.elapsed_time(b) for a, b in inst_marks) / args.steps      # GPU time of a step, spin excluded
+    ms_per_step_instrumented = sum(a.elapsed_time(b) for a, b in inst_marks) / args.steps      # GPU time of a step, blocker excluded
     netrun.api = api
     if plan is not None:
         plan.run = plan_run
@@ -336,6 +349,9 @@ def main():
                          "TFLOPs": lf / (lms * 1e-3) / 1e12, "share_of_conv_ms": lms / conv_ms}
     if args.detail:
         print(f"per entry point, ms/step: " + ", ".join(f"{k}={v:.3f}" for k, v in sorted(tot.items())), file=sys.stderr)
+        for k, v in sorted(per.items()):          # step by step: a pass that runs slower in some steps than in others shows here
+            c = len(v) // n_timed_eager
+            print(f"  {k} per instrumented step: " + " ".join(f"{sum(v[i * c:(i + 1) * c]):.3f}" for i in range(n_timed_eager)), file=sys.stderr)
         for r in layer_rows:
             print(f"  {r['kind']:16s} {r['layer']:8s} {r['in']:>12s} K{r['K']:<4d} R{r['R']} S{r['S']} s{r['stride']}  {r['ms']:8.3f} ms  "
                   f"{r['flops'] / r['ms'] / 1e9:7.1f} TFLOP/s  {r['flops'] / r['bytes']:7.1f} flop/B  {r['bytes'] / r['ms'] / 1e6:7.0f} GB/s",
