@@ -64,7 +64,10 @@ typedef enum { STANZA_F32 = 0, STANZA_BF16 = 1 } stanza_dtype;
 enum {
     STANZA_CONV_BIAS = 1u,   /* fwd: add bias[k];  bwd_weight: also produce dbias */
     STANZA_CONV_RELU = 2u,   /* fwd: y = max(y, 0);  bwd_*: dy is gated by [y > 0] when y is given */
-    STANZA_CONV_ACCUM = 4u   /* bwd_data: dx += result instead of dx = result (residual joins) */
+    STANZA_CONV_ACCUM = 4u,  /* bwd_data: dx += result instead of dx = result (residual joins) */
+    STANZA_CONV_NINE_TAP = 8u /* bwd_weight (and its workspace query), float32 3x3 stride-1 pad-1 layers: take the kernel that keeps all */
+                             /* nine taps in one workgroup wherever it can run, also where the library would choose the implicit GEMM */
+                             /* (small or odd-sized images); same result up to summation order.  Ignored elsewhere. */
 };
 enum { STANZA_POOL_RELU = 1u };
 

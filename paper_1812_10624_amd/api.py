@@ -16,7 +16,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.environ.get("STANZA_LIB", os.path.join(_HERE, "libstanza.so"))   # override: an alternative build of the same library
 
 F32, BF16 = 0, 1
-CONV_BIAS, CONV_RELU, CONV_ACCUM = 1, 2, 4
+CONV_BIAS, CONV_RELU, CONV_ACCUM, CONV_NINE_TAP = 1, 2, 4, 8
 POOL_RELU = 1
 
 EXPORTS = (

@@ -630,12 +630,25 @@ static void launch_wgrad_taps(const TapsParams &tp, dim3 grid, hipStream_t st)
     else launch_wgrad_taps_g<false>(tp, grid, st);
 }
 
-WgradPlan plan_wgrad(const ConvGeo &g, bool want_bias, int bk)
+// Whether the nine-tap kernel is the faster choice for a layer it can handle.  Its MFMAs run over whole stages of pixel slots and
+// whole 64x64 (k, c) tiles, so what it gains by fetching each operand once it loses where the slots or the tiles are partly empty:
+// 7x7 and 8x8 images (stages of three rows, 54-71 % filled: the implicit GEMM is 10-31 % faster there), 13x13 (75 %: 7 %
+// faster), 35 pixels wide with 96 channels (49 %: 28 %).  From 80 % on (14, 28, 56, 112, 224 pixels wide with channel counts that
+// are multiples of 64: 87-93 %) the nine-tap kernel wins.
+static bool taps_pays(const ConvGeo &g, const TapsParams &t)
+{
+    const double slots = (double)g.W / (t.strips * t.XW) * g.H / (double)(t.rowblocks * t.RP);
+    const double tiles = (double)g.K / (cdiv(g.K, TAPS_T) * TAPS_T) * g.C / (double)(t.tiles_c * TAPS_T);
+    return slots * tiles >= 0.8;
+}
+
+WgradPlan plan_wgrad(const ConvGeo &g, bool want_bias, int bk, bool force_taps)
 {
     WgradPlan pl{};
     TapsParams tp;
     TapsC4Params tp4;
-    const bool nine = bk == BK && plan_wgrad_taps(g, &tp), nine4 = bk == BK && !nine && plan_wgrad_taps_c4(g, &tp4);
+    const bool nine = bk == BK && plan_wgrad_taps(g, &tp) && (force_taps || taps_pays(g, tp));
+    const bool nine4 = bk == BK && !nine && plan_wgrad_taps_c4(g, &tp4);
     if (nine || nine4) {
         pl.taps = nine ? 1 : 2;
         pl.splits = nine ? tp.slices : tp4.slices;
@@ -676,7 +689,8 @@ extern "C" size_t stanza_conv_workspace_bytes(const stanza_conv_desc *desc, int 
 {
     ConvGeo g;
     if (!desc || which < 0 || which > 2 || conv_geometry(desc, &g) != STANZA_OK) return 0;
-    if (which == 2) return plan_wgrad(g, (desc->flags & STANZA_CONV_BIAS) != 0, desc->dtype == STANZA_BF16 ? BKH : BK).bytes;
+    if (which == 2)
+        return plan_wgrad(g, (desc->flags & STANZA_CONV_BIAS) != 0, desc->dtype == STANZA_BF16 ? BKH : BK, (desc->flags & STANZA_CONV_NINE_TAP) != 0).bytes;
     if (desc->dtype != STANZA_F32) return 0;
     const size_t fl = which == 0 ? igemm_partial_floats(MODE_FWD, g.N * g.Ho * g.Wo, g.K, g.R * g.S * g.C)
                                  : igemm_partial_floats(MODE_BWD_DATA, g.N * g.H * g.W, g.C, g.R * g.S * g.K);
@@ -834,7 +848,7 @@ extern "C" int stanza_conv_bwd_weight(const stanza_conv_desc *desc, const void *
     const bool want_bias = desc->flags & STANZA_CONV_BIAS;
     if (!x || !dy || !dw || (want_bias && !dbias)) return STANZA_ENULL;
     if (!aligned16(x) || !aligned16(dy) || !aligned16(dw) || !aligned16(y) || !aligned16(ws)) return STANZA_EALIGN;
-    const WgradPlan pl = plan_wgrad(p.g, want_bias, desc->dtype == STANZA_BF16 ? BKH : BK);
+    const WgradPlan pl = plan_wgrad(p.g, want_bias, desc->dtype == STANZA_BF16 ? BKH : BK, (desc->flags & STANZA_CONV_NINE_TAP) != 0);
     if (pl.bytes > 0 && (!ws || ws_bytes < pl.bytes)) return ws ? STANZA_EWORKSPACE : STANZA_ENULL;
     hipStream_t st = (hipStream_t)stream;
     float *partial = (float *)ws;

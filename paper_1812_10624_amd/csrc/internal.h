@@ -32,7 +32,8 @@ struct WgradPlan {
     size_t db_floats;      // splits * K bias-gradient partials when splits > 1 and a bias gradient is wanted
     size_t bytes;
 };
-WgradPlan plan_wgrad(const ConvGeo &g, bool want_bias, int bk);   // bk: reduction depth of one LDS stage
+WgradPlan plan_wgrad(const ConvGeo &g, bool want_bias, int bk, bool force_taps);   // bk: reduction depth of one LDS stage; force_taps:
+                                                                                    // the nine-tap kernel wherever it can run
 // Stage geometry and work split of the nine-tap filter-gradient kernel; false when the layer is not one it handles.
 bool plan_wgrad_taps(const ConvGeo &g, TapsParams *tp);
 bool plan_wgrad_taps_c4(const ConvGeo &g, TapsC4Params *tp);

@@ -143,10 +143,13 @@ def test_conv_backward_weight_nine_tap_kernel(api, o32, case):
     x = r.standard_normal((N, H, W, C), dtype=np.float32)
     dy = r.standard_normal((N, H, W, K), dtype=np.float32)
     yfwd = r.standard_normal(dy.shape, dtype=np.float32)
-    for gate, bias in ((False, True), (True, True), (False, False)):
+    # with CONV_NINE_TAP (on the small and odd-sized images of this list the library would otherwise take the implicit GEMM), and
+    # once as the library chooses
+    for gate, bias, force in ((False, True, True), (True, True, True), (False, False, True), (True, True, False)):
         dye = o32.relu_bwd(dy, yfwd) if gate else dy
         ref_dw, ref_db = o32.conv_bwd_weight(g, x, dye)
-        d = api.conv_desc(N, H, W, C, K, 3, 3, 1, 1, api.F32, (api.CONV_BIAS if bias else 0) | (api.CONV_RELU if gate else 0))
+        d = api.conv_desc(N, H, W, C, K, 3, 3, 1, 1, api.F32,
+                          (api.CONV_BIAS if bias else 0) | (api.CONV_RELU if gate else 0) | (api.CONV_NINE_TAP if force else 0))
         ws = torch.empty(max(16, api.stanza_conv_workspace_bytes(d, 2)), dtype=torch.uint8, device="cuda:0")
         ws.fill_(0xFF)                                               # NaN bit patterns: every partial sum that is read was written
         dw = torch.full(ref_dw.shape, float("nan"), device="cuda:0")
