@@ -178,25 +178,55 @@ def test_cast_many_tensors_in_one_launch(api):
             srcs[t].copy_(torch.from_numpy(a))
 
 
-def test_conv_bf16_full_size_sampled(api, o32):
-    """VGG-16-shaped conv2 (64 x 224 x 224 x 64 -> 64) at the real batch size, sampled outputs."""
-    N, H, W, C, K, R, S, st, pad = 64, 224, 224, 64, 64, 3, 3, 1, 1
+# the shapes on which the bf16 tile plan changes: 128x64 tiles (64 columns, long reduction), 128x128 with fewer than two tiles per
+# CU, 64x64 for a short reduction and for a launch of few tiles, 128x64 for a column count that half-fills its last 128-wide tile
+BF16_FULL_CASES = [
+    ("vgg_c2", (64, 224, 224, 64, 64, 3, 3, 1, 1)),
+    ("vgg_c11", (64, 14, 14, 512, 512, 3, 3, 1, 1)),
+    ("res_s1_1x1_64", (64, 56, 56, 64, 64, 1, 1, 1, 0)),
+    ("inc_17x17_1x1", (32, 17, 17, 768, 192, 1, 1, 1, 0)),
+    ("inc_35x35_1x1", (32, 35, 35, 288, 64, 1, 1, 1, 0)),
+    ("inc_8x8_1x1", (32, 8, 8, 1280, 320, 1, 1, 1, 0)),
+]
+
+
+def _block_samples(shape, ncols, seed, block):
+    """One index in every block x block tile of the tensor seen as a [numel / ncols, ncols] matrix, plus the corners."""
+    rows = int(np.prod(shape)) // ncols
+    r = np.random.default_rng(seed)
+    rb, cb = (rows + block - 1) // block, (ncols + block - 1) // block
+    r0 = (np.arange(rb) * block)[:, None] + np.zeros((1, cb), np.int64)
+    c0 = np.zeros((rb, 1), np.int64) + (np.arange(cb) * block)[None, :]
+    rr = r0 + r.integers(0, np.minimum(block, rows - r0))
+    cc = c0 + r.integers(0, np.minimum(block, ncols - c0))
+    flat = list((rr * ncols + cc).ravel()) + [0, rows * ncols - 1]
+    return [tuple(int(v) for v in np.unravel_index(f, shape)) for f in flat]
+
+
+@pytest.mark.parametrize("name,case", BF16_FULL_CASES, ids=[c[0] for c in BF16_FULL_CASES])
+def test_conv_bf16_full_size_sampled(api, o32, name, case):
+    """Layers at their real batch sizes, the three passes, on outputs the checker computes one by one: at least one in every
+    128 x 128 block of the output seen as the GEMM's matrix (64 x 64 for the small layers), and the corners."""
+    N, H, W, C, K, R, S, st, pad = case
     g = ConvGeom(N, H, W, C, K, R, S, st, pad)
-    r = wl_mod.rng_for(31, "bf16full")
+    r = wl_mod.rng_for(31, "bf16full", *case)
     x = wl_mod.round_bf16(r.standard_normal((N, H, W, C), dtype=np.float32))
-    w = wl_mod.round_bf16(r.standard_normal((K, R, S, C), dtype=np.float32) * np.float32((2.0 / 576) ** 0.5))
+    w = wl_mod.round_bf16(r.standard_normal((K, R, S, C), dtype=np.float32) * np.float32((2.0 / (R * S * C)) ** 0.5))
     b = r.standard_normal(K, dtype=np.float32) * np.float32(0.1)
-    dy = wl_mod.round_bf16(r.standard_normal((N, H, W, K), dtype=np.float32))
+    dy = wl_mod.round_bf16(r.standard_normal((N, g.Ho, g.Wo, K), dtype=np.float32))
     xd, wd, dyd = dev16(x), dev16(w), dev16(dy)
+    block = 128 if N * H * W > 100000 else 64
+
+    def gate(got, want, scale, tol):
+        got, want = np.asarray(got, np.float64), np.asarray(want, np.float64)
+        assert (np.abs(got - want) / np.maximum(np.abs(want), 0.05 * scale)).max() < tol, name
+
     d = api.conv_desc(N, H, W, C, K, R, S, st, pad, api.BF16, api.CONV_BIAS | api.CONV_RELU)
-    y = torch.empty((N, H, W, K), dtype=torch.bfloat16, device="cuda:0")
+    y = torch.empty((N, g.Ho, g.Wo, K), dtype=torch.bfloat16, device="cuda:0")
     api.stanza_conv_fwd(d, xd, wd, dev32(b), y)
     yh = host16(y)
-    rs = np.random.default_rng(1)
-    idx = [tuple(int(rs.integers(0, s)) for s in yh.shape) for _ in range(40)] + [(0, 0, 0, 0), (63, 223, 223, 63)]
-    want = np.array([o32.conv_fwd_at(g, x, w, b, True, *i) for i in idx])
-    got = np.array([yh[i] for i in idx], np.float64)
-    assert (np.abs(got - want) / np.maximum(np.abs(want), 0.05 * np.abs(yh).max())).max() < TOL_BF16
+    idx = _block_samples(yh.shape, K, 1, block)
+    gate([yh[i] for i in idx], [o32.conv_fwd_at(g, x, w, b, True, *i) for i in idx], np.abs(yh).max(), TOL_BF16)
     del y, yh
     d0 = api.conv_desc(N, H, W, C, K, R, S, st, pad, api.BF16, api.CONV_BIAS)
     ws = torch.empty(max(16, api.stanza_conv_workspace_bytes(d0, 2)), dtype=torch.uint8, device="cuda:0")
@@ -204,17 +234,14 @@ def test_conv_bf16_full_size_sampled(api, o32):
     db = torch.empty((K,), device="cuda:0")
     api.stanza_conv_bwd_weight(d0, xd, dyd, None, dw, db, ws)
     dwh = host(dw)
-    idx = [tuple(int(rs.integers(0, s)) for s in dwh.shape) for _ in range(16)]
-    want = np.array([o32.conv_bwd_weight_at(g, x, dy, *i) for i in idx])
-    got = np.array([dwh[i] for i in idx], np.float64)
-    assert (np.abs(got - want) / np.maximum(np.abs(want), 0.05 * np.abs(dwh).max())).max() < 1e-3
+    idx = _block_samples(dwh.shape, R * S * C, 2, 64)[:400]
+    gate([dwh[i] for i in idx], [o32.conv_bwd_weight_at(g, x, dy, *i) for i in idx], np.abs(dwh).max(), 1e-3)
+    gate(host(db), [o32.colsum_at(dy.reshape(-1, K), j) for j in range(K)], np.abs(host(db)).max(), 1e-3)
     dx = torch.empty((N, H, W, C), dtype=torch.bfloat16, device="cuda:0")
     api.stanza_conv_bwd_data(api.conv_desc(N, H, W, C, K, R, S, st, pad, api.BF16, 0), dyd, None, wd, None, dx)
     dxh = host16(dx)
-    idx = [tuple(int(rs.integers(0, s)) for s in dxh.shape) for _ in range(40)]
-    want = np.array([o32.conv_bwd_data_at(g, dy, w, *i) for i in idx])
-    got = np.array([dxh[i] for i in idx], np.float64)
-    assert (np.abs(got - want) / np.maximum(np.abs(want), 0.05 * np.abs(dxh).max())).max() < TOL_BF16
+    idx = _block_samples(dxh.shape, C, 3, block)
+    gate([dxh[i] for i in idx], [o32.conv_bwd_data_at(g, dy, w, *i) for i in idx], np.abs(dxh).max(), TOL_BF16)
 
 
 def test_conv_worker_bf16_stack(api, o32):

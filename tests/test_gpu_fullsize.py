@@ -71,9 +71,17 @@ FULL_CASES = [
     ("alex_c1", (128, 224, 224, 3, 96, 11, 11, 4, 2)),
     ("alex_c2", (128, 27, 27, 96, 256, 5, 5, 1, 2)),
     ("res_stem", (64, 224, 224, 3, 64, 7, 7, 2, 3)),
-    ("res_s2_3x3", (64, 56, 56, 128, 128, 3, 3, 2, 1)),
+    ("res_s2_3x3_stride2", (64, 56, 56, 128, 128, 3, 3, 2, 1)),
     ("res_s2_proj", (64, 56, 56, 256, 512, 1, 1, 2, 0)),
     ("res_1x1", (64, 56, 56, 256, 64, 1, 1, 1, 0)),
+    # shapes whose tile plan differs from the large layers': short reductions (64x64 and 64x128 tiles), fewer than two 128x128
+    # tiles per CU with a medium reduction (smaller tiles, only the last round cut into slices), a 7x7 3x3 layer (its filter
+    # gradient goes to the implicit GEMM, not the nine-tap kernel)
+    ("res_s1_1x1_64", (64, 56, 56, 64, 64, 1, 1, 1, 0)),
+    ("res_s1_1x1_256", (64, 56, 56, 64, 256, 1, 1, 1, 0)),
+    ("res_s2_3x3", (64, 28, 28, 128, 128, 3, 3, 1, 1)),
+    ("res_s4_1x1", (64, 7, 7, 512, 2048, 1, 1, 1, 0)),
+    ("res_s4_3x3", (64, 7, 7, 512, 512, 3, 3, 1, 1)),
 ]
 
 
