@@ -386,6 +386,9 @@ def main():
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step,
         "ms_per_step_instrumented": ms_per_step_instrumented,      # the second pass, with an event pair around every call
+        "per_entry_point_ms": {k: round(v, 4) for k, v in sorted(tot.items())},      # of that pass, per step
+        # untimed forward passes that the instrumented pass queues ahead of its steps (they are in a profiler's trace of this run)
+        "blocker_forward_passes": 2 + n_block * args.steps,
         "step_ms_median": step_ms[len(step_ms) // 2], "step_ms_min": step_ms[0], "step_ms_max": step_ms[-1],
         "device": {"name": props.name, "compute_units": props.multi_processor_count,
                    "sclk_mhz_during_timed_steps": sclk.summary(),

@@ -70,8 +70,9 @@ static TileShape pick_shape(int mode, int M, int Nn, int Kd, int splits, bool ca
         // Fewer than two 128x128 tiles per CU, and a reduction too short for cutting every tile into slices to pay (the slices'
         // raw sums are written and read back): take the largest tile of which there are at least two per CU, so that only the
         // tiles of its last, partly filled round are cut.  Measured 11-17 % faster on the 28x28x128, 14x14x1024->512 and
-        // 7x7x512->2048 layers of the residual stacks; from Kd = 2304 on the 128x128 tiles with every tile cut win.
-        if (Nn > 64 && Kd <= 1536 && (int64_t)cdiv(M, 128) * cdiv(Nn, 128) < want) {
+        // 7x7x512->2048 layers of the residual stacks; from Kd = 2304 on the 128x128 tiles with every tile cut win, and so they do
+        // on the 512-row GEMMs of the FC worker (its last layer's data gradient: 60 against 50 us).
+        if (M >= 1024 && Nn > 64 && Kd <= 1536 && (int64_t)cdiv(M, 128) * cdiv(Nn, 128) < want) {
             if (Nn % 128 == 0 && (int64_t)cdiv(M, 64) * (Nn / 128) >= want) return T64x128;
             if ((int64_t)cdiv(M, 128) * cdiv(Nn, 64) >= want) return T128x64;
             if ((int64_t)cdiv(M, 64) * cdiv(Nn, 64) >= want) return T64x64;
