@@ -37,7 +37,17 @@ __device__ __forceinline__ uint16_t f32_to_bf16(float f)
     u += 0x7fffu + ((u >> 16) & 1u);
     return (uint16_t)(u >> 16);
 }
-__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) { return (uint32_t)f32_to_bf16(lo) | ((uint32_t)f32_to_bf16(hi) << 16); }
+// Two floats rounded to nearest even and packed, through the hardware conversion (v_cvt_pk_bf16_f32): the same bits as
+// f32_to_bf16 for every finite input, in one instruction instead of eight and without the branch around the NaN case (the
+// epilogue converts 64 values per lane: written out it was 1,100 vector and 600 scalar instructions per tile and wavefront, as
+// many as 18 stages of the main loop).
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi)
+{
+    typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+    typedef float f32x2_t __attribute__((ext_vector_type(2)));
+    const f32x2_t v = {lo, hi};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_t));
+}
 __device__ __forceinline__ bool bf16_pos(uint16_t h) { return h != 0 && !(h & 0x8000u); }   // h > 0 (finite inputs)
 __device__ __forceinline__ uint16_t h8at(const uint4 &v, int e) { return reinterpret_cast<const uint16_t *>(&v)[e]; }
 // keep element e of v where the matching element of m is > 0
@@ -174,13 +184,15 @@ __global__ __launch_bounds__(NTHREADS, 2) void igemm_bf16_kernel(const GemmParam
     if (FAST) {
 #pragma unroll
         for (int i = 0; i < AV; ++i) {
+            // bit (ar * tapS + as) = row tap ar inside the image AND column tap as inside it: the column bits once, then one
+            // shifted copy per valid row tap (R + S steps instead of R * S)
+            uint32_t cb = 0;
+            for (int as = 0; as < tapS; ++as)
+                cb |= (uint32_t)(MODE == MODE_FWD ? (unsigned)(a_wb[i] + as) < (unsigned)g.W : (unsigned)(a_wb[i] - as) < (unsigned)g.Wo) << as;
             uint32_t mk = 0;
-            for (int tap = 0, ar = 0, as = 0; tap < tapRS; ++tap) {
-                const bool ok = MODE == MODE_FWD
-                                    ? ((unsigned)(a_hb[i] + ar) < (unsigned)g.H && (unsigned)(a_wb[i] + as) < (unsigned)g.W)
-                                    : ((unsigned)(a_hb[i] - ar) < (unsigned)g.Ho && (unsigned)(a_wb[i] - as) < (unsigned)g.Wo);
-                mk |= (uint32_t)ok << tap;
-                if (++as == tapS) { as = 0; ++ar; }
+            for (int ar = 0, sh = 0; sh < tapRS; ++ar, sh += tapS) {
+                const bool ok = MODE == MODE_FWD ? (unsigned)(a_hb[i] + ar) < (unsigned)g.H : (unsigned)(a_hb[i] - ar) < (unsigned)g.Ho;
+                mk |= ok ? cb << sh : 0u;
             }
             a_mask[i] = mk;
         }
