@@ -603,7 +603,7 @@ bool plan_fwd_c4(const ConvGeo &g, FwdC4Params *fp)
     f.rowblocks = cdiv(g.H, F4_ROWS);
     f.total_stages = g.N * f.strips * f.rowblocks;
     f.tiles = cdiv(g.K, TAPS_T);
-    int slices = max(1, 8 * CUS / f.tiles);          // two rounds of four resident workgroups per CU
+    int slices = max(1, 4 * CUS / f.tiles);          // one round of four resident workgroups per CU (two rounds: 2 % slower)
     slices = max(1, min(slices, f.total_stages / 4));
     f.stages_per_item = cdiv(f.total_stages, slices);
     f.slices = cdiv(f.total_stages, f.stages_per_item);

@@ -649,6 +649,9 @@ __global__ __launch_bounds__(NTHREADS, (BM >= 256 ? 3 : (VECA && VECB) ? 4 : 2))
             StatsHeader h{STATS_MAGIC, p.tilesM, p.tilesN, p.dp_tiles, BM, BN, p.M, p.Nn};
             *reinterpret_cast<StatsHeader *>(p.stats) = h;
         }
+        // a thread meets the same 4 columns in every pass: their bias is loaded once, before any store
+        float4 bias4 = zero4();
+        if (MODE == MODE_FWD && (p.flags & EPI_BIAS) && n0 + (t % CH4) * 4 < p.Nn) bias4 = ldg4(p.bias + n0 + (t % CH4) * 4);
 #pragma unroll
         for (int chunk = 0; chunk < BM / CROWS; ++chunk) {
             __syncthreads();       // the stage buffers (first chunk) or the previous chunk have been read by everyone
@@ -663,43 +666,58 @@ __global__ __launch_bounds__(NTHREADS, (BM >= 256 ? 3 : (VECA && VECB) ? 4 : 2))
                         Cs[(tile_row % CROWS + 8 * (r >> 2) + 4 * lk + (r & 3)) * BN + wave_n * WTN + wcol(j, lrow)] = acc[i][j][r];
             }
             __syncthreads();
+            // What the epilogue reads from global memory (residual, previous gradient, mask) is folded into the staged tile
+            // first, every thread on the elements it will store, and the stores follow in a loop of their own.  Loads and stores
+            // share one counter and return out of order with respect to each other, so a load that is waited for while stores
+            // are in flight waits for every one of those stores: with load and store in the same pass, each pass cost a full
+            // round trip to memory (32 per 128x128 tile).
+            constexpr int PASSES = CROWS / ROWS_PASS;
+            const int c4 = (t % CH4) * 4, col = n0 + c4;
+            const bool want_a = MODE == MODE_FWD ? (p.flags & EPI_RESIDUAL) != 0 : (p.flags & EPI_ACCUM) != 0;
+            const bool want_m = MODE == MODE_BWD_DATA && (p.flags & EPI_XMASK);
+            // (one sweep per operand, its loads issued together: 4 * PASSES registers, which the staged accumulators left free)
+            auto fold = [&](const float *src, auto op) {
+                float4 g4[PASSES];
 #pragma unroll
-            for (int pass = 0; pass < CROWS / ROWS_PASS; ++pass) {
-                const int row_l = pass * ROWS_PASS + t / CH4, c4 = (t % CH4) * 4;
-                const int row = m0 + chunk * CROWS + row_l, col = n0 + c4;
+                for (int pass = 0; pass < PASSES; ++pass) {
+                    const int row = m0 + chunk * CROWS + pass * ROWS_PASS + t / CH4;
+                    g4[pass] = (row < p.M && col < p.Nn) ? ldg4(src + out_index(row, col)) : zero4();
+                }
+#pragma unroll
+                for (int pass = 0; pass < PASSES; ++pass) {
+                    const int row_l = pass * ROWS_PASS + t / CH4;
+                    float4 *c = reinterpret_cast<float4 *>(&Cs[row_l * BN + c4]);
+                    *c = op(*c, g4[pass]);      // (rows past the end: staged, never stored)
+                }
+            };
+            if (want_a) {
+                if (MODE == MODE_FWD)        // (bias before the residual)
+                    fold(p.res, [&](float4 v, float4 a) { return make_float4(v.x + bias4.x + a.x, v.y + bias4.y + a.y, v.z + bias4.z + a.z, v.w + bias4.w + a.w); });
+                else
+                    fold(p.out, [&](float4 v, float4 a) { return make_float4(v.x + a.x, v.y + a.y, v.z + a.z, v.w + a.w); });
+            }
+            if (want_m) fold(p.xmask, [&](float4 v, float4 m) { return gate4(v, m); });
+            const float4 bias_now = (MODE == MODE_FWD && !want_a) ? bias4 : zero4();
+#pragma unroll
+            for (int pass = 0; pass < PASSES; ++pass) {
+                const int row_l = pass * ROWS_PASS + t / CH4;
+                const int row = m0 + chunk * CROWS + row_l;
                 if (row >= p.M || col >= p.Nn) continue;
                 float4 v = *reinterpret_cast<const float4 *>(&Cs[row_l * BN + c4]);
-                const size_t o = out_index(row, col);
                 if (MODE == MODE_FWD) {
-                    if (p.flags & EPI_BIAS) {
-                        const float4 b = ldg4(p.bias + col);
-                        v.x += b.x; v.y += b.y; v.z += b.z; v.w += b.w;
-                    }
-                    if (stats) {
+                    v.x += bias_now.x; v.y += bias_now.y; v.z += bias_now.z; v.w += bias_now.w;
+                    if (stats) {       // (never together with a residual: conv_fwd_any)
                         if (chunk == 0 && pass == 0) {       // the tile's first row (always inside the matrix), with the bias
                             sk = *reinterpret_cast<const float4 *>(&Cs[c4]);
-                            if (p.flags & EPI_BIAS) {
-                                const float4 b = ldg4(p.bias + col);
-                                sk.x += b.x; sk.y += b.y; sk.z += b.z; sk.w += b.w;
-                            }
+                            sk.x += bias4.x; sk.y += bias4.y; sk.z += bias4.z; sk.w += bias4.w;
                         }
                         const float4 d = make_float4(v.x - sk.x, v.y - sk.y, v.z - sk.z, v.w - sk.w);
                         sa.x += d.x; sa.y += d.y; sa.z += d.z; sa.w += d.w;
                         sb.x = fmaf(d.x, d.x, sb.x); sb.y = fmaf(d.y, d.y, sb.y); sb.z = fmaf(d.z, d.z, sb.z); sb.w = fmaf(d.w, d.w, sb.w);
                     }
-                    if (p.flags & EPI_RESIDUAL) {
-                        const float4 rr = ldg4(p.res + o);
-                        v.x += rr.x; v.y += rr.y; v.z += rr.z; v.w += rr.w;
-                    }
                     if (p.flags & EPI_RELU) v = make_float4(fmaxf(v.x, 0.f), fmaxf(v.y, 0.f), fmaxf(v.z, 0.f), fmaxf(v.w, 0.f));
-                } else {
-                    if (p.flags & EPI_ACCUM) {
-                        const float4 old = ldg4(p.out + o);
-                        v.x += old.x; v.y += old.y; v.z += old.z; v.w += old.w;
-                    }
-                    if (p.flags & EPI_XMASK) v = gate4(v, ldg4(p.xmask + o));
                 }
-                *reinterpret_cast<float4 *>(p.out + o) = v;
+                *reinterpret_cast<float4 *>(p.out + out_index(row, col)) = v;
             }
         }
         if (stats) {
@@ -732,6 +750,39 @@ __global__ __launch_bounds__(NTHREADS, (BM >= 256 ? 3 : (VECA && VECB) ? 4 : 2))
         const int col = n0 + wave_n * WTN + 2 * lrow;
         if ((p.Nn & 1) == 0) {
             if (col >= p.Nn) return;
+            if (p.flags & EPI_SGD) {
+                // fused momentum update: the parameters and velocities of SG rows are loaded before the first of their stores
+                // (a load waited for with stores in flight waits for those stores as well: row by row, every row cost a round
+                // trip to memory, 32 per tile)
+                constexpr int SG = 8;
+#pragma unroll
+                for (int i = 0; i < TM; ++i) {
+#pragma unroll
+                    for (int r0 = 0; r0 < 16; r0 += SG) {
+                        float2 w[SG], vel[SG];
+#pragma unroll
+                        for (int q = 0; q < SG; ++q) {
+                            const int r = r0 + q, row = m0 + wave_m * WTM + wrow(i, 8 * (r >> 2) + 4 * lk + (r & 3));
+                            const size_t o = (size_t)min(row, p.M - 1) * p.Nn + col;
+                            w[q] = *reinterpret_cast<const float2 *>(p.sgd_w + o);
+                            vel[q] = *reinterpret_cast<const float2 *>(p.sgd_v + o);
+                        }
+#pragma unroll
+                        for (int q = 0; q < SG; ++q) {
+                            const int r = r0 + q, row = m0 + wave_m * WTM + wrow(i, 8 * (r >> 2) + 4 * lk + (r & 3));
+                            if (row >= p.M) continue;
+                            const size_t o = (size_t)row * p.Nn + col;
+                            const float2 v = make_float2(acc[i][0][r], acc[i][1][r]);
+                            float2 ve = vel[q];
+                            ve.x = p.mom * ve.x + (v.x + p.wd * w[q].x);
+                            ve.y = p.mom * ve.y + (v.y + p.wd * w[q].y);
+                            *reinterpret_cast<float2 *>(p.sgd_v + o) = ve;
+                            *reinterpret_cast<float2 *>(p.sgd_w + o) = make_float2(w[q].x - p.lr * ve.x, w[q].y - p.lr * ve.y);
+                        }
+                    }
+                }
+                return;
+            }
 #pragma unroll
             for (int i = 0; i < TM; ++i) {
 #pragma unroll
@@ -739,17 +790,7 @@ __global__ __launch_bounds__(NTHREADS, (BM >= 256 ? 3 : (VECA && VECB) ? 4 : 2))
                     const int row = m0 + wave_m * WTM + wrow(i, 8 * (r >> 2) + 4 * lk + (r & 3));
                     if (row >= p.M) continue;
                     const size_t o = (size_t)row * p.Nn + col;
-                    float2 v = make_float2(acc[i][0][r], acc[i][1][r]);
-                    if (p.flags & EPI_SGD) {
-                        const float2 w = *reinterpret_cast<const float2 *>(p.sgd_w + o);
-                        float2 vel = *reinterpret_cast<const float2 *>(p.sgd_v + o);
-                        vel.x = p.mom * vel.x + (v.x + p.wd * w.x);
-                        vel.y = p.mom * vel.y + (v.y + p.wd * w.y);
-                        *reinterpret_cast<float2 *>(p.sgd_v + o) = vel;
-                        *reinterpret_cast<float2 *>(p.sgd_w + o) = make_float2(w.x - p.lr * vel.x, w.y - p.lr * vel.y);
-                    } else {
-                        *reinterpret_cast<float2 *>(p.out + split_off + o) = v;
-                    }
+                    *reinterpret_cast<float2 *>(p.out + split_off + o) = make_float2(acc[i][0][r], acc[i][1][r]);
                 }
             }
             return;

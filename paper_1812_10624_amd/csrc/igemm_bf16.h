@@ -585,17 +585,32 @@ __global__ __launch_bounds__(NTHREADS, 2) void igemm_bf16_kernel(const GemmParam
             }
         }
         __syncthreads();
+        // The masks of up to eight passes are loaded before the first of their stores: loads and stores share one counter and
+        // return out of order with respect to each other, so a load waited for with stores in flight waits for those stores too
+        // (pass by pass, every pass cost a round trip to memory).  The accumulators are dead by now: the registers are there.
+        constexpr int PASSES = CROWS / ROWS_PER_PASS, PG = PASSES < 8 ? PASSES : 8;
+        static_assert(PASSES % PG == 0, "pass groups");
+        const int c8 = (t % CH8) * 8, col = n0 + c8;
+        const bool want_m = MODE == MODE_BWD_DATA && (p.flags & EPI_XMASK);
 #pragma unroll
-        for (int pass = 0; pass < CROWS / ROWS_PER_PASS; ++pass) {
-            const int row_l = pass * ROWS_PER_PASS + t / CH8, c8 = (t % CH8) * 8;
-            const int row = m0 + half * CROWS + row_l, col = n0 + c8;
-            if (row >= p.M || col >= p.Nn) continue;
-            uint4 v = *reinterpret_cast<const uint4 *>(&smem[row_l * LDC + c8]);
-            const size_t o = out_index(row, col);
-            if (MODE == MODE_BWD_DATA) {
-                if (p.flags & EPI_XMASK) v = gate8(v, *reinterpret_cast<const uint4 *>(xm + o));
+        for (int grp = 0; grp < PASSES / PG; ++grp) {
+            uint4 pre_m[PG];
+            if (want_m) {
+#pragma unroll
+                for (int q = 0; q < PG; ++q) {
+                    const int row = m0 + half * CROWS + (grp * PG + q) * ROWS_PER_PASS + t / CH8;
+                    pre_m[q] = (row < p.M && col < p.Nn) ? *reinterpret_cast<const uint4 *>(xm + out_index(row, col)) : make_uint4(0u, 0u, 0u, 0u);
+                }
             }
-            *reinterpret_cast<uint4 *>(outh + o) = v;
+#pragma unroll
+            for (int q = 0; q < PG; ++q) {
+                const int row_l = (grp * PG + q) * ROWS_PER_PASS + t / CH8;
+                const int row = m0 + half * CROWS + row_l;
+                if (row >= p.M || col >= p.Nn) continue;
+                uint4 v = *reinterpret_cast<const uint4 *>(&smem[row_l * LDC + c8]);
+                if (want_m) v = gate8(v, pre_m[q]);
+                *reinterpret_cast<uint4 *>(outh + out_index(row, col)) = v;
+            }
         }
     }
 }

@@ -542,6 +542,11 @@ __global__ __launch_bounds__(256, 4) void fwd_c4_kernel(const FwdC4Params p)
     int buf = 0;
     fetch(n, rb, strip, sid < send);
     stash(0);
+    // Every load issued so far (the filter registers among them) is waited for here, once.  Loads and stores share one counter
+    // and return out of order with respect to each other, so a load that is waited for while stores are in flight waits for
+    // every one of those stores: left pending into the loop, the first use of a filter register waited in every iteration for
+    // all stores of the previous stage.
+    __builtin_amdgcn_s_waitcnt(0);
     __syncthreads();
     for (; sid < send; ++sid) {
         int rb2 = rb + 1, strip2 = strip, n2 = n;
@@ -551,6 +556,7 @@ __global__ __launch_bounds__(256, 4) void fwd_c4_kernel(const FwdC4Params p)
         }
         const bool live2 = sid + 1 < send;
         fetch(n2, rb2, strip2, live2);
+        __builtin_amdgcn_sched_barrier(0);      // (the load is issued here, a stage of MFMAs ahead of its use)
         const float *win = xW + buf * F4_WIN + a_off;
         f32x4 acc[2][4];
 #pragma unroll
@@ -565,6 +571,10 @@ __global__ __launch_bounds__(256, 4) void fwd_c4_kernel(const FwdC4Params p)
 #pragma unroll
                 for (int kt = 0; kt < 4; ++kt) acc[g][kt] = __builtin_amdgcn_mfma_f32_16x16x4f32(a, b[kt][tap], acc[g][kt], 0, 0, 0);
             }
+        // The next window goes to LDS BEFORE this stage's stores are issued (same reason as above): the stores in flight at this
+        // wait are those of the previous stage, a whole stage of MFMAs old.  The other window buffer is free: its last readers
+        // passed the barrier that ended the previous stage.
+        if (live2) stash(buf ^ 1);
         // accumulator register r of lane l: pixel 4*(l/16) + r, channel 16*kt + l%16.  Through this wavefront's LDS patch the
         // tile turns into whole pixel rows: lane l then holds 4 consecutive channels (4*(l%16) ..) of pixel l/16 + 4*j.
         const int prow = rb * F4_ROWS + wave;
@@ -592,7 +602,6 @@ __global__ __launch_bounds__(256, 4) void fwd_c4_kernel(const FwdC4Params p)
             __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
         }
         buf ^= 1;
-        if (live2) stash(buf);
         __syncthreads();
         rb = rb2; strip = strip2; n = n2;
     }
