@@ -335,6 +335,63 @@ int launch_igemm(int mode, GemmParams &p, int bw_splits, float *partial, size_t 
     return STANZA_EINVAL;
 }
 
+// The stride classes of a strided layer's data gradient (n <= MAX_CLASSES parameter sets that differ in their class geometry,
+// row count and reduction length) as ONE launch: one tile shape for all of them, chosen for their tiles together; no tile is cut
+// into reduction slices (the classes together fill the CUs, and their rows are scattered pixels).
+template <int BM, int BN, int WM, int WN>
+static int launch_classes_tile(GemmClasses &P, int n, bool vec, hipStream_t st)
+{
+    int most = 0;
+    for (int i = 0; i < n; ++i) {
+        GemmParams &q = P.q[i];
+        q.tilesM = cdiv(q.M, BM);
+        q.tilesN = cdiv(q.Nn, BN);
+        q.tiles = q.dp_tiles = q.tilesM * q.tilesN;
+        q.split_tiles = 0;
+        q.splits = 1;
+        q.chunks_per_split = cdiv(q.Kd, BK);
+        most = max(most, q.tiles);
+    }
+    const dim3 grid((unsigned)(cdiv(most, 8) * 8), (unsigned)n);
+    const bool fast = vec && P.q[0].g.K % BK == 0;
+    if (fast) hipLaunchKernelGGL((igemm_classes_kernel<BM, BN, WM, WN, true, true, true>), grid, dim3(NTHREADS), 0, st, P);
+    else if (vec) hipLaunchKernelGGL((igemm_classes_kernel<BM, BN, WM, WN, true, true, false>), grid, dim3(NTHREADS), 0, st, P);
+    else hipLaunchKernelGGL((igemm_classes_kernel<BM, BN, WM, WN, false, false, false>), grid, dim3(NTHREADS), 0, st, P);
+    return launch_status();
+}
+
+static int launch_igemm_classes(GemmClasses &P, int n, hipStream_t st)
+{
+    if (n < 1 || n > MAX_CLASSES) return STANZA_EINVAL;
+    const ConvGeo &g = P.q[0].g;
+    const int64_t yb = (int64_t)g.N * g.Ho * g.Wo * g.K * 4, wb = (int64_t)g.K * g.R * g.S * g.C * 4, lim = int64_t(1) << 31;
+    int64_t rows = 0;
+    int kd_max = 0;
+    for (int i = 0; i < n; ++i) {
+        GemmParams &q = P.q[i];
+        if (q.M <= 0 || q.Nn <= 0 || q.Kd < 0) return STANZA_EINVAL;
+        q.partial = nullptr;
+        q.fd_c = make_fastdiv(g.C);
+        q.fd_k = make_fastdiv(g.K);
+        q.fd_howo = make_fastdiv(g.Ho * g.Wo);
+        q.fd_wo = make_fastdiv(g.Wo);
+        const int rc = prepare_stride_class(q, BK);
+        if (rc) return rc;
+        q.a_bytes = (uint32_t)(yb < lim ? yb : 0);
+        q.b_bytes = (uint32_t)(wb < lim ? wb : 0);
+        rows += q.M;
+        kd_max = max(kd_max, q.Kd);
+    }
+    const bool vec = g.K % 4 == 0 && g.C % 4 == 0 && yb < lim && wb < lim;
+    switch (pick_shape(MODE_BWD_DATA, (int)(rows < INT32_MAX ? rows : INT32_MAX), P.q[0].Nn, kd_max, 1, false)) {
+    case T256x64: return launch_classes_tile<256, 64, 4, 1>(P, n, vec, st);
+    case T128x64: return launch_classes_tile<128, 64, 2, 2>(P, n, vec, st);
+    case T64x64: return launch_classes_tile<64, 64, 2, 2>(P, n, vec, st);
+    case T64x128: return launch_classes_tile<64, 128, 2, 2>(P, n, vec, st);
+    default: return launch_classes_tile<128, 128, 2, 2>(P, n, vec, st);
+    }
+}
+
 // ------------------------------------------------------------------ bf16-in path
 template <int MODE, int BM, int BN, int WM, int WN>
 static int launch_tile_bf16(GemmParams &p, int splits, hipStream_t st)
@@ -382,6 +439,70 @@ static int launch_mode_bf16(GemmParams &p, int splits, hipStream_t st)
     // third fewer zeros (17-25 % faster on those layers of the Inception stack)
     if (MODE != MODE_BWD_WEIGHT && p.Nn % 128 != 0 && p.Nn % 128 <= 64) return launch_tile_bf16<MODE, 128, 64, 2, 2>(p, splits, st);
     return launch_tile_bf16<MODE, 128, 128, 2, 2>(p, splits, st);
+}
+
+// bf16 form of launch_igemm_classes: the tile shape by the rules of launch_mode_bf16, applied to the classes' tiles together
+template <int BM, int BN, int WM, int WN>
+static int launch_classes_tile_bf16(GemmClasses &P, int n, hipStream_t st)
+{
+    int most = 0;
+    for (int i = 0; i < n; ++i) {
+        GemmParams &q = P.q[i];
+        q.tilesM = cdiv(q.M, BM);
+        q.tilesN = cdiv(q.Nn, BN);
+        q.tiles = q.tilesM * q.tilesN;
+        q.splits = 1;
+        most = max(most, q.tiles);
+    }
+    const dim3 grid((unsigned)(cdiv(most, 8) * 8), (unsigned)n);
+    const ConvGeo &g = P.q[0].g;
+    const bool fast = g.R * g.S <= 32 && g.K % BKH == 0;
+    const bool gated = P.q[0].flags & LOAD_AMASK;
+    if (fast && !gated) hipLaunchKernelGGL((igemm_bf16_classes_kernel<BM, BN, WM, WN, true, false>), grid, dim3(NTHREADS), 0, st, P);
+    else if (fast) hipLaunchKernelGGL((igemm_bf16_classes_kernel<BM, BN, WM, WN, true, true>), grid, dim3(NTHREADS), 0, st, P);
+    else if (!gated) hipLaunchKernelGGL((igemm_bf16_classes_kernel<BM, BN, WM, WN, false, false>), grid, dim3(NTHREADS), 0, st, P);
+    else hipLaunchKernelGGL((igemm_bf16_classes_kernel<BM, BN, WM, WN, false, true>), grid, dim3(NTHREADS), 0, st, P);
+    return launch_status();
+}
+
+static int launch_igemm_bf16_classes(GemmClasses &P, int n, hipStream_t st)
+{
+    if (n < 1 || n > MAX_CLASSES) return STANZA_EINVAL;
+    const ConvGeo &g = P.q[0].g;
+    if (g.C % 8 || g.K % 8) return STANZA_EUNSUPPORTED;
+    const int64_t yb = (int64_t)g.N * g.Ho * g.Wo * g.K * 2, wb = (int64_t)g.K * g.R * g.S * g.C * 2;
+    if (yb >= (int64_t(1) << 31) || wb >= (int64_t(1) << 31)) return STANZA_EUNSUPPORTED;
+    int64_t items128 = 0, items64 = 0;
+    int kd_max = 0, m_max = 0;
+    const int Nn = P.q[0].Nn;
+    for (int i = 0; i < n; ++i) {
+        GemmParams &q = P.q[i];
+        if (q.M <= 0 || q.Nn <= 0 || q.Kd < 0) return STANZA_EINVAL;
+        q.fd_c = make_fastdiv(g.C);
+        q.fd_k = make_fastdiv(g.K);
+        q.fd_howo = make_fastdiv(g.Ho * g.Wo);
+        q.fd_wo = make_fastdiv(g.Wo);
+        const int rc = prepare_stride_class(q, BKH);
+        if (rc) return rc;
+        q.a_bytes = (uint32_t)yb;
+        q.b_bytes = (uint32_t)wb;
+        items128 += (int64_t)cdiv(q.M, 128) * cdiv(Nn, 128);
+        items64 += cdiv(q.M, 128);
+        kd_max = max(kd_max, q.Kd);
+        m_max = max(m_max, q.M);
+    }
+    // (the rules of launch_mode_bf16 for MODE_BWD_DATA, with the classes' work items added up)
+    if (Nn <= 64) {
+        if (kd_max <= 288) return launch_classes_tile_bf16<64, 64, 2, 2>(P, n, st);
+        if (items64 >= 512) return launch_classes_tile_bf16<128, 64, 2, 2>(P, n, st);
+        return launch_classes_tile_bf16<64, 64, 2, 2>(P, n, st);
+    }
+    if (m_max <= 64 || items128 < 160) {
+        if (m_max > 64 && kd_max <= 3072) return launch_classes_tile_bf16<64, 64, 2, 2>(P, n, st);
+        return launch_classes_tile_bf16<64, 128, 2, 2>(P, n, st);
+    }
+    if (Nn % 128 != 0 && Nn % 128 <= 64) return launch_classes_tile_bf16<128, 64, 2, 2>(P, n, st);
+    return launch_classes_tile_bf16<128, 128, 2, 2>(P, n, st);
 }
 
 int launch_igemm_bf16(int mode, GemmParams &p, int splits, hipStream_t st)
@@ -714,6 +835,11 @@ static int launch_any(const stanza_conv_desc *d, int mode, GemmParams &p, int sp
     return launch_igemm(mode, p, 1, (float *)ws, ws ? ws_bytes / 4 : 0, st);
 }
 
+static int launch_classes(const stanza_conv_desc *d, GemmClasses &P, int n, hipStream_t st)
+{
+    return d->dtype == STANZA_BF16 ? launch_igemm_bf16_classes(P, n, st) : launch_igemm_classes(P, n, st);
+}
+
 static int conv_fwd_any(const stanza_conv_desc *desc, const void *x, const void *w, const float *bias, const void *res, bool want_res, void *y,
                         void *ws, size_t ws_bytes, void *stream, float *stats = nullptr)
 {
@@ -812,6 +938,9 @@ extern "C" int stanza_conv_bwd_data(const stanza_conv_desc *desc, const void *dy
     // pixels.  A pixel of class (a, b) only receives the taps r = a, a + stride_h, ..., s = b, b + stride_w, ...; gathering them
     // class by class multiplies no zeros (a 3x3 stride-2 layer has classes of 4, 2, 2 and 1 taps instead of 9 taps of which
     // three quarters miss).  The classes write disjoint pixels and together cover dx.
+    // Up to MAX_CLASSES classes go out as one launch.
+    GemmClasses P;
+    int n = 0;
     for (int a = 0; a < g.sh; ++a) {
         for (int b = 0; b < g.sw; ++b) {
             GemmParams q = p;
@@ -831,10 +960,14 @@ extern "C" int stanza_conv_bwd_data(const stanza_conv_desc *desc, const void *dy
             q.M = g.N * c.Hc * c.Wc;
             q.Kd = c.Rc * c.Sc * g.K;
             q.flags |= OUT_STRIDED;
-            rc = launch_any(desc, MODE_BWD_DATA, q, 1, nullptr, 0, (hipStream_t)stream);
-            if (rc) return rc;
+            P.q[n++] = q;
+            if (n == MAX_CLASSES) {
+                if ((rc = launch_classes(desc, P, n, (hipStream_t)stream))) return rc;
+                n = 0;
+            }
         }
     }
+    if (n > 0 && (rc = launch_classes(desc, P, n, (hipStream_t)stream))) return rc;
     return STANZA_OK;
 }
 

@@ -145,10 +145,10 @@ __device__ __forceinline__ float4 gate4(float4 v, float4 m)
 // FAST (FWD / BWD_DATA with both vector paths, channel count a multiple of BK): a stage lies
 // inside one filter tap, so the tap is wavefront-uniform (scalar registers) and a row's address is a precomputed row
 // offset plus a scalar; no per-thread division or multiplication is left in the main loop.
-template <int MODE, int BM, int BN, int WM, int WN, bool VECA, bool VECB, bool FAST = false>
-// register cap: 128 (four workgroups per CU) for the vector-fetch variants of the 128-row tiles; the scalar-gather variants
-// (3-channel first layers) need more and spill under it
-__global__ __launch_bounds__(NTHREADS, (BM >= 256 ? 3 : (VECA && VECB) ? 4 : 2)) void igemm_kernel(const GemmParams p)
+// The workgroup's whole program; p lives in the kernel's argument segment (igemm_kernel: the argument itself;
+// igemm_classes_kernel: one of several parameter sets, picked by blockIdx.y).
+template <int MODE, int BM, int BN, int WM, int WN, bool VECA, bool VECB, bool FAST>
+__device__ __forceinline__ void igemm_body(const GemmParams p)
 {
     static_assert(WM * WN == 4, "four wavefronts per workgroup");
     static_assert(BM % 64 == 0 && BN % 64 == 0, "loader granularity");
@@ -833,6 +833,27 @@ __global__ __launch_bounds__(NTHREADS, (BM >= 256 ? 3 : (VECA && VECB) ? 4 : 2))
             }
         }
     }
+}
+
+template <int MODE, int BM, int BN, int WM, int WN, bool VECA, bool VECB, bool FAST = false>
+// register cap: 128 (four workgroups per CU) for the vector-fetch variants of the 128-row tiles; the scalar-gather variants
+// (3-channel first layers) need more and spill under it
+__global__ __launch_bounds__(NTHREADS, (BM >= 256 ? 3 : (VECA && VECB) ? 4 : 2)) void igemm_kernel(const GemmParams p)
+{
+    igemm_body<MODE, BM, BN, WM, WN, VECA, VECB, FAST>(p);
+}
+
+// Several independent GEMMs of one shape family in one launch: the stride classes of a strided layer's data gradient (each
+// class gathers its own taps into its own, disjoint, pixels of dx).  One class by itself is a few dozen to a few hundred
+// tiles; launched one after the other they left most CUs idle.  blockIdx.y = class, blockIdx.x = its work items (workgroups
+// past a class's last tile leave at once).
+constexpr int MAX_CLASSES = 4;
+struct GemmClasses { GemmParams q[MAX_CLASSES]; };
+
+template <int BM, int BN, int WM, int WN, bool VECA, bool VECB, bool FAST>
+__global__ __launch_bounds__(NTHREADS, (BM >= 256 ? 3 : (VECA && VECB) ? 4 : 2)) void igemm_classes_kernel(const GemmClasses P)
+{
+    igemm_body<MODE_BWD_DATA, BM, BN, WM, WN, VECA, VECB, FAST>(P.q[blockIdx.y]);
 }
 
 }  // namespace stanza

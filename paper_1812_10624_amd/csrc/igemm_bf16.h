@@ -76,7 +76,7 @@ __device__ __forceinline__ s16x4 lds_tr4(const uint16_t *p)
 // AMASK: dy is gated by [y > 0] as it is read (a second fetch per A vector); without it the registers allow fetching two
 // stages ahead.
 template <int MODE, int BM, int BN, int WM, int WN, bool FAST, bool AMASK>
-__global__ __launch_bounds__(NTHREADS, 2) void igemm_bf16_kernel(const GemmParams p)
+__device__ __forceinline__ void igemm_bf16_body(const GemmParams p)
 {
     static_assert(WM * WN == 4, "four wavefronts per workgroup");
     static_assert(BM % 64 == 0 && BN % 64 == 0, "loader granularity");
@@ -613,6 +613,19 @@ __global__ __launch_bounds__(NTHREADS, 2) void igemm_bf16_kernel(const GemmParam
             }
         }
     }
+}
+
+template <int MODE, int BM, int BN, int WM, int WN, bool FAST, bool AMASK>
+__global__ __launch_bounds__(NTHREADS, 2) void igemm_bf16_kernel(const GemmParams p)
+{
+    igemm_bf16_body<MODE, BM, BN, WM, WN, FAST, AMASK>(p);
+}
+
+// The stride classes of a strided layer's data gradient in one launch (see igemm_classes_kernel): blockIdx.y = class.
+template <int BM, int BN, int WM, int WN, bool FAST, bool AMASK>
+__global__ __launch_bounds__(NTHREADS, 2) void igemm_bf16_classes_kernel(const GemmClasses P)
+{
+    igemm_bf16_body<MODE_BWD_DATA, BM, BN, WM, WN, FAST, AMASK>(P.q[blockIdx.y]);
 }
 
 }  // namespace stanza
