@@ -26,7 +26,7 @@ def o64():
 
 def pytest_terminal_summary(terminalreporter, exitstatus, config):
     """Parity report of a GPU run: per test function the largest E = max|got - ref| / max(|ref|, tau max|ref|) at the three
-    floors tau and the plain inf-norm ratio, printed and written to gpurun_out/parity_report.json."""
+    floors tau and the plain inf-norm ratio, printed and written to parity_report.json in the run's output folder."""
     try:
         import gpu_util
     except Exception:
