@@ -542,42 +542,61 @@ __device__ __forceinline__ void igemm_bf16_body(const GemmParams p)
         }
         return (size_t)row * p.Nn + col;
     };
+    // What the staging reads from global memory is loaded in clusters before it starts (the bias of this lane's columns once, the
+    // residual or the previous gradient of a whole staging pass together): one load after the other, each waited for where it is
+    // used, was 8 to 24 memory round trips in a row per tile, as long as the whole main loop of a 64-deep reduction.
+    float4 bias4[TN][4];
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+        for (int q4 = 0; q4 < 4; ++q4) bias4[j][q4] = zero4();
+    if (MODE == MODE_FWD && (p.flags & EPI_BIAS)) {
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int q4 = 0; q4 < 4; ++q4) {
+                const int col_l = wave_n * WTN + j * 32 + 8 * q4 + 4 * lk;
+                if (n0 + col_l < p.Nn) bias4[j][q4] = ldg4(p.bias + n0 + col_l);
+            }
+    }
+    const bool want_add = MODE == MODE_FWD ? (p.flags & EPI_RESIDUAL) != 0 : MODE == MODE_BWD_DATA ? (p.flags & EPI_ACCUM) != 0 : false;
 #pragma unroll
     for (int half = 0; half < BM / CROWS; ++half) {
         __syncthreads();
         if ((wave_m * WTM) / CROWS == half) {
+            uint2 add2[TN][4][TM];
+            if (want_add) {
+                // FWD: the shortcut's bf16 tensor of a residual join (added in float32, before the ReLU and the one rounding);
+                // BWD_DATA: the previous gradient (residual joins only)
+                const uint16_t *src = MODE == MODE_FWD ? reinterpret_cast<const uint16_t *>(p.res) : outh;
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+#pragma unroll
+                    for (int q4 = 0; q4 < 4; ++q4)
+#pragma unroll
+                        for (int i = 0; i < TM; ++i) {
+                            const int col = n0 + wave_n * WTN + j * 32 + 8 * q4 + 4 * lk, row = m0 + wave_m * WTM + i * 32 + lrow;
+                            add2[j][q4][i] = (row < p.M && col < p.Nn) ? *reinterpret_cast<const uint2 *>(src + out_index(row, col)) : make_uint2(0u, 0u);
+                        }
+            }
 #pragma unroll
             for (int j = 0; j < TN; ++j) {
 #pragma unroll
                 for (int q4 = 0; q4 < 4; ++q4) {
                     const int col_l = wave_n * WTN + j * 32 + 8 * q4 + 4 * lk;
-                    float4 bias = zero4();
-                    if (MODE == MODE_FWD && (p.flags & EPI_BIAS) && n0 + col_l < p.Nn) bias = ldg4(p.bias + n0 + col_l);
+                    const float4 bias = bias4[j][q4];
 #pragma unroll
                     for (int i = 0; i < TM; ++i) {
                         const int row_l = wave_m * WTM + i * 32 + lrow - half * CROWS;
                         float v0 = acc[i][j][4 * q4 + 0] + bias.x, v1 = acc[i][j][4 * q4 + 1] + bias.y;
                         float v2 = acc[i][j][4 * q4 + 2] + bias.z, v3 = acc[i][j][4 * q4 + 3] + bias.w;
-                        if (MODE == MODE_FWD && (p.flags & EPI_RESIDUAL)) {
-                            // residual join: the shortcut's bf16 tensor is added in float32, before the ReLU and the one rounding
-                            const int row = m0 + wave_m * WTM + i * 32 + lrow;
-                            if (row < p.M && n0 + col_l < p.Nn) {
-                                const uint2 rr = *reinterpret_cast<const uint2 *>(reinterpret_cast<const uint16_t *>(p.res) + out_index(row, n0 + col_l));
-                                v0 += bf16_to_f32((uint16_t)(rr.x & 0xffffu)); v1 += bf16_to_f32((uint16_t)(rr.x >> 16));
-                                v2 += bf16_to_f32((uint16_t)(rr.y & 0xffffu)); v3 += bf16_to_f32((uint16_t)(rr.y >> 16));
-                            }
+                        if (want_add) {
+                            const uint2 rr = add2[j][q4][i];
+                            v0 += bf16_to_f32((uint16_t)(rr.x & 0xffffu)); v1 += bf16_to_f32((uint16_t)(rr.x >> 16));
+                            v2 += bf16_to_f32((uint16_t)(rr.y & 0xffffu)); v3 += bf16_to_f32((uint16_t)(rr.y >> 16));
                         }
                         if (MODE == MODE_FWD && (p.flags & EPI_RELU)) {
                             v0 = fmaxf(v0, 0.f); v1 = fmaxf(v1, 0.f); v2 = fmaxf(v2, 0.f); v3 = fmaxf(v3, 0.f);
-                        }
-                        if (MODE == MODE_BWD_DATA && (p.flags & EPI_ACCUM)) {
-                            // residual joins only: the previous gradient is added before the one rounding to bf16
-                            const int row = m0 + wave_m * WTM + i * 32 + lrow;
-                            if (row < p.M && n0 + col_l < p.Nn) {
-                                const uint2 old = *reinterpret_cast<const uint2 *>(outh + out_index(row, n0 + col_l));
-                                v0 += bf16_to_f32((uint16_t)(old.x & 0xffffu)); v1 += bf16_to_f32((uint16_t)(old.x >> 16));
-                                v2 += bf16_to_f32((uint16_t)(old.y & 0xffffu)); v3 += bf16_to_f32((uint16_t)(old.y >> 16));
-                            }
                         }
                         *reinterpret_cast<uint2 *>(&smem[row_l * LDC + col_l]) = make_uint2(pack_bf16x2(v0, v1), pack_bf16x2(v2, v3));
                     }
