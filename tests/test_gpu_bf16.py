@@ -44,6 +44,7 @@ CASES = [
     (2, 29, 29, 16, 32, 3, 3, 2, 1),
     (2, 27, 27, 16, 24, 5, 5, 1, 2),
     (3, 13, 13, 32, 72, 3, 3, 1, 1),
+    (2, 20, 19, 8, 16, 5, 5, 3, 2),        # stride 3: nine stride classes of the data gradient, in three launches, odd class sizes
 ]
 
 

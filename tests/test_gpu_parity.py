@@ -40,6 +40,7 @@ CONV_CASES = [
     (2, 35, 33, 3, 16, 7, 7, 2, 3),        # stem
     (2, 27, 27, 12, 20, 5, 5, 1, 2),
     (1, 67, 67, 3, 24, 11, 11, 4, 2),
+    (2, 20, 19, 8, 16, 5, 5, 3, 2),        # stride 3: nine stride classes of the data gradient, in three launches, odd class sizes
     (2, 9, 9, 6, 10, 3, 3, 1, 0),          # C, K not multiples of 4
     (4, 1, 1, 300, 70, 1, 1, 1, 0),        # an FC layer as a convolution
 ]
