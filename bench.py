@@ -84,6 +84,9 @@ def main():
     ap.add_argument("--dtype", default="f32", choices=["f32", "bf16"], help="conv-stack storage type (accumulation is always f32)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--detail", action="store_true", help="per-call timing table on stderr")
+    ap.add_argument("--one-stream", action="store_true",
+                    help="issue the filter gradients on the caller's stream like every other call, instead of on a second stream beside "
+                         "the data gradients (the per-call pass always runs this way)")
     ap.add_argument("--dropout", type=float, default=0.0, help="seeded dropout after the FC worker's hidden layers (0: none)")
     ap.add_argument("--graph", action="store_true",
                     help="replay the step as one HIP graph in the timed region (launch-bound workloads); the per-call breakdown "
@@ -140,6 +143,7 @@ def main():
     worker = ConvWorker(wl.ops, wl.image, B, cp, dtype=api.BF16 if args.dtype == "bf16" else api.F32, feat_out=feats[:B])
     fcw = FcWorker(wl.fc_dims, n, fp, fm, wl.lr, wl.momentum, wl.weight_decay, dropout=(args.dropout, seed) if args.dropout > 0 else None,
                    dtype=api.BF16 if (args.dtype == "bf16" and all(d % 8 == 0 for d in wl.fc_dims[:-1])) else api.F32)
+    worker.overlap_wgrad = not args.one_stream
     joined_ops = sorted(worker.joined)           # ops that run with the residual join fused into their epilogue
     shard0 = W.flat_tensors(worker.grads)
     shards = [shard0] + [[torch.randn(t.shape, device=dev, generator=gen) * 1e-3 for t in shard0] for _ in range(K - 1)]
@@ -244,7 +248,20 @@ def main():
     assert all(math.isfinite(v) for v in live.values()), live
     assert (args.steps < 2 or live["loss_after_first_timed_step"] != live["loss_after_last_timed_step"]) \
         and live["handed_over_features_nonzero_fraction"] > 0.01, live
+    # ---- a few steps with every call on one stream (what the per-call pass below and the committed kernel traces measure), so that
+    # the line shows what the second stream of the backward pass is worth
+    worker.overlap_wgrad = False
+    n_one = min(args.steps, 5)
+    one_a, one_b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    step()
+    one_a.record()
+    for _ in range(n_one):
+        step()
+    one_b.record()
+    torch.cuda.synchronize()
+    ms_per_step_one_stream = one_a.elapsed_time(one_b) / n_one
     # ---- the same K steps again, eager, with an event pair around every entry-point call: per-call times, roofline
+    # (still one stream: a call's event pair then brackets that call's kernels alone)
     netrun.api = tap
     plan = getattr(worker, "cast_plan", None)          # the one-launch cast of all bf16 filter copies is a method of its plan object
     if plan is not None:
@@ -385,7 +402,9 @@ def main():
         "unit": "images/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step,
-        "ms_per_step_instrumented": ms_per_step_instrumented,      # the second pass, with an event pair around every call
+        "backward_streams": 1 if (args.one_stream or args.graph) else 2,   # filter gradients beside the data gradients on a second stream
+        "ms_per_step_one_stream": ms_per_step_one_stream,          # eager, every call on the caller's stream
+        "ms_per_step_instrumented": ms_per_step_instrumented,      # the per-call pass, one stream, an event pair around every call
         "per_entry_point_ms": {k: round(v, 4) for k, v in sorted(tot.items())},      # of that pass, per step
         # untimed forward passes that the instrumented pass queues ahead of its steps (they are in a profiler's trace of this run)
         "blocker_forward_passes": 2 + n_block * args.steps,

@@ -169,3 +169,36 @@ def test_plain_aggregation_call_inside_a_graph_capture(api, o32, K, numels):
             assert rel_err(host(gv[t]), v_ref[t]) < 1e-5, (rep, t)
             assert param_update_err(host(gw[t]), w_ref[t], before[t]) < 1e-4, (rep, t)
             assert rel_err(host(gw[t]), w_ref[t]) < 1e-6, (rep, t)
+
+
+@pytest.mark.parametrize("name,B", [("resnet50", 4), ("inception3", 2), ("vgg16", 2)])
+def test_backward_on_two_streams_equals_one_stream(api, name, B):
+    """The backward pass issues filter gradients on a second stream beside the data gradients (Sec. 3.2: the CONV worker's
+    backward pass; nothing reads a filter gradient before the aggregation).  Same kernels, same operands, so every gradient must
+    come out bit for bit as on one stream -- also where a residual join's gradient, which a filter-gradient launch reads, is
+    later accumulated into by the shortcut's side, and over repeated steps (the second stream of one step against the
+    caller's stream of the next)."""
+    from paper_1812_10624_amd.netrun import ConvWorker
+    wl = wl_mod.get_workload(name)
+    img = dev(wl_mod.gen_images(wl, 3, 0, B))
+    gcp = {n: (dev(w), None if b is None else dev(b)) for n, (w, b) in wl_mod.gen_conv_params(wl, 3).items()}
+    wk = ConvWorker(wl.ops, wl.image, B, gcp)
+    feat = wk.forward(img)
+    dfeat = torch.randn(feat.shape, device="cuda:0", generator=torch.Generator(device="cuda:0").manual_seed(11)) / B
+    wk.overlap_wgrad = False
+    wk.backward(dfeat)
+    torch.cuda.synchronize()
+    ref = {n: tuple(None if g is None else g.clone() for g in gs) for n, gs in wk.grads.items()}
+    wk.overlap_wgrad = True
+    for rep in range(3):
+        for gs in wk.grads.values():
+            for g in gs:
+                if g is not None:
+                    g.fill_(float("nan"))            # on the caller's stream: the pass must order its second stream behind this
+        wk.backward(dfeat)
+        got = {n: tuple(None if g is None else g.clone() for g in gs) for n, gs in wk.grads.items()}   # caller's stream, no sync
+        torch.cuda.synchronize()
+        for n in ref:
+            for which in range(2):
+                if ref[n][which] is not None:
+                    assert torch.equal(got[n][which], ref[n][which]), (name, rep, n, which)
