@@ -85,8 +85,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--detail", action="store_true", help="per-call timing table on stderr")
     ap.add_argument("--one-stream", action="store_true",
-                    help="issue the filter gradients on the caller's stream like every other call, instead of on a second stream beside "
-                         "the data gradients (the per-call pass always runs this way)")
+                    help="issue every call of the CONV worker on the caller's stream, instead of spreading independent calls (a layer's "
+                         "filter gradient beside its data gradient, the branches of a module) over several streams; the per-call pass "
+                         "always runs this way")
     ap.add_argument("--dropout", type=float, default=0.0, help="seeded dropout after the FC worker's hidden layers (0: none)")
     ap.add_argument("--graph", action="store_true",
                     help="replay the step as one HIP graph in the timed region (launch-bound workloads); the per-call breakdown "
@@ -143,7 +144,7 @@ def main():
     worker = ConvWorker(wl.ops, wl.image, B, cp, dtype=api.BF16 if args.dtype == "bf16" else api.F32, feat_out=feats[:B])
     fcw = FcWorker(wl.fc_dims, n, fp, fm, wl.lr, wl.momentum, wl.weight_decay, dropout=(args.dropout, seed) if args.dropout > 0 else None,
                    dtype=api.BF16 if (args.dtype == "bf16" and all(d % 8 == 0 for d in wl.fc_dims[:-1])) else api.F32)
-    worker.overlap_wgrad = not args.one_stream
+    worker.multi_stream = not args.one_stream
     joined_ops = sorted(worker.joined)           # ops that run with the residual join fused into their epilogue
     shard0 = W.flat_tensors(worker.grads)
     shards = [shard0] + [[torch.randn(t.shape, device=dev, generator=gen) * 1e-3 for t in shard0] for _ in range(K - 1)]
@@ -215,8 +216,21 @@ def main():
         api.stanza_add_relu_fwd(ca, cb, cc)
         torch.cuda.synchronize()
         del ca, cb, cc
-    for _ in range(args.warmup):
+    # warm-up steps are issued exactly like the timed ones, the event mark after each step included (the first timing event that
+    # a process records is not free, and it belongs here, not in the first timed step)
+    warm_marks = [torch.cuda.Event(enable_timing=True) for _ in range(args.warmup + 1)]
+    warm_marks[0].record()
+    for i in range(args.warmup):
         step()
+        warm_marks[i + 1].record()
+    # The interpreter's cyclic garbage collector is emptied here and what exists now is taken out of its reach: a full collection
+    # walks every object of the process (torch's modules included) and takes some 40 ms; when its allocation count happened to come
+    # up in the first timed step -- the one step that the host does not issue a whole step ahead of the GPU -- the GPU sat idle for
+    # those 40 ms (seen as a first step of 85-95 ms against 47.6; which step it hits depends on how many objects were allocated
+    # before, so it came and went with unrelated changes).  Collections still run afterwards, over the few objects made since.
+    import gc
+    gc.collect()
+    gc.freeze()
     torch.cuda.synchronize()
     # ---- the timed region: K steps as a caller runs them, nothing between the calls.  (An event pair around every call keeps each
     # kernel from starting before the previous call's end event has been written: 1 % of a VGG-16-shaped step, 8 % of a
@@ -229,16 +243,15 @@ def main():
     else:
         run_step = step
     marks = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
-    with SclkSampler() as sclk:
-        t0 = time.perf_counter()
-        marks[0].record()
-        for i in range(args.steps):
-            run_step()
-            marks[i + 1].record()
-            if i == 0:
-                loss_first = fcw.loss.clone()      # one 4-byte device copy inside the timed region
-        torch.cuda.synchronize()
-        t1 = time.perf_counter()
+    t0 = time.perf_counter()
+    marks[0].record()
+    for i in range(args.steps):
+        run_step()
+        marks[i + 1].record()
+        if i == 0:
+            loss_first = fcw.loss.clone()      # one 4-byte device copy inside the timed region
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
     # The timed data is live: every step is a real SGD step on the same batch, so the loss is finite and moves, and the features
     # this worker hands over keep about half of their units active (a stack whose activations had died would time faster).
     import math
@@ -249,8 +262,8 @@ def main():
     assert (args.steps < 2 or live["loss_after_first_timed_step"] != live["loss_after_last_timed_step"]) \
         and live["handed_over_features_nonzero_fraction"] > 0.01, live
     # ---- a few steps with every call on one stream (what the per-call pass below and the committed kernel traces measure), so that
-    # the line shows what the second stream of the backward pass is worth
-    worker.overlap_wgrad = False
+    # the line shows what issuing independent calls on several streams is worth
+    worker.multi_stream = False
     n_one = min(args.steps, 5)
     one_a, one_b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     step()
@@ -260,6 +273,12 @@ def main():
     one_b.record()
     torch.cuda.synchronize()
     ms_per_step_one_stream = one_a.elapsed_time(one_b) / n_one
+    # ---- the driver's shader clock while such steps run, read in a pass of its own, so that the sampling thread (it takes the
+    # interpreter's lock every 4 ms) stays out of every timed pass
+    with SclkSampler() as sclk:
+        for _ in range(n_one):
+            step()
+        torch.cuda.synchronize()
     # ---- the same K steps again, eager, with an event pair around every entry-point call: per-call times, roofline
     # (still one stream: a call's event pair then brackets that call's kernels alone)
     netrun.api = tap
@@ -311,7 +330,8 @@ def main():
     if plan is not None:
         plan.run = plan_run
     ms_per_step = (t1 - t0) * 1e3 / args.steps
-    step_ms = sorted(marks[i].elapsed_time(marks[i + 1]) for i in range(args.steps))     # each step between events on the stream
+    step_ms_in_order = [marks[i].elapsed_time(marks[i + 1]) for i in range(args.steps)]
+    step_ms = sorted(step_ms_in_order)     # each step between events on the stream
     props = torch.cuda.get_device_properties(0)
 
     tot = {k: sum(v) / n_timed_eager for k, v in per.items()}      # ms per step per entry point
@@ -402,17 +422,18 @@ def main():
         "unit": "images/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step,
-        "backward_streams": 1 if (args.one_stream or args.graph) else 2,   # filter gradients beside the data gradients on a second stream
+        "conv_worker_streams": 1 if (args.one_stream or args.graph) else worker.n_streams,   # independent calls side by side
         "ms_per_step_one_stream": ms_per_step_one_stream,          # eager, every call on the caller's stream
         "ms_per_step_instrumented": ms_per_step_instrumented,      # the per-call pass, one stream, an event pair around every call
         "per_entry_point_ms": {k: round(v, 4) for k, v in sorted(tot.items())},      # of that pass, per step
         # untimed forward passes that the instrumented pass queues ahead of its steps (they are in a profiler's trace of this run)
         "blocker_forward_passes": 2 + n_block * args.steps,
+        "step_ms_in_order": [round(v, 3) for v in step_ms_in_order],
         "step_ms_median": step_ms[len(step_ms) // 2], "step_ms_min": step_ms[0], "step_ms_max": step_ms[-1],
         "device": {"name": props.name, "compute_units": props.multi_processor_count,
-                   "sclk_mhz_during_timed_steps": sclk.summary(),
+                   "sclk_mhz_during_steps": sclk.summary(),
                    "note": "clocks and power state as the box provides them (not set by this run); sclk is the driver's own figure "
-                           "(pp_dpm_sclk, sampled every 4 ms while the timed steps run); the roofline peaks assume 2400 MHz; cycle counters "
+                           "(pp_dpm_sclk, sampled every 4 ms while a few further, untimed steps run); the roofline peaks assume 2400 MHz; cycle counters "
                            "read inside the GEMM kernels show lower effective clocks than the driver reports (bf16 launches 1.5-1.9 GHz)"},
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": args.dtype, "data": "synthetic", "launch": "hip_graph_replay" if args.graph else "eager",

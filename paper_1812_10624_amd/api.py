@@ -143,8 +143,18 @@ def _ptr(t: Optional[torch.Tensor]):
     return C.c_void_p(t.data_ptr())
 
 
+_issue_stream = None     # torch.cuda.Stream that the next calls are enqueued on instead of torch's current stream
+
+
+def set_stream(stream):
+    """Every following call goes to `stream` (None: back to torch's current stream).  For a sequencer that spreads independent
+    calls over several streams and orders them with events; cheaper than switching torch's current stream around each call."""
+    global _issue_stream
+    _issue_stream = stream
+
+
 def _stream():
-    return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+    return C.c_void_p((torch.cuda.current_stream() if _issue_stream is None else _issue_stream).cuda_stream)
 
 
 def _ws(t: Optional[torch.Tensor]):

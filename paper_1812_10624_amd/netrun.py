@@ -5,6 +5,7 @@ This is the role the training loop plays in the paper (Sec. 3.2, Fig. 5): it own
 """
 from __future__ import annotations
 
+import inspect
 from typing import Dict, List, Optional
 
 import torch
@@ -12,12 +13,137 @@ import torch
 from . import api
 
 
-# Filter gradients run beside the data gradients (second stream) for layers of at most this many 128 x 128 tiles of dy.  Measured at
-# batch 64, images/s with the limit at 800 / 1,600 / 3,200 / 6,400 / 12,800 / none against one stream: VGG-16-shaped 1,333 / 1,332 /
+# Filter gradients run beside the data gradients (on another stream) for layers of at most this many 128 x 128 tiles of dy.  Measured
+# at batch 64, images/s with the limit at 800 / 1,600 / 3,200 / 6,400 / 12,800 / none against one stream: VGG-16-shaped 1,333 / 1,332 /
 # 1,341 / 1,344 / 1,343 / 1,319 against 1,328; ResNet-50-shaped 3,841 / 3,935 / 3,958 / 3,948 / 3,946 / 3,947 against 3,635;
 # Inception-V3-shaped 1,634 / 1,637 / 1,645 / 1,646 / 1,645 / 1,643 against 1,539.  Only the two 224 x 224 x 64 layers of the VGG
 # stacks (25,088 tiles) lose.
 OVERLAP_MAX_TILES = 8192
+
+# Arguments that a call WRITES (or updates in place); every other tensor argument is read.  The workspace counts as written.
+_WRITES = {
+    "stanza_conv_fwd": ("y", "ws"), "stanza_conv_fwd_res": ("y", "ws"), "stanza_conv_fwd_stats": ("y", "stats", "ws"),
+    "stanza_conv_bwd_data": ("dx", "ws"), "stanza_conv_bwd_weight": ("dw", "dbias", "ws"),
+    "stanza_pool_relu_fwd": ("y", "argmax"), "stanza_pool_relu_bwd": ("dx",),
+    "stanza_avgpool_fwd": ("y",), "stanza_avgpool_bwd": ("dx",),
+    "stanza_add_relu_fwd": ("o",), "stanza_add_relu_bwd": ("dz",),
+    "stanza_gap_fwd": ("f",), "stanza_gap_bwd": ("dx",),
+    "stanza_cast_f32_to_bf16": ("dst",), "stanza_cast_bf16_to_f32": ("dst",), "stanza_copy_channels": ("dst",),
+    "stanza_bn_fwd": ("y", "save_mean", "save_istd", "ws", "running_mean", "running_var"),
+    "stanza_bn_fwd_res": ("y", "save_mean", "save_istd", "ws", "running_mean", "running_var"),
+    "stanza_bn_fwd_stats": ("y", "save_mean", "save_istd", "running_mean", "running_var"),
+    "stanza_bn_bwd": ("dx", "dgamma", "dbeta", "ws"),
+}
+_PARAMS = {name: tuple(inspect.signature(getattr(api, name)).parameters) for name in _WRITES}
+
+
+class StreamSchedule:
+    """Spreads the calls of one pass (a CONV worker's forward or backward pass, Sec. 3.2) over a few streams of default priority
+    and orders them with events, so that launches that do not depend on each other -- the branches of an Inception module, a
+    projection shortcut beside its block, a layer's filter gradient beside its data gradient -- run side by side and fill each
+    other's partly empty rounds of workgroups.  The caller names a stream for every call (a hint: any choice is correct); which
+    call must wait for which is found from the calls themselves: a call waits for the last writer of every tensor it touches,
+    and a writer also for every reader since (tensors are told apart by their storage, so views of one buffer count as that
+    buffer).  The first pass of a kind works this out and keeps the result -- per call its stream, the events to wait for and
+    the event to record -- and later passes replay that list: the sequence of calls of a pass never changes.
+    A pass starts with every stream waiting for the caller's stream and ends with the caller's stream waiting for all of them, so
+    nothing outside the pass sees more than one stream.  Under graph capture, or switched off, calls go straight to the current
+    stream."""
+
+    def __init__(self, dev, n_streams: int):
+        self.side = [torch.cuda.Stream(device=dev) for _ in range(n_streams - 1)]
+        self.n = n_streams
+        self.plans: Dict[str, list] = {}
+        self.ev_fork = torch.cuda.Event()
+        self.ev_join = [torch.cuda.Event() for _ in self.side]
+        self.on = False
+
+    def begin(self, tag: str, enabled: bool):
+        self.on = enabled and not torch.cuda.is_current_stream_capturing()
+        if not self.on:
+            return
+        self.main = torch.cuda.current_stream()
+        self.streams = [self.main] + self.side
+        self.tag, self.plan, self.at = tag, self.plans.get(tag), 0
+        if self.plan is None:
+            self.new, self.seq = [], 0
+            self.last_writer: Dict[int, tuple] = {}      # storage -> (stream index, sequence number, event)
+            self.readers: Dict[int, list] = {}           # storage -> the same, for every reader since the last writer
+            self.seen = [dict() for _ in range(self.n)]  # per stream: other stream -> latest sequence number already waited for
+        # only the streams that this pass uses join in (all of them while the pass is worked out): the caller's stream is not
+        # made to wait for a queue that has nothing to do and may be slow to wake up
+        self.active = self.side if self.plan is None else [self.side[i - 1] for i in sorted({e[0] for e in self.plan} - {0})]
+        if self.active:
+            self.ev_fork.record(self.main)
+        for st in self.active:
+            st.wait_event(self.ev_fork)
+
+    def _work_out(self, s: int, name: str, args, kw):
+        deps: Dict[int, tuple] = {}
+
+        def need(dep):
+            o, q, ev = dep
+            if o != s and q > self.seen[s].get(o, -1) and (o not in deps or deps[o][0] < q):
+                deps[o] = (q, ev)                        # a stream runs in order: its latest event stands for the earlier ones
+        reads, writes = [], []
+        for pname, val in list(zip(_PARAMS[name], args)) + list(kw.items()):
+            if isinstance(val, torch.Tensor):
+                (writes if pname in _WRITES[name] else reads).append(val.untyped_storage().data_ptr())
+        for k in reads:
+            if k in self.last_writer:
+                need(self.last_writer[k])
+        for k in writes:
+            if k in self.last_writer:
+                need(self.last_writer[k])
+            for r in self.readers.get(k, ()):
+                need(r)
+        ev = torch.cuda.Event()
+        me = (s, self.seq, ev)
+        self.seq += 1
+        for k in reads:
+            self.readers.setdefault(k, []).append(me)
+        for k in writes:
+            self.last_writer[k] = me
+            self.readers[k] = []
+        for o, (q, _) in deps.items():
+            self.seen[s][o] = q
+        return [e for _, e in deps.values()], ev
+
+    def call(self, s: int, name: str, *args, **kw):
+        fn = getattr(api, name)
+        if not self.on:
+            return fn(*args, **kw)
+        if self.plan is None:
+            waits, ev = self._work_out(s, name, args, kw)
+            self.new.append((s, name, waits, ev))
+        else:
+            if self.at >= len(self.plan) or self.plan[self.at][:2] != (s, name):
+                raise RuntimeError(f"the {self.tag} pass changed its sequence of calls at call {self.at} ({name})")
+            _, _, waits, ev = self.plan[self.at]
+            self.at += 1
+        st = self.streams[s]
+        for w in waits:
+            st.wait_event(w)
+        api.set_stream(st)
+        try:
+            fn(*args, **kw)
+        finally:
+            api.set_stream(None)
+        if ev is not None:
+            ev.record(st)
+
+    def end(self):
+        if not self.on:
+            return
+        if self.plan is None:
+            waited = {id(e) for _, _, waits, _ in self.new for e in waits}       # replays record only the events somebody waits for
+            self.plans[self.tag] = [(s, name, waits, ev if id(ev) in waited else None) for s, name, waits, ev in self.new]
+        elif self.at != len(self.plan):
+            raise RuntimeError(f"the {self.tag} pass ended after {self.at} of {len(self.plan)} calls")
+        for st, ev in zip(self.active, self.ev_join):
+            ev.record(st)
+            self.main.wait_event(ev)
+        self.on = False
 
 
 class ConvWorker:
@@ -114,6 +240,7 @@ class ConvWorker:
                     self.stats_conv[i] = i + 1
                     stats_bytes = max(stats_bytes, need)
         self.stats_bn = set(self.stats_conv.values())
+        self.stats_at: Dict[str, int] = {}        # conv output -> index of the statistics buffer its last forward pass wrote
         self.stats_buf = torch.empty(stats_bytes, device=self.dev, dtype=torch.uint8) if stats_bytes else None
         if dtype == api.BF16:
             assert all(op["op"] in ("conv", "pool", "avgpool", "concat", "bn", "add_relu", "gap") for op in ops)
@@ -141,18 +268,22 @@ class ConvWorker:
         ws_bytes = max([api.stanza_conv_workspace_bytes(d, which) for i, d in self.descs.items() if ops[i]["op"] == "conv"
                         for which in (0, 1, 2)] + [16])
         self.ws = torch.empty(ws_bytes, device=self.dev, dtype=torch.uint8)
-        # The filter gradient of a layer and the data gradient of the same layer both start from dy and neither reads what the
-        # other writes: the backward pass issues the filter gradients on a second stream (default priority, its own workspace),
-        # so that the last, partly filled round of workgroups of one launch is filled up by the other.  Nothing reads a filter
-        # gradient before the aggregation; the pass ends by making the caller's stream wait for the second one.  Set
-        # overlap_wgrad = False for one stream (per-call timing; under graph capture the pass takes one stream by itself).
-        self.overlap_wgrad = True
-        self.side = torch.cuda.Stream(device=self.dev) if self.dev.type == "cuda" else None
-        wg_bytes = max([api.stanza_conv_workspace_bytes(d, 2) for i, d in self.descs.items() if ops[i]["op"] == "conv"] + [16])
-        self.ws_side = torch.empty(wg_bytes, device=self.dev, dtype=torch.uint8)
-        self.ev_dy = torch.cuda.Event() if self.side is not None else None
-        self.ev_side = torch.cuda.Event() if self.side is not None else None
-        self.ev_read: Dict[int, torch.cuda.Event] = {}
+        # Calls that do not depend on each other go to different streams (StreamSchedule): in the backward pass a layer's filter
+        # gradient beside its data gradient (both start from dy, neither reads what the other writes, and nothing reads a filter
+        # gradient before the aggregation), and where the op list forks (Inception modules, projection shortcuts) the branches
+        # beside each other, forward and backward.  Every stream has its own workspaces.  multi_stream = False: every call on
+        # the caller's stream (per-call timing; under graph capture a pass takes one stream by itself).
+        uses: Dict[str, int] = {}
+        for op in ops:
+            for nm in ([op["src"]] if "src" in op else []) + list(op.get("srcs", ())) + [op[k] for k in ("a", "b") if k in op]:
+                uses[nm] = uses.get(nm, 0) + 1
+        self.n_streams = 4 if max(uses.values()) > 1 else 2
+        self.multi_stream = self.dev.type == "cuda"
+        self.sched = StreamSchedule(self.dev, self.n_streams) if self.dev.type == "cuda" else None
+        self.wss = [self.ws] + [torch.empty(ws_bytes, device=self.dev, dtype=torch.uint8) for _ in range(self.n_streams - 1)]
+        self.bn_wss = [self.bn_ws] + [None if self.bn_ws is None else torch.empty_like(self.bn_ws) for _ in range(self.n_streams - 1)]
+        self.stats_bufs = [self.stats_buf] + [None if self.stats_buf is None else torch.empty_like(self.stats_buf)
+                                              for _ in range(self.n_streams - 1)]
         for i in self.padded:
             cp = self.descs[i].C
             k, r, s_, _ = params[ops[i]["name"]][0].shape
@@ -182,79 +313,100 @@ class ConvWorker:
             self.buf["x0"].copy_(images)
         if self.dtype == api.BF16 and self.cast_plan is not None:
             self.cast_plan.run()                     # this step's bf16 copies of the master filters
+        sched, ns = self.sched, self.n_streams
+        sched.begin("forward", self.multi_stream)
+        q = sched.call
+        # Stream hints: the first reader of a buffer goes on where the buffer was written, the k-th reader k streams further.
+        at_stream: Dict[str, int] = {}           # buffer -> stream of its writer
+        taken: Dict[str, int] = {}               # buffer -> readers issued so far
+
+        def stream_for(name):
+            k = taken.get(name, 0)
+            taken[name] = k + 1
+            return (at_stream.get(name, 0) + k) % ns
         for i, op in enumerate(self.ops):
             kind = op["op"]
             if i in self.skip_fwd:                  # a residual join computed by the preceding convolution's epilogue
                 continue
+            s = stream_for(op["src"] if "src" in op else op["srcs"][-1] if "srcs" in op else op["a"])
+            at_stream[op["dst"]] = s
+            if i in self.joined:
+                at_stream[self.ops[self.joined[i][0]]["dst"]] = s
             if kind == "conv" and i in self.joined:
                 w, b = self.params[op["name"]]
                 j, other = self.joined[i]
                 if self.dtype == api.BF16:
                     w = self.w16[op["name"]]
-                api.stanza_conv_fwd_res(self.join_desc[i], self.buf[op["src"]], w, b, self.buf[other], self.buf[self.ops[j]["dst"]], self.ws)
+                q(s, "stanza_conv_fwd_res", self.join_desc[i], self.buf[op["src"]], w, b, self.buf[other], self.buf[self.ops[j]["dst"]],
+                  self.wss[s])
             elif kind == "conv":
                 w, b = self.params[op["name"]]
                 if i in self.padded:
                     c = self.padded[i]
-                    api.stanza_copy_channels(self.buf["x0"], 0, self.x0pad32, 0, c)
-                    api.stanza_copy_channels(w, 0, self.wpad32, 0, c)
+                    q(s, "stanza_copy_channels", self.buf["x0"], 0, self.x0pad32, 0, c)
+                    q(s, "stanza_copy_channels", w, 0, self.wpad32, 0, c)
                     if self.dtype == api.BF16:
-                        api.stanza_cast_f32_to_bf16(self.x0pad32, self.x0pad16)
-                        api.stanza_cast_f32_to_bf16(self.wpad32, self.w16[op["name"]])
-                        api.stanza_conv_fwd(self.descs[i], self.x0pad16, self.w16[op["name"]], b, self.buf[op["dst"]], self.ws)
+                        q(s, "stanza_cast_f32_to_bf16", self.x0pad32, self.x0pad16)
+                        q(s, "stanza_cast_f32_to_bf16", self.wpad32, self.w16[op["name"]])
+                        q(s, "stanza_conv_fwd", self.descs[i], self.x0pad16, self.w16[op["name"]], b, self.buf[op["dst"]], self.wss[s])
                     else:
-                        api.stanza_conv_fwd(self.descs[i], self.x0pad32, self.wpad32, b, self.buf[op["dst"]], self.ws)
+                        q(s, "stanza_conv_fwd", self.descs[i], self.x0pad32, self.wpad32, b, self.buf[op["dst"]], self.wss[s])
                 elif self.dtype == api.BF16 and not self.f32_layer[i]:
-                    api.stanza_conv_fwd(self.descs[i], self.buf[op["src"]], self.w16[op["name"]], b, self.buf[op["dst"]], self.ws)
+                    q(s, "stanza_conv_fwd", self.descs[i], self.buf[op["src"]], self.w16[op["name"]], b, self.buf[op["dst"]], self.wss[s])
                 elif self.f32_layer[i]:
                     y32 = self.tmp32[: self.buf[op["dst"]].numel()].view(self.shapes[op["dst"]])
-                    api.stanza_conv_fwd(self.descs[i], self.buf[op["src"]], w, b, y32, self.ws)
-                    api.stanza_cast_f32_to_bf16(y32, self.buf[op["dst"]])
+                    q(s, "stanza_conv_fwd", self.descs[i], self.buf[op["src"]], w, b, y32, self.wss[s])
+                    q(s, "stanza_cast_f32_to_bf16", y32, self.buf[op["dst"]])
                 elif i in self.stats_conv:
-                    api.stanza_conv_fwd_stats(self.descs[i], self.buf[op["src"]], w, b, self.buf[op["dst"]], self.stats_buf, self.ws)
+                    q(s, "stanza_conv_fwd_stats", self.descs[i], self.buf[op["src"]], w, b, self.buf[op["dst"]], self.stats_bufs[s],
+                      self.wss[s])
+                    self.stats_at[op["dst"]] = s
                 else:
-                    api.stanza_conv_fwd(self.descs[i], self.buf[op["src"]], w, b, self.buf[op["dst"]], self.ws)
+                    q(s, "stanza_conv_fwd", self.descs[i], self.buf[op["src"]], w, b, self.buf[op["dst"]], self.wss[s])
             elif kind == "pool":
-                api.stanza_pool_relu_fwd(self.descs[i], self.buf[op["src"]], self.buf[op["dst"]], self.argmax[op["dst"]], self.dtype)
+                q(s, "stanza_pool_relu_fwd", self.descs[i], self.buf[op["src"]], self.buf[op["dst"]], self.argmax[op["dst"]], self.dtype)
             elif kind == "avgpool":
-                api.stanza_avgpool_fwd(self.descs[i], self.buf[op["src"]], self.buf[op["dst"]], self.dtype)
+                q(s, "stanza_avgpool_fwd", self.descs[i], self.buf[op["src"]], self.buf[op["dst"]], self.dtype)
             elif kind == "concat":
                 at = 0
                 for sname in op["srcs"]:
                     cs = self.shapes[sname][3]
-                    api.stanza_copy_channels(self.buf[sname], 0, self.buf[op["dst"]], at, cs)
+                    q(s, "stanza_copy_channels", self.buf[sname], 0, self.buf[op["dst"]], at, cs)
                     at += cs
             elif kind == "bn" and i in self.stats_bn:
                 gamma, beta = self.params[op["name"]]
                 mean, istd = self.bn_stats[op["name"]]
+                stats = self.stats_bufs[self.stats_at[op["src"]]]      # where the producing convolution left them
                 if i in self.joined:
                     j, other = self.joined[i]
-                    api.stanza_bn_fwd_stats(self.buf[op["src"]], self.stats_buf, gamma, beta, self.buf[self.ops[j]["dst"]], mean, istd,
-                                            op["eps"], True, res=self.buf[other])
+                    q(s, "stanza_bn_fwd_stats", self.buf[op["src"]], stats, gamma, beta, self.buf[self.ops[j]["dst"]], mean, istd,
+                      op["eps"], True, res=self.buf[other])
                 else:
-                    api.stanza_bn_fwd_stats(self.buf[op["src"]], self.stats_buf, gamma, beta, self.buf[op["dst"]], mean, istd, op["eps"],
-                                            op["relu"])
+                    q(s, "stanza_bn_fwd_stats", self.buf[op["src"]], stats, gamma, beta, self.buf[op["dst"]], mean, istd, op["eps"],
+                      op["relu"])
             elif kind == "bn" and i in self.joined:
                 gamma, beta = self.params[op["name"]]
                 mean, istd = self.bn_stats[op["name"]]
                 j, other = self.joined[i]
-                api.stanza_bn_fwd_res(self.buf[op["src"]], gamma, beta, self.buf[other], self.buf[self.ops[j]["dst"]], mean, istd, self.bn_ws,
-                                      op["eps"], True, dtype=self.dtype)
+                q(s, "stanza_bn_fwd_res", self.buf[op["src"]], gamma, beta, self.buf[other], self.buf[self.ops[j]["dst"]], mean, istd,
+                  self.bn_wss[s], op["eps"], True, dtype=self.dtype)
             elif kind == "bn":
                 gamma, beta = self.params[op["name"]]
                 mean, istd = self.bn_stats[op["name"]]
-                api.stanza_bn_fwd(self.buf[op["src"]], gamma, beta, self.buf[op["dst"]], mean, istd, self.bn_ws, op["eps"], op["relu"],
-                                  dtype=self.dtype)
+                q(s, "stanza_bn_fwd", self.buf[op["src"]], gamma, beta, self.buf[op["dst"]], mean, istd, self.bn_wss[s], op["eps"],
+                  op["relu"], dtype=self.dtype)
             elif kind == "add_relu":
-                api.stanza_add_relu_fwd(self.buf[op["a"]], self.buf[op["b"]], self.buf[op["dst"]], self.dtype)
+                q(s, "stanza_add_relu_fwd", self.buf[op["a"]], self.buf[op["b"]], self.buf[op["dst"]], self.dtype)
             elif kind == "gap":
                 # the features are float32 in every stack: a bf16 stack's global average pool widens as it sums
-                api.stanza_gap_fwd(self.buf[op["src"]], self.feat32 if self.dtype == api.BF16 else self.buf[op["dst"]], self.dtype)
+                q(s, "stanza_gap_fwd", self.buf[op["src"]], self.feat32 if self.dtype == api.BF16 else self.buf[op["dst"]], self.dtype)
+        out = self.buf["feat"]
         if self.dtype == api.BF16:
             if self.producer["feat"]["op"] != "gap":
-                api.stanza_cast_bf16_to_f32(self.buf["feat"], self.feat32)
-            return self.feat32
-        return self.buf["feat"]
+                q(at_stream.get("feat", 0), "stanza_cast_bf16_to_f32", self.buf["feat"], self.feat32)
+            out = self.feat32
+        sched.end()
+        return out
 
     # ------------------------------------------------------------------ backward
     def _grad_buffer(self, name, like=None):
@@ -265,43 +417,30 @@ class ConvWorker:
     def backward(self, dfeat: torch.Tensor):
         """dfeat: float32 gradient of the activations handed to the FC worker, [B, A] or the buffer's own shape."""
         dfeat = dfeat.reshape(self.shapes["feat"])
+        sched, ns = self.sched, self.n_streams
+        sched.begin("backward", self.multi_stream)
+        q = sched.call
         if self.dtype == api.BF16 and self.producer["feat"]["op"] != "gap":
-            api.stanza_cast_f32_to_bf16(dfeat.contiguous(), self.dfeat16)
+            q(0, "stanza_cast_f32_to_bf16", dfeat.contiguous(), self.dfeat16)
             dfeat = self.dfeat16
         have: Dict[str, torch.Tensor] = {"feat": dfeat}
         gated = {"feat": False}   # True when the stored gradient is already multiplied by [buffer > 0]
-        main = torch.cuda.current_stream()
-        two = self.overlap_wgrad and self.side is not None and not torch.cuda.is_current_stream_capturing()
-        pending: Dict[int, torch.cuda.Event] = {}     # dy buffer -> end of its last reader on the second stream
-        if two:
-            # the second stream's first launch must not overtake what the caller's stream has queued (the previous step's
-            # aggregation reads the gradient buffers that this pass rewrites)
-            self.ev_dy.record(main)
-            self.side.wait_event(self.ev_dy)
+        at_stream: Dict[str, int] = {"feat": 0}      # buffer -> stream of the last writer of its gradient (a hint, like forward's)
 
-        def wgrad(*a):
-            """A filter-gradient call: on the second stream once dy, complete on the caller's stream at this point, is there.
-            Layers with more than OVERLAP_MAX_TILES 128 x 128 tiles of dy stay on the caller's stream: their launches run many
-            full rounds of workgroups, there is little of a last round to fill, and the two kernels then only take each other's
-            cache and HBM bandwidth."""
-            dsc = a[0]
-            ho, wo = api.conv_out_hw(dsc)
-            tiles = -(-dsc.N * ho * wo // 128) * -(-dsc.K // 128)
-            if not two or tiles > OVERLAP_MAX_TILES:
-                api.stanza_conv_bwd_weight(*a, self.ws)
-                return
-            self.ev_dy.record(main)
-            with torch.cuda.stream(self.side):
-                self.side.wait_event(self.ev_dy)
-                api.stanza_conv_bwd_weight(*a, self.ws_side)
-                # whoever later ADDS into this dy on the caller's stream (the gradient of a residual join is shared by both
-                # addends, and the shortcut's side accumulates into it) must wait for this reader
-                ev = self.ev_read.setdefault(a[2].data_ptr(), torch.cuda.Event())
-                ev.record(self.side)
-                pending[a[2].data_ptr()] = ev
+        def wgrad(s, d, *a):
+            """A filter-gradient call: two streams on from its layer's data gradient.  Layers with more than OVERLAP_MAX_TILES
+            128 x 128 tiles of dy stay on that stream: their launches run many full rounds of workgroups, there is little of a
+            last round to fill, and the two kernels then only take each other's cache and HBM bandwidth."""
+            ho, wo = api.conv_out_hw(d)
+            tiles = -(-d.N * ho * wo // 128) * -(-d.K // 128)
+            if tiles <= OVERLAP_MAX_TILES:
+                s = (s + ns // 2) % ns
+            q(s, "stanza_conv_bwd_weight", d, *a, self.wss[s])
+            return s
         for i in reversed(range(len(self.ops))):
             op = self.ops[i]
             kind = op["op"]
+            s = at_stream.get(op["dst"], 0)
             if kind == "conv":
                 d = self.descs[i]
                 dy = have.pop(op["dst"])
@@ -310,9 +449,8 @@ class ConvWorker:
                 w, _ = self.params[op["name"]]
                 dw, db = self.grads[op["name"]]
                 if i in self.padded:
-                    wgrad(d, self.x0pad16 if self.dtype == api.BF16 else self.x0pad32, dy, y, self.dwpad32, db)
-                    with torch.cuda.stream(self.side if two else main):
-                        api.stanza_copy_channels(self.dwpad32, 0, dw, 0, self.padded[i])
+                    sw = wgrad(s, d, self.x0pad16 if self.dtype == api.BF16 else self.x0pad32, dy, y, self.dwpad32, db)
+                    q(sw, "stanza_copy_channels", self.dwpad32, 0, dw, 0, self.padded[i])
                     continue
                 if self.f32_layer.get(i, False):
                     # mixed layer (first conv of a bf16 stack): float32 filter gradient from a float32 copy of dy
@@ -320,42 +458,46 @@ class ConvWorker:
                     if y is not None:
                         raise NotImplementedError("ungated gradient into a mixed-precision first layer")
                     dy32 = self.tmp32[: dy.numel()].view(dy.shape)
-                    api.stanza_cast_bf16_to_f32(dy, dy32)
-                    api.stanza_conv_bwd_weight(d, self.buf["x0"], dy32, None, dw, db, self.ws)
+                    q(s, "stanza_cast_bf16_to_f32", dy, dy32)
+                    q(s, "stanza_conv_bwd_weight", d, self.buf["x0"], dy32, None, dw, db, self.wss[s])
                     continue
                 wk = self.w16[op["name"]] if self.dtype == api.BF16 else w
-                wgrad(d, self.buf[op["src"]], dy, y, dw, db)
+                wgrad(s, d, self.buf[op["src"]], dy, y, dw, db)
                 src = op["src"]
                 if src != "x0":
                     prod = self.producer[src]
                     x_mask = self.buf[src] if (prod["op"] == "conv" and prod["relu"]) else None
                     dd = api.ConvDesc.from_buffer_copy(d)
                     if src in have:
+                        # (a join's gradient is shared by both addends: adding into it waits, like any writer, for the calls
+                        # that read it on other streams)
                         dd.flags |= api.CONV_ACCUM
                         dx = have[src]
-                        if dx.data_ptr() in pending:
-                            main.wait_event(pending.pop(dx.data_ptr()))
                     else:
                         dx = self._grad_buffer(src)
                         have[src] = dx
-                    api.stanza_conv_bwd_data(dd, dy, y, wk, x_mask, dx, self.ws)
+                    q(s, "stanza_conv_bwd_data", dd, dy, y, wk, x_mask, dx, self.wss[s])
                     gated[src] = x_mask is not None
+                    at_stream[src] = s
             elif kind == "avgpool":
                 dx = self._grad_buffer(op["src"])
                 assert op["src"] not in have, "a pooling branch must be the last reader of its input in the op list"
-                api.stanza_avgpool_bwd(self.descs[i], have.pop(op["dst"]), dx, self.dtype)
+                q(s, "stanza_avgpool_bwd", self.descs[i], have.pop(op["dst"]), dx, self.dtype)
                 have[op["src"]] = dx
                 gated[op["src"]] = False
+                at_stream[op["src"]] = s
             elif kind == "concat":
                 wide = have.pop(op["dst"])
                 at = 0
-                for sname in op["srcs"]:
+                for k, sname in enumerate(op["srcs"]):
                     cs = self.shapes[sname][3]
                     part = self._grad_buffer(sname)
                     assert sname not in have
-                    api.stanza_copy_channels(wide, at, part, 0, cs)
+                    sk = (s + k) % ns                 # every branch of the module takes its part of the gradient to a stream of its own
+                    q(sk, "stanza_copy_channels", wide, at, part, 0, cs)
                     have[sname] = part
                     gated[sname] = False
+                    at_stream[sname] = sk
                     at += cs
             elif kind == "bn":
                 # the layer undoes its own ReLU from x, whether or not the incoming gradient is gated already
@@ -364,33 +506,35 @@ class ConvWorker:
                 dgamma, dbeta = self.grads[op["name"]]
                 dx = self._grad_buffer(op["src"])
                 assert op["src"] not in have
-                api.stanza_bn_bwd(self.buf[op["src"]], have.pop(op["dst"]), gamma, beta, mean, istd, dx, dgamma, dbeta, self.bn_ws,
-                                  op["relu"], dtype=self.dtype)
+                q(s, "stanza_bn_bwd", self.buf[op["src"]], have.pop(op["dst"]), gamma, beta, mean, istd, dx, dgamma, dbeta, self.bn_wss[s],
+                  op["relu"], dtype=self.dtype)
                 have[op["src"]] = dx
                 gated[op["src"]] = False
+                at_stream[op["src"]] = s
             elif kind == "pool":
                 dx = self._grad_buffer(op["src"])
                 assert op["src"] not in have
-                api.stanza_pool_relu_bwd(self.descs[i], have.pop(op["dst"]), self.buf[op["dst"]], self.argmax[op["dst"]], dx, self.dtype)
+                q(s, "stanza_pool_relu_bwd", self.descs[i], have.pop(op["dst"]), self.buf[op["dst"]], self.argmax[op["dst"]], dx, self.dtype)
                 have[op["src"]] = dx
                 gated[op["src"]] = bool(op["relu"])   # [P>0] at the argmax equals [Y>0] there
+                at_stream[op["src"]] = s
             elif kind == "add_relu":
                 dz = self._grad_buffer(op["dst"] + "#dz", like=op["dst"])
-                api.stanza_add_relu_bwd(have.pop(op["dst"]), self.buf[op["dst"]], dz, self.dtype)
+                q(s, "stanza_add_relu_bwd", have.pop(op["dst"]), self.buf[op["dst"]], dz, self.dtype)
                 # Both addends receive dz.  They share one tensor: in the reversed op order every reader of
-                # the main-branch gradient runs before the first accumulation into the shortcut's gradient.
-                for name in (op["a"], op["b"]):
+                # the main-branch gradient is issued before the first accumulation into the shortcut's gradient.
+                for k, name in enumerate((op["a"], op["b"])):
                     assert name not in have
                     have[name] = dz
                     gated[name] = False
+                    at_stream[name] = (s + k) % ns    # a projection shortcut's backward beside the block's
             elif kind == "gap":
                 dx = self._grad_buffer(op["src"])
-                api.stanza_gap_bwd(have.pop(op["dst"]).view(self.shapes[op["dst"]][0], -1), dx, self.dtype)
+                q(s, "stanza_gap_bwd", have.pop(op["dst"]).view(self.shapes[op["dst"]][0], -1), dx, self.dtype)
                 have[op["src"]] = dx
                 gated[op["src"]] = False
-        if two:
-            self.ev_side.record(self.side)
-            main.wait_event(self.ev_side)
+                at_stream[op["src"]] = s
+        sched.end()
         return self.grads
 
 

@@ -171,34 +171,39 @@ def test_plain_aggregation_call_inside_a_graph_capture(api, o32, K, numels):
             assert rel_err(host(gw[t]), w_ref[t]) < 1e-6, (rep, t)
 
 
-@pytest.mark.parametrize("name,B", [("resnet50", 4), ("inception3", 2), ("vgg16", 2)])
-def test_backward_on_two_streams_equals_one_stream(api, name, B):
-    """The backward pass issues filter gradients on a second stream beside the data gradients (Sec. 3.2: the CONV worker's
-    backward pass; nothing reads a filter gradient before the aggregation).  Same kernels, same operands, so every gradient must
-    come out bit for bit as on one stream -- also where a residual join's gradient, which a filter-gradient launch reads, is
-    later accumulated into by the shortcut's side, and over repeated steps (the second stream of one step against the
-    caller's stream of the next)."""
+@pytest.mark.parametrize("name,B,dt", [("resnet50", 4, "f32"), ("inception3", 2, "f32"), ("vgg16", 2, "f32"), ("resnet50bn", 3, "f32"),
+                                       ("resnet50", 3, "bf16"), ("inception3", 2, "bf16")])
+def test_passes_on_several_streams_equal_one_stream(api, name, B, dt):
+    """The CONV worker's passes (Sec. 3.2) spread calls that do not depend on each other over several streams: a layer's filter
+    gradient beside its data gradient, the branches of an Inception module or a projection shortcut beside each other.  Same
+    kernels, same operands, so the hand-off and every gradient must come out bit for bit as on one stream -- also where a residual
+    join's gradient, which other calls read, is later accumulated into by the shortcut's side, where several branches accumulate
+    into the gradient of their common input, and over repeated steps (the streams of one pass against the caller's stream before
+    and after it)."""
     from paper_1812_10624_amd.netrun import ConvWorker
     wl = wl_mod.get_workload(name)
     img = dev(wl_mod.gen_images(wl, 3, 0, B))
-    gcp = {n: (dev(w), None if b is None else dev(b)) for n, (w, b) in wl_mod.gen_conv_params(wl, 3).items()}
-    wk = ConvWorker(wl.ops, wl.image, B, gcp)
-    feat = wk.forward(img)
-    dfeat = torch.randn(feat.shape, device="cuda:0", generator=torch.Generator(device="cuda:0").manual_seed(11)) / B
-    wk.overlap_wgrad = False
+    gcp = {n: tuple(None if t is None else dev(t) for t in ts) for n, ts in wl_mod.gen_conv_params(wl, 3).items()}
+    wk = ConvWorker(wl.ops, wl.image, B, gcp, dtype=api.BF16 if dt == "bf16" else api.F32)
+    assert wk.n_streams == (2 if name == "vgg16" else 4)
+    wk.multi_stream = False
+    feat_ref = wk.forward(img).clone()
+    dfeat = torch.randn(feat_ref.shape, device="cuda:0", generator=torch.Generator(device="cuda:0").manual_seed(11)) / B
     wk.backward(dfeat)
     torch.cuda.synchronize()
     ref = {n: tuple(None if g is None else g.clone() for g in gs) for n, gs in wk.grads.items()}
-    wk.overlap_wgrad = True
+    wk.multi_stream = True
     for rep in range(3):
-        for gs in wk.grads.values():
-            for g in gs:
-                if g is not None:
-                    g.fill_(float("nan"))            # on the caller's stream: the pass must order its second stream behind this
+        for t in list(wk.buf.values()) + [g for gs in wk.grads.values() for g in gs if g is not None]:
+            if t is not wk.buf["x0"]:
+                t.fill_(float("nan"))                # on the caller's stream: the passes must order their streams behind this
+        feat = wk.forward().clone()                  # caller's stream, no synchronisation in between
         wk.backward(dfeat)
-        got = {n: tuple(None if g is None else g.clone() for g in gs) for n, gs in wk.grads.items()}   # caller's stream, no sync
+        got = {n: tuple(None if g is None else g.clone() for g in gs) for n, gs in wk.grads.items()}
         torch.cuda.synchronize()
+        assert torch.equal(feat, feat_ref), (name, rep)
         for n in ref:
             for which in range(2):
                 if ref[n][which] is not None:
                     assert torch.equal(got[n][which], ref[n][which]), (name, rep, n, which)
+    assert len(wk.sched.plans) == 2 and sum(len(w) for _, _, w, _ in wk.sched.plans["backward"]) > 0
