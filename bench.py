@@ -265,14 +265,17 @@ def main():
     # the line shows what issuing independent calls on several streams is worth
     worker.multi_stream = False
     n_one = min(args.steps, 5)
-    one_a, one_b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    step()
-    one_a.record()
-    for _ in range(n_one):
+    if args.one_stream or args.graph:
+        ms_per_step_one_stream = None if args.graph else (t1 - t0) * 1e3 / args.steps      # the timed steps were such steps
+    else:
+        one_a, one_b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         step()
-    one_b.record()
-    torch.cuda.synchronize()
-    ms_per_step_one_stream = one_a.elapsed_time(one_b) / n_one
+        one_a.record()
+        for _ in range(n_one):
+            step()
+        one_b.record()
+        torch.cuda.synchronize()
+        ms_per_step_one_stream = one_a.elapsed_time(one_b) / n_one
     # ---- the driver's shader clock while such steps run, read in a pass of its own, so that the sampling thread (it takes the
     # interpreter's lock every 4 ms) stays out of every timed pass
     with SclkSampler() as sclk:

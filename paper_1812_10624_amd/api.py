@@ -58,13 +58,49 @@ class FcDesc(C.Structure):
 
 
 _lib = None
+_tape = None             # while a list: every library call made through this module is also appended to it as (function, arguments)
+
+
+class _Taping:
+    """Stands in for the library while calls are being taped: passes each call on and notes it."""
+
+    def __getattr__(self, name):
+        fn = getattr(_lib, name)
+
+        if fn.restype is not C.c_int or name in ("stanza_version",):      # a query, not a launch: nothing to issue again
+            return fn
+
+        def call(*args):
+            _tape.append((fn, args, name))
+            return fn(*args)
+        return call
+
+
+_taping = _Taping()
+
+
+def tape_calls(tape):
+    """tape: a list, or None to stop.  A sequencer whose calls never change (same buffers, same descriptors, same stream) can
+    tape one pass and afterwards issue the taped library calls directly, without marshalling their arguments again.  The
+    argument objects on the tape keep descriptors alive; the tensors behind the raw pointers are the caller's to keep."""
+    global _tape
+    load()
+    _tape = tape
+
+
+def replay_call(entry):
+    """Issue one taped call again, with the error check of the call that taped it."""
+    fn, args, name = entry
+    rc = fn(*args)
+    if rc:
+        _check(rc, name)
 
 
 def load() -> C.CDLL:
     """Load libstanza.so (built beforehand by `__graft_entry__.build()` / `python -m paper_1812_10624_amd.build`)."""
     global _lib
     if _lib is not None:
-        return _lib
+        return _lib if _tape is None else _taping
     if not os.path.exists(LIB_PATH):
         raise StanzaError(f"{LIB_PATH} is missing: build it with `python -m paper_1812_10624_amd.build` (no CPU fallback exists)")
     lib = C.CDLL(LIB_PATH)

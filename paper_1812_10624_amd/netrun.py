@@ -19,6 +19,10 @@ from . import api
 # Inception-V3-shaped 1,634 / 1,637 / 1,645 / 1,646 / 1,645 / 1,643 against 1,539.  Only the two 224 x 224 x 64 layers of the VGG
 # stacks (25,088 tiles) lose.
 OVERLAP_MAX_TILES = 8192
+# ... and of at least this many: a smaller launch is over before an event has passed from one stream to the other (the two 128-row
+# layers of the MLP-shaped workload, 8 tiles: 0.58 against 0.56 ms per step in float32, 0.43 against 0.39 in bf16, with their filter
+# gradients on a second stream).
+OVERLAP_MIN_TILES = 16
 
 # Arguments that a call WRITES (or updates in place); every other tensor argument is read.  The workspace counts as written.
 _WRITES = {
@@ -41,42 +45,79 @@ class StreamSchedule:
     """Spreads the calls of one pass (a CONV worker's forward or backward pass, Sec. 3.2) over a few streams of default priority
     and orders them with events, so that launches that do not depend on each other -- the branches of an Inception module, a
     projection shortcut beside its block, a layer's filter gradient beside its data gradient -- run side by side and fill each
-    other's partly empty rounds of workgroups.  The caller names a stream for every call (a hint: any choice is correct); which
-    call must wait for which is found from the calls themselves: a call waits for the last writer of every tensor it touches,
-    and a writer also for every reader since (tensors are told apart by their storage, so views of one buffer count as that
-    buffer).  The first pass of a kind works this out and keeps the result -- per call its stream, the events to wait for and
-    the event to record -- and later passes replay that list: the sequence of calls of a pass never changes.
-    A pass starts with every stream waiting for the caller's stream and ends with the caller's stream waiting for all of them, so
-    nothing outside the pass sees more than one stream.  Under graph capture, or switched off, calls go straight to the current
-    stream."""
+    other's partly empty rounds of workgroups.
+
+    begin / call / end issue a pass call by call and work it out on the way.  The caller names a stream for every call (a hint:
+    any choice is correct); which call must wait for which is found from the calls themselves: a call waits for the last writer
+    of every tensor it touches, and a writer also for every reader since (tensors are told apart by their storage, so views of
+    one buffer count as that buffer).  Every library call made on the way is taped with its marshalled arguments.
+
+    replay issues the pass again from that tape: the same library calls on the same streams between the same events, with no
+    sequencing logic and no argument conversion (this is most of the host's time for a stack of short kernels).  The tape holds
+    raw device addresses, so it stands only while the pass works on the same buffers from the same caller's stream: the
+    sequencer's own buffers never move, and the addresses of what the caller hands in are the tape's key.
+
+    A pass starts with every stream it uses waiting for the caller's stream and ends with the caller's stream waiting for them,
+    so nothing outside the pass sees more than one stream.  Under graph capture, or switched off, calls go straight to the
+    current stream."""
 
     def __init__(self, dev, n_streams: int):
         self.side = [torch.cuda.Stream(device=dev) for _ in range(n_streams - 1)]
         self.n = n_streams
-        self.plans: Dict[str, list] = {}
+        self.plans: Dict[str, list] = {}         # pass -> per call (stream index, entry point, events to wait for, event to record, tape)
+        self.keys: Dict[str, tuple] = {}         # pass -> (caller's stream, addresses of the caller's tensors) its tape was made with
+        self.used: Dict[str, list] = {}          # pass -> the side streams it uses
         self.ev_fork = torch.cuda.Event()
         self.ev_join = [torch.cuda.Event() for _ in self.side]
         self.on = False
 
-    def begin(self, tag: str, enabled: bool):
+    def _fork(self, main, active):
+        if active:
+            self.ev_fork.record(main)
+        for st in active:
+            st.wait_event(self.ev_fork)
+
+    def _join(self, main, active):
+        for st, ev in zip(active, self.ev_join):
+            ev.record(st)
+            main.wait_event(ev)
+
+    def replay(self, tag: str, enabled: bool, key=()) -> bool:
+        """Issue the pass `tag` from its tape.  False when there is no tape that fits (none yet, other tensors handed in, another
+        caller's stream, graph capture, switched off): the pass then has to be issued call by call."""
+        plan = self.plans.get(tag)
+        if not enabled or plan is None or torch.cuda.is_current_stream_capturing():
+            return False
+        main = torch.cuda.current_stream()
+        if self.keys[tag] != (main.cuda_stream,) + tuple(key):
+            return False
+        streams = [main] + self.side
+        active = [self.side[i - 1] for i in self.used[tag]]      # a stream that the pass does not use is not made to join in
+        self._fork(main, active)
+        issue = api.replay_call
+        for s, _, waits, ev, tape in plan:
+            st = streams[s]
+            for w in waits:
+                st.wait_event(w)
+            for entry in tape:
+                issue(entry)
+            if ev is not None:
+                ev.record(st)
+        self._join(main, active)
+        return True
+
+    def begin(self, tag: str, enabled: bool, key=()):
         self.on = enabled and not torch.cuda.is_current_stream_capturing()
         if not self.on:
             return
+        self.tag, self.key = tag, key
         self.main = torch.cuda.current_stream()
         self.streams = [self.main] + self.side
-        self.tag, self.plan, self.at = tag, self.plans.get(tag), 0
-        if self.plan is None:
-            self.new, self.seq = [], 0
-            self.last_writer: Dict[int, tuple] = {}      # storage -> (stream index, sequence number, event)
-            self.readers: Dict[int, list] = {}           # storage -> the same, for every reader since the last writer
-            self.seen = [dict() for _ in range(self.n)]  # per stream: other stream -> latest sequence number already waited for
-        # only the streams that this pass uses join in (all of them while the pass is worked out): the caller's stream is not
-        # made to wait for a queue that has nothing to do and may be slow to wake up
-        self.active = self.side if self.plan is None else [self.side[i - 1] for i in sorted({e[0] for e in self.plan} - {0})]
-        if self.active:
-            self.ev_fork.record(self.main)
-        for st in self.active:
-            st.wait_event(self.ev_fork)
+        self.new, self.seq = [], 0
+        self.last_writer: Dict[int, tuple] = {}      # storage -> (stream index, sequence number, event)
+        self.readers: Dict[int, list] = {}           # storage -> the same, for every reader since the last writer
+        self.seen = [dict() for _ in range(self.n)]  # per stream: other stream -> latest sequence number already waited for
+        self._fork(self.main, self.side)
 
     def _work_out(self, s: int, name: str, args, kw):
         deps: Dict[int, tuple] = {}
@@ -113,36 +154,29 @@ class StreamSchedule:
         fn = getattr(api, name)
         if not self.on:
             return fn(*args, **kw)
-        if self.plan is None:
-            waits, ev = self._work_out(s, name, args, kw)
-            self.new.append((s, name, waits, ev))
-        else:
-            if self.at >= len(self.plan) or self.plan[self.at][:2] != (s, name):
-                raise RuntimeError(f"the {self.tag} pass changed its sequence of calls at call {self.at} ({name})")
-            _, _, waits, ev = self.plan[self.at]
-            self.at += 1
+        waits, ev = self._work_out(s, name, args, kw)
         st = self.streams[s]
         for w in waits:
             st.wait_event(w)
+        tape = []
         api.set_stream(st)
+        api.tape_calls(tape)
         try:
             fn(*args, **kw)
         finally:
             api.set_stream(None)
-        if ev is not None:
-            ev.record(st)
+            api.tape_calls(None)
+        ev.record(st)
+        self.new.append((s, name, waits, ev, tape))
 
     def end(self):
         if not self.on:
             return
-        if self.plan is None:
-            waited = {id(e) for _, _, waits, _ in self.new for e in waits}       # replays record only the events somebody waits for
-            self.plans[self.tag] = [(s, name, waits, ev if id(ev) in waited else None) for s, name, waits, ev in self.new]
-        elif self.at != len(self.plan):
-            raise RuntimeError(f"the {self.tag} pass ended after {self.at} of {len(self.plan)} calls")
-        for st, ev in zip(self.active, self.ev_join):
-            ev.record(st)
-            self.main.wait_event(ev)
+        waited = {id(e) for _, _, waits, _, _ in self.new for e in waits}       # replays record only the events somebody waits for
+        self.plans[self.tag] = [(s, name, waits, ev if id(ev) in waited else None, tape) for s, name, waits, ev, tape in self.new]
+        self.keys[self.tag] = (self.main.cuda_stream,) + tuple(self.key)
+        self.used[self.tag] = sorted({e[0] for e in self.new} - {0})
+        self._join(self.main, self.side)
         self.on = False
 
 
@@ -314,6 +348,8 @@ class ConvWorker:
         if self.dtype == api.BF16 and self.cast_plan is not None:
             self.cast_plan.run()                     # this step's bf16 copies of the master filters
         sched, ns = self.sched, self.n_streams
+        if sched.replay("forward", self.multi_stream):
+            return self.feat32 if self.dtype == api.BF16 else self.buf["feat"]
         sched.begin("forward", self.multi_stream)
         q = sched.call
         # Stream hints: the first reader of a buffer goes on where the buffer was written, the k-th reader k streams further.
@@ -418,7 +454,10 @@ class ConvWorker:
         """dfeat: float32 gradient of the activations handed to the FC worker, [B, A] or the buffer's own shape."""
         dfeat = dfeat.reshape(self.shapes["feat"])
         sched, ns = self.sched, self.n_streams
-        sched.begin("backward", self.multi_stream)
+        key = (dfeat.data_ptr(),) if dfeat.is_contiguous() and dfeat.dtype == torch.float32 else (None, id(dfeat))
+        if key[0] is not None and sched.replay("backward", self.multi_stream, key):
+            return self.grads
+        sched.begin("backward", self.multi_stream, key)
         q = sched.call
         if self.dtype == api.BF16 and self.producer["feat"]["op"] != "gap":
             q(0, "stanza_cast_f32_to_bf16", dfeat.contiguous(), self.dfeat16)
@@ -433,7 +472,7 @@ class ConvWorker:
             last round to fill, and the two kernels then only take each other's cache and HBM bandwidth."""
             ho, wo = api.conv_out_hw(d)
             tiles = -(-d.N * ho * wo // 128) * -(-d.K // 128)
-            if tiles <= OVERLAP_MAX_TILES:
+            if OVERLAP_MIN_TILES <= tiles <= OVERLAP_MAX_TILES:
                 s = (s + ns // 2) % ns
             q(s, "stanza_conv_bwd_weight", d, *a, self.wss[s])
             return s

@@ -206,4 +206,15 @@ def test_passes_on_several_streams_equal_one_stream(api, name, B, dt):
             for which in range(2):
                 if ref[n][which] is not None:
                     assert torch.equal(got[n][which], ref[n][which]), (name, rep, n, which)
-    assert len(wk.sched.plans) == 2 and sum(len(w) for _, _, w, _ in wk.sched.plans["backward"]) > 0
+    # the second and third repetition were issued from the tape of the first (same buffers, same stream), across events
+    assert len(wk.sched.plans) == 2 and sum(len(e[2]) for e in wk.sched.plans["backward"]) > 0
+    assert all(len(e[4]) >= 1 for e in wk.sched.plans["forward"])
+    # other tensors handed in: the pass is worked out and taped anew, same bits
+    dfeat2 = dfeat.clone()
+    wk.backward(dfeat2)
+    torch.cuda.synchronize()
+    assert wk.sched.keys["backward"][1] == dfeat2.data_ptr()
+    for n in ref:
+        for which in range(2):
+            if ref[n][which] is not None:
+                assert torch.equal(wk.grads[n][which], ref[n][which]), (name, "new dfeat", n, which)
