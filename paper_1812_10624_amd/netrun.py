@@ -187,7 +187,12 @@ class ConvWorker:
     dtype=api.BF16 keeps activations, activation gradients and a per-step copy of the filters in bfloat16
     (master filters, filter/bias gradients, images, features and feature gradients stay float32); the image
     layer (C = 3) runs with its channels zero-padded to 8; any other conv whose channel counts are not multiples of 8 runs in
-    float32 between casts."""
+    float32 between casts.
+
+    With multi_stream (the default on a GPU) the passes are issued from a tape after the first one (StreamSchedule): the tensors in
+    `params` and `feat_out` must stay the same tensors for the life of the worker (they are updated in place by the aggregation and
+    the FC worker); the gradient handed to backward may be another tensor at any time, the pass is then taped anew.  One thread
+    issues the passes of all workers: the issue stream and the tape are state of the binding module."""
 
     def __init__(self, ops: List[dict], image_shape, batch: int, params: Dict[str, tuple], device="cuda:0", dtype=api.F32,
                  feat_out: Optional[torch.Tensor] = None):
