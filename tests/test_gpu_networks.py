@@ -172,7 +172,9 @@ def test_plain_aggregation_call_inside_a_graph_capture(api, o32, K, numels):
 
 
 @pytest.mark.parametrize("name,B,dt", [("resnet50", 4, "f32"), ("inception3", 2, "f32"), ("vgg16", 2, "f32"), ("resnet50bn", 3, "f32"),
-                                       ("resnet50", 3, "bf16"), ("inception3", 2, "bf16")])
+                                       ("resnet50", 3, "bf16"), ("inception3", 2, "bf16"),
+                                       # at the batch sizes bench.py times, where the launches are as long and as many-tiled as there
+                                       ("resnet50", 64, "f32"), ("inception3", 32, "f32"), ("vgg16", 64, "f32"), ("resnet50bn", 64, "bf16")])
 def test_passes_on_several_streams_equal_one_stream(api, name, B, dt):
     """The CONV worker's passes (Sec. 3.2) spread calls that do not depend on each other over several streams: a layer's filter
     gradient beside its data gradient, the branches of an Inception module or a projection shortcut beside each other.  Same
